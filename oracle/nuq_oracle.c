@@ -1,0 +1,432 @@
+/*
+ * NUQSGD compression path -- plain CPU oracle.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Slow, sequential, fp64, one coordinate at a time, written from the paper.
+ * It is the reference the HIP kernels are checked against; it shares no code
+ * with them and must never be called from the product path.  Only the tests,
+ * the smoke check and the benchmark's cpu_baseline leg may use it.
+ *
+ * What each function follows:
+ *   nuqo_bucket_norms      Def. 1 (Sec. 3.1): r_i = |v_i| / ||v||, Euclidean norm,
+ *                          one norm per bucket (Sec. 5 "bucket size").
+ *   nuqo_quantize_coord    Def. 1 with the level set of Sec. 3.1
+ *                          (0, 2^-s, ..., 1/2, 1); App. B eqs. (h_case1), (h_case2)
+ *                          for the two-point law and its probabilities.
+ *   nuqo_erc_*             App. A, Alg. 2 (Elias recursive coding).
+ *   nuqo_encode            App. A, ENCODE: rounds of ERC(gap), sign bit,
+ *                          ERC(log2(2^{s+1} h)); App. C parts R and E.
+ *   nuqo_decode_average    App. A, DECODE, then the aggregate of Alg. 1:
+ *                          (1/K) * sum_k decoded gradient.
+ *
+ * Points the paper leaves open (random number source, bit order, how the end
+ * of a bucket's records is known, padding) are fixed by the wire-format
+ * description in the project's design notes; this file implements that text.
+ *
+ * Pinned by tests/test_oracle_*.py: level sets, rounding probabilities by
+ * exhaustive enumeration of the 2^24 uniform draws, unbiasedness, the exact
+ * variance formula and Theorem 1's bound, Lemma 4's sparsity bound, hand-worked
+ * ERC codewords, decode(encode(x)) == x, a hand-worked ENCODE bit string.
+ * The exact random bits of a particular (seed, bucket, index) are fixed by
+ * the format text, not by the paper: "parity unpinned" by the paper for those.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define NUQO_OK 0
+#define NUQO_EINVAL (-1)
+#define NUQO_ECAPACITY (-2)
+#define NUQO_EMALFORMED (-5)
+
+/* ------------------------------------------------------------------ norms */
+
+/* Def. 1: ||v|| of every bucket, fp64, plain left-to-right sum. */
+void nuqo_bucket_norms(const float *v, uint64_t d, uint32_t bucket, double *norms)
+{
+    uint64_t nb = (d + bucket - 1) / bucket;
+    for (uint64_t b = 0; b < nb; b++) {
+        uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        double acc = 0.0;
+        for (uint64_t i = lo; i < hi; i++)
+            acc += (double)v[i] * (double)v[i];
+        norms[b] = sqrt(acc);
+    }
+}
+
+/* -------------------------------------------------------------------- rng */
+
+/*
+ * Counter-based uniform draw u in [0, 2^24) for coordinate `idx` of bucket
+ * `bucket_index` under `seed`.  The paper only asks for independent draws;
+ * the generator is this project's choice:
+ *   per bucket : z = seed + (bucket_index + 1) * 0x9E3779B97F4A7C15, then the
+ *                SplitMix64 output function; k0 = low word, k1 = high word.
+ *   per index  : x = (k0 + idx) * 0x9E3779B1;  x ^= (x >> 15) ^ k1;
+ *                x *= 0x85EBCA6B;  x ^= x >> 16;  u = x >> 8.
+ */
+void nuqo_rng_key(uint64_t seed, uint64_t bucket_index, uint32_t *k0, uint32_t *k1)
+{
+    uint64_t z = seed + (bucket_index + 1u) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z = z ^ (z >> 31);
+    *k0 = (uint32_t)z;
+    *k1 = (uint32_t)(z >> 32);
+}
+
+uint32_t nuqo_rng_u24(uint32_t k0, uint32_t k1, uint32_t idx)
+{
+    uint32_t x = (k0 + idx) * 0x9E3779B1u;
+    x = x ^ (x >> 15) ^ k1;
+    x = x * 0x85EBCA6Bu;
+    x = x ^ (x >> 16);
+    return x >> 8;
+}
+
+/* Fill u[i] for every coordinate of a d-vector cut into buckets. */
+void nuqo_rng_fill(uint64_t seed, uint64_t d, uint32_t bucket, uint32_t *u)
+{
+    uint64_t nb = (d + bucket - 1) / bucket;
+    for (uint64_t b = 0; b < nb; b++) {
+        uint32_t k0, k1;
+        nuqo_rng_key(seed, b, &k0, &k1);
+        uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        for (uint64_t i = lo; i < hi; i++)
+            u[i] = nuqo_rng_u24(k0, k1, (uint32_t)(i - lo));
+    }
+}
+
+/* --------------------------------------------------------------- quantizer */
+
+/*
+ * Level index j in {0..s+1} of h_i for one coordinate (l_0 = 0, l_j = 2^(j-1-s)).
+ *
+ * Def. 1: r = |v_i| / ||v||; level(r) is the bin with l_j <= r <= l_{j+1};
+ * p(r) = (r - l_j) / (l_{j+1} - l_j); h = l_{j+1} with probability p(r), else l_j.
+ * The draw is "up" iff u/2^24 < p(r), u a 24-bit uniform integer.
+ *
+ * Everything is done on r*||v|| instead of r so that no division is needed:
+ * l_j*||v|| is exact in fp64, |v_i| - l_j*||v|| is exact (the two are within
+ * a factor of two), u * (tau*||v||) is a 24-bit by 24-bit product, exact.
+ * So the comparison below is the real-number statement, with no rounding.
+ *
+ * r >= 1 can only come from a norm that was rounded down; it maps to the top
+ * level.  A zero norm or a zero coordinate gives level 0 (Q_s(0) = 0).
+ */
+int nuqo_quantize_coord(float vi, float norm, int s, uint32_t u24)
+{
+    double n = (double)norm;
+    double a = fabs((double)vi);
+    if (!(n > 0.0) || a == 0.0)
+        return 0;
+    int j = 0; /* largest j with l_j * n <= a */
+    for (int t = 1; t <= s + 1; t++)
+        if (ldexp(n, t - 1 - s) <= a)
+            j = t;
+    if (j == s + 1)
+        return s + 1;
+    double lo_n = (j == 0) ? 0.0 : ldexp(n, j - 1 - s); /* l_j * n      */
+    double hi_n = ldexp(n, j - s);                      /* l_{j+1} * n  */
+    double tau_n = hi_n - lo_n;
+    int up = ((double)u24 * tau_n) < ((a - lo_n) * 16777216.0);
+    return up ? j + 1 : j;
+}
+
+/* Same, vectorised over an array of draws for one fixed (vi, norm, s). */
+void nuqo_quantize_coord_many(float vi, float norm, int s, const uint32_t *u24,
+                              uint64_t count, uint8_t *levels)
+{
+    for (uint64_t i = 0; i < count; i++)
+        levels[i] = (uint8_t)nuqo_quantize_coord(vi, norm, s, u24[i]);
+}
+
+/* hist[j] += number of draws u in [u_begin, u_end) that give level index j. */
+void nuqo_level_histogram(float vi, float norm, int s, uint32_t u_begin, uint32_t u_end,
+                          uint64_t *hist)
+{
+    for (uint32_t u = u_begin; u < u_end; u++)
+        hist[nuqo_quantize_coord(vi, norm, s, u)]++;
+}
+
+/*
+ * q[i] = level index (bits 0..6) | sign (bit 7, 1 = negative, only when the
+ * level is nonzero).  `u24` holds one draw per coordinate.
+ */
+void nuqo_quantize_given_u(const float *v, uint64_t d, uint32_t bucket, int s,
+                           const float *norms, const uint32_t *u24, uint8_t *q)
+{
+    for (uint64_t i = 0; i < d; i++) {
+        int j = nuqo_quantize_coord(v[i], norms[i / bucket], s, u24[i]);
+        uint8_t sign = (j > 0 && signbit(v[i])) ? 0x80 : 0;
+        q[i] = (uint8_t)j | sign;
+    }
+}
+
+/* Same with the counter generator above. */
+void nuqo_quantize(const float *v, uint64_t d, uint32_t bucket, int s, uint64_t seed,
+                   const float *norms, uint8_t *q)
+{
+    uint64_t nb = (d + bucket - 1) / bucket;
+    for (uint64_t b = 0; b < nb; b++) {
+        uint32_t k0, k1;
+        nuqo_rng_key(seed, b, &k0, &k1);
+        uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        for (uint64_t i = lo; i < hi; i++) {
+            uint32_t u = nuqo_rng_u24(k0, k1, (uint32_t)(i - lo));
+            int j = nuqo_quantize_coord(v[i], norms[b], s, u);
+            uint8_t sign = (j > 0 && signbit(v[i])) ? 0x80 : 0;
+            q[i] = (uint8_t)j | sign;
+        }
+    }
+}
+
+/* --------------------------------------------------------------------- ERC */
+
+/*
+ * Alg. 2, encoder.  The code of N is: the binary expansions of N, of
+ * (bits(N) - 1), of (bits of that - 1), ... down to (but excluding) 1, written
+ * last-computed first, then a single 0.  Writes '0'/'1' characters into `out`
+ * (at least 64 bytes), returns the length.
+ */
+static int bit_width(uint64_t x)
+{
+    int w = 0;
+    while (x) {
+        w++;
+        x >>= 1;
+    }
+    return w;
+}
+
+int nuqo_erc_encode(uint64_t N, char *out)
+{
+    if (N < 1)
+        return NUQO_EINVAL;
+    uint64_t groups[8];
+    int ng = 0;
+    while (N != 1) { /* "prepend binary(N); N' = #bits prepended - 1; recurse" */
+        groups[ng++] = N;
+        N = (uint64_t)bit_width(N) - 1;
+    }
+    int len = 0;
+    for (int g = ng - 1; g >= 0; g--) { /* the last group computed is the first written */
+        int w = bit_width(groups[g]);
+        for (int k = w - 1; k >= 0; k--)
+            out[len++] = ((groups[g] >> k) & 1) ? '1' : '0';
+    }
+    out[len++] = '0'; /* "place a 0 at the end" */
+    return len;
+}
+
+int nuqo_erc_length(uint64_t N)
+{
+    char tmp[96];
+    return nuqo_erc_encode(N, tmp);
+}
+
+/* A bit string held MSB-first in 32-bit words: stream bit t is bit 31-(t&31)
+ * of words[t>>5]. */
+static inline int get_bit(const uint32_t *words, uint64_t t)
+{
+    return (int)((words[t >> 5] >> (31 - (t & 31))) & 1u);
+}
+
+static inline void put_bit(uint32_t *words, uint64_t t, int bit)
+{
+    if (bit)
+        words[t >> 5] |= 1u << (31 - (t & 31));
+}
+
+/*
+ * Alg. 2, decoder, reading from bit `*pos` and never at or beyond `end`.
+ * "Start with N = 1; if the next bit is 0 stop and return N; else read that
+ * bit plus N following bits and update N."  Returns 0 on success, NUQO_EMALFORMED
+ * if the code runs past `end` or N leaves the 32-bit range.
+ */
+int nuqo_erc_decode(const uint32_t *words, uint64_t *pos, uint64_t end, uint64_t *N_out)
+{
+    uint64_t N = 1, t = *pos;
+    for (;;) {
+        if (t >= end)
+            return NUQO_EMALFORMED;
+        if (get_bit(words, t) == 0) {
+            *pos = t + 1;
+            *N_out = N;
+            return NUQO_OK;
+        }
+        if (N + 1 > 33 || t + N + 1 > end)
+            return NUQO_EMALFORMED;
+        uint64_t val = 0;
+        for (uint64_t k = 0; k < N + 1; k++)
+            val = (val << 1) | (uint64_t)get_bit(words, t + k);
+        t += N + 1;
+        N = val;
+    }
+}
+
+/* ------------------------------------------------------------------ ENCODE */
+
+#define NUQO_SYNC_EMPTY 0x80000000u
+
+static uint64_t num_sync(uint32_t bucket, uint32_t sync_stride)
+{
+    if (sync_stride == 0)
+        return 0;
+    return (bucket + sync_stride - 1) / sync_stride - 1;
+}
+
+/*
+ * ENCODE (App. A) of every bucket of q into one word array.
+ *
+ * Per bucket (the bucket is the paper's vector v; its 32-bit norm travels in the
+ * norms array next to the bit string): scan coordinates in index order; for
+ * every nonzero h emit ERC(gap) where gap = index - previous nonzero index
+ * (indices 1-based with t_0 = 0, so the first gap is the 1-based position),
+ * then one sign bit (1 = negative), then ERC(log2(2^(s+1) h)) = ERC(j), j the
+ * level index.  Nothing is emitted after the last nonzero.
+ *
+ * Layout: bit_off[0] = 0.  Bucket b's records start at the first 32-bit
+ * boundary at or after bit_off[b] and end (exclusive) at bit_off[b+1]; pad bits
+ * are zero.  words must hold words_cap zero-initialised entries on entry.
+ *
+ * sync (may be NULL when sync_stride == 0): for bucket b and segment
+ * g = 1 .. ceil(bucket/sync_stride)-1, entry sync[b*nsync + g-1] describes the
+ * first record whose coordinate index (0-based, inside the bucket) is in
+ * [g*S, (g+1)*S): bits 0..20 = bit offset of that record from the bucket's first
+ * bit, bits 21..30 = its index minus g*S; or 0x80000000 when the segment holds
+ * no nonzero.  It lets a decoder enter the bucket's bit string at a segment
+ * boundary; the bit string itself does not depend on it.
+ *
+ * Returns 0, or NUQO_ECAPACITY if words_cap is too small, NUQO_EINVAL on bad
+ * arguments or a level index above s+1.
+ */
+int nuqo_encode(const uint8_t *q, uint64_t d, uint32_t bucket, int s, uint32_t sync_stride,
+                uint64_t *bit_off, uint32_t *words, uint64_t words_cap, uint32_t *sync)
+{
+    if (d == 0 || bucket == 0 || s < 1)
+        return NUQO_EINVAL;
+    if (sync_stride != 0 && (sync_stride > 1024 || (sync_stride & (sync_stride - 1))))
+        return NUQO_EINVAL;
+    uint64_t nb = (d + bucket - 1) / bucket;
+    uint64_t nsync = num_sync(bucket, sync_stride);
+    uint64_t end_prev = 0;
+    bit_off[0] = 0;
+    char code[96];
+    for (uint64_t b = 0; b < nb; b++) {
+        uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        uint64_t start = (end_prev + 31) / 32 * 32;
+        uint64_t t = start;
+        int64_t prev = -1; /* 0-based index of the previous nonzero; t_0 = 0 in 1-based terms */
+        for (uint64_t g = 0; g < nsync; g++)
+            sync[b * nsync + g] = NUQO_SYNC_EMPTY;
+        for (uint64_t i = lo; i < hi; i++) {
+            int j = q[i] & 0x7f;
+            if (j == 0)
+                continue;
+            if (j > s + 1)
+                return NUQO_EINVAL;
+            int64_t idx = (int64_t)(i - lo);
+            if (sync_stride) {
+                uint64_t g = (uint64_t)idx / sync_stride;
+                if (g >= 1 && sync[b * nsync + g - 1] == NUQO_SYNC_EMPTY)
+                    sync[b * nsync + g - 1] =
+                        (uint32_t)(t - start) | ((uint32_t)(idx - g * sync_stride) << 21);
+            }
+            uint64_t gap = (uint64_t)(idx - prev);
+            int glen = nuqo_erc_encode(gap, code);
+            int jlen = nuqo_erc_encode((uint64_t)j, code + glen + 1);
+            code[glen] = (q[i] & 0x80) ? '1' : '0';
+            int len = glen + 1 + jlen;
+            if ((t + len + 31) / 32 > words_cap)
+                return NUQO_ECAPACITY;
+            for (int k = 0; k < len; k++)
+                put_bit(words, t + k, code[k] == '1');
+            t += len;
+            prev = idx;
+        }
+        bit_off[b + 1] = t;
+        end_prev = t;
+    }
+    return NUQO_OK;
+}
+
+/* ------------------------------------------------------------------ DECODE */
+
+/*
+ * DECODE (App. A) of one worker's bit strings into q (level | sign<<7 per
+ * coordinate): per bucket read ERC^-1 -> gap, one sign bit, ERC^-1 -> level
+ * index, until the bucket's bits are used up.  Returns NUQO_EMALFORMED if a
+ * record crosses the bucket's end, an index leaves the bucket, or a level
+ * index is outside 1..s+1.
+ */
+int nuqo_decode_levels(const uint64_t *bit_off, const uint32_t *words, uint64_t d,
+                       uint32_t bucket, int s, uint8_t *q)
+{
+    uint64_t nb = (d + bucket - 1) / bucket;
+    memset(q, 0, d);
+    for (uint64_t b = 0; b < nb; b++) {
+        uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        uint64_t t = (bit_off[b] + 31) / 32 * 32, end = bit_off[b + 1];
+        if (end < t)
+            return NUQO_EMALFORMED;
+        int64_t prev = -1;
+        while (t < end) {
+            uint64_t gap, j;
+            int rc = nuqo_erc_decode(words, &t, end, &gap);
+            if (rc)
+                return rc;
+            if (t >= end)
+                return NUQO_EMALFORMED;
+            int neg = get_bit(words, t++);
+            rc = nuqo_erc_decode(words, &t, end, &j);
+            if (rc)
+                return rc;
+            int64_t idx = prev + (int64_t)gap;
+            if (idx >= (int64_t)(hi - lo) || j < 1 || j > (uint64_t)s + 1)
+                return NUQO_EMALFORMED;
+            q[lo + idx] = (uint8_t)j | (neg ? 0x80 : 0);
+            prev = idx;
+        }
+    }
+    return NUQO_OK;
+}
+
+/*
+ * DECODE each of K workers, rebuild Q_s(v) = ||v|| * sign * l_j (Def. 1), and
+ * aggregate as in Alg. 1: out = [out +] scale * sum_k Q_k, fp64, workers in
+ * order.  out64 has d entries; if accumulate is zero it is overwritten.
+ */
+int nuqo_decode_average(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                        const uint32_t *const *words, uint64_t d, uint32_t bucket, int s,
+                        double scale, int accumulate, double *out64)
+{
+    uint8_t *q = (uint8_t *)malloc(d);
+    double *sum = (double *)calloc(d, sizeof(double));
+    if (!q || !sum) {
+        free(q);
+        free(sum);
+        return NUQO_EINVAL;
+    }
+    for (uint32_t k = 0; k < K; k++) {
+        int rc = nuqo_decode_levels(bit_off[k], words[k], d, bucket, s, q);
+        if (rc) {
+            free(q);
+            free(sum);
+            return rc;
+        }
+        for (uint64_t i = 0; i < d; i++) {
+            int j = q[i] & 0x7f;
+            if (j == 0)
+                continue;
+            double h = ldexp(1.0, j - 1 - s); /* l_j */
+            double val = (double)norms[k][i / bucket] * h;
+            sum[i] += (q[i] & 0x80) ? -val : val;
+        }
+    }
+    for (uint64_t i = 0; i < d; i++)
+        out64[i] = (accumulate ? out64[i] : 0.0) + scale * sum[i];
+    free(q);
+    free(sum);
+    return NUQO_OK;
+}
