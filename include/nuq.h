@@ -1,0 +1,149 @@
+/*
+ * nuq.h -- C ABI of the NUQSGD gradient-compression hot path for AMD MI355X (gfx950).
+ *
+ * The path (arXiv 1908.06077): per-bucket Euclidean norms -> nonuniform stochastic
+ * quantization of |v_i|/||v|| onto the levels (0, 2^-s, ..., 1/2, 1) with sign
+ * (Sec. 3.1, Def. 1) -> ENCODE into Elias-recursive-coded bit strings (App. A,
+ * Alg. 2) -> DECODE, dequantize and average K workers' gradients (App. A; the
+ * aggregate line of Alg. 1).
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller, unless the
+ *     comment says "host".  The library never frees or keeps them.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work and
+ *     return without synchronising, except nuq_last_error_flags.
+ *   - Return value: NUQ_OK or a negative NUQ_E* code.  Argument errors are detected
+ *     on the host before anything is enqueued.  Conditions only visible on the device
+ *     (capacity overflow, non-finite norm, malformed stream) set sticky device flags
+ *     read back with nuq_last_error_flags.
+ *   - d = number of coordinates (>= 1), bucket = bucket size n (1..NUQ_MAX_BUCKET),
+ *     B = ceil(d / bucket) buckets, bucket b covers [b*n, min((b+1)*n, d)),
+ *     s = number of internal levels (1..NUQ_MAX_S), level index j in 0..s+1 with
+ *     l_0 = 0 and l_j = 2^(j-1-s).
+ *
+ * Message layout produced by nuq_encode / nuq_quantize_encode (one per worker):
+ *   norms[B]      fp32 bucket norms (the 32-bit ||v|| of App. A, kept beside the bits).
+ *   bit_off[B+1]  u64.  bit_off[0] = 0.  Bucket b's records are stream bits
+ *                 [start_b, bit_off[b+1]) with start_b = bit_off[b] rounded up to a
+ *                 multiple of 32.
+ *   words[W]      u32, W = ceil(bit_off[B] / 32).  Stream bit t is bit 31-(t%32) of
+ *                 words[t/32].  Pad bits are zero.
+ *   sync[B*nsync] u32 decoder index, nsync = nuq_num_sync(bucket, sync_stride).
+ *                 Entry (b, g), g = 1..nsync, stored at sync[b*nsync + g-1]: for the
+ *                 first nonzero whose in-bucket index is in [g*S, (g+1)*S):
+ *                 bits 0..20 = bit offset of its record from start_b,
+ *                 bits 21..30 = index - g*S;  NUQ_SYNC_EMPTY if there is none.
+ *   A record, for a nonzero at in-bucket index i whose previous nonzero is at i_prev
+ *   (-1 if none): ERC(i - i_prev), one sign bit (1 = negative), ERC(j).
+ */
+#ifndef NUQ_H
+#define NUQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *nuq_stream_t; /* hipStream_t */
+
+enum {
+    NUQ_OK = 0,
+    NUQ_EINVAL = -1,     /* bad argument (size, range, NULL, misaligned)            */
+    NUQ_ECAPACITY = -2,  /* a caller-provided buffer is too small (host-detectable) */
+    NUQ_ENONFINITE = -3, /* reserved for host-side checks                           */
+    NUQ_EHIP = -4        /* a HIP runtime call failed                               */
+};
+
+/* Sticky device flags (nuq_last_error_flags). */
+enum {
+    NUQ_FLAG_CAPACITY = 1,  /* encoded words did not fit words_cap; words is incomplete */
+    NUQ_FLAG_NONFINITE = 2, /* a bucket norm was Inf/NaN; that bucket was encoded empty */
+    NUQ_FLAG_MALFORMED = 4  /* a decoded stream broke the format; output is incomplete  */
+};
+
+#define NUQ_MAX_BUCKET 32768u
+#define NUQ_MAX_S 14u
+#define NUQ_MAX_WORKERS 32u /* K per nuq_decode_accumulate call */
+#define NUQ_SYNC_EMPTY 0x80000000u
+
+/* ---- sizes (pure host arithmetic, no device work) -------------------------------- */
+
+/* B = ceil(d / bucket); 0 if bucket == 0. */
+uint64_t nuq_num_buckets(uint64_t d, uint32_t bucket);
+
+/* Sync entries per bucket: 0 if sync_stride == 0, else ceil(bucket / sync_stride) - 1. */
+uint32_t nuq_num_sync(uint32_t bucket, uint32_t sync_stride);
+
+/* Upper bound on W for any input: every coordinate nonzero at the longest level code,
+ * i.e. d * (2 + |ERC(s+1)|) bits, plus one word of padding per bucket. */
+uint64_t nuq_max_words(uint64_t d, uint32_t bucket, uint32_t s);
+
+/* Bytes of scratch nuq_encode / nuq_quantize_encode need for these sizes. */
+uint64_t nuq_encode_workspace_bytes(uint64_t d, uint32_t bucket, uint32_t s);
+
+/* ---- step 1: bucket norms (Def. 1: r_i = |v_i| / ||v||) --------------------------- */
+
+/* norms[b] = sqrt(sum of v_i^2 over bucket b), rounded to fp32.
+ * v: d floats, 4-byte aligned (16-byte alignment with bucket % 4 == 0 takes the
+ * vector-load path).  norms: B floats. */
+int nuq_bucket_norms(const float *v, uint64_t d, uint32_t bucket, float *norms,
+                     nuq_stream_t stream);
+
+/* ---- step 2: quantizer (Def. 1; App. B eqs. h_case1, h_case2) --------------------- */
+
+/* q[i] = level index j (bits 0..6) | sign (bit 7, 1 = negative, only if j > 0).
+ * With r = |v_i| / norms[b] in bin [l_j, l_{j+1}) the result is j+1 with probability
+ * p = (r - l_j) / (l_{j+1} - l_j), else j; the draw is the counter hash of
+ * (seed, b, index in bucket) (24 uniform bits, "up" iff u / 2^24 < p, evaluated
+ * exactly).  r >= 1 gives s+1; a zero norm or coordinate gives 0.
+ * norms: B floats, normally the output of nuq_bucket_norms.  q: d bytes. */
+int nuq_quantize(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64_t seed,
+                 const float *norms, uint8_t *q, nuq_stream_t stream);
+
+/* ---- step 3: ENCODE (App. A; Alg. 2) ------------------------------------------------ */
+
+/* Encodes the level/sign bytes q[d] into bit_off[B+1], words[<= words_cap] and, when
+ * sync_stride != 0, sync[B*nsync] (sync may be NULL when sync_stride == 0).
+ * sync_stride: 0, or a power of two in 64..1024.
+ * workspace: at least nuq_encode_workspace_bytes(d, bucket, s) bytes, 16-byte aligned;
+ * contents are scratch.  If the encoded size exceeds words_cap the device flag
+ * NUQ_FLAG_CAPACITY is raised, bit_off is still complete and words holds the buckets
+ * that fit.  A level index above s+1 in q is a caller error (undefined bits). */
+int nuq_encode(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint32_t sync_stride,
+               uint64_t *bit_off, uint32_t *words, uint64_t words_cap, uint32_t *sync,
+               void *workspace, uint64_t workspace_bytes, nuq_stream_t stream);
+
+/* Steps 1-3 fused: v is read from memory once.  Outputs norms[B] as nuq_bucket_norms
+ * would, and bit_off / words / sync exactly as nuq_encode(nuq_quantize(v, norms)) would.
+ * A bucket whose norm is not finite is encoded as empty and raises NUQ_FLAG_NONFINITE. */
+int nuq_quantize_encode(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64_t seed,
+                        uint32_t sync_stride, float *norms, uint64_t *bit_off, uint32_t *words,
+                        uint64_t words_cap, uint32_t *sync, void *workspace,
+                        uint64_t workspace_bytes, nuq_stream_t stream);
+
+/* ---- step 4: DECODE + dequantize + aggregate (App. A DECODE; Alg. 1 aggregate) ------ */
+
+/* out[i] = (accumulate ? out[i] : 0) + scale * sum_k norms_k[b] * sign * l_j, where
+ * (sign, j) of coordinate i is decoded from worker k's bit string (0 if absent).
+ * norms, bit_off, words, sync: HOST arrays of K device pointers (one message per
+ * worker, all encoded with the same d, bucket, s, sync_stride); sync may be NULL or hold
+ * NULLs when sync_stride == 0.  1 <= K <= NUQ_MAX_WORKERS; average with scale = 1/K.
+ * The sum over workers is taken in fp32 in no fixed order.  out: d floats.
+ * A record that leaves its bucket's bit range or index range, or a level index outside
+ * 1..s+1, raises NUQ_FLAG_MALFORMED and ends that bucket's decoding. */
+int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                          const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
+                          uint32_t bucket, uint32_t s, uint32_t sync_stride, float scale,
+                          int accumulate, float *out, nuq_stream_t stream);
+
+/* ---- errors ---------------------------------------------------------------------- */
+
+/* Waits for `stream`, copies the sticky device flags of the current device to
+ * *host_flags (host pointer) and clears them. */
+int nuq_last_error_flags(uint32_t *host_flags, nuq_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NUQ_H */

@@ -61,7 +61,7 @@ def lib() -> ctypes.CDLL:
         L.nuqo_level_histogram.restype = None
         L.nuqo_quantize_given_u.argtypes = [vp, u64, u32, i32, vp, vp, vp]
         L.nuqo_quantize_given_u.restype = None
-        L.nuqo_quantize.argtypes = [vp, u64, u32, i32, u64, vp, vp]
+        L.nuqo_quantize.argtypes = [vp, u64, u32, i32, u64, vp, u64, vp]
         L.nuqo_quantize.restype = None
         L.nuqo_erc_encode.argtypes = [u64, ctypes.c_char_p]
         L.nuqo_erc_encode.restype = i32
@@ -154,13 +154,14 @@ def quantize_given_u(v: np.ndarray, bucket: int, s: int, norms: np.ndarray, u24:
     return q
 
 
-def quantize(v: np.ndarray, bucket: int, s: int, seed: int, norms: np.ndarray) -> np.ndarray:
-    """q[i] = level index | sign << 7, with the counter generator of the format text."""
+def quantize(v: np.ndarray, bucket: int, s: int, seed: int, norms: np.ndarray, first_bucket: int = 0) -> np.ndarray:
+    """q[i] = level index | sign << 7, with the counter generator of the format text.
+    `first_bucket` > 0 when v holds buckets first_bucket.. of a longer vector."""
     v = np.ascontiguousarray(v, dtype=np.float32)
     norms = np.ascontiguousarray(norms, dtype=np.float32)
     assert norms.size == num_buckets(v.size, bucket)
     q = np.empty(v.size, dtype=np.uint8)
-    lib().nuqo_quantize(_p(v), v.size, bucket, s, seed & (2 ** 64 - 1), _p(norms), _p(q))
+    lib().nuqo_quantize(_p(v), v.size, bucket, s, seed & (2 ** 64 - 1), _p(norms), first_bucket, _p(q))
     return q
 
 

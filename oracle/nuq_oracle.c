@@ -163,14 +163,16 @@ void nuqo_quantize_given_u(const float *v, uint64_t d, uint32_t bucket, int s,
     }
 }
 
-/* Same with the counter generator above. */
+/* Same with the counter generator above.  v, norms and q describe buckets
+ * first_bucket, first_bucket+1, ... of a longer vector (first_bucket = 0 for a
+ * whole vector); only the generator's bucket index depends on it. */
 void nuqo_quantize(const float *v, uint64_t d, uint32_t bucket, int s, uint64_t seed,
-                   const float *norms, uint8_t *q)
+                   const float *norms, uint64_t first_bucket, uint8_t *q)
 {
     uint64_t nb = (d + bucket - 1) / bucket;
     for (uint64_t b = 0; b < nb; b++) {
         uint32_t k0, k1;
-        nuqo_rng_key(seed, b, &k0, &k1);
+        nuqo_rng_key(seed, first_bucket + b, &k0, &k1);
         uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
         for (uint64_t i = lo; i < hi; i++) {
             uint32_t u = nuqo_rng_u24(k0, k1, (uint32_t)(i - lo));

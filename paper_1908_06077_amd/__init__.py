@@ -1,0 +1,13 @@
+"""NUQSGD gradient-compression hot path for AMD MI355X: thin binding over libnuq.so.
+
+Every function here only marshals arguments (torch tensors -> device pointers, the current
+HIP stream) into the C ABI declared in include/nuq.h; all steps of the path run in the HIP
+kernels.  There is no CPU fallback: importing the package fails if the library is missing.
+"""
+from .binding import (  # noqa: F401
+    NuqError, Message,
+    FLAG_CAPACITY, FLAG_NONFINITE, FLAG_MALFORMED, SYNC_EMPTY, MAX_BUCKET, MAX_S, MAX_WORKERS,
+    nuq_num_buckets, nuq_num_sync, nuq_max_words, nuq_encode_workspace_bytes,
+    nuq_bucket_norms, nuq_quantize, nuq_encode, nuq_quantize_encode, nuq_decode_accumulate,
+    nuq_last_error_flags, library_path, exported_symbols,
+)

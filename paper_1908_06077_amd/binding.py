@@ -1,0 +1,154 @@
+"""ctypes binding of the C ABI in include/nuq.h.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libnuq.so")
+
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        "libnuq.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+        "(or `python paper_1908_06077_amd/build.py`) first; there is no fallback path")
+
+_lib = ctypes.CDLL(_LIB_PATH)
+
+FLAG_CAPACITY, FLAG_NONFINITE, FLAG_MALFORMED = 1, 2, 4
+SYNC_EMPTY = 0x80000000
+MAX_BUCKET, MAX_S, MAX_WORKERS = 32768, 14, 32
+
+_u64, _u32, _i32, _vp, _f32 = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p, ctypes.c_float
+
+_SIGNATURES = {
+    "nuq_num_buckets": (_u64, [_u64, _u32]),
+    "nuq_num_sync": (_u32, [_u32, _u32]),
+    "nuq_max_words": (_u64, [_u64, _u32, _u32]),
+    "nuq_encode_workspace_bytes": (_u64, [_u64, _u32, _u32]),
+    "nuq_bucket_norms": (_i32, [_vp, _u64, _u32, _vp, _vp]),
+    "nuq_quantize": (_i32, [_vp, _u64, _u32, _u32, _u64, _vp, _vp, _vp]),
+    "nuq_encode": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
+    "nuq_quantize_encode": (_i32, [_vp, _u64, _u32, _u32, _u64, _u32, _vp, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
+    "nuq_decode_accumulate": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _i32, _vp, _vp]),
+    "nuq_last_error_flags": (_i32, [_vp, _vp]),
+}
+for _name, (_res, _args) in _SIGNATURES.items():
+    _fn = getattr(_lib, _name)
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def exported_symbols() -> list[str]:
+    return sorted(_SIGNATURES)
+
+
+class NuqError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        names = {-1: "NUQ_EINVAL", -2: "NUQ_ECAPACITY", -3: "NUQ_ENONFINITE", -4: "NUQ_EHIP"}
+        super().__init__("%s returned %s" % (fn, names.get(code, str(code))))
+        self.code = code
+
+
+def _check(fn: str, code: int) -> None:
+    if code != 0:
+        raise NuqError(fn, code)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: torch.Tensor | None, dtype: torch.dtype | None = None) -> int:
+    if t is None:
+        return 0
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return t.data_ptr()
+
+
+# ------------------------------------------------------------------ sizes (host only)
+
+def nuq_num_buckets(d: int, bucket: int) -> int:
+    return _lib.nuq_num_buckets(d, bucket)
+
+
+def nuq_num_sync(bucket: int, sync_stride: int) -> int:
+    return _lib.nuq_num_sync(bucket, sync_stride)
+
+
+def nuq_max_words(d: int, bucket: int, s: int) -> int:
+    return _lib.nuq_max_words(d, bucket, s)
+
+
+def nuq_encode_workspace_bytes(d: int, bucket: int, s: int) -> int:
+    return _lib.nuq_encode_workspace_bytes(d, bucket, s)
+
+
+# ------------------------------------------------------------------------- the path
+
+def nuq_bucket_norms(v: torch.Tensor, bucket: int, norms: torch.Tensor) -> None:
+    _check("nuq_bucket_norms",
+           _lib.nuq_bucket_norms(_ptr(v, torch.float32), v.numel(), bucket, _ptr(norms, torch.float32), _stream()))
+
+
+def nuq_quantize(v: torch.Tensor, bucket: int, s: int, seed: int, norms: torch.Tensor, q: torch.Tensor) -> None:
+    _check("nuq_quantize",
+           _lib.nuq_quantize(_ptr(v, torch.float32), v.numel(), bucket, s, seed & (2 ** 64 - 1),
+                             _ptr(norms, torch.float32), _ptr(q, torch.uint8), _stream()))
+
+
+@dataclass
+class Message:
+    """One worker's encoded gradient: device tensors laid out as include/nuq.h describes."""
+    norms: torch.Tensor       # float32 [B]
+    bit_off: torch.Tensor     # int64 [B+1] (u64 bit pattern)
+    words: torch.Tensor       # int32 [words_cap] (u32 bit pattern)
+    sync: torch.Tensor | None  # int32 [B*nsync]
+
+
+def nuq_encode(q: torch.Tensor, bucket: int, s: int, sync_stride: int, bit_off: torch.Tensor, words: torch.Tensor,
+               sync: torch.Tensor | None, workspace: torch.Tensor) -> None:
+    _check("nuq_encode",
+           _lib.nuq_encode(_ptr(q, torch.uint8), q.numel(), bucket, s, sync_stride, _ptr(bit_off, torch.int64),
+                           _ptr(words, torch.int32), words.numel(), _ptr(sync), _ptr(workspace),
+                           workspace.numel() * workspace.element_size(), _stream()))
+
+
+def nuq_quantize_encode(v: torch.Tensor, bucket: int, s: int, seed: int, sync_stride: int, norms: torch.Tensor,
+                        bit_off: torch.Tensor, words: torch.Tensor, sync: torch.Tensor | None,
+                        workspace: torch.Tensor) -> None:
+    _check("nuq_quantize_encode",
+           _lib.nuq_quantize_encode(_ptr(v, torch.float32), v.numel(), bucket, s, seed & (2 ** 64 - 1), sync_stride,
+                                    _ptr(norms, torch.float32), _ptr(bit_off, torch.int64),
+                                    _ptr(words, torch.int32), words.numel(), _ptr(sync), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream()))
+
+
+def nuq_decode_accumulate(messages: list[Message], d: int, bucket: int, s: int, sync_stride: int, scale: float,
+                          accumulate: bool, out: torch.Tensor) -> None:
+    K = len(messages)
+    arr = lambda ts: (ctypes.c_void_p * K)(*[_ptr(t) for t in ts])
+    norms = arr([m.norms for m in messages])
+    offs = arr([m.bit_off for m in messages])
+    words = arr([m.words for m in messages])
+    sync = arr([m.sync for m in messages])
+    if out.numel() != d:
+        raise ValueError("out must hold d floats")
+    _check("nuq_decode_accumulate",
+           _lib.nuq_decode_accumulate(K, norms, offs, words, sync, d, bucket, s, sync_stride, float(scale),
+                                      1 if accumulate else 0, _ptr(out, torch.float32), _stream()))
+
+
+def nuq_last_error_flags() -> int:
+    flags = ctypes.c_uint32(0)
+    _check("nuq_last_error_flags", _lib.nuq_last_error_flags(ctypes.byref(flags), _stream()))
+    return flags.value

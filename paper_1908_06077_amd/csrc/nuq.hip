@@ -1,0 +1,349 @@
+// C ABI of the NUQSGD compression path (see include/nuq.h): argument checks, launch
+// geometry and workspace layout.  All arithmetic of the method lives in the kernels.
+#include "../../include/nuq.h"
+
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "nuq_decode_kernels.hpp"
+#include "nuq_device.hpp"
+#include "nuq_encode_kernels.hpp"
+
+namespace {
+
+using namespace nuq;
+
+// Sticky error flags, one word per device (each device holds its own copy of the symbol).
+__device__ uint32_t g_flags;
+
+uint32_t *flags_ptr()
+{
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_flags)) != hipSuccess)
+        return nullptr;
+    return static_cast<uint32_t *>(p);
+}
+
+uint32_t erc_len_host(uint32_t N)
+{
+    uint32_t len = 1;
+    while (N > 1) {
+        uint32_t w = 0;
+        for (uint32_t x = N; x; x >>= 1)
+            ++w;
+        len += w;
+        N = w - 1;
+    }
+    return len;
+}
+
+bool valid_common(uint64_t d, uint32_t bucket, uint32_t s)
+{
+    return d >= 1 && bucket >= 1 && bucket <= NUQ_MAX_BUCKET && s >= 1 && s <= NUQ_MAX_S;
+}
+
+bool valid_sync(uint32_t sync_stride)
+{
+    return sync_stride == 0 ||
+           (sync_stride >= 64 && sync_stride <= 1024 && (sync_stride & (sync_stride - 1)) == 0);
+}
+
+uint32_t log2u(uint32_t x)
+{
+    uint32_t l = 0;
+    while ((1u << l) < x)
+        ++l;
+    return l;
+}
+
+uint32_t slot_words_for(uint32_t bucket, uint32_t s)
+{
+    const uint64_t bits = (uint64_t)bucket * (2u + erc_len_host(s + 1));
+    return (uint32_t)(((bits + 31) / 32 + 3) & ~3ull);   // 16-byte multiple
+}
+
+struct Workspace {
+    uint32_t *lens;
+    uint64_t *block_sums;
+    uint32_t *staging;
+    uint64_t bytes;
+};
+
+Workspace carve(void *base, uint64_t nb, uint32_t slot_words)
+{
+    auto up = [](uint64_t x) { return (x + 255) & ~255ull; };
+    const uint64_t nblk = (nb + kScanChunk - 1) / kScanChunk;
+    uint64_t off = 0;
+    Workspace w;
+    char *p = static_cast<char *>(base);
+    w.lens = reinterpret_cast<uint32_t *>(p + off);
+    off += up(nb * 4);
+    w.block_sums = reinterpret_cast<uint64_t *>(p + off);
+    off += up((nblk + 1) * 8);
+    w.staging = reinterpret_cast<uint32_t *>(p + off);
+    off += up(nb * (uint64_t)slot_words * 4);
+    w.bytes = off;
+    return w;
+}
+
+// Team shape per bucket size: (threads per bucket, float4 rows per thread).
+template <class F>
+int dispatch_team(uint32_t bucket, F &&f)
+{
+    if (bucket <= 512)
+        return f(std::integral_constant<int, 64>{}, std::integral_constant<int, 2>{});
+    if (bucket <= 2048)
+        return f(std::integral_constant<int, 64>{}, std::integral_constant<int, 8>{});
+    if (bucket <= 8192)
+        return f(std::integral_constant<int, 256>{}, std::integral_constant<int, 8>{});
+    if (bucket <= 16384)
+        return f(std::integral_constant<int, 256>{}, std::integral_constant<int, 16>{});
+    return f(std::integral_constant<int, 1024>{}, std::integral_constant<int, 8>{});
+}
+
+int check_launch()
+{
+    return hipGetLastError() == hipSuccess ? NUQ_OK : NUQ_EHIP;
+}
+
+int run_offsets_and_gather(const Workspace &w, uint64_t nb, uint32_t slot_words, uint64_t *bit_off,
+                           uint32_t *words, uint64_t words_cap, uint32_t *flags, hipStream_t st)
+{
+    const uint64_t nblk = (nb + kScanChunk - 1) / kScanChunk;
+    hipLaunchKernelGGL(k_scan_block_sums, dim3((uint32_t)nblk), dim3(256), 0, st, w.lens, nb, w.block_sums);
+    hipLaunchKernelGGL(k_scan_of_sums, dim3(1), dim3(256), 0, st, w.block_sums, nblk);
+    hipLaunchKernelGGL(k_scan_offsets, dim3((uint32_t)nblk), dim3(256), 0, st, w.lens, nb, w.block_sums, bit_off);
+    hipLaunchKernelGGL(k_gather, dim3((uint32_t)((nb + 3) / 4)), dim3(256), 0, st, w.staging, slot_words,
+                       bit_off, nb, words, words_cap, flags);
+    return check_launch();
+}
+
+template <int MODE>
+int encode_common(const float *v, const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint64_t seed,
+                  uint32_t sync_stride, float *norms, uint64_t *bit_off, uint32_t *words, uint64_t words_cap,
+                  uint32_t *sync, void *workspace, uint64_t workspace_bytes, nuq_stream_t stream)
+{
+    if (!valid_common(d, bucket, s) || !valid_sync(sync_stride) || !bit_off || !words || !workspace)
+        return NUQ_EINVAL;
+    if ((MODE == 0 && (!v || !norms)) || (MODE == 1 && !q))
+        return NUQ_EINVAL;
+    const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
+    if (nsync && !sync)
+        return NUQ_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 15u) || (MODE == 0 && (reinterpret_cast<uintptr_t>(v) & 3u)))
+        return NUQ_EINVAL;
+    const uint64_t nb = nuq_num_buckets(d, bucket);
+    const uint32_t slot_words = slot_words_for(bucket, s);
+    const Workspace w = carve(workspace, nb, slot_words);
+    if (w.bytes > workspace_bytes)
+        return NUQ_ECAPACITY;
+    uint32_t *flags = flags_ptr();
+    if (!flags)
+        return NUQ_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    EncodeParams P{};
+    P.v = v;
+    P.q_in = q;
+    P.norms_out = norms;
+    P.d = d;
+    P.nb = nb;
+    P.seed = seed;
+    P.bucket = bucket;
+    P.s = s;
+    P.sync_shift = sync_stride ? log2u(sync_stride) : 0;
+    P.nsync = nsync;
+    P.slot_words = slot_words;
+    P.lens = w.lens;
+    P.staging = w.staging;
+    P.sync = sync;
+    P.flags = flags;
+    int rc = dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
+        constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
+        using G = TeamGeom<TEAM>;
+        P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
+        P.lds_words = team_lds_words(P.rows, TEAM, slot_words, nsync);
+        const size_t lds_bytes = (size_t)P.lds_words * 4 * G::kTeamsPerWG;
+        if (lds_bytes > 160 * 1024)
+            return (int)NUQ_EINVAL;
+        auto kern = k_encode<TEAM, VPT, MODE>;
+        if (lds_bytes > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_bytes) != hipSuccess)
+            return (int)NUQ_EHIP;
+        const uint64_t grid = (nb + G::kTeamsPerWG - 1) / G::kTeamsPerWG;
+        hipLaunchKernelGGL(kern, dim3((uint32_t)grid), dim3(G::kWG), lds_bytes, st, P);
+        return check_launch();
+    });
+    if (rc != NUQ_OK)
+        return rc;
+    return run_offsets_and_gather(w, nb, slot_words, bit_off, words, words_cap, flags, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t nuq_num_buckets(uint64_t d, uint32_t bucket)
+{
+    return bucket ? (d + bucket - 1) / bucket : 0;
+}
+
+uint32_t nuq_num_sync(uint32_t bucket, uint32_t sync_stride)
+{
+    return sync_stride ? (bucket + sync_stride - 1) / sync_stride - 1 : 0;
+}
+
+uint64_t nuq_max_words(uint64_t d, uint32_t bucket, uint32_t s)
+{
+    if (!bucket)
+        return 0;
+    return (d * (2u + erc_len_host(s + 1)) + 31) / 32 + nuq_num_buckets(d, bucket);
+}
+
+uint64_t nuq_encode_workspace_bytes(uint64_t d, uint32_t bucket, uint32_t s)
+{
+    if (!valid_common(d, bucket, s))
+        return 0;
+    return carve(nullptr, nuq_num_buckets(d, bucket), slot_words_for(bucket, s)).bytes;
+}
+
+int nuq_bucket_norms(const float *v, uint64_t d, uint32_t bucket, float *norms, nuq_stream_t stream)
+{
+    if (!v || !norms || !valid_common(d, bucket, 1) || (reinterpret_cast<uintptr_t>(v) & 3u))
+        return NUQ_EINVAL;
+    EncodeParams P{};
+    P.v = v;
+    P.norms_out = norms;
+    P.d = d;
+    P.bucket = bucket;
+    P.nb = nuq_num_buckets(d, bucket);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
+        constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
+        using G = TeamGeom<TEAM>;
+        const uint64_t grid = (P.nb + G::kTeamsPerWG - 1) / G::kTeamsPerWG;
+        hipLaunchKernelGGL((k_bucket_norms<TEAM, VPT>), dim3((uint32_t)grid), dim3(G::kWG), 0, st, P);
+        return check_launch();
+    });
+}
+
+int nuq_quantize(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64_t seed, const float *norms,
+                 uint8_t *q, nuq_stream_t stream)
+{
+    if (!v || !norms || !q || !valid_common(d, bucket, s) || (reinterpret_cast<uintptr_t>(v) & 3u))
+        return NUQ_EINVAL;
+    EncodeParams P{};
+    P.v = v;
+    P.norms_in = norms;
+    P.q_out = q;
+    P.d = d;
+    P.bucket = bucket;
+    P.s = s;
+    P.seed = seed;
+    P.nb = nuq_num_buckets(d, bucket);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
+        constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
+        using G = TeamGeom<TEAM>;
+        P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
+        const uint64_t grid = (P.nb + G::kTeamsPerWG - 1) / G::kTeamsPerWG;
+        hipLaunchKernelGGL((k_quantize<TEAM, VPT>), dim3((uint32_t)grid), dim3(G::kWG), 0, st, P);
+        return check_launch();
+    });
+}
+
+int nuq_encode(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint32_t sync_stride, uint64_t *bit_off,
+               uint32_t *words, uint64_t words_cap, uint32_t *sync, void *workspace, uint64_t workspace_bytes,
+               nuq_stream_t stream)
+{
+    return encode_common<1>(nullptr, q, d, bucket, s, 0, sync_stride, nullptr, bit_off, words, words_cap, sync,
+                            workspace, workspace_bytes, stream);
+}
+
+int nuq_quantize_encode(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64_t seed,
+                        uint32_t sync_stride, float *norms, uint64_t *bit_off, uint32_t *words, uint64_t words_cap,
+                        uint32_t *sync, void *workspace, uint64_t workspace_bytes, nuq_stream_t stream)
+{
+    return encode_common<0>(v, nullptr, d, bucket, s, seed, sync_stride, norms, bit_off, words, words_cap, sync,
+                            workspace, workspace_bytes, stream);
+}
+
+int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                          const uint32_t *const *words, const uint32_t *const *sync, uint64_t d, uint32_t bucket,
+                          uint32_t s, uint32_t sync_stride, float scale, int accumulate, float *out,
+                          nuq_stream_t stream)
+{
+    if (K < 1 || K > NUQ_MAX_WORKERS || !norms || !bit_off || !words || !out || !valid_common(d, bucket, s) ||
+        !valid_sync(sync_stride))
+        return NUQ_EINVAL;
+    const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
+    if (nsync && !sync)
+        return NUQ_EINVAL;
+    DecodeParams P{};
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!norms[k] || !bit_off[k] || !words[k] || (nsync && !sync[k]))
+            return NUQ_EINVAL;
+        P.norms[k] = norms[k];
+        P.bit_off[k] = bit_off[k];
+        P.words[k] = words[k];
+        P.sync[k] = nsync ? sync[k] : nullptr;
+    }
+    uint32_t *flags = flags_ptr();
+    if (!flags)
+        return NUQ_EHIP;
+    P.out = out;
+    P.flags = flags;
+    P.d = d;
+    P.nb = nuq_num_buckets(d, bucket);
+    P.K = K;
+    P.bucket = bucket;
+    P.s = s;
+    P.sync_shift = nsync ? log2u(sync_stride) : 0;
+    P.nsync = nsync;
+    P.nseg = nsync + 1;
+    P.scale = scale;
+    P.accumulate = accumulate;
+    uint64_t grid;
+    if (bucket <= kTileMax) {
+        P.buckets_per_tile = kTileMax / bucket;
+        P.tiles_per_bucket = 1;
+        P.tile_coords = P.buckets_per_tile * bucket;
+        P.segs_per_tile = P.nseg;
+        grid = (P.nb + P.buckets_per_tile - 1) / P.buckets_per_tile;
+    } else {
+        P.buckets_per_tile = 0;
+        P.tile_coords = kTileMax;
+        P.tiles_per_bucket = (bucket + kTileMax - 1) / kTileMax;
+        P.segs_per_tile = P.sync_shift ? (kTileMax >> P.sync_shift) : 1;
+        grid = P.nb * P.tiles_per_bucket;
+    }
+    if (grid > 0x7fffffffull)
+        return NUQ_EINVAL;
+    hipLaunchKernelGGL(k_decode_accumulate, dim3((uint32_t)grid), dim3(256), (size_t)P.tile_coords * 4,
+                       static_cast<hipStream_t>(stream), P);
+    return check_launch();
+}
+
+int nuq_last_error_flags(uint32_t *host_flags, nuq_stream_t stream)
+{
+    if (!host_flags)
+        return NUQ_EINVAL;
+    uint32_t *flags = flags_ptr();
+    if (!flags)
+        return NUQ_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(host_flags, flags, sizeof(uint32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return NUQ_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess)
+        return NUQ_EHIP;
+    const uint32_t zero = 0;
+    if (hipMemcpyAsync(flags, &zero, sizeof(uint32_t), hipMemcpyHostToDevice, st) != hipSuccess)
+        return NUQ_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess)
+        return NUQ_EHIP;
+    return NUQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,252 @@
+// Device-side building blocks of the NUQSGD compression kernels (gfx950, wave64).
+//
+//   - counter hash for the rounding draws
+//   - the exact nonuniform stochastic rounding rule (Def. 1, Sec. 3.1; App. B)
+//   - Elias recursive coding of gaps and level indices (App. A, Alg. 2)
+//   - team-wide reductions and scans (a "team" is the group of threads that owns one bucket)
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nuq {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ uint32_t f2u(float x) { return __float_as_uint(x); }
+__device__ __forceinline__ float u2f(uint32_t x) { return __uint_as_float(x); }
+
+// ---------------------------------------------------------------- rounding draws
+//
+// One 24-bit uniform integer per coordinate.  Per bucket the 64-bit mixer below turns
+// (seed, bucket index) into two key words; per coordinate x = (k0 + i) * C1 is advanced by
+// adding C1, then one xor-shift/multiply/xor-shift round absorbs k1.
+
+constexpr uint32_t kRngC1 = 0x9E3779B1u;
+constexpr uint32_t kRngC2 = 0x85EBCA6Bu;
+
+struct BucketKey {
+    uint32_t k0, k1;
+};
+
+__device__ __forceinline__ BucketKey bucket_key(uint64_t seed, uint64_t bucket_index)
+{
+    uint64_t z = seed + (bucket_index + 1ull) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return BucketKey{(uint32_t)z, (uint32_t)(z >> 32)};
+}
+
+// x = (k0 + index) * C1 on entry.
+__device__ __forceinline__ uint32_t draw24(uint32_t x, uint32_t k1)
+{
+    x = x ^ (x >> 15) ^ k1;
+    x *= kRngC2;
+    x ^= x >> 16;
+    return x >> 8;
+}
+
+// ------------------------------------------------------------------- quantizer
+//
+// Levels l_0 = 0, l_j = 2^(j-1-s).  For a = |v_i| and the fp32 bucket norm N the rule is
+//   j = largest index with l_j * N <= a;  a >= N -> s+1;
+//   up to j+1  iff  u * (l_{j+1} - l_j) * N  <  (a - l_j * N) * 2^24   (real numbers).
+// Integer view: with nS = N * 2^-s (a float, exponent field lowered by s), the bin of a
+// is m = floor((bits(a) - bits(nS)) / 2^23): m < 0 is the bin below the first level,
+// m >= s means a >= N.  lo = nS * 2^m and a - lo are exact floats; the product u * w with
+// w = lo * 2^-24 (or nS * 2^-24 in the lowest bin) is compared exactly through its
+// rounded value p and the fma residual e = u*w - p.
+// Exactness needs w and e to be normal floats; norms below 2^-60 are handled by scaling
+// the whole bucket by 2^100 first (a power of two: ratios are unchanged).
+
+struct BucketScale {
+    uint32_t ns_bits;  // bits of (prescaled) N * 2^-s
+    uint32_t c_bits;   // bits of (prescaled) N * 2^(-s-24)
+    float prescale;    // 1 or 2^100
+    int s;
+    bool dead;         // zero or non-finite norm: every level is 0
+};
+
+__device__ __forceinline__ BucketScale make_scale(float norm, int s)
+{
+    BucketScale B;
+    B.s = s;
+    B.dead = !(norm > 0.0f) || !(norm < __builtin_huge_valf());
+    B.prescale = 1.0f;
+    if (norm < 0x1p-60f) {
+        B.prescale = 0x1p100f;
+        norm *= 0x1p100f;
+    }
+    B.ns_bits = f2u(norm) - ((uint32_t)s << 23);
+    B.c_bits = B.ns_bits - (24u << 23);
+    return B;
+}
+
+// Level index of one coordinate for the 24-bit draw u.  `v` is the raw coordinate.
+__device__ __forceinline__ int quantize_level(float v, uint32_t u, const BucketScale &B)
+{
+    float a = fabsf(v);
+    if (B.prescale != 1.0f)
+        a *= B.prescale;
+    const uint32_t ab = f2u(a);
+    const int m = (int)(ab - B.ns_bits) >> 23;
+    if (m >= B.s)
+        return B.s + 1;
+    const uint32_t sh = m < 0 ? 0u : (uint32_t)m << 23;
+    const float w = u2f(B.c_bits + sh);
+    const float x = m < 0 ? a : a - u2f(B.ns_bits + sh);
+    const int jlo = m < 0 ? 0 : m + 1;
+    const float uf = (float)u;
+    const float p = uf * w;
+    const float e = __builtin_fmaf(uf, w, -p);
+    const uint32_t pb = f2u(p), xb = f2u(x);
+    const bool up = (pb < xb) || (pb == xb && e < 0.0f);
+    return jlo + (up ? 1 : 0);
+}
+
+// ------------------------------------------------------------------------- ERC
+//
+// Alg. 2 for 1 <= N <= 65535: groups binary(N), binary(bits(N)-1), ... (values >= 2 only),
+// last computed first, then one 0.  At most three groups, at most 23 bits.
+// Returns the code right-aligned; `len` receives its length.
+__device__ __forceinline__ uint32_t erc_code(uint32_t N, uint32_t &len)
+{
+    const uint32_t w0 = 32u - (uint32_t)__clz((int)N);
+    uint32_t code = N, l = w0;
+    if (w0 >= 3u) {
+        const uint32_t n1 = w0 - 1u, w1 = 32u - (uint32_t)__clz((int)n1);
+        code |= n1 << l;
+        l += w1;
+        if (w1 >= 3u) {
+            code |= (w1 - 1u) << l;
+            l += 2u;
+        }
+    }
+    if (N == 1u) {
+        len = 1u;
+        return 0u;
+    }
+    len = l + 1u;
+    return code << 1;
+}
+
+// Decoder of Alg. 2 on a 32-bit window (MSB first) holding `avail` valid bits.
+// Consumes the code from the window.  Returns false if the code does not end inside the
+// window or a group is wider than 24 bits.
+__device__ __forceinline__ bool erc_decode_window(uint32_t &win, int &avail, uint32_t &N)
+{
+    N = 1u;
+#pragma unroll 1
+    for (int it = 0; it < 6; ++it) {
+        if (avail < 1)
+            return false;
+        if ((win >> 31) == 0u) {
+            win <<= 1;
+            avail -= 1;
+            return true;
+        }
+        const int k = (int)N + 1;
+        if (k > avail || k > 24)
+            return false;
+        N = win >> (32 - k);
+        win <<= k;
+        avail -= k;
+    }
+    return false;
+}
+
+// ------------------------------------------------------- team reductions / scans
+//
+// TEAM threads (64, 256 or 1024) own one bucket.  A workgroup holds max(256, TEAM) threads,
+// i.e. 4 one-wave teams or a single multi-wave team.  Multi-wave variants use a small LDS
+// scratch and __syncthreads(); every thread of the workgroup must call them.
+
+template <int TEAM>
+__device__ __forceinline__ double team_sum_f64(double x, double *scratch /* TEAM/64 doubles */)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        x += __shfl_xor(x, off, kWave);
+    if constexpr (TEAM > kWave) {
+        constexpr int NW = TEAM / kWave;
+        const int wave = (threadIdx.x % TEAM) / kWave;
+        __syncthreads();
+        if ((threadIdx.x & (kWave - 1)) == 0)
+            scratch[wave] = x;
+        __syncthreads();
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+            t += scratch[w];
+        x = t;
+    }
+    return x;
+}
+
+// Exclusive prefix sum over the team in thread order; `total` receives the team sum.
+template <int TEAM>
+__device__ __forceinline__ uint32_t team_exclusive_sum(uint32_t v, uint32_t *scratch /* TEAM/64 */,
+                                                       uint32_t &total)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    uint32_t inc = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t t = __shfl_up(inc, off, kWave);
+        if (lane >= off)
+            inc += t;
+    }
+    if constexpr (TEAM == kWave) {
+        total = __shfl(inc, kWave - 1, kWave);
+        return inc - v;
+    } else {
+        constexpr int NW = TEAM / kWave;
+        const int wave = (threadIdx.x % TEAM) / kWave;
+        __syncthreads();
+        if (lane == kWave - 1)
+            scratch[wave] = inc;
+        __syncthreads();
+        uint32_t before = 0, all = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const uint32_t t = scratch[w];
+            before += (w < wave) ? t : 0u;
+            all += t;
+        }
+        total = all;
+        return before + inc - v;
+    }
+}
+
+// Exclusive running maximum over the team in thread order (identity = `ident`).
+template <int TEAM>
+__device__ __forceinline__ int team_exclusive_max(int v, int ident, int *scratch /* TEAM/64 */)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int t = __shfl_up(inc, off, kWave);
+        if (lane >= off)
+            inc = max(inc, t);
+    }
+    int exc = __shfl_up(inc, 1, kWave);
+    if (lane == 0)
+        exc = ident;
+    if constexpr (TEAM > kWave) {
+        constexpr int NW = TEAM / kWave;
+        const int wave = (threadIdx.x % TEAM) / kWave;
+        __syncthreads();
+        if (lane == kWave - 1)
+            scratch[wave] = inc;
+        __syncthreads();
+        int before = ident;
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+            before = (w < wave) ? max(before, scratch[w]) : before;
+        exc = max(exc, before);
+    }
+    return exc;
+}
+
+}  // namespace nuq

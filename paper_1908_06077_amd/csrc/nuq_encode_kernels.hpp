@@ -1,0 +1,421 @@
+// Norms, quantizer and ENCODE kernels (Def. 1, App. A) -- one team of threads per bucket.
+//
+// Element layout inside a team: thread t, row i holds the four consecutive coordinates
+// 4*(i*TEAM + t) .. +3 of its bucket, so every row is one fully coalesced 16-byte load per
+// lane.  Level/sign bytes are exchanged through LDS so that in the coding phase thread t
+// owns the contiguous coordinates [t*C, (t+1)*C), C = 4*ceil(n / (4*TEAM)) <= 64.
+#pragma once
+#include "nuq_device.hpp"
+
+namespace nuq {
+
+constexpr uint32_t kFlagCapacity = 1u, kFlagNonfinite = 2u, kFlagMalformed = 4u;
+constexpr uint32_t kSyncEmpty = 0x80000000u;
+
+struct EncodeParams {
+    const float *v;        // fused / quantize / norms input
+    const uint8_t *q_in;   // encode-from-bytes input
+    uint8_t *q_out;        // quantize output
+    const float *norms_in; // quantize input
+    float *norms_out;      // norms / fused output
+    uint64_t d;
+    uint64_t nb;
+    uint64_t seed;
+    uint32_t bucket;
+    uint32_t s;
+    uint32_t sync_shift;   // log2(sync stride), 0 = no sync
+    uint32_t nsync;
+    uint32_t slot_words;   // staging words per bucket
+    uint32_t rows;         // ceil(bucket / (4*TEAM))
+    uint32_t lds_words;    // LDS words per team
+    uint32_t *lens;        // [nb] payload bits per bucket
+    uint32_t *staging;     // [nb * slot_words]
+    uint32_t *sync;        // [nb * nsync]
+    uint32_t *flags;
+};
+
+template <int TEAM>
+struct TeamGeom {
+    static constexpr int kWG = TEAM < 256 ? 256 : TEAM;
+    static constexpr int kTeamsPerWG = kWG / TEAM;
+};
+
+// Load the four coordinates of vector `vi` of a bucket of `nbk` coordinates starting at `vb`.
+__device__ __forceinline__ float4 load_vec4(const float *vb, uint32_t vi, uint32_t nbk, bool aligned)
+{
+    const uint32_t e0 = 4u * vi;
+    if (aligned && e0 + 3u < nbk)
+        return reinterpret_cast<const float4 *>(vb)[vi];
+    float4 r;
+    r.x = e0 + 0u < nbk ? vb[e0 + 0u] : 0.0f;
+    r.y = e0 + 1u < nbk ? vb[e0 + 1u] : 0.0f;
+    r.z = e0 + 2u < nbk ? vb[e0 + 2u] : 0.0f;
+    r.w = e0 + 3u < nbk ? vb[e0 + 3u] : 0.0f;
+    return r;
+}
+
+// Bucket norm from a per-row accessor.  fp32 partial sums (four accumulators per thread),
+// fp64 across the team; if the fp32 result could have lost range (tiny or huge sums) the
+// whole sum is redone in fp64.  Every thread of the team returns the same value.
+template <int TEAM, int VPT, class Row>
+__device__ __forceinline__ float team_norm(Row row, double *scratch)
+{
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const float4 x = row(i);
+        a0 = __builtin_fmaf(x.x, x.x, a0);
+        a1 = __builtin_fmaf(x.y, x.y, a1);
+        a2 = __builtin_fmaf(x.z, x.z, a2);
+        a3 = __builtin_fmaf(x.w, x.w, a3);
+    }
+    double tot = team_sum_f64<TEAM>((double)((a0 + a1) + (a2 + a3)), scratch);
+    if (!(tot >= 0x1p-80 && tot <= 0x1p100)) {   // also catches NaN
+        double p = 0.0;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const float4 x = row(i);
+            p += (double)x.x * (double)x.x;
+            p += (double)x.y * (double)x.y;
+            p += (double)x.z * (double)x.z;
+            p += (double)x.w * (double)x.w;
+        }
+        tot = team_sum_f64<TEAM>(p, scratch);
+    }
+    return (float)sqrt(tot);
+}
+
+// ------------------------------------------------------------------ norms kernel
+template <int TEAM, int VPT>
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_bucket_norms(EncodeParams P)
+{
+    __shared__ double scratch[16];
+    const uint32_t tid = threadIdx.x % TEAM;
+    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + threadIdx.x / TEAM;
+    const bool active = b < P.nb;
+    const uint64_t base = active ? b * P.bucket : 0;
+    const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
+    const float *vb = P.v + base;
+    const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
+    auto row = [&](int i) { return load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned); };
+    const float nrm = team_norm<TEAM, VPT>(row, scratch);
+    if (active && tid == 0)
+        P.norms_out[b] = nrm;
+}
+
+// Quantize the four coordinates of one vector; returns the four level|sign<<7 bytes.
+// x0 = (k0 + index of first coordinate) * C1.
+__device__ __forceinline__ uint32_t quantize_vec4(const float4 &x, uint32_t x0, uint32_t k1,
+                                                  const BucketScale &B)
+{
+    const float xs[4] = {x.x, x.y, x.z, x.w};
+    uint32_t packed = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t u = draw24(x0 + (uint32_t)c * kRngC1, k1);
+        const int j = quantize_level(xs[c], u, B);
+        const uint32_t sign = (j > 0) ? ((f2u(xs[c]) >> 24) & 0x80u) : 0u;
+        packed |= ((uint32_t)j | sign) << (8 * c);
+    }
+    return packed;
+}
+
+// --------------------------------------------------------------- quantize kernel
+template <int TEAM, int VPT>
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P)
+{
+    const uint32_t tid = threadIdx.x % TEAM;
+    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + threadIdx.x / TEAM;
+    if (b >= P.nb)
+        return;
+    const uint64_t base = b * P.bucket;
+    const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - base);
+    const float *vb = P.v + base;
+    uint8_t *qb = P.q_out + base;
+    const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
+    const bool qaligned = (reinterpret_cast<uintptr_t>(qb) & 3u) == 0;
+    const BucketScale B = make_scale(P.norms_in[b], (int)P.s);
+    const BucketKey key = bucket_key(P.seed, b);
+#pragma unroll 1
+    for (uint32_t i = 0; i < P.rows; ++i) {
+        const uint32_t vi = i * TEAM + tid;
+        const uint32_t e0 = 4u * vi;
+        if (e0 >= nbk)
+            break;
+        const float4 x = load_vec4(vb, vi, nbk, aligned);
+        const uint32_t packed = B.dead ? 0u : quantize_vec4(x, (key.k0 + e0) * kRngC1, key.k1, B);
+        if (qaligned && e0 + 3u < nbk) {
+            reinterpret_cast<uint32_t *>(qb)[vi] = packed;
+        } else {
+            for (uint32_t c = 0; c < 4u && e0 + c < nbk; ++c)
+                qb[e0 + c] = (uint8_t)(packed >> (8 * c));
+        }
+    }
+}
+
+// ----------------------------------------------------------------- coding phase
+//
+// On entry the team's level/sign bytes are in LDS (qb32, bytes at or beyond the bucket's
+// length are zero) and a barrier has been passed.  Produces the bucket's bit string in
+// LDS `out`, copies it to the bucket's staging slot, writes its bit length and its sync
+// entries.  Every thread of the workgroup must call it (it contains barriers).
+template <int TEAM>
+__device__ __forceinline__ void encode_from_lds(const EncodeParams &P, bool active, uint64_t b,
+                                                const uint32_t *qb32, uint32_t *out,
+                                                uint32_t *sync_l, uint32_t *scratch)
+{
+    const uint32_t tid = threadIdx.x % TEAM;
+    const uint32_t rows = P.rows;
+    const uint32_t base = tid * rows * 4u;
+
+    uint64_t nz = 0;
+    for (uint32_t w = 0; w < rows; ++w) {
+        const uint32_t word = qb32[tid * rows + w];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if ((word >> (8 * k)) & 0x7fu)
+                nz |= 1ull << (4u * w + (uint32_t)k);
+    }
+    const int last = nz ? (int)base + 63 - __clzll((long long)nz) : -1;
+    const int prev0 = team_exclusive_max<TEAM>(last, -1, reinterpret_cast<int *>(scratch));
+
+    const uint8_t *qbytes = reinterpret_cast<const uint8_t *>(qb32);
+    uint32_t bits = 0;
+    {
+        uint64_t m = nz;
+        int p = prev0;
+        while (m) {
+            const int k = __ffsll((unsigned long long)m) - 1;
+            m &= m - 1;
+            const int e = (int)base + k;
+            uint32_t lg, lj;
+            erc_code((uint32_t)(e - p), lg);
+            erc_code((uint32_t)(qbytes[e] & 0x7fu), lj);
+            bits += lg + 1u + lj;
+            p = e;
+        }
+    }
+    uint32_t total;
+    const uint32_t off0 = team_exclusive_sum<TEAM>(bits, scratch + 16, total);
+    const uint32_t nwords = (total + 31u) >> 5;
+    for (uint32_t i = tid; i < nwords; i += TEAM)
+        out[i] = 0u;
+    for (uint32_t i = tid; i < P.nsync; i += TEAM)
+        sync_l[i] = kSyncEmpty;
+    __syncthreads();
+    {
+        uint64_t m = nz;
+        int p = prev0;
+        uint32_t t = off0;
+        while (m) {
+            const int k = __ffsll((unsigned long long)m) - 1;
+            m &= m - 1;
+            const int e = (int)base + k;
+            const uint32_t code = qbytes[e];
+            uint32_t lg, lj;
+            const uint32_t cg = erc_code((uint32_t)(e - p), lg);
+            const uint32_t cj = erc_code(code & 0x7fu, lj);
+            const uint32_t len = lg + 1u + lj;
+            const uint32_t rec = (cg << (1u + lj)) | ((code >> 7) << lj) | cj;
+            const uint32_t wi = t >> 5, bo = t & 31u;
+            const uint64_t sh = (uint64_t)rec << (64u - bo - len);
+            atomicOr(&out[wi], (uint32_t)(sh >> 32));
+            if ((uint32_t)sh)
+                atomicOr(&out[wi + 1u], (uint32_t)sh);
+            if (P.sync_shift) {
+                const int g = e >> P.sync_shift;
+                if (g >= 1 && p < (g << P.sync_shift))
+                    sync_l[g - 1] = t | ((uint32_t)(e - (g << P.sync_shift)) << 21);
+            }
+            t += len;
+            p = e;
+        }
+    }
+    __syncthreads();
+    if (active) {
+        uint32_t *slot = P.staging + b * P.slot_words;
+        for (uint32_t i = tid; i < nwords; i += TEAM)
+            slot[i] = out[i];
+        uint32_t *sg = P.sync + b * P.nsync;
+        for (uint32_t i = tid; i < P.nsync; i += TEAM)
+            sg[i] = sync_l[i];
+        if (tid == 0)
+            P.lens[b] = total;
+    }
+}
+
+// LDS carve-up per team (in 32-bit words): [qb32: rows*TEAM][out: slot_words + 1]
+// [sync: nsync][scratch: 64 (16 ints, 16 uints, 16 doubles)]
+__host__ __device__ inline uint32_t team_lds_words(uint32_t rows, uint32_t team, uint32_t slot_words,
+                                                   uint32_t nsync)
+{
+    uint32_t w = rows * team + slot_words + 1u + nsync;
+    w = (w + 1u) & ~1u;   // keep the scratch 8-byte aligned
+    return w + 64u;
+}
+
+// MODE 0: fused norms + quantize + encode from v.  MODE 1: encode from level/sign bytes.
+template <int TEAM, int VPT, int MODE>
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P)
+{
+    extern __shared__ __align__(16) uint32_t smem[];
+    const uint32_t tid = threadIdx.x % TEAM;
+    const uint32_t team = threadIdx.x / TEAM;
+    uint32_t *lds = smem + team * P.lds_words;
+    uint32_t *qb32 = lds;
+    uint32_t *out = qb32 + P.rows * TEAM;
+    uint32_t *sync_l = out + P.slot_words + 1u;
+    uint32_t *scratch = lds + P.lds_words - 64u;
+
+    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + team;
+    const bool active = b < P.nb;
+    const uint64_t base = active ? b * P.bucket : 0;
+    const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
+
+    if constexpr (MODE == 0) {
+        const float *vb = P.v + base;
+        const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
+        float4 x[VPT];
+#pragma unroll
+        for (int i = 0; i < VPT; ++i)
+            x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
+        auto row = [&](int i) { return x[i]; };
+        const float nrm = team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32));
+        const bool finite = nrm < __builtin_huge_valf();   // false for NaN too
+        if (active && tid == 0) {
+            P.norms_out[b] = nrm;
+            if (!finite)
+                atomicOr(P.flags, kFlagNonfinite);
+        }
+        const BucketScale B = make_scale(nrm, (int)P.s);
+        const BucketKey key = bucket_key(P.seed, b);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            if ((uint32_t)i < P.rows) {
+                const uint32_t vi = (uint32_t)i * TEAM + tid;
+                qb32[vi] = B.dead ? 0u : quantize_vec4(x[i], (key.k0 + 4u * vi) * kRngC1, key.k1, B);
+            }
+        }
+    } else {
+        const uint8_t *qg = P.q_in + base;
+        const bool aligned = (reinterpret_cast<uintptr_t>(qg) & 3u) == 0;
+        for (uint32_t i = 0; i < P.rows; ++i) {
+            const uint32_t vi = i * TEAM + tid;
+            const uint32_t e0 = 4u * vi;
+            uint32_t word = 0;
+            if (aligned && e0 + 3u < nbk) {
+                word = reinterpret_cast<const uint32_t *>(qg)[vi];
+            } else {
+                for (uint32_t c = 0; c < 4u; ++c)
+                    if (e0 + c < nbk)
+                        word |= (uint32_t)qg[e0 + c] << (8u * c);
+            }
+            qb32[vi] = word;
+        }
+    }
+    __syncthreads();
+    encode_from_lds<TEAM>(P, active, b, qb32, out, sync_l, scratch);
+}
+
+// ------------------------------------------------- offsets and gather of the slots
+//
+// wc_b = ceil(len_b / 32) words per bucket; start word of bucket b = sum of wc over earlier
+// buckets; bit_off[b+1] = 32 * start_b + len_b.  Three small kernels: per-1024-bucket sums,
+// a scan of those sums, then offsets.
+
+constexpr int kScanChunk = 1024;
+
+__global__ __launch_bounds__(256) void k_scan_block_sums(const uint32_t *lens, uint64_t nb,
+                                                         uint64_t *block_sums)
+{
+    __shared__ uint32_t scratch[4];
+    const uint64_t i0 = (uint64_t)blockIdx.x * kScanChunk + threadIdx.x * 4u;
+    uint32_t s = 0;
+    for (uint32_t k = 0; k < 4u; ++k)
+        if (i0 + k < nb)
+            s += (lens[i0 + k] + 31u) >> 5;
+    uint32_t total;
+    team_exclusive_sum<256>(s, scratch, total);
+    if (threadIdx.x == 0)
+        block_sums[blockIdx.x] = total;
+}
+
+// Single workgroup: block_sums[i] <- sum of block_sums[0..i) ; block_sums[nblk] <- grand total.
+__global__ __launch_bounds__(256) void k_scan_of_sums(uint64_t *block_sums, uint64_t nblk)
+{
+    __shared__ uint64_t carry;
+    __shared__ uint64_t wave_tot[4];
+    if (threadIdx.x == 0)
+        carry = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (uint64_t i0 = 0; i0 < nblk; i0 += 256) {
+        const uint64_t i = i0 + threadIdx.x;
+        const uint64_t v = i < nblk ? block_sums[i] : 0ull;
+        uint64_t inc = v;
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint64_t t = __shfl_up(inc, off, 64);
+            if (lane >= off)
+                inc += t;
+        }
+        if (lane == 63)
+            wave_tot[wave] = inc;
+        __syncthreads();
+        uint64_t before = carry;
+        for (int w = 0; w < wave; ++w)
+            before += wave_tot[w];
+        if (i < nblk)
+            block_sums[i] = before + inc - v;
+        __syncthreads();
+        if (threadIdx.x == 255)
+            carry = before + inc;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0)
+        block_sums[nblk] = carry;
+}
+
+__global__ __launch_bounds__(256) void k_scan_offsets(const uint32_t *lens, uint64_t nb,
+                                                      const uint64_t *block_sums, uint64_t *bit_off)
+{
+    __shared__ uint32_t scratch[4];
+    const uint64_t i0 = (uint64_t)blockIdx.x * kScanChunk + threadIdx.x * 4u;
+    uint32_t l[4], wc[4], s = 0;
+    for (uint32_t k = 0; k < 4u; ++k) {
+        l[k] = i0 + k < nb ? lens[i0 + k] : 0u;
+        wc[k] = (l[k] + 31u) >> 5;
+        s += wc[k];
+    }
+    uint32_t total;
+    uint64_t start = block_sums[blockIdx.x] + team_exclusive_sum<256>(s, scratch, total);
+    for (uint32_t k = 0; k < 4u; ++k) {
+        if (i0 + k < nb)
+            bit_off[i0 + k + 1] = 32ull * start + l[k];
+        start += wc[k];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        bit_off[0] = 0;
+}
+
+// One wave per bucket copies its staging slot to its place in `words`.
+__global__ __launch_bounds__(256) void k_gather(const uint32_t *staging, uint32_t slot_words,
+                                                const uint64_t *bit_off, uint64_t nb, uint32_t *words,
+                                                uint64_t words_cap, uint32_t *flags)
+{
+    const uint64_t b = (uint64_t)blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (b >= nb)
+        return;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t start = (bit_off[b] + 31ull) >> 5;
+    const uint64_t end = (bit_off[b + 1] + 31ull) >> 5;
+    if (end > words_cap) {
+        if (lane == 0 && end > start)
+            atomicOr(flags, kFlagCapacity);
+        return;
+    }
+    const uint32_t *slot = staging + b * slot_words;
+    for (uint64_t i = start + lane; i < end; i += 64u)
+        words[i] = slot[i - start];
+}
+
+}  // namespace nuq

@@ -1,0 +1,87 @@
+"""Helpers for the GPU parity tests: run the HIP path through the C ABI, run the oracle on the
+same inputs, compare to the bars the tests state."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_1908_06077_amd as nuq
+
+DEV = torch.device("cuda:0")
+
+
+def u32(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint32)
+
+
+def u64(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint64)
+
+
+def alloc_message(d, n, s, S, words_cap=None):
+    B = nuq.nuq_num_buckets(d, n)
+    cap = nuq.nuq_max_words(d, n, s) if words_cap is None else words_cap
+    return nuq.Message(torch.full((B,), -1.0, dtype=torch.float32, device=DEV),
+                       torch.full((B + 1,), -1, dtype=torch.int64, device=DEV),
+                       torch.zeros(max(cap, 1), dtype=torch.int32, device=DEV),
+                       torch.full((max(1, B * nuq.nuq_num_sync(n, S)),), 0x55555555, dtype=torch.int32, device=DEV))
+
+
+def workspace(d, n, s):
+    return torch.empty(nuq.nuq_encode_workspace_bytes(d, n, s), dtype=torch.uint8, device=DEV)
+
+
+def fused_encode(v: torch.Tensor, n, s, seed, S, words_cap=None):
+    m = alloc_message(v.numel(), n, s, S, words_cap)
+    nuq.nuq_quantize_encode(v, n, s, seed, S, m.norms, m.bit_off, m.words, m.sync, workspace(v.numel(), n, s))
+    return m
+
+
+def check_norms(v_np, n, norms_gpu):
+    want = oracle.bucket_norms(v_np, n)
+    got = norms_gpu.astype(np.float64)
+    # bar: 1e-6 relative to the fp64 norm (the benchmark spec); zero norms must be exactly zero.  A norm below the
+    # smallest normal float cannot be held to 1e-6 by the fp32 output format itself: there the bar is half a
+    # unit of the subnormal grid (2^-150), i.e. the correctly rounded value.
+    tol = np.maximum(1e-6 * want, np.where(want > 0, 2.0 ** -150 * (1 + 1e-9), 0.0))
+    assert np.all(np.abs(got - want) <= tol), float(np.max(np.abs(got - want) / np.maximum(want, 1e-300)))
+
+
+def check_message_against_oracle(v_np, n, s, seed, S, m: "nuq.Message", first_bucket=0):
+    """Bit-exact: levels/signs are implied by the bit strings; offsets, words and sync must be identical
+    to the oracle's when it is fed the GPU's norms."""
+    d = v_np.size
+    norms = m.norms.cpu().numpy()
+    q = oracle.quantize(v_np, n, s, seed, norms, first_bucket)
+    bo, words, sync = oracle.encode(q, n, s, S)
+    got_bo = u64(m.bit_off)
+    np.testing.assert_array_equal(got_bo, bo)
+    got_words = u32(m.words)
+    np.testing.assert_array_equal(got_words[: words.size], words)
+    assert not got_words[words.size:].any()          # nothing written past the end
+    if sync.size:
+        np.testing.assert_array_equal(u32(m.sync)[: sync.size], sync)
+    return q, bo, words, sync
+
+
+def check_average(msgs_np, d, n, s, scale, out_gpu: np.ndarray, prior=None):
+    """bars: per bucket ||out - ref||_2 <= 1e-6 ||ref||_2 and per element |diff| <= 1e-6 * scale * sum_k |term_k|."""
+    K = len(msgs_np)
+    scale32 = float(np.float32(scale))
+    want = oracle.decode_average([m[0] for m in msgs_np], [m[1] for m in msgs_np], [m[2] for m in msgs_np],
+                                 d, n, s, scale32, prior=prior)
+    mag = np.zeros(d)
+    for norms, bo, words in msgs_np:
+        q = oracle.decode_levels(bo, words, d, n, s)
+        mag += np.abs(oracle.dequantize(q, n, s, norms))
+    mag = mag * abs(scale32) + (np.abs(prior) if prior is not None else 0.0)
+    got = out_gpu.astype(np.float64)
+    diff = np.abs(got - want)
+    assert np.all(diff <= 1e-6 * mag + 1e-45), float(np.max(diff / np.maximum(mag, 1e-300)))
+    B = (d + n - 1) // n
+    for b in range(B):
+        sl = slice(b * n, min(d, (b + 1) * n))
+        # (+ the fp32 subnormal grid, 2^-149 per element, for outputs below the smallest normal float)
+        assert np.linalg.norm(got[sl] - want[sl]) <= 1e-6 * np.linalg.norm(want[sl]) + 2.0 ** -149 * np.sqrt(n)
+    return want

@@ -1,0 +1,197 @@
+"""GPU parity: every step of the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bars (the benchmark spec the benchmark spec): level indices, signs, offsets, bit strings and sync
+entries bit-exact when the oracle is fed the GPU's norms; norms within 1e-6 relative of the oracle's fp64
+norms; decoded averages within 1e-6 relative."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_util
+    return gpu_util
+
+
+def make_vector(kind, d, n, rng):
+    if kind == "gauss":
+        return (rng.standard_normal(d) * 0.01).astype(np.float32)
+    if kind == "mixed":          # per-chunk scales over many decades, some zero runs, some spikes
+        v = rng.standard_normal(d)
+        scale = 10.0 ** rng.uniform(-6, 1, size=(d + 99) // 100)
+        v *= np.repeat(scale, 100)[:d]
+        v[rng.random(d) < 0.05] = 0.0
+        v[rng.integers(0, d, size=max(1, d // 500))] *= 300.0
+        return v.astype(np.float32)
+    if kind == "edges":          # zero bucket, single spike, on-level ratios, -0.0, constant bucket
+        v = (rng.standard_normal(d) * 0.1).astype(np.float32)
+        if d >= 4 * n:
+            v[0:n] = 0.0
+            v[n:2 * n] = 0.0
+            v[n + n // 2] = -7.5
+            v[2 * n:3 * n] = 0.25
+            v[3 * n:3 * n + min(n, 16)] = -0.0
+        return v
+    raise ValueError(kind)
+
+
+SHAPES = [
+    # (d, bucket, s, sync_stride, kind)
+    (8192, 8192, 3, 512, "gauss"),
+    (100_000, 8192, 3, 512, "mixed"),        # several buckets + ragged tail
+    (100_003, 8192, 4, 1024, "mixed"),
+    (50_000, 8192, 3, 0, "edges"),
+    (5000, 8192, 3, 512, "gauss"),           # d < bucket
+    (70_001, 16384, 7, 1024, "mixed"),
+    (70_001, 16384, 7, 0, "mixed"),          # large bucket without a sync index
+    (40_000, 512, 3, 512, "mixed"),
+    (40_000, 512, 3, 64, "edges"),
+    (33_333, 1000, 2, 256, "mixed"),
+    (9_999, 1001, 5, 128, "mixed"),          # bucket not a multiple of 4: unaligned path
+    (3_000, 7, 1, 0, "mixed"),
+    (1_000, 1, 3, 0, "gauss"),               # bucket of one coordinate: r = 1 always
+    (10_000, 2048, 14, 512, "mixed"),
+    (120_000, 32768, 3, 1024, "mixed"),
+    (66_000, 20000, 9, 512, "edges"),
+    (1, 8192, 3, 512, "gauss"),
+]
+
+
+@pytest.mark.parametrize("d,n,s,S,kind", SHAPES)
+def test_each_step_and_fused_path_match_oracle(g, d, n, s, S, kind):
+    nuq = g.nuq
+    rng = np.random.default_rng(d * 31 + n + s)
+    v_np = make_vector(kind, d, n, rng)
+    v = torch.from_numpy(v_np).to(g.DEV)
+    B = nuq.nuq_num_buckets(d, n)
+    seed = 0x1234_5678_9ABC_DEF0 + d
+
+    # step 1
+    norms = torch.empty(B, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_bucket_norms(v, n, norms)
+    norms_np = norms.cpu().numpy()
+    g.check_norms(v_np, n, norms_np)
+
+    # step 2: level|sign bytes, bit-exact
+    q = torch.full((d,), 0x7F, dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_quantize(v, n, s, seed, norms, q)
+    q_ref = oracle.quantize(v_np, n, s, seed, norms_np)
+    np.testing.assert_array_equal(q.cpu().numpy(), q_ref)
+
+    # step 3: ENCODE of those bytes, bit-exact
+    m = g.alloc_message(d, n, s, S)
+    nuq.nuq_encode(q, n, s, S, m.bit_off, m.words, m.sync if nuq.nuq_num_sync(n, S) else None, g.workspace(d, n, s))
+    bo, words, sync = oracle.encode(q_ref, n, s, S)
+    np.testing.assert_array_equal(g.u64(m.bit_off), bo)
+    np.testing.assert_array_equal(g.u32(m.words)[: words.size], words)
+    assert not g.u32(m.words)[words.size:].any()
+    if sync.size:
+        np.testing.assert_array_equal(g.u32(m.sync)[: sync.size], sync)
+
+    # fused steps 1-3: same norms as step 1 (bit for bit), same message
+    mf = g.fused_encode(v, n, s, seed, S)
+    np.testing.assert_array_equal(mf.norms.cpu().numpy(), norms_np)
+    g.check_message_against_oracle(v_np, n, s, seed, S, mf)
+    assert nuq.nuq_last_error_flags() == 0
+
+    # step 4 with K = 1: DECODE(ENCODE(x)) reproduces Q_s(v)
+    out = torch.full((d,), 7.0, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_decode_accumulate([mf], d, n, s, S, 1.0, False, out)
+    assert nuq.nuq_last_error_flags() == 0
+    g.check_average([(norms_np, bo, words)], d, n, s, 1.0, out.cpu().numpy())
+
+
+@pytest.mark.parametrize("d,n,s,S,K", [(60_000, 8192, 3, 512, 8), (30_000, 512, 3, 0, 4), (50_000, 16384, 7, 1024, 4),
+                                       (20_000, 1000, 4, 256, 32), (9_000, 8192, 3, 512, 3)])
+def test_decode_average_of_K_workers(g, d, n, s, S, K):
+    nuq = g.nuq
+    rng = np.random.default_rng(K * 1000 + n)
+    msgs, msgs_np = [], []
+    for k in range(K):
+        v_np = make_vector("mixed", d, n, rng)
+        m = g.fused_encode(torch.from_numpy(v_np).to(g.DEV), n, s, k, S)
+        q, bo, words, _ = g.check_message_against_oracle(v_np, n, s, k, S, m)
+        msgs.append(m)
+        msgs_np.append((m.norms.cpu().numpy(), bo, words))
+    out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
+    g.check_average(msgs_np, d, n, s, 1.0 / K, out.cpu().numpy())
+    # accumulate = 1 adds to what is there
+    prior = torch.from_numpy(rng.standard_normal(d).astype(np.float32)).to(g.DEV)
+    out2 = prior.clone()
+    nuq.nuq_decode_accumulate(msgs, d, n, s, S, 0.5, True, out2)
+    g.check_average(msgs_np, d, n, s, 0.5, out2.cpu().numpy(), prior=prior.cpu().numpy().astype(np.float64))
+    assert nuq.nuq_last_error_flags() == 0
+
+
+def test_extreme_magnitudes_and_subnormals(g):
+    """Tiny norms (the bucket is rescaled inside the kernel), subnormal coordinates, huge values."""
+    nuq = g.nuq
+    n, s, S = 512, 3, 0
+    rng = np.random.default_rng(77)
+    parts = [rng.standard_normal(n) * sc for sc in (1e-30, 1e-38, 3e-41, 1e-44, 1e18, 1e-19, 1e-22, 1.0)]
+    parts[7][:] = 0.0
+    parts[7][5] = 1e-45          # a single subnormal coordinate: r = 1
+    v_np = np.concatenate(parts).astype(np.float32)
+    v = torch.from_numpy(v_np).to(g.DEV)
+    m = g.fused_encode(v, n, s, 3, S)
+    g.check_norms(v_np, n, m.norms.cpu().numpy())
+    q, bo, words, _ = g.check_message_against_oracle(v_np, n, s, 3, S, m)
+    assert (q[: 6 * n] & 0x7F).any()
+    out = torch.empty(v_np.size, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_decode_accumulate([m], v_np.size, n, s, S, 1.0, False, out)
+    g.check_average([(m.norms.cpu().numpy(), bo, words)], v_np.size, n, s, 1.0, out.cpu().numpy())
+    assert nuq.nuq_last_error_flags() == 0
+
+
+def test_device_flags(g):
+    nuq = g.nuq
+    d, n, s = 20_000, 8192, 3
+    v = torch.randn(d, device=g.DEV)
+    # capacity: offsets are complete, flag raised
+    m = g.fused_encode(v, n, s, 1, 512, words_cap=10)
+    assert nuq.nuq_last_error_flags() == nuq.FLAG_CAPACITY
+    full = g.fused_encode(v, n, s, 1, 512)
+    assert nuq.nuq_last_error_flags() == 0
+    np.testing.assert_array_equal(g.u64(m.bit_off), g.u64(full.bit_off))
+    # non-finite input: flagged, that bucket encoded empty, others untouched
+    v2 = v.clone()
+    v2[100] = float("inf")
+    m2 = g.fused_encode(v2, n, s, 1, 512)
+    assert nuq.nuq_last_error_flags() == nuq.FLAG_NONFINITE
+    bo2, bo = g.u64(m2.bit_off), g.u64(full.bit_off)
+    assert bo2[1] == 0 and bo2[2] - bo2[1] == bo[2] - ((bo[1] + 31) // 32 * 32)
+    # malformed stream: corrupt an offset so a record is cut; decode flags it and returns
+    bad = nuq.Message(full.norms, full.bit_off.clone(), full.words, full.sync)
+    bad.bit_off[1] -= 3
+    out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_decode_accumulate([bad], d, n, s, 512, 1.0, False, out)
+    assert nuq.nuq_last_error_flags() & nuq.FLAG_MALFORMED
+
+
+def test_full_size_configs_1_to_3(g):
+    """BASELINE configs 1-3 at full size, every bucket compared (the oracle needs a few seconds each)."""
+    nuq = g.nuq
+    for cfg in (1, 2, 3):
+        w = workloads.workload(cfg)
+        S = 512
+        K = min(w.K, 2)                 # config 3: two of the eight workers element by element
+        msgs, msgs_np = [], []
+        for k in range(K):
+            v = workloads.generate(w, k, g.DEV)
+            m = g.fused_encode(v, w.bucket, w.s, w.quant_seed(k), S)
+            v_np = v.cpu().numpy()
+            g.check_norms(v_np, w.bucket, m.norms.cpu().numpy())
+            q, bo, words, _ = g.check_message_against_oracle(v_np, w.bucket, w.s, w.quant_seed(k), S, m)
+            msgs.append(m)
+            msgs_np.append((m.norms.cpu().numpy(), bo, words))
+            print("cfg %d worker %d: bits/coord %.4f" % (cfg, k, (32 * len(bo) - 32 + int(bo[-1])) / w.d), flush=True)
+        out = torch.empty(w.d, dtype=torch.float32, device=g.DEV)
+        nuq.nuq_decode_accumulate(msgs, w.d, w.bucket, w.s, S, 1.0 / K, False, out)
+        g.check_average(msgs_np, w.d, w.bucket, w.s, 1.0 / K, out.cpu().numpy())
+        assert nuq.nuq_last_error_flags() == 0
