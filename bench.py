@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the NUQSGD compression hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic gradients: fused
+norms + quantize + ENCODE of each of the K workers' gradients, then DECODE + average of the K
+messages.  The default workload is the benchmark's configs[2] (ResNet-50-shaped, 25.6 M fp32
+parameters, K = 8, bucket 8192, s = 3), the configuration the >= 50 % HBM target is quoted on.
+
+Prints one JSON line:
+  value      = fp32-in GB/s of the whole step: 4*d*K bytes of gradients pushed through
+               encode and decode+average, inputs resident in HBM, per wall second of the step
+  roofline   = the fused quantize+encode kernel (dominant by time), algorithmic bytes per launch
+               over its mean launch duration from HIP events recorded on its stream
+  cpu_baseline = the CPU oracle timed on the same workload on this host (one thread)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (BASELINE.json configs, 1-based)")
+    ap.add_argument("--sync-stride", type=int, default=512)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1908_06077_amd as nuq
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    w = workloads.workload(args.config)
+    d, n, s, K, S = w.d, w.bucket, w.s, w.K, args.sync_stride
+    if n <= S:
+        S = 0
+    B = nuq.nuq_num_buckets(d, n)
+    nsync = nuq.nuq_num_sync(n, S)
+
+    grads = [workloads.generate(w, k, dev) for k in range(K)]
+    ws = torch.empty(nuq.nuq_encode_workspace_bytes(d, n, s), dtype=torch.uint8, device=dev)
+    # size the word buffers from a first encode (worst-case capacity would be 1 B/coord per worker)
+    probe = nuq.Message(torch.empty(B, dtype=torch.float32, device=dev),
+                        torch.empty(B + 1, dtype=torch.int64, device=dev),
+                        torch.zeros(16, dtype=torch.int32, device=dev),
+                        torch.empty(max(1, B * nsync), dtype=torch.int32, device=dev))
+    msgs = []
+    for k in range(K):
+        nuq.nuq_quantize_encode(grads[k], n, s, w.quant_seed(k), S, probe.norms, probe.bit_off, probe.words,
+                                probe.sync, ws)
+        nuq.nuq_last_error_flags()          # capacity flag expected here
+        nwords = (int(probe.bit_off[-1].item()) + 31) // 32
+        msgs.append(nuq.Message(torch.empty(B, dtype=torch.float32, device=dev),
+                                torch.empty(B + 1, dtype=torch.int64, device=dev),
+                                torch.zeros(nwords + 64, dtype=torch.int32, device=dev),
+                                torch.empty(max(1, B * nsync), dtype=torch.int32, device=dev)))
+    out = torch.empty(d, dtype=torch.float32, device=dev)
+
+    def step():
+        for k in range(K):
+            m = msgs[k]
+            nuq.nuq_quantize_encode(grads[k], n, s, w.quant_seed(k), S, m.norms, m.bit_off, m.words, m.sync, ws)
+        nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert nuq.nuq_last_error_flags() == 0, "device error flags raised during warmup"
+
+    # phase split (events on the stream the library launches on) and per-launch kernel brackets
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    nuq.nuq_timing_begin(min(4096, args.steps * (K + 1)))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        for k in range(K):
+            m = msgs[k]
+            nuq.nuq_quantize_encode(grads[k], n, s, w.quant_seed(k), S, m.norms, m.bit_off, m.words, m.sync, ws)
+        ev[i][1].record()
+        nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    launches = nuq.nuq_timing_collect()
+    assert nuq.nuq_last_error_flags() == 0, "device error flags raised during the timed region"
+
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    ms_enc = float(np.median([e[0].elapsed_time(e[1]) for e in ev]))
+    ms_dec = float(np.median([e[1].elapsed_time(e[2]) for e in ev]))
+    in_bytes = 4.0 * d * K
+    value = in_bytes / (ms_step * 1e-3) / 1e9
+
+    # message sizes -> bits per coordinate and algorithmic bytes
+    total_bits = [int(m.bit_off[-1].item()) for m in msgs]
+    starts = [(m.bit_off[:-1] + 31) // 32 * 32 for m in msgs]
+    payload_bits = [int((m.bit_off[1:] - st).sum().item()) for m, st in zip(msgs, starts)]
+    W = [(tb + 31) // 32 for tb in total_bits]
+    paper_bits = float(np.mean([(32 * B + pb) / d for pb in payload_bits]))
+    wire_bits = float(np.mean([(32 * Wk + 32 * B + 64 * (B + 1) + 32 * B * nsync) / d for Wk in W]))
+
+    enc_alg = [4.0 * d + 4 * B + 8 * (B + 1) + 4 * Wk + 4 * B * nsync for Wk in W]      # per worker launch
+    dec_alg = sum(4.0 * Wk + 12 * B + 4 * B * nsync for Wk in W) + 4.0 * d               # per launch
+    enc_ms = [t for e, t in launches if e == nuq.T_QUANTIZE_ENCODE]
+    dec_ms = [t for e, t in launches if e == nuq.T_DECODE]
+    enc_kernel_ms = float(np.mean(enc_ms))
+    dec_kernel_ms = float(np.mean(dec_ms))
+    enc_gbs = float(np.mean(enc_alg)) / (enc_kernel_ms * 1e-3) / 1e9
+    dec_gbs = dec_alg / (dec_kernel_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "quantize+encode and decode+avg GB/s (fp32 in) + % HBM peak; bits/coord",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "configs[%d] %s: d=%d fp32, bucket=%d, s=%d, K=%d workers, sync_stride=%d"
+                               % (args.config - 1, w.name, d, n, s, K, S)},
+        "phases": {
+            "quantize_encode": {"ms": round(ms_enc, 4), "fp32_in_GBps": round(in_bytes / (ms_enc * 1e-3) / 1e9, 2),
+                                "hbm_frac": round(sum(enc_alg) / (ms_enc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+            "decode_average": {"ms": round(ms_dec, 4), "fp32_GBps": round(in_bytes / (ms_dec * 1e-3) / 1e9, 2),
+                               "hbm_frac": round(dec_alg / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        },
+        "bits_per_coord": {"paper": round(paper_bits, 4), "wire": round(wire_bits, 4)},
+        "roofline": {"kernel": "k_encode (fused norms+quantize+ENCODE), one launch per worker",
+                     "bound": "hbm", "achieved": round(enc_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(enc_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "bytes_per_launch": round(float(np.mean(enc_alg))), "launch_ms": round(enc_kernel_ms, 5),
+                     "launches": len(enc_ms)},
+        "roofline_decode": {"kernel": "k_decode_accumulate (DECODE + average of K messages)",
+                            "bound": "hbm", "achieved": round(dec_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": round(dec_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                            "bytes_per_launch": round(dec_alg), "launch_ms": round(dec_kernel_ms, 5),
+                            "launches": len(dec_ms)},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, grads, S)
+    print(json.dumps(result))
+
+
+def cpu_baseline(w, grads, S):
+    """The CPU oracle as it stands, one thread, on the same workload (bounded to ~30 s of CPU work)."""
+    import numpy as np
+    import oracle
+
+    d, n, s, K = w.d, w.bucket, w.s, w.K
+    # bound the sample: the oracle runs ~20 M coordinates/s/worker on the encode side
+    budget_coords = 300_000_000
+    d_s = d if d * K <= budget_coords else max(n, (budget_coords // K) // n * n)
+    host = [g[:d_s].cpu().numpy() for g in grads]
+    t0 = time.perf_counter()
+    parts = []
+    for k in range(K):
+        norms = oracle.bucket_norms(host[k], n).astype(np.float32)
+        q = oracle.quantize(host[k], n, s, w.quant_seed(k), norms)
+        bo, words, _ = oracle.encode(q, n, s, S)
+        parts.append((norms, bo, words))
+    t1 = time.perf_counter()
+    oracle.decode_average([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], d_s, n, s, 1.0 / K)
+    t2 = time.perf_counter()
+    in_bytes = 4.0 * d_s * K
+    return {"value": round(in_bytes / (t2 - t0) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "same workload, first %d of %d coordinates of each of the %d workers; "
+                      "encode %.2f s, decode+average %.2f s" % (d_s, d, K, t1 - t0, t2 - t1)}
+
+
+if __name__ == "__main__":
+    main()

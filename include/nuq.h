@@ -143,6 +143,22 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
  * *host_flags (host pointer) and clears them. */
 int nuq_last_error_flags(uint32_t *host_flags, nuq_stream_t stream);
 
+/* ---- measurement aid (not part of the method) ----------------------------------------- */
+
+/* Entry-point ids reported by nuq_timing_collect. */
+enum { NUQ_T_NORMS = 1, NUQ_T_QUANTIZE = 2, NUQ_T_ENCODE = 3, NUQ_T_QUANTIZE_ENCODE = 4, NUQ_T_DECODE = 5 };
+
+/* After nuq_timing_begin(n), each of the next n launches of a main kernel (the per-bucket kernel
+ * of nuq_bucket_norms / nuq_quantize / nuq_encode / nuq_quantize_encode, the tile kernel of
+ * nuq_decode_accumulate) is bracketed by a pair of HIP events recorded on its stream.  The small
+ * offset-scan and gather kernels of the encoders are outside the brackets.  n <= 4096.
+ * Not thread-safe; meant for benchmarks. */
+int nuq_timing_begin(uint32_t max_launches);
+
+/* Waits for the bracketed launches, writes up to `cap` durations (milliseconds) and entry-point
+ * ids to the HOST arrays ms[] and entry[], the number written to *count, and ends the capture. */
+int nuq_timing_collect(float *ms, int32_t *entry, uint32_t cap, uint32_t *count);
+
 #ifdef __cplusplus
 }
 #endif

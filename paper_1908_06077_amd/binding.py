@@ -34,6 +34,8 @@ _SIGNATURES = {
     "nuq_quantize_encode": (_i32, [_vp, _u64, _u32, _u32, _u64, _u32, _vp, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
     "nuq_decode_accumulate": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _i32, _vp, _vp]),
     "nuq_last_error_flags": (_i32, [_vp, _vp]),
+    "nuq_timing_begin": (_i32, [_u32]),
+    "nuq_timing_collect": (_i32, [_vp, _vp, _u32, _vp]),
 }
 for _name, (_res, _args) in _SIGNATURES.items():
     _fn = getattr(_lib, _name)
@@ -152,3 +154,21 @@ def nuq_last_error_flags() -> int:
     flags = ctypes.c_uint32(0)
     _check("nuq_last_error_flags", _lib.nuq_last_error_flags(ctypes.byref(flags), _stream()))
     return flags.value
+
+
+# ------------------------------------------------------------ measurement aid
+
+T_NORMS, T_QUANTIZE, T_ENCODE, T_QUANTIZE_ENCODE, T_DECODE = 1, 2, 3, 4, 5
+
+
+def nuq_timing_begin(max_launches: int) -> None:
+    _check("nuq_timing_begin", _lib.nuq_timing_begin(max_launches))
+
+
+def nuq_timing_collect(cap: int = 4096) -> list[tuple[int, float]]:
+    """[(entry point id, milliseconds)] for the launches bracketed since nuq_timing_begin."""
+    ms = (ctypes.c_float * cap)()
+    entry = (ctypes.c_int32 * cap)()
+    count = ctypes.c_uint32(0)
+    _check("nuq_timing_collect", _lib.nuq_timing_collect(ms, entry, cap, ctypes.byref(count)))
+    return [(entry[i], ms[i]) for i in range(count.value)]

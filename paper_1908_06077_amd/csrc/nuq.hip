@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
+#include <vector>
 
 #include "nuq_decode_kernels.hpp"
 #include "nuq_device.hpp"
@@ -24,6 +25,31 @@ uint32_t *flags_ptr()
         return nullptr;
     return static_cast<uint32_t *>(p);
 }
+
+// ---- optional per-launch timing (benchmarks only) ----
+struct Timing {
+    std::vector<hipEvent_t> start, stop;
+    std::vector<int32_t> entry;
+    uint32_t cap = 0, used = 0;
+} g_timing;
+
+struct ScopedTiming {
+    hipStream_t st;
+    int slot = -1;
+    ScopedTiming(int entry, hipStream_t s) : st(s)
+    {
+        if (g_timing.used < g_timing.cap) {
+            slot = (int)g_timing.used++;
+            g_timing.entry[slot] = entry;
+            (void)hipEventRecord(g_timing.start[slot], st);
+        }
+    }
+    ~ScopedTiming()
+    {
+        if (slot >= 0)
+            (void)hipEventRecord(g_timing.stop[slot], st);
+    }
+};
 
 uint32_t erc_len_host(uint32_t N)
 {
@@ -173,6 +199,7 @@ int encode_common(const float *v, const uint8_t *q, uint64_t d, uint32_t bucket,
                                 (int)lds_bytes) != hipSuccess)
             return (int)NUQ_EHIP;
         const uint64_t grid = (nb + G::kTeamsPerWG - 1) / G::kTeamsPerWG;
+        ScopedTiming timing(MODE == 0 ? NUQ_T_QUANTIZE_ENCODE : NUQ_T_ENCODE, st);
         hipLaunchKernelGGL(kern, dim3((uint32_t)grid), dim3(G::kWG), lds_bytes, st, P);
         return check_launch();
     });
@@ -224,6 +251,7 @@ int nuq_bucket_norms(const float *v, uint64_t d, uint32_t bucket, float *norms, 
         constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
         using G = TeamGeom<TEAM>;
         const uint64_t grid = (P.nb + G::kTeamsPerWG - 1) / G::kTeamsPerWG;
+        ScopedTiming timing(NUQ_T_NORMS, st);
         hipLaunchKernelGGL((k_bucket_norms<TEAM, VPT>), dim3((uint32_t)grid), dim3(G::kWG), 0, st, P);
         return check_launch();
     });
@@ -249,6 +277,7 @@ int nuq_quantize(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64
         using G = TeamGeom<TEAM>;
         P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
         const uint64_t grid = (P.nb + G::kTeamsPerWG - 1) / G::kTeamsPerWG;
+        ScopedTiming timing(NUQ_T_QUANTIZE, st);
         hipLaunchKernelGGL((k_quantize<TEAM, VPT>), dim3((uint32_t)grid), dim3(G::kWG), 0, st, P);
         return check_launch();
     });
@@ -321,6 +350,7 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
     }
     if (grid > 0x7fffffffull)
         return NUQ_EINVAL;
+    ScopedTiming timing(NUQ_T_DECODE, static_cast<hipStream_t>(stream));
     hipLaunchKernelGGL(k_decode_accumulate, dim3((uint32_t)grid), dim3(256), (size_t)P.tile_coords * 4,
                        static_cast<hipStream_t>(stream), P);
     return check_launch();
@@ -344,6 +374,48 @@ int nuq_last_error_flags(uint32_t *host_flags, nuq_stream_t stream)
     if (hipStreamSynchronize(st) != hipSuccess)
         return NUQ_EHIP;
     return NUQ_OK;
+}
+
+int nuq_timing_begin(uint32_t max_launches)
+{
+    if (max_launches > 4096 || g_timing.cap != 0)
+        return NUQ_EINVAL;
+    g_timing.start.resize(max_launches);
+    g_timing.stop.resize(max_launches);
+    g_timing.entry.assign(max_launches, 0);
+    for (uint32_t i = 0; i < max_launches; ++i)
+        if (hipEventCreate(&g_timing.start[i]) != hipSuccess || hipEventCreate(&g_timing.stop[i]) != hipSuccess)
+            return NUQ_EHIP;
+    g_timing.used = 0;
+    g_timing.cap = max_launches;
+    return NUQ_OK;
+}
+
+int nuq_timing_collect(float *ms, int32_t *entry, uint32_t cap, uint32_t *count)
+{
+    if (!ms || !entry || !count)
+        return NUQ_EINVAL;
+    int rc = NUQ_OK;
+    uint32_t n = 0;
+    for (uint32_t i = 0; i < g_timing.used; ++i) {
+        if (hipEventSynchronize(g_timing.stop[i]) != hipSuccess)
+            rc = NUQ_EHIP;
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, g_timing.start[i], g_timing.stop[i]) != hipSuccess)
+            rc = NUQ_EHIP;
+        if (n < cap) {
+            ms[n] = t;
+            entry[n] = g_timing.entry[i];
+            ++n;
+        }
+    }
+    for (uint32_t i = 0; i < g_timing.cap; ++i) {
+        (void)hipEventDestroy(g_timing.start[i]);
+        (void)hipEventDestroy(g_timing.stop[i]);
+    }
+    g_timing = Timing{};
+    *count = n;
+    return rc;
 }
 
 }  // extern "C"
