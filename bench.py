@@ -36,6 +36,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (BASELINE.json configs, 1-based)")
     ap.add_argument("--sync-stride", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-worker-calls", action="store_true",
+                    help="encode with K nuq_quantize_encode calls instead of one nuq_quantize_encode_batch")
     return ap.parse_args()
 
 
@@ -63,7 +65,8 @@ def main():
     nsync = nuq.nuq_num_sync(n, S)
 
     grads = [workloads.generate(w, k, dev) for k in range(K)]
-    ws = torch.empty(nuq.nuq_encode_workspace_bytes(d, n, s), dtype=torch.uint8, device=dev)
+    ws = torch.empty(nuq.nuq_encode_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=dev)
+    seeds = [w.quant_seed(k) for k in range(K)]
     # size the word buffers from a first encode (worst-case capacity would be 1 B/coord per worker)
     probe = nuq.Message(torch.empty(B, dtype=torch.float32, device=dev),
                         torch.empty(B + 1, dtype=torch.int64, device=dev),
@@ -81,10 +84,16 @@ def main():
                                 torch.empty(max(1, B * nsync), dtype=torch.int32, device=dev)))
     out = torch.empty(d, dtype=torch.float32, device=dev)
 
+    def encode_all():
+        if args.per_worker_calls:
+            for k in range(K):
+                m = msgs[k]
+                nuq.nuq_quantize_encode(grads[k], n, s, seeds[k], S, m.norms, m.bit_off, m.words, m.sync, ws)
+        else:
+            nuq.nuq_quantize_encode_batch(grads, n, s, seeds, S, msgs, ws)
+
     def step():
-        for k in range(K):
-            m = msgs[k]
-            nuq.nuq_quantize_encode(grads[k], n, s, w.quant_seed(k), S, m.norms, m.bit_off, m.words, m.sync, ws)
+        encode_all()
         nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
 
     for _ in range(args.warmup):
@@ -99,9 +108,7 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         ev[i][0].record()
-        for k in range(K):
-            m = msgs[k]
-            nuq.nuq_quantize_encode(grads[k], n, s, w.quant_seed(k), S, m.norms, m.bit_off, m.words, m.sync, ws)
+        encode_all()
         ev[i][1].record()
         nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
         ev[i][2].record()
@@ -124,13 +131,14 @@ def main():
     paper_bits = float(np.mean([(32 * B + pb) / d for pb in payload_bits]))
     wire_bits = float(np.mean([(32 * Wk + 32 * B + 64 * (B + 1) + 32 * B * nsync) / d for Wk in W]))
 
-    enc_alg = [4.0 * d + 4 * B + 8 * (B + 1) + 4 * Wk + 4 * B * nsync for Wk in W]      # per worker launch
+    enc_alg = [4.0 * d + 4 * B + 8 * (B + 1) + 4 * Wk + 4 * B * nsync for Wk in W]      # per worker
     dec_alg = sum(4.0 * Wk + 12 * B + 4 * B * nsync for Wk in W) + 4.0 * d               # per launch
     enc_ms = [t for e, t in launches if e == nuq.T_QUANTIZE_ENCODE]
     dec_ms = [t for e, t in launches if e == nuq.T_DECODE]
     enc_kernel_ms = float(np.mean(enc_ms))
     dec_kernel_ms = float(np.mean(dec_ms))
-    enc_gbs = float(np.mean(enc_alg)) / (enc_kernel_ms * 1e-3) / 1e9
+    enc_launch_bytes = float(np.mean(enc_alg)) if args.per_worker_calls else float(sum(enc_alg))
+    enc_gbs = enc_launch_bytes / (enc_kernel_ms * 1e-3) / 1e9
     dec_gbs = dec_alg / (dec_kernel_ms * 1e-3) / 1e9
 
     result = {
@@ -155,10 +163,11 @@ def main():
                                "hbm_frac": round(dec_alg / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         },
         "bits_per_coord": {"paper": round(paper_bits, 4), "wire": round(wire_bits, 4)},
-        "roofline": {"kernel": "k_encode (fused norms+quantize+ENCODE), one launch per worker",
+        "roofline": {"kernel": "k_encode (fused norms+quantize+ENCODE), one launch per %s"
+                               % ("worker" if args.per_worker_calls else "step (all K workers)"),
                      "bound": "hbm", "achieved": round(enc_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(enc_gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                     "bytes_per_launch": round(float(np.mean(enc_alg))), "launch_ms": round(enc_kernel_ms, 5),
+                     "bytes_per_launch": round(enc_launch_bytes), "launch_ms": round(enc_kernel_ms, 5),
                      "launches": len(enc_ms)},
         "roofline_decode": {"kernel": "k_decode_accumulate (DECODE + average of K messages)",
                             "bound": "hbm", "achieved": round(dec_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",

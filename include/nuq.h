@@ -29,10 +29,12 @@
  *   words[W]      u32, W = ceil(bit_off[B] / 32).  Stream bit t is bit 31-(t%32) of
  *                 words[t/32].  Pad bits are zero.
  *   sync[B*nsync] u32 decoder index, nsync = nuq_num_sync(bucket, sync_stride).
- *                 Entry (b, g), g = 1..nsync, stored at sync[b*nsync + g-1]: for the
- *                 first nonzero whose in-bucket index is in [g*S, (g+1)*S):
- *                 bits 0..20 = bit offset of its record from start_b,
- *                 bits 21..30 = index - g*S;  NUQ_SYNC_EMPTY if there is none.
+ *                 Entry (b, g), g = 1..nsync, stored at sync[b*nsync + g-1], describes the
+ *                 first record whose in-bucket index is >= g*S:
+ *                 bits 0..20 = bit offset of that record from start_b (the bucket's bit
+ *                 length if there is none); if its index is below (g+1)*S:
+ *                 bits 21..30 = index - g*S, bit 31 = 0; otherwise (segment g holds no
+ *                 nonzero) bits 21..30 = 0 and bit 31 (NUQ_SYNC_EMPTY) = 1.
  *   A record, for a nonzero at in-bucket index i whose previous nonzero is at i_prev
  *   (-1 if none): ERC(i - i_prev), one sign bit (1 = negative), ERC(j).
  */
@@ -79,8 +81,9 @@ uint32_t nuq_num_sync(uint32_t bucket, uint32_t sync_stride);
  * i.e. d * (2 + |ERC(s+1)|) bits, plus one word of padding per bucket. */
 uint64_t nuq_max_words(uint64_t d, uint32_t bucket, uint32_t s);
 
-/* Bytes of scratch nuq_encode / nuq_quantize_encode need for these sizes. */
-uint64_t nuq_encode_workspace_bytes(uint64_t d, uint32_t bucket, uint32_t s);
+/* Bytes of scratch the encoders need for K workers of these sizes (K = 1 for nuq_encode and
+ * nuq_quantize_encode); 0 on invalid sizes. */
+uint64_t nuq_encode_workspace_bytes(uint32_t K, uint64_t d, uint32_t bucket, uint32_t s);
 
 /* ---- step 1: bucket norms (Def. 1: r_i = |v_i| / ||v||) --------------------------- */
 
@@ -106,7 +109,7 @@ int nuq_quantize(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64
 /* Encodes the level/sign bytes q[d] into bit_off[B+1], words[<= words_cap] and, when
  * sync_stride != 0, sync[B*nsync] (sync may be NULL when sync_stride == 0).
  * sync_stride: 0, or a power of two in 64..1024.
- * workspace: at least nuq_encode_workspace_bytes(d, bucket, s) bytes, 16-byte aligned;
+ * workspace: at least nuq_encode_workspace_bytes(1, d, bucket, s) bytes, 16-byte aligned;
  * contents are scratch.  If the encoded size exceeds words_cap the device flag
  * NUQ_FLAG_CAPACITY is raised, bit_off is still complete and words holds the buckets
  * that fit.  A level index above s+1 in q is a caller error (undefined bits). */
@@ -121,6 +124,17 @@ int nuq_quantize_encode(const float *v, uint64_t d, uint32_t bucket, uint32_t s,
                         uint32_t sync_stride, float *norms, uint64_t *bit_off, uint32_t *words,
                         uint64_t words_cap, uint32_t *sync, void *workspace,
                         uint64_t workspace_bytes, nuq_stream_t stream);
+
+/* The same for K workers' gradients in one launch (the K simulated workers of Alg. 1 on one
+ * device).  v, norms, bit_off, words, sync: HOST arrays of K device pointers; seeds, words_cap:
+ * HOST arrays of K values.  Worker k's message equals what
+ * nuq_quantize_encode(v[k], ..., seeds[k], ...) produces.  1 <= K <= NUQ_MAX_WORKERS.
+ * workspace: at least nuq_encode_workspace_bytes(K, d, bucket, s) bytes. */
+int nuq_quantize_encode_batch(uint32_t K, const float *const *v, const uint64_t *seeds, uint64_t d,
+                              uint32_t bucket, uint32_t s, uint32_t sync_stride, float *const *norms,
+                              uint64_t *const *bit_off, uint32_t *const *words,
+                              const uint64_t *words_cap, uint32_t *const *sync, void *workspace,
+                              uint64_t workspace_bytes, nuq_stream_t stream);
 
 /* ---- step 4: DECODE + dequantize + aggregate (App. A DECODE; Alg. 1 aggregate) ------ */
 

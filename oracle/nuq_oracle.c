@@ -294,11 +294,14 @@ static uint64_t num_sync(uint32_t bucket, uint32_t sync_stride)
  *
  * sync (may be NULL when sync_stride == 0): for bucket b and segment
  * g = 1 .. ceil(bucket/sync_stride)-1, entry sync[b*nsync + g-1] describes the
- * first record whose coordinate index (0-based, inside the bucket) is in
- * [g*S, (g+1)*S): bits 0..20 = bit offset of that record from the bucket's first
- * bit, bits 21..30 = its index minus g*S; or 0x80000000 when the segment holds
- * no nonzero.  It lets a decoder enter the bucket's bit string at a segment
- * boundary; the bit string itself does not depend on it.
+ * first record whose coordinate index (0-based, inside the bucket) is >= g*S:
+ * bits 0..20 = bit offset of that record from the bucket's first bit (the
+ * bucket's bit length if there is no such record); if that record's index is
+ * inside [g*S, (g+1)*S), bits 21..30 = index - g*S and bit 31 = 0; otherwise
+ * (segment g holds no nonzero) bits 21..30 = 0 and bit 31 = 1.  It lets a
+ * decoder enter the bucket's bit string at a segment boundary and tells it
+ * which bits belong to which run of segments; the bit string itself does not
+ * depend on it.
  *
  * Returns 0, or NUQO_ECAPACITY if words_cap is too small, NUQO_EINVAL on bad
  * arguments or a level index above s+1.
@@ -320,8 +323,7 @@ int nuqo_encode(const uint8_t *q, uint64_t d, uint32_t bucket, int s, uint32_t s
         uint64_t start = (end_prev + 31) / 32 * 32;
         uint64_t t = start;
         int64_t prev = -1; /* 0-based index of the previous nonzero; t_0 = 0 in 1-based terms */
-        for (uint64_t g = 0; g < nsync; g++)
-            sync[b * nsync + g] = NUQO_SYNC_EMPTY;
+        uint64_t next_g = 1; /* first segment whose entry is not written yet */
         for (uint64_t i = lo; i < hi; i++) {
             int j = q[i] & 0x7f;
             if (j == 0)
@@ -329,11 +331,15 @@ int nuqo_encode(const uint8_t *q, uint64_t d, uint32_t bucket, int s, uint32_t s
             if (j > s + 1)
                 return NUQO_EINVAL;
             int64_t idx = (int64_t)(i - lo);
-            if (sync_stride) {
-                uint64_t g = (uint64_t)idx / sync_stride;
-                if (g >= 1 && sync[b * nsync + g - 1] == NUQO_SYNC_EMPTY)
-                    sync[b * nsync + g - 1] =
-                        (uint32_t)(t - start) | ((uint32_t)(idx - g * sync_stride) << 21);
+            /* this record is the first one at or after g*S for every pending g with g*S <= idx */
+            while (next_g <= nsync && next_g * sync_stride <= (uint64_t)idx) {
+                uint32_t e = (uint32_t)(t - start);
+                if ((uint64_t)idx < (next_g + 1) * sync_stride)
+                    e |= (uint32_t)((uint64_t)idx - next_g * sync_stride) << 21;
+                else
+                    e |= NUQO_SYNC_EMPTY;
+                sync[b * nsync + next_g - 1] = e;
+                next_g++;
             }
             uint64_t gap = (uint64_t)(idx - prev);
             int glen = nuqo_erc_encode(gap, code);
@@ -347,6 +353,8 @@ int nuqo_encode(const uint8_t *q, uint64_t d, uint32_t bucket, int s, uint32_t s
             t += len;
             prev = idx;
         }
+        for (; next_g <= nsync; next_g++) /* no record at or after these boundaries */
+            sync[b * nsync + next_g - 1] = (uint32_t)(t - start) | NUQO_SYNC_EMPTY;
         bit_off[b + 1] = t;
         end_prev = t;
     }

@@ -27,7 +27,8 @@ _SIGNATURES = {
     "nuq_num_buckets": (_u64, [_u64, _u32]),
     "nuq_num_sync": (_u32, [_u32, _u32]),
     "nuq_max_words": (_u64, [_u64, _u32, _u32]),
-    "nuq_encode_workspace_bytes": (_u64, [_u64, _u32, _u32]),
+    "nuq_encode_workspace_bytes": (_u64, [_u32, _u64, _u32, _u32]),
+    "nuq_quantize_encode_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]),
     "nuq_bucket_norms": (_i32, [_vp, _u64, _u32, _vp, _vp]),
     "nuq_quantize": (_i32, [_vp, _u64, _u32, _u32, _u64, _vp, _vp, _vp]),
     "nuq_encode": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
@@ -91,8 +92,8 @@ def nuq_max_words(d: int, bucket: int, s: int) -> int:
     return _lib.nuq_max_words(d, bucket, s)
 
 
-def nuq_encode_workspace_bytes(d: int, bucket: int, s: int) -> int:
-    return _lib.nuq_encode_workspace_bytes(d, bucket, s)
+def nuq_encode_workspace_bytes(K: int, d: int, bucket: int, s: int) -> int:
+    return _lib.nuq_encode_workspace_bytes(K, d, bucket, s)
 
 
 # ------------------------------------------------------------------------- the path
@@ -133,6 +134,24 @@ def nuq_quantize_encode(v: torch.Tensor, bucket: int, s: int, seed: int, sync_st
                                     _ptr(norms, torch.float32), _ptr(bit_off, torch.int64),
                                     _ptr(words, torch.int32), words.numel(), _ptr(sync), _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream()))
+
+
+def nuq_quantize_encode_batch(vs: list[torch.Tensor], bucket: int, s: int, seeds: list[int], sync_stride: int,
+                              messages: list["Message"], workspace: torch.Tensor) -> None:
+    K = len(vs)
+    d = vs[0].numel()
+    if any(v.numel() != d for v in vs) or len(seeds) != K or len(messages) != K:
+        raise ValueError("K gradients of equal length, K seeds and K messages are needed")
+    arr = lambda ts, dt=None: (ctypes.c_void_p * K)(*[_ptr(t, dt) for t in ts])
+    u64s = lambda xs: (ctypes.c_uint64 * K)(*[x & (2 ** 64 - 1) for x in xs])
+    _check("nuq_quantize_encode_batch",
+           _lib.nuq_quantize_encode_batch(K, arr(vs, torch.float32), u64s(seeds), d, bucket, s, sync_stride,
+                                          arr([m.norms for m in messages], torch.float32),
+                                          arr([m.bit_off for m in messages], torch.int64),
+                                          arr([m.words for m in messages], torch.int32),
+                                          u64s([m.words.numel() for m in messages]),
+                                          arr([m.sync for m in messages]), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream()))
 
 
 def nuq_decode_accumulate(messages: list[Message], d: int, bucket: int, s: int, sync_stride: int, scale: float,

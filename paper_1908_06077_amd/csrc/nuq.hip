@@ -91,24 +91,24 @@ uint32_t slot_words_for(uint32_t bucket, uint32_t s)
 
 struct Workspace {
     uint32_t *lens;
-    uint64_t *block_sums;
+    uint64_t *chunk_sums;
     uint32_t *staging;
     uint64_t bytes;
 };
 
-Workspace carve(void *base, uint64_t nb, uint32_t slot_words)
+Workspace carve(void *base, uint32_t K, uint64_t nb, uint32_t slot_words)
 {
     auto up = [](uint64_t x) { return (x + 255) & ~255ull; };
-    const uint64_t nblk = (nb + kScanChunk - 1) / kScanChunk;
+    const uint64_t nchunks = (nb + kChunk - 1) / kChunk;
     uint64_t off = 0;
     Workspace w;
     char *p = static_cast<char *>(base);
     w.lens = reinterpret_cast<uint32_t *>(p + off);
-    off += up(nb * 4);
-    w.block_sums = reinterpret_cast<uint64_t *>(p + off);
-    off += up((nblk + 1) * 8);
+    off += up((uint64_t)K * nb * 4);
+    w.chunk_sums = reinterpret_cast<uint64_t *>(p + off);
+    off += up((uint64_t)K * (nchunks + 1) * 8);
     w.staging = reinterpret_cast<uint32_t *>(p + off);
-    off += up(nb * (uint64_t)slot_words * 4);
+    off += up((uint64_t)K * nb * slot_words * 4);
     w.bytes = off;
     return w;
 }
@@ -133,35 +133,38 @@ int check_launch()
     return hipGetLastError() == hipSuccess ? NUQ_OK : NUQ_EHIP;
 }
 
-int run_offsets_and_gather(const Workspace &w, uint64_t nb, uint32_t slot_words, uint64_t *bit_off,
-                           uint32_t *words, uint64_t words_cap, uint32_t *flags, hipStream_t st)
+// Grid of a per-bucket kernel: x = workgroups over the buckets of one worker, y = worker.
+template <int TEAM>
+bool bucket_grid(uint64_t nb, uint32_t K, dim3 &grid)
 {
-    const uint64_t nblk = (nb + kScanChunk - 1) / kScanChunk;
-    hipLaunchKernelGGL(k_scan_block_sums, dim3((uint32_t)nblk), dim3(256), 0, st, w.lens, nb, w.block_sums);
-    hipLaunchKernelGGL(k_scan_of_sums, dim3(1), dim3(256), 0, st, w.block_sums, nblk);
-    hipLaunchKernelGGL(k_scan_offsets, dim3((uint32_t)nblk), dim3(256), 0, st, w.lens, nb, w.block_sums, bit_off);
-    hipLaunchKernelGGL(k_gather, dim3((uint32_t)((nb + 3) / 4)), dim3(256), 0, st, w.staging, slot_words,
-                       bit_off, nb, words, words_cap, flags);
-    return check_launch();
+    const uint64_t gx = (nb + TeamGeom<TEAM>::kTeamsPerWG - 1) / TeamGeom<TEAM>::kTeamsPerWG;
+    if (gx > 0x7fffffffull)
+        return false;
+    grid = dim3((uint32_t)gx, K);
+    return true;
 }
 
+// MODE 0: fused norms + quantize + ENCODE from v.  MODE 1: ENCODE from level/sign bytes.
 template <int MODE>
-int encode_common(const float *v, const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint64_t seed,
-                  uint32_t sync_stride, float *norms, uint64_t *bit_off, uint32_t *words, uint64_t words_cap,
-                  uint32_t *sync, void *workspace, uint64_t workspace_bytes, nuq_stream_t stream)
+int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket, uint32_t s, uint32_t sync_stride,
+                 void *workspace, uint64_t workspace_bytes, nuq_stream_t stream)
 {
-    if (!valid_common(d, bucket, s) || !valid_sync(sync_stride) || !bit_off || !words || !workspace)
-        return NUQ_EINVAL;
-    if ((MODE == 0 && (!v || !norms)) || (MODE == 1 && !q))
+    if (K < 1 || K > kMaxBatch || !valid_common(d, bucket, s) || !valid_sync(sync_stride) || !workspace ||
+        (reinterpret_cast<uintptr_t>(workspace) & 15u))
         return NUQ_EINVAL;
     const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
-    if (nsync && !sync)
-        return NUQ_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(workspace) & 15u) || (MODE == 0 && (reinterpret_cast<uintptr_t>(v) & 3u)))
-        return NUQ_EINVAL;
+    for (uint32_t k = 0; k < K; ++k) {
+        const EncodeWorker &w = Wk.w[k];
+        if (!w.bit_off || !w.words || (nsync && !w.sync))
+            return NUQ_EINVAL;
+        if (MODE == 0 && (!w.v || !w.norms_out || (reinterpret_cast<uintptr_t>(w.v) & 3u)))
+            return NUQ_EINVAL;
+        if (MODE == 1 && !w.q_in)
+            return NUQ_EINVAL;
+    }
     const uint64_t nb = nuq_num_buckets(d, bucket);
     const uint32_t slot_words = slot_words_for(bucket, s);
-    const Workspace w = carve(workspace, nb, slot_words);
+    const Workspace w = carve(workspace, K, nb, slot_words);
     if (w.bytes > workspace_bytes)
         return NUQ_ECAPACITY;
     uint32_t *flags = flags_ptr();
@@ -170,12 +173,8 @@ int encode_common(const float *v, const uint8_t *q, uint64_t d, uint32_t bucket,
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     EncodeParams P{};
-    P.v = v;
-    P.q_in = q;
-    P.norms_out = norms;
     P.d = d;
     P.nb = nb;
-    P.seed = seed;
     P.bucket = bucket;
     P.s = s;
     P.sync_shift = sync_stride ? log2u(sync_stride) : 0;
@@ -183,7 +182,6 @@ int encode_common(const float *v, const uint8_t *q, uint64_t d, uint32_t bucket,
     P.slot_words = slot_words;
     P.lens = w.lens;
     P.staging = w.staging;
-    P.sync = sync;
     P.flags = flags;
     int rc = dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
         constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
@@ -198,14 +196,27 @@ int encode_common(const float *v, const uint8_t *q, uint64_t d, uint32_t bucket,
             hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_bytes) != hipSuccess)
             return (int)NUQ_EHIP;
-        const uint64_t grid = (nb + G::kTeamsPerWG - 1) / G::kTeamsPerWG;
+        dim3 grid;
+        if (!bucket_grid<TEAM>(nb, K, grid))
+            return (int)NUQ_EINVAL;
         ScopedTiming timing(MODE == 0 ? NUQ_T_QUANTIZE_ENCODE : NUQ_T_ENCODE, st);
-        hipLaunchKernelGGL(kern, dim3((uint32_t)grid), dim3(G::kWG), lds_bytes, st, P);
+        hipLaunchKernelGGL(kern, grid, dim3(G::kWG), lds_bytes, st, P, Wk);
         return check_launch();
     });
     if (rc != NUQ_OK)
         return rc;
-    return run_offsets_and_gather(w, nb, slot_words, bit_off, words, words_cap, flags, st);
+
+    // offsets + gather
+    const uint64_t nchunks = (nb + kChunk - 1) / kChunk;
+    const uint64_t *prefix = nullptr;
+    if (nb > kDirectSumMax) {
+        hipLaunchKernelGGL(k_chunk_sums, dim3((uint32_t)nchunks, K), dim3(256), 0, st, w.lens, nb, nchunks,
+                           w.chunk_sums);
+        hipLaunchKernelGGL(k_chunk_scan, dim3(K), dim3(256), 0, st, w.chunk_sums, nchunks);
+        prefix = w.chunk_sums;
+    }
+    hipLaunchKernelGGL(k_finish, dim3((uint32_t)((nb + 3) / 4), K), dim3(256), 0, st, P, Wk, prefix, nchunks);
+    return check_launch();
 }
 
 }  // namespace
@@ -229,11 +240,11 @@ uint64_t nuq_max_words(uint64_t d, uint32_t bucket, uint32_t s)
     return (d * (2u + erc_len_host(s + 1)) + 31) / 32 + nuq_num_buckets(d, bucket);
 }
 
-uint64_t nuq_encode_workspace_bytes(uint64_t d, uint32_t bucket, uint32_t s)
+uint64_t nuq_encode_workspace_bytes(uint32_t K, uint64_t d, uint32_t bucket, uint32_t s)
 {
-    if (!valid_common(d, bucket, s))
+    if (K < 1 || K > kMaxBatch || !valid_common(d, bucket, s))
         return 0;
-    return carve(nullptr, nuq_num_buckets(d, bucket), slot_words_for(bucket, s)).bytes;
+    return carve(nullptr, K, nuq_num_buckets(d, bucket), slot_words_for(bucket, s)).bytes;
 }
 
 int nuq_bucket_norms(const float *v, uint64_t d, uint32_t bucket, float *norms, nuq_stream_t stream)
@@ -241,18 +252,20 @@ int nuq_bucket_norms(const float *v, uint64_t d, uint32_t bucket, float *norms, 
     if (!v || !norms || !valid_common(d, bucket, 1) || (reinterpret_cast<uintptr_t>(v) & 3u))
         return NUQ_EINVAL;
     EncodeParams P{};
-    P.v = v;
-    P.norms_out = norms;
+    EncodeBatch Wk{};
+    Wk.w[0].v = v;
+    Wk.w[0].norms_out = norms;
     P.d = d;
     P.bucket = bucket;
     P.nb = nuq_num_buckets(d, bucket);
     hipStream_t st = static_cast<hipStream_t>(stream);
     return dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
         constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
-        using G = TeamGeom<TEAM>;
-        const uint64_t grid = (P.nb + G::kTeamsPerWG - 1) / G::kTeamsPerWG;
+        dim3 grid;
+        if (!bucket_grid<TEAM>(P.nb, 1, grid))
+            return (int)NUQ_EINVAL;
         ScopedTiming timing(NUQ_T_NORMS, st);
-        hipLaunchKernelGGL((k_bucket_norms<TEAM, VPT>), dim3((uint32_t)grid), dim3(G::kWG), 0, st, P);
+        hipLaunchKernelGGL((k_bucket_norms<TEAM, VPT>), grid, dim3(TeamGeom<TEAM>::kWG), 0, st, P, Wk);
         return check_launch();
     });
 }
@@ -263,22 +276,24 @@ int nuq_quantize(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64
     if (!v || !norms || !q || !valid_common(d, bucket, s) || (reinterpret_cast<uintptr_t>(v) & 3u))
         return NUQ_EINVAL;
     EncodeParams P{};
-    P.v = v;
-    P.norms_in = norms;
-    P.q_out = q;
+    EncodeBatch Wk{};
+    Wk.w[0].v = v;
+    Wk.w[0].norms_in = norms;
+    Wk.w[0].q_out = q;
+    Wk.w[0].seed = seed;
     P.d = d;
     P.bucket = bucket;
     P.s = s;
-    P.seed = seed;
     P.nb = nuq_num_buckets(d, bucket);
     hipStream_t st = static_cast<hipStream_t>(stream);
     return dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
         constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
-        using G = TeamGeom<TEAM>;
         P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
-        const uint64_t grid = (P.nb + G::kTeamsPerWG - 1) / G::kTeamsPerWG;
+        dim3 grid;
+        if (!bucket_grid<TEAM>(P.nb, 1, grid))
+            return (int)NUQ_EINVAL;
         ScopedTiming timing(NUQ_T_QUANTIZE, st);
-        hipLaunchKernelGGL((k_quantize<TEAM, VPT>), dim3((uint32_t)grid), dim3(G::kWG), 0, st, P);
+        hipLaunchKernelGGL((k_quantize<TEAM, VPT>), grid, dim3(TeamGeom<TEAM>::kWG), 0, st, P, Wk);
         return check_launch();
     });
 }
@@ -287,16 +302,48 @@ int nuq_encode(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint32
                uint32_t *words, uint64_t words_cap, uint32_t *sync, void *workspace, uint64_t workspace_bytes,
                nuq_stream_t stream)
 {
-    return encode_common<1>(nullptr, q, d, bucket, s, 0, sync_stride, nullptr, bit_off, words, words_cap, sync,
-                            workspace, workspace_bytes, stream);
+    EncodeBatch Wk{};
+    Wk.w[0].q_in = q;
+    Wk.w[0].bit_off = bit_off;
+    Wk.w[0].words = words;
+    Wk.w[0].words_cap = words_cap;
+    Wk.w[0].sync = sync;
+    return encode_batch<1>(1, Wk, d, bucket, s, sync_stride, workspace, workspace_bytes, stream);
 }
 
 int nuq_quantize_encode(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64_t seed,
                         uint32_t sync_stride, float *norms, uint64_t *bit_off, uint32_t *words, uint64_t words_cap,
                         uint32_t *sync, void *workspace, uint64_t workspace_bytes, nuq_stream_t stream)
 {
-    return encode_common<0>(v, nullptr, d, bucket, s, seed, sync_stride, norms, bit_off, words, words_cap, sync,
-                            workspace, workspace_bytes, stream);
+    EncodeBatch Wk{};
+    Wk.w[0].v = v;
+    Wk.w[0].seed = seed;
+    Wk.w[0].norms_out = norms;
+    Wk.w[0].bit_off = bit_off;
+    Wk.w[0].words = words;
+    Wk.w[0].words_cap = words_cap;
+    Wk.w[0].sync = sync;
+    return encode_batch<0>(1, Wk, d, bucket, s, sync_stride, workspace, workspace_bytes, stream);
+}
+
+int nuq_quantize_encode_batch(uint32_t K, const float *const *v, const uint64_t *seeds, uint64_t d, uint32_t bucket,
+                              uint32_t s, uint32_t sync_stride, float *const *norms, uint64_t *const *bit_off,
+                              uint32_t *const *words, const uint64_t *words_cap, uint32_t *const *sync,
+                              void *workspace, uint64_t workspace_bytes, nuq_stream_t stream)
+{
+    if (K < 1 || K > kMaxBatch || !v || !seeds || !norms || !bit_off || !words || !words_cap)
+        return NUQ_EINVAL;
+    EncodeBatch Wk{};
+    for (uint32_t k = 0; k < K; ++k) {
+        Wk.w[k].v = v[k];
+        Wk.w[k].seed = seeds[k];
+        Wk.w[k].norms_out = norms[k];
+        Wk.w[k].bit_off = bit_off[k];
+        Wk.w[k].words = words[k];
+        Wk.w[k].words_cap = words_cap[k];
+        Wk.w[k].sync = sync ? sync[k] : nullptr;
+    }
+    return encode_batch<0>(K, Wk, d, bucket, s, sync_stride, workspace, workspace_bytes, stream);
 }
 
 int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
@@ -335,24 +382,24 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
     P.scale = scale;
     P.accumulate = accumulate;
     uint64_t grid;
-    if (bucket <= kTileMax) {
-        P.buckets_per_tile = kTileMax / bucket;
+    if (bucket <= kTileCoords) {
+        const uint32_t by_size = kTileCoords / bucket, by_streams = kMaxStreams / K;
+        P.buckets_per_tile = by_size < by_streams ? by_size : by_streams;
         P.tiles_per_bucket = 1;
         P.tile_coords = P.buckets_per_tile * bucket;
         P.segs_per_tile = P.nseg;
         grid = (P.nb + P.buckets_per_tile - 1) / P.buckets_per_tile;
     } else {
         P.buckets_per_tile = 0;
-        P.tile_coords = kTileMax;
-        P.tiles_per_bucket = (bucket + kTileMax - 1) / kTileMax;
-        P.segs_per_tile = P.sync_shift ? (kTileMax >> P.sync_shift) : 1;
+        P.tile_coords = kTileCoords;
+        P.tiles_per_bucket = (bucket + kTileCoords - 1) / kTileCoords;
+        P.segs_per_tile = P.sync_shift ? (kTileCoords >> P.sync_shift) : 1;
         grid = P.nb * P.tiles_per_bucket;
     }
     if (grid > 0x7fffffffull)
         return NUQ_EINVAL;
     ScopedTiming timing(NUQ_T_DECODE, static_cast<hipStream_t>(stream));
-    hipLaunchKernelGGL(k_decode_accumulate, dim3((uint32_t)grid), dim3(256), (size_t)P.tile_coords * 4,
-                       static_cast<hipStream_t>(stream), P);
+    hipLaunchKernelGGL(k_decode_accumulate, dim3((uint32_t)grid), dim3(256), 0, static_cast<hipStream_t>(stream), P);
     return check_launch();
 }
 

@@ -1,10 +1,12 @@
 // DECODE + dequantize + aggregate (App. A DECODE; Alg. 1 aggregate line).
 //
-// A workgroup owns a tile of consecutive output coordinates (whole buckets when the bucket is
-// small, a run of sync segments of one bucket when it is large) and keeps the tile's fp32 sum
-// in LDS.  Each (worker, bucket, segment) bit string is parsed by one lane, sequentially, as the
-// format requires; lanes add their dequantized values into the tile with LDS float atomics;
-// the tile is then written out once, coalesced.
+// A workgroup owns a tile of consecutive output coordinates: whole buckets when the bucket is
+// small, a run of sync segments of one bucket when it is large.  The tile's sum lives in LDS
+// as fp64 (LDS fp64 atomic adds run ~20x faster than fp32 ones on this chip, and a sum of
+// <= 32 fp32 values scaled by powers of two is exact in fp64 unless their exponents span
+// more than 2^29).  The bit strings the tile needs are first copied to LDS with coalesced
+// loads.  Each (worker, bucket, segment) bit string is then parsed by one lane, sequentially,
+// as the format requires; the tile is finally scaled, rounded to fp32 and written out once.
 #pragma once
 #include "nuq_device.hpp"
 #include "nuq_encode_kernels.hpp"
@@ -12,7 +14,10 @@
 namespace nuq {
 
 constexpr uint32_t kMaxWorkers = 32;
-constexpr uint32_t kTileMax = 8192;   // coordinates per workgroup tile (32 KB of LDS)
+constexpr uint32_t kTileCoords = 4096;     // coordinates per workgroup tile (32 KB of fp64)
+constexpr uint32_t kStageWords = 1344;     // LDS words for staged bit strings
+constexpr uint32_t kMaxStreams = 256;      // (bucket, worker) bit strings per tile
+constexpr uint32_t kNoStage = 0xFFFFFFFFu;
 
 struct DecodeParams {
     const float *norms[kMaxWorkers];
@@ -29,96 +34,139 @@ struct DecodeParams {
     uint32_t sync_shift;        // log2 stride, 0 = none
     uint32_t nsync;
     uint32_t nseg;              // segments per bucket (nsync + 1)
-    uint32_t buckets_per_tile;  // >= 1 when bucket <= kTileMax, else 0
+    uint32_t buckets_per_tile;  // >= 1: the tile is this many whole buckets; 0: part of one bucket
     uint32_t tiles_per_bucket;  // >= 1
-    uint32_t tile_coords;       // coordinates a tile spans (full tiles)
-    uint32_t segs_per_tile;     // segments of one bucket inside a tile (large buckets)
+    uint32_t tile_coords;       // coordinates a full tile spans
+    uint32_t segs_per_tile;     // segments of one bucket inside a tile
     float scale;
     int accumulate;
 };
 
-// 32 stream bits starting at bit `pos` (MSB first); bits at or after `end` read as zero and
-// no word at or after `end` is touched.
-__device__ __forceinline__ uint32_t peek32(const uint32_t *words, uint64_t pos, uint64_t end)
+// Branch-free decoder of Alg. 2 for values below 65536 on a 32-bit window (MSB first).
+// Code shapes: "0" -> 1;  "1x0" -> 2..3;  "1x 1y..y 0" -> 4..15 (group of x+1 bits);
+// "1x 1y..y 1z..z 0" -> 16..65535 (group of y+1 bits).  `len` receives the code length
+// (<= 23); returns false if the shape is none of these (a fourth group would follow).
+__device__ __forceinline__ bool erc_decode_bits(uint32_t w, uint32_t &N, uint32_t &len)
 {
-    const uint64_t wi = pos >> 5;
-    const uint32_t bo = (uint32_t)pos & 31u;
-    const uint32_t hi = words[wi];
-    const uint32_t lo = (bo != 0u && ((wi + 1) << 5) < end) ? words[wi + 1] : 0u;
-    return bo ? (hi << bo) | (lo >> (32u - bo)) : hi;
+    const uint32_t g1 = w >> 30;                       // 2 or 3 when the first bit is set
+    const uint32_t k2 = g1 + 1u;                       // width of the second group
+    const uint32_t o2 = 30u - k2;
+    const uint32_t g2 = (w >> o2) & ((1u << k2) - 1u); // second group (leading bit set if present)
+    const uint32_t k3 = g2 + 1u;                       // width of the third group (<= 16)
+    const uint32_t o3 = o2 - min(k3, o2);
+    const uint32_t g3 = (w >> o3) & ((1u << min(k3, 16u)) - 1u);
+    const bool one = (w >> 31) == 0u;
+    const bool two = ((w >> 29) & 1u) == 0u;           // terminator right after the first group
+    const bool three = ((w >> (o2 - 1u)) & 1u) == 0u;  // terminator right after the second group
+    N = one ? 1u : two ? g1 : three ? g2 : g3;
+    len = one ? 1u : two ? 3u : three ? 3u + k2 : 3u + k2 + k3;
+    const bool term_ok = one || two || three || (k3 <= 16u && o3 >= 1u && ((w >> (o3 - 1u)) & 1u) == 0u);
+    return term_ok;
 }
 
-// Parse the records of one segment of one worker's bucket and add their values into `tile`.
-//   seg_lo/seg_hi : in-bucket index range this lane is responsible for
-//   tile_lo       : in-bucket index of tile[0]
-__device__ __forceinline__ void decode_segment(const DecodeParams &P, uint32_t k, uint64_t b,
-                                               uint32_t g, uint32_t nbk, uint32_t seg_lo,
-                                               uint32_t seg_hi, float *tile, int tile_lo)
-{
-    const uint64_t start = (P.bit_off[k][b] + 31ull) & ~31ull;
-    const uint64_t end = P.bit_off[k][b + 1];
-    if (end <= start)
-        return;
-    uint64_t pos = start;
-    int prev = -1;
-    int forced = -1;   // position of the first record when entering through a sync entry
-    if (g > 0u) {
-        if (P.sync_shift) {
-            const uint32_t e = P.sync[k][b * P.nsync + g - 1u];
-            if (e == kSyncEmpty)
-                return;
-            pos = start + (e & 0x1FFFFFu);
-            forced = (int)((g << P.sync_shift) + ((e >> 21) & 0x3FFu));
-            if (pos >= end || forced >= (int)nbk) {
-                atomicOr(P.flags, kFlagMalformed);
-                return;
-            }
-        }
-        // without a sync index the lane walks from the bucket's first record and drops
-        // everything below seg_lo
+// Bit reader over a word array (LDS or global), MSB first, 64-bit buffer.
+template <class WordPtr>
+struct BitReader {
+    WordPtr words;      // word 0 holds stream bit 0 of this reader's frame
+    uint32_t next;      // next word to load
+    uint32_t limit;     // words at or beyond this index read as zero
+    uint64_t buf;       // upcoming bits, MSB aligned
+    uint32_t cnt;       // valid bits in buf
+
+    __device__ __forceinline__ void init(WordPtr w, uint32_t bit_pos, uint32_t limit_words)
+    {
+        words = w;
+        limit = limit_words;
+        next = bit_pos >> 5;
+        const uint32_t bo = bit_pos & 31u;
+        buf = 0;
+        cnt = 0;
+        refill();
+        buf <<= bo;
+        cnt -= bo;
+        refill();
     }
-    const float nrm = P.norms[k][b];
-    const uint32_t *words = P.words[k];
-    while (pos < end) {
-        const uint64_t left = end - pos;
-        int avail = left < 32 ? (int)left : 32;
-        const int avail0 = avail;
-        uint32_t win = peek32(words, pos, end);
-        uint32_t gap, j;
-        bool ok = erc_decode_window(win, avail, gap);
-        ok = ok && avail >= 1;
-        const uint32_t neg = win >> 31;
-        win <<= 1;
-        avail -= 1;
-        ok = ok && erc_decode_window(win, avail, j);
+    __device__ __forceinline__ void refill()
+    {
+        if (cnt <= 32u) {
+            const uint32_t w = next < limit ? words[next] : 0u;
+            ++next;
+            buf |= (uint64_t)w << (32u - cnt);
+            cnt += 32u;
+        }
+    }
+    __device__ __forceinline__ uint32_t peek() const { return (uint32_t)(buf >> 32); }
+    __device__ __forceinline__ void skip(uint32_t n)
+    {
+        buf <<= n;
+        cnt -= n;
+    }
+};
+
+// Parse one unit: the records of worker k's bucket b whose bits lie in [bit_lo, bit_hi)
+// (offsets from the bucket's first bit), and add their values into the tile.
+//   forced   : in-bucket index of the first record (>= 0 when entered through a sync entry,
+//              whose gap code is then skipped), or -1 to start from the bucket's beginning
+//   idx_lo/idx_hi : records below idx_lo are dropped (walks without an index), a record at or
+//              above idx_hi is a format error
+template <class WordPtr>
+__device__ __forceinline__ void decode_unit(const DecodeParams &P, WordPtr words, uint32_t limit_words,
+                                            uint32_t bit_lo, uint32_t bit_hi, int forced, uint32_t idx_lo,
+                                            uint32_t idx_hi, double wnorm, double *tile, int tile_lo)
+{
+    BitReader<WordPtr> br;
+    br.init(words, bit_lo, limit_words);
+    uint32_t pos = bit_lo;
+    int prev = -1;
+    while (pos < bit_hi) {
+        br.refill();
+        uint32_t w = br.peek();
+        uint32_t gap, lg, j, lj;
+        bool ok = erc_decode_bits(w, gap, lg);
+        w <<= lg;
+        const uint32_t neg = w >> 31;
+        w <<= 1;
+        ok = erc_decode_bits(w, j, lj) && ok;
+        const uint32_t len = lg + 1u + lj;
         int idx = prev + (int)gap;
         if (forced >= 0) {
             idx = forced;
             forced = -1;
         }
-        if (!ok || idx >= (int)nbk || idx <= prev || j < 1u || j > P.s + 1u) {
+        if (!ok || len > 31u || pos + len > bit_hi || idx <= prev || (uint32_t)idx >= idx_hi || j < 1u ||
+            j > P.s + 1u) {
             atomicOr(P.flags, kFlagMalformed);
             return;
         }
-        if ((uint32_t)idx >= seg_hi)
-            return;
-        if ((uint32_t)idx >= seg_lo) {
-            // ||v|| * l_j with l_j = 2^(j-1-s): an exact power-of-two scaling
-            float val = ldexpf(nrm, (int)j - 1 - (int)P.s);
+        if ((uint32_t)idx >= idx_lo) {
+            // ||v|| * l_j = (||v|| * 2^(-1-s)) * 2^j, exact in fp64
+            double val = ldexp(wnorm, (int)j);
             atomicAdd(&tile[idx - tile_lo], neg ? -val : val);
         }
-        pos += (uint64_t)(avail0 - avail);
+        br.skip(len);
+        pos += len;
         prev = idx;
     }
 }
 
+struct GlobalWords {
+    const uint32_t *p;
+    __device__ __forceinline__ uint32_t operator[](uint32_t i) const { return p[i]; }
+};
+
 __global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
 {
-    extern __shared__ __align__(16) float tile[];
-    // Which coordinates does this tile cover?
+    __shared__ __align__(16) double tile[kTileCoords];
+    __shared__ uint32_t stage[kStageWords];
+    __shared__ uint32_t st_lds[kMaxStreams];     // LDS word offset of a staged bit string, or kNoStage
+    __shared__ uint32_t st_bit0[kMaxStreams];    // first staged bit (multiple of 32), from the bucket's first bit
+    __shared__ uint32_t st_bit1[kMaxStreams];    // one past the last staged bit
+    __shared__ uint32_t scan_scratch[4];
+
+    // ---- which coordinates does this tile cover?
     uint64_t b0;        // first bucket of the tile
-    uint32_t nbuck;     // buckets in the tile (small buckets) or 1
-    uint32_t in_lo;     // in-bucket index where the tile starts (large buckets)
+    uint32_t nbuck;     // buckets in the tile
+    uint32_t in_lo;     // in-bucket index where the tile starts (tiles that are part of a bucket)
     if (P.buckets_per_tile) {
         b0 = (uint64_t)blockIdx.x * P.buckets_per_tile;
         nbuck = (uint32_t)min((uint64_t)P.buckets_per_tile, P.nb - b0);
@@ -128,50 +176,196 @@ __global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
         nbuck = 1;
         in_lo = (blockIdx.x % P.tiles_per_bucket) * P.tile_coords;
     }
-    const uint64_t c_lo = b0 * P.bucket + in_lo;                       // first coordinate
-    const uint64_t c_hi = P.buckets_per_tile
-                              ? min(P.d, (b0 + nbuck) * (uint64_t)P.bucket)
-                              : min(P.d, min(c_lo + P.tile_coords, (b0 + 1) * (uint64_t)P.bucket));
+    const uint64_t c_lo = b0 * P.bucket + in_lo;
+    const uint64_t c_hi = P.buckets_per_tile ? min(P.d, (b0 + nbuck) * (uint64_t)P.bucket)
+                                             : min(P.d, min(c_lo + P.tile_coords, (b0 + 1) * (uint64_t)P.bucket));
     if (c_hi <= c_lo)   // a tile of the (short) last bucket that starts beyond the vector's end
         return;
     const uint32_t span = (uint32_t)(c_hi - c_lo);
-    for (uint32_t i = threadIdx.x; i < span; i += blockDim.x)
-        tile[i] = 0.0f;
-    __syncthreads();
+    const uint32_t g0 = P.sync_shift ? (in_lo >> P.sync_shift) : 0u;                // first segment of the tile
+    const bool partial = !P.buckets_per_tile;                                        // part of one bucket
+    const uint32_t g1 = partial && P.sync_shift ? min(P.nseg, g0 + P.segs_per_tile) : P.nseg;   // one past the last
 
-    // Parse units: (bucket in tile, segment in tile, worker).
-    const uint32_t segs = P.buckets_per_tile ? P.nseg : P.segs_per_tile;
-    const uint32_t units = nbuck * segs * P.K;
-    for (uint32_t u = threadIdx.x; u < units; u += blockDim.x) {
-        const uint32_t k = u % P.K;
-        const uint32_t r = u / P.K;
-        const uint32_t sg = r % segs;
-        const uint64_t b = b0 + r / segs;
-        const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
-        uint32_t g, seg_lo, seg_hi;
-        if (P.sync_shift) {
-            g = (in_lo >> P.sync_shift) + sg;
-            seg_lo = g << P.sync_shift;
-            seg_hi = min(nbk, (g + 1u) << P.sync_shift);
-        } else if (P.buckets_per_tile) {
-            g = 0;
-            seg_lo = 0;
-            seg_hi = nbk;
-        } else {                          // large bucket without an index: walk from the start
-            g = in_lo ? 1u : 0u;
-            seg_lo = in_lo;
-            seg_hi = min(nbk, in_lo + P.tile_coords);
+    for (uint32_t i = threadIdx.x; i < (span + 1u) / 2u; i += 256u)
+        reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
+
+    // ---- stage the bit strings: stream = (bucket in tile, worker)
+    const uint32_t nstreams = nbuck * P.K;
+    uint32_t my_words = 0, my_w0 = 0;
+    const uint32_t *my_src = nullptr;
+    if (threadIdx.x < nstreams) {
+        const uint32_t k = threadIdx.x % P.K;
+        const uint64_t b = b0 + threadIdx.x / P.K;
+        const uint64_t start = (P.bit_off[k][b] + 31ull) & ~31ull;
+        const uint64_t end = P.bit_off[k][b + 1];
+        uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
+        uint32_t lo = 0, hi = len;
+        if (partial && P.sync_shift) {
+            const uint32_t *sy = P.sync[k] + b * P.nsync;
+            if (g0 > 0u)
+                lo = min(sy[g0 - 1u] & 0x1FFFFFu, len);
+            if (g1 < P.nseg)
+                hi = min(sy[g1 - 1u] & 0x1FFFFFu, len);
         }
-        if (seg_lo >= nbk)
-            continue;
-        const int tile_lo = P.buckets_per_tile ? -(int)((b - b0) * P.bucket) : (int)in_lo;
-        decode_segment(P, k, b, g, nbk, seg_lo, seg_hi, tile, tile_lo);
+        my_w0 = lo >> 5;
+        my_words = hi > lo ? ((hi + 31u) >> 5) - my_w0 : 0u;
+        if (partial && !P.sync_shift)
+            my_words = 0u;               // walked from global memory (see below)
+        my_src = P.words[k] + (start >> 5) + my_w0;
+    }
+    uint32_t total_words;
+    const uint32_t my_off = team_exclusive_sum<256>(my_words, scan_scratch, total_words);
+    if (threadIdx.x < nstreams) {
+        st_lds[threadIdx.x] = (my_off + my_words <= kStageWords) ? my_off : kNoStage;
+        st_bit0[threadIdx.x] = my_w0 << 5;
+        st_bit1[threadIdx.x] = (my_w0 + my_words) << 5;
+    }
+    // each wave copies streams wave, wave+4, ...; descriptors travel by shuffle inside the wave
+    {
+        const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+        for (uint32_t l = 0; l < 64u; ++l) {                       // nstreams <= 256 = 4 waves x 64
+            const uint32_t sidx = wave * 64u + l;
+            if (sidx >= nstreams)
+                break;
+            const uint32_t nw = __shfl(my_words, (int)l, 64);
+            const uint32_t off = __shfl(my_off, (int)l, 64);
+            const uint64_t src = __shfl((unsigned long long)reinterpret_cast<uintptr_t>(my_src), (int)l, 64);
+            if (off + nw > kStageWords)
+                continue;
+            const uint32_t *sp = reinterpret_cast<const uint32_t *>(src);
+            for (uint32_t i = lane; i < nw; i += 64u)
+                stage[off + i] = sp[i];
+        }
     }
     __syncthreads();
+
+    // ---- parse units: (bucket in tile, segment in tile, worker)
+    const uint32_t segs = g1 - g0;
+    const uint32_t units = nbuck * segs * P.K;
+    const double wscale = ldexp(1.0, -1 - (int)P.s);
+    for (uint32_t u = threadIdx.x; u < units; u += 256u) {
+        const uint32_t k = u % P.K;
+        const uint32_t r = u / P.K;
+        const uint32_t g = g0 + r % segs;
+        const uint32_t bi = r / segs;
+        const uint64_t b = b0 + bi;
+        const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
+        const uint32_t sidx = bi * P.K + k;
+        const uint64_t start = (P.bit_off[k][b] + 31ull) & ~31ull;
+        const uint64_t end = P.bit_off[k][b + 1];
+        const uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
+        uint32_t bit_lo = 0, bit_hi = len, idx_lo = 0, idx_hi = nbk;
+        int forced = -1;
+        if (P.sync_shift) {
+            const uint32_t *sy = P.sync[k] + b * P.nsync;
+            idx_lo = g << P.sync_shift;
+            idx_hi = min(nbk, (g + 1u) << P.sync_shift);
+            if (idx_lo >= nbk)
+                continue;
+            if (g > 0u) {
+                const uint32_t e = sy[g - 1u];
+                if (e & kSyncEmpty)
+                    continue;
+                bit_lo = e & 0x1FFFFFu;
+                forced = (int)(idx_lo + ((e >> 21) & 0x3FFu));
+            }
+            if (g + 1u < P.nseg)
+                bit_hi = sy[g] & 0x1FFFFFu;
+            if (bit_lo > bit_hi || bit_hi > len) {
+                atomicOr(P.flags, kFlagMalformed);
+                continue;
+            }
+        } else if (partial) {            // part of a large bucket without an index: walk from its start
+            idx_lo = in_lo;
+            idx_hi = nbk;                // later tiles' records are met too; stop at the tile's end below
+            if (idx_lo >= nbk)
+                continue;
+        }
+        const double wnorm = (double)P.norms[k][b] * wscale;
+        const int tile_lo = partial ? (int)in_lo : -(int)(bi * P.bucket);
+        const uint32_t loff = st_lds[sidx];
+        if (partial && !P.sync_shift) {
+            // slow path: global words, records beyond the tile are skipped by bounding idx_hi
+            GlobalWords gw{P.words[k] + (start >> 5)};
+            const uint32_t hi_idx = min(nbk, in_lo + P.tile_coords);
+            // parse the whole bucket; only [idx_lo, hi_idx) lands in the tile
+            BitReader<GlobalWords> br;
+            br.init(gw, 0, (len + 31u) >> 5);
+            uint32_t pos = 0;
+            int prev = -1;
+            while (pos < len) {
+                br.refill();
+                uint32_t w = br.peek(), gap, lg, j, lj;
+                bool ok = erc_decode_bits(w, gap, lg);
+                w <<= lg;
+                const uint32_t neg = w >> 31;
+                w <<= 1;
+                ok = erc_decode_bits(w, j, lj) && ok;
+                const uint32_t rl = lg + 1u + lj;
+                const int idx = prev + (int)gap;
+                if (!ok || rl > 31u || pos + rl > len || (uint32_t)idx >= nbk || j < 1u || j > P.s + 1u) {
+                    atomicOr(P.flags, kFlagMalformed);
+                    break;
+                }
+                if ((uint32_t)idx >= hi_idx)
+                    break;
+                if ((uint32_t)idx >= idx_lo) {
+                    const double val = ldexp(wnorm, (int)j);
+                    atomicAdd(&tile[idx - tile_lo], neg ? -val : val);
+                }
+                br.skip(rl);
+                pos += rl;
+                prev = idx;
+            }
+        } else if (loff != kNoStage) {
+            const uint32_t bit0 = st_bit0[sidx];
+            if (bit_lo < bit0 || bit_hi > st_bit1[sidx]) {   // a sync index that is not monotone
+                atomicOr(P.flags, kFlagMalformed);
+                continue;
+            }
+            const uint32_t *lw = stage + loff;
+            decode_unit(P, lw, ((bit_hi + 31u) >> 5) - (bit0 >> 5), bit_lo - bit0, bit_hi - bit0, forced, idx_lo, idx_hi,
+                        wnorm, tile, tile_lo);
+        } else {
+            GlobalWords gw{P.words[k] + (start >> 5)};
+            decode_unit(P, gw, (bit_hi + 31u) >> 5, bit_lo, bit_hi, forced, idx_lo, idx_hi, wnorm, tile, tile_lo);
+        }
+    }
+    __syncthreads();
+
+    // ---- scale, round to fp32, write
     float *o = P.out + c_lo;
-    for (uint32_t i = threadIdx.x; i < span; i += blockDim.x) {
-        const float val = P.scale * tile[i];
-        o[i] = P.accumulate ? o[i] + val : val;
+    const double sc = (double)P.scale;
+    const bool vec = (reinterpret_cast<uintptr_t>(o) & 15u) == 0;
+    if (vec) {
+        const uint32_t n4 = span >> 2;
+        for (uint32_t i = threadIdx.x; i < n4; i += 256u) {
+            const double2 a = reinterpret_cast<const double2 *>(tile)[2u * i];
+            const double2 c = reinterpret_cast<const double2 *>(tile)[2u * i + 1u];
+            float4 r;
+            r.x = (float)(sc * a.x);
+            r.y = (float)(sc * a.y);
+            r.z = (float)(sc * c.x);
+            r.w = (float)(sc * c.y);
+            float4 *dst = reinterpret_cast<float4 *>(o) + i;
+            if (P.accumulate) {
+                const float4 old = *dst;
+                r.x += old.x;
+                r.y += old.y;
+                r.z += old.z;
+                r.w += old.w;
+            }
+            *dst = r;
+        }
+        for (uint32_t i = (n4 << 2) + threadIdx.x; i < span; i += 256u) {
+            const float r = (float)(sc * tile[i]);
+            o[i] = P.accumulate ? o[i] + r : r;
+        }
+    } else {
+        for (uint32_t i = threadIdx.x; i < span; i += 256u) {
+            const float r = (float)(sc * tile[i]);
+            o[i] = P.accumulate ? o[i] + r : r;
+        }
     }
 }
 

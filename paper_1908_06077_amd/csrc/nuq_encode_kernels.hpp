@@ -12,15 +12,29 @@ namespace nuq {
 constexpr uint32_t kFlagCapacity = 1u, kFlagNonfinite = 2u, kFlagMalformed = 4u;
 constexpr uint32_t kSyncEmpty = 0x80000000u;
 
-struct EncodeParams {
+constexpr uint32_t kMaxBatch = 32;   // workers per launch
+
+// Per-worker pointers of a batched launch (blockIdx.y selects the worker).
+struct EncodeWorker {
     const float *v;        // fused / quantize / norms input
     const uint8_t *q_in;   // encode-from-bytes input
     uint8_t *q_out;        // quantize output
     const float *norms_in; // quantize input
     float *norms_out;      // norms / fused output
+    uint32_t *sync;        // [nb * nsync]
+    uint64_t *bit_off;     // [nb + 1]
+    uint32_t *words;
+    uint64_t words_cap;
+    uint64_t seed;
+};
+
+struct EncodeBatch {
+    EncodeWorker w[kMaxBatch];
+};
+
+struct EncodeParams {
     uint64_t d;
     uint64_t nb;
-    uint64_t seed;
     uint32_t bucket;
     uint32_t s;
     uint32_t sync_shift;   // log2(sync stride), 0 = no sync
@@ -28,9 +42,8 @@ struct EncodeParams {
     uint32_t slot_words;   // staging words per bucket
     uint32_t rows;         // ceil(bucket / (4*TEAM))
     uint32_t lds_words;    // LDS words per team
-    uint32_t *lens;        // [nb] payload bits per bucket
-    uint32_t *staging;     // [nb * slot_words]
-    uint32_t *sync;        // [nb * nsync]
+    uint32_t *lens;        // [K * nb] payload bits per bucket, worker-major
+    uint32_t *staging;     // [K * nb * slot_words]
     uint32_t *flags;
 };
 
@@ -87,20 +100,21 @@ __device__ __forceinline__ float team_norm(Row row, double *scratch)
 
 // ------------------------------------------------------------------ norms kernel
 template <int TEAM, int VPT>
-__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_bucket_norms(EncodeParams P)
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_bucket_norms(EncodeParams P, EncodeBatch Wk)
 {
     __shared__ double scratch[16];
+    const EncodeWorker &W = Wk.w[blockIdx.y];
     const uint32_t tid = threadIdx.x % TEAM;
     const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + threadIdx.x / TEAM;
     const bool active = b < P.nb;
     const uint64_t base = active ? b * P.bucket : 0;
     const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
-    const float *vb = P.v + base;
+    const float *vb = W.v + base;
     const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
     auto row = [&](int i) { return load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned); };
     const float nrm = team_norm<TEAM, VPT>(row, scratch);
     if (active && tid == 0)
-        P.norms_out[b] = nrm;
+        W.norms_out[b] = nrm;
 }
 
 // Quantize the four coordinates of one vector; returns the four level|sign<<7 bytes.
@@ -122,20 +136,21 @@ __device__ __forceinline__ uint32_t quantize_vec4(const float4 &x, uint32_t x0, 
 
 // --------------------------------------------------------------- quantize kernel
 template <int TEAM, int VPT>
-__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P)
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P, EncodeBatch Wk)
 {
+    const EncodeWorker &W = Wk.w[blockIdx.y];
     const uint32_t tid = threadIdx.x % TEAM;
     const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + threadIdx.x / TEAM;
     if (b >= P.nb)
         return;
     const uint64_t base = b * P.bucket;
     const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - base);
-    const float *vb = P.v + base;
-    uint8_t *qb = P.q_out + base;
+    const float *vb = W.v + base;
+    uint8_t *qb = W.q_out + base;
     const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
     const bool qaligned = (reinterpret_cast<uintptr_t>(qb) & 3u) == 0;
-    const BucketScale B = make_scale(P.norms_in[b], (int)P.s);
-    const BucketKey key = bucket_key(P.seed, b);
+    const BucketScale B = make_scale(W.norms_in[b], (int)P.s);
+    const BucketKey key = bucket_key(W.seed, b);
 #pragma unroll 1
     for (uint32_t i = 0; i < P.rows; ++i) {
         const uint32_t vi = i * TEAM + tid;
@@ -160,7 +175,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P
 // LDS `out`, copies it to the bucket's staging slot, writes its bit length and its sync
 // entries.  Every thread of the workgroup must call it (it contains barriers).
 template <int TEAM>
-__device__ __forceinline__ void encode_from_lds(const EncodeParams &P, bool active, uint64_t b,
+__device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const EncodeWorker &W, bool active, uint64_t b,
                                                 const uint32_t *qb32, uint32_t *out,
                                                 uint32_t *sync_l, uint32_t *scratch)
 {
@@ -201,7 +216,7 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, bool acti
     for (uint32_t i = tid; i < nwords; i += TEAM)
         out[i] = 0u;
     for (uint32_t i = tid; i < P.nsync; i += TEAM)
-        sync_l[i] = kSyncEmpty;
+        sync_l[i] = total | kSyncEmpty;   // "no record at or after this boundary" until one is found
     __syncthreads();
     {
         uint64_t m = nz;
@@ -223,9 +238,10 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, bool acti
             if ((uint32_t)sh)
                 atomicOr(&out[wi + 1u], (uint32_t)sh);
             if (P.sync_shift) {
-                const int g = e >> P.sync_shift;
-                if (g >= 1 && p < (g << P.sync_shift))
-                    sync_l[g - 1] = t | ((uint32_t)(e - (g << P.sync_shift)) << 21);
+                // this record is the first one at or after every segment boundary in (p, e]
+                const int g_hi = e >> P.sync_shift;
+                for (int g = max((p >> P.sync_shift) + 1, 1); g <= g_hi; ++g)
+                    sync_l[g - 1] = g == g_hi ? (t | ((uint32_t)(e - (g << P.sync_shift)) << 21)) : (t | kSyncEmpty);
             }
             t += len;
             p = e;
@@ -233,14 +249,15 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, bool acti
     }
     __syncthreads();
     if (active) {
-        uint32_t *slot = P.staging + b * P.slot_words;
+        const uint64_t gb = (uint64_t)blockIdx.y * P.nb + b;   // bucket index over the whole batch
+        uint32_t *slot = P.staging + gb * P.slot_words;
         for (uint32_t i = tid; i < nwords; i += TEAM)
             slot[i] = out[i];
-        uint32_t *sg = P.sync + b * P.nsync;
+        uint32_t *sg = W.sync + b * P.nsync;
         for (uint32_t i = tid; i < P.nsync; i += TEAM)
             sg[i] = sync_l[i];
         if (tid == 0)
-            P.lens[b] = total;
+            P.lens[gb] = total;
     }
 }
 
@@ -256,9 +273,10 @@ __host__ __device__ inline uint32_t team_lds_words(uint32_t rows, uint32_t team,
 
 // MODE 0: fused norms + quantize + encode from v.  MODE 1: encode from level/sign bytes.
 template <int TEAM, int VPT, int MODE>
-__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P)
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, EncodeBatch Wk)
 {
     extern __shared__ __align__(16) uint32_t smem[];
+    const EncodeWorker &W = Wk.w[blockIdx.y];
     const uint32_t tid = threadIdx.x % TEAM;
     const uint32_t team = threadIdx.x / TEAM;
     uint32_t *lds = smem + team * P.lds_words;
@@ -273,7 +291,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P)
     const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
 
     if constexpr (MODE == 0) {
-        const float *vb = P.v + base;
+        const float *vb = W.v + base;
         const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
         float4 x[VPT];
 #pragma unroll
@@ -283,12 +301,12 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P)
         const float nrm = team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32));
         const bool finite = nrm < __builtin_huge_valf();   // false for NaN too
         if (active && tid == 0) {
-            P.norms_out[b] = nrm;
+            W.norms_out[b] = nrm;
             if (!finite)
                 atomicOr(P.flags, kFlagNonfinite);
         }
         const BucketScale B = make_scale(nrm, (int)P.s);
-        const BucketKey key = bucket_key(P.seed, b);
+        const BucketKey key = bucket_key(W.seed, b);
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             if ((uint32_t)i < P.rows) {
@@ -297,7 +315,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P)
             }
         }
     } else {
-        const uint8_t *qg = P.q_in + base;
+        const uint8_t *qg = W.q_in + base;
         const bool aligned = (reinterpret_cast<uintptr_t>(qg) & 3u) == 0;
         for (uint32_t i = 0; i < P.rows; ++i) {
             const uint32_t vi = i * TEAM + tid;
@@ -314,47 +332,64 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P)
         }
     }
     __syncthreads();
-    encode_from_lds<TEAM>(P, active, b, qb32, out, sync_l, scratch);
+    encode_from_lds<TEAM>(P, W, active, b, qb32, out, sync_l, scratch);
 }
 
 // ------------------------------------------------- offsets and gather of the slots
 //
-// wc_b = ceil(len_b / 32) words per bucket; start word of bucket b = sum of wc over earlier
-// buckets; bit_off[b+1] = 32 * start_b + len_b.  Three small kernels: per-1024-bucket sums,
-// a scan of those sums, then offsets.
+// wc_b = ceil(len_b / 32) words per bucket; start word of bucket b = sum of wc over the worker's
+// earlier buckets; bit_off[b+1] = 32 * start_b + len_b.  One "finish" kernel per batch: a
+// workgroup owns four buckets of one worker, sums the word counts before them (directly, or
+// from per-chunk prefix sums when the worker has many buckets), writes their offsets and
+// copies their staging slots (one wave per bucket) to their place in `words`.
 
-constexpr int kScanChunk = 1024;
+constexpr uint32_t kChunk = 1024;          // buckets per chunk of the two-level sum
+constexpr uint64_t kDirectSumMax = 8192;   // up to this many buckets every workgroup sums directly
 
-__global__ __launch_bounds__(256) void k_scan_block_sums(const uint32_t *lens, uint64_t nb,
-                                                         uint64_t *block_sums)
+__device__ __forceinline__ uint64_t block_sum_u64(uint64_t x, uint64_t *scratch /* 4 */)
 {
-    __shared__ uint32_t scratch[4];
-    const uint64_t i0 = (uint64_t)blockIdx.x * kScanChunk + threadIdx.x * 4u;
-    uint32_t s = 0;
-    for (uint32_t k = 0; k < 4u; ++k)
-        if (i0 + k < nb)
-            s += (lens[i0 + k] + 31u) >> 5;
-    uint32_t total;
-    team_exclusive_sum<256>(s, scratch, total);
-    if (threadIdx.x == 0)
-        block_sums[blockIdx.x] = total;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        x += __shfl_xor((unsigned long long)x, off, kWave);
+    __syncthreads();
+    if ((threadIdx.x & 63u) == 0)
+        scratch[threadIdx.x >> 6] = x;
+    __syncthreads();
+    return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
-// Single workgroup: block_sums[i] <- sum of block_sums[0..i) ; block_sums[nblk] <- grand total.
-__global__ __launch_bounds__(256) void k_scan_of_sums(uint64_t *block_sums, uint64_t nblk)
+// chunk_sums[k * (nchunks + 1) + c] = words of worker k's buckets [c*1024, (c+1)*1024)
+__global__ __launch_bounds__(256) void k_chunk_sums(const uint32_t *lens, uint64_t nb, uint64_t nchunks,
+                                                    uint64_t *chunk_sums)
+{
+    __shared__ uint64_t scratch[4];
+    const uint32_t *l = lens + (uint64_t)blockIdx.y * nb;
+    const uint64_t i0 = (uint64_t)blockIdx.x * kChunk;
+    uint64_t s = 0;
+    for (uint32_t k = threadIdx.x; k < kChunk; k += 256u)
+        if (i0 + k < nb)
+            s += (l[i0 + k] + 31u) >> 5;
+    s = block_sum_u64(s, scratch);
+    if (threadIdx.x == 0)
+        chunk_sums[(uint64_t)blockIdx.y * (nchunks + 1) + blockIdx.x] = s;
+}
+
+// One workgroup per worker: chunk_sums[c] <- sum of chunk_sums[0..c) (in place).
+__global__ __launch_bounds__(256) void k_chunk_scan(uint64_t *chunk_sums, uint64_t nchunks)
 {
     __shared__ uint64_t carry;
     __shared__ uint64_t wave_tot[4];
+    uint64_t *cs = chunk_sums + (uint64_t)blockIdx.x * (nchunks + 1);
     if (threadIdx.x == 0)
         carry = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (uint64_t i0 = 0; i0 < nblk; i0 += 256) {
+    for (uint64_t i0 = 0; i0 < nchunks; i0 += 256) {
         const uint64_t i = i0 + threadIdx.x;
-        const uint64_t v = i < nblk ? block_sums[i] : 0ull;
+        const uint64_t v = i < nchunks ? cs[i] : 0ull;
         uint64_t inc = v;
         for (int off = 1; off < 64; off <<= 1) {
-            const uint64_t t = __shfl_up(inc, off, 64);
+            const uint64_t t = __shfl_up((unsigned long long)inc, off, 64);
             if (lane >= off)
                 inc += t;
         }
@@ -364,58 +399,61 @@ __global__ __launch_bounds__(256) void k_scan_of_sums(uint64_t *block_sums, uint
         uint64_t before = carry;
         for (int w = 0; w < wave; ++w)
             before += wave_tot[w];
-        if (i < nblk)
-            block_sums[i] = before + inc - v;
+        if (i < nchunks)
+            cs[i] = before + inc - v;
         __syncthreads();
         if (threadIdx.x == 255)
             carry = before + inc;
         __syncthreads();
     }
-    if (threadIdx.x == 0)
-        block_sums[nblk] = carry;
 }
 
-__global__ __launch_bounds__(256) void k_scan_offsets(const uint32_t *lens, uint64_t nb,
-                                                      const uint64_t *block_sums, uint64_t *bit_off)
+// grid (ceil(nb / 4), K).  chunk_prefix == nullptr: sum the lengths of all earlier buckets directly.
+__global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, const uint64_t *chunk_prefix,
+                                                uint64_t nchunks)
 {
-    __shared__ uint32_t scratch[4];
-    const uint64_t i0 = (uint64_t)blockIdx.x * kScanChunk + threadIdx.x * 4u;
-    uint32_t l[4], wc[4], s = 0;
-    for (uint32_t k = 0; k < 4u; ++k) {
-        l[k] = i0 + k < nb ? lens[i0 + k] : 0u;
-        wc[k] = (l[k] + 31u) >> 5;
-        s += wc[k];
+    __shared__ uint64_t scratch[4];
+    const EncodeWorker &W = Wk.w[blockIdx.y];
+    const uint32_t *lens = P.lens + (uint64_t)blockIdx.y * P.nb;
+    const uint64_t b_first = (uint64_t)blockIdx.x * 4u;
+    uint64_t lo = 0, base = 0;
+    if (chunk_prefix) {
+        const uint64_t c = b_first / kChunk;
+        lo = c * kChunk;
+        base = chunk_prefix[(uint64_t)blockIdx.y * (nchunks + 1) + c];
     }
-    uint32_t total;
-    uint64_t start = block_sums[blockIdx.x] + team_exclusive_sum<256>(s, scratch, total);
-    for (uint32_t k = 0; k < 4u; ++k) {
-        if (i0 + k < nb)
-            bit_off[i0 + k + 1] = 32ull * start + l[k];
-        start += wc[k];
-    }
-    if (blockIdx.x == 0 && threadIdx.x == 0)
-        bit_off[0] = 0;
-}
+    uint64_t part = 0;
+    for (uint64_t i = lo + threadIdx.x; i < b_first; i += 256u)
+        part += (lens[i] + 31u) >> 5;
+    uint64_t start = base + block_sum_u64(part, scratch);   // first word of bucket b_first
 
-// One wave per bucket copies its staging slot to its place in `words`.
-__global__ __launch_bounds__(256) void k_gather(const uint32_t *staging, uint32_t slot_words,
-                                                const uint64_t *bit_off, uint64_t nb, uint32_t *words,
-                                                uint64_t words_cap, uint32_t *flags)
-{
-    const uint64_t b = (uint64_t)blockIdx.x * 4u + (threadIdx.x >> 6);
-    if (b >= nb)
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint64_t b = b_first + wave;
+    uint32_t len = 0;
+    for (uint32_t w = 0; w <= wave; ++w) {                  // (at most four) lengths of this workgroup's buckets
+        const uint32_t l = b_first + w < P.nb ? lens[b_first + w] : 0u;
+        if (w < wave)
+            start += (l + 31u) >> 5;
+        else
+            len = l;
+    }
+    if (b >= P.nb)
         return;
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint64_t start = (bit_off[b] + 31ull) >> 5;
-    const uint64_t end = (bit_off[b + 1] + 31ull) >> 5;
-    if (end > words_cap) {
-        if (lane == 0 && end > start)
-            atomicOr(flags, kFlagCapacity);
+    if (lane == 0) {
+        W.bit_off[b + 1] = 32ull * start + len;
+        if (b == 0)
+            W.bit_off[0] = 0;
+    }
+    const uint64_t nw = (len + 31u) >> 5;
+    if (start + nw > W.words_cap) {
+        if (lane == 0 && nw)
+            atomicOr(P.flags, kFlagCapacity);
         return;
     }
-    const uint32_t *slot = staging + b * slot_words;
-    for (uint64_t i = start + lane; i < end; i += 64u)
-        words[i] = slot[i - start];
+    const uint32_t *slot = P.staging + ((uint64_t)blockIdx.y * P.nb + b) * P.slot_words;
+    uint32_t *dst = W.words + start;
+    for (uint64_t i = lane; i < nw; i += 64u)
+        dst[i] = slot[i];
 }
 
 }  // namespace nuq

@@ -29,7 +29,7 @@ def alloc_message(d, n, s, S, words_cap=None):
 
 
 def workspace(d, n, s):
-    return torch.empty(nuq.nuq_encode_workspace_bytes(d, n, s), dtype=torch.uint8, device=DEV)
+    return torch.empty(nuq.nuq_encode_workspace_bytes(1, d, n, s), dtype=torch.uint8, device=DEV)
 
 
 def fused_encode(v: torch.Tensor, n, s, seed, S, words_cap=None):

@@ -41,8 +41,8 @@ def test_size_helpers(nuq):
     # worst case: every coordinate nonzero at the top level: 1 (gap) + 1 (sign) + |ERC(s+1)| bits each
     assert nuq.nuq_max_words(8192, 8192, 3) == 8192 * 8 // 32 + 1        # |ERC(4)| = 6
     assert nuq.nuq_max_words(64, 64, 7) == (64 * 9 + 31) // 32 + 1       # |ERC(8)| = 7
-    assert nuq.nuq_encode_workspace_bytes(1 << 20, 8192, 3) >= 128 * 8192
-    assert nuq.nuq_encode_workspace_bytes(1 << 20, 0, 3) == 0
+    assert nuq.nuq_encode_workspace_bytes(1, 1 << 20, 8192, 3) >= 128 * 8192
+    assert nuq.nuq_encode_workspace_bytes(1, 1 << 20, 0, 3) == 0
 
 
 def test_argument_errors_are_reported_on_the_host(nuq):

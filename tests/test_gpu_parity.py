@@ -129,6 +129,23 @@ def test_decode_average_of_K_workers(g, d, n, s, S, K):
     assert nuq.nuq_last_error_flags() == 0
 
 
+@pytest.mark.parametrize("d,n,s,S,K", [(70_000, 8192, 3, 512, 8), (20_000, 512, 3, 0, 4), (40_000, 16384, 7, 256, 3)])
+def test_batched_encode_equals_per_worker_encode(g, d, n, s, S, K):
+    nuq = g.nuq
+    rng = np.random.default_rng(5 * K + n)
+    vs = [torch.from_numpy(make_vector("mixed", d, n, rng)).to(g.DEV) for _ in range(K)]
+    seeds = [1000 + 7 * k for k in range(K)]
+    msgs = [g.alloc_message(d, n, s, S) for _ in range(K)]
+    ws = torch.empty(nuq.nuq_encode_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_quantize_encode_batch(vs, n, s, seeds, S, msgs, ws)
+    assert nuq.nuq_last_error_flags() == 0
+    for k in range(K):
+        g.check_message_against_oracle(vs[k].cpu().numpy(), n, s, seeds[k], S, msgs[k])
+        one = g.fused_encode(vs[k], n, s, seeds[k], S)
+        np.testing.assert_array_equal(one.norms.cpu().numpy(), msgs[k].norms.cpu().numpy())
+        np.testing.assert_array_equal(g.u64(one.bit_off), g.u64(msgs[k].bit_off))
+
+
 def test_extreme_magnitudes_and_subnormals(g):
     """Tiny norms (the bucket is rescaled inside the kernel), subnormal coordinates, huge values."""
     nuq = g.nuq

@@ -142,26 +142,30 @@ def test_roundtrip_and_sync_entries(bucket, s, stride):
     np.testing.assert_array_equal(oracle.decode_levels(bit_off, words, d, bucket, s), q)
     ns = oracle.num_sync(bucket, stride)
     assert sync.size == ns * oracle.num_buckets(d, bucket)
-    # every sync entry points at a record boundary: decoding the tail from there,
-    # with the first gap replaced by the recorded position, reproduces the tail of q
+    # every sync entry holds the offset of the first record at or after its boundary: decoding from
+    # there, with the first gap replaced by the recorded position, reproduces that record
     for b in range(oracle.num_buckets(d, bucket)):
         seg = q[b * bucket:(b + 1) * bucket]
         start = (int(bit_off[b]) + 31) // 32 * 32
+        nzall = np.flatnonzero(seg & 0x7F)
         for g in range(1, ns + 1):
             e = int(sync[b * ns + g - 1])
-            part = seg[g * stride:(g + 1) * stride]
-            nz = np.flatnonzero(part & 0x7F)
-            if nz.size == 0:
-                assert e == oracle.SYNC_EMPTY
+            after = nzall[nzall >= g * stride]
+            off = e & 0x1FFFFF
+            if after.size == 0:
+                assert e == (int(bit_off[b + 1]) - start) | oracle.SYNC_EMPTY
                 continue
-            assert (e >> 21) == nz[0]
-            t = start + (e & 0x1FFFFF)
-            bits = oracle.words_to_bits(words, t, int(bit_off[b + 1]))
+            first = int(after[0])
+            if first < (g + 1) * stride:
+                assert (e >> 31) == 0 and ((e >> 21) & 0x3FF) == first - g * stride
+            else:
+                assert (e >> 31) == 1 and ((e >> 21) & 0x3FF) == 0
+            bits = oracle.words_to_bits(words, start + off, int(bit_off[b + 1]))
             gap, p = oracle.erc_decode(bits)
-            prev = np.flatnonzero(seg[:g * stride + nz[0]] & 0x7F)
-            assert gap == g * stride + nz[0] - (prev[-1] if prev.size else -1)
-            assert bits[p] == ("1" if part[nz[0]] & 0x80 else "0")
-            assert oracle.erc_decode(bits, p + 1)[0] == (part[nz[0]] & 0x7F)
+            prev = nzall[nzall < first]
+            assert gap == first - (int(prev[-1]) if prev.size else -1)
+            assert bits[p] == ("1" if seg[first] & 0x80 else "0")
+            assert oracle.erc_decode(bits, p + 1)[0] == (seg[first] & 0x7F)
 
 
 def test_decode_rejects_malformed_streams():
