@@ -67,21 +67,18 @@ def main():
     grads = [workloads.generate(w, k, dev) for k in range(K)]
     ws = torch.empty(nuq.nuq_encode_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=dev)
     seeds = [w.quant_seed(k) for k in range(K)]
-    # size the word buffers from a first encode (worst-case capacity would be 1 B/coord per worker)
-    probe = nuq.Message(torch.empty(B, dtype=torch.float32, device=dev),
-                        torch.empty(B + 1, dtype=torch.int64, device=dev),
-                        torch.zeros(16, dtype=torch.int32, device=dev),
-                        torch.empty(max(1, B * nsync), dtype=torch.int32, device=dev))
-    msgs = []
-    for k in range(K):
-        nuq.nuq_quantize_encode(grads[k], n, s, w.quant_seed(k), S, probe.norms, probe.bit_off, probe.words,
-                                probe.sync, ws)
-        nuq.nuq_last_error_flags()          # capacity flag expected here
-        nwords = (int(probe.bit_off[-1].item()) + 31) // 32
-        msgs.append(nuq.Message(torch.empty(B, dtype=torch.float32, device=dev),
-                                torch.empty(B + 1, dtype=torch.int64, device=dev),
-                                torch.zeros(nwords + 64, dtype=torch.int32, device=dev),
-                                torch.empty(max(1, B * nsync), dtype=torch.int32, device=dev)))
+    # size the word buffers from a first encode into 16-word buffers (the capacity flag is expected; offsets are
+    # complete); worst-case capacity would be ~1 B/coord per worker
+    def new_msg(nwords):
+        return nuq.Message(torch.empty(B, dtype=torch.float32, device=dev),
+                           torch.empty(B + 1, dtype=torch.int64, device=dev),
+                           torch.zeros(nwords, dtype=torch.int32, device=dev),
+                           torch.empty(max(1, B * nsync), dtype=torch.int32, device=dev))
+    probes = [new_msg(16) for _ in range(K)]
+    nuq.nuq_quantize_encode_batch(grads, n, s, seeds, S, probes, ws)
+    nuq.nuq_last_error_flags()
+    msgs = [new_msg((int(p.bit_off[-1].item()) + 31) // 32 + 64) for p in probes]
+    del probes
     out = torch.empty(d, dtype=torch.float32, device=dev)
 
     def encode_all():
