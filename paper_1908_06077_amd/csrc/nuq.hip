@@ -399,7 +399,7 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
     if (grid > 0x7fffffffull)
         return NUQ_EINVAL;
     ScopedTiming timing(NUQ_T_DECODE, static_cast<hipStream_t>(stream));
-    hipLaunchKernelGGL(k_decode_accumulate, dim3((uint32_t)grid), dim3(256), 0, static_cast<hipStream_t>(stream), P);
+    hipLaunchKernelGGL(k_decode_accumulate, dim3((uint32_t)grid), dim3(kDecodeWG), 0, static_cast<hipStream_t>(stream), P);
     return check_launch();
 }
 

@@ -7,6 +7,11 @@
 // more than 2^29).  The bit strings the tile needs are first copied to LDS with coalesced
 // loads.  Each (worker, bucket, segment) bit string is then parsed by one lane, sequentially,
 // as the format requires; the tile is finally scaled, rounded to fp32 and written out once.
+//
+// The parse loop is bound by instruction issue, so it is kept short: a 128-entry table indexed
+// by the next seven stream bits resolves every Elias code of up to seven bits (values 1..15:
+// all level indices and two thirds of the gaps) in one LDS read and gives the position and
+// width of the last group of longer codes; format checks are accumulated and tested once.
 #pragma once
 #include "nuq_device.hpp"
 #include "nuq_encode_kernels.hpp"
@@ -14,9 +19,10 @@
 namespace nuq {
 
 constexpr uint32_t kMaxWorkers = 32;
-constexpr uint32_t kTileCoords = 4096;     // coordinates per workgroup tile (32 KB of fp64)
-constexpr uint32_t kStageWords = 1344;     // LDS words for staged bit strings
-constexpr uint32_t kMaxStreams = 256;      // (bucket, worker) bit strings per tile
+constexpr uint32_t kDecodeWG = 128;        // threads per workgroup
+constexpr uint32_t kTileCoords = 2048;     // coordinates per workgroup tile (16 KB of fp64)
+constexpr uint32_t kStageWords = 704;      // LDS words for staged bit strings
+constexpr uint32_t kMaxStreams = 128;      // (bucket, worker) bit strings per tile
 constexpr uint32_t kNoStage = 0xFFFFFFFFu;
 
 struct DecodeParams {
@@ -154,14 +160,93 @@ struct GlobalWords {
     __device__ __forceinline__ uint32_t operator[](uint32_t i) const { return p[i]; }
 };
 
-__global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
+// ---- seven-bit code table -------------------------------------------------------------
+// Entry for the next seven stream bits p (MSB first):
+//   short code (complete within the seven bits): bits 0..4 = code length, bits 5..9 = value
+//   long code (three groups): bit 15 set, bits 0..4 = bits before the last group (5 or 6),
+//   bits 5..9 = width of the last group (5..16); the value is that group, one 0 follows.
+__device__ __forceinline__ uint32_t code_table_entry(uint32_t p)
+{
+    const uint32_t w = p << 25;
+    uint32_t N, len;
+    erc_decode_bits(w, N, len);
+    if (len <= 7u)
+        return len | (N << 5);
+    const uint32_t k2 = (w >> 30) + 1u;                         // second group's width (3 or 4)
+    const uint32_t g2 = (w >> (30u - k2)) & ((1u << k2) - 1u);  // second group = last group's width - 1
+    return 0x8000u | (2u + k2) | ((g2 + 1u) << 5);
+}
+
+// Decode one Elias code from the window w with the table; returns the value, `len` its length.
+__device__ __forceinline__ uint32_t table_decode(const uint16_t *lut, uint32_t w, uint32_t &len)
+{
+    const uint32_t e = lut[w >> 25];
+    const uint32_t a = e & 31u;              // length, or bits before the last group
+    const uint32_t v = (e >> 5) & 31u;       // value, or width of the last group
+    const uint32_t big = ((w << a) >> 1) >> (31u - v);   // last group of a long code (v >= 5)
+    const bool is_long = (e & 0x8000u) != 0u;
+    len = is_long ? a + v + 1u : a;
+    return is_long ? big : v;
+}
+
+// Fast parse of one unit from words held in `words` (LDS or global through the accessor).
+// Reads are clamped to word index `last_word`; format violations set *bad and never leave
+// [idx_lo, idx_hi) of the tile.
+template <class WordPtr>
+__device__ __forceinline__ void decode_unit_fast(WordPtr words, uint32_t last_word, const uint16_t *lut,
+                                                 uint32_t bit_lo, uint32_t bit_hi, int forced, uint32_t idx_hi,
+                                                 uint32_t smax, double wnorm, double *tile_at0, bool &bad)
+{
+    uint32_t next = bit_lo >> 5;
+    const uint32_t bo = bit_lo & 31u;
+    uint64_t buf = ((uint64_t)words[min(next, last_word)] << 32) | words[min(next + 1u, last_word)];
+    next += 2u;
+    buf <<= bo;
+    uint32_t cnt = 64u - bo;
+    int remaining = (int)(bit_hi - bit_lo);
+    int prev = -1;
+    if (forced >= 0 && remaining > 0) {       // entered through a sync entry: the first gap is replaced
+        uint32_t lg;
+        const uint32_t gap = table_decode(lut, (uint32_t)(buf >> 32), lg);
+        prev = forced - (int)gap;
+    }
+    while (remaining > 0) {
+        if (cnt <= 32u) {
+            const uint32_t wd = words[min(next, last_word)];
+            ++next;
+            buf |= (uint64_t)wd << (32u - cnt);
+            cnt += 32u;
+        }
+        const uint32_t w = (uint32_t)(buf >> 32);
+        uint32_t lg, lj;
+        const uint32_t gap = table_decode(lut, w, lg);
+        const uint32_t w2 = w << lg;                      // sign bit on top
+        const uint32_t j = table_decode(lut, w2 << 1, lj);
+        const uint32_t len = lg + 1u + lj;
+        uint32_t idx = (uint32_t)(prev + (int)gap);
+        bad |= (idx >= idx_hi) | (j - 1u >= smax) | (len > 31u);
+        idx = min(idx, idx_hi - 1u);
+        // ||v|| * l_j = (||v|| * 2^(-1-s)) * 2^j, exact in fp64; the sign goes into the top bit
+        const double mag = ldexp(wnorm, (int)min(j, 15u));
+        const uint64_t vb = (uint64_t)__double_as_longlong(mag) ^ ((uint64_t)(w2 & 0x80000000u) << 32);
+        atomicAdd(tile_at0 + idx, __longlong_as_double((long long)vb));
+        buf <<= len;
+        cnt -= len;
+        remaining -= (int)len;
+        prev = (int)idx;
+    }
+    bad |= remaining != 0;
+}
+
+__global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
 {
     __shared__ __align__(16) double tile[kTileCoords];
     __shared__ uint32_t stage[kStageWords];
-    __shared__ uint32_t st_lds[kMaxStreams];     // LDS word offset of a staged bit string, or kNoStage
-    __shared__ uint32_t st_bit0[kMaxStreams];    // first staged bit (multiple of 32), from the bucket's first bit
-    __shared__ uint32_t st_bit1[kMaxStreams];    // one past the last staged bit
-    __shared__ uint32_t scan_scratch[4];
+    __shared__ uint32_t st_off[kMaxStreams + 1];  // exclusive prefix of staged words per stream
+    __shared__ uint32_t st_bit0[kMaxStreams];     // first staged bit (multiple of 32), from the bucket's first bit
+    __shared__ uint64_t st_src[kMaxStreams];      // global address of the first staged word
+    __shared__ uint16_t lut[128];
+    __shared__ uint32_t scan_scratch[2];
 
     // ---- which coordinates does this tile cover?
     uint64_t b0;        // first bucket of the tile
@@ -184,21 +269,23 @@ __global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
     const uint32_t span = (uint32_t)(c_hi - c_lo);
     const uint32_t g0 = P.sync_shift ? (in_lo >> P.sync_shift) : 0u;                // first segment of the tile
     const bool partial = !P.buckets_per_tile;                                        // part of one bucket
+    const bool walk = partial && !P.sync_shift;                                      // no index: walk from the start
     const uint32_t g1 = partial && P.sync_shift ? min(P.nseg, g0 + P.segs_per_tile) : P.nseg;   // one past the last
+    const uint32_t tid = threadIdx.x;
 
-    for (uint32_t i = threadIdx.x; i < (span + 1u) / 2u; i += 256u)
+    for (uint32_t i = tid; i < (span + 1u) / 2u; i += kDecodeWG)
         reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
+    lut[tid] = (uint16_t)code_table_entry(tid);
 
-    // ---- stage the bit strings: stream = (bucket in tile, worker)
+    // ---- which words does each stream = (bucket in tile, worker) need?
     const uint32_t nstreams = nbuck * P.K;
-    uint32_t my_words = 0, my_w0 = 0;
-    const uint32_t *my_src = nullptr;
-    if (threadIdx.x < nstreams) {
-        const uint32_t k = threadIdx.x % P.K;
-        const uint64_t b = b0 + threadIdx.x / P.K;
+    uint32_t my_words = 0;
+    if (tid < nstreams) {
+        const uint32_t k = tid % P.K;
+        const uint64_t b = b0 + tid / P.K;
         const uint64_t start = (P.bit_off[k][b] + 31ull) & ~31ull;
         const uint64_t end = P.bit_off[k][b + 1];
-        uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
+        const uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
         uint32_t lo = 0, hi = len;
         if (partial && P.sync_shift) {
             const uint32_t *sy = P.sync[k] + b * P.nsync;
@@ -207,35 +294,31 @@ __global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
             if (g1 < P.nseg)
                 hi = min(sy[g1 - 1u] & 0x1FFFFFu, len);
         }
-        my_w0 = lo >> 5;
-        my_words = hi > lo ? ((hi + 31u) >> 5) - my_w0 : 0u;
-        if (partial && !P.sync_shift)
-            my_words = 0u;               // walked from global memory (see below)
-        my_src = P.words[k] + (start >> 5) + my_w0;
+        const uint32_t w0 = lo >> 5;
+        my_words = (hi > lo && !walk) ? ((hi + 31u) >> 5) - w0 : 0u;
+        st_bit0[tid] = w0 << 5;
+        st_src[tid] = reinterpret_cast<uint64_t>(P.words[k] + (start >> 5) + w0);
     }
     uint32_t total_words;
-    const uint32_t my_off = team_exclusive_sum<256>(my_words, scan_scratch, total_words);
-    if (threadIdx.x < nstreams) {
-        st_lds[threadIdx.x] = (my_off + my_words <= kStageWords) ? my_off : kNoStage;
-        st_bit0[threadIdx.x] = my_w0 << 5;
-        st_bit1[threadIdx.x] = (my_w0 + my_words) << 5;
-    }
-    // each wave copies streams wave, wave+4, ...; descriptors travel by shuffle inside the wave
-    {
-        const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-        for (uint32_t l = 0; l < 64u; ++l) {                       // nstreams <= 256 = 4 waves x 64
-            const uint32_t sidx = wave * 64u + l;
-            if (sidx >= nstreams)
-                break;
-            const uint32_t nw = __shfl(my_words, (int)l, 64);
-            const uint32_t off = __shfl(my_off, (int)l, 64);
-            const uint64_t src = __shfl((unsigned long long)reinterpret_cast<uintptr_t>(my_src), (int)l, 64);
-            if (off + nw > kStageWords)
-                continue;
-            const uint32_t *sp = reinterpret_cast<const uint32_t *>(src);
-            for (uint32_t i = lane; i < nw; i += 64u)
-                stage[off + i] = sp[i];
+    const uint32_t my_off = team_exclusive_sum<kDecodeWG>(my_words, scan_scratch, total_words);
+    if (tid < nstreams)
+        st_off[tid] = my_off;
+    if (tid == 0)
+        st_off[nstreams] = total_words;
+    __syncthreads();
+
+    // ---- copy them to LDS: word i of the concatenation belongs to the stream found by bisection
+    const uint32_t staged_words = min(total_words, kStageWords);
+    for (uint32_t i = tid; i < staged_words; i += kDecodeWG) {
+        uint32_t lo = 0, hi = nstreams;          // st_off[lo] <= i < st_off[hi]
+        while (hi - lo > 1u) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (st_off[mid] <= i)
+                lo = mid;
+            else
+                hi = mid;
         }
+        stage[i] = reinterpret_cast<const uint32_t *>(st_src[lo])[i - st_off[lo]];
     }
     __syncthreads();
 
@@ -243,7 +326,8 @@ __global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
     const uint32_t segs = g1 - g0;
     const uint32_t units = nbuck * segs * P.K;
     const double wscale = ldexp(1.0, -1 - (int)P.s);
-    for (uint32_t u = threadIdx.x; u < units; u += 256u) {
+    bool bad = false;
+    for (uint32_t u = tid; u < units; u += kDecodeWG) {
         const uint32_t k = u % P.K;
         const uint32_t r = u / P.K;
         const uint32_t g = g0 + r % segs;
@@ -271,24 +355,23 @@ __global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
             }
             if (g + 1u < P.nseg)
                 bit_hi = sy[g] & 0x1FFFFFu;
-            if (bit_lo > bit_hi || bit_hi > len) {
-                atomicOr(P.flags, kFlagMalformed);
+            if (bit_lo > bit_hi || bit_hi > len || (forced >= 0 && (uint32_t)forced >= idx_hi)) {
+                bad = true;
                 continue;
             }
-        } else if (partial) {            // part of a large bucket without an index: walk from its start
+        } else if (walk) {
             idx_lo = in_lo;
-            idx_hi = nbk;                // later tiles' records are met too; stop at the tile's end below
             if (idx_lo >= nbk)
                 continue;
         }
+        if (bit_hi <= bit_lo)
+            continue;
         const double wnorm = (double)P.norms[k][b] * wscale;
         const int tile_lo = partial ? (int)in_lo : -(int)(bi * P.bucket);
-        const uint32_t loff = st_lds[sidx];
-        if (partial && !P.sync_shift) {
-            // slow path: global words, records beyond the tile are skipped by bounding idx_hi
+        if (walk) {
+            // no index: parse the bucket from its first record in global memory, keep what lands in the tile
             GlobalWords gw{P.words[k] + (start >> 5)};
             const uint32_t hi_idx = min(nbk, in_lo + P.tile_coords);
-            // parse the whole bucket; only [idx_lo, hi_idx) lands in the tile
             BitReader<GlobalWords> br;
             br.init(gw, 0, (len + 31u) >> 5);
             uint32_t pos = 0;
@@ -304,7 +387,7 @@ __global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
                 const uint32_t rl = lg + 1u + lj;
                 const int idx = prev + (int)gap;
                 if (!ok || rl > 31u || pos + rl > len || (uint32_t)idx >= nbk || j < 1u || j > P.s + 1u) {
-                    atomicOr(P.flags, kFlagMalformed);
+                    bad = true;
                     break;
                 }
                 if ((uint32_t)idx >= hi_idx)
@@ -317,20 +400,26 @@ __global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
                 pos += rl;
                 prev = idx;
             }
-        } else if (loff != kNoStage) {
-            const uint32_t bit0 = st_bit0[sidx];
-            if (bit_lo < bit0 || bit_hi > st_bit1[sidx]) {   // a sync index that is not monotone
-                atomicOr(P.flags, kFlagMalformed);
-                continue;
-            }
-            const uint32_t *lw = stage + loff;
-            decode_unit(P, lw, ((bit_hi + 31u) >> 5) - (bit0 >> 5), bit_lo - bit0, bit_hi - bit0, forced, idx_lo, idx_hi,
-                        wnorm, tile, tile_lo);
-        } else {
-            GlobalWords gw{P.words[k] + (start >> 5)};
-            decode_unit(P, gw, (bit_hi + 31u) >> 5, bit_lo, bit_hi, forced, idx_lo, idx_hi, wnorm, tile, tile_lo);
+            continue;
+        }
+        const uint32_t so = st_off[sidx], se = st_off[sidx + 1u];
+        const uint32_t bit0 = st_bit0[sidx];
+        if (bit_lo < bit0 || bit_hi > bit0 + ((se - so) << 5)) {   // a sync index that is not monotone
+            bad = true;
+            continue;
+        }
+        double *tile_at0 = tile - tile_lo;       // address of in-bucket index 0 (never dereferenced outside the tile)
+        if (se <= kStageWords) {
+            decode_unit_fast(stage + so, se - so - 1u, lut, bit_lo - bit0, bit_hi - bit0, forced, idx_hi, P.s + 1u,
+                             wnorm, tile_at0, bad);
+        } else {                                  // did not fit in LDS: read the words from global memory
+            GlobalWords gw{reinterpret_cast<const uint32_t *>(st_src[sidx])};
+            decode_unit_fast(gw, se - so - 1u, lut, bit_lo - bit0, bit_hi - bit0, forced, idx_hi, P.s + 1u, wnorm,
+                             tile_at0, bad);
         }
     }
+    if (bad)
+        atomicOr(P.flags, kFlagMalformed);
     __syncthreads();
 
     // ---- scale, round to fp32, write
@@ -339,7 +428,7 @@ __global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
     const bool vec = (reinterpret_cast<uintptr_t>(o) & 15u) == 0;
     if (vec) {
         const uint32_t n4 = span >> 2;
-        for (uint32_t i = threadIdx.x; i < n4; i += 256u) {
+        for (uint32_t i = tid; i < n4; i += kDecodeWG) {
             const double2 a = reinterpret_cast<const double2 *>(tile)[2u * i];
             const double2 c = reinterpret_cast<const double2 *>(tile)[2u * i + 1u];
             float4 r;
@@ -357,12 +446,12 @@ __global__ __launch_bounds__(256) void k_decode_accumulate(DecodeParams P)
             }
             *dst = r;
         }
-        for (uint32_t i = (n4 << 2) + threadIdx.x; i < span; i += 256u) {
+        for (uint32_t i = (n4 << 2) + tid; i < span; i += kDecodeWG) {
             const float r = (float)(sc * tile[i]);
             o[i] = P.accumulate ? o[i] + r : r;
         }
     } else {
-        for (uint32_t i = threadIdx.x; i < span; i += 256u) {
+        for (uint32_t i = tid; i < span; i += kDecodeWG) {
             const float r = (float)(sc * tile[i]);
             o[i] = P.accumulate ? o[i] + r : r;
         }
