@@ -188,7 +188,7 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
         using G = TeamGeom<TEAM>;
         P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
         P.lds_words = team_lds_words(P.rows, TEAM, slot_words, nsync);
-        const size_t lds_bytes = (size_t)P.lds_words * 4 * G::kTeamsPerWG;
+        const size_t lds_bytes = (size_t)P.lds_words * 4 * G::kTeamsPerWG + 256 * 4;   // + the code table
         if (lds_bytes > 160 * 1024)
             return (int)NUQ_EINVAL;
         auto kern = k_encode<TEAM, VPT, MODE>;

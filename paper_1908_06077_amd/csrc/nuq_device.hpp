@@ -53,15 +53,19 @@ __device__ __forceinline__ uint32_t draw24(uint32_t x, uint32_t k1)
 //   up to j+1  iff  u * (l_{j+1} - l_j) * N  <  (a - l_j * N) * 2^24   (real numbers).
 // Integer view: with nS = N * 2^-s (a float, exponent field lowered by s), the bin of a
 // is m = floor((bits(a) - bits(nS)) / 2^23): m < 0 is the bin below the first level,
-// m >= s means a >= N.  lo = nS * 2^m and a - lo are exact floats; the product u * w with
-// w = lo * 2^-24 (or nS * 2^-24 in the lowest bin) is compared exactly through its
-// rounded value p and the fma residual e = u*w - p.
-// Exactness needs w and e to be normal floats; norms below 2^-60 are handled by scaling
-// the whole bucket by 2^100 first (a power of two: ratios are unchanged).
+// m >= s means a >= N.  lo = nS * 2^m and x = a - lo are exact floats, w = lo * 2^-24 (or
+// nS * 2^-24 in the lowest bin) is an exact float, and one fused multiply-add
+// t = fma(u, w, -x) rounds the exact value u*w - x once: rounding never changes the sign
+// of a nonzero value (fp32 denormals are kept: the kernels run in IEEE denormal mode), so
+// "up" is exactly "t < 0".  w must be a normal float for the scaling to be exact; norms
+// below 2^-60 are handled by scaling the whole bucket by 2^100 first (a power of two:
+// ratios are unchanged).
 
 struct BucketScale {
     uint32_t ns_bits;  // bits of (prescaled) N * 2^-s
     uint32_t c_bits;   // bits of (prescaled) N * 2^(-s-24)
+    float ns;          // the same as floats
+    float c;
     float prescale;    // 1 or 2^100
     int s;
     bool dead;         // zero or non-finite norm: every level is 0
@@ -79,29 +83,22 @@ __device__ __forceinline__ BucketScale make_scale(float norm, int s)
     }
     B.ns_bits = f2u(norm) - ((uint32_t)s << 23);
     B.c_bits = B.ns_bits - (24u << 23);
+    B.ns = u2f(B.ns_bits);
+    B.c = u2f(B.c_bits);
     return B;
 }
 
-// Level index of one coordinate for the 24-bit draw u.  `v` is the raw coordinate.
-__device__ __forceinline__ int quantize_level(float v, uint32_t u, const BucketScale &B)
+// Level index of one coordinate for the 24-bit draw u; a = |v| (already prescaled).
+__device__ __forceinline__ int quantize_level(float a, uint32_t u, const BucketScale &B)
 {
-    float a = fabsf(v);
-    if (B.prescale != 1.0f)
-        a *= B.prescale;
-    const uint32_t ab = f2u(a);
-    const int m = (int)(ab - B.ns_bits) >> 23;
+    const int m = (int)(f2u(a) - B.ns_bits) >> 23;
     if (m >= B.s)
         return B.s + 1;
     const uint32_t sh = m < 0 ? 0u : (uint32_t)m << 23;
     const float w = u2f(B.c_bits + sh);
     const float x = m < 0 ? a : a - u2f(B.ns_bits + sh);
-    const int jlo = m < 0 ? 0 : m + 1;
-    const float uf = (float)u;
-    const float p = uf * w;
-    const float e = __builtin_fmaf(uf, w, -p);
-    const uint32_t pb = f2u(p), xb = f2u(x);
-    const bool up = (pb < xb) || (pb == xb && e < 0.0f);
-    return jlo + (up ? 1 : 0);
+    const float t = __builtin_fmaf((float)u, w, -x);
+    return (m < 0 ? 0 : m + 1) + (t < 0.0f ? 1 : 0);
 }
 
 // ------------------------------------------------------------------------- ERC
@@ -183,21 +180,28 @@ __device__ __forceinline__ double team_sum_f64(double x, double *scratch /* TEAM
     return x;
 }
 
+// Inclusive prefix sum across the 64 lanes of a wave with DPP moves: four row-shift steps scan
+// each row of 16 lanes, two row-broadcast steps carry the row totals forward.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15 -> rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
 // Exclusive prefix sum over the team in thread order; `total` receives the team sum.
 template <int TEAM>
 __device__ __forceinline__ uint32_t team_exclusive_sum(uint32_t v, uint32_t *scratch /* TEAM/64 */,
                                                        uint32_t &total)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    uint32_t inc = v;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t t = __shfl_up(inc, off, kWave);
-        if (lane >= off)
-            inc += t;
-    }
+    const uint32_t inc = wave_inclusive_sum(v);
     if constexpr (TEAM == kWave) {
-        total = __shfl(inc, kWave - 1, kWave);
+        total = (uint32_t)__builtin_amdgcn_readlane((int)inc, kWave - 1);
         return inc - v;
     } else {
         constexpr int NW = TEAM / kWave;

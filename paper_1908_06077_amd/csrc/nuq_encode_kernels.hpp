@@ -119,15 +119,42 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_bucket_norms(EncodePara
 
 // Quantize the four coordinates of one vector; returns the four level|sign<<7 bytes.
 // x0 = (k0 + index of first coordinate) * C1.
+//
+// Fast path, taken when every lane's four coordinates lie below the first level (the usual case:
+// |v_i| < 2^-s ||v||): the level is 0 or 1, "up" is the sign bit of t = fma(u, c, -|v|), and the
+// bytes are assembled from the top bytes of v (sign) and t (up) with byte permutes.
 __device__ __forceinline__ uint32_t quantize_vec4(const float4 &x, uint32_t x0, uint32_t k1,
                                                   const BucketScale &B)
 {
-    const float xs[4] = {x.x, x.y, x.z, x.w};
+    float xs[4] = {x.x, x.y, x.z, x.w};
+    if (B.prescale != 1.0f) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            xs[c] *= B.prescale;
+    }
+    const float big = fmaxf(fmaxf(fabsf(xs[0]), fabsf(xs[1])), fmaxf(fabsf(xs[2]), fabsf(xs[3])));
+    uint32_t u[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        u[c] = draw24(x0 + (uint32_t)c * kRngC1, k1);
+    if (__all(big < B.ns)) {
+        uint32_t tb[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            tb[c] = f2u(__builtin_fmaf((float)u[c], B.c, -fabsf(xs[c])));
+        // top bytes of t0..t3 and of v0..v3, one per result byte
+        const uint32_t t01 = __builtin_amdgcn_perm(tb[1], tb[0], 0x0c0c0703u);
+        const uint32_t t23 = __builtin_amdgcn_perm(tb[3], tb[2], 0x0c0c0703u);
+        const uint32_t v01 = __builtin_amdgcn_perm(f2u(xs[1]), f2u(xs[0]), 0x0c0c0703u);
+        const uint32_t v23 = __builtin_amdgcn_perm(f2u(xs[3]), f2u(xs[2]), 0x0c0c0703u);
+        const uint32_t up7 = __builtin_amdgcn_perm(t23, t01, 0x05040100u) & 0x80808080u;   // bit 7 of byte c = up_c
+        const uint32_t sg = __builtin_amdgcn_perm(v23, v01, 0x05040100u);
+        return (sg & up7) | (up7 >> 7);
+    }
     uint32_t packed = 0;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        const uint32_t u = draw24(x0 + (uint32_t)c * kRngC1, k1);
-        const int j = quantize_level(xs[c], u, B);
+        const int j = quantize_level(fabsf(xs[c]), u[c], B);
         const uint32_t sign = (j > 0) ? ((f2u(xs[c]) >> 24) & 0x80u) : 0u;
         packed |= ((uint32_t)j | sign) << (8 * c);
     }
@@ -174,38 +201,66 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P
 // length are zero) and a barrier has been passed.  Produces the bucket's bit string in
 // LDS `out`, copies it to the bucket's staging slot, writes its bit length and its sync
 // entries.  Every thread of the workgroup must call it (it contains barriers).
+//
+// Steps: (1) every thread finds the nonzeros of its contiguous chunk and the team compacts
+// their indices into `rec` (a prefix sum gives the ranks); (2) the records are dealt out evenly,
+// a thread takes a contiguous run of them, looks up gap and level codes in a 256-entry table
+// and sums their lengths; a second prefix sum gives every run its bit offset; (3) the same
+// runs are walked again to OR the record bits into `out`.
+
+// erc_lut[N] for N < 256: code (right-aligned) | length << 16.
+__device__ __forceinline__ uint32_t erc_lookup(const uint32_t *erc_lut, uint32_t N, uint32_t &len)
+{
+    if (N < 256u) {
+        const uint32_t e = erc_lut[N];
+        len = e >> 16;
+        return e & 0xffffu;
+    }
+    return erc_code(N, len);
+}
+
 template <int TEAM>
 __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const EncodeWorker &W, bool active, uint64_t b,
-                                                const uint32_t *qb32, uint32_t *out,
-                                                uint32_t *sync_l, uint32_t *scratch)
+                                                const uint32_t *qb32, uint32_t *out, uint16_t *rec,
+                                                const uint32_t *erc_lut, uint32_t *sync_l, uint32_t *scratch)
 {
     const uint32_t tid = threadIdx.x % TEAM;
     const uint32_t rows = P.rows;
     const uint32_t base = tid * rows * 4u;
+    const uint8_t *qbytes = reinterpret_cast<const uint8_t *>(qb32);
 
+    // (1) nonzero mask of this thread's chunk, ranks, compaction
     uint64_t nz = 0;
     for (uint32_t w = 0; w < rows; ++w) {
         const uint32_t word = qb32[tid * rows + w];
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if ((word >> (8 * k)) & 0x7fu)
-                nz |= 1ull << (4u * w + (uint32_t)k);
+        // bit 7 of every byte whose low seven bits (the level) are not all zero
+        const uint32_t t = ((word & 0x7f7f7f7fu) + 0x7f7f7f7fu) & 0x80808080u;
+        const uint32_t nib = (((t >> 7) * 0x00204081u) >> 21) & 0xfu;   // bits 0,8,16,24 -> 0..3
+        nz |= (uint64_t)nib << (4u * w);
     }
-    const int last = nz ? (int)base + 63 - __clzll((long long)nz) : -1;
-    const int prev0 = team_exclusive_max<TEAM>(last, -1, reinterpret_cast<int *>(scratch));
-
-    const uint8_t *qbytes = reinterpret_cast<const uint8_t *>(qb32);
-    uint32_t bits = 0;
+    uint32_t nnz;
+    uint32_t rank = team_exclusive_sum<TEAM>((uint32_t)__popcll((unsigned long long)nz), scratch, nnz);
     {
         uint64_t m = nz;
-        int p = prev0;
         while (m) {
             const int k = __ffsll((unsigned long long)m) - 1;
             m &= m - 1;
-            const int e = (int)base + k;
+            rec[rank++] = (uint16_t)(base + (uint32_t)k);
+        }
+    }
+    __syncthreads();
+
+    // (2) lengths of this thread's run of records
+    const uint32_t per = (nnz + TEAM - 1u) / TEAM;
+    const uint32_t r0 = min(tid * per, nnz), r1 = min(r0 + per, nnz);
+    uint32_t bits = 0;
+    {
+        int p = r0 ? (int)rec[r0 - 1u] : -1;
+        for (uint32_t r = r0; r < r1; ++r) {
+            const int e = (int)rec[r];
             uint32_t lg, lj;
-            erc_code((uint32_t)(e - p), lg);
-            erc_code((uint32_t)(qbytes[e] & 0x7fu), lj);
+            erc_lookup(erc_lut, (uint32_t)(e - p), lg);
+            erc_lookup(erc_lut, qbytes[e] & 0x7fu, lj);
             bits += lg + 1u + lj;
             p = e;
         }
@@ -218,22 +273,21 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     for (uint32_t i = tid; i < P.nsync; i += TEAM)
         sync_l[i] = total | kSyncEmpty;   // "no record at or after this boundary" until one is found
     __syncthreads();
+
+    // (3) emit
     {
-        uint64_t m = nz;
-        int p = prev0;
+        int p = r0 ? (int)rec[r0 - 1u] : -1;
         uint32_t t = off0;
-        while (m) {
-            const int k = __ffsll((unsigned long long)m) - 1;
-            m &= m - 1;
-            const int e = (int)base + k;
+        for (uint32_t r = r0; r < r1; ++r) {
+            const int e = (int)rec[r];
             const uint32_t code = qbytes[e];
             uint32_t lg, lj;
-            const uint32_t cg = erc_code((uint32_t)(e - p), lg);
-            const uint32_t cj = erc_code(code & 0x7fu, lj);
+            const uint32_t cg = erc_lookup(erc_lut, (uint32_t)(e - p), lg);
+            const uint32_t cj = erc_lookup(erc_lut, code & 0x7fu, lj);
             const uint32_t len = lg + 1u + lj;
-            const uint32_t rec = (cg << (1u + lj)) | ((code >> 7) << lj) | cj;
+            const uint32_t bitsrec = (cg << (1u + lj)) | ((code >> 7) << lj) | cj;
             const uint32_t wi = t >> 5, bo = t & 31u;
-            const uint64_t sh = (uint64_t)rec << (64u - bo - len);
+            const uint64_t sh = (uint64_t)bitsrec << (64u - bo - len);
             atomicOr(&out[wi], (uint32_t)(sh >> 32));
             if ((uint32_t)sh)
                 atomicOr(&out[wi + 1u], (uint32_t)sh);
@@ -261,12 +315,13 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     }
 }
 
-// LDS carve-up per team (in 32-bit words): [qb32: rows*TEAM][out: slot_words + 1]
-// [sync: nsync][scratch: 64 (16 ints, 16 uints, 16 doubles)]
+// LDS carve-up per team (in 32-bit words): [qb32: rows*TEAM][rec: rows*TEAM*2 (u16 per coordinate)]
+// [out: slot_words + 1][sync: nsync][scratch: 64 (16 unused, 16 uints, 16 doubles)]; the
+// workgroup's 256-entry code table follows the last team.
 __host__ __device__ inline uint32_t team_lds_words(uint32_t rows, uint32_t team, uint32_t slot_words,
                                                    uint32_t nsync)
 {
-    uint32_t w = rows * team + slot_words + 1u + nsync;
+    uint32_t w = rows * team * 3u + slot_words + 1u + nsync;
     w = (w + 1u) & ~1u;   // keep the scratch 8-byte aligned
     return w + 64u;
 }
@@ -281,9 +336,16 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
     const uint32_t team = threadIdx.x / TEAM;
     uint32_t *lds = smem + team * P.lds_words;
     uint32_t *qb32 = lds;
-    uint32_t *out = qb32 + P.rows * TEAM;
+    uint16_t *rec = reinterpret_cast<uint16_t *>(qb32 + P.rows * TEAM);
+    uint32_t *out = qb32 + P.rows * TEAM * 3u;
     uint32_t *sync_l = out + P.slot_words + 1u;
     uint32_t *scratch = lds + P.lds_words - 64u;
+    uint32_t *erc_lut = smem + TeamGeom<TEAM>::kTeamsPerWG * P.lds_words;
+    if (threadIdx.x < 256u) {
+        uint32_t len;
+        const uint32_t code = erc_code(threadIdx.x ? threadIdx.x : 1u, len);
+        erc_lut[threadIdx.x] = code | (len << 16);
+    }
 
     const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + team;
     const bool active = b < P.nb;
@@ -332,7 +394,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
         }
     }
     __syncthreads();
-    encode_from_lds<TEAM>(P, W, active, b, qb32, out, sync_l, scratch);
+    encode_from_lds<TEAM>(P, W, active, b, qb32, out, rec, erc_lut, sync_l, scratch);
 }
 
 // ------------------------------------------------- offsets and gather of the slots
