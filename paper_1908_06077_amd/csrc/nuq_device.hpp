@@ -8,6 +8,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace nuq {
 
 constexpr int kWave = 64;
@@ -158,12 +160,47 @@ __device__ __forceinline__ bool erc_decode_window(uint32_t &win, int &avail, uin
 // i.e. 4 one-wave teams or a single multi-wave team.  Multi-wave variants use a small LDS
 // scratch and __syncthreads(); every thread of the workgroup must call them.
 
+// Value of a wave-uniform quantity as a scalar (lets the compiler keep what derives from it in
+// scalar registers and branch on it without touching the exec mask).
+__device__ __forceinline__ uint32_t uniform_u32(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)x);
+}
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t x)
+{
+    return ((uint64_t)uniform_u32((uint32_t)(x >> 32)) << 32) | uniform_u32((uint32_t)x);
+}
+__device__ __forceinline__ float uniform_f32(float x) { return u2f(uniform_u32(f2u(x))); }
+
+// Sum of x over the 64 lanes of a wave, returned in every lane: DPP row shifts and row
+// broadcasts leave the total in lane 63, which is then read as a scalar.
+__device__ __forceinline__ double wave_sum_f64(double x)
+{
+    auto step = [](double v, auto ctrl, auto row_mask, auto bound) {
+        const uint64_t b = (uint64_t)__double_as_longlong(v);
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, decltype(ctrl)::value,
+                                                                  decltype(row_mask)::value, 0xf, decltype(bound)::value);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), decltype(ctrl)::value,
+                                                                  decltype(row_mask)::value, 0xf, decltype(bound)::value);
+        return v + __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+    };
+    using std::integral_constant;
+    x = step(x, integral_constant<int, 0x111>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{});
+    x = step(x, integral_constant<int, 0x112>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{});
+    x = step(x, integral_constant<int, 0x114>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{});
+    x = step(x, integral_constant<int, 0x118>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{});
+    x = step(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{}, integral_constant<bool, false>{});
+    x = step(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{}, integral_constant<bool, false>{});
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, kWave - 1);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), kWave - 1);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
 template <int TEAM>
 __device__ __forceinline__ double team_sum_f64(double x, double *scratch /* TEAM/64 doubles */)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1)
-        x += __shfl_xor(x, off, kWave);
+    x = wave_sum_f64(x);
     if constexpr (TEAM > kWave) {
         constexpr int NW = TEAM / kWave;
         const int wave = (threadIdx.x % TEAM) / kWave;

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_bucket_norms(EncodePara
 }
 
 // Quantize the four coordinates of one vector; returns the four level|sign<<7 bytes.
-// x0 = (k0 + index of first coordinate) * C1.
+// x0 = (k0 + index of first coordinate) * C1.  The caller has applied B.prescale to x.
 //
 // Fast path, taken when every lane's four coordinates lie below the first level (the usual case:
 // |v_i| < 2^-s ||v||): the level is 0 or 1, "up" is the sign bit of t = fma(u, c, -|v|), and the
@@ -126,12 +126,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_bucket_norms(EncodePara
 __device__ __forceinline__ uint32_t quantize_vec4(const float4 &x, uint32_t x0, uint32_t k1,
                                                   const BucketScale &B)
 {
-    float xs[4] = {x.x, x.y, x.z, x.w};
-    if (B.prescale != 1.0f) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-            xs[c] *= B.prescale;
-    }
+    const float xs[4] = {x.x, x.y, x.z, x.w};   // already multiplied by B.prescale
     const float big = fmaxf(fmaxf(fabsf(xs[0]), fabsf(xs[1])), fmaxf(fabsf(xs[2]), fabsf(xs[3])));
     uint32_t u[4];
 #pragma unroll
@@ -167,7 +162,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P
 {
     const EncodeWorker &W = Wk.w[blockIdx.y];
     const uint32_t tid = threadIdx.x % TEAM;
-    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + threadIdx.x / TEAM;
+    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + uniform_u32(threadIdx.x / TEAM);
     if (b >= P.nb)
         return;
     const uint64_t base = b * P.bucket;
@@ -176,7 +171,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P
     uint8_t *qb = W.q_out + base;
     const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
     const bool qaligned = (reinterpret_cast<uintptr_t>(qb) & 3u) == 0;
-    const BucketScale B = make_scale(W.norms_in[b], (int)P.s);
+    const BucketScale B = make_scale(uniform_f32(W.norms_in[b]), (int)P.s);
     const BucketKey key = bucket_key(W.seed, b);
 #pragma unroll 1
     for (uint32_t i = 0; i < P.rows; ++i) {
@@ -184,7 +179,13 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P
         const uint32_t e0 = 4u * vi;
         if (e0 >= nbk)
             break;
-        const float4 x = load_vec4(vb, vi, nbk, aligned);
+        float4 x = load_vec4(vb, vi, nbk, aligned);
+        if (B.prescale != 1.0f) {
+            x.x *= B.prescale;
+            x.y *= B.prescale;
+            x.z *= B.prescale;
+            x.w *= B.prescale;
+        }
         const uint32_t packed = B.dead ? 0u : quantize_vec4(x, (key.k0 + e0) * kRngC1, key.k1, B);
         if (qaligned && e0 + 3u < nbk) {
             reinterpret_cast<uint32_t *>(qb)[vi] = packed;
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
     extern __shared__ __align__(16) uint32_t smem[];
     const EncodeWorker &W = Wk.w[blockIdx.y];
     const uint32_t tid = threadIdx.x % TEAM;
-    const uint32_t team = threadIdx.x / TEAM;
+    const uint32_t team = uniform_u32(threadIdx.x / TEAM);   // a wave never straddles teams
     uint32_t *lds = smem + team * P.lds_words;
     uint32_t *qb32 = lds;
     uint16_t *rec = reinterpret_cast<uint16_t *>(qb32 + P.rows * TEAM);
@@ -356,11 +357,17 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
         const float *vb = W.v + base;
         const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
         float4 x[VPT];
+        if (aligned && nbk == (uint32_t)VPT * TEAM * 4u) {   // a full bucket that fills every row: plain vector loads
 #pragma unroll
-        for (int i = 0; i < VPT; ++i)
-            x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
+            for (int i = 0; i < VPT; ++i)
+                x[i] = reinterpret_cast<const float4 *>(vb)[(uint32_t)i * TEAM + tid];
+        } else {
+#pragma unroll
+            for (int i = 0; i < VPT; ++i)
+                x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
+        }
         auto row = [&](int i) { return x[i]; };
-        const float nrm = team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32));
+        const float nrm = uniform_f32(team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32)));
         const bool finite = nrm < __builtin_huge_valf();   // false for NaN too
         if (active && tid == 0) {
             W.norms_out[b] = nrm;
@@ -369,6 +376,15 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
         }
         const BucketScale B = make_scale(nrm, (int)P.s);
         const BucketKey key = bucket_key(W.seed, b);
+        if (B.prescale != 1.0f) {   // tiny norm: work on the bucket scaled by a power of two
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) {
+                x[i].x *= B.prescale;
+                x[i].y *= B.prescale;
+                x[i].z *= B.prescale;
+                x[i].w *= B.prescale;
+            }
+        }
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             if ((uint32_t)i < P.rows) {
