@@ -104,7 +104,7 @@ Workspace carve(void *base, uint32_t K, uint64_t nb, uint32_t slot_words)
     Workspace w;
     char *p = static_cast<char *>(base);
     w.lens = reinterpret_cast<uint32_t *>(p + off);
-    off += up((uint64_t)K * nb * 4);
+    off += up((uint64_t)K * ((nb + 3) & ~3ull) * 4);
     w.chunk_sums = reinterpret_cast<uint64_t *>(p + off);
     off += up((uint64_t)K * (nchunks + 1) * 8);
     w.staging = reinterpret_cast<uint32_t *>(p + off);
@@ -175,6 +175,7 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
     EncodeParams P{};
     P.d = d;
     P.nb = nb;
+    P.nb_stride = (nb + 3) & ~3ull;
     P.bucket = bucket;
     P.s = s;
     P.sync_shift = sync_stride ? log2u(sync_stride) : 0;
@@ -210,12 +211,13 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
     const uint64_t nchunks = (nb + kChunk - 1) / kChunk;
     const uint64_t *prefix = nullptr;
     if (nb > kDirectSumMax) {
-        hipLaunchKernelGGL(k_chunk_sums, dim3((uint32_t)nchunks, K), dim3(256), 0, st, w.lens, nb, nchunks,
-                           w.chunk_sums);
+        hipLaunchKernelGGL(k_chunk_sums, dim3((uint32_t)nchunks, K), dim3(256), 0, st, w.lens, nb, P.nb_stride,
+                           nchunks, w.chunk_sums);
         hipLaunchKernelGGL(k_chunk_scan, dim3(K), dim3(256), 0, st, w.chunk_sums, nchunks);
         prefix = w.chunk_sums;
     }
-    hipLaunchKernelGGL(k_finish, dim3((uint32_t)((nb + 3) / 4), K), dim3(256), 0, st, P, Wk, prefix, nchunks);
+    hipLaunchKernelGGL(k_finish, dim3((uint32_t)((nb + kFinishBuckets - 1) / kFinishBuckets), K), dim3(256), 0, st, P, Wk,
+                       prefix, nchunks);
     return check_launch();
 }
 

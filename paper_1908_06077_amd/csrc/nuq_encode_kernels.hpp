@@ -42,7 +42,8 @@ struct EncodeParams {
     uint32_t slot_words;   // staging words per bucket
     uint32_t rows;         // ceil(bucket / (4*TEAM))
     uint32_t lds_words;    // LDS words per team
-    uint32_t *lens;        // [K * nb] payload bits per bucket, worker-major
+    uint64_t nb_stride;    // nb rounded up to a multiple of 4: stride between workers in lens
+    uint32_t *lens;        // [K * nb_stride] payload bits per bucket, worker-major
     uint32_t *staging;     // [K * nb * slot_words]
     uint32_t *flags;
 };
@@ -312,7 +313,7 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
         for (uint32_t i = tid; i < P.nsync; i += TEAM)
             sg[i] = sync_l[i];
         if (tid == 0)
-            P.lens[gb] = total;
+            P.lens[(uint64_t)blockIdx.y * P.nb_stride + b] = total;
     }
 }
 
@@ -437,11 +438,11 @@ __device__ __forceinline__ uint64_t block_sum_u64(uint64_t x, uint64_t *scratch 
 }
 
 // chunk_sums[k * (nchunks + 1) + c] = words of worker k's buckets [c*1024, (c+1)*1024)
-__global__ __launch_bounds__(256) void k_chunk_sums(const uint32_t *lens, uint64_t nb, uint64_t nchunks,
-                                                    uint64_t *chunk_sums)
+__global__ __launch_bounds__(256) void k_chunk_sums(const uint32_t *lens, uint64_t nb, uint64_t nb_stride,
+                                                    uint64_t nchunks, uint64_t *chunk_sums)
 {
     __shared__ uint64_t scratch[4];
-    const uint32_t *l = lens + (uint64_t)blockIdx.y * nb;
+    const uint32_t *l = lens + (uint64_t)blockIdx.y * nb_stride;
     const uint64_t i0 = (uint64_t)blockIdx.x * kChunk;
     uint64_t s = 0;
     for (uint32_t k = threadIdx.x; k < kChunk; k += 256u)
@@ -486,52 +487,76 @@ __global__ __launch_bounds__(256) void k_chunk_scan(uint64_t *chunk_sums, uint64
     }
 }
 
-// grid (ceil(nb / 4), K).  chunk_prefix == nullptr: sum the lengths of all earlier buckets directly.
+constexpr uint32_t kFinishBuckets = 16;   // buckets per workgroup of k_finish
+
+// grid (ceil(nb / 16), K).  chunk_prefix == nullptr: sum the lengths of all earlier buckets directly.
 __global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, const uint64_t *chunk_prefix,
                                                 uint64_t nchunks)
 {
     __shared__ uint64_t scratch[4];
+    __shared__ uint32_t wstart[kFinishBuckets + 1];   // first word of each bucket, relative to the workgroup's first
+    __shared__ uint32_t skip[kFinishBuckets];
     const EncodeWorker &W = Wk.w[blockIdx.y];
-    const uint32_t *lens = P.lens + (uint64_t)blockIdx.y * P.nb;
-    const uint64_t b_first = (uint64_t)blockIdx.x * 4u;
+    const uint32_t *__restrict__ lens = P.lens + (uint64_t)blockIdx.y * P.nb_stride;
+    const uint64_t b_first = (uint64_t)blockIdx.x * kFinishBuckets;
+    const uint32_t tid = threadIdx.x;
+
+    // words before this workgroup's first bucket
     uint64_t lo = 0, base = 0;
     if (chunk_prefix) {
         const uint64_t c = b_first / kChunk;
         lo = c * kChunk;
         base = chunk_prefix[(uint64_t)blockIdx.y * (nchunks + 1) + c];
     }
-    uint64_t part = 0;
-    for (uint64_t i = lo + threadIdx.x; i < b_first; i += 256u)
-        part += (lens[i] + 31u) >> 5;
-    uint64_t start = base + block_sum_u64(part, scratch);   // first word of bucket b_first
-
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
-    const uint64_t b = b_first + wave;
-    uint32_t len = 0;
-    for (uint32_t w = 0; w <= wave; ++w) {                  // (at most four) lengths of this workgroup's buckets
-        const uint32_t l = b_first + w < P.nb ? lens[b_first + w] : 0u;
-        if (w < wave)
-            start += (l + 31u) >> 5;
-        else
-            len = l;
+    uint32_t my_len = 0;
+    if (tid < kFinishBuckets && b_first + tid < P.nb)
+        my_len = lens[b_first + tid];
+    uint32_t part = 0;     // < 2^32: at most 8192 lengths of < 2^21 bits each are summed here
+    {
+        // lo and b_first are multiples of 16, so the range splits into aligned groups of four lengths
+        const uint4 *__restrict__ l4 = reinterpret_cast<const uint4 *>(lens + lo);
+        const uint32_t n4 = (uint32_t)((b_first - lo) >> 2);
+#pragma unroll 4
+        for (uint32_t i = tid; i < n4; i += 256u) {
+            const uint4 v = l4[i];
+            part += ((v.x + 31u) >> 5) + ((v.y + 31u) >> 5) + ((v.z + 31u) >> 5) + ((v.w + 31u) >> 5);
+        }
     }
-    if (b >= P.nb)
-        return;
-    if (lane == 0) {
-        W.bit_off[b + 1] = 32ull * start + len;
-        if (b == 0)
+    base += block_sum_u64(part, scratch);
+    if (tid < kFinishBuckets)
+        wstart[tid + 1] = (my_len + 31u) >> 5;
+    if (tid == 0)
+        wstart[0] = 0;
+    __syncthreads();
+    if (tid == 0)
+        for (uint32_t j = 1; j <= kFinishBuckets; ++j)
+            wstart[j] += wstart[j - 1];
+    __syncthreads();
+    if (tid < kFinishBuckets && b_first + tid < P.nb) {
+        const uint64_t start = base + wstart[tid];
+        W.bit_off[b_first + tid + 1] = 32ull * start + my_len;
+        if (b_first + tid == 0)
             W.bit_off[0] = 0;
-    }
-    const uint64_t nw = (len + 31u) >> 5;
-    if (start + nw > W.words_cap) {
-        if (lane == 0 && nw)
+        const bool over = base + wstart[tid + 1] > W.words_cap;
+        skip[tid] = over;
+        if (over && my_len)
             atomicOr(P.flags, kFlagCapacity);
-        return;
     }
-    const uint32_t *slot = P.staging + ((uint64_t)blockIdx.y * P.nb + b) * P.slot_words;
-    uint32_t *dst = W.words + start;
-    for (uint64_t i = lane; i < nw; i += 64u)
-        dst[i] = slot[i];
+    __syncthreads();
+
+    // copy the staging slots: word w of the workgroup's run belongs to the bucket found by bisection
+    const uint32_t total = wstart[kFinishBuckets];
+    const uint32_t *__restrict__ staging = P.staging + ((uint64_t)blockIdx.y * P.nb + b_first) * P.slot_words;
+    uint32_t *__restrict__ dst = W.words + base;
+#pragma unroll 4
+    for (uint32_t w = tid; w < total; w += 256u) {
+        uint32_t j = 0;
+#pragma unroll
+        for (uint32_t step = kFinishBuckets / 2; step >= 1; step >>= 1)
+            j += (wstart[j + step] <= w) ? step : 0u;
+        if (!skip[j])
+            dst[w] = staging[(uint64_t)j * P.slot_words + (w - wstart[j])];
+    }
 }
 
 }  // namespace nuq
