@@ -8,10 +8,13 @@
 // loads.  Each (worker, bucket, segment) bit string is then parsed by one lane, sequentially,
 // as the format requires; the tile is finally scaled, rounded to fp32 and written out once.
 //
-// The parse loop is bound by instruction issue, so it is kept short: a 128-entry table indexed
-// by the next seven stream bits resolves every Elias code of up to seven bits (values 1..15:
-// all level indices and two thirds of the gaps) in one LDS read and gives the position and
-// width of the last group of longer codes; format checks are accumulated and tested once.
+// The parse loop is bound by instruction issue and by the latency of its dependent LDS reads,
+// so it is kept short: the window at the current bit position comes from one two-word LDS
+// read, a 128-entry table indexed by the next seven stream bits resolves every gap code of up
+// to seven bits (values 1..15) and gives position and width of the last group of longer ones,
+// the level code is taken apart with byte permutes, and format checks are accumulated and
+// tested once.  Every metadata load of a tile (offsets, sync entries, norms) is issued before
+// the first wait.
 #pragma once
 #include "nuq_device.hpp"
 #include "nuq_encode_kernels.hpp"
@@ -109,143 +112,122 @@ struct BitReader {
     }
 };
 
-// Parse one unit: the records of worker k's bucket b whose bits lie in [bit_lo, bit_hi)
-// (offsets from the bucket's first bit), and add their values into the tile.
-//   forced   : in-bucket index of the first record (>= 0 when entered through a sync entry,
-//              whose gap code is then skipped), or -1 to start from the bucket's beginning
-//   idx_lo/idx_hi : records below idx_lo are dropped (walks without an index), a record at or
-//              above idx_hi is a format error
-template <class WordPtr>
-__device__ __forceinline__ void decode_unit(const DecodeParams &P, WordPtr words, uint32_t limit_words,
-                                            uint32_t bit_lo, uint32_t bit_hi, int forced, uint32_t idx_lo,
-                                            uint32_t idx_hi, double wnorm, double *tile, int tile_lo)
-{
-    BitReader<WordPtr> br;
-    br.init(words, bit_lo, limit_words);
-    uint32_t pos = bit_lo;
-    int prev = -1;
-    while (pos < bit_hi) {
-        br.refill();
-        uint32_t w = br.peek();
-        uint32_t gap, lg, j, lj;
-        bool ok = erc_decode_bits(w, gap, lg);
-        w <<= lg;
-        const uint32_t neg = w >> 31;
-        w <<= 1;
-        ok = erc_decode_bits(w, j, lj) && ok;
-        const uint32_t len = lg + 1u + lj;
-        int idx = prev + (int)gap;
-        if (forced >= 0) {
-            idx = forced;
-            forced = -1;
-        }
-        if (!ok || len > 31u || pos + len > bit_hi || idx <= prev || (uint32_t)idx >= idx_hi || j < 1u ||
-            j > P.s + 1u) {
-            atomicOr(P.flags, kFlagMalformed);
-            return;
-        }
-        if ((uint32_t)idx >= idx_lo) {
-            // ||v|| * l_j = (||v|| * 2^(-1-s)) * 2^j, exact in fp64
-            double val = ldexp(wnorm, (int)j);
-            atomicAdd(&tile[idx - tile_lo], neg ? -val : val);
-        }
-        br.skip(len);
-        pos += len;
-        prev = idx;
-    }
-}
-
-struct GlobalWords {
+struct WalkWords {
     const uint32_t *p;
     __device__ __forceinline__ uint32_t operator[](uint32_t i) const { return p[i]; }
 };
 
-// ---- seven-bit code table -------------------------------------------------------------
-// Entry for the next seven stream bits p (MSB first):
-//   short code (complete within the seven bits): bits 0..4 = code length, bits 5..9 = value
-//   long code (three groups): bit 15 set, bits 0..4 = bits before the last group (5 or 6),
-//   bits 5..9 = width of the last group (5..16); the value is that group, one 0 follows.
-__device__ __forceinline__ uint32_t code_table_entry(uint32_t p)
+struct GlobalWords {
+    const uint32_t *p;
+    uint32_t last;      // highest readable word index
+    __device__ __forceinline__ void pair(uint32_t i, uint32_t &hi, uint32_t &lo) const
+    {
+        hi = p[min(i, last)];
+        lo = p[min(i + 1u, last)];
+    }
+};
+
+// Words staged in LDS; the staging area is padded so that word i + 1 of any staged word i exists.
+struct StagedWords {
+    const uint32_t *p;
+    __device__ __forceinline__ void pair(uint32_t i, uint32_t &hi, uint32_t &lo) const
+    {
+        hi = p[i];
+        lo = p[i + 1u];
+    }
+};
+
+// ---- gap code table --------------------------------------------------------------------
+// Entry for the next seven stream bits p (MSB first), as fields of five bits each:
+//   bits  0..4   length of the whole code
+//   bits  5..9   position (from the LSB of a 32-bit window) of the last group of a three-group code
+//   bits 10..14  width of that group (5..16), 0 for a code complete within the seven bits
+//   bits 15..19  value of a code complete within the seven bits (1..15), else 0
+// so that value = field3 + bitfield(window, field1, field2) for every code of up to three groups.
+__device__ __forceinline__ uint32_t gap_table_entry(uint32_t p)
 {
     const uint32_t w = p << 25;
     uint32_t N, len;
     erc_decode_bits(w, N, len);
     if (len <= 7u)
-        return len | (N << 5);
+        return len | (N << 15);
     const uint32_t k2 = (w >> 30) + 1u;                         // second group's width (3 or 4)
     const uint32_t g2 = (w >> (30u - k2)) & ((1u << k2) - 1u);  // second group = last group's width - 1
-    return 0x8000u | (2u + k2) | ((g2 + 1u) << 5);
+    const uint32_t a = 2u + k2, v = g2 + 1u;
+    return (a + v + 1u) | ((32u - a - v) << 5) | (v << 10);
 }
 
-// Decode one Elias code from the window w with the table; returns the value, `len` its length.
-__device__ __forceinline__ uint32_t table_decode(const uint16_t *lut, uint32_t w, uint32_t &len)
+// Parse the records in bits [bit_lo, bit_hi) of a unit's frame and add their values into the tile.
+//   forced : in-bucket index of the first record when the unit was entered through a sync entry
+//            (its gap code is then only skipped), or -1 to start from the bucket's beginning
+//   idx_hi : a record at or above this index is a format error; smax = s + 1
+// Format violations set `bad`; nothing is ever added outside [0, idx_hi) of the bucket.
+//
+// One iteration per record, kept short because the loop is bound by instruction issue: the
+// 32-bit window at the current position is rebuilt from two adjacent words, the gap comes from
+// one table read, and the level code (at most seven bits: 0 | 1x0 | 101yy0 | 111yyy0) is taken
+// apart with byte-permute lookups on its first three bits.
+template <class Words>
+__device__ __forceinline__ void decode_unit_fast(const Words &words, const uint32_t *lut, uint32_t bit_lo,
+                                                 uint32_t bit_hi, int forced, uint32_t idx_hi, uint32_t smax,
+                                                 double wnorm, double *tile_at0, bool &bad)
 {
-    const uint32_t e = lut[w >> 25];
-    const uint32_t a = e & 31u;              // length, or bits before the last group
-    const uint32_t v = (e >> 5) & 31u;       // value, or width of the last group
-    const uint32_t big = ((w << a) >> 1) >> (31u - v);   // last group of a long code (v >= 5)
-    const bool is_long = (e & 0x8000u) != 0u;
-    len = is_long ? a + v + 1u : a;
-    return is_long ? big : v;
-}
-
-// Fast parse of one unit from words held in `words` (LDS or global through the accessor).
-// Reads are clamped to word index `last_word`; format violations set *bad and never leave
-// [idx_lo, idx_hi) of the tile.
-template <class WordPtr>
-__device__ __forceinline__ void decode_unit_fast(WordPtr words, uint32_t last_word, const uint16_t *lut,
-                                                 uint32_t bit_lo, uint32_t bit_hi, int forced, uint32_t idx_hi,
-                                                 uint32_t smax, double wnorm, double *tile_at0, bool &bad)
-{
-    uint32_t next = bit_lo >> 5;
-    const uint32_t bo = bit_lo & 31u;
-    uint64_t buf = ((uint64_t)words[min(next, last_word)] << 32) | words[min(next + 1u, last_word)];
-    next += 2u;
-    buf <<= bo;
-    uint32_t cnt = 64u - bo;
-    int remaining = (int)(bit_hi - bit_lo);
+    uint32_t pos = bit_lo;
     int prev = -1;
-    if (forced >= 0 && remaining > 0) {       // entered through a sync entry: the first gap is replaced
-        uint32_t lg;
-        const uint32_t gap = table_decode(lut, (uint32_t)(buf >> 32), lg);
+    if (forced >= 0 && pos < bit_hi) {
+        uint32_t hi, lo;
+        words.pair(pos >> 5, hi, lo);
+        const uint32_t w = (uint32_t)(((((uint64_t)hi << 32) | lo) << (pos & 31u)) >> 32);
+        const uint32_t e = lut[w >> 25];
+        const uint32_t gap = (e >> 15) + __builtin_amdgcn_ubfe(w, (e >> 5) & 31u, (e >> 10) & 31u);
         prev = forced - (int)gap;
     }
-    while (remaining > 0) {
-        if (cnt <= 32u) {
-            const uint32_t wd = words[min(next, last_word)];
-            ++next;
-            buf |= (uint64_t)wd << (32u - cnt);
-            cnt += 32u;
-        }
-        const uint32_t w = (uint32_t)(buf >> 32);
-        uint32_t lg, lj;
-        const uint32_t gap = table_decode(lut, w, lg);
-        const uint32_t w2 = w << lg;                      // sign bit on top
-        const uint32_t j = table_decode(lut, w2 << 1, lj);
-        const uint32_t len = lg + 1u + lj;
+    while (pos < bit_hi) {
+        uint32_t hi, lo;
+        words.pair(pos >> 5, hi, lo);
+        const uint32_t w = (uint32_t)(((((uint64_t)hi << 32) | lo) << (pos & 31u)) >> 32);
+        const uint32_t e = lut[w >> 25];
+        const uint32_t lg = e & 31u;
+        const uint32_t gap = (e >> 15) + __builtin_amdgcn_ubfe(w, (e >> 5) & 31u, (e >> 10) & 31u);
+        const uint32_t w2 = w << lg;                 // sign bit on top, level code below
+        const uint32_t c = w2 << 1;
+        const uint32_t sel = (c >> 29) | 0x0c0c0c00u;
+        const uint32_t lj = __builtin_amdgcn_perm(0x07030603u, 0x01010101u, sel);    // code length
+        const uint32_t off = __builtin_amdgcn_perm(0x1a1e1b1eu, 0u, sel);            // where its last group sits
+        const uint32_t wd = __builtin_amdgcn_perm(0x04020302u, 0u, sel);             // and how wide it is
+        const uint32_t j1 = __builtin_amdgcn_perm(0u, 0x01010101u, sel);             // the code "0"
+        const uint32_t j = j1 | __builtin_amdgcn_ubfe(c, off, wd);
+        const uint32_t unterminated = __builtin_amdgcn_ubfe(c, (off - 1u) & 31u, 1u);   // a third group would follow
         uint32_t idx = (uint32_t)(prev + (int)gap);
-        bad |= (idx >= idx_hi) | (j - 1u >= smax) | (len > 31u);
+        bad |= (idx >= idx_hi) | (j > smax) | (unterminated != 0u);
         idx = min(idx, idx_hi - 1u);
         // ||v|| * l_j = (||v|| * 2^(-1-s)) * 2^j, exact in fp64; the sign goes into the top bit
-        const double mag = ldexp(wnorm, (int)min(j, 15u));
-        const uint64_t vb = (uint64_t)__double_as_longlong(mag) ^ ((uint64_t)(w2 & 0x80000000u) << 32);
+        const double mag = ldexp(wnorm, (int)j);
+        const uint32_t mh = (uint32_t)((uint64_t)__double_as_longlong(mag) >> 32);
+        const uint32_t vh = (mh & 0x7fffffffu) | (w2 & 0x80000000u);
+        const uint64_t vb = ((uint64_t)vh << 32) | (uint32_t)__double_as_longlong(mag);
         atomicAdd(tile_at0 + idx, __longlong_as_double((long long)vb));
-        buf <<= len;
-        cnt -= len;
-        remaining -= (int)len;
+        pos += lg + 1u + lj;
         prev = (int)idx;
     }
-    bad |= remaining != 0;
+    bad |= pos != bit_hi;
 }
+
+// Metadata of one parse unit = (bucket in tile, segment, worker), as loaded from memory.
+struct UnitRaw {
+    uint64_t bo0, bo1;      // bit_off[b], bit_off[b + 1]
+    uint32_t e_lo, e_hi;    // sync entries that bound the segment (0 when not applicable)
+    float norm;
+};
 
 __global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
 {
     __shared__ __align__(16) double tile[kTileCoords];
-    __shared__ uint32_t stage[kStageWords];
+    __shared__ uint32_t stage[kStageWords + 2];
     __shared__ uint32_t st_off[kMaxStreams + 1];  // exclusive prefix of staged words per stream
     __shared__ uint32_t st_bit0[kMaxStreams];     // first staged bit (multiple of 32), from the bucket's first bit
     __shared__ uint64_t st_src[kMaxStreams];      // global address of the first staged word
-    __shared__ uint16_t lut[128];
+    __shared__ uint32_t lut[128];
     __shared__ uint32_t scan_scratch[2];
 
     // ---- which coordinates does this tile cover?
@@ -272,32 +254,78 @@ __global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
     const bool walk = partial && !P.sync_shift;                                      // no index: walk from the start
     const uint32_t g1 = partial && P.sync_shift ? min(P.nseg, g0 + P.segs_per_tile) : P.nseg;   // one past the last
     const uint32_t tid = threadIdx.x;
+    const uint32_t nstreams = nbuck * P.K;        // stream = (bucket in tile, worker)
+    const uint32_t segs = g1 - g0;
+    const uint32_t units = nstreams * segs;       // unit = (bucket in tile, segment, worker)
+
+    // Unit u's worker, bucket and segment, and its metadata loads (all independent of each other).
+    auto unit_coords = [&](uint32_t u, uint32_t &k, uint32_t &bi, uint32_t &g) {
+        k = u % P.K;
+        const uint32_t r = u / P.K;
+        g = g0 + r % segs;
+        bi = r / segs;
+    };
+    auto load_unit = [&](uint32_t u) {
+        uint32_t k, bi, g;
+        unit_coords(u, k, bi, g);
+        const uint64_t b = b0 + bi;
+        UnitRaw r;
+        r.bo0 = P.bit_off[k][b];
+        r.bo1 = P.bit_off[k][b + 1];
+        r.norm = P.norms[k][b];
+        r.e_lo = r.e_hi = 0;
+        if (P.sync_shift) {
+            const uint32_t *sy = P.sync[k] + b * P.nsync;
+            if (g > 0u)
+                r.e_lo = sy[g - 1u];
+            if (g + 1u < P.nseg)
+                r.e_hi = sy[g];
+        }
+        return r;
+    };
+
+    // ---- issue this thread's metadata loads: its stream's extent and its first unit
+    uint64_t s_bo0 = 0, s_bo1 = 0;
+    uint32_t s_e0 = 0, s_e1 = 0;
+    uint32_t s_k = 0;
+    uint64_t s_b = 0;
+    if (tid < nstreams) {
+        s_k = tid % P.K;
+        s_b = b0 + tid / P.K;
+        s_bo0 = P.bit_off[s_k][s_b];
+        s_bo1 = P.bit_off[s_k][s_b + 1];
+        if (partial && P.sync_shift) {
+            const uint32_t *sy = P.sync[s_k] + s_b * P.nsync;
+            if (g0 > 0u)
+                s_e0 = sy[g0 - 1u];
+            if (g1 < P.nseg)
+                s_e1 = sy[g1 - 1u];
+        }
+    }
+    UnitRaw first{};
+    if (tid < units)
+        first = load_unit(tid);
 
     for (uint32_t i = tid; i < (span + 1u) / 2u; i += kDecodeWG)
         reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
-    lut[tid] = (uint16_t)code_table_entry(tid);
+    lut[tid] = gap_table_entry(tid);
 
-    // ---- which words does each stream = (bucket in tile, worker) need?
-    const uint32_t nstreams = nbuck * P.K;
+    // ---- which words does each stream need?
     uint32_t my_words = 0;
     if (tid < nstreams) {
-        const uint32_t k = tid % P.K;
-        const uint64_t b = b0 + tid / P.K;
-        const uint64_t start = (P.bit_off[k][b] + 31ull) & ~31ull;
-        const uint64_t end = P.bit_off[k][b + 1];
-        const uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
+        const uint64_t start = (s_bo0 + 31ull) & ~31ull;
+        const uint32_t len = s_bo1 > start ? (uint32_t)(s_bo1 - start) : 0u;
         uint32_t lo = 0, hi = len;
         if (partial && P.sync_shift) {
-            const uint32_t *sy = P.sync[k] + b * P.nsync;
             if (g0 > 0u)
-                lo = min(sy[g0 - 1u] & 0x1FFFFFu, len);
+                lo = min(s_e0 & 0x1FFFFFu, len);
             if (g1 < P.nseg)
-                hi = min(sy[g1 - 1u] & 0x1FFFFFu, len);
+                hi = min(s_e1 & 0x1FFFFFu, len);
         }
         const uint32_t w0 = lo >> 5;
         my_words = (hi > lo && !walk) ? ((hi + 31u) >> 5) - w0 : 0u;
         st_bit0[tid] = w0 << 5;
-        st_src[tid] = reinterpret_cast<uint64_t>(P.words[k] + (start >> 5) + w0);
+        st_src[tid] = reinterpret_cast<uint64_t>(P.words[s_k] + (start >> 5) + w0);
     }
     uint32_t total_words;
     const uint32_t my_off = team_exclusive_sum<kDecodeWG>(my_words, scan_scratch, total_words);
@@ -320,41 +348,37 @@ __global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
         }
         stage[i] = reinterpret_cast<const uint32_t *>(st_src[lo])[i - st_off[lo]];
     }
+    if (tid < 2u)
+        stage[staged_words + tid] = 0u;          // the parser reads one word past the one it is in
     __syncthreads();
 
-    // ---- parse units: (bucket in tile, segment in tile, worker)
-    const uint32_t segs = g1 - g0;
-    const uint32_t units = nbuck * segs * P.K;
+    // ---- parse units
     const double wscale = ldexp(1.0, -1 - (int)P.s);
     bool bad = false;
     for (uint32_t u = tid; u < units; u += kDecodeWG) {
-        const uint32_t k = u % P.K;
-        const uint32_t r = u / P.K;
-        const uint32_t g = g0 + r % segs;
-        const uint32_t bi = r / segs;
+        const UnitRaw m = u == tid ? first : load_unit(u);
+        uint32_t k, bi, g;
+        unit_coords(u, k, bi, g);
         const uint64_t b = b0 + bi;
         const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
         const uint32_t sidx = bi * P.K + k;
-        const uint64_t start = (P.bit_off[k][b] + 31ull) & ~31ull;
-        const uint64_t end = P.bit_off[k][b + 1];
-        const uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
+        const uint64_t start = (m.bo0 + 31ull) & ~31ull;
+        const uint32_t len = m.bo1 > start ? (uint32_t)(m.bo1 - start) : 0u;
         uint32_t bit_lo = 0, bit_hi = len, idx_lo = 0, idx_hi = nbk;
         int forced = -1;
         if (P.sync_shift) {
-            const uint32_t *sy = P.sync[k] + b * P.nsync;
             idx_lo = g << P.sync_shift;
             idx_hi = min(nbk, (g + 1u) << P.sync_shift);
             if (idx_lo >= nbk)
                 continue;
             if (g > 0u) {
-                const uint32_t e = sy[g - 1u];
-                if (e & kSyncEmpty)
+                if (m.e_lo & kSyncEmpty)
                     continue;
-                bit_lo = e & 0x1FFFFFu;
-                forced = (int)(idx_lo + ((e >> 21) & 0x3FFu));
+                bit_lo = m.e_lo & 0x1FFFFFu;
+                forced = (int)(idx_lo + ((m.e_lo >> 21) & 0x3FFu));
             }
             if (g + 1u < P.nseg)
-                bit_hi = sy[g] & 0x1FFFFFu;
+                bit_hi = m.e_hi & 0x1FFFFFu;
             if (bit_lo > bit_hi || bit_hi > len || (forced >= 0 && (uint32_t)forced >= idx_hi)) {
                 bad = true;
                 continue;
@@ -366,13 +390,13 @@ __global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
         }
         if (bit_hi <= bit_lo)
             continue;
-        const double wnorm = (double)P.norms[k][b] * wscale;
+        const double wnorm = (double)m.norm * wscale;
         const int tile_lo = partial ? (int)in_lo : -(int)(bi * P.bucket);
         if (walk) {
             // no index: parse the bucket from its first record in global memory, keep what lands in the tile
-            GlobalWords gw{P.words[k] + (start >> 5)};
+            WalkWords gw{P.words[k] + (start >> 5)};
             const uint32_t hi_idx = min(nbk, in_lo + P.tile_coords);
-            BitReader<GlobalWords> br;
+            BitReader<WalkWords> br;
             br.init(gw, 0, (len + 31u) >> 5);
             uint32_t pos = 0;
             int prev = -1;
@@ -410,12 +434,11 @@ __global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
         }
         double *tile_at0 = tile - tile_lo;       // address of in-bucket index 0 (never dereferenced outside the tile)
         if (se <= kStageWords) {
-            decode_unit_fast(stage + so, se - so - 1u, lut, bit_lo - bit0, bit_hi - bit0, forced, idx_hi, P.s + 1u,
+            decode_unit_fast(StagedWords{stage + so}, lut, bit_lo - bit0, bit_hi - bit0, forced, idx_hi, P.s + 1u,
                              wnorm, tile_at0, bad);
         } else {                                  // did not fit in LDS: read the words from global memory
-            GlobalWords gw{reinterpret_cast<const uint32_t *>(st_src[sidx])};
-            decode_unit_fast(gw, se - so - 1u, lut, bit_lo - bit0, bit_hi - bit0, forced, idx_hi, P.s + 1u, wnorm,
-                             tile_at0, bad);
+            GlobalWords gw{reinterpret_cast<const uint32_t *>(st_src[sidx]), se - so - 1u};
+            decode_unit_fast(gw, lut, bit_lo - bit0, bit_hi - bit0, forced, idx_hi, P.s + 1u, wnorm, tile_at0, bad);
         }
     }
     if (bad)
