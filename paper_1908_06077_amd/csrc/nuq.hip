@@ -221,6 +221,25 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
     return check_launch();
 }
 
+// Workgroups of the persistent decode kernel that the current device holds at once (0 on error).
+uint32_t decode_resident_workgroups()
+{
+    static uint32_t cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return 0;
+    if (!cached[dev]) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(k_decode_accumulate),
+                                                         (int)kDecodeWG, 0) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || per_cu < 1 ||
+            cus < 1)
+            return 0;
+        cached[dev] = (uint32_t)per_cu * (uint32_t)cus;
+    }
+    return cached[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -383,25 +402,38 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
     P.nseg = nsync + 1;
     P.scale = scale;
     P.accumulate = accumulate;
-    uint64_t grid;
+    uint64_t ntiles;
+    uint32_t max_streams;
     if (bucket <= kTileCoords) {
         const uint32_t by_size = kTileCoords / bucket, by_streams = kMaxStreams / K;
         P.buckets_per_tile = by_size < by_streams ? by_size : by_streams;
         P.tiles_per_bucket = 1;
         P.tile_coords = P.buckets_per_tile * bucket;
         P.segs_per_tile = P.nseg;
-        grid = (P.nb + P.buckets_per_tile - 1) / P.buckets_per_tile;
+        ntiles = (P.nb + P.buckets_per_tile - 1) / P.buckets_per_tile;
+        max_streams = P.buckets_per_tile * K;
     } else {
         P.buckets_per_tile = 0;
         P.tile_coords = kTileCoords;
         P.tiles_per_bucket = (bucket + kTileCoords - 1) / kTileCoords;
         P.segs_per_tile = P.sync_shift ? (kTileCoords >> P.sync_shift) : 1;
-        grid = P.nb * P.tiles_per_bucket;
+        ntiles = P.nb * P.tiles_per_bucket;
+        max_streams = K;
     }
-    if (grid > 0x7fffffffull)
+    if (ntiles > 0x7fffffffull)
         return NUQ_EINVAL;
+    P.ntiles = (uint32_t)ntiles;
+    // threads per stream for the copy of its words: the largest power of two that gives every stream a group
+    P.lanes_shift = 0;
+    while ((2u << P.lanes_shift) * max_streams <= kDecodeWG)
+        ++P.lanes_shift;
+    P.stream_cap = kWordsPerThread << P.lanes_shift;
+    const uint32_t resident = decode_resident_workgroups();
+    if (!resident)
+        return NUQ_EHIP;
+    const uint32_t grid = P.ntiles < resident ? P.ntiles : resident;
     ScopedTiming timing(NUQ_T_DECODE, static_cast<hipStream_t>(stream));
-    hipLaunchKernelGGL(k_decode_accumulate, dim3((uint32_t)grid), dim3(kDecodeWG), 0, static_cast<hipStream_t>(stream), P);
+    hipLaunchKernelGGL(k_decode_accumulate, dim3(grid), dim3(kDecodeWG), 0, static_cast<hipStream_t>(stream), P);
     return check_launch();
 }
 
