@@ -423,15 +423,19 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
     if (ntiles > 0x7fffffffull)
         return NUQ_EINVAL;
     P.ntiles = (uint32_t)ntiles;
-    // threads per stream for the copy of its words: the largest power of two that gives every stream a group
+    // lanes (of the preparing wave) per stream for the copy of its words: the largest power of two that gives
+    // every stream a group
     P.lanes_shift = 0;
-    while ((2u << P.lanes_shift) * max_streams <= kDecodeWG)
+    while ((2u << P.lanes_shift) * max_streams <= 64u)
         ++P.lanes_shift;
-    P.stream_cap = kWordsPerThread << P.lanes_shift;
+    P.stream_cap = kWordsPerLane << P.lanes_shift;
     const uint32_t resident = decode_resident_workgroups();
     if (!resident)
         return NUQ_EHIP;
-    const uint32_t grid = P.ntiles < resident ? P.ntiles : resident;
+    // every workgroup walks the same number of tiles (one fewer for some): the fewest rounds the resident
+    // workgroups need, then the fewest workgroups that still finish in that many rounds
+    const uint32_t rounds = (P.ntiles + resident - 1) / resident;
+    const uint32_t grid = (P.ntiles + rounds - 1) / rounds;
     ScopedTiming timing(NUQ_T_DECODE, static_cast<hipStream_t>(stream));
     hipLaunchKernelGGL(k_decode_accumulate, dim3(grid), dim3(kDecodeWG), 0, static_cast<hipStream_t>(stream), P);
     return check_launch();

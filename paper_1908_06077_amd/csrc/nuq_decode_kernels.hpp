@@ -8,18 +8,15 @@
 // string -- a unit -- is parsed by one lane, sequentially, as the format requires, and the
 // tile is finally scaled, rounded to fp32 and written out once.
 //
-// LDS capacity bounds the number of tiles in flight, and a tile's life would mostly be spent
-// waiting on memory: offsets and sync entries first, then the words they point to.  So a
-// workgroup is persistent and walks a strided sequence of tiles as a software pipeline held in
-// registers: while tile t is parsed, the words of tile t+1 are in flight to registers (they go
-// to LDS once tile t's parse is over) and the metadata of tile t+2 is in flight too.
-//
-// The parse loop is bound by instruction issue and by the latency of its dependent LDS reads,
-// so it is kept short: the window at the current bit position comes from one two-word LDS
-// read, a 128-entry table indexed by the next seven stream bits resolves every gap code of up
-// to seven bits (values 1..15) and gives position and width of the last group of longer ones,
-// the level code is taken apart with byte permutes, and format checks are accumulated and
-// tested once.
+// LDS capacity bounds the number of tiles in flight, a lone wave issues a dependent
+// instruction only every nine cycles or so, and a tile's life would mostly be spent waiting on
+// memory (offsets and sync entries first, then the words they point to) and on bookkeeping.  So
+// a workgroup is persistent, walks a strided sequence of tiles, and its two waves have
+// different jobs: the first parses tile t while the second prepares tile t+1 -- works out
+// which words each unit needs, copies them into the other half of a double-buffered staging
+// area, leaves a four-word plan per unit in LDS -- and has the metadata loads of tile t+2 in
+// flight.  Both waves then write tile t out and clear it.  The critical path of a tile is its
+// parse and its write-out.
 #pragma once
 #include "nuq_device.hpp"
 #include "nuq_encode_kernels.hpp"
@@ -27,11 +24,12 @@
 namespace nuq {
 
 constexpr uint32_t kMaxWorkers = 32;
-constexpr uint32_t kDecodeWG = 128;        // threads per workgroup
+constexpr uint32_t kDecodeWG = 128;        // threads per workgroup: a parsing wave and a preparing wave
 constexpr uint32_t kTileCoords = 2048;     // coordinates per tile (16 KB of fp64)
-constexpr uint32_t kWordsPerThread = 5;    // staged words each thread carries through the pipeline
-constexpr uint32_t kStageWords = kDecodeWG * kWordsPerThread;   // LDS words for staged bit strings
+constexpr uint32_t kWordsPerLane = 8;      // staged words each lane of the preparing wave carries
+constexpr uint32_t kStageWords = kWave * kWordsPerLane;   // LDS words per staging buffer
 constexpr uint32_t kMaxStreams = 64;       // (bucket, worker) bit strings per tile
+constexpr uint32_t kPlanned = 2 * kWave;   // units of a tile that are planned ahead (two per preparing lane)
 
 struct DecodeParams {
     const float *norms[kMaxWorkers];
@@ -53,8 +51,8 @@ struct DecodeParams {
     uint32_t tiles_per_bucket;  // >= 1
     uint32_t tile_coords;       // coordinates a full tile spans
     uint32_t segs_per_tile;     // segments of one bucket inside a tile
-    uint32_t lanes_shift;       // log2 of the threads that copy one stream's words
-    uint32_t stream_cap;        // LDS words reserved per stream = kWordsPerThread << lanes_shift
+    uint32_t lanes_shift;       // log2 of the lanes that copy one stream's words
+    uint32_t stream_cap;        // LDS words reserved per stream = kWordsPerLane << lanes_shift
     float scale;
     int accumulate;
 };
@@ -125,44 +123,53 @@ struct WalkWords {
     __device__ __forceinline__ uint32_t operator[](uint32_t i) const { return p[i]; }
 };
 
+// Word sources for the parser.  pair_at(q) returns words q - 1 and q of the unit's frame (word 0 holds its
+// bit 0); only the second one matters when q - 1 does not exist.
 struct GlobalWords {
     const uint32_t *p;
     uint32_t last;      // highest readable word index
-    __device__ __forceinline__ void pair(uint32_t i, uint32_t &hi, uint32_t &lo) const
+    __device__ __forceinline__ void pair_at(uint32_t q, uint32_t &hi, uint32_t &lo) const
     {
-        hi = p[min(i, last)];
-        lo = p[min(i + 1u, last)];
+        hi = p[min(max(q, 1u) - 1u, last)];
+        lo = p[min(q, last)];
     }
 };
 
-// Words staged in LDS; the staging area is padded so that word i + 1 of any staged word i exists.
+// Words staged in LDS.  `p` points one word before the frame; a staging buffer is padded at both ends so
+// that every pair the parser can ask for exists.
 struct StagedWords {
     const uint32_t *p;
-    __device__ __forceinline__ void pair(uint32_t i, uint32_t &hi, uint32_t &lo) const
+    __device__ __forceinline__ void pair_at(uint32_t q, uint32_t &hi, uint32_t &lo) const
     {
-        hi = p[i];
-        lo = p[i + 1u];
+        hi = p[q];
+        lo = p[q + 1u];
     }
 };
 
 // ---- gap code table --------------------------------------------------------------------
-// Entry for the next seven stream bits p (MSB first), as fields of five bits each:
-//   bits  0..4   length of the whole code
-//   bits  5..9   position (from the LSB of a 32-bit window) of the last group of a three-group code
-//   bits 10..14  width of that group (5..16), 0 for a code complete within the seven bits
-//   bits 15..19  value of a code complete within the seven bits (1..15), else 0
-// so that value = field3 + bitfield(window, field1, field2) for every code of up to three groups.
+// Entry for the next seven stream bits p (MSB first):
+//   bits  0..4   length of the whole code (its first two groups fix it)
+//   bits  5..9   width of the last group of a three-group code (5..16), 0 for a code complete within the
+//                seven bits; that group ends one bit before the code does
+//   bits 10..13  value of a code complete within the seven bits (1..15), else 0
+// so that value = field2 + bitfield(window, 33 - length, width) for every code of up to three groups.
 __device__ __forceinline__ uint32_t gap_table_entry(uint32_t p)
 {
     const uint32_t w = p << 25;
     uint32_t N, len;
     erc_decode_bits(w, N, len);
     if (len <= 7u)
-        return len | (N << 15);
+        return len | (N << 10);
     const uint32_t k2 = (w >> 30) + 1u;                         // second group's width (3 or 4)
     const uint32_t g2 = (w >> (30u - k2)) & ((1u << k2) - 1u);  // second group = last group's width - 1
     const uint32_t a = 2u + k2, v = g2 + 1u;
-    return (a + v + 1u) | ((32u - a - v) << 5) | (v << 10);
+    return (a + v + 1u) | (v << 5);
+}
+
+// value of the gap code at the top of window w, given its table entry
+__device__ __forceinline__ uint32_t gap_value(uint32_t w, uint32_t e)
+{
+    return (e >> 10) + __builtin_amdgcn_ubfe(w, 33u - (e & 31u), (e >> 5) & 31u);
 }
 
 // Parse the records in bits [bit_lo, bit_hi) of a unit's frame and add their values into the tile.
@@ -171,37 +178,39 @@ __device__ __forceinline__ uint32_t gap_table_entry(uint32_t p)
 //   idx_hi : a record at or above this index is a format error; smax = s + 1
 // Format violations set `bad`; nothing is ever added outside [0, idx_hi) of the bucket.
 //
-// One iteration per record, kept short because the loop is bound by instruction issue: the
-// 32-bit window at the current position is rebuilt from two adjacent words, the gap comes from
-// one table read, and the level code (at most seven bits: 0 | 1x0 | 101yy0 | 111yyy0) is taken
-// apart with byte-permute lookups on its first three bits.
+// One iteration per record.  The loop is arranged around its one carried dependency, the bit position: the
+// 32-bit window at the position comes from two adjacent words through one funnel shift (position + 31 is the
+// loop variable: its word index names the second word of the pair, its complement is the shift), one table
+// read gives the gap code's length, byte permutes on the first three bits of the level code (at most seven
+// bits: 0 | 1x0 | 101yy0 | 111yyy0) give its length, and the read of the next record's words is issued right
+// then, before the value of this record is worked out and added.
 template <class Words>
-__device__ __forceinline__ void decode_unit_fast(const Words &words, const uint32_t *lut, uint32_t bit_lo,
+__device__ __forceinline__ void decode_unit_fast(const Words &words, const uint16_t *lut, uint32_t bit_lo,
                                                  uint32_t bit_hi, int forced, uint32_t idx_hi, uint32_t smax,
                                                  double wnorm, double *tile_at0, bool &bad)
 {
-    uint32_t pos = bit_lo;
+    uint32_t p31 = bit_lo + 31u;
+    const uint32_t end31 = bit_hi + 31u;
+    uint32_t hi, lo;
+    words.pair_at(p31 >> 5, hi, lo);
     int prev = -1;
-    if (forced >= 0 && pos < bit_hi) {
-        uint32_t hi, lo;
-        words.pair(pos >> 5, hi, lo);
-        const uint32_t w = (uint32_t)(((((uint64_t)hi << 32) | lo) << (pos & 31u)) >> 32);
+    if (forced >= 0 && p31 < end31) {
+        const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, ~p31);
         const uint32_t e = lut[w >> 25];
-        const uint32_t gap = (e >> 15) + __builtin_amdgcn_ubfe(w, (e >> 5) & 31u, (e >> 10) & 31u);
-        prev = forced - (int)gap;
+        prev = forced - (int)gap_value(w, e);
     }
-    while (pos < bit_hi) {
-        uint32_t hi, lo;
-        words.pair(pos >> 5, hi, lo);
-        const uint32_t w = (uint32_t)(((((uint64_t)hi << 32) | lo) << (pos & 31u)) >> 32);
+    while (p31 < end31) {
+        const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, ~p31);
         const uint32_t e = lut[w >> 25];
         const uint32_t lg = e & 31u;
-        const uint32_t gap = (e >> 15) + __builtin_amdgcn_ubfe(w, (e >> 5) & 31u, (e >> 10) & 31u);
         const uint32_t w2 = w << lg;                 // sign bit on top, level code below
         const uint32_t c = w2 << 1;
         const uint32_t sel = (c >> 29) | 0x0c0c0c00u;
         const uint32_t lj = __builtin_amdgcn_perm(0x07030603u, 0x01010101u, sel);    // code length
-        const uint32_t off = __builtin_amdgcn_perm(0x1a1e1b1eu, 0u, sel);            // where its last group sits
+        p31 += lg + 1u + lj;
+        words.pair_at(p31 >> 5, hi, lo);             // the next record's words
+        const uint32_t gap = gap_value(w, e);
+        const uint32_t off = __builtin_amdgcn_perm(0x1a1e1b1eu, 0u, sel);            // where the last group sits
         const uint32_t wd = __builtin_amdgcn_perm(0x04020302u, 0u, sel);             // and how wide it is
         const uint32_t j1 = __builtin_amdgcn_perm(0u, 0x01010101u, sel);             // the code "0"
         const uint32_t j = j1 | __builtin_amdgcn_ubfe(c, off, wd);
@@ -215,12 +224,10 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint3
         const uint32_t vh = (mh & 0x7fffffffu) | (w2 & 0x80000000u);
         const uint64_t vb = ((uint64_t)vh << 32) | (uint32_t)__double_as_longlong(mag);
         atomicAdd(tile_at0 + idx, __longlong_as_double((long long)vb));
-        pos += lg + 1u + lj;
         prev = (int)idx;
     }
-    bad |= pos != bit_hi;
+    bad |= p31 != end31;
 }
-
 
 // Where a tile lies.  Everything here is uniform over the workgroup.
 struct TileGeom {
@@ -260,7 +267,7 @@ __device__ __forceinline__ TileGeom tile_geom(const DecodeParams &P, uint32_t t)
     return G;
 }
 
-// What a thread loads for the stream whose words it helps to copy.
+// What a lane loads for the stream whose words it helps to copy.
 struct StreamRaw {
     uint64_t bo0, bo1;      // bit_off[b], bit_off[b + 1]
     uint32_t e0, e1;        // sync entries at the tile's first and one-past-last segment (partial tiles)
@@ -294,132 +301,95 @@ __device__ __forceinline__ StreamPart stream_part(const DecodeParams &P, const T
     return S;
 }
 
-// What a thread loads for the unit it parses.
+// What a lane loads for a unit.
 struct UnitRaw {
     uint64_t bo0, bo1;      // bit_off[b], bit_off[b + 1]
-    uint32_t e_lo, e_hi;    // sync entries that bound the segment (0 when not applicable)
+    uint32_t e_lo, e_hi;    // sync entries that bound the segment
     uint32_t e0, e1;        // sync entries that bound the tile (as in StreamRaw)
     float norm;
 };
 
 // A unit ready to parse.  kind: 0 = nothing to do, 1 = words staged in LDS, 2 = words in global memory.
 struct UnitPlan {
-    const uint32_t *gwords; // kind 2: first word needed
-    uint32_t glast;         // kind 2: highest readable word index
-    uint32_t stage_off;     // kind 1: first word in the staging area
+    uint64_t first_word;    // kind 2: first word needed, as an index into the worker's words[]
+    uint32_t nwords;        // kind 2: words needed
+    uint32_t stage_off;     // kind 1: first word in the staging buffer
     uint32_t bit_lo, bit_hi;// records to parse, relative to the first word needed
     uint32_t idx_hi;
     int forced;
-    int tile_lo;            // in-bucket index of the tile's first coordinate (negative for later buckets of a tile)
     float norm;
     uint32_t kind;
 };
 
-__global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
+// The same for a unit whose words are staged (or that has nothing to do), as it is handed from the preparing
+// wave to the parsing wave.  (Bit positions fit sixteen bits: a staging buffer holds 2^14 bits.)
+struct __align__(16) PackedPlan {
+    uint32_t bits;          // bit_lo | bit_hi << 16
+    uint32_t idx;           // idx_hi | (forced + 1) << 16
+    uint32_t where;         // stage_off | kind << 16
+    float norm;
+};
+
+__device__ __forceinline__ PackedPlan pack_plan(const UnitPlan &U)
+{
+    PackedPlan Q;
+    Q.bits = U.bit_lo | (U.bit_hi << 16);
+    Q.idx = U.idx_hi | ((uint32_t)(U.forced + 1) << 16);
+    Q.where = U.stage_off | (U.kind << 16);
+    Q.norm = U.norm;
+    return Q;
+}
+
+__global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams P)
 {
     __shared__ __align__(16) double tile[kTileCoords];
-    __shared__ uint32_t stage[kStageWords + 1];
-    __shared__ uint32_t lut[128];
+    // words at [1, kStageWords] of a buffer; the parser may read one word before and two after a stream's region
+    __shared__ uint32_t stage[2][kStageWords + 4];
+    __shared__ PackedPlan plans[kPlanned];
+    __shared__ uint16_t lut[128];
 
     const uint32_t tid = threadIdx.x;
-    const bool partial = !P.buckets_per_tile;                                        // tiles are parts of one bucket
-    const bool walk = partial && !P.sync_shift;                                      // no index: walk from the start
-    const uint32_t my_stream = tid >> P.lanes_shift;                                 // the stream this thread copies
-    const uint32_t my_lane = tid & ((1u << P.lanes_shift) - 1u);
+    const uint32_t lane = tid & (kWave - 1u);
+    const bool parser = tid < kWave;                  // first wave parses, second wave prepares
+    const bool partial = !P.buckets_per_tile;        // tiles are parts of one bucket
+    const bool walk = partial && !P.sync_shift;      // no index: every tile walks its bucket from the start
+    const uint64_t last_bucket = P.nb - 1u;
+    const double wscale = ldexp(1.0, -1 - (int)P.s);
 
     // Unit u of a tile is (bucket in tile bi, segment g, worker k), k fastest.
     auto unit_coords = [&](const TileGeom &G, uint32_t u, uint32_t &k, uint32_t &bi, uint32_t &g) {
-        const uint32_t segs = G.g1 - G.g0;
+        const uint32_t segs = max(G.g1 - G.g0, 1u);
         k = u % P.K;
         const uint32_t r = u / P.K;
         g = G.g0 + r % segs;
         bi = r / segs;
     };
-    // The worker of this thread's stream and of its first unit never changes from tile to tile, so the
-    // pointers to that worker's arrays are fetched once; a fetch per tile would put a dependent load (and a
-    // wait for everything in flight) in front of every metadata load.
-    const uint32_t sk = my_stream % P.K, sbi = my_stream / P.K;
-    const uint64_t *const s_bit_off = P.bit_off[sk];
-    const uint32_t *const s_words = P.words[sk];
-    const uint32_t *const s_sync = P.sync[sk];
-    const uint32_t uk = tid % P.K, ur = tid / P.K;
-    const uint32_t ubi = partial ? 0u : ur / P.nseg;        // multi-bucket tiles hold every segment of a bucket
-    const uint32_t ugr = partial ? ur : ur % P.nseg;        // segment, counted from the tile's first
-    const uint64_t *const u_bit_off = P.bit_off[uk];
-    const float *const u_norms = P.norms[uk];
-    const uint32_t *const u_sync = P.sync[uk];
-    // ---- loads (all independent of each other, nothing is waited for here)
-    auto load_stream = [&](const TileGeom &G) {
-        StreamRaw r{};
-        if (my_stream < G.nstreams && !walk) {
-            const uint64_t b = G.b0 + sbi;
-            r.bo0 = s_bit_off[b];
-            r.bo1 = s_bit_off[b + 1];
-            if (partial && P.sync_shift) {
-                const uint32_t *sy = s_sync + b * P.nsync;
-                if (G.g0 > 0u)
-                    r.e0 = sy[G.g0 - 1u];
-                if (G.g1 < P.nseg)
-                    r.e1 = sy[G.g1 - 1u];
-            }
-        }
-        return r;
-    };
-    auto load_unit_at = [&](const TileGeom &G, bool valid, uint32_t bi, uint32_t g, const uint64_t *bit_off,
-                            const float *norms, const uint32_t *sync) {
+    // Loads of a unit's metadata.  Nothing is predicated per lane: a lane without a unit, or a unit without a
+    // neighbouring sync entry, loads from a clamped index and ignores the value.
+    auto load_unit = [&](const TileGeom &G, uint32_t bi, uint32_t g, const uint64_t *bit_off, const float *norms,
+                         const uint32_t *sync) {
         UnitRaw r{};
-        if (valid) {
-            const uint64_t b = G.b0 + bi;
-            r.bo0 = bit_off[b];
-            r.bo1 = bit_off[b + 1];
-            r.norm = norms[b];
-            if (P.sync_shift) {
-                const uint32_t *sy = sync + b * P.nsync;
-                if (g > 0u)
-                    r.e_lo = sy[g - 1u];
-                if (g + 1u < P.nseg)
-                    r.e_hi = sy[g];
-                if (partial) {
-                    if (G.g0 > 0u)
-                        r.e0 = sy[G.g0 - 1u];
-                    if (G.g1 < P.nseg)
-                        r.e1 = sy[G.g1 - 1u];
-                }
+        const uint64_t b = min(G.b0 + bi, last_bucket);
+        r.bo0 = bit_off[b];
+        r.bo1 = bit_off[b + 1];
+        r.norm = norms[b];
+        if (P.sync_shift) {
+            const uint32_t *sy = sync + b * P.nsync;
+            const uint32_t gc = min(g, P.nsync);
+            r.e_lo = sy[max(gc, 1u) - 1u];
+            r.e_hi = sy[min(gc, P.nsync - 1u)];
+            if (partial) {
+                r.e0 = sy[max(G.g0, 1u) - 1u];
+                r.e1 = sy[min(G.g1, P.nsync) - 1u];
             }
         }
         return r;
     };
-    // the unit with the thread's own number
-    auto load_my_unit = [&](const TileGeom &G) {
-        return load_unit_at(G, tid < G.units, ubi, G.g0 + ugr, u_bit_off, u_norms, u_sync);
-    };
-    // ---- this thread's share of the copy of a tile's words: global -> registers, registers -> LDS
-    auto plan_words = [&](const TileGeom &G, const StreamRaw &r, const uint32_t *&src, uint32_t &cnt) {
-        cnt = 0;
-        src = s_words;
-        if (my_stream < G.nstreams && !walk) {
-            const StreamPart S = stream_part(P, G, r.bo0, r.bo1, r.e0, r.e1);
-            cnt = min(S.nwords, P.stream_cap);
-            src = s_words + S.first_word;
-        }
-    };
-    auto load_words = [&](const uint32_t *src, uint32_t cnt, uint32_t (&w)[kWordsPerThread]) {
-#pragma unroll
-        for (uint32_t i = 0; i < kWordsPerThread; ++i) {
-            const uint32_t wi = my_lane + (i << P.lanes_shift);
-            w[i] = wi < cnt ? src[wi] : 0u;
-        }
-    };
-    auto store_words = [&](const uint32_t (&w)[kWordsPerThread]) {
-        const uint32_t base = my_stream * P.stream_cap + my_lane;     // < kStageWords for every thread
-#pragma unroll
-        for (uint32_t i = 0; i < kWordsPerThread; ++i)
-            stage[base + (i << P.lanes_shift)] = w[i];
-    };
-    // ---- turn a unit's loaded metadata into what the parser needs
+    // Turn a unit's loaded metadata into what the parser needs.
     auto plan_unit = [&](const TileGeom &G, bool valid, uint32_t k, uint32_t bi, uint32_t g, const UnitRaw &m,
                          bool &bad) {
         UnitPlan U{};
+        U.forced = -1;
         if (!valid)
             return U;
         const uint64_t b = G.b0 + bi;
@@ -427,7 +397,6 @@ __global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
         const StreamPart S = stream_part(P, G, m.bo0, m.bo1, m.e0, m.e1);
         uint32_t bit_lo = 0, bit_hi = S.len, idx_lo = 0;
         U.idx_hi = nbk;
-        U.forced = -1;
         if (P.sync_shift) {
             idx_lo = g << P.sync_shift;
             U.idx_hi = min(nbk, (g + 1u) << P.sync_shift);
@@ -455,28 +424,39 @@ __global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
         U.bit_lo = bit_lo - S.bit0;
         U.bit_hi = bit_hi - S.bit0;
         U.norm = m.norm;
-        U.tile_lo = partial ? (int)G.in_lo : -(int)(bi * P.bucket);
         const uint32_t sidx = bi * P.K + k;
         if (S.nwords <= P.stream_cap && sidx < kMaxStreams) {
             U.kind = 1;
             U.stage_off = sidx * P.stream_cap;
         } else {                                  // did not fit in LDS: read the words from global memory
             U.kind = 2;
-            U.gwords = P.words[k] + S.first_word;     // (a per-lane fetch of the pointer: this path is rare)
-            U.glast = S.nwords - 1u;
+            U.first_word = S.first_word;
+            U.nwords = S.nwords;
         }
         return U;
     };
-    const double wscale = ldexp(1.0, -1 - (int)P.s);
-    auto parse_unit = [&](const UnitPlan &U, bool &bad) {
-        const double wnorm = (double)U.norm * wscale;
-        double *tile_at0 = tile - U.tile_lo;     // address of in-bucket index 0 (never dereferenced outside the tile)
-        if (U.kind == 1)
-            decode_unit_fast(StagedWords{stage + U.stage_off}, lut, U.bit_lo, U.bit_hi, U.forced, U.idx_hi, P.s + 1u,
-                             wnorm, tile_at0, bad);
-        else if (U.kind == 2)
-            decode_unit_fast(GlobalWords{U.gwords, U.glast}, lut, U.bit_lo, U.bit_hi, U.forced, U.idx_hi, P.s + 1u,
-                             wnorm, tile_at0, bad);
+    // address of in-bucket index 0 of bucket bi of the tile (never dereferenced outside the tile)
+    auto tile_origin = [&](const TileGeom &G, uint32_t bi) {
+        return partial ? tile - (int)G.in_lo : tile + bi * P.bucket;
+    };
+    auto parse_planned = [&](const TileGeom &G, uint32_t bi, const uint32_t *buf, const PackedPlan &Q, bool &bad) {
+        decode_unit_fast(StagedWords{buf + (Q.where & 0xFFFFu)}, lut, Q.bits & 0xFFFFu, Q.bits >> 16,
+                         (int)(Q.idx >> 16) - 1, Q.idx & 0xFFFFu, P.s + 1u, (double)Q.norm * wscale, tile_origin(G, bi),
+                         bad);
+    };
+    // Any unit, from scratch: units beyond the planned ones and units whose words were not staged.
+    auto slow_unit = [&](const TileGeom &G, const uint32_t *buf, uint32_t k, uint32_t bi, uint32_t g, bool report,
+                         bool &bad) {
+        const UnitRaw m = load_unit(G, bi, g, P.bit_off[k], P.norms[k], P.sync[k]);
+        bool plan_bad = false;
+        const UnitPlan X = plan_unit(G, true, k, bi, g, m, plan_bad);
+        if (report)                               // otherwise whoever planned this unit first has reported
+            bad |= plan_bad;
+        if (X.kind == 1)
+            parse_planned(G, bi, buf, pack_plan(X), bad);
+        else if (X.kind == 2)
+            decode_unit_fast(GlobalWords{P.words[k] + X.first_word, X.nwords - 1u}, lut, X.bit_lo, X.bit_hi, X.forced,
+                             X.idx_hi, P.s + 1u, (double)X.norm * wscale, tile_origin(G, bi), bad);
     };
     // Tiles of a large bucket without a sync index: every tile parses the bucket from its first record in
     // global memory and keeps what lands inside.
@@ -521,76 +501,151 @@ __global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
         }
     };
 
-    // ---- pipeline prologue
+    // ---- the preparing wave's constants: its stream, its two units (lane and lane + 64), their workers' arrays.
+    // A worker's pointers are fetched once: a fetch per tile would put a dependent load in front of every
+    // metadata load.
+    const uint32_t my_stream = lane >> P.lanes_shift;
+    const uint32_t my_sub = lane & ((1u << P.lanes_shift) - 1u);
+    const uint32_t sk = my_stream % P.K, sbi = my_stream / P.K;
+    const uint64_t *const s_bit_off = P.bit_off[sk];
+    const uint32_t *const s_words = P.words[sk];
+    const uint32_t *const s_sync = P.sync[sk];
+    uint32_t uk[2], ubi[2], ugr[2];
+#pragma unroll
+    for (uint32_t h = 0; h < 2u; ++h) {
+        const uint32_t u = lane + h * kWave;
+        uk[h] = u % P.K;
+        const uint32_t r = u / P.K;
+        ubi[h] = partial ? 0u : r / P.nseg;       // multi-bucket tiles hold every segment of a bucket
+        ugr[h] = partial ? r : r % P.nseg;        // segment, counted from the tile's first
+    }
+    const uint64_t *const u_bit_off = P.bit_off[uk[0]];
+    const float *const u_norms = P.norms[uk[0]];
+    const uint32_t *const u_sync = P.sync[uk[0]];
+    auto load_stream = [&](const TileGeom &G) {
+        StreamRaw r{};
+        if (walk)
+            return r;
+        const uint64_t b = min(G.b0 + sbi, last_bucket);
+        r.bo0 = s_bit_off[b];
+        r.bo1 = s_bit_off[b + 1];
+        if (partial && P.sync_shift) {
+            const uint32_t *sy = s_sync + b * P.nsync;
+            r.e0 = sy[max(G.g0, 1u) - 1u];
+            r.e1 = sy[min(G.g1, P.nsync) - 1u];
+        }
+        return r;
+    };
+    // Prepare a tile whose metadata has arrived: plans to LDS, words to the staging buffer `buf`.
+    auto prepare = [&](const TileGeom &G, const StreamRaw &sr, const UnitRaw &um, uint32_t *buf, bool &bad) {
+        // words: global -> registers
+        uint32_t cnt = 0;
+        const uint32_t *src = s_words;
+        if (my_stream < G.nstreams && !walk) {
+            const StreamPart S = stream_part(P, G, sr.bo0, sr.bo1, sr.e0, sr.e1);
+            cnt = min(S.nwords, P.stream_cap);
+            src = s_words + S.first_word;
+        }
+        uint32_t w[kWordsPerLane];
+#pragma unroll
+        for (uint32_t i = 0; i < kWordsPerLane; ++i) {
+            const uint32_t wi = my_sub + (i << P.lanes_shift);
+            const uint32_t *a = wi < cnt ? src + wi : P.flags;     // beyond the stream's part: any readable word
+            w[i] = *a;
+        }
+        // plans, while the words are in flight.  The metadata of a lane's first unit was requested a round ago; a
+        // tile with more units than lanes fetches the second one's here and waits (this wave has time to spare).
+        plans[lane] = pack_plan(plan_unit(G, lane < G.units, uk[0], ubi[0], G.g0 + ugr[0], um, bad));
+        if (G.units > kWave) {
+            const UnitRaw m2 = load_unit(G, ubi[1], G.g0 + ugr[1], P.bit_off[uk[1]], P.norms[uk[1]], P.sync[uk[1]]);
+            plans[lane + kWave] =
+                pack_plan(plan_unit(G, lane + kWave < G.units, uk[1], ubi[1], G.g0 + ugr[1], m2, bad));
+        }
+        // words: registers -> LDS
+        const uint32_t base = 1u + my_stream * P.stream_cap + my_sub;     // <= kStageWords for every lane
+#pragma unroll
+        for (uint32_t i = 0; i < kWordsPerLane; ++i)
+            buf[base + (i << P.lanes_shift)] = w[i];
+    };
+
+    // ---- prologue
     bool bad = false;
     const uint32_t stride = gridDim.x;
     uint32_t t = blockIdx.x;                    // < ntiles by the launch
     TileGeom G = tile_geom(P, t);
-    uint32_t words_next[kWordsPerThread];
-    UnitPlan U;
-    {
-        const StreamRaw sr = load_stream(G);
-        const UnitRaw um = load_my_unit(G);
-        const uint32_t *src;
-        uint32_t cnt;
-        plan_words(G, sr, src, cnt);
-        load_words(src, cnt, words_next);
-        U = plan_unit(G, tid < G.units, uk, ubi, G.g0 + ugr, um, bad);
+    StreamRaw sr{};                             // preparing wave: metadata of the tile after the next, in flight
+    UnitRaw um{};
+    if (parser) {
+        for (uint32_t i = lane; i < kTileCoords / 2u; i += kWave)
+            reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
+        lut[lane] = (uint16_t)gap_table_entry(lane);
+        lut[lane + kWave] = (uint16_t)gap_table_entry(lane + kWave);
+        if (lane < 8u)
+            stage[lane >> 2][(lane & 3u) ? kStageWords + (lane & 3u) : 0u] = 0u;    // the pads
+    } else {
+        sr = load_stream(G);
+        um = load_unit(G, ubi[0], G.g0 + ugr[0], u_bit_off, u_norms, u_sync);
+        prepare(G, sr, um, stage[0], bad);
+        if (t + stride < P.ntiles) {
+            const TileGeom G1 = tile_geom(P, t + stride);
+            sr = load_stream(G1);
+            um = load_unit(G1, ubi[0], G1.g0 + ugr[0], u_bit_off, u_norms, u_sync);
+        }
     }
-    // metadata of the tile after this one, in flight from here on
-    TileGeom Gn{};
-    StreamRaw sr_n{};
-    UnitRaw ur_n{};
-    if (t + stride < P.ntiles) {
-        Gn = tile_geom(P, t + stride);
-        sr_n = load_stream(Gn);
-        ur_n = load_my_unit(Gn);
+    __syncthreads();
+    PackedPlan Q[2] = {};
+    if (parser) {
+        Q[0] = plans[lane];
+        if (G.units > kWave)
+            Q[1] = plans[lane + kWave];
     }
-    for (uint32_t i = tid; i < kTileCoords / 2u; i += kDecodeWG)
-        reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
-    lut[tid] = gap_table_entry(tid);
-    if (tid == 0)
-        stage[kStageWords] = 0u;                 // the parser reads one word past the one it is in
-    store_words(words_next);
     __syncthreads();
 
-    for (;;) {
-        // ---- start the loads of the metadata of the tile after the next and the copy of the next tile's
-        // words, in this order and with every address computed first, so that nothing issued here has to be
-        // waited for before the parse below
-        const bool have_next = t + stride < P.ntiles;     // uniform
-        UnitPlan Un{};
-        const uint32_t *src_n = s_words;
-        uint32_t cnt_n = 0;
-        if (have_next) {
-            plan_words(Gn, sr_n, src_n, cnt_n);
-            Un = plan_unit(Gn, tid < Gn.units, uk, ubi, Gn.g0 + ugr, ur_n, bad);
-        }
-        TileGeom Gnn{};
-        const bool have_nn = have_next && t + stride < P.ntiles - stride;
-        if (have_nn) {
-            Gnn = tile_geom(P, t + 2u * stride);
-            sr_n = load_stream(Gnn);
-            ur_n = load_my_unit(Gnn);
-        }
-        if (have_next)
-            load_words(src_n, cnt_n, words_next);
-
-        // ---- parse this tile's units
-        if (walk) {
-            for (uint32_t u = tid; u < G.units; u += kDecodeWG)
-                walk_unit(G, u, bad);
-        } else {
-            parse_unit(U, bad);
-            for (uint32_t u = tid + kDecodeWG; u < G.units; u += kDecodeWG) {
-                uint32_t k, bi, g;
-                unit_coords(G, u, k, bi, g);
-                const UnitRaw m = load_unit_at(G, true, bi, g, P.bit_off[k], P.norms[k], P.sync[k]);
-                const UnitPlan X = plan_unit(G, true, k, bi, g, m, bad);
-                parse_unit(X, bad);
+    for (uint32_t cur = 0;; cur ^= 1u) {
+        const bool has1 = t + stride < P.ntiles;                        // uniform
+        const bool has2 = has1 && t + stride < P.ntiles - stride;
+        TileGeom G1{};
+        if (has1)
+            G1 = tile_geom(P, t + stride);
+        if (parser) {
+            // ---- parse this tile's units
+            const uint32_t *buf = stage[cur];
+            if (walk) {
+                for (uint32_t u = lane; u < G.units; u += kWave)
+                    walk_unit(G, u, bad);
+            } else {
+#pragma unroll
+                for (uint32_t h = 0; h < 2u; ++h) {
+                    if (h == 1u && G.units <= kWave)
+                        break;
+                    const uint32_t kind = Q[h].where >> 16;
+                    if (kind == 1u)
+                        parse_planned(G, ubi[h], buf, Q[h], bad);
+                    else if (kind == 2u)
+                        slow_unit(G, buf, uk[h], ubi[h], G.g0 + ugr[h], false, bad);
+                }
+                for (uint32_t u = lane + kPlanned; u < G.units; u += kWave) {
+                    uint32_t k, bi, g;
+                    unit_coords(G, u, k, bi, g);
+                    slow_unit(G, buf, k, bi, g, true, bad);
+                }
+            }
+        } else if (has1) {
+            // ---- prepare the next tile (its metadata was requested a round ago), request the metadata of the
+            // one after it
+            prepare(G1, sr, um, stage[cur ^ 1u], bad);
+            if (has2) {
+                const TileGeom G2 = tile_geom(P, t + 2u * stride);
+                sr = load_stream(G2);
+                um = load_unit(G2, ubi[0], G2.g0 + ugr[0], u_bit_off, u_norms, u_sync);
             }
         }
         __syncthreads();
+        if (parser && has1) {
+            Q[0] = plans[lane];
+            if (G1.units > kWave)
+                Q[1] = plans[lane + kWave];
+        }
 
         // ---- scale, round to fp32, write; leave the tile zeroed
         {
@@ -625,14 +680,11 @@ __global__ __launch_bounds__(kDecodeWG) void k_decode_accumulate(DecodeParams P)
                 o[i] = P.accumulate ? o[i] + r : r;
             }
         }
-        if (!have_next)
+        if (!has1)
             break;
-        store_words(words_next);                 // the stage is free: this tile's parse is over
         __syncthreads();
         t += stride;
-        G = Gn;
-        U = Un;
-        Gn = Gnn;
+        G = G1;
     }
     if (bad)
         atomicOr(P.flags, kFlagMalformed);
