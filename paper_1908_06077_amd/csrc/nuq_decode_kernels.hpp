@@ -346,6 +346,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     // words at [1, kStageWords] of a buffer; the parser may read one word before and two after a stream's region
     __shared__ uint32_t stage[2][kStageWords + 4];
     __shared__ PackedPlan plans[kPlanned];
+    __shared__ TileGeom next_geom;                // of the tile being prepared, for the wave that did not compute it
     __shared__ uint16_t lut[128];
 
     const uint32_t tid = threadIdx.x;
@@ -604,9 +605,6 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     for (uint32_t cur = 0;; cur ^= 1u) {
         const bool has1 = t + stride < P.ntiles;                        // uniform
         const bool has2 = has1 && t + stride < P.ntiles - stride;
-        TileGeom G1{};
-        if (has1)
-            G1 = tile_geom(P, t + stride);
         if (parser) {
             // ---- parse this tile's units
             const uint32_t *buf = stage[cur];
@@ -633,7 +631,10 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         } else if (has1) {
             // ---- prepare the next tile (its metadata was requested a round ago), request the metadata of the
             // one after it
-            prepare(G1, sr, um, stage[cur ^ 1u], bad);
+            const TileGeom GA = tile_geom(P, t + stride);
+            prepare(GA, sr, um, stage[cur ^ 1u], bad);
+            if (lane == 0)
+                next_geom = GA;
             if (has2) {
                 const TileGeom G2 = tile_geom(P, t + 2u * stride);
                 sr = load_stream(G2);
@@ -641,10 +642,22 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             }
         }
         __syncthreads();
-        if (parser && has1) {
-            Q[0] = plans[lane];
-            if (G1.units > kWave)
-                Q[1] = plans[lane + kWave];
+        TileGeom G1{};
+        if (has1) {
+            G1.b0 = uniform_u64(next_geom.b0);
+            G1.c_lo = uniform_u64(next_geom.c_lo);
+            G1.nbuck = uniform_u32(next_geom.nbuck);
+            G1.in_lo = uniform_u32(next_geom.in_lo);
+            G1.span = uniform_u32(next_geom.span);
+            G1.g0 = uniform_u32(next_geom.g0);
+            G1.g1 = uniform_u32(next_geom.g1);
+            G1.nstreams = uniform_u32(next_geom.nstreams);
+            G1.units = uniform_u32(next_geom.units);
+            if (parser) {
+                Q[0] = plans[lane];
+                if (G1.units > kWave)
+                    Q[1] = plans[lane + kWave];
+            }
         }
 
         // ---- scale, round to fp32, write; leave the tile zeroed
@@ -654,6 +667,31 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             const uint32_t span = G.span;
             const bool vec = (reinterpret_cast<uintptr_t>(o) & 15u) == 0;
             const uint32_t n4 = vec ? span >> 2 : 0u;
+            constexpr uint32_t kFull = kTileCoords / 4u / kDecodeWG;      // float4 stores per thread of a full tile
+            if (n4 == kTileCoords / 4u && !P.accumulate) {
+                // a full tile: LDS reads two at a time, so that their latencies overlap
+#pragma unroll
+                for (uint32_t r0 = 0; r0 < kFull; r0 += 2u) {
+                    double2 a[2], c[2];
+#pragma unroll
+                    for (uint32_t r = 0; r < 2u; ++r) {
+                        double2 *src = reinterpret_cast<double2 *>(tile) + 2u * (tid + (r0 + r) * kDecodeWG);
+                        a[r] = src[0];
+                        c[r] = src[1];
+                        src[0] = double2{0.0, 0.0};
+                        src[1] = double2{0.0, 0.0};
+                    }
+#pragma unroll
+                    for (uint32_t r = 0; r < 2u; ++r) {
+                        float4 v;
+                        v.x = (float)(sc * a[r].x);
+                        v.y = (float)(sc * a[r].y);
+                        v.z = (float)(sc * c[r].x);
+                        v.w = (float)(sc * c[r].y);
+                        reinterpret_cast<float4 *>(o)[tid + (r0 + r) * kDecodeWG] = v;
+                    }
+                }
+            } else
             for (uint32_t i = tid; i < n4; i += kDecodeWG) {
                 double2 *src = reinterpret_cast<double2 *>(tile) + 2u * i;
                 const double2 a = src[0], c = src[1];
@@ -674,7 +712,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
                 }
                 *dst = r;
             }
-            for (uint32_t i = (n4 << 2) + tid; i < span; i += kDecodeWG) {
+            for (uint32_t i = (n4 << 2) + tid; i < span; i += kDecodeWG) {      // (n4 = 0 without 16-byte alignment)
                 const float r = (float)(sc * tile[i]);
                 tile[i] = 0.0;
                 o[i] = P.accumulate ? o[i] + r : r;
