@@ -34,7 +34,11 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (BASELINE.json configs, 1-based)")
-    ap.add_argument("--sync-stride", type=int, default=512)
+    ap.add_argument("--sync-stride", type=int, default=None,
+                    help="decoder index stride in coordinates (0 = none); default 256, or 128 for buckets below 1024")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy before the timed region (a known-size reference "
+                         "for hardware-counter runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-worker-calls", action="store_true",
                     help="encode with K nuq_quantize_encode calls instead of one nuq_quantize_encode_batch")
@@ -58,7 +62,8 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     w = workloads.workload(args.config)
-    d, n, s, K, S = w.d, w.bucket, w.s, w.K, args.sync_stride
+    d, n, s, K = w.d, w.bucket, w.s, w.K
+    S = args.sync_stride if args.sync_stride is not None else (256 if n >= 1024 else 128)
     if n <= S:
         S = 0
     B = nuq.nuq_num_buckets(d, n)
@@ -93,6 +98,12 @@ def main():
         encode_all()
         nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -163,12 +174,13 @@ def main():
         "roofline": {"kernel": "k_encode (fused norms+quantize+ENCODE), one launch per %s"
                                % ("worker" if args.per_worker_calls else "step (all K workers)"),
                      "bound": "hbm", "achieved": round(enc_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(enc_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(enc_gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic("k_encode", args.config, S),
                      "bytes_per_launch": round(enc_launch_bytes), "launch_ms": round(enc_kernel_ms, 5),
                      "launches": len(enc_ms)},
         "roofline_decode": {"kernel": "k_decode_accumulate (DECODE + average of K messages)",
                             "bound": "hbm", "achieved": round(dec_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": round(dec_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                            "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
+                            "traffic": measured_traffic("k_decode_accumulate", args.config, S),
                             "bytes_per_launch": round(dec_alg), "launch_ms": round(dec_kernel_ms, 5),
                             "launches": len(dec_ms)},
     }
@@ -176,6 +188,20 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, grads, S)
     print(json.dumps(result))
+
+
+def measured_traffic(kernel, config, S):
+    """HBM bytes per launch of `kernel` from the hardware-counter runs recorded in profiles/hbm_traffic.json
+    (rocprofv3 FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size), or None if that file has no
+    entry for this workload.  The counters cannot be read from inside this process."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        return None
+    entry = table.get("config%d_stride%d" % (config, S), {}).get(kernel)
+    return None if entry is None else entry.get("bytes_per_launch")
 
 
 def cpu_baseline(w, grads, S):

@@ -143,7 +143,8 @@ int nuq_quantize_encode_batch(uint32_t K, const float *const *v, const uint64_t 
  * norms, bit_off, words, sync: HOST arrays of K device pointers (one message per
  * worker, all encoded with the same d, bucket, s, sync_stride); sync may be NULL or hold
  * NULLs when sync_stride == 0.  1 <= K <= NUQ_MAX_WORKERS; average with scale = 1/K.
- * The sum over workers is taken in fp32 in no fixed order.  out: d floats.
+ * The sum over workers is taken in fp64 (in no fixed order, which cannot change it unless the
+ * terms' exponents span more than 2^29), scaled in fp64 and rounded to fp32 once.  out: d floats.
  * A record that leaves its bucket's bit range or index range, or a level index outside
  * 1..s+1, raises NUQ_FLAG_MALFORMED and ends that bucket's decoding. */
 int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
