@@ -85,3 +85,49 @@ def check_average(msgs_np, d, n, s, scale, out_gpu: np.ndarray, prior=None):
         # (+ the fp32 subnormal grid, 2^-149 per element, for outputs below the smallest normal float)
         assert np.linalg.norm(got[sl] - want[sl]) <= 1e-6 * np.linalg.norm(want[sl]) + 2.0 ** -149 * np.sqrt(n)
     return want
+
+
+def batched_encode(vs, n, s, seeds, S):
+    """All workers in one launch, buffers sized like bench.py sizes them (a probe encode gives the lengths)."""
+    d, K = vs[0].numel(), len(vs)
+    B = nuq.nuq_num_buckets(d, n)
+    nsync = nuq.nuq_num_sync(n, S)
+    ws = torch.empty(nuq.nuq_encode_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=DEV)
+
+    def new_msg(nwords):
+        return nuq.Message(torch.empty(B, dtype=torch.float32, device=DEV),
+                           torch.empty(B + 1, dtype=torch.int64, device=DEV),
+                           torch.zeros(nwords, dtype=torch.int32, device=DEV),
+                           torch.empty(max(1, B * nsync), dtype=torch.int32, device=DEV))
+    probes = [new_msg(16) for _ in range(K)]
+    nuq.nuq_quantize_encode_batch(vs, n, s, seeds, S, probes, ws)
+    assert nuq.nuq_last_error_flags() & ~nuq.FLAG_CAPACITY == 0
+    msgs = [new_msg((int(p.bit_off[-1].item()) + 31) // 32 + 64) for p in probes]
+    del probes
+    nuq.nuq_quantize_encode_batch(vs, n, s, seeds, S, msgs, ws)
+    assert nuq.nuq_last_error_flags() == 0
+    return msgs
+
+
+def check_bucket_run(vs, msgs, out, n, s, seeds, S, scale, b_lo, b_hi):
+    """Buckets [b_lo, b_hi) of a large problem: every worker's message pieces bit-exact against the oracle run
+    on just those buckets (fed the GPU's norms), norms and the decoded average of the K workers to the bars."""
+    d = vs[0].numel()
+    c_lo, c_hi = b_lo * n, min(d, b_hi * n)
+    nsync = nuq.nuq_num_sync(n, S)
+    parts = []
+    for v, m, seed in zip(vs, msgs, seeds):
+        v_np = v[c_lo:c_hi].cpu().numpy()
+        norms = m.norms[b_lo:b_hi].cpu().numpy()
+        check_norms(v_np, n, norms)
+        q = oracle.quantize(v_np, n, s, seed, norms, b_lo)
+        bo, words, sync = oracle.encode(q, n, s, S)
+        got_bo = u64(m.bit_off[b_lo:b_hi + 1])
+        start = (int(got_bo[0]) + 31) // 32 * 32          # the run's first bucket starts on a word boundary
+        np.testing.assert_array_equal(got_bo[1:] - np.uint64(start), bo[1:])
+        got_words = u32(m.words[start // 32: start // 32 + words.size])
+        np.testing.assert_array_equal(got_words, words)
+        if sync.size:
+            np.testing.assert_array_equal(u32(m.sync[b_lo * nsync: b_hi * nsync]), sync)
+        parts.append((norms, bo, words))
+    check_average(parts, c_hi - c_lo, n, s, scale, out[c_lo:c_hi].cpu().numpy())

@@ -212,3 +212,35 @@ def test_full_size_configs_1_to_3(g):
         nuq.nuq_decode_accumulate(msgs, w.d, w.bucket, w.s, S, 1.0 / K, False, out)
         g.check_average(msgs_np, w.d, w.bucket, w.s, 1.0 / K, out.cpu().numpy())
         assert nuq.nuq_last_error_flags() == 0
+
+
+@pytest.mark.gpu
+def test_full_size_in_the_benchmark_configuration(g):
+    """BASELINE configs 3-5 at full size, launched the way bench.py launches them (all K workers in one encode
+    call, bench's sync stride, one decode call over the K messages).  Compared on sampled runs of buckets (the
+    first, the last with the short bucket, and seeded random ones), which the oracle computes one by one; global
+    structure (offsets non-decreasing, word-aligned starts accounted for, no error flags) checked everywhere."""
+    nuq = g.nuq
+    for cfg, nruns, run_len in ((3, 24, 4), (4, 12, 2), (5, 48, 32)):
+        w = workloads.workload(cfg)
+        n, s, K, d = w.bucket, w.s, w.K, w.d
+        S = 256 if n >= 1024 else 128
+        B = nuq.nuq_num_buckets(d, n)
+        print("cfg %d: generating %d x %d coordinates" % (cfg, K, d), flush=True)
+        vs = [workloads.generate(w, k, g.DEV) for k in range(K)]
+        seeds = [w.quant_seed(k) for k in range(K)]
+        msgs = g.batched_encode(vs, n, s, seeds, S)
+        out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+        nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
+        assert nuq.nuq_last_error_flags() == 0
+        for m in msgs:
+            bo = m.bit_off
+            assert int(bo[0].item()) == 0
+            assert bool((bo[1:] >= (bo[:-1] + 31) // 32 * 32).all())      # a bucket ends at or after its aligned start
+        rng = np.random.default_rng(cfg)
+        starts = {0, B - run_len} | {int(x) for x in rng.integers(0, B - run_len, size=nruns)}
+        for b_lo in sorted(starts):
+            g.check_bucket_run(vs, msgs, out, n, s, seeds, S, 1.0 / K, b_lo, b_lo + run_len)
+        print("cfg %d: %d runs of %d buckets bit-exact, averages within the bar" % (cfg, len(starts), run_len), flush=True)
+        del vs, msgs, out
+        torch.cuda.empty_cache()
