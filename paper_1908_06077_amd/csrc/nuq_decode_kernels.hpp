@@ -178,12 +178,18 @@ __device__ __forceinline__ uint32_t gap_value(uint32_t w, uint32_t e)
 //   idx_hi : a record at or above this index is a format error; smax = s + 1
 // Format violations set `bad`; nothing is ever added outside [0, idx_hi) of the bucket.
 //
-// One iteration per record.  The loop is arranged around its one carried dependency, the bit position: the
-// 32-bit window at the position comes from two adjacent words through one funnel shift (position + 31 is the
-// loop variable: its word index names the second word of the pair, its complement is the shift), one table
-// read gives the gap code's length, byte permutes on the first three bits of the level code (at most seven
-// bits: 0 | 1x0 | 101yy0 | 111yyy0) give its length, and the read of the next record's words is issued right
-// then, before the value of this record is worked out and added.
+// One iteration per record.  A lone wave issues an instruction every five cycles or so, a dependent one every
+// nine, and an LDS read takes ~64, so the loop is arranged around its one carried dependency, the bit position,
+// and software-pipelined by hand so that the two LDS reads on that chain are covered by work on the record
+// before:
+//   chain, first half : the 32-bit window at the position from two adjacent words through one funnel shift
+//                       (position + 31 is the loop variable: its word index names the second word of the pair,
+//                       its complement is the shift); the table read for the gap code is issued
+//   cover             : level and value of the previous record, its add into the tile
+//   chain, second half: gap code's length from the table entry, level code's length from byte permutes on
+//                       its first three bits (at most seven bits: 0 | 1x0 | 101yy0 | 111yyy0), next position,
+//                       the read of the next record's words is issued
+//   cover             : this record's gap value, index and index checks
 template <class Words>
 __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint16_t *lut, uint32_t bit_lo,
                                                  uint32_t bit_hi, int forced, uint32_t idx_hi, uint32_t smax,
@@ -191,41 +197,69 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
 {
     uint32_t p31 = bit_lo + 31u;
     const uint32_t end31 = bit_hi + 31u;
+    if (p31 >= end31) {
+        bad |= p31 != end31;
+        return;
+    }
     uint32_t hi, lo;
     words.pair_at(p31 >> 5, hi, lo);
     int prev = -1;
-    if (forced >= 0 && p31 < end31) {
-        const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, ~p31);
-        const uint32_t e = lut[w >> 25];
-        prev = forced - (int)gap_value(w, e);
-    }
-    while (p31 < end31) {
-        const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, ~p31);
-        const uint32_t e = lut[w >> 25];
+    // what the second cover step leaves for the first cover step of the next iteration
+    uint32_t idx, c, sel, w2;
+    uint32_t w, e;
+
+    auto chain_first = [&]() {
+        w = __builtin_amdgcn_alignbit(hi, lo, ~p31);
+        e = lut[w >> 25];
+    };
+    auto chain_second = [&]() {
         const uint32_t lg = e & 31u;
-        const uint32_t w2 = w << lg;                 // sign bit on top, level code below
-        const uint32_t c = w2 << 1;
-        const uint32_t sel = (c >> 29) | 0x0c0c0c00u;
-        const uint32_t lj = __builtin_amdgcn_perm(0x07030603u, 0x01010101u, sel);    // code length
+        w2 = w << lg;                            // sign bit on top, level code below
+        c = w2 << 1;
+        sel = (c >> 29) | 0x0c0c0c00u;
+        const uint32_t lj = __builtin_amdgcn_perm(0x07030603u, 0x01010101u, sel);    // level code's length
         p31 += lg + 1u + lj;
-        words.pair_at(p31 >> 5, hi, lo);             // the next record's words
+        words.pair_at(p31 >> 5, hi, lo);         // the next record's words
+    };
+    auto cover_index = [&]() {
         const uint32_t gap = gap_value(w, e);
+        uint32_t i = (uint32_t)(prev + (int)gap);
+        if (forced >= 0) {                       // entered through a sync entry: its index replaces the first gap
+            i = (uint32_t)forced;
+            forced = -1;
+        }
+        bad |= i >= idx_hi;
+        idx = min(i, idx_hi - 1u);
+        prev = (int)idx;
+    };
+    auto cover_value = [&]() {
         const uint32_t off = __builtin_amdgcn_perm(0x1a1e1b1eu, 0u, sel);            // where the last group sits
         const uint32_t wd = __builtin_amdgcn_perm(0x04020302u, 0u, sel);             // and how wide it is
         const uint32_t j1 = __builtin_amdgcn_perm(0u, 0x01010101u, sel);             // the code "0"
         const uint32_t j = j1 | __builtin_amdgcn_ubfe(c, off, wd);
         const uint32_t unterminated = __builtin_amdgcn_ubfe(c, (off - 1u) & 31u, 1u);   // a third group would follow
-        uint32_t idx = (uint32_t)(prev + (int)gap);
-        bad |= (idx >= idx_hi) | (j > smax) | (unterminated != 0u);
-        idx = min(idx, idx_hi - 1u);
+        bad |= (j > smax) | (unterminated != 0u);
         // ||v|| * l_j = (||v|| * 2^(-1-s)) * 2^j, exact in fp64; the sign goes into the top bit
         const double mag = ldexp(wnorm, (int)j);
         const uint32_t mh = (uint32_t)((uint64_t)__double_as_longlong(mag) >> 32);
         const uint32_t vh = (mh & 0x7fffffffu) | (w2 & 0x80000000u);
         const uint64_t vb = ((uint64_t)vh << 32) | (uint32_t)__double_as_longlong(mag);
         atomicAdd(tile_at0 + idx, __longlong_as_double((long long)vb));
-        prev = (int)idx;
+    };
+
+    chain_first();
+    chain_second();
+    cover_index();
+    while (p31 < end31) {
+        chain_first();
+        __builtin_amdgcn_sched_barrier(0);
+        cover_value();
+        __builtin_amdgcn_sched_barrier(0);
+        chain_second();
+        __builtin_amdgcn_sched_barrier(0);
+        cover_index();
     }
+    cover_value();
     bad |= p31 != end31;
 }
 
