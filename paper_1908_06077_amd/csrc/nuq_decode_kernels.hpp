@@ -207,6 +207,8 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
     // what the second cover step leaves for the first cover step of the next iteration
     uint32_t idx, c, sel, w2;
     uint32_t w, e;
+    // format checks are folded into three running values and tested once after the loop
+    uint32_t max_idx = 0, max_j = 0, any_unterminated = 0;
 
     auto chain_first = [&]() {
         w = __builtin_amdgcn_alignbit(hi, lo, ~p31);
@@ -228,7 +230,7 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
             i = (uint32_t)forced;
             forced = -1;
         }
-        bad |= i >= idx_hi;
+        max_idx = max(max_idx, i);
         idx = min(i, idx_hi - 1u);
         prev = (int)idx;
     };
@@ -237,8 +239,10 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
         const uint32_t wd = __builtin_amdgcn_perm(0x04020302u, 0u, sel);             // and how wide it is
         const uint32_t j1 = __builtin_amdgcn_perm(0u, 0x01010101u, sel);             // the code "0"
         const uint32_t j = j1 | __builtin_amdgcn_ubfe(c, off, wd);
-        const uint32_t unterminated = __builtin_amdgcn_ubfe(c, (off - 1u) & 31u, 1u);   // a third group would follow
-        bad |= (j > smax) | (unterminated != 0u);
+        // the bit below the last group is 1 if a third group follows (the field offset is taken modulo 32: for
+        // the code "0", off = 0 and the bit looked at is the code's own leading 0)
+        any_unterminated |= __builtin_amdgcn_ubfe(c, off - 1u, 1u);
+        max_j = max(max_j, j);
         // ||v|| * l_j = (||v|| * 2^(-1-s)) * 2^j, exact in fp64; the sign goes into the top bit
         const double mag = ldexp(wnorm, (int)j);
         const uint32_t mh = (uint32_t)((uint64_t)__double_as_longlong(mag) >> 32);
@@ -260,7 +264,7 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
         cover_index();
     }
     cover_value();
-    bad |= p31 != end31;
+    bad |= (p31 != end31) | (max_idx >= idx_hi) | (max_j > smax) | (any_unterminated != 0u);
 }
 
 // Where a tile lies.  Everything here is uniform over the workgroup.
