@@ -178,22 +178,34 @@ __device__ __forceinline__ uint32_t gap_value(uint32_t w, uint32_t e)
 //   idx_hi : a record at or above this index is a format error; smax = s + 1
 // Format violations set `bad`; nothing is ever added outside [0, idx_hi) of the bucket.
 //
+// ---- level code table ------------------------------------------------------------------
+// Entry for the seven stream bits p after a record's sign bit (MSB first): bits 0..3 = length of the level code
+// plus one (the sign bit), bits 4..7 = the level index 1..15, or 0 if no code ends within the seven bits (a third
+// group would follow: a level index above 15, which no message holds).
+__device__ __forceinline__ uint32_t level_table_entry(uint32_t p)
+{
+    uint32_t N, len;
+    erc_decode_bits(p << 25, N, len);
+    return len <= 7u ? (len + 1u) | (N << 4) : 8u;
+}
+
 // One iteration per record.  A lone wave issues an instruction every five cycles or so, a dependent one every
-// nine, and an LDS read takes ~64, so the loop is arranged around its one carried dependency, the bit position,
-// and software-pipelined by hand so that the two LDS reads on that chain are covered by work on the record
-// before:
-//   chain, first half : the 32-bit window at the position from two adjacent words through one funnel shift
-//                       (position + 31 is the loop variable: its word index names the second word of the pair,
-//                       its complement is the shift); the table read for the gap code is issued
-//   cover             : level and value of the previous record, its add into the tile
-//   chain, second half: gap code's length from the table entry, level code's length from byte permutes on
-//                       its first three bits (at most seven bits: 0 | 1x0 | 101yy0 | 111yyy0), next position,
-//                       the read of the next record's words is issued
-//   cover             : this record's gap value, index and index checks
+// nine, and an LDS read takes ~64, so the loop is kept short (format checks are folded into two running values
+// and tested once) and is arranged around its one carried dependency, the bit position.  It is
+// software-pipelined by hand so that the two LDS reads on that chain are covered by other work:
+//   chain 1 : the 32-bit window at the position from two adjacent words through one funnel shift (position + 31
+//             is the loop variable: its word index names the second word of the pair, its complement is the
+//             shift); the table read for the gap code is issued
+//   cover   : level and value of the previous record (its level table entry was requested an iteration ago), its
+//             add into the tile
+//   chain 2 : gap code's length from the entry; the level table read is issued (nothing on the chain waits for
+//             it); level code's length from a byte permute on its first three bits (the code is at most seven
+//             bits: 0 | 1x0 | 101yy0 | 111yyy0); next position; the read of the next record's words is issued
+//   cover   : this record's gap value and index, loop control
 template <class Words>
-__device__ __forceinline__ void decode_unit_fast(const Words &words, const uint16_t *lut, uint32_t bit_lo,
-                                                 uint32_t bit_hi, int forced, uint32_t idx_hi, uint32_t smax,
-                                                 double wnorm, double *tile_at0, bool &bad)
+__device__ __forceinline__ void decode_unit_fast(const Words &words, const uint16_t *lut, const uint8_t *lut_level,
+                                                 uint32_t bit_lo, uint32_t bit_hi, int forced, uint32_t idx_hi,
+                                                 uint32_t smax, double wnorm, double *tile_at0, bool &bad)
 {
     uint32_t p31 = bit_lo + 31u;
     const uint32_t end31 = bit_hi + 31u;
@@ -204,45 +216,38 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
     uint32_t hi, lo;
     words.pair_at(p31 >> 5, hi, lo);
     int prev = -1;
-    // what the second cover step leaves for the first cover step of the next iteration
-    uint32_t idx, c, sel, w2;
-    uint32_t w, e;
-    // format checks are folded into three running values and tested once after the loop
-    uint32_t max_idx = 0, max_j = 0, any_unterminated = 0;
+    uint32_t w, e;                  // window, gap entry
+    uint32_t idx, w2, e2;           // what an iteration leaves for the first cover step of the next: index, window
+                                    // at the sign bit, level entry (in flight)
+    uint32_t last_i = 0;            // index before clamping: non-decreasing, so the last one tells if any was too big
+    uint32_t max_jm1 = 0;           // largest level index minus one, as unsigned: a level 0 shows as 2^32 - 1
 
-    auto chain_first = [&]() {
+    auto chain1 = [&]() {
         w = __builtin_amdgcn_alignbit(hi, lo, ~p31);
         e = lut[w >> 25];
     };
-    auto chain_second = [&]() {
+    auto chain2 = [&]() {
         const uint32_t lg = e & 31u;
         w2 = w << lg;                            // sign bit on top, level code below
-        c = w2 << 1;
-        sel = (c >> 29) | 0x0c0c0c00u;
-        const uint32_t lj = __builtin_amdgcn_perm(0x07030603u, 0x01010101u, sel);    // level code's length
-        p31 += lg + 1u + lj;
+        e2 = lut_level[(w2 >> 24) & 0x7fu];
+        const uint32_t sel = ((w2 >> 28) & 7u) | 0x0c0c0c00u;
+        const uint32_t lj1 = __builtin_amdgcn_perm(0x08040704u, 0x02020202u, sel);   // sign bit + level code
+        p31 += lg + lj1;
         words.pair_at(p31 >> 5, hi, lo);         // the next record's words
     };
     auto cover_index = [&]() {
-        const uint32_t gap = gap_value(w, e);
-        uint32_t i = (uint32_t)(prev + (int)gap);
+        uint32_t i = (uint32_t)(prev + (int)gap_value(w, e));
         if (forced >= 0) {                       // entered through a sync entry: its index replaces the first gap
             i = (uint32_t)forced;
             forced = -1;
         }
-        max_idx = max(max_idx, i);
+        last_i = i;
         idx = min(i, idx_hi - 1u);
         prev = (int)idx;
     };
     auto cover_value = [&]() {
-        const uint32_t off = __builtin_amdgcn_perm(0x1a1e1b1eu, 0u, sel);            // where the last group sits
-        const uint32_t wd = __builtin_amdgcn_perm(0x04020302u, 0u, sel);             // and how wide it is
-        const uint32_t j1 = __builtin_amdgcn_perm(0u, 0x01010101u, sel);             // the code "0"
-        const uint32_t j = j1 | __builtin_amdgcn_ubfe(c, off, wd);
-        // the bit below the last group is 1 if a third group follows (the field offset is taken modulo 32: for
-        // the code "0", off = 0 and the bit looked at is the code's own leading 0)
-        any_unterminated |= __builtin_amdgcn_ubfe(c, off - 1u, 1u);
-        max_j = max(max_j, j);
+        const uint32_t j = e2 >> 4;
+        max_jm1 = max(max_jm1, j - 1u);
         // ||v|| * l_j = (||v|| * 2^(-1-s)) * 2^j, exact in fp64; the sign goes into the top bit
         const double mag = ldexp(wnorm, (int)j);
         const uint32_t mh = (uint32_t)((uint64_t)__double_as_longlong(mag) >> 32);
@@ -251,20 +256,20 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
         atomicAdd(tile_at0 + idx, __longlong_as_double((long long)vb));
     };
 
-    chain_first();
-    chain_second();
+    chain1();
+    chain2();
     cover_index();
     while (p31 < end31) {
-        chain_first();
+        chain1();
         __builtin_amdgcn_sched_barrier(0);
         cover_value();
         __builtin_amdgcn_sched_barrier(0);
-        chain_second();
+        chain2();
         __builtin_amdgcn_sched_barrier(0);
         cover_index();
     }
     cover_value();
-    bad |= (p31 != end31) | (max_idx >= idx_hi) | (max_j > smax) | (any_unterminated != 0u);
+    bad |= (p31 != end31) | (last_i >= idx_hi) | (max_jm1 >= smax);
 }
 
 // Where a tile lies.  Everything here is uniform over the workgroup.
@@ -386,6 +391,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     __shared__ PackedPlan plans[kPlanned];
     __shared__ TileGeom next_geom;                // of the tile being prepared, for the wave that did not compute it
     __shared__ uint16_t lut[128];
+    __shared__ uint8_t lut_level[128];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & (kWave - 1u);
@@ -479,7 +485,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         return partial ? tile - (int)G.in_lo : tile + bi * P.bucket;
     };
     auto parse_planned = [&](const TileGeom &G, uint32_t bi, const uint32_t *buf, const PackedPlan &Q, bool &bad) {
-        decode_unit_fast(StagedWords{buf + (Q.where & 0xFFFFu)}, lut, Q.bits & 0xFFFFu, Q.bits >> 16,
+        decode_unit_fast(StagedWords{buf + (Q.where & 0xFFFFu)}, lut, lut_level, Q.bits & 0xFFFFu, Q.bits >> 16,
                          (int)(Q.idx >> 16) - 1, Q.idx & 0xFFFFu, P.s + 1u, (double)Q.norm * wscale, tile_origin(G, bi),
                          bad);
     };
@@ -494,7 +500,8 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         if (X.kind == 1)
             parse_planned(G, bi, buf, pack_plan(X), bad);
         else if (X.kind == 2)
-            decode_unit_fast(GlobalWords{P.words[k] + X.first_word, X.nwords - 1u}, lut, X.bit_lo, X.bit_hi, X.forced,
+            decode_unit_fast(GlobalWords{P.words[k] + X.first_word, X.nwords - 1u}, lut, lut_level, X.bit_lo, X.bit_hi,
+                             X.forced,
                              X.idx_hi, P.s + 1u, (double)X.norm * wscale, tile_origin(G, bi), bad);
     };
     // Tiles of a large bucket without a sync index: every tile parses the bucket from its first record in
@@ -619,6 +626,8 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
         lut[lane] = (uint16_t)gap_table_entry(lane);
         lut[lane + kWave] = (uint16_t)gap_table_entry(lane + kWave);
+        lut_level[lane] = (uint8_t)level_table_entry(lane);
+        lut_level[lane + kWave] = (uint8_t)level_table_entry(lane + kWave);
         if (lane < 8u)
             stage[lane >> 2][(lane & 3u) ? kStageWords + (lane & 3u) : 0u] = 0u;    // the pads
     } else {
