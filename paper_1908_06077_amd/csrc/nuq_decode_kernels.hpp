@@ -141,6 +141,7 @@ struct StagedWords {
     const uint32_t *p;
     __device__ __forceinline__ void pair_at(uint32_t q, uint32_t &hi, uint32_t &lo) const
     {
+        asm volatile("" : "+v"(q));     // keeps "shift right by 5, then shift-left-and-add" from becoming three operations
         hi = p[q];
         lo = p[q + 1u];
     }
@@ -179,14 +180,13 @@ __device__ __forceinline__ uint32_t gap_value(uint32_t w, uint32_t e)
 // Format violations set `bad`; nothing is ever added outside [0, idx_hi) of the bucket.
 //
 // ---- level code table ------------------------------------------------------------------
-// Entry for the seven stream bits p after a record's sign bit (MSB first): bits 0..3 = length of the level code
-// plus one (the sign bit), bits 4..7 = the level index 1..15, or 0 if no code ends within the seven bits (a third
-// group would follow: a level index above 15, which no message holds).
+// Entry for the seven stream bits p after a record's sign bit (MSB first): the level index 1..15, or 0 if no code
+// ends within the seven bits (a third group would follow: a level index above 15, which no message holds).
 __device__ __forceinline__ uint32_t level_table_entry(uint32_t p)
 {
     uint32_t N, len;
     erc_decode_bits(p << 25, N, len);
-    return len <= 7u ? (len + 1u) | (N << 4) : 8u;
+    return len <= 7u ? N : 0u;
 }
 
 // One iteration per record.  A lone wave issues an instruction every five cycles or so, a dependent one every
@@ -246,7 +246,7 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
         prev = (int)idx;
     };
     auto cover_value = [&]() {
-        const uint32_t j = e2 >> 4;
+        const uint32_t j = e2;
         max_jm1 = max(max_jm1, j - 1u);
         // ||v|| * l_j = (||v|| * 2^(-1-s)) * 2^j, exact in fp64; the sign goes into the top bit
         const double mag = ldexp(wnorm, (int)j);
