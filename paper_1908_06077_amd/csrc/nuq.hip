@@ -188,7 +188,9 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
         constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
         using G = TeamGeom<TEAM>;
         P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
-        P.lds_words = team_lds_words(P.rows, TEAM, slot_words, nsync);
+        P.rec_cap = team_rec_cap(bucket);
+        P.out_cap = team_out_cap(slot_words);
+        P.lds_words = team_lds_words(P.rows, TEAM, P.rec_cap, P.out_cap, nsync);
         const size_t lds_bytes = (size_t)P.lds_words * 4 * G::kTeamsPerWG + 256 * 4;   // + the code table
         if (lds_bytes > 160 * 1024)
             return (int)NUQ_EINVAL;

@@ -42,6 +42,8 @@ struct EncodeParams {
     uint32_t slot_words;   // staging words per bucket
     uint32_t rows;         // ceil(bucket / (4*TEAM))
     uint32_t lds_words;    // LDS words per team
+    uint32_t rec_cap;      // nonzeros of a bucket whose indices fit the team's LDS list
+    uint32_t out_cap;      // words of a bucket's bit string that fit the team's LDS buffer
     uint64_t nb_stride;    // nb rounded up to a multiple of 4: stride between workers in lens
     uint32_t *lens;        // [K * nb_stride] payload bits per bucket, worker-major
     uint32_t *staging;     // [K * nb * slot_words]
@@ -221,6 +223,13 @@ __device__ __forceinline__ uint32_t erc_lookup(const uint32_t *erc_lut, uint32_t
     return erc_code(N, len);
 }
 
+// LDS is what bounds the number of buckets in flight on a CU, and a bucket's worst case (every coordinate
+// nonzero at the longest level code) is four to ten times what gradients produce.  So the team's index list and
+// bit-string buffer hold `rec_cap` nonzeros and `out_cap` words, sized for the usual case, and a bucket that
+// exceeds one of them takes a slower way around it:
+//   nonzeros fit, bits fit  : compacted index list, balanced record runs, bit string assembled in LDS
+//   nonzeros fit, bits don't: the same, but records are OR-ed into the (zeroed) staging slot in global memory
+//   nonzeros don't fit      : every thread codes the records of its own chunk, into the staging slot
 template <int TEAM>
 __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const EncodeWorker &W, bool active, uint64_t b,
                                                 const uint32_t *qb32, uint32_t *out, uint16_t *rec,
@@ -242,47 +251,74 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     }
     uint32_t nnz;
     uint32_t rank = team_exclusive_sum<TEAM>((uint32_t)__popcll((unsigned long long)nz), scratch, nnz);
-    {
+    const bool listed = nnz <= P.rec_cap;          // uniform over the team
+    int before_chunk = -1;                         // last nonzero before this thread's chunk (unlisted buckets)
+    if (listed) {
         uint64_t m = nz;
         while (m) {
             const int k = __ffsll((unsigned long long)m) - 1;
             m &= m - 1;
             rec[rank++] = (uint16_t)(base + (uint32_t)k);
         }
+    } else {
+        const int last = nz ? (int)base + 63 - __clzll((long long)nz) : -1;
+        before_chunk = team_exclusive_max<TEAM>(last, -1, reinterpret_cast<int *>(scratch + 16));
     }
     __syncthreads();
 
-    // (2) lengths of this thread's run of records
+    // The records this thread codes, in index order: f(index, previous nonzero's index, level|sign byte).
     const uint32_t per = (nnz + TEAM - 1u) / TEAM;
     const uint32_t r0 = min(tid * per, nnz), r1 = min(r0 + per, nnz);
-    uint32_t bits = 0;
-    {
-        int p = r0 ? (int)rec[r0 - 1u] : -1;
-        for (uint32_t r = r0; r < r1; ++r) {
-            const int e = (int)rec[r];
-            uint32_t lg, lj;
-            erc_lookup(erc_lut, (uint32_t)(e - p), lg);
-            erc_lookup(erc_lut, qbytes[e] & 0x7fu, lj);
-            bits += lg + 1u + lj;
-            p = e;
+    auto for_my_records = [&](auto &&f) {
+        if (listed) {
+            int p = r0 ? (int)rec[r0 - 1u] : -1;
+            for (uint32_t r = r0; r < r1; ++r) {
+                const int e = (int)rec[r];
+                f(e, p, (uint32_t)qbytes[e]);
+                p = e;
+            }
+        } else {
+            int p = before_chunk;
+            uint64_t m = nz;
+            while (m) {
+                const int e = (int)base + __ffsll((unsigned long long)m) - 1;
+                m &= m - 1;
+                f(e, p, (uint32_t)qbytes[e]);
+                p = e;
+            }
         }
-    }
+    };
+
+    // (2) lengths of this thread's records
+    uint32_t bits = 0;
+    for_my_records([&](int e, int p, uint32_t code) {
+        uint32_t lg, lj;
+        erc_lookup(erc_lut, (uint32_t)(e - p), lg);
+        erc_lookup(erc_lut, code & 0x7fu, lj);
+        bits += lg + 1u + lj;
+    });
     uint32_t total;
-    const uint32_t off0 = team_exclusive_sum<TEAM>(bits, scratch + 16, total);
+    const uint32_t off0 = team_exclusive_sum<TEAM>(bits, scratch + 32, total);
     const uint32_t nwords = (total + 31u) >> 5;
-    for (uint32_t i = tid; i < nwords; i += TEAM)
-        out[i] = 0u;
+    const bool in_lds = listed && nwords <= P.out_cap;           // uniform over the team
+    const uint64_t gb = (uint64_t)blockIdx.y * P.nb + b;         // bucket index over the whole batch
+    uint32_t *slot = P.staging + (active ? gb : 0) * P.slot_words;
+    if (in_lds) {
+        for (uint32_t i = tid; i < nwords; i += TEAM)
+            out[i] = 0u;
+    } else if (active) {
+        for (uint32_t i = tid; i < nwords; i += TEAM)
+            slot[i] = 0u;
+        __threadfence();       // the zeros are in place before any record is OR-ed over them
+    }
     for (uint32_t i = tid; i < P.nsync; i += TEAM)
         sync_l[i] = total | kSyncEmpty;   // "no record at or after this boundary" until one is found
     __syncthreads();
 
     // (3) emit
     {
-        int p = r0 ? (int)rec[r0 - 1u] : -1;
         uint32_t t = off0;
-        for (uint32_t r = r0; r < r1; ++r) {
-            const int e = (int)rec[r];
-            const uint32_t code = qbytes[e];
+        auto emit = [&](uint32_t *dst, int e, int p, uint32_t code) {
             uint32_t lg, lj;
             const uint32_t cg = erc_lookup(erc_lut, (uint32_t)(e - p), lg);
             const uint32_t cj = erc_lookup(erc_lut, code & 0x7fu, lj);
@@ -290,9 +326,9 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
             const uint32_t bitsrec = (cg << (1u + lj)) | ((code >> 7) << lj) | cj;
             const uint32_t wi = t >> 5, bo = t & 31u;
             const uint64_t sh = (uint64_t)bitsrec << (64u - bo - len);
-            atomicOr(&out[wi], (uint32_t)(sh >> 32));
+            atomicOr(&dst[wi], (uint32_t)(sh >> 32));
             if ((uint32_t)sh)
-                atomicOr(&out[wi + 1u], (uint32_t)sh);
+                atomicOr(&dst[wi + 1u], (uint32_t)sh);
             if (P.sync_shift) {
                 // this record is the first one at or after every segment boundary in (p, e]
                 const int g_hi = e >> P.sync_shift;
@@ -300,15 +336,17 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
                     sync_l[g - 1] = g == g_hi ? (t | ((uint32_t)(e - (g << P.sync_shift)) << 21)) : (t | kSyncEmpty);
             }
             t += len;
-            p = e;
-        }
+        };
+        if (in_lds)
+            for_my_records([&](int e, int p, uint32_t code) { emit(out, e, p, code); });
+        else if (active)
+            for_my_records([&](int e, int p, uint32_t code) { emit(slot, e, p, code); });
     }
     __syncthreads();
     if (active) {
-        const uint64_t gb = (uint64_t)blockIdx.y * P.nb + b;   // bucket index over the whole batch
-        uint32_t *slot = P.staging + gb * P.slot_words;
-        for (uint32_t i = tid; i < nwords; i += TEAM)
-            slot[i] = out[i];
+        if (in_lds)
+            for (uint32_t i = tid; i < nwords; i += TEAM)
+                slot[i] = out[i];
         uint32_t *sg = W.sync + b * P.nsync;
         for (uint32_t i = tid; i < P.nsync; i += TEAM)
             sg[i] = sync_l[i];
@@ -317,13 +355,26 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     }
 }
 
-// LDS carve-up per team (in 32-bit words): [qb32: rows*TEAM][rec: rows*TEAM*2 (u16 per coordinate)]
-// [out: slot_words + 1][sync: nsync][scratch: 64 (16 unused, 16 uints, 16 doubles)]; the
-// workgroup's 256-entry code table follows the last team.
-__host__ __device__ inline uint32_t team_lds_words(uint32_t rows, uint32_t team, uint32_t slot_words,
+// What a team's LDS holds of a bucket's nonzero list and bit string: everything for small buckets, a quarter
+// of the worst case for large ones (about four times what a Gaussian gradient produces).
+__host__ __device__ inline uint32_t team_rec_cap(uint32_t bucket)
+{
+    const uint32_t quarter = bucket / 4u;
+    return bucket <= 1024u ? bucket : (quarter > 1024u ? quarter : 1024u);
+}
+__host__ __device__ inline uint32_t team_out_cap(uint32_t slot_words)
+{
+    const uint32_t quarter = slot_words / 4u;
+    return slot_words <= 256u ? slot_words : (quarter > 256u ? quarter : 256u);
+}
+
+// LDS carve-up per team (in 32-bit words): [qb32: rows*TEAM][rec: rec_cap/2 (u16 per listed nonzero)]
+// [out: out_cap + 1][sync: nsync][scratch: 64 (16 uints, 16 ints, 16 uints, 8 doubles)]; the workgroup's
+// 256-entry code table follows the last team.
+__host__ __device__ inline uint32_t team_lds_words(uint32_t rows, uint32_t team, uint32_t rec_cap, uint32_t out_cap,
                                                    uint32_t nsync)
 {
-    uint32_t w = rows * team * 3u + slot_words + 1u + nsync;
+    uint32_t w = rows * team + (rec_cap + 1u) / 2u + out_cap + 1u + nsync;
     w = (w + 1u) & ~1u;   // keep the scratch 8-byte aligned
     return w + 64u;
 }
@@ -339,8 +390,8 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
     uint32_t *lds = smem + team * P.lds_words;
     uint32_t *qb32 = lds;
     uint16_t *rec = reinterpret_cast<uint16_t *>(qb32 + P.rows * TEAM);
-    uint32_t *out = qb32 + P.rows * TEAM * 3u;
-    uint32_t *sync_l = out + P.slot_words + 1u;
+    uint32_t *out = qb32 + P.rows * TEAM + (P.rec_cap + 1u) / 2u;
+    uint32_t *sync_l = out + P.out_cap + 1u;
     uint32_t *scratch = lds + P.lds_words - 64u;
     uint32_t *erc_lut = smem + TeamGeom<TEAM>::kTeamsPerWG * P.lds_words;
     if (threadIdx.x < 256u) {

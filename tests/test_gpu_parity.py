@@ -215,6 +215,49 @@ def test_full_size_configs_1_to_3(g):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("n,s,S", [(8192, 3, 256), (16384, 7, 512), (32768, 3, 1024), (2048, 14, 128), (512, 3, 128)])
+def test_encode_of_dense_buckets(g, n, s, S):
+    """Buckets far denser than gradients produce: more nonzeros than the encoder's LDS index list holds, or a bit
+    string longer than its LDS buffer (these buckets take the encoder's slower paths), next to ordinary ones.
+    Level|sign bytes are crafted and go through nuq_encode; the message must equal the oracle's and decode back."""
+    nuq = g.nuq
+    rng = np.random.default_rng(n + s)
+    nb = 7
+    d = nb * n - 5
+    q = np.zeros(d, dtype=np.uint8)
+
+    def fill(b, density, top_heavy):
+        lo, hi = b * n, min(d, (b + 1) * n)
+        m = rng.random(hi - lo) < density
+        lev = np.full(hi - lo, s + 1, dtype=np.uint8) if top_heavy else rng.integers(1, s + 2, size=hi - lo, dtype=np.uint8)
+        sign = (rng.random(hi - lo) < 0.5).astype(np.uint8) << 7
+        q[lo:hi] = np.where(m, lev | sign, 0)
+    fill(0, 1.0, True)       # every coordinate at the top level: the worst case
+    fill(1, 0.05, False)     # ordinary
+    fill(2, 0.26, True)      # a few more nonzeros than the list holds (large buckets)
+    fill(3, 0.24, True)      # the list holds them, the bit string is too long for the buffer
+    fill(4, 0.0, False)      # empty
+    fill(5, 0.6, False)
+    fill(6, 1.0, False)      # short last bucket, full
+    qd = torch.from_numpy(q).to(g.DEV)
+    m = g.alloc_message(d, n, s, S)
+    nuq.nuq_encode(qd, n, s, S, m.bit_off, m.words, m.sync if nuq.nuq_num_sync(n, S) else None, g.workspace(d, n, s))
+    assert nuq.nuq_last_error_flags() == 0
+    bo, words, sync = oracle.encode(q, n, s, S)
+    np.testing.assert_array_equal(g.u64(m.bit_off), bo)
+    np.testing.assert_array_equal(g.u32(m.words)[: words.size], words)
+    assert not g.u32(m.words)[words.size:].any()
+    if sync.size:
+        np.testing.assert_array_equal(g.u32(m.sync)[: sync.size], sync)
+    norms_np = (10.0 ** rng.uniform(-3, 3, size=nb)).astype(np.float32)
+    m.norms.copy_(torch.from_numpy(norms_np))
+    out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_decode_accumulate([m], d, n, s, S, 1.0, False, out)
+    assert nuq.nuq_last_error_flags() == 0
+    g.check_average([(norms_np, bo, words)], d, n, s, 1.0, out.cpu().numpy())
+
+
+@pytest.mark.gpu
 def test_full_size_in_the_benchmark_configuration(g):
     """BASELINE configs 3-5 at full size, launched the way bench.py launches them (all K workers in one encode
     call, bench's sync stride, one decode call over the K messages).  Compared on sampled runs of buckets (the
