@@ -191,7 +191,7 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
         P.rec_cap = team_rec_cap(bucket);
         P.out_cap = team_out_cap(slot_words);
         P.lds_words = team_lds_words(P.rows, TEAM, P.rec_cap, P.out_cap, nsync);
-        const size_t lds_bytes = (size_t)P.lds_words * 4 * G::kTeamsPerWG + 256 * 4;   // + the code table
+        const size_t lds_bytes = (size_t)P.lds_words * 4 * G::kTeamsPerWG + 2 * 256 * 4;   // + the two code tables
         if (lds_bytes > 160 * 1024)
             return (int)NUQ_EINVAL;
         auto kern = k_encode<TEAM, VPT, MODE>;

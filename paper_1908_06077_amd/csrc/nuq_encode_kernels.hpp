@@ -212,6 +212,51 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P
 // and sums their lengths; a second prefix sum gives every run its bit offset; (3) the same
 // runs are walked again to OR the record bits into `out`.
 
+// Code table for N < 256, built at compile time: code (right-aligned) | length << 16; entry 0 repeats entry 1.
+// A workgroup copies it to LDS once instead of computing it.
+struct ErcTable {
+    uint32_t v[256];
+};
+constexpr uint32_t bit_width_c(uint32_t x)
+{
+    uint32_t w = 0;
+    while (x) {
+        ++w;
+        x >>= 1;
+    }
+    return w;
+}
+constexpr ErcTable make_erc_table()
+{
+    ErcTable t{};
+    for (uint32_t i = 0; i < 256u; ++i) {
+        const uint32_t N = i ? i : 1u;
+        // Alg. 2: groups binary(N), binary(bits(N) - 1), ... while the value is at least 2, last computed first, one 0
+        uint32_t code = 0, len = 0;
+        for (uint32_t g = N; g >= 2u; g = bit_width_c(g) - 1u) {
+            code |= g << len;
+            len += bit_width_c(g);
+        }
+        t.v[i] = (code << 1) | ((len + 1u) << 16);
+    }
+    return t;
+}
+__device__ const ErcTable kErcTable = make_erc_table();
+
+// Table for the tail of a record, indexed by the level|sign byte (level in bits 0..6, 1..15; sign in bit 7): the
+// sign bit followed by the level's code, right-aligned, | their length << 16.
+constexpr ErcTable make_tail_table()
+{
+    const ErcTable erc = make_erc_table();
+    ErcTable t{};
+    for (uint32_t i = 0; i < 256u; ++i) {
+        const uint32_t e = erc.v[i & 15u], code = e & 0xffffu, len = e >> 16;
+        t.v[i] = ((i >> 7) << len) | code | ((len + 1u) << 16);
+    }
+    return t;
+}
+__device__ const ErcTable kTailTable = make_tail_table();
+
 // erc_lut[N] for N < 256: code (right-aligned) | length << 16.
 __device__ __forceinline__ uint32_t erc_lookup(const uint32_t *erc_lut, uint32_t N, uint32_t &len)
 {
@@ -221,6 +266,20 @@ __device__ __forceinline__ uint32_t erc_lookup(const uint32_t *erc_lut, uint32_t
         return e & 0xffffu;
     }
     return erc_code(N, len);
+}
+
+// Orders a team's LDS traffic between the phases of the coding pass.  A team of one wave needs no hardware barrier
+// (its lanes run in lockstep and its LDS operations complete in order), only the wait and a fence for the
+// compiler; the teams of a workgroup are independent of each other.
+template <int TEAM>
+__device__ __forceinline__ void team_barrier()
+{
+    if constexpr (TEAM > kWave) {
+        __syncthreads();
+    } else {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 // LDS is what bounds the number of buckets in flight on a CU, and a bucket's worst case (every coordinate
@@ -233,7 +292,8 @@ __device__ __forceinline__ uint32_t erc_lookup(const uint32_t *erc_lut, uint32_t
 template <int TEAM>
 __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const EncodeWorker &W, bool active, uint64_t b,
                                                 const uint32_t *qb32, uint32_t *out, uint16_t *rec,
-                                                const uint32_t *erc_lut, uint32_t *sync_l, uint32_t *scratch)
+                                                const uint32_t *erc_lut, const uint32_t *tail_lut, uint32_t *sync_l,
+                                                uint32_t *scratch)
 {
     const uint32_t tid = threadIdx.x % TEAM;
     const uint32_t rows = P.rows;
@@ -264,7 +324,7 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
         const int last = nz ? (int)base + 63 - __clzll((long long)nz) : -1;
         before_chunk = team_exclusive_max<TEAM>(last, -1, reinterpret_cast<int *>(scratch + 16));
     }
-    __syncthreads();
+    team_barrier<TEAM>();
 
     // The records this thread codes, in index order: f(index, previous nonzero's index, level|sign byte).
     const uint32_t per = (nnz + TEAM - 1u) / TEAM;
@@ -289,14 +349,50 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
         }
     };
 
-    // (2) lengths of this thread's records
+    // A record's bits (right-aligned) and length: ERC(gap), then sign and ERC(level) from the tail table.
+    auto make_record = [&](int e, int p, uint32_t byte, uint32_t &len) {
+        uint32_t lg;
+        const uint32_t cg = erc_lookup(erc_lut, (uint32_t)(e - p), lg);
+        const uint32_t tl = tail_lut[byte];
+        len = lg + (tl >> 16);
+        return (cg << (tl >> 16)) | (tl & 0xffffu);
+    };
+
+    // (2) lengths of this thread's records.  The first kKept records of a run from the list stay in registers
+    // for the third pass (a run is nnz / TEAM records: two or three for gradients).
+    constexpr uint32_t kKept = 4;
+    uint32_t kept_bits[kKept], kept_len[kKept];
+    int kept_e[kKept];
     uint32_t bits = 0;
-    for_my_records([&](int e, int p, uint32_t code) {
-        uint32_t lg, lj;
-        erc_lookup(erc_lut, (uint32_t)(e - p), lg);
-        erc_lookup(erc_lut, code & 0x7fu, lj);
-        bits += lg + 1u + lj;
-    });
+    if (listed) {
+        int p = r0 ? (int)rec[r0 - 1u] : -1;
+#pragma unroll
+        for (uint32_t i = 0; i < kKept; ++i) {
+            kept_len[i] = 0;
+            kept_bits[i] = 0;
+            kept_e[i] = p;
+            if (r0 + i < r1) {
+                const int e = (int)rec[r0 + i];
+                kept_bits[i] = make_record(e, p, (uint32_t)qbytes[e], kept_len[i]);
+                kept_e[i] = e;
+                bits += kept_len[i];
+                p = e;
+            }
+        }
+        for (uint32_t r = r0 + kKept; r < r1; ++r) {
+            const int e = (int)rec[r];
+            uint32_t len;
+            make_record(e, p, (uint32_t)qbytes[e], len);
+            bits += len;
+            p = e;
+        }
+    } else {
+        for_my_records([&](int e, int p, uint32_t byte) {
+            uint32_t len;
+            make_record(e, p, byte, len);
+            bits += len;
+        });
+    }
     uint32_t total;
     const uint32_t off0 = team_exclusive_sum<TEAM>(bits, scratch + 32, total);
     const uint32_t nwords = (total + 31u) >> 5;
@@ -313,17 +409,12 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     }
     for (uint32_t i = tid; i < P.nsync; i += TEAM)
         sync_l[i] = total | kSyncEmpty;   // "no record at or after this boundary" until one is found
-    __syncthreads();
+    team_barrier<TEAM>();
 
     // (3) emit
     {
         uint32_t t = off0;
-        auto emit = [&](uint32_t *dst, int e, int p, uint32_t code) {
-            uint32_t lg, lj;
-            const uint32_t cg = erc_lookup(erc_lut, (uint32_t)(e - p), lg);
-            const uint32_t cj = erc_lookup(erc_lut, code & 0x7fu, lj);
-            const uint32_t len = lg + 1u + lj;
-            const uint32_t bitsrec = (cg << (1u + lj)) | ((code >> 7) << lj) | cj;
+        auto emit = [&](uint32_t *dst, int e, int p, uint32_t bitsrec, uint32_t len) {
             const uint32_t wi = t >> 5, bo = t & 31u;
             const uint64_t sh = (uint64_t)bitsrec << (64u - bo - len);
             atomicOr(&dst[wi], (uint32_t)(sh >> 32));
@@ -337,12 +428,36 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
             }
             t += len;
         };
+        auto emit_all = [&](uint32_t *dst) {
+            if (listed) {
+                int p = r0 ? (int)rec[r0 - 1u] : -1;
+#pragma unroll
+                for (uint32_t i = 0; i < kKept; ++i) {
+                    if (kept_len[i])
+                        emit(dst, kept_e[i], p, kept_bits[i], kept_len[i]);
+                    p = kept_e[i];
+                }
+                for (uint32_t r = r0 + kKept; r < r1; ++r) {
+                    const int e = (int)rec[r];
+                    uint32_t len;
+                    const uint32_t bitsrec = make_record(e, p, (uint32_t)qbytes[e], len);
+                    emit(dst, e, p, bitsrec, len);
+                    p = e;
+                }
+            } else {
+                for_my_records([&](int e, int p, uint32_t byte) {
+                    uint32_t len;
+                    const uint32_t bitsrec = make_record(e, p, byte, len);
+                    emit(dst, e, p, bitsrec, len);
+                });
+            }
+        };
         if (in_lds)
-            for_my_records([&](int e, int p, uint32_t code) { emit(out, e, p, code); });
+            emit_all(out);
         else if (active)
-            for_my_records([&](int e, int p, uint32_t code) { emit(slot, e, p, code); });
+            emit_all(slot);
     }
-    __syncthreads();
+    team_barrier<TEAM>();
     if (active) {
         if (in_lds)
             for (uint32_t i = tid; i < nwords; i += TEAM)
@@ -370,7 +485,7 @@ __host__ __device__ inline uint32_t team_out_cap(uint32_t slot_words)
 
 // LDS carve-up per team (in 32-bit words): [qb32: rows*TEAM][rec: rec_cap/2 (u16 per listed nonzero)]
 // [out: out_cap + 1][sync: nsync][scratch: 64 (16 uints, 16 ints, 16 uints, 8 doubles)]; the workgroup's
-// 256-entry code table follows the last team.
+// two 256-entry code tables follow the last team.
 __host__ __device__ inline uint32_t team_lds_words(uint32_t rows, uint32_t team, uint32_t rec_cap, uint32_t out_cap,
                                                    uint32_t nsync)
 {
@@ -394,10 +509,10 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
     uint32_t *sync_l = out + P.out_cap + 1u;
     uint32_t *scratch = lds + P.lds_words - 64u;
     uint32_t *erc_lut = smem + TeamGeom<TEAM>::kTeamsPerWG * P.lds_words;
+    uint32_t *tail_lut = erc_lut + 256;
     if (threadIdx.x < 256u) {
-        uint32_t len;
-        const uint32_t code = erc_code(threadIdx.x ? threadIdx.x : 1u, len);
-        erc_lut[threadIdx.x] = code | (len << 16);
+        erc_lut[threadIdx.x] = kErcTable.v[threadIdx.x];
+        tail_lut[threadIdx.x] = kTailTable.v[threadIdx.x];
     }
 
     const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + team;
@@ -462,7 +577,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
         }
     }
     __syncthreads();
-    encode_from_lds<TEAM>(P, W, active, b, qb32, out, rec, erc_lut, sync_l, scratch);
+    encode_from_lds<TEAM>(P, W, active, b, qb32, out, rec, erc_lut, tail_lut, sync_l, scratch);
 }
 
 // ------------------------------------------------- offsets and gather of the slots
