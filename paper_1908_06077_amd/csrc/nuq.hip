@@ -117,8 +117,8 @@ Workspace carve(void *base, uint32_t K, uint64_t nb, uint32_t slot_words)
 template <class F>
 int dispatch_team(uint32_t bucket, F &&f)
 {
-    if (bucket <= 512)
-        return f(std::integral_constant<int, 64>{}, std::integral_constant<int, 2>{});
+    if (bucket <= 512)   // four buckets per wave
+        return f(std::integral_constant<int, 16>{}, std::integral_constant<int, 8>{});
     if (bucket <= 2048)
         return f(std::integral_constant<int, 64>{}, std::integral_constant<int, 8>{});
     if (bucket <= 8192)

@@ -156,9 +156,33 @@ __device__ __forceinline__ bool erc_decode_window(uint32_t &win, int &avail, uin
 
 // ------------------------------------------------------- team reductions / scans
 //
-// TEAM threads (64, 256 or 1024) own one bucket.  A workgroup holds max(256, TEAM) threads,
-// i.e. 4 one-wave teams or a single multi-wave team.  Multi-wave variants use a small LDS
-// scratch and __syncthreads(); every thread of the workgroup must call them.
+// TEAM threads (16, 64, 256 or 1024) own one bucket.  A workgroup holds max(256, TEAM) threads,
+// i.e. 16 teams of a quarter wave (a DPP row) each, 4 one-wave teams or a single multi-wave team.
+// Multi-wave variants use a small LDS scratch and __syncthreads(); every thread of the workgroup must
+// call them.  A quarter-wave team serves small buckets: the per-bucket work that a wave does once
+// (norm reduction, scale, hash key, scans) then serves four buckets at a time.
+constexpr int kRow = 16;   // lanes of a DPP row
+
+// A value that is the same in every thread of a team, as a scalar when the team is at least a wave.
+template <int TEAM>
+__device__ __forceinline__ uint32_t team_uniform_u32(uint32_t x)
+{
+    if constexpr (TEAM >= 64)
+        return (uint32_t)__builtin_amdgcn_readfirstlane((int)x);
+    else
+        return x;
+}
+template <int TEAM>
+__device__ __forceinline__ float team_uniform_f32(float x)
+{
+    return u2f(team_uniform_u32<TEAM>(f2u(x)));
+}
+
+// The value lane 15 of each DPP row holds, in every lane of that row.
+__device__ __forceinline__ uint32_t row_last_u32(uint32_t x)
+{
+    return (uint32_t)__shfl((int)x, (int)((threadIdx.x & (kWave - 1)) | (kRow - 1)), kWave);
+}
 
 // Value of a wave-uniform quantity as a scalar (lets the compiler keep what derives from it in
 // scalar registers and branch on it without touching the exec mask).
@@ -197,9 +221,32 @@ __device__ __forceinline__ double wave_sum_f64(double x)
     return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
 }
 
+// Sum of x over each row of 16 lanes, returned in every lane of the row: four row shifts leave the total in the
+// row's last lane (the same summation order for every bucket), which is then handed to the others.
+__device__ __forceinline__ double row_sum_f64(double x)
+{
+    auto step = [](double v, auto ctrl) {
+        const uint64_t b = (uint64_t)__double_as_longlong(v);
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, decltype(ctrl)::value, 0xf, 0xf, true);
+        const uint32_t hi =
+            (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), decltype(ctrl)::value, 0xf, 0xf, true);
+        return v + __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+    };
+    using std::integral_constant;
+    x = step(x, integral_constant<int, 0x111>{});
+    x = step(x, integral_constant<int, 0x112>{});
+    x = step(x, integral_constant<int, 0x114>{});
+    x = step(x, integral_constant<int, 0x118>{});
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = row_last_u32((uint32_t)b), hi = row_last_u32((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
 template <int TEAM>
 __device__ __forceinline__ double team_sum_f64(double x, double *scratch /* TEAM/64 doubles */)
 {
+    if constexpr (TEAM == kRow)
+        return row_sum_f64(x);
     x = wave_sum_f64(x);
     if constexpr (TEAM > kWave) {
         constexpr int NW = TEAM / kWave;
@@ -235,6 +282,15 @@ template <int TEAM>
 __device__ __forceinline__ uint32_t team_exclusive_sum(uint32_t v, uint32_t *scratch /* TEAM/64 */,
                                                        uint32_t &total)
 {
+    if constexpr (TEAM == kRow) {
+        uint32_t inc = v;
+        inc += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)inc, 0x111, 0xf, 0xf, true);   // row_shr:1
+        inc += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)inc, 0x112, 0xf, 0xf, true);   // row_shr:2
+        inc += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)inc, 0x114, 0xf, 0xf, true);   // row_shr:4
+        inc += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)inc, 0x118, 0xf, 0xf, true);   // row_shr:8
+        total = row_last_u32(inc);
+        return inc - v;
+    }
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t inc = wave_inclusive_sum(v);
     if constexpr (TEAM == kWave) {
@@ -263,6 +319,18 @@ __device__ __forceinline__ uint32_t team_exclusive_sum(uint32_t v, uint32_t *scr
 template <int TEAM>
 __device__ __forceinline__ int team_exclusive_max(int v, int ident, int *scratch /* TEAM/64 */)
 {
+    if constexpr (TEAM == kRow) {
+        const int l = threadIdx.x & (kRow - 1);
+        int inc = v;
+#pragma unroll
+        for (int off = 1; off < kRow; off <<= 1) {
+            const int t = __shfl_up(inc, off, kRow);
+            if (l >= off)
+                inc = max(inc, t);
+        }
+        const int exc = __shfl_up(inc, 1, kRow);
+        return l == 0 ? ident : exc;
+    }
     const int lane = threadIdx.x & (kWave - 1);
     int inc = v;
 #pragma unroll

@@ -165,7 +165,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P
 {
     const EncodeWorker &W = Wk.w[blockIdx.y];
     const uint32_t tid = threadIdx.x % TEAM;
-    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + uniform_u32(threadIdx.x / TEAM);
+    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + team_uniform_u32<TEAM>(threadIdx.x / TEAM);
     if (b >= P.nb)
         return;
     const uint64_t base = b * P.bucket;
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize(EncodeParams P
     uint8_t *qb = W.q_out + base;
     const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
     const bool qaligned = (reinterpret_cast<uintptr_t>(qb) & 3u) == 0;
-    const BucketScale B = make_scale(uniform_f32(W.norms_in[b]), (int)P.s);
+    const BucketScale B = make_scale(team_uniform_f32<TEAM>(W.norms_in[b]), (int)P.s);
     const BucketKey key = bucket_key(W.seed, b);
 #pragma unroll 1
     for (uint32_t i = 0; i < P.rows; ++i) {
@@ -501,7 +501,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
     extern __shared__ __align__(16) uint32_t smem[];
     const EncodeWorker &W = Wk.w[blockIdx.y];
     const uint32_t tid = threadIdx.x % TEAM;
-    const uint32_t team = uniform_u32(threadIdx.x / TEAM);   // a wave never straddles teams
+    const uint32_t team = team_uniform_u32<TEAM>(threadIdx.x / TEAM);   // a scalar unless a wave holds four teams
     uint32_t *lds = smem + team * P.lds_words;
     uint32_t *qb32 = lds;
     uint16_t *rec = reinterpret_cast<uint16_t *>(qb32 + P.rows * TEAM);
@@ -534,7 +534,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
                 x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
         }
         auto row = [&](int i) { return x[i]; };
-        const float nrm = uniform_f32(team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32)));
+        const float nrm = team_uniform_f32<TEAM>(team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32)));
         const bool finite = nrm < __builtin_huge_valf();   // false for NaN too
         if (active && tid == 0) {
             W.norms_out[b] = nrm;
