@@ -258,6 +258,50 @@ def test_encode_of_dense_buckets(g, n, s, S):
 
 
 @pytest.mark.gpu
+def test_encode_and_decode_replayed_from_a_hip_graph(g):
+    """The whole step (batched encode of K workers, decode + average) captured into a HIP graph and replayed
+    several times with eager work in between: every replay must reproduce the eager messages and output."""
+    nuq = g.nuq
+    d, n, s, S, K = 200_000, 8192, 3, 256, 4
+    rng = np.random.default_rng(7)
+    vs = [torch.from_numpy((rng.standard_normal(d) * 0.01).astype(np.float32)).to(g.DEV) for _ in range(K)]
+    seeds = [11 + k for k in range(K)]
+    msgs = g.batched_encode(vs, n, s, seeds, S)                  # eager reference (also warms everything up)
+    out_ref = torch.empty(d, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out_ref)
+    ref = [(m.bit_off.clone(), m.words.clone(), m.sync.clone(), m.norms.clone()) for m in msgs]
+
+    B = nuq.nuq_num_buckets(d, n)
+    ws = torch.empty(nuq.nuq_encode_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=g.DEV)
+    gm = [nuq.Message(torch.empty_like(m.norms), torch.empty_like(m.bit_off), torch.zeros_like(m.words),
+                      torch.empty_like(m.sync)) for m in msgs]
+    out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            nuq.nuq_quantize_encode_batch(vs, n, s, seeds, S, gm, ws)
+            nuq.nuq_decode_accumulate(gm, d, n, s, S, 1.0 / K, False, out)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for m in gm:                      # eager work between replays: scrub the outputs
+            m.bit_off.fill_(-1)
+            m.words.zero_()
+            m.sync.fill_(0x55)
+            m.norms.fill_(-1.0)
+        out.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for m, (bo, words, sync, norms) in zip(gm, ref):
+            assert torch.equal(m.bit_off, bo) and torch.equal(m.words, words) and torch.equal(m.sync, sync)
+            assert torch.equal(m.norms, norms)
+        assert torch.equal(out, out_ref), rep
+    assert nuq.nuq_last_error_flags() == 0
+
+
+@pytest.mark.gpu
 def test_full_size_in_the_benchmark_configuration(g):
     """BASELINE configs 3-5 at full size, launched the way bench.py launches them (all K workers in one encode
     call, bench's sync stride, one decode call over the K messages).  Compared on sampled runs of buckets (the
