@@ -434,10 +434,10 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
     const uint32_t resident = decode_resident_workgroups();
     if (!resident)
         return NUQ_EHIP;
-    // every workgroup walks the same number of tiles (one fewer for some): the fewest rounds the resident
-    // workgroups need, then the fewest workgroups that still finish in that many rounds
-    const uint32_t rounds = (P.ntiles + resident - 1) / resident;
-    const uint32_t grid = (P.ntiles + rounds - 1) / rounds;
+    // Every resident workgroup slot is used.  Workgroups walk tiles with stride `grid`, so the first
+    // ntiles mod grid of them get one tile more than the rest: those are the workgroups that arrive first on their
+    // CUs, whose parsing waves are the oldest on their SIMDs and run faster than the later ones.
+    const uint32_t grid = P.ntiles < resident ? P.ntiles : resident;
     ScopedTiming timing(NUQ_T_DECODE, static_cast<hipStream_t>(stream));
     hipLaunchKernelGGL(k_decode_accumulate, dim3(grid), dim3(kDecodeWG), 0, static_cast<hipStream_t>(stream), P);
     return check_launch();

@@ -13,9 +13,9 @@
 // memory (offsets and sync entries first, then the words they point to) and on bookkeeping.  So
 // a workgroup is persistent, walks a strided sequence of tiles, and its two waves have
 // different jobs: the first parses tile t while the second prepares tile t+1 -- works out
-// which words each unit needs, copies them into the other half of a double-buffered staging
-// area, leaves a four-word plan per unit in LDS -- and has the metadata loads of tile t+2 in
-// flight.  Both waves then write tile t out and clear it.  The critical path of a tile is its
+// which words each unit needs, fetches them into registers, leaves a three-word plan per unit
+// in LDS -- and has the metadata loads of tile t+2 in flight.  When the parse is over the
+// fetched words go to the LDS staging area and both waves write tile t out and clear it.  The critical path of a tile is its
 // parse and its write-out.
 #pragma once
 #include "nuq_device.hpp"
@@ -365,11 +365,12 @@ struct UnitPlan {
 };
 
 // The same for a unit whose words are staged (or that has nothing to do), as it is handed from the preparing
-// wave to the parsing wave.  (Bit positions fit sixteen bits: a staging buffer holds 2^14 bits.)
-struct __align__(16) PackedPlan {
+// wave to the parsing wave, in three words (every byte of LDS counts here: an eighth workgroup fits a CU only
+// below 20480 bytes each).  Bit positions fit sixteen bits: the staging area holds 2^14 bits; the parser works
+// out idx_hi itself.
+struct PackedPlan {
     uint32_t bits;          // bit_lo | bit_hi << 16
-    uint32_t idx;           // idx_hi | (forced + 1) << 16
-    uint32_t where;         // stage_off | kind << 16
+    uint32_t where;         // stage_off | kind << 12 | (forced + 1) << 16
     float norm;
 };
 
@@ -377,8 +378,7 @@ __device__ __forceinline__ PackedPlan pack_plan(const UnitPlan &U)
 {
     PackedPlan Q;
     Q.bits = U.bit_lo | (U.bit_hi << 16);
-    Q.idx = U.idx_hi | ((uint32_t)(U.forced + 1) << 16);
-    Q.where = U.stage_off | (U.kind << 16);
+    Q.where = U.stage_off | (U.kind << 12) | ((uint32_t)(U.forced + 1) << 16);
     Q.norm = U.norm;
     return Q;
 }
@@ -386,8 +386,8 @@ __device__ __forceinline__ PackedPlan pack_plan(const UnitPlan &U)
 __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams P)
 {
     __shared__ __align__(16) double tile[kTileCoords];
-    // words at [1, kStageWords] of a buffer; the parser may read one word before and two after a stream's region
-    __shared__ uint32_t stage[2][kStageWords + 4];
+    // words at [1, kStageWords]; the parser may read one word before and two after a stream's region
+    __shared__ uint32_t stage[kStageWords + 4];
     __shared__ PackedPlan plans[kPlanned];
     __shared__ TileGeom next_geom;                // of the tile being prepared, for the wave that did not compute it
     __shared__ uint16_t lut[128];
@@ -484,10 +484,13 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     auto tile_origin = [&](const TileGeom &G, uint32_t bi) {
         return partial ? tile - (int)G.in_lo : tile + bi * P.bucket;
     };
-    auto parse_planned = [&](const TileGeom &G, uint32_t bi, const uint32_t *buf, const PackedPlan &Q, bool &bad) {
-        decode_unit_fast(StagedWords{buf + (Q.where & 0xFFFFu)}, lut, lut_level, Q.bits & 0xFFFFu, Q.bits >> 16,
-                         (int)(Q.idx >> 16) - 1, Q.idx & 0xFFFFu, P.s + 1u, (double)Q.norm * wscale, tile_origin(G, bi),
-                         bad);
+    const uint32_t last_len = (uint32_t)(P.d - last_bucket * P.bucket);     // coordinates of the last bucket
+    auto parse_planned = [&](const TileGeom &G, uint32_t bi, uint32_t g, const uint32_t *buf, const PackedPlan &Q,
+                             bool &bad) {
+        const uint32_t nbk = G.b0 + bi == last_bucket ? last_len : P.bucket;
+        const uint32_t idx_hi = P.sync_shift ? min(nbk, (g + 1u) << P.sync_shift) : nbk;
+        decode_unit_fast(StagedWords{buf + (Q.where & 0xFFFu)}, lut, lut_level, Q.bits & 0xFFFFu, Q.bits >> 16,
+                         (int)(Q.where >> 16) - 1, idx_hi, P.s + 1u, (double)Q.norm * wscale, tile_origin(G, bi), bad);
     };
     // Any unit, from scratch: units beyond the planned ones and units whose words were not staged.
     auto slow_unit = [&](const TileGeom &G, const uint32_t *buf, uint32_t k, uint32_t bi, uint32_t g, bool report,
@@ -498,7 +501,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         if (report)                               // otherwise whoever planned this unit first has reported
             bad |= plan_bad;
         if (X.kind == 1)
-            parse_planned(G, bi, buf, pack_plan(X), bad);
+            parse_planned(G, bi, g, buf, pack_plan(X), bad);
         else if (X.kind == 2)
             decode_unit_fast(GlobalWords{P.words[k] + X.first_word, X.nwords - 1u}, lut, lut_level, X.bit_lo, X.bit_hi,
                              X.forced,
@@ -547,15 +550,12 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         }
     };
 
-    // ---- the preparing wave's constants: its stream, its two units (lane and lane + 64), their workers' arrays.
-    // A worker's pointers are fetched once: a fetch per tile would put a dependent load in front of every
-    // metadata load.
+    // ---- the preparing wave's constants: its stream and its two units (lane and lane + 64).  The pointers to
+    // their workers' arrays are fetched from the kernel arguments every round rather than kept: this wave has
+    // time to spare, registers are what is short.
     const uint32_t my_stream = lane >> P.lanes_shift;
     const uint32_t my_sub = lane & ((1u << P.lanes_shift) - 1u);
     const uint32_t sk = my_stream % P.K, sbi = my_stream / P.K;
-    const uint64_t *const s_bit_off = P.bit_off[sk];
-    const uint32_t *const s_words = P.words[sk];
-    const uint32_t *const s_sync = P.sync[sk];
     uint32_t uk[2], ubi[2], ugr[2];
 #pragma unroll
     for (uint32_t h = 0; h < 2u; ++h) {
@@ -565,34 +565,33 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         ubi[h] = partial ? 0u : r / P.nseg;       // multi-bucket tiles hold every segment of a bucket
         ugr[h] = partial ? r : r % P.nseg;        // segment, counted from the tile's first
     }
-    const uint64_t *const u_bit_off = P.bit_off[uk[0]];
-    const float *const u_norms = P.norms[uk[0]];
-    const uint32_t *const u_sync = P.sync[uk[0]];
     auto load_stream = [&](const TileGeom &G) {
         StreamRaw r{};
         if (walk)
             return r;
         const uint64_t b = min(G.b0 + sbi, last_bucket);
+        const uint64_t *s_bit_off = P.bit_off[sk];
         r.bo0 = s_bit_off[b];
         r.bo1 = s_bit_off[b + 1];
         if (partial && P.sync_shift) {
-            const uint32_t *sy = s_sync + b * P.nsync;
+            const uint32_t *sy = P.sync[sk] + b * P.nsync;
             r.e0 = sy[max(G.g0, 1u) - 1u];
             r.e1 = sy[min(G.g1, P.nsync) - 1u];
         }
         return r;
     };
-    // Prepare a tile whose metadata has arrived: plans to LDS, words to the staging buffer `buf`.
-    auto prepare = [&](const TileGeom &G, const StreamRaw &sr, const UnitRaw &um, uint32_t *buf, bool &bad) {
+    // Prepare a tile whose metadata has arrived: plans to LDS, this lane's share of its words into registers.
+    auto prepare = [&](const TileGeom &G, const StreamRaw &sr, const UnitRaw &um, uint32_t (&w)[kWordsPerLane],
+                       bool &bad) {
         // words: global -> registers
         uint32_t cnt = 0;
+        const uint32_t *const s_words = P.words[sk];
         const uint32_t *src = s_words;
         if (my_stream < G.nstreams && !walk) {
             const StreamPart S = stream_part(P, G, sr.bo0, sr.bo1, sr.e0, sr.e1);
             cnt = min(S.nwords, P.stream_cap);
             src = s_words + S.first_word;
         }
-        uint32_t w[kWordsPerLane];
 #pragma unroll
         for (uint32_t i = 0; i < kWordsPerLane; ++i) {
             const uint32_t wi = my_sub + (i << P.lanes_shift);
@@ -607,11 +606,13 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             plans[lane + kWave] =
                 pack_plan(plan_unit(G, lane + kWave < G.units, uk[1], ubi[1], G.g0 + ugr[1], m2, bad));
         }
-        // words: registers -> LDS
+    };
+    // ... and from the registers to the staging area, once the parse that read it is over
+    auto store_words = [&](const uint32_t (&w)[kWordsPerLane]) {
         const uint32_t base = 1u + my_stream * P.stream_cap + my_sub;     // <= kStageWords for every lane
 #pragma unroll
         for (uint32_t i = 0; i < kWordsPerLane; ++i)
-            buf[base + (i << P.lanes_shift)] = w[i];
+            stage[base + (i << P.lanes_shift)] = w[i];
     };
 
     // ---- prologue
@@ -621,6 +622,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     TileGeom G = tile_geom(P, t);
     StreamRaw sr{};                             // preparing wave: metadata of the tile after the next, in flight
     UnitRaw um{};
+    uint32_t wnext[kWordsPerLane] = {};         // preparing wave: its share of the next tile's words
     if (parser) {
         for (uint32_t i = lane; i < kTileCoords / 2u; i += kWave)
             reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
@@ -628,16 +630,17 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         lut[lane + kWave] = (uint16_t)gap_table_entry(lane + kWave);
         lut_level[lane] = (uint8_t)level_table_entry(lane);
         lut_level[lane + kWave] = (uint8_t)level_table_entry(lane + kWave);
-        if (lane < 8u)
-            stage[lane >> 2][(lane & 3u) ? kStageWords + (lane & 3u) : 0u] = 0u;    // the pads
+        if (lane < 4u)
+            stage[lane ? kStageWords + lane : 0u] = 0u;    // the pads
     } else {
         sr = load_stream(G);
-        um = load_unit(G, ubi[0], G.g0 + ugr[0], u_bit_off, u_norms, u_sync);
-        prepare(G, sr, um, stage[0], bad);
+        um = load_unit(G, ubi[0], G.g0 + ugr[0], P.bit_off[uk[0]], P.norms[uk[0]], P.sync[uk[0]]);
+        prepare(G, sr, um, wnext, bad);
+        store_words(wnext);
         if (t + stride < P.ntiles) {
             const TileGeom G1 = tile_geom(P, t + stride);
             sr = load_stream(G1);
-            um = load_unit(G1, ubi[0], G1.g0 + ugr[0], u_bit_off, u_norms, u_sync);
+            um = load_unit(G1, ubi[0], G1.g0 + ugr[0], P.bit_off[uk[0]], P.norms[uk[0]], P.sync[uk[0]]);
         }
     }
     __syncthreads();
@@ -649,12 +652,12 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     }
     __syncthreads();
 
-    for (uint32_t cur = 0;; cur ^= 1u) {
+    for (;;) {
         const bool has1 = t + stride < P.ntiles;                        // uniform
         const bool has2 = has1 && t + stride < P.ntiles - stride;
         if (parser) {
             // ---- parse this tile's units
-            const uint32_t *buf = stage[cur];
+            const uint32_t *buf = stage;
             if (walk) {
                 for (uint32_t u = lane; u < G.units; u += kWave)
                     walk_unit(G, u, bad);
@@ -663,9 +666,9 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
                 for (uint32_t h = 0; h < 2u; ++h) {
                     if (h == 1u && G.units <= kWave)
                         break;
-                    const uint32_t kind = Q[h].where >> 16;
+                    const uint32_t kind = (Q[h].where >> 12) & 3u;
                     if (kind == 1u)
-                        parse_planned(G, ubi[h], buf, Q[h], bad);
+                        parse_planned(G, ubi[h], G.g0 + ugr[h], buf, Q[h], bad);
                     else if (kind == 2u)
                         slow_unit(G, buf, uk[h], ubi[h], G.g0 + ugr[h], false, bad);
                 }
@@ -679,13 +682,13 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             // ---- prepare the next tile (its metadata was requested a round ago), request the metadata of the
             // one after it
             const TileGeom GA = tile_geom(P, t + stride);
-            prepare(GA, sr, um, stage[cur ^ 1u], bad);
+            prepare(GA, sr, um, wnext, bad);
             if (lane == 0)
                 next_geom = GA;
             if (has2) {
                 const TileGeom G2 = tile_geom(P, t + 2u * stride);
                 sr = load_stream(G2);
-                um = load_unit(G2, ubi[0], G2.g0 + ugr[0], u_bit_off, u_norms, u_sync);
+                um = load_unit(G2, ubi[0], G2.g0 + ugr[0], P.bit_off[uk[0]], P.norms[uk[0]], P.sync[uk[0]]);
             }
         }
         __syncthreads();
@@ -704,6 +707,8 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
                 Q[0] = plans[lane];
                 if (G1.units > kWave)
                     Q[1] = plans[lane + kWave];
+            } else {
+                store_words(wnext);          // the staging area is free: this tile's parse is over
             }
         }
 
