@@ -123,28 +123,19 @@ struct WalkWords {
     __device__ __forceinline__ uint32_t operator[](uint32_t i) const { return p[i]; }
 };
 
-// Word sources for the parser.  pair_at(q) returns words q - 1 and q of the unit's frame (word 0 holds its
-// bit 0); only the second one matters when q - 1 does not exist.
+// Word sources for the parser.  at(q) returns word q - 1 of the unit's frame (word 0 holds its bit 0); what it
+// returns for a word that does not exist is never looked at.
 struct GlobalWords {
     const uint32_t *p;
     uint32_t last;      // highest readable word index
-    __device__ __forceinline__ void pair_at(uint32_t q, uint32_t &hi, uint32_t &lo) const
-    {
-        hi = p[min(max(q, 1u) - 1u, last)];
-        lo = p[min(q, last)];
-    }
+    __device__ __forceinline__ uint32_t at(uint32_t q) const { return p[min(max(q, 1u) - 1u, last)]; }
 };
 
-// Words staged in LDS.  `p` points one word before the frame; a staging buffer is padded at both ends so
-// that every pair the parser can ask for exists.
+// Words staged in LDS.  `p` points one word before the frame; the staging area is padded at both ends so
+// that every word the parser can ask for exists.
 struct StagedWords {
     const uint32_t *p;
-    __device__ __forceinline__ void pair_at(uint32_t q, uint32_t &hi, uint32_t &lo) const
-    {
-        asm volatile("" : "+v"(q));     // keeps "shift right by 5, then shift-left-and-add" from becoming three operations
-        hi = p[q];
-        lo = p[q + 1u];
-    }
+    __device__ __forceinline__ uint32_t at(uint32_t q) const { return p[q]; }
 };
 
 // ---- gap code table --------------------------------------------------------------------
@@ -195,12 +186,16 @@ __device__ __forceinline__ uint32_t level_table_entry(uint32_t p)
 // software-pipelined by hand so that the two LDS reads on that chain are covered by other work:
 //   chain 1 : the 32-bit window at the position from two adjacent words through one funnel shift (position + 31
 //             is the loop variable: its word index names the second word of the pair, its complement is the
-//             shift); the table read for the gap code is issued
+//             shift); the table read for the gap code is issued.  The two words and the one after them are
+//             held in registers: a record is at most 31 bits (gap code <= 23, sign, level code <= 7), so the
+//             pair moves on by one word at most, and the word that then enters was requested an iteration
+//             ago: no read of stream words is on the chain
 //   cover   : level and value of the previous record (its level table entry was requested an iteration ago), its
 //             add into the tile
 //   chain 2 : gap code's length from the entry; the level table read is issued (nothing on the chain waits for
 //             it); level code's length from a byte permute on its first three bits (the code is at most seven
-//             bits: 0 | 1x0 | 101yy0 | 111yyy0); next position; the read of the next record's words is issued
+//             bits: 0 | 1x0 | 101yy0 | 111yyy0); next position; the pair moves on if the position's word index
+//             did, and the word after the pair is requested
 //   cover   : this record's gap value and index, loop control
 template <class Words>
 __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint16_t *lut, const uint8_t *lut_level,
@@ -213,8 +208,8 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
         bad |= p31 != end31;
         return;
     }
-    uint32_t hi, lo;
-    words.pair_at(p31 >> 5, hi, lo);
+    uint32_t q = p31 >> 5;
+    uint32_t hi = words.at(q), lo = words.at(q + 1u), nx = words.at(q + 2u);
     int prev = -1;
     uint32_t w, e;                  // window, gap entry
     uint32_t idx, w2, e2;           // what an iteration leaves for the first cover step of the next: index, window
@@ -232,8 +227,13 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
         e2 = lut_level[(w2 >> 24) & 0x7fu];
         const uint32_t sel = ((w2 >> 28) & 7u) | 0x0c0c0c00u;
         const uint32_t lj1 = __builtin_amdgcn_perm(0x08040704u, 0x02020202u, sel);   // sign bit + level code
-        p31 += lg + lj1;
-        words.pair_at(p31 >> 5, hi, lo);         // the next record's words
+        p31 += lg + lj1;                         // by 31 at most
+        const uint32_t qn = p31 >> 5;
+        const bool moved = qn != q;
+        hi = moved ? lo : hi;
+        lo = moved ? nx : lo;
+        q = qn;
+        nx = words.at(qn + 2u);
     };
     auto cover_index = [&]() {
         uint32_t i = (uint32_t)(prev + (int)gap_value(w, e));
@@ -386,8 +386,8 @@ __device__ __forceinline__ PackedPlan pack_plan(const UnitPlan &U)
 __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams P)
 {
     __shared__ __align__(16) double tile[kTileCoords];
-    // words at [1, kStageWords]; the parser may read one word before and two after a stream's region
-    __shared__ uint32_t stage[kStageWords + 4];
+    // words at [1, kStageWords]; the parser may read one word before and three after a stream's region
+    __shared__ uint32_t stage[kStageWords + 5];
     __shared__ PackedPlan plans[kPlanned];
     __shared__ TileGeom next_geom;                // of the tile being prepared, for the wave that did not compute it
     __shared__ uint16_t lut[128];
@@ -630,7 +630,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         lut[lane + kWave] = (uint16_t)gap_table_entry(lane + kWave);
         lut_level[lane] = (uint8_t)level_table_entry(lane);
         lut_level[lane + kWave] = (uint8_t)level_table_entry(lane + kWave);
-        if (lane < 4u)
+        if (lane < 5u)
             stage[lane ? kStageWords + lane : 0u] = 0u;    // the pads
     } else {
         sr = load_stream(G);
