@@ -289,7 +289,7 @@ __device__ __forceinline__ void team_barrier()
 //   nonzeros fit, bits fit  : compacted index list, balanced record runs, bit string assembled in LDS
 //   nonzeros fit, bits don't: the same, but records are OR-ed into the (zeroed) staging slot in global memory
 //   nonzeros don't fit      : every thread codes the records of its own chunk, into the staging slot
-template <int TEAM>
+template <int TEAM, int VPT>
 __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const EncodeWorker &W, bool active, uint64_t b,
                                                 const uint32_t *qb32, uint32_t *out, uint16_t *rec,
                                                 const uint32_t *erc_lut, const uint32_t *tail_lut, uint32_t *sync_l,
@@ -300,26 +300,38 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     const uint32_t base = tid * rows * 4u;
     const uint8_t *qbytes = reinterpret_cast<const uint8_t *>(qb32);
 
-    // (1) nonzero mask of this thread's chunk, ranks, compaction
-    uint64_t nz = 0;
-    for (uint32_t w = 0; w < rows; ++w) {
-        const uint32_t word = qb32[tid * rows + w];
-        // bit 7 of every byte whose low seven bits (the level) are not all zero
-        const uint32_t t = ((word & 0x7f7f7f7fu) + 0x7f7f7f7fu) & 0x80808080u;
-        const uint32_t nib = (((t >> 7) * 0x00204081u) >> 21) & 0xfu;   // bits 0,8,16,24 -> 0..3
-        nz |= (uint64_t)nib << (4u * w);
+    // (1) nonzero mask of this thread's chunk (rows <= VPT <= 16 words: two 32-bit halves), ranks, compaction
+    static_assert(VPT <= 16, "the chunk's mask is 64 bits");
+    uint32_t nz_lo = 0, nz_hi = 0;
+#pragma unroll
+    for (int w = 0; w < VPT; ++w) {
+        if ((uint32_t)w < rows) {
+            const uint32_t word = qb32[tid * rows + (uint32_t)w];
+            // bit 0 of every byte whose low seven bits (the level) are not all zero, then the four bits side by side
+            const uint32_t t = (((word & 0x7f7f7f7fu) + 0x7f7f7f7fu) >> 7) & 0x01010101u;
+            const uint32_t nib = __builtin_amdgcn_udot4(t, 0x08040201u, 0u, false);
+            if (w < 8)
+                nz_lo |= nib << (4 * w);
+            else
+                nz_hi |= nib << (4 * (w - 8));
+        }
     }
+    const uint64_t nz = ((uint64_t)nz_hi << 32) | nz_lo;
     uint32_t nnz;
-    uint32_t rank = team_exclusive_sum<TEAM>((uint32_t)__popcll((unsigned long long)nz), scratch, nnz);
+    uint32_t rank = team_exclusive_sum<TEAM>((uint32_t)(__popc(nz_lo) + __popc(nz_hi)), scratch, nnz);
     const bool listed = nnz <= P.rec_cap;          // uniform over the team
     int before_chunk = -1;                         // last nonzero before this thread's chunk (unlisted buckets)
     if (listed) {
-        uint64_t m = nz;
-        while (m) {
-            const int k = __ffsll((unsigned long long)m) - 1;
-            m &= m - 1;
-            rec[rank++] = (uint16_t)(base + (uint32_t)k);
-        }
+        auto list = [&](uint32_t m, uint32_t at) {
+            while (m) {
+                const uint32_t k = (uint32_t)__builtin_ctz(m);
+                m &= m - 1u;
+                rec[rank++] = (uint16_t)(at + k);
+            }
+        };
+        list(nz_lo, base);
+        if constexpr (VPT > 8)
+            list(nz_hi, base + 32u);
     } else {
         const int last = nz ? (int)base + 63 - __clzll((long long)nz) : -1;
         before_chunk = team_exclusive_max<TEAM>(last, -1, reinterpret_cast<int *>(scratch + 16));
@@ -552,11 +564,12 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
                 x[i].w *= B.prescale;
             }
         }
+        const uint32_t x0 = (key.k0 + 4u * tid) * kRngC1;      // row i starts 4 * TEAM * i coordinates further on
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             if ((uint32_t)i < P.rows) {
                 const uint32_t vi = (uint32_t)i * TEAM + tid;
-                qb32[vi] = B.dead ? 0u : quantize_vec4(x[i], (key.k0 + 4u * vi) * kRngC1, key.k1, B);
+                qb32[vi] = B.dead ? 0u : quantize_vec4(x[i], x0 + (uint32_t)i * (4u * TEAM * kRngC1), key.k1, B);
             }
         }
     } else {
@@ -577,7 +590,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
         }
     }
     __syncthreads();
-    encode_from_lds<TEAM>(P, W, active, b, qb32, out, rec, erc_lut, tail_lut, sync_l, scratch);
+    encode_from_lds<TEAM, VPT>(P, W, active, b, qb32, out, rec, erc_lut, tail_lut, sync_l, scratch);
 }
 
 // ------------------------------------------------- offsets and gather of the slots
