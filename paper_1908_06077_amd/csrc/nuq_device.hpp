@@ -61,12 +61,15 @@ __device__ __forceinline__ uint32_t draw24(uint32_t x, uint32_t k1)
 // of a nonzero value (fp32 denormals are kept: the kernels run in IEEE denormal mode), so
 // "up" is exactly "t < 0".  w must be a normal float for the scaling to be exact; norms
 // below 2^-60 are handled by scaling the whole bucket by 2^100 first (a power of two:
-// ratios are unchanged).
+// ratios are unchanged).  The same test without per-bin scales: a2 = a * 2^-m (the bits of
+// nS plus the low 23 bits of the difference) lies in [nS, 2 nS), a2 - nS is exact, and
+// t = fma(u, nS * 2^-24, -(a2 - nS)) is the t above divided by 2^m.
 
 struct BucketScale {
     uint32_t ns_bits;  // bits of (prescaled) N * 2^-s
     uint32_t c_bits;   // bits of (prescaled) N * 2^(-s-24)
     float ns;          // the same as floats
+    float ns2;         // 2 * ns (finite whenever s >= 1)
     float c;
     float prescale;    // 1 or 2^100
     int s;
@@ -86,21 +89,9 @@ __device__ __forceinline__ BucketScale make_scale(float norm, int s)
     B.ns_bits = f2u(norm) - ((uint32_t)s << 23);
     B.c_bits = B.ns_bits - (24u << 23);
     B.ns = u2f(B.ns_bits);
+    B.ns2 = u2f(B.ns_bits + (1u << 23));
     B.c = u2f(B.c_bits);
     return B;
-}
-
-// Level index of one coordinate for the 24-bit draw u; a = |v| (already prescaled).
-__device__ __forceinline__ int quantize_level(float a, uint32_t u, const BucketScale &B)
-{
-    const int m = (int)(f2u(a) - B.ns_bits) >> 23;
-    if (m >= B.s)
-        return B.s + 1;
-    const uint32_t sh = m < 0 ? 0u : (uint32_t)m << 23;
-    const float w = u2f(B.c_bits + sh);
-    const float x = m < 0 ? a : a - u2f(B.ns_bits + sh);
-    const float t = __builtin_fmaf((float)u, w, -x);
-    return (m < 0 ? 0 : m + 1) + (t < 0.0f ? 1 : 0);
 }
 
 // ------------------------------------------------------------------------- ERC

@@ -123,9 +123,14 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_bucket_norms(EncodePara
 // Quantize the four coordinates of one vector; returns the four level|sign<<7 bytes.
 // x0 = (k0 + index of first coordinate) * C1.  The caller has applied B.prescale to x.
 //
-// Fast path, taken when every lane's four coordinates lie below the first level (the usual case:
-// |v_i| < 2^-s ||v||): the level is 0 or 1, "up" is the sign bit of t = fma(u, c, -|v|), and the
-// bytes are assembled from the top bytes of v (sign) and t (up) with byte permutes.
+// Three routes, chosen per wave from the largest |v_i| of the vector over all lanes:
+//   below the first level (the usual case: |v_i| < 2^-s ||v||): the level is 0 or 1, "up" is the sign bit of
+//     t = fma(u, c, -|v|), and the bytes are assembled from the top bytes of v (sign) and t (up) with byte permutes;
+//   below twice the first level (s >= 1): bins [0, ns) and [ns, 2 ns) have the same width, so only the bin's lower end
+//     differs per coordinate;
+//   anything else: no branches; |v| is scaled into [ns, 2 ns) by replacing its exponent (its distance to the lower
+//     end of its bin, divided by the bin's width in units of c, is then a - ns for every bin), bin index from the
+//     difference of the bit patterns.
 __device__ __forceinline__ uint32_t quantize_vec4(const float4 &x, uint32_t x0, uint32_t k1,
                                                   const BucketScale &B)
 {
@@ -149,14 +154,33 @@ __device__ __forceinline__ uint32_t quantize_vec4(const float4 &x, uint32_t x0, 
         const uint32_t sg = __builtin_amdgcn_perm(v23, v01, 0x05040100u);
         return (sg & up7) | (up7 >> 7);
     }
-    uint32_t packed = 0;
+    uint32_t levels = 0;
+    if (B.s >= 1 && __all(big < B.ns2)) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const int j = quantize_level(fabsf(xs[c]), u[c], B);
-        const uint32_t sign = (j > 0) ? ((f2u(xs[c]) >> 24) & 0x80u) : 0u;
-        packed |= ((uint32_t)j | sign) << (8 * c);
+        for (int c = 0; c < 4; ++c) {
+            const float a = fabsf(xs[c]);
+            const float over = a - B.ns;                       // exact when it is used (ns <= a < 2 ns)
+            const bool low = over < 0.0f;
+            const float t = __builtin_fmaf((float)u[c], B.c, -(low ? a : over));
+            levels |= ((low ? 0u : 1u) + (t < 0.0f ? 1u : 0u)) << (8 * c);
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int diff = (int)((f2u(xs[c]) & 0x7fffffffu) - B.ns_bits);
+            const int m = diff >> 23;                          // bin: floor(log2(a / ns)), negative below the first level
+            const float a2 = u2f(B.ns_bits + ((uint32_t)diff & 0x007fffffu));
+            const float t = __builtin_fmaf((float)u[c], B.c, -(m < 0 ? fabsf(xs[c]) : a2 - B.ns));
+            const int j = min(max(m, -1) + 1 + (t < 0.0f ? 1 : 0), B.s + 1);   // m >= s: the top level, no draw
+            levels |= (uint32_t)j << (8 * c);
+        }
     }
-    return packed;
+    // sign bytes of the four coordinates, kept where the level is not zero (a level is below 128)
+    const uint32_t v01 = __builtin_amdgcn_perm(f2u(xs[1]), f2u(xs[0]), 0x0c0c0703u);
+    const uint32_t v23 = __builtin_amdgcn_perm(f2u(xs[3]), f2u(xs[2]), 0x0c0c0703u);
+    const uint32_t sg = __builtin_amdgcn_perm(v23, v01, 0x05040100u);
+    const uint32_t nz7 = (levels + 0x7f7f7f7fu) & 0x80808080u;
+    return (sg & nz7) | levels;
 }
 
 // --------------------------------------------------------------- quantize kernel
