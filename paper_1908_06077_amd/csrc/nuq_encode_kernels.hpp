@@ -395,8 +395,9 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     };
 
     // (2) lengths of this thread's records.  The first kKept records of a run from the list stay in registers
-    // for the third pass (a run is nnz / TEAM records: two or three for gradients).
-    constexpr uint32_t kKept = 4;
+    // for the third pass (a run is nnz / TEAM records: two or three for gradients in large buckets, eight where
+    // a quarter of a 512-coordinate bucket is nonzero).
+    constexpr uint32_t kKept = TEAM <= 64 ? 8 : 4;
     uint32_t kept_bits[kKept], kept_len[kKept];
     int kept_e[kKept];
     uint32_t bits = 0;
