@@ -218,8 +218,12 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
         hipLaunchKernelGGL(k_chunk_scan, dim3(K), dim3(256), 0, st, w.chunk_sums, nchunks);
         prefix = w.chunk_sums;
     }
-    hipLaunchKernelGGL(k_finish, dim3((uint32_t)((nb + kFinishBuckets - 1) / kFinishBuckets), K), dim3(256), 0, st, P, Wk,
-                       prefix, nchunks);
+    const uint32_t fb = finish_buckets(bucket);
+    const dim3 fgrid((uint32_t)((nb + fb - 1) / fb), K);
+    if (fb == 64u)
+        hipLaunchKernelGGL(k_finish<64>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks);
+    else
+        hipLaunchKernelGGL(k_finish<16>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks);
     return check_launch();
 }
 

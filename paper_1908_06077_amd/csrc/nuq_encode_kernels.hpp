@@ -622,9 +622,11 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
 //
 // wc_b = ceil(len_b / 32) words per bucket; start word of bucket b = sum of wc over the worker's
 // earlier buckets; bit_off[b+1] = 32 * start_b + len_b.  One "finish" kernel per batch: a
-// workgroup owns four buckets of one worker, sums the word counts before them (directly, or
-// from per-chunk prefix sums when the worker has many buckets), writes their offsets and
-// copies their staging slots (one wave per bucket) to their place in `words`.
+// workgroup owns FB consecutive buckets of one worker (16, or 64 where buckets are small, so
+// that a workgroup still has a few thousand words to move), sums the word counts before them
+// (directly, or from per-chunk prefix sums when the worker has many buckets), writes their
+// offsets and copies their staging slots to their place in `words`, one word per thread at
+// a time, the word's bucket found by bisection.
 
 constexpr uint32_t kChunk = 1024;          // buckets per chunk of the two-level sum
 constexpr uint64_t kDirectSumMax = 8192;   // up to this many buckets every workgroup sums directly
@@ -691,18 +693,21 @@ __global__ __launch_bounds__(256) void k_chunk_scan(uint64_t *chunk_sums, uint64
     }
 }
 
-constexpr uint32_t kFinishBuckets = 16;   // buckets per workgroup of k_finish
+// Buckets per workgroup of k_finish.
+__host__ __device__ inline uint32_t finish_buckets(uint32_t bucket) { return bucket <= 1024u ? 64u : 16u; }
 
-// grid (ceil(nb / 16), K).  chunk_prefix == nullptr: sum the lengths of all earlier buckets directly.
+// grid (ceil(nb / FB), K), FB = 16 or 64.  chunk_prefix == nullptr: sum the lengths of all earlier buckets directly.
+template <uint32_t FB>
 __global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, const uint64_t *chunk_prefix,
                                                 uint64_t nchunks)
 {
+    static_assert(FB == 16 || FB == 64, "one wave scans the workgroup's word counts");
     __shared__ uint64_t scratch[4];
-    __shared__ uint32_t wstart[kFinishBuckets + 1];   // first word of each bucket, relative to the workgroup's first
-    __shared__ uint32_t skip[kFinishBuckets];
+    __shared__ uint32_t wstart[FB + 1];   // first word of each bucket, relative to the workgroup's first
+    __shared__ uint32_t skip[FB];
     const EncodeWorker &W = Wk.w[blockIdx.y];
     const uint32_t *__restrict__ lens = P.lens + (uint64_t)blockIdx.y * P.nb_stride;
-    const uint64_t b_first = (uint64_t)blockIdx.x * kFinishBuckets;
+    const uint64_t b_first = (uint64_t)blockIdx.x * FB;
     const uint32_t tid = threadIdx.x;
 
     // words before this workgroup's first bucket
@@ -713,7 +718,7 @@ __global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, 
         base = chunk_prefix[(uint64_t)blockIdx.y * (nchunks + 1) + c];
     }
     uint32_t my_len = 0;
-    if (tid < kFinishBuckets && b_first + tid < P.nb)
+    if (tid < FB && b_first + tid < P.nb)
         my_len = lens[b_first + tid];
     uint32_t part = 0;     // < 2^32: at most 8192 lengths of < 2^21 bits each are summed here
     {
@@ -727,16 +732,21 @@ __global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, 
         }
     }
     base += block_sum_u64(part, scratch);
-    if (tid < kFinishBuckets)
-        wstart[tid + 1] = (my_len + 31u) >> 5;
-    if (tid == 0)
-        wstart[0] = 0;
+    if (tid < kWave) {                      // the first wave: inclusive scan of the word counts
+        uint32_t inc = tid < FB ? (my_len + 31u) >> 5 : 0u;
+#pragma unroll
+        for (int off = 1; off < (int)FB; off <<= 1) {
+            const uint32_t t = (uint32_t)__shfl_up((int)inc, off, kWave);
+            if ((int)tid >= off)
+                inc += t;
+        }
+        if (tid < FB)
+            wstart[tid + 1] = inc;
+        if (tid == 0)
+            wstart[0] = 0;
+    }
     __syncthreads();
-    if (tid == 0)
-        for (uint32_t j = 1; j <= kFinishBuckets; ++j)
-            wstart[j] += wstart[j - 1];
-    __syncthreads();
-    if (tid < kFinishBuckets && b_first + tid < P.nb) {
+    if (tid < FB && b_first + tid < P.nb) {
         const uint64_t start = base + wstart[tid];
         W.bit_off[b_first + tid + 1] = 32ull * start + my_len;
         if (b_first + tid == 0)
@@ -749,14 +759,14 @@ __global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, 
     __syncthreads();
 
     // copy the staging slots: word w of the workgroup's run belongs to the bucket found by bisection
-    const uint32_t total = wstart[kFinishBuckets];
+    const uint32_t total = wstart[FB];
     const uint32_t *__restrict__ staging = P.staging + ((uint64_t)blockIdx.y * P.nb + b_first) * P.slot_words;
     uint32_t *__restrict__ dst = W.words + base;
 #pragma unroll 4
     for (uint32_t w = tid; w < total; w += 256u) {
         uint32_t j = 0;
 #pragma unroll
-        for (uint32_t step = kFinishBuckets / 2; step >= 1; step >>= 1)
+        for (uint32_t step = FB / 2; step >= 1; step >>= 1)
             j += (wstart[j + step] <= w) ? step : 0u;
         if (!skip[j])
             dst[w] = staging[(uint64_t)j * P.slot_words + (w - wstart[j])];
