@@ -167,17 +167,18 @@ __device__ __forceinline__ uint32_t gap_value(uint32_t w, uint32_t e)
 // Parse the records in bits [bit_lo, bit_hi) of a unit's frame and add their values into the tile.
 //   forced : in-bucket index of the first record when the unit was entered through a sync entry
 //            (its gap code is then only skipped), or -1 to start from the bucket's beginning
-//   idx_hi : a record at or above this index is a format error; smax = s + 1
+//   idx_hi : a record at or above this index is a format error
 // Format violations set `bad`; nothing is ever added outside [0, idx_hi) of the bucket.
 //
 // ---- level code table ------------------------------------------------------------------
-// Entry for the seven stream bits p after a record's sign bit (MSB first): the level index 1..15, or 0 if no code
-// ends within the seven bits (a third group would follow: a level index above 15, which no message holds).
-__device__ __forceinline__ uint32_t level_table_entry(uint32_t p)
+// Entry for the seven stream bits p after a record's sign bit (MSB first): the level index 1..smax (smax = s + 1
+// <= 15), or 0 for what the message cannot hold: a larger index, or no code that ends within the seven bits (a
+// third group would follow: an index above 15).
+__device__ __forceinline__ uint32_t level_table_entry(uint32_t p, uint32_t smax)
 {
     uint32_t N, len;
     erc_decode_bits(p << 25, N, len);
-    return len <= 7u ? N : 0u;
+    return len <= 7u && N <= smax ? N : 0u;
 }
 
 // One iteration per record.  A lone wave issues an instruction every five cycles or so, a dependent one every
@@ -200,7 +201,7 @@ __device__ __forceinline__ uint32_t level_table_entry(uint32_t p)
 template <class Words>
 __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint16_t *lut, const uint8_t *lut_level,
                                                  uint32_t bit_lo, uint32_t bit_hi, int forced, uint32_t idx_hi,
-                                                 uint32_t smax, double wnorm, double *tile_at0, bool &bad)
+                                                 double wnorm, double *tile_at0, bool &bad)
 {
     uint32_t p31 = bit_lo + 31u;
     const uint32_t end31 = bit_hi + 31u;
@@ -215,7 +216,7 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
     uint32_t idx, w2, e2;           // what an iteration leaves for the first cover step of the next: index, window
                                     // at the sign bit, level entry (in flight)
     uint32_t last_i = 0;            // index before clamping: non-decreasing, so the last one tells if any was too big
-    uint32_t max_jm1 = 0;           // largest level index minus one, as unsigned: a level 0 shows as 2^32 - 1
+    uint32_t min_j = 1;             // smallest table entry met: 0 marks a level code the message cannot hold
 
     auto chain1 = [&]() {
         w = __builtin_amdgcn_alignbit(hi, lo, ~p31);
@@ -247,7 +248,7 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
     };
     auto cover_value = [&]() {
         const uint32_t j = e2;
-        max_jm1 = max(max_jm1, j - 1u);
+        min_j = min(min_j, j);
         // ||v|| * l_j = (||v|| * 2^(-1-s)) * 2^j, exact in fp64; the sign goes into the top bit
         const double mag = ldexp(wnorm, (int)j);
         const uint32_t mh = (uint32_t)((uint64_t)__double_as_longlong(mag) >> 32);
@@ -269,7 +270,7 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
         cover_index();
     }
     cover_value();
-    bad |= (p31 != end31) | (last_i >= idx_hi) | (max_jm1 >= smax);
+    bad |= (p31 != end31) | (last_i >= idx_hi) | (min_j == 0u);
 }
 
 // Where a tile lies.  Everything here is uniform over the workgroup.
@@ -490,7 +491,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         const uint32_t nbk = G.b0 + bi == last_bucket ? last_len : P.bucket;
         const uint32_t idx_hi = P.sync_shift ? min(nbk, (g + 1u) << P.sync_shift) : nbk;
         decode_unit_fast(StagedWords{buf + (Q.where & 0xFFFu)}, lut, lut_level, Q.bits & 0xFFFFu, Q.bits >> 16,
-                         (int)(Q.where >> 16) - 1, idx_hi, P.s + 1u, (double)Q.norm * wscale, tile_origin(G, bi), bad);
+                         (int)(Q.where >> 16) - 1, idx_hi, (double)Q.norm * wscale, tile_origin(G, bi), bad);
     };
     // Any unit, from scratch: units beyond the planned ones and units whose words were not staged.
     auto slow_unit = [&](const TileGeom &G, const uint32_t *buf, uint32_t k, uint32_t bi, uint32_t g, bool report,
@@ -505,7 +506,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         else if (X.kind == 2)
             decode_unit_fast(GlobalWords{P.words[k] + X.first_word, X.nwords - 1u}, lut, lut_level, X.bit_lo, X.bit_hi,
                              X.forced,
-                             X.idx_hi, P.s + 1u, (double)X.norm * wscale, tile_origin(G, bi), bad);
+                             X.idx_hi, (double)X.norm * wscale, tile_origin(G, bi), bad);
     };
     // Tiles of a large bucket without a sync index: every tile parses the bucket from its first record in
     // global memory and keeps what lands inside.
@@ -628,8 +629,8 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
         lut[lane] = (uint16_t)gap_table_entry(lane);
         lut[lane + kWave] = (uint16_t)gap_table_entry(lane + kWave);
-        lut_level[lane] = (uint8_t)level_table_entry(lane);
-        lut_level[lane + kWave] = (uint8_t)level_table_entry(lane + kWave);
+        lut_level[lane] = (uint8_t)level_table_entry(lane, P.s + 1u);
+        lut_level[lane + kWave] = (uint8_t)level_table_entry(lane + kWave, P.s + 1u);
         if (lane < 5u)
             stage[lane ? kStageWords + lane : 0u] = 0u;    // the pads
     } else {
