@@ -129,6 +129,45 @@ def test_decode_average_of_K_workers(g, d, n, s, S, K):
     assert nuq.nuq_last_error_flags() == 0
 
 
+def random_cases(count, seed):
+    """Seeded draws over the whole parameter space of the entry points: vector length, bucket size (log-uniform
+    over 1..32768), s, sync stride, number of workers, value distribution."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        n = int(round(2.0 ** rng.uniform(0, 15)))
+        if rng.random() < 0.3:
+            n = int(2 ** rng.integers(6, 16))                  # powers of two: whole rows, aligned buckets
+        d = int(rng.integers(1, 12 * n + 2)) if rng.random() < 0.5 else int(rng.integers(1, 150_000))
+        s = int(rng.integers(1, 15))
+        S = int(rng.choice([0, 64, 128, 256, 512, 1024]))
+        K = int(rng.choice([1, 2, 3, 5, 8]))
+        kind = str(rng.choice(["gauss", "mixed", "edges"]))
+        cases.append((d, n, s, S, K, kind))
+    return cases
+
+
+@pytest.mark.parametrize("d,n,s,S,K,kind", random_cases(40, 20240607))
+def test_random_shapes(g, d, n, s, S, K, kind):
+    """Batched fused encode of K workers and decode + average on randomly drawn shapes: messages bit-exact,
+    norms and averages to the bars."""
+    nuq = g.nuq
+    rng = np.random.default_rng([d, n, s, S, K])
+    vs_np = [make_vector(kind, d, n, rng) for _ in range(K)]
+    vs = [torch.from_numpy(v).to(g.DEV) for v in vs_np]
+    seeds = [int(x) for x in rng.integers(0, 2 ** 63, size=K)]
+    msgs = g.batched_encode(vs, n, s, seeds, S)
+    msgs_np = []
+    for v_np, m, seed in zip(vs_np, msgs, seeds):
+        g.check_norms(v_np, n, m.norms.cpu().numpy())
+        _, bo, words, _ = g.check_message_against_oracle(v_np, n, s, seed, S, m)
+        msgs_np.append((m.norms.cpu().numpy(), bo, words))
+    out = torch.full((d,), 3.0, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
+    assert nuq.nuq_last_error_flags() == 0
+    g.check_average(msgs_np, d, n, s, 1.0 / K, out.cpu().numpy())
+
+
 @pytest.mark.parametrize("d,n,s,S,K", [(70_000, 8192, 3, 512, 8), (20_000, 512, 3, 0, 4), (40_000, 16384, 7, 256, 3)])
 def test_batched_encode_equals_per_worker_encode(g, d, n, s, S, K):
     nuq = g.nuq
