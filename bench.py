@@ -39,6 +39,10 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy before the timed region (a known-size reference "
                          "for hardware-counter runs)")
+    ap.add_argument("--reference-kernels", action="store_true",
+                    help="also time PyTorch's own sum, copy and fill over a tensor of the step's input size and add "
+                         "them to the line as `reference` (what library streaming kernels reach on this GPU: context "
+                         "for the roofline fractions, not a target)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-worker-calls", action="store_true",
                     help="encode with K nuq_quantize_encode calls instead of one nuq_quantize_encode_batch")
@@ -190,9 +194,36 @@ def main():
                             "launches": len(dec_ms)},
     }
 
+    if args.reference_kernels:
+        result["reference"] = reference_kernels(torch, d * K, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, grads, S)
     print(json.dumps(result))
+
+
+def reference_kernels(torch, numel, dev):
+    """PyTorch's own streaming kernels over `numel` floats (the step's input size): achieved HBM TB/s."""
+    x = torch.empty(numel, dtype=torch.float32, device=dev).normal_()
+    y = torch.empty_like(x)
+
+    def timed(f, reps=20):
+        f()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            f()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    nbytes = 4.0 * numel
+    out = {}
+    for name, f, traffic in (("sum", lambda: x.sum(), nbytes), ("copy", lambda: y.copy_(x), 2 * nbytes),
+                             ("fill", lambda: y.zero_(), nbytes)):
+        ms = timed(f)
+        out[name] = {"ms": round(ms, 4), "TBps": round(traffic / (ms * 1e-3) / 1e12, 2)}
+    return out
 
 
 def measured_traffic(kernel, config, S):
