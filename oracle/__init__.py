@@ -75,6 +75,16 @@ def lib() -> ctypes.CDLL:
         L.nuqo_decode_levels.restype = i32
         L.nuqo_decode_average.argtypes = [u32, vp, vp, vp, u64, u32, i32, ctypes.c_double, i32, vp]
         L.nuqo_decode_average.restype = i32
+        L.nuqo_bucket_norms_linf.argtypes = [vp, u64, u32, vp]
+        L.nuqo_bucket_norms_linf.restype = None
+        L.nuqo_quantize_coord_table.argtypes = [ctypes.c_float, ctypes.c_float, i32, vp, u32]
+        L.nuqo_quantize_coord_table.restype = i32
+        L.nuqo_level_histogram_table.argtypes = [ctypes.c_float, ctypes.c_float, i32, vp, u32, u32, vp]
+        L.nuqo_level_histogram_table.restype = None
+        L.nuqo_quantize_table.argtypes = [vp, u64, u32, i32, vp, u64, vp, u64, vp]
+        L.nuqo_quantize_table.restype = None
+        L.nuqo_decode_average_table.argtypes = [u32, vp, vp, vp, u64, u32, i32, vp, ctypes.c_double, i32, vp]
+        L.nuqo_decode_average_table.restype = i32
         _lib = L
     return _lib
 
@@ -266,6 +276,77 @@ def decode_average(norms_list, bit_off_list, words_list, d: int, bucket: int, s:
     out = np.zeros(d, dtype=np.float64) if prior is None else np.array(prior, dtype=np.float64)
     rc = lib().nuqo_decode_average(K, arr(norms_list), arr(bit_off_list), arr(words_list), d, bucket, s,
                                    float(scale), 0 if prior is None else 1, _p(out))
+    if rc:
+        raise ValueError("malformed stream: %d" % rc)
+    return out
+
+
+# ------------------------------------------------------- general level sets
+
+def _table(lev, s: int) -> np.ndarray:
+    lev = np.ascontiguousarray(lev, dtype=np.float32)
+    assert lev.size == s + 2 and lev[0] == 0.0 and lev[-1] == 1.0 and np.all(np.diff(lev) > 0)
+    return lev
+
+
+def bucket_norms_linf(v: np.ndarray, bucket: int) -> np.ndarray:
+    """Maximum norm of each bucket (QSGDinf's normalization)."""
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    out = np.empty(num_buckets(v.size, bucket), dtype=np.float64)
+    lib().nuqo_bucket_norms_linf(_p(v), v.size, bucket, _p(out))
+    return out
+
+
+def quantize_coord_table(vi: float, norm: float, lev, u24: int) -> int:
+    """Def. 1 with an arbitrary level sequence (Sec. 4.1, generally spaced levels)."""
+    s = len(lev) - 2
+    lev = _table(lev, s)
+    return lib().nuqo_quantize_coord_table(float(np.float32(vi)), float(np.float32(norm)), s, _p(lev), u24)
+
+
+def level_histogram_table(vi: float, norm: float, lev, u_begin: int = 0, u_end: int = 1 << 24) -> np.ndarray:
+    s = len(lev) - 2
+    lev = _table(lev, s)
+    hist = np.zeros(16, dtype=np.uint64)
+    lib().nuqo_level_histogram_table(float(np.float32(vi)), float(np.float32(norm)), s, _p(lev), u_begin, u_end,
+                                     _p(hist))
+    return hist
+
+
+def quantize_table(v: np.ndarray, bucket: int, lev, seed: int, norms: np.ndarray, first_bucket: int = 0) -> np.ndarray:
+    """q[i] = level index | sign << 7 for the level sequence lev[0..s+1], counter generator as in quantize()."""
+    s = len(lev) - 2
+    lev = _table(lev, s)
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    norms = np.ascontiguousarray(norms, dtype=np.float32)
+    assert norms.size == num_buckets(v.size, bucket)
+    q = np.empty(v.size, dtype=np.uint8)
+    lib().nuqo_quantize_table(_p(v), v.size, bucket, s, _p(lev), seed & (2 ** 64 - 1), _p(norms), first_bucket, _p(q))
+    return q
+
+
+def dequantize_table(q: np.ndarray, bucket: int, lev, norms: np.ndarray) -> np.ndarray:
+    """Def. 1: Q(v_i) = ||v|| * sign * l_j with l_j from the table, fp64."""
+    lev = np.asarray(lev, dtype=np.float32).astype(np.float64)
+    j = (q & 0x7F).astype(np.int64)
+    sign = np.where(q & 0x80, -1.0, 1.0)
+    nrm = np.repeat(np.asarray(norms, dtype=np.float64), bucket)[: q.size]
+    return nrm * sign * lev[j]
+
+
+def decode_average_table(norms_list, bit_off_list, words_list, d: int, bucket: int, lev,
+                         scale: float, prior: np.ndarray | None = None) -> np.ndarray:
+    """decode_average() with the table's level values."""
+    s = len(lev) - 2
+    lev = _table(lev, s)
+    K = len(norms_list)
+    norms_list = [np.ascontiguousarray(a, dtype=np.float32) for a in norms_list]
+    bit_off_list = [np.ascontiguousarray(a, dtype=np.uint64) for a in bit_off_list]
+    words_list = [np.ascontiguousarray(a if a.size else np.zeros(1, np.uint32), dtype=np.uint32) for a in words_list]
+    arr = lambda xs: (ctypes.c_void_p * K)(*[_p(x) for x in xs])
+    out = np.zeros(d, dtype=np.float64) if prior is None else np.array(prior, dtype=np.float64)
+    rc = lib().nuqo_decode_average_table(K, arr(norms_list), arr(bit_off_list), arr(words_list), d, bucket, s,
+                                         _p(lev), float(scale), 0 if prior is None else 1, _p(out))
     if rc:
         raise ValueError("malformed stream: %d" % rc)
     return out

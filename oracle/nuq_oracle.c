@@ -17,6 +17,12 @@
  *                          ERC(log2(2^{s+1} h)); App. C parts R and E.
  *   nuqo_decode_average    App. A, DECODE, then the aggregate of Alg. 1:
  *                          (1/K) * sum_k decoded gradient.
+ *   nuqo_*_table,          the same quantizer for an arbitrary level sequence
+ *   nuqo_bucket_norms_linf l_0 = 0 < l_1 < ... < l_{s+1} = 1 (Sec. 3.1 before the special
+ *                          case; Sec. 4.1 "Generally spaced levels", eqs. (genh_case1),
+ *                          (genh_case2); the exponential family (0, p^s, ..., p, 1) of
+ *                          Sec. 4.1; uniform levels = QSGD, with the maximum norm = QSGDinf,
+ *                          Sec. 1 and Sec. 2).
  *
  * Points the paper leaves open (random number source, bit order, how the end
  * of a bucket's records is known, padding) are fixed by the wire-format
@@ -28,6 +34,11 @@
  * ERC codewords, decode(encode(x)) == x, a hand-worked ENCODE bit string.
  * The exact random bits of a particular (seed, bucket, index) are fixed by
  * the format text, not by the paper: "parity unpinned" by the paper for those.
+ * The level-table functions are pinned by tests/test_oracle_levels.py: equality
+ * with the functions above on the table (0, 2^-s, ..., 1/2, 1), exhaustive
+ * enumeration of the draws against p(r) as an exact fraction, unbiasedness and
+ * the variance formula on uniform and exponential tables, the ordering of the
+ * three schemes' variances on Gaussian vectors.
  */
 #include <math.h>
 #include <stdint.h>
@@ -177,6 +188,85 @@ void nuqo_quantize(const float *v, uint64_t d, uint32_t bucket, int s, uint64_t 
         for (uint64_t i = lo; i < hi; i++) {
             uint32_t u = nuqo_rng_u24(k0, k1, (uint32_t)(i - lo));
             int j = nuqo_quantize_coord(v[i], norms[b], s, u);
+            uint8_t sign = (j > 0 && signbit(v[i])) ? 0x80 : 0;
+            q[i] = (uint8_t)j | sign;
+        }
+    }
+}
+
+/* ---------------------------------------------------- general level sets */
+
+/* Maximum norm of every bucket (the normalization of QSGDinf): max_i |v_i|, exact. */
+void nuqo_bucket_norms_linf(const float *v, uint64_t d, uint32_t bucket, double *norms)
+{
+    uint64_t nb = (d + bucket - 1) / bucket;
+    for (uint64_t b = 0; b < nb; b++) {
+        uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        double m = 0.0;
+        for (uint64_t i = lo; i < hi; i++) {
+            double a = fabs((double)v[i]);
+            if (a > m || a != a)
+                m = a;
+        }
+        norms[b] = m;
+    }
+}
+
+/*
+ * Level index of one coordinate for an arbitrary level sequence lev[0..s+1]
+ * (fp32 values, lev[0] = 0 < lev[1] < ... < lev[s+1] = 1).  Def. 1 with the
+ * two cases of Sec. 4.1: r in [l_j, l_{j+1}] goes up to l_{j+1} with probability
+ * p = (r - l_j) / tau_j, tau_j = l_{j+1} - l_j.
+ *
+ * As above everything is multiplied through by ||v||: l_j * ||v|| is a product
+ * of two 24-bit significands, exact in fp64.  tau_j * ||v|| and |v_i| - l_j * ||v||
+ * are each one fp64 subtraction and u * (tau_j * ||v||) one fp64 product, each
+ * rounded to nearest: for levels that are not powers of two these may round, so
+ * the decision is DEFINED as the outcome of exactly this sequence of IEEE fp64
+ * operations (the kernels perform the same sequence).  It differs from the
+ * real-number statement u / 2^24 < p(r) for at most one value of u.
+ */
+int nuqo_quantize_coord_table(float vi, float norm, int s, const float *lev, uint32_t u24)
+{
+    double n = (double)norm;
+    double a = fabs((double)vi);
+    if (!(n > 0.0) || a == 0.0)
+        return 0;
+    int j = 0; /* largest j with l_j * n <= a */
+    for (int t = 1; t <= s + 1; t++)
+        if ((double)lev[t] * n <= a)
+            j = t;
+    if (j == s + 1)
+        return s + 1;
+    double lo_n = (double)lev[j] * n;
+    double hi_n = (double)lev[j + 1] * n;
+    double tau_n = hi_n - lo_n;
+    double x = a - lo_n;
+    double lhs = (double)u24 * tau_n;
+    double rhs = x * 16777216.0;
+    return lhs < rhs ? j + 1 : j;
+}
+
+/* hist[j] += number of draws u in [u_begin, u_end) that give level index j. */
+void nuqo_level_histogram_table(float vi, float norm, int s, const float *lev, uint32_t u_begin,
+                                uint32_t u_end, uint64_t *hist)
+{
+    for (uint32_t u = u_begin; u < u_end; u++)
+        hist[nuqo_quantize_coord_table(vi, norm, s, lev, u)]++;
+}
+
+/* q bytes of a whole vector with the counter generator, as nuqo_quantize. */
+void nuqo_quantize_table(const float *v, uint64_t d, uint32_t bucket, int s, const float *lev,
+                         uint64_t seed, const float *norms, uint64_t first_bucket, uint8_t *q)
+{
+    uint64_t nb = (d + bucket - 1) / bucket;
+    for (uint64_t b = 0; b < nb; b++) {
+        uint32_t k0, k1;
+        nuqo_rng_key(seed, first_bucket + b, &k0, &k1);
+        uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        for (uint64_t i = lo; i < hi; i++) {
+            uint32_t u = nuqo_rng_u24(k0, k1, (uint32_t)(i - lo));
+            int j = nuqo_quantize_coord_table(v[i], norms[b], s, lev, u);
             uint8_t sign = (j > 0 && signbit(v[i])) ? 0x80 : 0;
             q[i] = (uint8_t)j | sign;
         }
@@ -407,9 +497,9 @@ int nuqo_decode_levels(const uint64_t *bit_off, const uint32_t *words, uint64_t 
  * aggregate as in Alg. 1: out = [out +] scale * sum_k Q_k, fp64, workers in
  * order.  out64 has d entries; if accumulate is zero it is overwritten.
  */
-int nuqo_decode_average(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
-                        const uint32_t *const *words, uint64_t d, uint32_t bucket, int s,
-                        double scale, int accumulate, double *out64)
+static int decode_average_any(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                              const uint32_t *const *words, uint64_t d, uint32_t bucket, int s,
+                              const float *lev, double scale, int accumulate, double *out64)
 {
     uint8_t *q = (uint8_t *)malloc(d);
     double *sum = (double *)calloc(d, sizeof(double));
@@ -429,7 +519,7 @@ int nuqo_decode_average(uint32_t K, const float *const *norms, const uint64_t *c
             int j = q[i] & 0x7f;
             if (j == 0)
                 continue;
-            double h = ldexp(1.0, j - 1 - s); /* l_j */
+            double h = lev ? (double)lev[j] : ldexp(1.0, j - 1 - s); /* l_j */
             double val = (double)norms[k][i / bucket] * h;
             sum[i] += (q[i] & 0x80) ? -val : val;
         }
@@ -439,4 +529,19 @@ int nuqo_decode_average(uint32_t K, const float *const *norms, const uint64_t *c
     free(q);
     free(sum);
     return NUQO_OK;
+}
+
+int nuqo_decode_average(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                        const uint32_t *const *words, uint64_t d, uint32_t bucket, int s,
+                        double scale, int accumulate, double *out64)
+{
+    return decode_average_any(K, norms, bit_off, words, d, bucket, s, NULL, scale, accumulate, out64);
+}
+
+/* The same with Q(v_i) = ||v|| * sign * lev[j] for an arbitrary level sequence lev[0..s+1]. */
+int nuqo_decode_average_table(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                              const uint32_t *const *words, uint64_t d, uint32_t bucket, int s,
+                              const float *lev, double scale, int accumulate, double *out64)
+{
+    return decode_average_any(K, norms, bit_off, words, d, bucket, s, lev, scale, accumulate, out64);
 }

@@ -154,3 +154,20 @@ def generate(w: Workload, worker: int, device: str | torch.device = "cpu") -> to
     else:
         raise ValueError(w.kind)
     return out
+
+
+def level_table(kind: str, s: int, p: float = 0.5) -> list[float]:
+    """A level sequence l_0 = 0 < l_1 < ... < l_s < l_{s+1} = 1 to hand to the level-table entry points, as fp32
+    values: "exp" (0, p^s, ..., p^2, p, 1) (p = 1/2: the nonuniform levels of the paper's main scheme),
+    "uniform" (0, 1/(s+1), ..., s/(s+1), 1) (the uniform grid of QSGD).  An input like any other: the method's
+    arithmetic starts where a table is used."""
+    if kind == "exp":
+        vals = [0.0] + [p ** (s + 1 - j) for j in range(1, s + 2)]
+    elif kind == "uniform":
+        vals = [j / (s + 1) for j in range(s + 2)]
+    else:
+        raise ValueError(kind)
+    out = [float(torch.tensor(x, dtype=torch.float64).to(torch.float32)) for x in vals]
+    out[0], out[-1] = 0.0, 1.0
+    assert all(b > a for a, b in zip(out, out[1:])), "levels collapse in fp32"
+    return out
