@@ -152,6 +152,36 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
                           uint32_t bucket, uint32_t s, uint32_t sync_stride, float scale,
                           int accumulate, float *out, nuq_stream_t stream);
 
+/* ---- other level sequences and the maximum norm (Sec. 3.1 before the special case; Sec. 4.1,
+ *      "Generally spaced levels": exponential levels (0, p^s, ..., p, 1); uniform levels = QSGD,
+ *      with the maximum norm = QSGDinf, Sec. 1 and Sec. 2) ------------------------------------ */
+
+/* A level table is s + 2 floats in HOST memory, 0 = levels[0] < levels[1] < ... < levels[s+1] = 1
+ * (anything else: NUQ_EINVAL).  It is read during the call. */
+
+/* norms[b] = max_i |v_i| over bucket b (exact; NaN if the bucket holds a NaN).  Arguments as
+ * nuq_bucket_norms. */
+int nuq_bucket_norms_linf(const float *v, uint64_t d, uint32_t bucket, float *norms,
+                          nuq_stream_t stream);
+
+/* nuq_quantize for the level sequence `levels`: with e_t = levels[t] * norms[b] and a = |v_i|,
+ * j = largest t with e_t <= a (j = s+1: the top level), else j+1 iff
+ * u * (e_{j+1} - e_j) < (a - e_j) * 2^24, evaluated as exactly that sequence of IEEE fp64 operations
+ * (the products e_t are exact; the two differences and the product with u round to nearest), u the
+ * 24-bit draw of nuq_quantize.  For levels[t] = 2^(t-1-s) nothing rounds and q equals nuq_quantize's.
+ * norms may come from nuq_bucket_norms or nuq_bucket_norms_linf; a zero or non-finite norm gives an
+ * all-zero bucket.  q feeds nuq_encode unchanged (a level index is coded the same way whatever its
+ * value). */
+int nuq_quantize_table(const float *v, uint64_t d, uint32_t bucket, uint32_t s, const float *levels,
+                       uint64_t seed, const float *norms, uint8_t *q, nuq_stream_t stream);
+
+/* nuq_decode_accumulate with l_j = levels[j]: out[i] = (accumulate ? out[i] : 0) +
+ * scale * sum_k norms_k[b] * sign * levels[j].  Everything else as nuq_decode_accumulate. */
+int nuq_decode_accumulate_table(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                                const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
+                                uint32_t bucket, uint32_t s, uint32_t sync_stride, const float *levels,
+                                float scale, int accumulate, float *out, nuq_stream_t stream);
+
 /* ---- errors ---------------------------------------------------------------------- */
 
 /* Waits for `stream`, copies the sticky device flags of the current device to

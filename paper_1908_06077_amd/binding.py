@@ -34,6 +34,9 @@ _SIGNATURES = {
     "nuq_encode": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
     "nuq_quantize_encode": (_i32, [_vp, _u64, _u32, _u32, _u64, _u32, _vp, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
     "nuq_decode_accumulate": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _i32, _vp, _vp]),
+    "nuq_bucket_norms_linf": (_i32, [_vp, _u64, _u32, _vp, _vp]),
+    "nuq_quantize_table": (_i32, [_vp, _u64, _u32, _u32, _vp, _u64, _vp, _vp, _vp]),
+    "nuq_decode_accumulate_table": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _f32, _i32, _vp, _vp]),
     "nuq_last_error_flags": (_i32, [_vp, _vp]),
     "nuq_timing_begin": (_i32, [_u32]),
     "nuq_timing_collect": (_i32, [_vp, _vp, _u32, _vp]),
@@ -167,6 +170,43 @@ def nuq_decode_accumulate(messages: list[Message], d: int, bucket: int, s: int, 
     _check("nuq_decode_accumulate",
            _lib.nuq_decode_accumulate(K, norms, offs, words, sync, d, bucket, s, sync_stride, float(scale),
                                       1 if accumulate else 0, _ptr(out, torch.float32), _stream()))
+
+
+# ------------------------------------------- other level sequences, maximum norm
+
+def _levels(levels, s: int):
+    if len(levels) != s + 2:
+        raise ValueError("a level table holds s + 2 values")
+    return (ctypes.c_float * (s + 2))(*[float(x) for x in levels])
+
+
+def nuq_bucket_norms_linf(v: torch.Tensor, bucket: int, norms: torch.Tensor) -> None:
+    _check("nuq_bucket_norms_linf",
+           _lib.nuq_bucket_norms_linf(_ptr(v, torch.float32), v.numel(), bucket, _ptr(norms, torch.float32), _stream()))
+
+
+def nuq_quantize_table(v: torch.Tensor, bucket: int, levels, seed: int, norms: torch.Tensor, q: torch.Tensor) -> None:
+    s = len(levels) - 2
+    _check("nuq_quantize_table",
+           _lib.nuq_quantize_table(_ptr(v, torch.float32), v.numel(), bucket, s, _levels(levels, s),
+                                   seed & (2 ** 64 - 1), _ptr(norms, torch.float32), _ptr(q, torch.uint8), _stream()))
+
+
+def nuq_decode_accumulate_table(messages: list[Message], d: int, bucket: int, levels, sync_stride: int, scale: float,
+                                accumulate: bool, out: torch.Tensor) -> None:
+    K = len(messages)
+    s = len(levels) - 2
+    arr = lambda ts: (ctypes.c_void_p * K)(*[_ptr(t) for t in ts])
+    norms = arr([m.norms for m in messages])
+    offs = arr([m.bit_off for m in messages])
+    words = arr([m.words for m in messages])
+    sync = arr([m.sync for m in messages])
+    if out.numel() != d:
+        raise ValueError("out must hold d floats")
+    _check("nuq_decode_accumulate_table",
+           _lib.nuq_decode_accumulate_table(K, norms, offs, words, sync, d, bucket, s, sync_stride,
+                                            _levels(levels, s), float(scale), 1 if accumulate else 0,
+                                            _ptr(out, torch.float32), _stream()))
 
 
 def nuq_last_error_flags() -> int:

@@ -10,6 +10,7 @@
 #include "nuq_decode_kernels.hpp"
 #include "nuq_device.hpp"
 #include "nuq_encode_kernels.hpp"
+#include "nuq_table_kernels.hpp"
 
 namespace {
 
@@ -62,6 +63,17 @@ uint32_t erc_len_host(uint32_t N)
         N = w - 1;
     }
     return len;
+}
+
+// A level table: s + 2 finite values, 0 = l_0 < l_1 < ... < l_{s+1} = 1.
+bool valid_levels(const float *lev, uint32_t s)
+{
+    if (lev[0] != 0.0f || lev[s + 1] != 1.0f)
+        return false;
+    for (uint32_t j = 0; j <= s; ++j)
+        if (!(lev[j] < lev[j + 1]))
+            return false;
+    return true;
 }
 
 bool valid_common(uint64_t d, uint32_t bucket, uint32_t s)
@@ -228,22 +240,23 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
 }
 
 // Workgroups of the persistent decode kernel that the current device holds at once (0 on error).
-uint32_t decode_resident_workgroups()
+uint32_t decode_resident_workgroups(bool table)
 {
-    static uint32_t cached[64] = {};
+    static uint32_t cached[2][64] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
         return 0;
-    if (!cached[dev]) {
+    if (!cached[table][dev]) {
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(k_decode_accumulate),
-                                                         (int)kDecodeWG, 0) != hipSuccess ||
+        const void *kern = table ? reinterpret_cast<const void *>(k_decode_accumulate<true>)
+                                 : reinterpret_cast<const void *>(k_decode_accumulate<false>);
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, (int)kDecodeWG, 0) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || per_cu < 1 ||
             cus < 1)
             return 0;
-        cached[dev] = (uint32_t)per_cu * (uint32_t)cus;
+        cached[table][dev] = (uint32_t)per_cu * (uint32_t)cus;
     }
-    return cached[dev];
+    return cached[table][dev];
 }
 
 }  // namespace
@@ -325,6 +338,61 @@ int nuq_quantize(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64
     });
 }
 
+int nuq_bucket_norms_linf(const float *v, uint64_t d, uint32_t bucket, float *norms, nuq_stream_t stream)
+{
+    if (!v || !norms || !valid_common(d, bucket, 1) || (reinterpret_cast<uintptr_t>(v) & 3u))
+        return NUQ_EINVAL;
+    EncodeParams P{};
+    EncodeBatch Wk{};
+    Wk.w[0].v = v;
+    Wk.w[0].norms_out = norms;
+    P.d = d;
+    P.bucket = bucket;
+    P.nb = nuq_num_buckets(d, bucket);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
+        constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
+        dim3 grid;
+        if (!bucket_grid<TEAM>(P.nb, 1, grid))
+            return (int)NUQ_EINVAL;
+        ScopedTiming timing(NUQ_T_NORMS, st);
+        hipLaunchKernelGGL((k_bucket_norms_linf<TEAM, VPT>), grid, dim3(TeamGeom<TEAM>::kWG), 0, st, P, Wk);
+        return check_launch();
+    });
+}
+
+int nuq_quantize_table(const float *v, uint64_t d, uint32_t bucket, uint32_t s, const float *levels, uint64_t seed,
+                       const float *norms, uint8_t *q, nuq_stream_t stream)
+{
+    if (!v || !norms || !q || !levels || !valid_common(d, bucket, s) || !valid_levels(levels, s) ||
+        (reinterpret_cast<uintptr_t>(v) & 3u))
+        return NUQ_EINVAL;
+    EncodeParams P{};
+    EncodeBatch Wk{};
+    LevelTable T{};
+    for (uint32_t j = 0; j < s + 2u; ++j)
+        T.lev[j] = levels[j];
+    Wk.w[0].v = v;
+    Wk.w[0].norms_in = norms;
+    Wk.w[0].q_out = q;
+    Wk.w[0].seed = seed;
+    P.d = d;
+    P.bucket = bucket;
+    P.s = s;
+    P.nb = nuq_num_buckets(d, bucket);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
+        constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
+        P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
+        dim3 grid;
+        if (!bucket_grid<TEAM>(P.nb, 1, grid))
+            return (int)NUQ_EINVAL;
+        ScopedTiming timing(NUQ_T_QUANTIZE, st);
+        hipLaunchKernelGGL((k_quantize_table<TEAM, VPT>), grid, dim3(TeamGeom<TEAM>::kWG), 0, st, P, Wk, T);
+        return check_launch();
+    });
+}
+
 int nuq_encode(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint32_t sync_stride, uint64_t *bit_off,
                uint32_t *words, uint64_t words_cap, uint32_t *sync, void *workspace, uint64_t workspace_bytes,
                nuq_stream_t stream)
@@ -373,13 +441,14 @@ int nuq_quantize_encode_batch(uint32_t K, const float *const *v, const uint64_t 
     return encode_batch<0>(K, Wk, d, bucket, s, sync_stride, workspace, workspace_bytes, stream);
 }
 
-int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
-                          const uint32_t *const *words, const uint32_t *const *sync, uint64_t d, uint32_t bucket,
-                          uint32_t s, uint32_t sync_stride, float scale, int accumulate, float *out,
-                          nuq_stream_t stream)
+// levels: nullptr for the levels 2^(j-1-s), else the s + 2 values of a level table (host memory).
+static int decode_accumulate_any(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                                 const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
+                                 uint32_t bucket, uint32_t s, uint32_t sync_stride, const float *levels, float scale,
+                                 int accumulate, float *out, nuq_stream_t stream)
 {
     if (K < 1 || K > NUQ_MAX_WORKERS || !norms || !bit_off || !words || !out || !valid_common(d, bucket, s) ||
-        !valid_sync(sync_stride))
+        !valid_sync(sync_stride) || (levels && !valid_levels(levels, s)))
         return NUQ_EINVAL;
     const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
     if (nsync && !sync)
@@ -435,7 +504,7 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
     while ((2u << P.lanes_shift) * max_streams <= 64u)
         ++P.lanes_shift;
     P.stream_cap = kWordsPerLane << P.lanes_shift;
-    const uint32_t resident = decode_resident_workgroups();
+    const uint32_t resident = decode_resident_workgroups(levels != nullptr);
     if (!resident)
         return NUQ_EHIP;
     // Every resident workgroup slot is used.  Workgroups walk tiles with stride `grid`, so the first
@@ -443,8 +512,36 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
     // CUs, whose parsing waves are the oldest on their SIMDs and run faster than the later ones.
     const uint32_t grid = P.ntiles < resident ? P.ntiles : resident;
     ScopedTiming timing(NUQ_T_DECODE, static_cast<hipStream_t>(stream));
-    hipLaunchKernelGGL(k_decode_accumulate, dim3(grid), dim3(kDecodeWG), 0, static_cast<hipStream_t>(stream), P);
+    if (levels) {
+        for (uint32_t j = 0; j < s + 2u; ++j)
+            P.lev[j] = levels[j];
+        hipLaunchKernelGGL(k_decode_accumulate<true>, dim3(grid), dim3(kDecodeWG), 0,
+                           static_cast<hipStream_t>(stream), P);
+    } else {
+        hipLaunchKernelGGL(k_decode_accumulate<false>, dim3(grid), dim3(kDecodeWG), 0,
+                           static_cast<hipStream_t>(stream), P);
+    }
     return check_launch();
+}
+
+int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                          const uint32_t *const *words, const uint32_t *const *sync, uint64_t d, uint32_t bucket,
+                          uint32_t s, uint32_t sync_stride, float scale, int accumulate, float *out,
+                          nuq_stream_t stream)
+{
+    return decode_accumulate_any(K, norms, bit_off, words, sync, d, bucket, s, sync_stride, nullptr, scale,
+                                 accumulate, out, stream);
+}
+
+int nuq_decode_accumulate_table(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                                const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
+                                uint32_t bucket, uint32_t s, uint32_t sync_stride, const float *levels, float scale,
+                                int accumulate, float *out, nuq_stream_t stream)
+{
+    if (!levels)
+        return NUQ_EINVAL;
+    return decode_accumulate_any(K, norms, bit_off, words, sync, d, bucket, s, sync_stride, levels, scale,
+                                 accumulate, out, stream);
 }
 
 int nuq_last_error_flags(uint32_t *host_flags, nuq_stream_t stream)

@@ -55,6 +55,7 @@ struct DecodeParams {
     uint32_t stream_cap;        // LDS words reserved per stream = kWordsPerLane << lanes_shift
     float scale;
     int accumulate;
+    float lev[16];              // level-table variant: l_0 = 0 .. l_{s+1} = 1
 };
 
 // Branch-free decoder of Alg. 2 for values below 65536 on a 32-bit window (MSB first).
@@ -198,10 +199,13 @@ __device__ __forceinline__ uint32_t level_table_entry(uint32_t p, uint32_t smax)
 //             bits: 0 | 1x0 | 101yy0 | 111yyy0); next position; the pair moves on if the position's word index
 //             did, and the word after the pair is requested
 //   cover   : this record's gap value and index, loop control
-template <class Words>
+//
+// kTable: the value of level j is wnorm * lev[j] (an arbitrary level sequence, lev in LDS) instead of
+// wnorm * 2^j (wnorm = ||v|| * 2^(-1-s)); both are exact in fp64.
+template <bool kTable, class Words>
 __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint16_t *lut, const uint8_t *lut_level,
-                                                 uint32_t bit_lo, uint32_t bit_hi, int forced, uint32_t idx_hi,
-                                                 double wnorm, double *tile_at0, bool &bad)
+                                                 const float *lev, uint32_t bit_lo, uint32_t bit_hi, int forced,
+                                                 uint32_t idx_hi, double wnorm, double *tile_at0, bool &bad)
 {
     uint32_t p31 = bit_lo + 31u;
     const uint32_t end31 = bit_hi + 31u;
@@ -250,7 +254,11 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
         const uint32_t j = e2;
         min_j = min(min_j, j);
         // ||v|| * l_j = (||v|| * 2^(-1-s)) * 2^j, exact in fp64; the sign goes into the top bit
-        const double mag = ldexp(wnorm, (int)j);
+        double mag;
+        if constexpr (kTable)
+            mag = wnorm * (double)lev[j];
+        else
+            mag = ldexp(wnorm, (int)j);
         const uint32_t mh = (uint32_t)((uint64_t)__double_as_longlong(mag) >> 32);
         const uint32_t vh = (mh & 0x7fffffffu) | (w2 & 0x80000000u);
         const uint64_t vb = ((uint64_t)vh << 32) | (uint32_t)__double_as_longlong(mag);
@@ -384,6 +392,7 @@ __device__ __forceinline__ PackedPlan pack_plan(const UnitPlan &U)
     return Q;
 }
 
+template <bool kTable>
 __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams P)
 {
     __shared__ __align__(16) double tile[kTileCoords];
@@ -393,6 +402,11 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     __shared__ TileGeom next_geom;                // of the tile being prepared, for the wave that did not compute it
     __shared__ uint16_t lut[128];
     __shared__ uint8_t lut_level[128];
+    float *lev = nullptr;                         // level values (level-table variant only)
+    if constexpr (kTable) {
+        __shared__ float lev_s[16];
+        lev = lev_s;
+    }
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & (kWave - 1u);
@@ -400,7 +414,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     const bool partial = !P.buckets_per_tile;        // tiles are parts of one bucket
     const bool walk = partial && !P.sync_shift;      // no index: every tile walks its bucket from the start
     const uint64_t last_bucket = P.nb - 1u;
-    const double wscale = ldexp(1.0, -1 - (int)P.s);
+    const double wscale = kTable ? 1.0 : ldexp(1.0, -1 - (int)P.s);
 
     // Unit u of a tile is (bucket in tile bi, segment g, worker k), k fastest.
     auto unit_coords = [&](const TileGeom &G, uint32_t u, uint32_t &k, uint32_t &bi, uint32_t &g) {
@@ -490,7 +504,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
                              bool &bad) {
         const uint32_t nbk = G.b0 + bi == last_bucket ? last_len : P.bucket;
         const uint32_t idx_hi = P.sync_shift ? min(nbk, (g + 1u) << P.sync_shift) : nbk;
-        decode_unit_fast(StagedWords{buf + (Q.where & 0xFFFu)}, lut, lut_level, Q.bits & 0xFFFFu, Q.bits >> 16,
+        decode_unit_fast<kTable>(StagedWords{buf + (Q.where & 0xFFFu)}, lut, lut_level, lev, Q.bits & 0xFFFFu, Q.bits >> 16,
                          (int)(Q.where >> 16) - 1, idx_hi, (double)Q.norm * wscale, tile_origin(G, bi), bad);
     };
     // Any unit, from scratch: units beyond the planned ones and units whose words were not staged.
@@ -504,7 +518,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         if (X.kind == 1)
             parse_planned(G, bi, g, buf, pack_plan(X), bad);
         else if (X.kind == 2)
-            decode_unit_fast(GlobalWords{P.words[k] + X.first_word, X.nwords - 1u}, lut, lut_level, X.bit_lo, X.bit_hi,
+            decode_unit_fast<kTable>(GlobalWords{P.words[k] + X.first_word, X.nwords - 1u}, lut, lut_level, lev, X.bit_lo, X.bit_hi,
                              X.forced,
                              X.idx_hi, (double)X.norm * wscale, tile_origin(G, bi), bad);
     };
@@ -542,7 +556,11 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             if ((uint32_t)idx >= hi_idx)
                 break;
             if ((uint32_t)idx >= G.in_lo) {
-                const double val = ldexp(wnorm, (int)j);
+                double val;
+                if constexpr (kTable)
+                    val = wnorm * (double)lev[j];
+                else
+                    val = ldexp(wnorm, (int)j);
                 atomicAdd(&tile[(uint32_t)idx - G.in_lo], neg ? -val : val);
             }
             br.skip(rl);
@@ -629,6 +647,10 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
         lut[lane] = (uint16_t)gap_table_entry(lane);
         lut[lane + kWave] = (uint16_t)gap_table_entry(lane + kWave);
+        if constexpr (kTable) {
+            if (lane < 16u)
+                lev[lane] = P.lev[lane];
+        }
         lut_level[lane] = (uint8_t)level_table_entry(lane, P.s + 1u);
         lut_level[lane + kWave] = (uint8_t)level_table_entry(lane + kWave, P.s + 1u);
         if (lane < 5u)

@@ -63,3 +63,16 @@ def test_argument_errors_are_reported_on_the_host(nuq):
     lib.nuq_last_error_flags.restype = ctypes.c_int
     lib.nuq_last_error_flags.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     assert lib.nuq_last_error_flags(None, None) == EINVAL
+    # level tables (host arrays) are validated before anything is launched
+    lib.nuq_quantize_table.restype = ctypes.c_int
+    lib.nuq_quantize_table.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
+                                       ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    table = lambda *xs: (ctypes.c_float * len(xs))(*xs)
+    assert lib.nuq_quantize_table(16, 10, 4, 3, None, 0, 16, 16, None) == EINVAL                            # no table
+    assert lib.nuq_quantize_table(16, 10, 4, 3, table(0, .25, .5, .5, 1), 0, 16, 16, None) == EINVAL        # not increasing
+    assert lib.nuq_quantize_table(16, 10, 4, 3, table(.1, .25, .5, .75, 1), 0, 16, 16, None) == EINVAL      # l_0 != 0
+    assert lib.nuq_quantize_table(16, 10, 4, 3, table(0, .25, .5, .75, .9), 0, 16, 16, None) == EINVAL      # l_{s+1} != 1
+    assert lib.nuq_quantize_table(16, 10, 4, 3, table(0, .25, float("nan"), .75, 1), 0, 16, 16, None) == EINVAL
+    lib.nuq_bucket_norms_linf.restype = ctypes.c_int
+    lib.nuq_bucket_norms_linf.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.nuq_bucket_norms_linf(None, 10, 4, None, None) == EINVAL
