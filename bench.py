@@ -39,6 +39,12 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy before the timed region (a known-size reference "
                          "for hardware-counter runs)")
+    ap.add_argument("--levels", default="nuq",
+                    help="level sequence: nuq (the paper's main scheme, levels 2^(j-1-s): the default path), "
+                         "uniform (QSGD's grid) or exp:P (0, P^s, ..., P, 1); anything but nuq runs the level-table "
+                         "entry points")
+    ap.add_argument("--norm", default="l2", choices=["l2", "linf"],
+                    help="bucket norm for a level table: Euclidean, or maximum (QSGDinf with --levels uniform)")
     ap.add_argument("--reference-kernels", action="store_true",
                     help="also time PyTorch's own sum, copy and fill over a tensor of the step's input size and add "
                          "them to the line as `reference` (what library streaming kernels reach on this GPU: context "
@@ -83,24 +89,45 @@ def main():
                            torch.empty(B + 1, dtype=torch.int64, device=dev),
                            torch.zeros(nwords, dtype=torch.int32, device=dev),
                            torch.empty(max(1, B * nsync), dtype=torch.int32, device=dev))
+    # a level table only when one is asked for: the default is the main scheme's own entry points
+    lev = None
+    if args.levels != "nuq" or args.norm != "l2":
+        kind, _, pstr = args.levels.partition(":")
+        lev = workloads.level_table("exp" if kind in ("nuq", "exp") else kind, s, float(pstr) if pstr else 0.5)
+    norm_kind = nuq.NORM_LINF if args.norm == "linf" else nuq.NORM_L2
+
+    def encode_batch(messages):
+        if lev is not None:
+            nuq.nuq_quantize_encode_table_batch(grads, n, lev, norm_kind, seeds, S, messages, ws)
+        else:
+            nuq.nuq_quantize_encode_batch(grads, n, s, seeds, S, messages, ws)
+
     probes = [new_msg(16) for _ in range(K)]
-    nuq.nuq_quantize_encode_batch(grads, n, s, seeds, S, probes, ws)
+    encode_batch(probes)
     nuq.nuq_last_error_flags()
     msgs = [new_msg((int(p.bit_off[-1].item()) + 31) // 32 + 64) for p in probes]
     del probes
     out = torch.empty(d, dtype=torch.float32, device=dev)
 
     def encode_all():
-        if args.per_worker_calls:
+        if lev is not None:
+            encode_batch(msgs)
+        elif args.per_worker_calls:
             for k in range(K):
                 m = msgs[k]
                 nuq.nuq_quantize_encode(grads[k], n, s, seeds[k], S, m.norms, m.bit_off, m.words, m.sync, ws)
         else:
             nuq.nuq_quantize_encode_batch(grads, n, s, seeds, S, msgs, ws)
 
+    def decode_all():
+        if lev is not None:
+            nuq.nuq_decode_accumulate_table(msgs, d, n, lev, S, 1.0 / K, False, out)
+        else:
+            nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
+
     def step():
         encode_all()
-        nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
+        decode_all()
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -130,7 +157,7 @@ def main():
         e[0].record()
         encode_all()
         e[1].record()
-        nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
+        decode_all()
         e[2].record()
     torch.cuda.synchronize()
 
@@ -171,8 +198,9 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "configs[%d] %s: d=%d fp32, bucket=%d, s=%d, K=%d workers, sync_stride=%d"
-                               % (args.config - 1, w.name, d, n, s, K, S)},
+        "config": {"workload": "configs[%d] %s: d=%d fp32, bucket=%d, s=%d, K=%d workers, sync_stride=%d%s"
+                               % (args.config - 1, w.name, d, n, s, K, S,
+                                  "" if lev is None else ", level table %s, %s norm" % (args.levels, args.norm))},
         "phases": {
             "quantize_encode": {"ms": round(ms_enc, 4), "fp32_in_GBps": round(in_bytes / (ms_enc * 1e-3) / 1e9, 2),
                                 "hbm_frac": round(sum(enc_alg) / (ms_enc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
@@ -197,7 +225,7 @@ def main():
     if args.reference_kernels:
         result["reference"] = reference_kernels(torch, d * K, dev)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, grads, S)
+        result["cpu_baseline"] = cpu_baseline(w, grads, S, lev, args.norm)
     print(json.dumps(result))
 
 
@@ -240,7 +268,7 @@ def measured_traffic(kernel, config, S):
     return None if entry is None else entry.get("bytes_per_launch")
 
 
-def cpu_baseline(w, grads, S):
+def cpu_baseline(w, grads, S, lev=None, norm="l2"):
     """The CPU oracle as it stands, one thread, on the same workload (bounded to ~30 s of CPU work)."""
     import numpy as np
     import oracle
@@ -253,12 +281,19 @@ def cpu_baseline(w, grads, S):
     t0 = time.perf_counter()
     parts = []
     for k in range(K):
-        norms = oracle.bucket_norms(host[k], n).astype(np.float32)
-        q = oracle.quantize(host[k], n, s, w.quant_seed(k), norms)
+        norms = (oracle.bucket_norms_linf if norm == "linf" else oracle.bucket_norms)(host[k], n).astype(np.float32)
+        if lev is None:
+            q = oracle.quantize(host[k], n, s, w.quant_seed(k), norms)
+        else:
+            q = oracle.quantize_table(host[k], n, lev, w.quant_seed(k), norms)
         bo, words, _ = oracle.encode(q, n, s, S)
         parts.append((norms, bo, words))
     t1 = time.perf_counter()
-    oracle.decode_average([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], d_s, n, s, 1.0 / K)
+    if lev is None:
+        oracle.decode_average([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], d_s, n, s, 1.0 / K)
+    else:
+        oracle.decode_average_table([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], d_s, n, lev,
+                                    1.0 / K)
     t2 = time.perf_counter()
     in_bytes = 4.0 * d_s * K
     return {"value": round(in_bytes / (t2 - t0) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",

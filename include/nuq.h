@@ -156,6 +156,9 @@ int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t 
  *      "Generally spaced levels": exponential levels (0, p^s, ..., p, 1); uniform levels = QSGD,
  *      with the maximum norm = QSGDinf, Sec. 1 and Sec. 2) ------------------------------------ */
 
+#define NUQ_NORM_L2 0u   /* Euclidean norm of the bucket */
+#define NUQ_NORM_LINF 1u /* maximum norm of the bucket   */
+
 /* A level table is s + 2 floats in HOST memory, 0 = levels[0] < levels[1] < ... < levels[s+1] = 1
  * (anything else: NUQ_EINVAL).  It is read during the call. */
 
@@ -174,6 +177,18 @@ int nuq_bucket_norms_linf(const float *v, uint64_t d, uint32_t bucket, float *no
  * value). */
 int nuq_quantize_table(const float *v, uint64_t d, uint32_t bucket, uint32_t s, const float *levels,
                        uint64_t seed, const float *norms, uint8_t *q, nuq_stream_t stream);
+
+/* nuq_quantize_encode_batch for the level sequence `levels` and the norm `norm_kind` (NUQ_NORM_L2:
+ * as nuq_bucket_norms; NUQ_NORM_LINF: as nuq_bucket_norms_linf): v is read once; worker k's norms are
+ * what the norm entry point gives and its message is what
+ * nuq_encode(nuq_quantize_table(v[k], ..., levels, seeds[k], norms[k])) gives.  Other arguments as
+ * nuq_quantize_encode_batch. */
+int nuq_quantize_encode_table_batch(uint32_t K, const float *const *v, const uint64_t *seeds, uint64_t d,
+                                    uint32_t bucket, uint32_t s, const float *levels, uint32_t norm_kind,
+                                    uint32_t sync_stride, float *const *norms, uint64_t *const *bit_off,
+                                    uint32_t *const *words, const uint64_t *words_cap,
+                                    uint32_t *const *sync, void *workspace, uint64_t workspace_bytes,
+                                    nuq_stream_t stream);
 
 /* nuq_decode_accumulate with l_j = levels[j]: out[i] = (accumulate ? out[i] : 0) +
  * scale * sum_k norms_k[b] * sign * levels[j].  Everything else as nuq_decode_accumulate. */

@@ -36,6 +36,8 @@ _SIGNATURES = {
     "nuq_decode_accumulate": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _i32, _vp, _vp]),
     "nuq_bucket_norms_linf": (_i32, [_vp, _u64, _u32, _vp, _vp]),
     "nuq_quantize_table": (_i32, [_vp, _u64, _u32, _u32, _vp, _u64, _vp, _vp, _vp]),
+    "nuq_quantize_encode_table_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _vp, _u32, _u32, _vp, _vp, _vp, _vp, _vp,
+                                               _vp, _u64, _vp]),
     "nuq_decode_accumulate_table": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _f32, _i32, _vp, _vp]),
     "nuq_last_error_flags": (_i32, [_vp, _vp]),
     "nuq_timing_begin": (_i32, [_u32]),
@@ -190,6 +192,29 @@ def nuq_quantize_table(v: torch.Tensor, bucket: int, levels, seed: int, norms: t
     _check("nuq_quantize_table",
            _lib.nuq_quantize_table(_ptr(v, torch.float32), v.numel(), bucket, s, _levels(levels, s),
                                    seed & (2 ** 64 - 1), _ptr(norms, torch.float32), _ptr(q, torch.uint8), _stream()))
+
+
+NORM_L2, NORM_LINF = 0, 1
+
+
+def nuq_quantize_encode_table_batch(vs: list[torch.Tensor], bucket: int, levels, norm_kind: int, seeds: list[int],
+                                    sync_stride: int, messages: list["Message"], workspace: torch.Tensor) -> None:
+    K = len(vs)
+    d = vs[0].numel()
+    s = len(levels) - 2
+    if any(v.numel() != d for v in vs) or len(seeds) != K or len(messages) != K:
+        raise ValueError("K gradients of equal length, K seeds and K messages are needed")
+    arr = lambda ts, dt=None: (ctypes.c_void_p * K)(*[_ptr(t, dt) for t in ts])
+    u64s = lambda xs: (ctypes.c_uint64 * K)(*[x & (2 ** 64 - 1) for x in xs])
+    _check("nuq_quantize_encode_table_batch",
+           _lib.nuq_quantize_encode_table_batch(K, arr(vs, torch.float32), u64s(seeds), d, bucket, s,
+                                                _levels(levels, s), norm_kind, sync_stride,
+                                                arr([m.norms for m in messages], torch.float32),
+                                                arr([m.bit_off for m in messages], torch.int64),
+                                                arr([m.words for m in messages], torch.int32),
+                                                u64s([m.words.numel() for m in messages]),
+                                                arr([m.sync for m in messages]), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size(), _stream()))
 
 
 def nuq_decode_accumulate_table(messages: list[Message], d: int, bucket: int, levels, sync_stride: int, scale: float,

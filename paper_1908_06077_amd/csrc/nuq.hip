@@ -156,20 +156,29 @@ bool bucket_grid(uint64_t nb, uint32_t K, dim3 &grid)
     return true;
 }
 
-// MODE 0: fused norms + quantize + ENCODE from v.  MODE 1: ENCODE from level/sign bytes.
+// MODE 0: fused norms + quantize + ENCODE from v.  MODE 1: ENCODE from level/sign bytes.  MODE 2: as 0 with the
+// level table `levels` (host memory, s + 2 values) and the norm `norm_kind` selects.
 template <int MODE>
 int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket, uint32_t s, uint32_t sync_stride,
-                 void *workspace, uint64_t workspace_bytes, nuq_stream_t stream)
+                 void *workspace, uint64_t workspace_bytes, nuq_stream_t stream, const float *levels = nullptr,
+                 uint32_t norm_kind = NUQ_NORM_L2)
 {
     if (K < 1 || K > kMaxBatch || !valid_common(d, bucket, s) || !valid_sync(sync_stride) || !workspace ||
         (reinterpret_cast<uintptr_t>(workspace) & 15u))
         return NUQ_EINVAL;
+    LevelTable T{};
+    if (MODE == 2) {
+        if (!levels || !valid_levels(levels, s) || (norm_kind != NUQ_NORM_L2 && norm_kind != NUQ_NORM_LINF))
+            return NUQ_EINVAL;
+        for (uint32_t j = 0; j < s + 2u; ++j)
+            T.lev[j] = levels[j];
+    }
     const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
     for (uint32_t k = 0; k < K; ++k) {
         const EncodeWorker &w = Wk.w[k];
         if (!w.bit_off || !w.words || (nsync && !w.sync))
             return NUQ_EINVAL;
-        if (MODE == 0 && (!w.v || !w.norms_out || (reinterpret_cast<uintptr_t>(w.v) & 3u)))
+        if (MODE != 1 && (!w.v || !w.norms_out || (reinterpret_cast<uintptr_t>(w.v) & 3u)))
             return NUQ_EINVAL;
         if (MODE == 1 && !w.q_in)
             return NUQ_EINVAL;
@@ -196,6 +205,7 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
     P.lens = w.lens;
     P.staging = w.staging;
     P.flags = flags;
+    P.norm_linf = norm_kind == NUQ_NORM_LINF ? 1u : 0u;
     int rc = dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
         constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
         using G = TeamGeom<TEAM>;
@@ -214,8 +224,8 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
         dim3 grid;
         if (!bucket_grid<TEAM>(nb, K, grid))
             return (int)NUQ_EINVAL;
-        ScopedTiming timing(MODE == 0 ? NUQ_T_QUANTIZE_ENCODE : NUQ_T_ENCODE, st);
-        hipLaunchKernelGGL(kern, grid, dim3(G::kWG), lds_bytes, st, P, Wk);
+        ScopedTiming timing(MODE == 1 ? NUQ_T_ENCODE : NUQ_T_QUANTIZE_ENCODE, st);
+        hipLaunchKernelGGL(kern, grid, dim3(G::kWG), lds_bytes, st, P, Wk, T);
         return check_launch();
     });
     if (rc != NUQ_OK)
@@ -522,6 +532,27 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
                            static_cast<hipStream_t>(stream), P);
     }
     return check_launch();
+}
+
+int nuq_quantize_encode_table_batch(uint32_t K, const float *const *v, const uint64_t *seeds, uint64_t d,
+                                    uint32_t bucket, uint32_t s, const float *levels, uint32_t norm_kind,
+                                    uint32_t sync_stride, float *const *norms, uint64_t *const *bit_off,
+                                    uint32_t *const *words, const uint64_t *words_cap, uint32_t *const *sync,
+                                    void *workspace, uint64_t workspace_bytes, nuq_stream_t stream)
+{
+    if (K < 1 || K > kMaxBatch || !v || !seeds || !norms || !bit_off || !words || !words_cap || !levels)
+        return NUQ_EINVAL;
+    EncodeBatch Wk{};
+    for (uint32_t k = 0; k < K; ++k) {
+        Wk.w[k].v = v[k];
+        Wk.w[k].seed = seeds[k];
+        Wk.w[k].norms_out = norms[k];
+        Wk.w[k].bit_off = bit_off[k];
+        Wk.w[k].words = words[k];
+        Wk.w[k].words_cap = words_cap[k];
+        Wk.w[k].sync = sync ? sync[k] : nullptr;
+    }
+    return encode_batch<2>(K, Wk, d, bucket, s, sync_stride, workspace, workspace_bytes, stream, levels, norm_kind);
 }
 
 int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,

@@ -349,4 +349,81 @@ __device__ __forceinline__ int team_exclusive_max(int v, int ident, int *scratch
     return exc;
 }
 
+// --------------------------------------------------------- level tables (arbitrary level sequences)
+//
+// Def. 1 for any 0 = l_0 < l_1 < ... < l_{s+1} = 1 (Sec. 3.1 before the special case; Sec. 4.1 "Generally spaced
+// levels").  The decision is the outcome of this sequence of IEEE fp64 operations (each rounded to nearest; the
+// products of two fp32 values are exact):
+//   e_t = l_t * ||v||;  j = largest t with e_t <= |v_i| (s+1: the top level, no draw);
+//   tau = e_{j+1} - e_j;  x = |v_i| - e_j;  up iff u * tau < x * 2^24.
+// On levels that are powers of two nothing rounds and this is the rule of the main quantizer.
+
+struct LevelTable {
+    float lev[16];   // lev[0] = 0 ... lev[s+1] = 1; entries above s+1 are 0
+};
+
+// Maximum of x over the team; every thread returns it.  scratch: 16 words of LDS (teams of several waves).
+template <int TEAM>
+__device__ __forceinline__ uint32_t team_max_u32(uint32_t x, uint32_t *scratch)
+{
+    constexpr int kLanes = TEAM < kWave ? TEAM : kWave;
+#pragma unroll
+    for (int off = kLanes / 2; off >= 1; off >>= 1)
+        x = max(x, (uint32_t)__shfl_xor((int)x, off, kWave));
+    if constexpr (TEAM > kWave) {
+        const uint32_t wave = threadIdx.x / kWave;
+        __syncthreads();
+        if ((threadIdx.x & (kWave - 1)) == 0)
+            scratch[wave] = x;
+        __syncthreads();
+        x = scratch[0];
+#pragma unroll
+        for (int w = 1; w < TEAM / kWave; ++w)
+            x = max(x, scratch[w]);
+    }
+    return x;
+}
+
+// Level|sign bytes of four coordinates whose first has in-bucket index idx0 (+ k0), for the bucket whose edges
+// e_t = l_t * ||v|| lie in LDS (e1 = edges[1]).  Called by whole waves: the first-bin route is chosen per wave.
+__device__ __forceinline__ uint32_t quantize_table_vec4(const float4 &x, uint32_t counter0, uint32_t k1,
+                                                        const double *edges, double e1, uint32_t s, bool dead)
+{
+    const float xs[4] = {x.x, x.y, x.z, x.w};
+    const float big = fmaxf(fmaxf(fabsf(xs[0]), fabsf(xs[1])), fmaxf(fabsf(xs[2]), fabsf(xs[3])));
+    uint32_t levels = 0;
+    if (!dead) {
+        if (__all(!((double)big >= e1))) {          // every coordinate of every lane below the first level
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t u = draw24((counter0 + (uint32_t)c) * kRngC1, k1);
+                const double a = (double)fabsf(xs[c]);
+                levels |= ((double)u * e1 < a * 16777216.0 ? 1u : 0u) << (8 * c);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t u = draw24((counter0 + (uint32_t)c) * kRngC1, k1);
+                const double a = (double)fabsf(xs[c]);
+                uint32_t j = 0;
+                for (uint32_t t = 1; t <= s + 1u; ++t)
+                    j += edges[t] <= a ? 1u : 0u;   // the levels increase: the count is the largest index
+                if (j <= s) {
+                    const double lo = edges[j], hi = edges[j + 1u];
+                    const double tau = hi - lo;
+                    const double over = a - lo;
+                    j += (double)u * tau < over * 16777216.0 ? 1u : 0u;
+                }
+                levels |= j << (8 * c);
+            }
+        }
+    }
+    // sign bytes of the four coordinates, kept where the level is not zero (a level is below 128)
+    const uint32_t v01 = __builtin_amdgcn_perm(f2u(xs[1]), f2u(xs[0]), 0x0c0c0703u);
+    const uint32_t v23 = __builtin_amdgcn_perm(f2u(xs[3]), f2u(xs[2]), 0x0c0c0703u);
+    const uint32_t sg = __builtin_amdgcn_perm(v23, v01, 0x05040100u);
+    const uint32_t nz7 = (levels + 0x7f7f7f7fu) & 0x80808080u;
+    return (sg & nz7) | levels;
+}
+
 }  // namespace nuq

@@ -48,6 +48,7 @@ struct EncodeParams {
     uint32_t *lens;        // [K * nb_stride] payload bits per bucket, worker-major
     uint32_t *staging;     // [K * nb * slot_words]
     uint32_t *flags;
+    uint32_t norm_linf;    // level-table mode: 0 = Euclidean norm, 1 = maximum norm
 };
 
 template <int TEAM>
@@ -312,7 +313,8 @@ __device__ __forceinline__ void team_barrier()
 // exceeds one of them takes a slower way around it:
 //   nonzeros fit, bits fit  : compacted index list, balanced record runs, bit string assembled in LDS
 //   nonzeros fit, bits don't: the same, but records are OR-ed into the (zeroed) staging slot in global memory
-//   nonzeros don't fit      : every thread codes the records of its own chunk, into the staging slot
+//   nonzeros don't fit      : every thread codes the records of its own chunk; the bit string is assembled in LDS
+//                             over the list's and the buffer's words together if it fits there, else in the slot
 template <int TEAM, int VPT>
 __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const EncodeWorker &W, bool active, uint64_t b,
                                                 const uint32_t *qb32, uint32_t *out, uint16_t *rec,
@@ -433,12 +435,16 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     uint32_t total;
     const uint32_t off0 = team_exclusive_sum<TEAM>(bits, scratch + 32, total);
     const uint32_t nwords = (total + 31u) >> 5;
-    const bool in_lds = listed && nwords <= P.out_cap;           // uniform over the team
+    // An unlisted bucket does not use the index list, so its bit string may spread over the list's LDS as well
+    // (the two regions are adjacent): three quarters of the worst case for large buckets.
+    uint32_t *const obuf = listed ? out : reinterpret_cast<uint32_t *>(rec);
+    const uint32_t ocap = listed ? P.out_cap : (P.rec_cap + 1u) / 2u + P.out_cap;
+    const bool in_lds = nwords <= ocap;                          // uniform over the team
     const uint64_t gb = (uint64_t)blockIdx.y * P.nb + b;         // bucket index over the whole batch
     uint32_t *slot = P.staging + (active ? gb : 0) * P.slot_words;
     if (in_lds) {
         for (uint32_t i = tid; i < nwords; i += TEAM)
-            out[i] = 0u;
+            obuf[i] = 0u;
     } else if (active) {
         for (uint32_t i = tid; i < nwords; i += TEAM)
             slot[i] = 0u;
@@ -490,7 +496,7 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
             }
         };
         if (in_lds)
-            emit_all(out);
+            emit_all(obuf);
         else if (active)
             emit_all(slot);
     }
@@ -498,7 +504,7 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     if (active) {
         if (in_lds)
             for (uint32_t i = tid; i < nwords; i += TEAM)
-                slot[i] = out[i];
+                slot[i] = obuf[i];
         uint32_t *sg = W.sync + b * P.nsync;
         for (uint32_t i = tid; i < P.nsync; i += TEAM)
             sg[i] = sync_l[i];
@@ -531,9 +537,10 @@ __host__ __device__ inline uint32_t team_lds_words(uint32_t rows, uint32_t team,
     return w + 64u;
 }
 
-// MODE 0: fused norms + quantize + encode from v.  MODE 1: encode from level/sign bytes.
+// MODE 0: fused norms + quantize + encode from v.  MODE 1: encode from level/sign bytes.  MODE 2: as 0 for the level
+// table T and the norm P.norm_linf selects (T is ignored in the other modes).
 template <int TEAM, int VPT, int MODE>
-__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, EncodeBatch Wk)
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, EncodeBatch Wk, LevelTable T)
 {
     extern __shared__ __align__(16) uint32_t smem[];
     const EncodeWorker &W = Wk.w[blockIdx.y];
@@ -557,7 +564,49 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
     const uint64_t base = active ? b * P.bucket : 0;
     const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
 
-    if constexpr (MODE == 0) {
+    if constexpr (MODE == 2) {
+        __shared__ double edges_all[TeamGeom<TEAM>::kTeamsPerWG][16];
+        double *edges = edges_all[threadIdx.x / TEAM];
+        const float *vb = W.v + base;
+        const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
+        float4 x[VPT];
+#pragma unroll
+        for (int i = 0; i < VPT; ++i)
+            x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
+        float nrm;
+        if (P.norm_linf) {
+            uint32_t m = 0;
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) {
+                m = max(max(m, f2u(x[i].x) & 0x7fffffffu), f2u(x[i].y) & 0x7fffffffu);
+                m = max(max(m, f2u(x[i].z) & 0x7fffffffu), f2u(x[i].w) & 0x7fffffffu);
+            }
+            nrm = u2f(team_max_u32<TEAM>(m, scratch));
+        } else {
+            auto row = [&](int i) { return x[i]; };
+            nrm = team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32));
+        }
+        nrm = team_uniform_f32<TEAM>(nrm);
+        const bool finite = nrm < __builtin_huge_valf();   // false for NaN too
+        if (active && tid == 0) {
+            W.norms_out[b] = nrm;
+            if (!finite)
+                atomicOr(P.flags, kFlagNonfinite);
+        }
+        const bool dead = !(nrm > 0.0f) || !finite;
+        if (tid < 16u)
+            edges[tid] = (double)T.lev[tid] * (double)nrm;
+        team_barrier<TEAM>();
+        const double e1 = edges[1];
+        const BucketKey key = bucket_key(W.seed, b);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            if ((uint32_t)i < P.rows) {
+                const uint32_t vi = (uint32_t)i * TEAM + tid;
+                qb32[vi] = quantize_table_vec4(x[i], key.k0 + 4u * vi, key.k1, edges, e1, P.s, dead);
+            }
+        }
+    } else if constexpr (MODE == 0) {
         const float *vb = W.v + base;
         const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
         float4 x[VPT];

@@ -8,32 +8,6 @@
 
 namespace nuq {
 
-struct LevelTable {
-    float lev[16];   // lev[0] = 0 ... lev[s+1] = 1; entries above s+1 are 0
-};
-
-// Maximum of x over the team; every thread returns it.  scratch: 16 words of LDS per workgroup (teams of several waves).
-template <int TEAM>
-__device__ __forceinline__ uint32_t team_max_u32(uint32_t x, uint32_t *scratch)
-{
-    constexpr int kLanes = TEAM < kWave ? TEAM : kWave;
-#pragma unroll
-    for (int off = kLanes / 2; off >= 1; off >>= 1)
-        x = max(x, (uint32_t)__shfl_xor((int)x, off, kWave));
-    if constexpr (TEAM > kWave) {
-        const uint32_t wave = threadIdx.x / kWave;
-        __syncthreads();
-        if ((threadIdx.x & (kWave - 1)) == 0)
-            scratch[wave] = x;
-        __syncthreads();
-        x = scratch[0];
-#pragma unroll
-        for (int w = 1; w < TEAM / kWave; ++w)
-            x = max(x, scratch[w]);
-    }
-    return x;
-}
-
 // norms_out[b] = max_i |v_i| over bucket b: exact.  Bit patterns of non-negative floats order like the floats, and a
 // NaN's pattern lies above every number's, so a NaN coordinate makes the norm NaN.
 template <int TEAM, int VPT>
@@ -60,11 +34,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_bucket_norms_linf(Encod
         W.norms_out[b] = u2f(m);
 }
 
-// q bytes for an arbitrary level table.  The decision is the outcome of this sequence of IEEE fp64 operations (each
-// rounded to nearest; the products of two fp32 values are exact):
-//   e_t = l_t * ||v||;  j = largest t with e_t <= |v_i| (s+1: the top level, no draw);
-//   tau = e_{j+1} - e_j;  x = |v_i| - e_j;  up iff u * tau < x * 2^24.
-// On levels that are powers of two nothing rounds and this is the rule of the main quantizer.
+// q bytes for an arbitrary level table (quantize_table_vec4), one bucket per team.
 template <int TEAM, int VPT>
 __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize_table(EncodeParams P, EncodeBatch Wk, LevelTable T)
 {
@@ -94,40 +64,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_quantize_table(EncodePa
         const uint32_t e0 = 4u * vi;
         const bool mine = e0 < nbk;                     // lanes beyond the bucket's end run along with zeros
         const float4 x = mine ? load_vec4(vb, vi, nbk, aligned) : float4{0.f, 0.f, 0.f, 0.f};
-        const float xs[4] = {x.x, x.y, x.z, x.w};
-        const float big = fmaxf(fmaxf(fabsf(xs[0]), fabsf(xs[1])), fmaxf(fabsf(xs[2]), fabsf(xs[3])));
-        uint32_t levels = 0;
-        if (!dead) {
-            if (__all(!((double)big >= e1))) {          // every coordinate of every lane below the first level
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const uint32_t u = draw24((key.k0 + e0 + (uint32_t)c) * kRngC1, key.k1);
-                    const double a = (double)fabsf(xs[c]);
-                    levels |= ((double)u * e1 < a * 16777216.0 ? 1u : 0u) << (8 * c);
-                }
-            } else {
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const uint32_t u = draw24((key.k0 + e0 + (uint32_t)c) * kRngC1, key.k1);
-                    const double a = (double)fabsf(xs[c]);
-                    uint32_t j = 0;
-                    for (uint32_t t = 1; t <= P.s + 1u; ++t)
-                        j += edges[t] <= a ? 1u : 0u;   // the levels increase: the count is the largest index
-                    if (j <= P.s) {
-                        const double lo = edges[j], hi = edges[j + 1u];
-                        const double tau = hi - lo;
-                        const double over = a - lo;
-                        j += (double)u * tau < over * 16777216.0 ? 1u : 0u;
-                    }
-                    levels |= j << (8 * c);
-                }
-            }
-        }
-        const uint32_t v01 = __builtin_amdgcn_perm(f2u(xs[1]), f2u(xs[0]), 0x0c0c0703u);
-        const uint32_t v23 = __builtin_amdgcn_perm(f2u(xs[3]), f2u(xs[2]), 0x0c0c0703u);
-        const uint32_t sg = __builtin_amdgcn_perm(v23, v01, 0x05040100u);
-        const uint32_t nz7 = (levels + 0x7f7f7f7fu) & 0x80808080u;
-        const uint32_t packed = (sg & nz7) | levels;
+        const uint32_t packed = quantize_table_vec4(x, key.k0 + e0, key.k1, edges, e1, P.s, dead);
         if (mine) {
             if (qaligned && e0 + 3u < nbk) {
                 reinterpret_cast<uint32_t *>(qb)[vi] = packed;

@@ -58,7 +58,7 @@ def test_norms_quantizer_message_and_average_match_oracle(g, d, n, tname, norm, 
     S = 256 if n > 256 else 0
     rng = np.random.default_rng(d + n + s)
     K = 3
-    msgs, msgs_np = [], []
+    msgs, msgs_np, vs = [], [], []
     for k in range(K):
         v_np = make_vector(kind, d, n, rng)
         v = torch.from_numpy(v_np).to(g.DEV)
@@ -89,6 +89,18 @@ def test_norms_quantizer_message_and_average_match_oracle(g, d, n, tname, norm, 
             np.testing.assert_array_equal(g.u32(m.sync)[: sync.size], sync)
         msgs.append(m)
         msgs_np.append((norms_np, bo, words))
+        vs.append(v)
+    # the fused call (v read once, all workers in one launch) gives the same norms and messages, bit for bit
+    fused = [g.alloc_message(d, n, s, S) for _ in range(K)]
+    ws = torch.empty(nuq.nuq_encode_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_quantize_encode_table_batch(vs, n, lev, nuq.NORM_LINF if norm == "linf" else nuq.NORM_L2,
+                                        [77 + k for k in range(K)], S, fused, ws)
+    for f, (norms_np, bo, words) in zip(fused, msgs_np):
+        np.testing.assert_array_equal(f.norms.cpu().numpy(), norms_np)
+        np.testing.assert_array_equal(g.u64(f.bit_off), bo)
+        np.testing.assert_array_equal(g.u32(f.words)[: words.size], words)
+        assert not g.u32(f.words)[words.size:].any()
+    assert nuq.nuq_last_error_flags() == 0
     out = torch.full((d,), 5.0, dtype=torch.float32, device=g.DEV)
     nuq.nuq_decode_accumulate_table(msgs, d, n, lev, S, 1.0 / K, False, out)
     assert nuq.nuq_last_error_flags() == 0
