@@ -211,13 +211,15 @@ def main():
         "roofline": {"kernel": "k_encode (fused norms+quantize+ENCODE), one launch per %s"
                                % ("worker" if args.per_worker_calls else "step (all K workers)"),
                      "bound": "hbm", "achieved": round(enc_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(enc_gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic("k_encode", args.config, S),
+                     "frac": round(enc_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": None if lev is not None else measured_traffic("k_encode", args.config, S),
                      "bytes_per_launch": round(enc_launch_bytes), "launch_ms": round(enc_kernel_ms, 5),
                      "launches": len(enc_ms)},
         "roofline_decode": {"kernel": "k_decode_accumulate (DECODE + average of K messages)",
                             "bound": "hbm", "achieved": round(dec_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
-                            "traffic": measured_traffic("k_decode_accumulate", args.config, S),
+                            "traffic": None if lev is not None
+                            else measured_traffic("k_decode_accumulate", args.config, S),
                             "bytes_per_launch": round(dec_alg), "launch_ms": round(dec_kernel_ms, 5),
                             "launches": len(dec_ms)},
     }
