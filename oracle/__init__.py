@@ -75,6 +75,12 @@ def lib() -> ctypes.CDLL:
         L.nuqo_decode_levels.restype = i32
         L.nuqo_decode_average.argtypes = [u32, vp, vp, vp, u64, u32, i32, ctypes.c_double, i32, vp]
         L.nuqo_decode_average.restype = i32
+        L.nuqo_fixed_words.argtypes = [u64, u32, u32]
+        L.nuqo_fixed_words.restype = u64
+        L.nuqo_pack_fixed.argtypes = [vp, u64, u32, i32, u32, vp]
+        L.nuqo_pack_fixed.restype = i32
+        L.nuqo_unpack_fixed.argtypes = [vp, u64, u32, i32, u32, vp]
+        L.nuqo_unpack_fixed.restype = i32
         L.nuqo_bucket_norms_linf.argtypes = [vp, u64, u32, vp]
         L.nuqo_bucket_norms_linf.restype = None
         L.nuqo_quantize_coord_table.argtypes = [ctypes.c_float, ctypes.c_float, i32, vp, u32]
@@ -350,3 +356,39 @@ def decode_average_table(norms_list, bit_off_list, words_list, d: int, bucket: i
     if rc:
         raise ValueError("malformed stream: %d" % rc)
     return out
+
+
+# -------------------------------------------------------- fixed-width coding
+
+def fixed_words(d: int, bucket: int, b: int) -> int:
+    return lib().nuqo_fixed_words(d, bucket, b)
+
+
+def pack_fixed(q: np.ndarray, bucket: int, s: int, b: int) -> np.ndarray:
+    """Sec. 5's fixed-width variants: every coordinate's sign and level index in b bits (layout: design notes)."""
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    out = np.zeros(max(1, fixed_words(q.size, bucket, b)), dtype=np.uint32)
+    rc = lib().nuqo_pack_fixed(_p(q), q.size, bucket, s, b, _p(out))
+    if rc:
+        raise ValueError("pack_fixed: %d" % rc)
+    return out[: fixed_words(q.size, bucket, b)]
+
+
+def unpack_fixed(packed: np.ndarray, d: int, bucket: int, s: int, b: int) -> np.ndarray:
+    packed = np.ascontiguousarray(packed, dtype=np.uint32)
+    assert packed.size >= fixed_words(d, bucket, b)
+    q = np.empty(d, dtype=np.uint8)
+    rc = lib().nuqo_unpack_fixed(_p(packed), d, bucket, s, b, _p(q))
+    if rc:
+        raise ValueError("unpack_fixed: %d" % rc)
+    return q
+
+
+def unpack_average_fixed(norms_list, packed_list, d: int, bucket: int, s: int, b: int, scale: float,
+                         prior: np.ndarray | None = None) -> np.ndarray:
+    """Unpack each worker, rebuild ||v|| * sign * l_j (Def. 1) and aggregate as in Alg. 1, fp64, workers in order."""
+    out = np.zeros(d, dtype=np.float64)
+    for norms, packed in zip(norms_list, packed_list):
+        out += dequantize(unpack_fixed(packed, d, bucket, s, b), bucket, s, norms)
+    out *= float(scale)
+    return out if prior is None else np.asarray(prior, dtype=np.float64) + out

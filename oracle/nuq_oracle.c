@@ -24,6 +24,10 @@
  *                          Sec. 4.1; uniform levels = QSGD, with the maximum norm = QSGDinf,
  *                          Sec. 1 and Sec. 2).
  *
+ *   nuqo_pack_fixed,       Sec. 5: the fixed-width variants ("4-bit", "8-bit" NUQSGD; 3 bits in
+ *   nuqo_unpack_fixed      Table 1): every coordinate sends its sign and level index in b bits.
+ *                          The paper gives no layout; the one used is in the design notes.
+ *
  * Points the paper leaves open (random number source, bit order, how the end
  * of a bucket's records is known, padding) are fixed by the wire-format
  * description in the project's design notes; this file implements that text.
@@ -34,6 +38,8 @@
  * ERC codewords, decode(encode(x)) == x, a hand-worked ENCODE bit string.
  * The exact random bits of a particular (seed, bucket, index) are fixed by
  * the format text, not by the paper: "parity unpinned" by the paper for those.
+ * The fixed-width functions are pinned by tests/test_oracle_fixed.py: a hand-packed
+ * example, the size formula, unpack(pack(q)) == q, bit positions of single codes.
  * The level-table functions are pinned by tests/test_oracle_levels.py: equality
  * with the functions above on the table (0, 2^-s, ..., 1/2, 1), exhaustive
  * enumeration of the draws against p(r) as an exact fraction, unbiasedness and
@@ -544,4 +550,60 @@ int nuqo_decode_average_table(uint32_t K, const float *const *norms, const uint6
                               const float *lev, double scale, int accumulate, double *out64)
 {
     return decode_average_any(K, norms, bit_off, words, d, bucket, s, lev, scale, accumulate, out64);
+}
+
+/* ------------------------------------------------------- fixed-width coding */
+
+/*
+ * Fixed-width message (Sec. 5, "4-bit"/"8-bit" variants): coordinate i of a
+ * bucket is the b-bit code  sign << (b-1) | level index  (level index < 2^(b-1),
+ * so s + 2 <= 2^(b-1); a zero level carries sign 0), at bits [i*b, i*b + b) of the
+ * bucket's field, most significant bit first, in 32-bit words as in ENCODE.
+ * Every bucket's field is wpb = ceil(bucket * b / 32) words (the last, short
+ * bucket too; unused bits are 0), so bucket k starts at word k * wpb.
+ */
+uint64_t nuqo_fixed_words(uint64_t d, uint32_t bucket, uint32_t b)
+{
+    uint64_t nb = (d + bucket - 1) / bucket;
+    return nb * (((uint64_t)bucket * b + 31) / 32);
+}
+
+int nuqo_pack_fixed(const uint8_t *q, uint64_t d, uint32_t bucket, int s, uint32_t b, uint32_t *packed)
+{
+    if (b < 2 || b > 8 || (uint32_t)(s + 2) > (1u << (b - 1)))
+        return NUQO_EINVAL;
+    uint64_t nb = (d + bucket - 1) / bucket, wpb = ((uint64_t)bucket * b + 31) / 32;
+    memset(packed, 0, nb * wpb * sizeof(uint32_t));
+    for (uint64_t k = 0; k < nb; k++) {
+        uint64_t lo = k * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        for (uint64_t i = lo; i < hi; i++) {
+            uint32_t level = q[i] & 0x7f, neg = q[i] >> 7;
+            if (level > (uint32_t)s + 1 || (level == 0 && neg))
+                return NUQO_EINVAL;
+            uint32_t code = (neg << (b - 1)) | level;
+            for (uint32_t t = 0; t < b; t++) /* most significant bit of the code first */
+                put_bit(packed + k * wpb, (i - lo) * b + t, (code >> (b - 1 - t)) & 1);
+        }
+    }
+    return NUQO_OK;
+}
+
+int nuqo_unpack_fixed(const uint32_t *packed, uint64_t d, uint32_t bucket, int s, uint32_t b, uint8_t *q)
+{
+    if (b < 2 || b > 8 || (uint32_t)(s + 2) > (1u << (b - 1)))
+        return NUQO_EINVAL;
+    uint64_t nb = (d + bucket - 1) / bucket, wpb = ((uint64_t)bucket * b + 31) / 32;
+    for (uint64_t k = 0; k < nb; k++) {
+        uint64_t lo = k * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        for (uint64_t i = lo; i < hi; i++) {
+            uint32_t code = 0;
+            for (uint32_t t = 0; t < b; t++)
+                code = (code << 1) | (uint32_t)get_bit(packed + k * wpb, (i - lo) * b + t);
+            uint32_t level = code & ((1u << (b - 1)) - 1u), neg = code >> (b - 1);
+            if (level > (uint32_t)s + 1 || (level == 0 && neg))
+                return NUQO_EMALFORMED;
+            q[i] = (uint8_t)(level | (neg << 7));
+        }
+    }
+    return NUQO_OK;
 }
