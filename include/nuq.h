@@ -197,6 +197,33 @@ int nuq_decode_accumulate_table(uint32_t K, const float *const *norms, const uin
                                 uint32_t bucket, uint32_t s, uint32_t sync_stride, const float *levels,
                                 float scale, int accumulate, float *out, nuq_stream_t stream);
 
+/* ---- fixed-width coding (Sec. 5: the "4-bit" and "8-bit" variants; 3 bits in Table 1) ------------ */
+
+/* Every coordinate sends sign and level index in b bits, 3 <= b <= 8 with s + 2 <= 2^(b-1) (else
+ * NUQ_EINVAL).  Message of one worker = norms[B] and packed[nuq_fixed_words(d, bucket, b)] u32:
+ * coordinate i of a bucket is the code  sign << (b-1) | level index  at bits [i*b, i*b + b) of the
+ * bucket's field, most significant bit first (bit t of a field = bit 31 - t%32 of its word t/32);
+ * each bucket's field is ceil(bucket * b / 32) words (the short last bucket's too; unused bits 0). */
+uint64_t nuq_fixed_words(uint64_t d, uint32_t bucket, uint32_t b);
+
+/* packed <- the level|sign bytes q[d] (as nuq_quantize writes them). */
+int nuq_pack_fixed(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint32_t b,
+                   uint32_t *packed, nuq_stream_t stream);
+
+/* Norms, quantizer and packing of K workers' gradients in one launch, v read once: norms[k] as
+ * nuq_bucket_norms(v[k]) and packed[k] as nuq_pack_fixed(nuq_quantize(v[k], ..., seeds[k], norms[k])).
+ * v, norms, packed: HOST arrays of K device pointers; seeds: HOST array.  1 <= K <= NUQ_MAX_WORKERS. */
+int nuq_quantize_pack_fixed_batch(uint32_t K, const float *const *v, const uint64_t *seeds, uint64_t d,
+                                  uint32_t bucket, uint32_t s, uint32_t b, float *const *norms,
+                                  uint32_t *const *packed, nuq_stream_t stream);
+
+/* out[i] = (accumulate ? out[i] : 0) + scale * sum_k norms_k[b] * sign * l_j from K fixed-width
+ * messages (HOST arrays of K device pointers): fp64 sum in worker order, rounded to fp32 once.
+ * A code with a level index above s+1, or a signed zero, raises NUQ_FLAG_MALFORMED. */
+int nuq_unpack_accumulate_fixed(uint32_t K, const float *const *norms, const uint32_t *const *packed,
+                                uint64_t d, uint32_t bucket, uint32_t s, uint32_t b, float scale,
+                                int accumulate, float *out, nuq_stream_t stream);
+
 /* ---- errors ---------------------------------------------------------------------- */
 
 /* Waits for `stream`, copies the sticky device flags of the current device to

@@ -39,6 +39,10 @@ _SIGNATURES = {
     "nuq_quantize_encode_table_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _vp, _u32, _u32, _vp, _vp, _vp, _vp, _vp,
                                                _vp, _u64, _vp]),
     "nuq_decode_accumulate_table": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _f32, _i32, _vp, _vp]),
+    "nuq_fixed_words": (_u64, [_u64, _u32, _u32]),
+    "nuq_pack_fixed": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp]),
+    "nuq_quantize_pack_fixed_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
+    "nuq_unpack_accumulate_fixed": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _i32, _vp, _vp]),
     "nuq_last_error_flags": (_i32, [_vp, _vp]),
     "nuq_timing_begin": (_i32, [_u32]),
     "nuq_timing_collect": (_i32, [_vp, _vp, _u32, _vp]),
@@ -232,6 +236,41 @@ def nuq_decode_accumulate_table(messages: list[Message], d: int, bucket: int, le
            _lib.nuq_decode_accumulate_table(K, norms, offs, words, sync, d, bucket, s, sync_stride,
                                             _levels(levels, s), float(scale), 1 if accumulate else 0,
                                             _ptr(out, torch.float32), _stream()))
+
+
+# --------------------------------------------------------- fixed-width coding
+
+def nuq_fixed_words(d: int, bucket: int, b: int) -> int:
+    return _lib.nuq_fixed_words(d, bucket, b)
+
+
+def nuq_pack_fixed(q: torch.Tensor, bucket: int, s: int, b: int, packed: torch.Tensor) -> None:
+    _check("nuq_pack_fixed",
+           _lib.nuq_pack_fixed(_ptr(q, torch.uint8), q.numel(), bucket, s, b, _ptr(packed, torch.int32), _stream()))
+
+
+def nuq_quantize_pack_fixed_batch(vs: list[torch.Tensor], bucket: int, s: int, b: int, seeds: list[int],
+                                  norms: list[torch.Tensor], packed: list[torch.Tensor]) -> None:
+    K = len(vs)
+    d = vs[0].numel()
+    if any(v.numel() != d for v in vs) or len(seeds) != K or len(norms) != K or len(packed) != K:
+        raise ValueError("K gradients of equal length, K seeds, K norm arrays and K packed arrays are needed")
+    arr = lambda ts, dt: (ctypes.c_void_p * K)(*[_ptr(t, dt) for t in ts])
+    _check("nuq_quantize_pack_fixed_batch",
+           _lib.nuq_quantize_pack_fixed_batch(K, arr(vs, torch.float32),
+                                              (ctypes.c_uint64 * K)(*[x & (2 ** 64 - 1) for x in seeds]), d, bucket,
+                                              s, b, arr(norms, torch.float32), arr(packed, torch.int32), _stream()))
+
+
+def nuq_unpack_accumulate_fixed(norms: list[torch.Tensor], packed: list[torch.Tensor], d: int, bucket: int, s: int,
+                                b: int, scale: float, accumulate: bool, out: torch.Tensor) -> None:
+    K = len(norms)
+    arr = lambda ts, dt: (ctypes.c_void_p * K)(*[_ptr(t, dt) for t in ts])
+    if out.numel() != d:
+        raise ValueError("out must hold d floats")
+    _check("nuq_unpack_accumulate_fixed",
+           _lib.nuq_unpack_accumulate_fixed(K, arr(norms, torch.float32), arr(packed, torch.int32), d, bucket, s, b,
+                                            float(scale), 1 if accumulate else 0, _ptr(out, torch.float32), _stream()))
 
 
 def nuq_last_error_flags() -> int:

@@ -10,6 +10,7 @@
 #include "nuq_decode_kernels.hpp"
 #include "nuq_device.hpp"
 #include "nuq_encode_kernels.hpp"
+#include "nuq_fixed_kernels.hpp"
 #include "nuq_table_kernels.hpp"
 
 namespace {
@@ -247,6 +248,62 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
     else
         hipLaunchKernelGGL(k_finish<16>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks);
     return check_launch();
+}
+
+bool valid_fixed(uint32_t s, uint32_t b)
+{
+    return b >= 3 && b <= 8 && s + 2u <= (1u << (b - 1u));
+}
+
+// MODE 0: norms + quantizer + fixed-width packing from v.  MODE 1: packing of level|sign bytes.
+template <int MODE>
+int pack_fixed_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket, uint32_t s, uint32_t b,
+                     nuq_stream_t stream)
+{
+    if (K < 1 || K > kMaxBatch || !valid_common(d, bucket, s) || !valid_fixed(s, b))
+        return NUQ_EINVAL;
+    for (uint32_t k = 0; k < K; ++k) {
+        const EncodeWorker &w = Wk.w[k];
+        if (!w.words)
+            return NUQ_EINVAL;
+        if (MODE == 0 && (!w.v || !w.norms_out || (reinterpret_cast<uintptr_t>(w.v) & 3u)))
+            return NUQ_EINVAL;
+        if (MODE == 1 && !w.q_in)
+            return NUQ_EINVAL;
+    }
+    uint32_t *flags = flags_ptr();
+    if (!flags)
+        return NUQ_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    EncodeParams P{};
+    P.d = d;
+    P.nb = nuq_num_buckets(d, bucket);
+    P.bucket = bucket;
+    P.s = s;
+    P.flags = flags;
+    FixedParams F{};
+    F.b = b;
+    F.wpb = (bucket * b + 31u) / 32u;
+    return dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
+        constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
+        using G = TeamGeom<TEAM>;
+        P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
+        P.lds_words = fixed_lds_words(P.rows, TEAM, F.wpb);
+        const size_t lds_bytes = (size_t)P.lds_words * 4 * G::kTeamsPerWG;
+        if (lds_bytes > 160 * 1024)
+            return (int)NUQ_EINVAL;
+        auto kern = k_pack_fixed<TEAM, VPT, MODE>;
+        if (lds_bytes > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_bytes) != hipSuccess)
+            return (int)NUQ_EHIP;
+        dim3 grid;
+        if (!bucket_grid<TEAM>(P.nb, K, grid))
+            return (int)NUQ_EINVAL;
+        ScopedTiming timing(MODE == 1 ? NUQ_T_ENCODE : NUQ_T_QUANTIZE_ENCODE, st);
+        hipLaunchKernelGGL(kern, grid, dim3(G::kWG), lds_bytes, st, P, Wk, F);
+        return check_launch();
+    });
 }
 
 // Workgroups of the persistent decode kernel that the current device holds at once (0 on error).
@@ -573,6 +630,79 @@ int nuq_decode_accumulate_table(uint32_t K, const float *const *norms, const uin
         return NUQ_EINVAL;
     return decode_accumulate_any(K, norms, bit_off, words, sync, d, bucket, s, sync_stride, levels, scale,
                                  accumulate, out, stream);
+}
+
+uint64_t nuq_fixed_words(uint64_t d, uint32_t bucket, uint32_t b)
+{
+    if (!bucket || b < 3 || b > 8)
+        return 0;
+    return nuq_num_buckets(d, bucket) * (((uint64_t)bucket * b + 31) / 32);
+}
+
+int nuq_pack_fixed(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint32_t b, uint32_t *packed,
+                   nuq_stream_t stream)
+{
+    EncodeBatch Wk{};
+    Wk.w[0].q_in = q;
+    Wk.w[0].words = packed;
+    return pack_fixed_batch<1>(1, Wk, d, bucket, s, b, stream);
+}
+
+int nuq_quantize_pack_fixed_batch(uint32_t K, const float *const *v, const uint64_t *seeds, uint64_t d,
+                                  uint32_t bucket, uint32_t s, uint32_t b, float *const *norms,
+                                  uint32_t *const *packed, nuq_stream_t stream)
+{
+    if (K < 1 || K > kMaxBatch || !v || !seeds || !norms || !packed)
+        return NUQ_EINVAL;
+    EncodeBatch Wk{};
+    for (uint32_t k = 0; k < K; ++k) {
+        Wk.w[k].v = v[k];
+        Wk.w[k].seed = seeds[k];
+        Wk.w[k].norms_out = norms[k];
+        Wk.w[k].words = packed[k];
+    }
+    return pack_fixed_batch<0>(K, Wk, d, bucket, s, b, stream);
+}
+
+int nuq_unpack_accumulate_fixed(uint32_t K, const float *const *norms, const uint32_t *const *packed, uint64_t d,
+                                uint32_t bucket, uint32_t s, uint32_t b, float scale, int accumulate, float *out,
+                                nuq_stream_t stream)
+{
+    if (K < 1 || K > NUQ_MAX_WORKERS || !norms || !packed || !out || !valid_common(d, bucket, s) ||
+        !valid_fixed(s, b))
+        return NUQ_EINVAL;
+    UnpackParams P{};
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!norms[k] || !packed[k])
+            return NUQ_EINVAL;
+        P.norms[k] = norms[k];
+        P.packed[k] = packed[k];
+    }
+    uint32_t *flags = flags_ptr();
+    if (!flags)
+        return NUQ_EHIP;
+    P.out = out;
+    P.flags = flags;
+    P.d = d;
+    P.K = K;
+    P.bucket = bucket;
+    P.s = s;
+    P.b = b;
+    P.wpb = (bucket * b + 31u) / 32u;
+    P.scale = scale;
+    P.accumulate = accumulate;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool vec = bucket % 4u == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0;
+    const uint64_t threads = vec ? (d + 3) / 4 : d;
+    const uint64_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffull)
+        return NUQ_EINVAL;
+    ScopedTiming timing(NUQ_T_DECODE, st);
+    if (vec)
+        hipLaunchKernelGGL(k_unpack_accumulate_fixed<4>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
+    else
+        hipLaunchKernelGGL(k_unpack_accumulate_fixed<1>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
+    return check_launch();
 }
 
 int nuq_last_error_flags(uint32_t *host_flags, nuq_stream_t stream)

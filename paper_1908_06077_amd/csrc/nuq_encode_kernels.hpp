@@ -537,6 +537,76 @@ __host__ __device__ inline uint32_t team_lds_words(uint32_t rows, uint32_t team,
     return w + 64u;
 }
 
+// Front of the fused kernels: the bucket's coordinates into registers (v is read once), its norm (written to
+// norms_out), the quantizer, level|sign bytes into the team's LDS words qb32[rows * TEAM].
+template <int TEAM, int VPT>
+__device__ __forceinline__ void front_quantize_to_lds(const EncodeParams &P, const EncodeWorker &W, uint64_t b,
+                                                      bool active, uint64_t base, uint32_t nbk, uint32_t tid,
+                                                      uint32_t *qb32, uint32_t *scratch)
+{
+    const float *vb = W.v + base;
+    const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
+    float4 x[VPT];
+    if (aligned && nbk == (uint32_t)VPT * TEAM * 4u) {   // a full bucket that fills every row: plain vector loads
+#pragma unroll
+        for (int i = 0; i < VPT; ++i)
+            x[i] = reinterpret_cast<const float4 *>(vb)[(uint32_t)i * TEAM + tid];
+    } else {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i)
+            x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
+    }
+    auto row = [&](int i) { return x[i]; };
+    const float nrm = team_uniform_f32<TEAM>(team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32)));
+    const bool finite = nrm < __builtin_huge_valf();   // false for NaN too
+    if (active && tid == 0) {
+        W.norms_out[b] = nrm;
+        if (!finite)
+            atomicOr(P.flags, kFlagNonfinite);
+    }
+    const BucketScale B = make_scale(nrm, (int)P.s);
+    const BucketKey key = bucket_key(W.seed, b);
+    if (B.prescale != 1.0f) {   // tiny norm: work on the bucket scaled by a power of two
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            x[i].x *= B.prescale;
+            x[i].y *= B.prescale;
+            x[i].z *= B.prescale;
+            x[i].w *= B.prescale;
+        }
+    }
+    const uint32_t x0 = (key.k0 + 4u * tid) * kRngC1;      // row i starts 4 * TEAM * i coordinates further on
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        if ((uint32_t)i < P.rows) {
+            const uint32_t vi = (uint32_t)i * TEAM + tid;
+            qb32[vi] = B.dead ? 0u : quantize_vec4(x[i], x0 + (uint32_t)i * (4u * TEAM * kRngC1), key.k1, B);
+        }
+    }
+}
+
+// Front of the kernels that start from level|sign bytes: q_in into the team's LDS words.
+template <int TEAM>
+__device__ __forceinline__ void front_bytes_to_lds(const EncodeParams &P, const EncodeWorker &W, uint64_t base,
+                                                   uint32_t nbk, uint32_t tid, uint32_t *qb32)
+{
+    const uint8_t *qg = W.q_in + base;
+    const bool aligned = (reinterpret_cast<uintptr_t>(qg) & 3u) == 0;
+    for (uint32_t i = 0; i < P.rows; ++i) {
+        const uint32_t vi = i * TEAM + tid;
+        const uint32_t e0 = 4u * vi;
+        uint32_t word = 0;
+        if (aligned && e0 + 3u < nbk) {
+            word = reinterpret_cast<const uint32_t *>(qg)[vi];
+        } else {
+            for (uint32_t c = 0; c < 4u; ++c)
+                if (e0 + c < nbk)
+                    word |= (uint32_t)qg[e0 + c] << (8u * c);
+        }
+        qb32[vi] = word;
+    }
+}
+
 // MODE 0: fused norms + quantize + encode from v.  MODE 1: encode from level/sign bytes.  MODE 2: as 0 for the level
 // table T and the norm P.norm_linf selects (T is ignored in the other modes).
 template <int TEAM, int VPT, int MODE>
@@ -607,61 +677,9 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
             }
         }
     } else if constexpr (MODE == 0) {
-        const float *vb = W.v + base;
-        const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
-        float4 x[VPT];
-        if (aligned && nbk == (uint32_t)VPT * TEAM * 4u) {   // a full bucket that fills every row: plain vector loads
-#pragma unroll
-            for (int i = 0; i < VPT; ++i)
-                x[i] = reinterpret_cast<const float4 *>(vb)[(uint32_t)i * TEAM + tid];
-        } else {
-#pragma unroll
-            for (int i = 0; i < VPT; ++i)
-                x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
-        }
-        auto row = [&](int i) { return x[i]; };
-        const float nrm = team_uniform_f32<TEAM>(team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32)));
-        const bool finite = nrm < __builtin_huge_valf();   // false for NaN too
-        if (active && tid == 0) {
-            W.norms_out[b] = nrm;
-            if (!finite)
-                atomicOr(P.flags, kFlagNonfinite);
-        }
-        const BucketScale B = make_scale(nrm, (int)P.s);
-        const BucketKey key = bucket_key(W.seed, b);
-        if (B.prescale != 1.0f) {   // tiny norm: work on the bucket scaled by a power of two
-#pragma unroll
-            for (int i = 0; i < VPT; ++i) {
-                x[i].x *= B.prescale;
-                x[i].y *= B.prescale;
-                x[i].z *= B.prescale;
-                x[i].w *= B.prescale;
-            }
-        }
-        const uint32_t x0 = (key.k0 + 4u * tid) * kRngC1;      // row i starts 4 * TEAM * i coordinates further on
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            if ((uint32_t)i < P.rows) {
-                const uint32_t vi = (uint32_t)i * TEAM + tid;
-                qb32[vi] = B.dead ? 0u : quantize_vec4(x[i], x0 + (uint32_t)i * (4u * TEAM * kRngC1), key.k1, B);
-            }
-        }
+        front_quantize_to_lds<TEAM, VPT>(P, W, b, active, base, nbk, tid, qb32, scratch);
     } else {
-        const uint8_t *qg = W.q_in + base;
-        const bool aligned = (reinterpret_cast<uintptr_t>(qg) & 3u) == 0;
-        for (uint32_t i = 0; i < P.rows; ++i) {
-            const uint32_t vi = i * TEAM + tid;
-            const uint32_t e0 = 4u * vi;
-            uint32_t word = 0;
-            if (aligned && e0 + 3u < nbk) {
-                word = reinterpret_cast<const uint32_t *>(qg)[vi];
-            } else {
-                for (uint32_t c = 0; c < 4u; ++c)
-                    if (e0 + c < nbk)
-                        word |= (uint32_t)qg[e0 + c] << (8u * c);
-            }
-            qb32[vi] = word;
-        }
+        front_bytes_to_lds<TEAM>(P, W, base, nbk, tid, qb32);
     }
     __syncthreads();
     encode_from_lds<TEAM, VPT>(P, W, active, b, qb32, out, rec, erc_lut, tail_lut, sync_l, scratch);

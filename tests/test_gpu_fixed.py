@@ -1,0 +1,129 @@
+"""GPU parity of the fixed-width coding (b bits per coordinate) through the C ABI against the CPU oracle: packed
+words bit-exact (from bytes, and from the fused norms + quantizer + packing when the oracle is fed the GPU's norms),
+unpacked averages within 1e-6 (the GPU sums in fp64 in worker order like the oracle)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from test_gpu_parity import make_vector
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_util
+    return gpu_util
+
+
+CASES = [
+    # (d, bucket, s, b, K, kind)
+    (100_000, 8192, 3, 4, 3, "mixed"),
+    (100_003, 8192, 6, 4, 8, "gauss"),
+    (70_001, 16384, 7, 8, 2, "mixed"),
+    (40_000, 512, 2, 3, 4, "mixed"),
+    (40_000, 512, 3, 4, 4, "edges"),
+    (33_333, 1000, 9, 5, 3, "mixed"),
+    (9_999, 1001, 5, 4, 2, "mixed"),         # bucket not a multiple of 4: scalar unpack, unaligned loads
+    (3_000, 7, 1, 3, 5, "mixed"),
+    (120_000, 32768, 14, 8, 2, "mixed"),
+    (66_000, 20000, 3, 7, 3, "edges"),
+    (10_000, 2048, 14, 5, 1, "mixed"),
+    (1, 8192, 3, 4, 1, "gauss"),
+]
+
+
+@pytest.mark.parametrize("d,n,s,b,K,kind", CASES)
+def test_pack_fused_pack_and_unpack_average(g, d, n, s, b, K, kind):
+    nuq = g.nuq
+    rng = np.random.default_rng(d + n + s + b)
+    B = nuq.nuq_num_buckets(d, n)
+    W = nuq.nuq_fixed_words(d, n, b)
+    assert W == oracle.fixed_words(d, n, b)
+    vs_np = [make_vector(kind, d, n, rng) for _ in range(K)]
+    vs = [torch.from_numpy(v).to(g.DEV) for v in vs_np]
+    seeds = [int(x) for x in rng.integers(0, 2 ** 63, size=K)]
+    norms = [torch.full((B,), -1.0, dtype=torch.float32, device=g.DEV) for _ in range(K)]
+    packed = [torch.full((W,), 0x55555555, dtype=torch.int32, device=g.DEV) for _ in range(K)]
+    nuq.nuq_quantize_pack_fixed_batch(vs, n, s, b, seeds, norms, packed)
+    assert nuq.nuq_last_error_flags() == 0
+    norms_np, packed_np = [], []
+    for k in range(K):
+        nk = norms[k].cpu().numpy()
+        g.check_norms(vs_np[k], n, nk)
+        q_ref = oracle.quantize(vs_np[k], n, s, seeds[k], nk)
+        want = oracle.pack_fixed(q_ref, n, s, b)
+        np.testing.assert_array_equal(g.u32(packed[k]), want)
+        norms_np.append(nk)
+        packed_np.append(want)
+        if k == 0:       # the unfused chain gives the same words: norms -> bytes -> packing
+            n2 = torch.empty(B, dtype=torch.float32, device=g.DEV)
+            nuq.nuq_bucket_norms(vs[0], n, n2)
+            assert torch.equal(n2, norms[0])
+            q = torch.empty(d, dtype=torch.uint8, device=g.DEV)
+            nuq.nuq_quantize(vs[0], n, s, seeds[0], n2, q)
+            p2 = torch.full((W,), 0x33333333, dtype=torch.int32, device=g.DEV)
+            nuq.nuq_pack_fixed(q, n, s, b, p2)
+            assert torch.equal(p2, packed[0])
+    out = torch.full((d,), 9.0, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_unpack_accumulate_fixed(norms, packed, d, n, s, b, 1.0 / K, False, out)
+    assert nuq.nuq_last_error_flags() == 0
+    check(norms_np, packed_np, d, n, s, b, 1.0 / K, out.cpu().numpy())
+    prior = torch.from_numpy(rng.standard_normal(d).astype(np.float32)).to(g.DEV)
+    out2 = prior.clone()
+    nuq.nuq_unpack_accumulate_fixed(norms, packed, d, n, s, b, 0.5, True, out2)
+    check(norms_np, packed_np, d, n, s, b, 0.5, out2.cpu().numpy(), prior=prior.cpu().numpy().astype(np.float64))
+
+
+def check(norms_np, packed_np, d, n, s, b, scale, got, prior=None):
+    scale32 = float(np.float32(scale))
+    want = oracle.unpack_average_fixed(norms_np, packed_np, d, n, s, b, scale32, prior=prior)
+    mag = np.zeros(d)
+    for norms, packed in zip(norms_np, packed_np):
+        mag += np.abs(oracle.dequantize(oracle.unpack_fixed(packed, d, n, s, b), n, s, norms))
+    mag = mag * abs(scale32) + (np.abs(prior) if prior is not None else 0.0)
+    diff = np.abs(got.astype(np.float64) - want)
+    assert np.all(diff <= 1e-6 * mag + 1e-45), float(np.max(diff / np.maximum(mag, 1e-300)))
+
+
+def test_malformed_codes_raise_the_flag(g):
+    nuq = g.nuq
+    d, n, s, b = 64, 64, 2, 4
+    norms = [torch.ones(1, dtype=torch.float32, device=g.DEV)]
+    out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+    for word in (0x70000000, 0x80000000):       # level index 7 > s + 1; a signed zero
+        packed = [torch.tensor([word - (1 << 32) if word >> 31 else word] + [0] * 7, dtype=torch.int32, device=g.DEV)]
+        nuq.nuq_unpack_accumulate_fixed(norms, packed, d, n, s, b, 1.0, False, out)
+        assert nuq.nuq_last_error_flags() == nuq.FLAG_MALFORMED
+
+
+def test_four_bit_at_benchmark_size(g):
+    """Config 3 at full size, 4 bits: all 8 workers packed in one launch; sampled buckets against the oracle, the
+    average on the same buckets."""
+    nuq = g.nuq
+    w = workloads.workload(3)
+    d, n, s, K, b = w.d, w.bucket, w.s, w.K, 4
+    B, W = nuq.nuq_num_buckets(d, n), nuq.nuq_fixed_words(d, n, b)
+    wpb = W // B
+    vs = [workloads.generate(w, k, g.DEV) for k in range(K)]
+    seeds = [w.quant_seed(k) for k in range(K)]
+    norms = [torch.empty(B, dtype=torch.float32, device=g.DEV) for _ in range(K)]
+    packed = [torch.empty(W, dtype=torch.int32, device=g.DEV) for _ in range(K)]
+    nuq.nuq_quantize_pack_fixed_batch(vs, n, s, b, seeds, norms, packed)
+    out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_unpack_accumulate_fixed(norms, packed, d, n, s, b, 1.0 / K, False, out)
+    assert nuq.nuq_last_error_flags() == 0
+    rng = np.random.default_rng(3)
+    for bk in [0, B - 1] + [int(x) for x in rng.integers(0, B, size=10)]:
+        sl = slice(bk * n, min(d, (bk + 1) * n))
+        nn, pp = [], []
+        for k in range(K):
+            v_np = vs[k][sl].cpu().numpy()
+            nk = norms[k][bk:bk + 1].cpu().numpy()
+            want = oracle.pack_fixed(oracle.quantize(v_np, n, s, seeds[k], nk, first_bucket=bk), n, s, b)
+            np.testing.assert_array_equal(g.u32(packed[k][bk * wpb:(bk + 1) * wpb]), want)
+            nn.append(nk)
+            pp.append(want)
+        check(nn, pp, sl.stop - sl.start, n, s, b, 1.0 / K, out[sl].cpu().numpy())
