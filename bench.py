@@ -43,6 +43,9 @@ def parse_args():
                     help="level sequence: nuq (the paper's main scheme, levels 2^(j-1-s): the default path), "
                          "uniform (QSGD's grid) or exp:P (0, P^s, ..., P, 1); anything but nuq runs the level-table "
                          "entry points")
+    ap.add_argument("--fixed-bits", type=int, default=0,
+                    help="b in 3..8: fixed-width coding (sign and level index in b bits per coordinate, the paper's "
+                         "\"4-bit\"/\"8-bit\" variants) instead of the ERC bit strings; main scheme's levels only")
     ap.add_argument("--norm", default="l2", choices=["l2", "linf"],
                     help="bucket norm for a level table: Euclidean, or maximum (QSGDinf with --levels uniform)")
     ap.add_argument("--reference-kernels", action="store_true",
@@ -102,15 +105,27 @@ def main():
         else:
             nuq.nuq_quantize_encode_batch(grads, n, s, seeds, S, messages, ws)
 
-    probes = [new_msg(16) for _ in range(K)]
-    encode_batch(probes)
-    nuq.nuq_last_error_flags()
-    msgs = [new_msg((int(p.bit_off[-1].item()) + 31) // 32 + 64) for p in probes]
-    del probes
+    fb = args.fixed_bits
+    if fb:
+        if lev is not None:
+            print("--fixed-bits goes with the main scheme's levels", file=sys.stderr)
+            sys.exit(2)
+        wpb = (n * fb + 31) // 32
+        fnorms = [torch.empty(B, dtype=torch.float32, device=dev) for _ in range(K)]
+        fpacked = [torch.empty(nuq.nuq_fixed_words(d, n, fb), dtype=torch.int32, device=dev) for _ in range(K)]
+        msgs = []
+    else:
+        probes = [new_msg(16) for _ in range(K)]
+        encode_batch(probes)
+        nuq.nuq_last_error_flags()
+        msgs = [new_msg((int(p.bit_off[-1].item()) + 31) // 32 + 64) for p in probes]
+        del probes
     out = torch.empty(d, dtype=torch.float32, device=dev)
 
     def encode_all():
-        if lev is not None:
+        if fb:
+            nuq.nuq_quantize_pack_fixed_batch(grads, n, s, fb, seeds, fnorms, fpacked)
+        elif lev is not None:
             encode_batch(msgs)
         elif args.per_worker_calls:
             for k in range(K):
@@ -120,7 +135,9 @@ def main():
             nuq.nuq_quantize_encode_batch(grads, n, s, seeds, S, msgs, ws)
 
     def decode_all():
-        if lev is not None:
+        if fb:
+            nuq.nuq_unpack_accumulate_fixed(fnorms, fpacked, d, n, s, fb, 1.0 / K, False, out)
+        elif lev is not None:
             nuq.nuq_decode_accumulate_table(msgs, d, n, lev, S, 1.0 / K, False, out)
         else:
             nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
@@ -168,15 +185,21 @@ def main():
     value = in_bytes / (ms_step * 1e-3) / 1e9
 
     # message sizes -> bits per coordinate and algorithmic bytes
-    total_bits = [int(m.bit_off[-1].item()) for m in msgs]
-    starts = [(m.bit_off[:-1] + 31) // 32 * 32 for m in msgs]
-    payload_bits = [int((m.bit_off[1:] - st).sum().item()) for m, st in zip(msgs, starts)]
-    W = [(tb + 31) // 32 for tb in total_bits]
-    paper_bits = float(np.mean([(32 * B + pb) / d for pb in payload_bits]))
-    wire_bits = float(np.mean([(32 * Wk + 32 * B + 64 * (B + 1) + 32 * B * nsync) / d for Wk in W]))
-
-    enc_alg = [4.0 * d + 4 * B + 8 * (B + 1) + 4 * Wk + 4 * B * nsync for Wk in W]      # per worker
-    dec_alg = sum(4.0 * Wk + 12 * B + 4 * B * nsync for Wk in W) + 4.0 * d               # per launch
+    if fb:
+        W = [B * wpb] * K
+        paper_bits = (32.0 * B + float(fb) * d) / d
+        wire_bits = (32.0 * B + 32.0 * B * wpb) / d
+        enc_alg = [4.0 * d + 4 * B + 4 * Wk for Wk in W]                                    # per worker
+        dec_alg = sum(4.0 * Wk + 4 * B for Wk in W) + 4.0 * d                               # per launch
+    else:
+        total_bits = [int(m.bit_off[-1].item()) for m in msgs]
+        starts = [(m.bit_off[:-1] + 31) // 32 * 32 for m in msgs]
+        payload_bits = [int((m.bit_off[1:] - st).sum().item()) for m, st in zip(msgs, starts)]
+        W = [(tb + 31) // 32 for tb in total_bits]
+        paper_bits = float(np.mean([(32 * B + pb) / d for pb in payload_bits]))
+        wire_bits = float(np.mean([(32 * Wk + 32 * B + 64 * (B + 1) + 32 * B * nsync) / d for Wk in W]))
+        enc_alg = [4.0 * d + 4 * B + 8 * (B + 1) + 4 * Wk + 4 * B * nsync for Wk in W]      # per worker
+        dec_alg = sum(4.0 * Wk + 12 * B + 4 * B * nsync for Wk in W) + 4.0 * d               # per launch
     enc_ms = [t for e, t in launches if e == nuq.T_QUANTIZE_ENCODE]
     dec_ms = [t for e, t in launches if e == nuq.T_DECODE]
     enc_kernel_ms = float(np.mean(enc_ms))
@@ -200,6 +223,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[%d] %s: d=%d fp32, bucket=%d, s=%d, K=%d workers, sync_stride=%d%s"
                                % (args.config - 1, w.name, d, n, s, K, S,
+                                  (", fixed-width %d bits" % fb) if fb else
                                   "" if lev is None else ", level table %s, %s norm" % (args.levels, args.norm))},
         "phases": {
             "quantize_encode": {"ms": round(ms_enc, 4), "fp32_in_GBps": round(in_bytes / (ms_enc * 1e-3) / 1e9, 2),
@@ -208,17 +232,19 @@ def main():
                                "hbm_frac": round(dec_alg / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         },
         "bits_per_coord": {"paper": round(paper_bits, 4), "wire": round(wire_bits, 4)},
-        "roofline": {"kernel": "k_encode (fused norms+quantize+ENCODE), one launch per %s"
-                               % ("worker" if args.per_worker_calls else "step (all K workers)"),
+        "roofline": {"kernel": ("k_pack_fixed (fused norms+quantize+b-bit packing), one launch per step (all K workers)"
+                                if fb else "k_encode (fused norms+quantize+ENCODE), one launch per %s"
+                                % ("worker" if args.per_worker_calls else "step (all K workers)")),
                      "bound": "hbm", "achieved": round(enc_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(enc_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None if lev is not None else measured_traffic("k_encode", args.config, S),
+                     "traffic": None if lev is not None or fb else measured_traffic("k_encode", args.config, S),
                      "bytes_per_launch": round(enc_launch_bytes), "launch_ms": round(enc_kernel_ms, 5),
                      "launches": len(enc_ms)},
-        "roofline_decode": {"kernel": "k_decode_accumulate (DECODE + average of K messages)",
+        "roofline_decode": {"kernel": ("k_unpack_accumulate_fixed (unpack + average of K messages)" if fb else
+                                       "k_decode_accumulate (DECODE + average of K messages)"),
                             "bound": "hbm", "achieved": round(dec_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
-                            "traffic": None if lev is not None
+                            "traffic": None if lev is not None or fb
                             else measured_traffic("k_decode_accumulate", args.config, S),
                             "bytes_per_launch": round(dec_alg), "launch_ms": round(dec_kernel_ms, 5),
                             "launches": len(dec_ms)},
@@ -227,7 +253,7 @@ def main():
     if args.reference_kernels:
         result["reference"] = reference_kernels(torch, d * K, dev)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, grads, S, lev, args.norm)
+        result["cpu_baseline"] = cpu_baseline(w, grads, S, lev, args.norm, fb)
     print(json.dumps(result))
 
 
@@ -270,7 +296,7 @@ def measured_traffic(kernel, config, S):
     return None if entry is None else entry.get("bytes_per_launch")
 
 
-def cpu_baseline(w, grads, S, lev=None, norm="l2"):
+def cpu_baseline(w, grads, S, lev=None, norm="l2", fb=0):
     """The CPU oracle as it stands, one thread, on the same workload (bounded to ~30 s of CPU work)."""
     import numpy as np
     import oracle
@@ -288,10 +314,15 @@ def cpu_baseline(w, grads, S, lev=None, norm="l2"):
             q = oracle.quantize(host[k], n, s, w.quant_seed(k), norms)
         else:
             q = oracle.quantize_table(host[k], n, lev, w.quant_seed(k), norms)
+        if fb:
+            parts.append((norms, oracle.pack_fixed(q, n, s, fb), None))
+            continue
         bo, words, _ = oracle.encode(q, n, s, S)
         parts.append((norms, bo, words))
     t1 = time.perf_counter()
-    if lev is None:
+    if fb:
+        oracle.unpack_average_fixed([p[0] for p in parts], [p[1] for p in parts], d_s, n, s, fb, 1.0 / K)
+    elif lev is None:
         oracle.decode_average([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], d_s, n, s, 1.0 / K)
     else:
         oracle.decode_average_table([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], d_s, n, lev,

@@ -692,16 +692,25 @@ int nuq_unpack_accumulate_fixed(uint32_t K, const float *const *norms, const uin
     P.scale = scale;
     P.accumulate = accumulate;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool vec = bucket % 4u == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0;
-    const uint64_t threads = vec ? (d + 3) / 4 : d;
+    const bool wide = bucket % 32u == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0;
+    const uint64_t threads = wide ? (d + 31) / 32 : d;
     const uint64_t blocks = (threads + 255) / 256;
     if (blocks > 0x7fffffffull)
         return NUQ_EINVAL;
     ScopedTiming timing(NUQ_T_DECODE, st);
-    if (vec)
-        hipLaunchKernelGGL(k_unpack_accumulate_fixed<4>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
-    else
-        hipLaunchKernelGGL(k_unpack_accumulate_fixed<1>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
+    const dim3 grid((uint32_t)blocks);
+    if (!wide) {
+        hipLaunchKernelGGL(k_unpack_accumulate_fixed1, grid, dim3(256), 0, st, P);
+    } else {
+        switch (b) {
+        case 3: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<3>, grid, dim3(256), 0, st, P); break;
+        case 4: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<4>, grid, dim3(256), 0, st, P); break;
+        case 5: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<5>, grid, dim3(256), 0, st, P); break;
+        case 6: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<6>, grid, dim3(256), 0, st, P); break;
+        case 7: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<7>, grid, dim3(256), 0, st, P); break;
+        default: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<8>, grid, dim3(256), 0, st, P); break;
+        }
+    }
     return check_launch();
 }
 

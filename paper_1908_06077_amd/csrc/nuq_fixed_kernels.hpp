@@ -94,64 +94,118 @@ struct UnpackParams {
     int accumulate;
 };
 
-// out[i] = [out[i] +] scale * sum_k norms_k[bucket] * sign * 2^(level - 1 - s): fp64 sum in worker order, one
-// rounding.  A thread owns four consecutive coordinates (one 16-byte store) when buckets are multiples of four,
-// else one.  A level index above s + 1, or a signed zero, raises the malformed flag.
-template <int VEC>
-__global__ __launch_bounds__(256) void k_unpack_accumulate_fixed(UnpackParams P)
+// out[i] = [out[i] +] scale * sum_k norms_k[bucket] * sign * 2^(level - 1 - s): fp64 sum in worker order, rounded to
+// fp32 (the prior, when there is one, is added in fp32 after that).  A level index above s + 1, or a signed zero,
+// raises the malformed flag.
+//
+// Buckets that are multiples of 32 coordinates: a thread owns 32 consecutive coordinates, i.e. exactly B whole words
+// of every worker's field (one contiguous load per worker, coalesced over the wave), and the workgroup's 8192 results
+// go through LDS so that the stores are whole lines too.
+template <int B>
+__global__ __launch_bounds__(256) void k_unpack_accumulate_fixed32(UnpackParams P)
 {
-    const uint64_t i0 = ((uint64_t)blockIdx.x * 256u + threadIdx.x) * VEC;
-    if (i0 >= P.d)
-        return;
-    const uint64_t bk = i0 / P.bucket;
-    const uint32_t j0 = (uint32_t)(i0 - bk * P.bucket);
-    const uint32_t bit0 = j0 * P.b;
-    const uint32_t nbits = VEC * P.b;                       // <= 32
-    const uint32_t wi = bit0 >> 5, sh = bit0 & 31u;
-    const bool two = sh + nbits > 32u;                      // the codes straddle a word boundary
-    const uint32_t mask_level = (1u << (P.b - 1u)) - 1u;
-    double sum[VEC];
+    __shared__ float tile[256 * 33];                          // a thread's 32 results in a row of 33: no bank conflicts
+    const uint64_t chunk = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    const uint64_t i0 = chunk * 32u;
+    double sum[32];
 #pragma unroll
-    for (int c = 0; c < VEC; ++c)
+    for (int c = 0; c < 32; ++c)
         sum[c] = 0.0;
     bool bad = false;
-    for (uint32_t k = 0; k < P.K; ++k) {
-        const uint32_t *f = P.packed[k] + bk * P.wpb + wi;
-        const uint32_t w0 = f[0];
-        const uint32_t w1 = two ? f[1] : 0u;
-        const uint64_t win = (((uint64_t)w0 << 32) | w1) << sh;     // the VEC codes on top
-        const double nrm = (double)P.norms[k][bk];
+    if (i0 < P.d) {
+        const uint64_t bk = P.d <= 0xffffffffull ? (uint64_t)((uint32_t)i0 / P.bucket) : i0 / P.bucket;
+        const uint32_t j0 = (uint32_t)(i0 - bk * P.bucket);
+        const uint64_t word0 = bk * P.wpb + (uint64_t)(j0 / 32u) * B;
+        constexpr uint32_t kLevelMask = (1u << (B - 1)) - 1u;
+        for (uint32_t k = 0; k < P.K; ++k) {
+            const uint32_t *f = P.packed[k] + word0;
+            uint32_t w[B];
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            const uint32_t code = (uint32_t)(win >> (64u - (uint32_t)(c + 1) * P.b)) & ((1u << P.b) - 1u);
-            const uint32_t level = code & mask_level, neg = code >> (P.b - 1u);
-            bad |= level > P.s + 1u || (level == 0u && neg);
-            if (level) {
-                const double val = ldexp(nrm, (int)level - 1 - (int)P.s);
-                sum[c] += neg ? -val : val;
+            for (int t = 0; t < B; ++t)
+                w[t] = f[t];
+            const double nrm = (double)P.norms[k][bk];
+#pragma unroll
+            for (int c = 0; c < 32; ++c) {
+                // code c occupies bits [c*B, c*B + B) of the B words, most significant bit first
+                const int bit = c * B, wi = bit >> 5, off = bit & 31;
+                uint32_t code;
+                if (off + B <= 32)
+                    code = (w[wi] >> (32 - off - B)) & ((1u << B) - 1u);
+                else
+                    code = ((w[wi] << (off + B - 32)) | (w[wi + 1 < B ? wi + 1 : wi] >> (64 - off - B))) & ((1u << B) - 1u);
+                const uint32_t level = code & kLevelMask, neg = code >> (B - 1);
+                bad |= level > P.s + 1u || (level == 0u && neg);
+                if (level) {
+                    const double val = ldexp(nrm, (int)level - 1 - (int)P.s);
+                    sum[c] += neg ? -val : val;
+                }
             }
         }
     }
     if (bad)
         atomicOr(P.flags, kFlagMalformed);
     const double sc = (double)P.scale;
-    if constexpr (VEC == 4) {
-        float4 o;
-        const bool whole = i0 + 3u < P.d;
-        if (whole) {
-            float4 prev = P.accumulate ? *reinterpret_cast<const float4 *>(P.out + i0) : float4{0.f, 0.f, 0.f, 0.f};
-            o.x = (float)((double)prev.x + sc * sum[0]);
-            o.y = (float)((double)prev.y + sc * sum[1]);
-            o.z = (float)((double)prev.z + sc * sum[2]);
-            o.w = (float)((double)prev.w + sc * sum[3]);
-            *reinterpret_cast<float4 *>(P.out + i0) = o;
+#pragma unroll
+    for (int c = 0; c < 32; ++c)
+        tile[threadIdx.x * 33u + (uint32_t)c] = (float)(sc * sum[c]);
+    __syncthreads();
+    const uint64_t base = (uint64_t)blockIdx.x * 8192u;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const uint32_t e = ((uint32_t)it * 256u + threadIdx.x) * 4u;          // element of the workgroup's 8192
+        const uint64_t i = base + e;
+        if (i >= P.d)
+            continue;
+        const float *row = tile + (e >> 5) * 33u + (e & 31u);
+        float4 o{row[0], row[1], row[2], row[3]};
+        if (i + 3u < P.d) {
+            if (P.accumulate) {
+                const float4 prev = *reinterpret_cast<const float4 *>(P.out + i);
+                o.x += prev.x;
+                o.y += prev.y;
+                o.z += prev.z;
+                o.w += prev.w;
+            }
+            *reinterpret_cast<float4 *>(P.out + i) = o;
         } else {
-            for (uint32_t c = 0; c < 4u && i0 + c < P.d; ++c)
-                P.out[i0 + c] = (float)((P.accumulate ? (double)P.out[i0 + c] : 0.0) + sc * sum[c]);
+            const float r[4] = {o.x, o.y, o.z, o.w};
+            for (uint32_t c = 0; c < 4u && i + c < P.d; ++c)
+                P.out[i + c] = P.accumulate ? P.out[i + c] + r[c] : r[c];
         }
-    } else {
-        P.out[i0] = (float)((P.accumulate ? (double)P.out[i0] : 0.0) + sc * sum[0]);
     }
+}
+
+// Any bucket size: one coordinate per thread.
+__global__ __launch_bounds__(256) void k_unpack_accumulate_fixed1(UnpackParams P)
+{
+    const uint64_t i0 = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (i0 >= P.d)
+        return;
+    const uint64_t bk = i0 / P.bucket;
+    const uint32_t j0 = (uint32_t)(i0 - bk * P.bucket);
+    const uint32_t bit0 = j0 * P.b;
+    const uint32_t wi = bit0 >> 5, sh = bit0 & 31u;
+    const bool two = sh + P.b > 32u;                        // the code straddles a word boundary
+    const uint32_t mask_level = (1u << (P.b - 1u)) - 1u;
+    double sum = 0.0;
+    bool bad = false;
+    for (uint32_t k = 0; k < P.K; ++k) {
+        const uint32_t *f = P.packed[k] + bk * P.wpb + wi;
+        const uint32_t w0 = f[0];
+        const uint32_t w1 = two ? f[1] : 0u;
+        const uint64_t win = (((uint64_t)w0 << 32) | w1) << sh;     // the code on top
+        const uint32_t code = (uint32_t)(win >> (64u - P.b));
+        const uint32_t level = code & mask_level, neg = code >> (P.b - 1u);
+        bad |= level > P.s + 1u || (level == 0u && neg);
+        if (level) {
+            const double val = ldexp((double)P.norms[k][bk], (int)level - 1 - (int)P.s);
+            sum += neg ? -val : val;
+        }
+    }
+    if (bad)
+        atomicOr(P.flags, kFlagMalformed);
+    const float r = (float)((double)P.scale * sum);
+    P.out[i0] = P.accumulate ? P.out[i0] + r : r;
 }
 
 }  // namespace nuq
