@@ -81,6 +81,14 @@ def lib() -> ctypes.CDLL:
         L.nuqo_pack_fixed.restype = i32
         L.nuqo_unpack_fixed.argtypes = [vp, u64, u32, i32, u32, vp]
         L.nuqo_unpack_fixed.restype = i32
+        L.nuqo_huffman_lengths.argtypes = [vp, i32, vp]
+        L.nuqo_huffman_lengths.restype = i32
+        L.nuqo_huffman_codes.argtypes = [vp, i32, vp]
+        L.nuqo_huffman_codes.restype = i32
+        L.nuqo_encode_huffman.argtypes = [vp, u64, u32, i32, u32, vp, vp, vp, u64, vp]
+        L.nuqo_encode_huffman.restype = i32
+        L.nuqo_decode_huffman.argtypes = [vp, vp, u64, u32, i32, vp, vp]
+        L.nuqo_decode_huffman.restype = i32
         L.nuqo_bucket_norms_linf.argtypes = [vp, u64, u32, vp]
         L.nuqo_bucket_norms_linf.restype = None
         L.nuqo_quantize_coord_table.argtypes = [ctypes.c_float, ctypes.c_float, i32, vp, u32]
@@ -392,3 +400,59 @@ def unpack_average_fixed(norms_list, packed_list, d: int, bucket: int, s: int, b
         out += dequantize(unpack_fixed(packed, d, bucket, s, b), bucket, s, norms)
     out *= float(scale)
     return out if prior is None else np.asarray(prior, dtype=np.float64) + out
+
+
+# ------------------------------------------------------ Huffman-coded levels
+
+def level_histogram_of(q: np.ndarray, s: int) -> np.ndarray:
+    """Counts of the level indices 0..s+1 in level|sign bytes."""
+    return np.bincount(np.asarray(q, dtype=np.uint8) & 0x7F, minlength=s + 2)[: s + 2].astype(np.uint64)
+
+
+def huffman_lengths(hist, s: int) -> np.ndarray:
+    """Sec. 5 ("Efficient Encoding"): code lengths of the level indices from a sample's histogram."""
+    hist = np.ascontiguousarray(hist, dtype=np.uint64)
+    assert hist.size == s + 2
+    out = np.zeros(s + 2, dtype=np.uint8)
+    rc = lib().nuqo_huffman_lengths(_p(hist), s, _p(out))
+    if rc:
+        raise ValueError("huffman_lengths: %d" % rc)
+    return out
+
+
+def huffman_codes(lengths, s: int) -> list[str]:
+    """Canonical codewords as '0'/'1' strings."""
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    codes = np.zeros(16, dtype=np.uint32)
+    rc = lib().nuqo_huffman_codes(_p(lengths), s, _p(codes))
+    if rc:
+        raise ValueError("lengths do not describe a complete code")
+    return [format(int(codes[j]), "0%db" % int(lengths[j])) for j in range(s + 2)]
+
+
+def encode_huffman(q: np.ndarray, bucket: int, s: int, lengths, sync_stride: int = 0):
+    """Codeword of every coordinate's level index, then its sign bit when nonzero.  Returns (bit_off, words, sync)."""
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    d = q.size
+    nb = num_buckets(d, bucket)
+    cap = (d * 16 + 31) // 32 + nb
+    bit_off = np.zeros(nb + 1, dtype=np.uint64)
+    words = np.zeros(max(cap, 1), dtype=np.uint32)
+    ns = num_sync(bucket, sync_stride)
+    sync = np.zeros(max(nb * ns, 1), dtype=np.uint32)
+    rc = lib().nuqo_encode_huffman(_p(q), d, bucket, s, sync_stride, _p(lengths), _p(bit_off), _p(words), cap, _p(sync))
+    if rc:
+        raise RuntimeError("nuqo_encode_huffman failed: %d" % rc)
+    return bit_off, words[: (int(bit_off[-1]) + 31) // 32].copy(), sync[: nb * ns].copy()
+
+
+def decode_huffman(bit_off, words, d: int, bucket: int, s: int, lengths) -> np.ndarray:
+    bit_off = np.ascontiguousarray(bit_off, dtype=np.uint64)
+    words = np.ascontiguousarray(words if len(words) else np.zeros(1, np.uint32), dtype=np.uint32)
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    q = np.empty(d, dtype=np.uint8)
+    rc = lib().nuqo_decode_huffman(_p(bit_off), _p(words), d, bucket, s, _p(lengths), _p(q))
+    if rc:
+        raise ValueError("malformed stream: %d" % rc)
+    return q

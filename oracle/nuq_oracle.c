@@ -28,6 +28,10 @@
  *   nuqo_unpack_fixed      Table 1): every coordinate sends its sign and level index in b bits.
  *                          The paper gives no layout; the one used is in the design notes.
  *
+ *   nuqo_huffman_*         Sec. 5, "Efficient Encoding": a Huffman code for the level indices,
+ *                          built once from a sample's histogram ("encoded NUQSGD").  The
+ *                          paper says no more; construction and layout are in the design notes.
+ *
  * Points the paper leaves open (random number source, bit order, how the end
  * of a bucket's records is known, padding) are fixed by the wire-format
  * description in the project's design notes; this file implements that text.
@@ -40,6 +44,9 @@
  * the format text, not by the paper: "parity unpinned" by the paper for those.
  * The fixed-width functions are pinned by tests/test_oracle_fixed.py: a hand-packed
  * example, the size formula, unpack(pack(q)) == q, bit positions of single codes.
+ * The Huffman functions are pinned by tests/test_oracle_huffman.py: textbook code lengths
+ * (dyadic and Fibonacci weights), Kraft equality, optimality against brute force over all
+ * length assignments, hand-built canonical codes, a hand-coded bit string, the round trip.
  * The level-table functions are pinned by tests/test_oracle_levels.py: equality
  * with the functions above on the table (0, 2^-s, ..., 1/2, 1), exhaustive
  * enumeration of the draws against p(r) as an exact fraction, unbiasedness and
@@ -604,6 +611,162 @@ int nuqo_unpack_fixed(const uint32_t *packed, uint64_t d, uint32_t bucket, int s
                 return NUQO_EMALFORMED;
             q[i] = (uint8_t)(level | (neg << 7));
         }
+    }
+    return NUQO_OK;
+}
+
+/* ----------------------------------------------------- Huffman-coded levels */
+
+/*
+ * Code lengths for the level indices 0..s+1 from a histogram (Sec. 5: the code is built from
+ * an initial sample and then kept).  Huffman's algorithm on the weights hist[j] + 1 (so that a
+ * level the sample never showed still has a code): repeatedly merge the two smallest nodes,
+ * nodes ordered by (weight, id), a leaf's id being its symbol, the k-th merged node's id being
+ * nsym + k.  The length of a symbol is its depth.  nsym = s + 2 <= 16, so lengths are <= 15.
+ */
+int nuqo_huffman_lengths(const uint64_t *hist, int s, uint8_t *lengths)
+{
+    int nsym = s + 2;
+    if (s < 1 || nsym > 16)
+        return NUQO_EINVAL;
+    uint64_t weight[32];
+    int parent[32], alive[32];
+    for (int j = 0; j < nsym; j++) {
+        weight[j] = hist[j] + 1;
+        parent[j] = -1;
+        alive[j] = 1;
+    }
+    int nodes = nsym;
+    for (int step = 0; step < nsym - 1; step++) {
+        int a = -1, b = -1; /* smallest and second smallest by (weight, id): ids ascend with the index */
+        for (int i = 0; i < nodes; i++) {
+            if (!alive[i])
+                continue;
+            if (a < 0 || weight[i] < weight[a]) {
+                b = a;
+                a = i;
+            } else if (b < 0 || weight[i] < weight[b]) {
+                b = i;
+            }
+        }
+        weight[nodes] = weight[a] + weight[b];
+        parent[nodes] = -1;
+        alive[nodes] = 1;
+        alive[a] = alive[b] = 0;
+        parent[a] = parent[b] = nodes;
+        nodes++;
+    }
+    for (int j = 0; j < nsym; j++) {
+        int depth = 0;
+        for (int i = j; parent[i] >= 0; i = parent[i])
+            depth++;
+        lengths[j] = (uint8_t)depth;
+    }
+    return NUQO_OK;
+}
+
+/*
+ * Canonical code for given lengths: symbols in order of (length, symbol); the first gets
+ * code 0, each next one (previous code + 1) shifted left by the increase in length.
+ */
+int nuqo_huffman_codes(const uint8_t *lengths, int s, uint32_t *codes)
+{
+    int nsym = s + 2;
+    uint32_t code = 0;
+    int prev_len = 0, first = 1;
+    for (int len = 1; len <= 15; len++)
+        for (int j = 0; j < nsym; j++) {
+            if (lengths[j] != len)
+                continue;
+            if (!first)
+                code = (code + 1) << (len - prev_len);
+            first = 0;
+            prev_len = len;
+            codes[j] = code;
+        }
+    /* a complete code: the last codeword is all ones */
+    return (!first && code == (1u << prev_len) - 1u) ? NUQO_OK : NUQO_EINVAL;
+}
+
+/*
+ * Message of the level|sign bytes q: per bucket, for every coordinate in order, the codeword of
+ * its level index (most significant bit first) followed, when the level is not zero, by its sign
+ * bit.  bit_off, words and alignment as in nuqo_encode.  sync entry (b, g), g = 1..nsync: the
+ * bit offset, from the bucket's start, of coordinate g * sync_stride.
+ */
+int nuqo_encode_huffman(const uint8_t *q, uint64_t d, uint32_t bucket, int s, uint32_t sync_stride,
+                        const uint8_t *lengths, uint64_t *bit_off, uint32_t *words, uint64_t words_cap,
+                        uint32_t *sync)
+{
+    uint32_t codes[16];
+    if (nuqo_huffman_codes(lengths, s, codes))
+        return NUQO_EINVAL;
+    uint64_t nb = (d + bucket - 1) / bucket, nsync = num_sync(bucket, sync_stride);
+    uint64_t t = 0;
+    memset(words, 0, words_cap * sizeof(uint32_t));
+    bit_off[0] = 0;
+    for (uint64_t b = 0; b < nb; b++) {
+        uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        t = (t + 31) / 32 * 32;
+        uint64_t start = t;
+        for (uint64_t g = 1; g <= nsync; g++)
+            sync[b * nsync + g - 1] = 0;
+        for (uint64_t i = lo; i < hi; i++) {
+            uint32_t level = q[i] & 0x7f, neg = q[i] >> 7;
+            if (level > (uint32_t)s + 1 || (level == 0 && neg))
+                return NUQO_EINVAL;
+            if (sync_stride && (i - lo) % sync_stride == 0 && i > lo)
+                sync[b * nsync + (i - lo) / sync_stride - 1] = (uint32_t)(t - start);
+            uint32_t need = lengths[level] + (level ? 1u : 0u);
+            if ((t + need + 31) / 32 > words_cap)
+                return NUQO_ECAPACITY;
+            for (int k = lengths[level] - 1; k >= 0; k--)
+                put_bit(words, t++, (codes[level] >> k) & 1);
+            if (level)
+                put_bit(words, t++, (int)neg);
+        }
+        for (uint64_t g = 1; g <= nsync; g++) /* boundaries at or beyond a short last bucket's end: its end */
+            if (g * sync_stride >= hi - lo)
+                sync[b * nsync + g - 1] = (uint32_t)(t - start);
+        bit_off[b + 1] = t;
+    }
+    return NUQO_OK;
+}
+
+/* Back to level|sign bytes, bit by bit: walk the canonical code one length at a time. */
+int nuqo_decode_huffman(const uint64_t *bit_off, const uint32_t *words, uint64_t d, uint32_t bucket, int s,
+                        const uint8_t *lengths, uint8_t *q)
+{
+    uint32_t codes[16];
+    if (nuqo_huffman_codes(lengths, s, codes))
+        return NUQO_EINVAL;
+    int nsym = s + 2;
+    uint64_t nb = (d + bucket - 1) / bucket;
+    for (uint64_t b = 0; b < nb; b++) {
+        uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
+        uint64_t t = (bit_off[b] + 31) / 32 * 32, end = bit_off[b + 1];
+        for (uint64_t i = lo; i < hi; i++) {
+            uint32_t prefix = 0;
+            int len = 0, level = -1;
+            while (level < 0) {
+                if (t >= end || len == 15)
+                    return NUQO_EMALFORMED;
+                prefix = (prefix << 1) | (uint32_t)get_bit(words, t++);
+                len++;
+                for (int j = 0; j < nsym; j++)
+                    if (lengths[j] == len && codes[j] == prefix)
+                        level = j;
+            }
+            int neg = 0;
+            if (level) {
+                if (t >= end)
+                    return NUQO_EMALFORMED;
+                neg = get_bit(words, t++);
+            }
+            q[i] = (uint8_t)(level | (neg << 7));
+        }
+        if (t != end)
+            return NUQO_EMALFORMED;
     }
     return NUQO_OK;
 }
