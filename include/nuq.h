@@ -224,6 +224,46 @@ int nuq_unpack_accumulate_fixed(uint32_t K, const float *const *norms, const uin
                                 uint64_t d, uint32_t bucket, uint32_t s, uint32_t b, float scale,
                                 int accumulate, float *out, nuq_stream_t stream);
 
+/* ---- Huffman-coded levels (Sec. 5, "Efficient Encoding": a Huffman code for the level indices, built
+ *      from a sample and then kept) ------------------------------------------------------------------ */
+
+/* hist[0..15] (DEVICE, overwritten) <- how often each level index occurs in the level|sign bytes q[d]. */
+int nuq_level_histogram(const uint8_t *q, uint64_t d, uint64_t *hist, nuq_stream_t stream);
+
+/* Host arithmetic.  lengths[0..s+1] <- code lengths from the histogram hist[0..s+1] (both HOST):
+ * Huffman's algorithm on hist[j] + 1 (a level the sample never showed still gets a code), merging
+ * the two smallest nodes by (weight, id), a leaf's id being its symbol, the k-th merged node's id
+ * s + 2 + k.  Lengths are 1..s+1.  The codewords are the canonical ones: symbols by (length, symbol),
+ * the first is 0, each next one (previous + 1) shifted left by the increase in length. */
+int nuq_huffman_lengths(const uint64_t *hist, uint32_t s, uint8_t *lengths);
+
+/* Capacity that always suffices for nuq_encode_huffman's words, and its workspace size. */
+uint64_t nuq_huffman_max_words(uint64_t d, uint32_t bucket);
+uint64_t nuq_encode_huffman_workspace_bytes(uint64_t d, uint32_t bucket);
+
+/* Message of the bytes q[d] under the code `lengths` (HOST, s + 2 values; NUQ_EINVAL unless they give a
+ * complete prefix code): per bucket, for every coordinate in order, the codeword of its level index
+ * (most significant bit first), then its sign bit when the level is not zero.  bit_off[B+1], words,
+ * word alignment, capacity flag and workspace alignment as for nuq_encode.  sync entry (b, g),
+ * g = 1..nsync: bit offset, from the bucket's start, of coordinate g * sync_stride (the bucket's bit
+ * length where the bucket ends before it). */
+int nuq_encode_huffman(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint32_t sync_stride,
+                       const uint8_t *lengths, uint64_t *bit_off, uint32_t *words, uint64_t words_cap,
+                       uint32_t *sync, void *workspace, uint64_t workspace_bytes, nuq_stream_t stream);
+
+/* q[d] <- the level|sign bytes of such a message.  A segment that does not end where the next one
+ * starts, a prefix that is no codeword, or a sync entry out of order raises NUQ_FLAG_MALFORMED. */
+int nuq_decode_huffman(const uint64_t *bit_off, const uint32_t *words, const uint32_t *sync, uint64_t d,
+                       uint32_t bucket, uint32_t s, uint32_t sync_stride, const uint8_t *lengths,
+                       uint8_t *q, nuq_stream_t stream);
+
+/* out[i] = (accumulate ? out[i] : 0) + scale * sum_k norms_k[b] * sign * l_j from K arrays of
+ * level|sign bytes (norms, q: HOST arrays of K device pointers): the aggregate of Alg. 1 for messages
+ * already decoded to bytes.  fp64 sum in worker order, rounded to fp32 once. */
+int nuq_average_levels(uint32_t K, const float *const *norms, const uint8_t *const *q, uint64_t d,
+                       uint32_t bucket, uint32_t s, float scale, int accumulate, float *out,
+                       nuq_stream_t stream);
+
 /* ---- errors ---------------------------------------------------------------------- */
 
 /* Waits for `stream`, copies the sticky device flags of the current device to

@@ -43,6 +43,13 @@ _SIGNATURES = {
     "nuq_pack_fixed": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp]),
     "nuq_quantize_pack_fixed_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "nuq_unpack_accumulate_fixed": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _i32, _vp, _vp]),
+    "nuq_level_histogram": (_i32, [_vp, _u64, _vp, _vp]),
+    "nuq_huffman_lengths": (_i32, [_vp, _u32, _vp]),
+    "nuq_huffman_max_words": (_u64, [_u64, _u32]),
+    "nuq_encode_huffman_workspace_bytes": (_u64, [_u64, _u32]),
+    "nuq_encode_huffman": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
+    "nuq_decode_huffman": (_i32, [_vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
+    "nuq_average_levels": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _f32, _i32, _vp, _vp]),
     "nuq_last_error_flags": (_i32, [_vp, _vp]),
     "nuq_timing_begin": (_i32, [_u32]),
     "nuq_timing_collect": (_i32, [_vp, _vp, _u32, _vp]),
@@ -271,6 +278,68 @@ def nuq_unpack_accumulate_fixed(norms: list[torch.Tensor], packed: list[torch.Te
     _check("nuq_unpack_accumulate_fixed",
            _lib.nuq_unpack_accumulate_fixed(K, arr(norms, torch.float32), arr(packed, torch.int32), d, bucket, s, b,
                                             float(scale), 1 if accumulate else 0, _ptr(out, torch.float32), _stream()))
+
+
+# -------------------------------------------------------- Huffman-coded levels
+
+def nuq_level_histogram(q: torch.Tensor, hist: torch.Tensor) -> None:
+    """hist: int64[16] on the device, overwritten."""
+    if hist.numel() < 16:
+        raise ValueError("hist holds 16 counters")
+    _check("nuq_level_histogram",
+           _lib.nuq_level_histogram(_ptr(q, torch.uint8), q.numel(), _ptr(hist, torch.int64), _stream()))
+
+
+def nuq_huffman_lengths(hist: list[int], s: int) -> list[int]:
+    """Host arithmetic: code lengths of the level indices 0..s+1 from their counts."""
+    if len(hist) != s + 2:
+        raise ValueError("one count per level index 0..s+1")
+    h = (ctypes.c_uint64 * (s + 2))(*[int(x) for x in hist])
+    out = (ctypes.c_uint8 * (s + 2))()
+    _check("nuq_huffman_lengths", _lib.nuq_huffman_lengths(h, s, out))
+    return list(out)
+
+
+def nuq_huffman_max_words(d: int, bucket: int) -> int:
+    return _lib.nuq_huffman_max_words(d, bucket)
+
+
+def nuq_encode_huffman_workspace_bytes(d: int, bucket: int) -> int:
+    return _lib.nuq_encode_huffman_workspace_bytes(d, bucket)
+
+
+def _lengths(lengths, s: int):
+    if len(lengths) != s + 2:
+        raise ValueError("one code length per level index 0..s+1")
+    return (ctypes.c_uint8 * (s + 2))(*[int(x) for x in lengths])
+
+
+def nuq_encode_huffman(q: torch.Tensor, bucket: int, s: int, sync_stride: int, lengths, bit_off: torch.Tensor,
+                       words: torch.Tensor, sync: torch.Tensor | None, workspace: torch.Tensor) -> None:
+    _check("nuq_encode_huffman",
+           _lib.nuq_encode_huffman(_ptr(q, torch.uint8), q.numel(), bucket, s, sync_stride, _lengths(lengths, s),
+                                   _ptr(bit_off, torch.int64), _ptr(words, torch.int32), words.numel(), _ptr(sync),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def nuq_decode_huffman(bit_off: torch.Tensor, words: torch.Tensor, sync: torch.Tensor | None, d: int, bucket: int,
+                       s: int, sync_stride: int, lengths, q: torch.Tensor) -> None:
+    if q.numel() != d:
+        raise ValueError("q must hold d bytes")
+    _check("nuq_decode_huffman",
+           _lib.nuq_decode_huffman(_ptr(bit_off, torch.int64), _ptr(words, torch.int32), _ptr(sync), d, bucket, s,
+                                   sync_stride, _lengths(lengths, s), _ptr(q, torch.uint8), _stream()))
+
+
+def nuq_average_levels(norms: list[torch.Tensor], qs: list[torch.Tensor], d: int, bucket: int, s: int, scale: float,
+                       accumulate: bool, out: torch.Tensor) -> None:
+    K = len(norms)
+    arr = lambda ts, dt: (ctypes.c_void_p * K)(*[_ptr(t, dt) for t in ts])
+    if out.numel() != d or len(qs) != K:
+        raise ValueError("K norm arrays, K byte arrays and d floats of output are needed")
+    _check("nuq_average_levels",
+           _lib.nuq_average_levels(K, arr(norms, torch.float32), arr(qs, torch.uint8), d, bucket, s, float(scale),
+                                   1 if accumulate else 0, _ptr(out, torch.float32), _stream()))
 
 
 def nuq_last_error_flags() -> int:

@@ -11,6 +11,7 @@
 #include "nuq_device.hpp"
 #include "nuq_encode_kernels.hpp"
 #include "nuq_fixed_kernels.hpp"
+#include "nuq_huffman_kernels.hpp"
 #include "nuq_table_kernels.hpp"
 
 namespace {
@@ -304,6 +305,54 @@ int pack_fixed_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t buc
         hipLaunchKernelGGL(kern, grid, dim3(G::kWG), lds_bytes, st, P, Wk, F);
         return check_launch();
     });
+}
+
+// Canonical code tables from code lengths (host arithmetic).  False unless the lengths describe a complete
+// prefix code over the s + 2 level indices with lengths 1..15.
+bool huffman_tables(const uint8_t *lengths, uint32_t s, HuffmanCode &H)
+{
+    H = HuffmanCode{};
+    H.nsym = s + 2u;
+    uint32_t next = 0, code = 0, prev_len = 0;
+    bool any = false;
+    for (uint32_t len = 1; len <= 15u; ++len) {
+        H.offset[len] = next;
+        for (uint32_t j = 0; j < H.nsym; ++j) {
+            if (lengths[j] != len)
+                continue;
+            if (any)
+                code = (code + 1u) << (len - prev_len);
+            any = true;
+            prev_len = len;
+            if (!H.count[len])
+                H.first[len] = code;
+            ++H.count[len];
+            H.code[j] = code;
+            H.len[j] = len;
+            H.sorted[next++] = j;
+            H.maxlen = len;
+        }
+    }
+    return any && next == H.nsym && code == (1u << prev_len) - 1u;
+}
+
+struct HuffmanWorkspace {
+    uint32_t *lens;
+    uint64_t *chunk_sums;
+    uint64_t bytes;
+};
+
+HuffmanWorkspace carve_huffman(void *base, uint64_t nb)
+{
+    HuffmanWorkspace w{};
+    const uint64_t nb_stride = (nb + 3) & ~3ull, nchunks = (nb + kChunk - 1) / kChunk;
+    uint8_t *p = static_cast<uint8_t *>(base);
+    w.lens = reinterpret_cast<uint32_t *>(p);
+    uint64_t off = (nb_stride * 4 + 15) & ~15ull;
+    w.chunk_sums = reinterpret_cast<uint64_t *>(p + off);
+    off += (nchunks + 1) * 8;
+    w.bytes = (off + 15) & ~15ull;
+    return w;
 }
 
 // Workgroups of the persistent decode kernel that the current device holds at once (0 on error).
@@ -711,6 +760,206 @@ int nuq_unpack_accumulate_fixed(uint32_t K, const float *const *norms, const uin
         default: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<8>, grid, dim3(256), 0, st, P); break;
         }
     }
+    return check_launch();
+}
+
+int nuq_level_histogram(const uint8_t *q, uint64_t d, uint64_t *hist, nuq_stream_t stream)
+{
+    if (!q || !hist || d < 1)
+        return NUQ_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(k_zero_u64, dim3(1), dim3(64), 0, st, reinterpret_cast<unsigned long long *>(hist), 16u);
+    const uint64_t blocks = (d + 256ull * 64 - 1) / (256ull * 64);
+    hipLaunchKernelGGL(k_level_histogram, dim3((uint32_t)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, st, q, d,
+                       reinterpret_cast<unsigned long long *>(hist));
+    return check_launch();
+}
+
+int nuq_huffman_lengths(const uint64_t *hist, uint32_t s, uint8_t *lengths)
+{
+    if (!hist || !lengths || s < 1 || s > NUQ_MAX_S)
+        return NUQ_EINVAL;
+    // Huffman's algorithm on hist[j] + 1; the two smallest nodes by (weight, id) are merged, a leaf's id is its
+    // symbol, merged nodes get ids nsym, nsym + 1, ... in order of creation.
+    const uint32_t nsym = s + 2u;
+    struct Node {
+        uint64_t weight;
+        int parent;
+        bool open;
+    } node[32];
+    for (uint32_t j = 0; j < nsym; ++j)
+        node[j] = Node{hist[j] + 1u, -1, true};
+    uint32_t count = nsym;
+    while (count < 2u * nsym - 1u) {
+        int lo1 = -1, lo2 = -1;
+        for (uint32_t i = 0; i < count; ++i) {
+            if (!node[i].open)
+                continue;
+            if (lo1 < 0 || node[i].weight < node[lo1].weight) {
+                lo2 = lo1;
+                lo1 = (int)i;
+            } else if (lo2 < 0 || node[i].weight < node[lo2].weight) {
+                lo2 = (int)i;
+            }
+        }
+        node[count] = Node{node[lo1].weight + node[lo2].weight, -1, true};
+        node[lo1].open = node[lo2].open = false;
+        node[lo1].parent = node[lo2].parent = (int)count;
+        ++count;
+    }
+    for (uint32_t j = 0; j < nsym; ++j) {
+        uint32_t depth = 0;
+        for (int i = (int)j; node[i].parent >= 0; i = node[i].parent)
+            ++depth;
+        lengths[j] = (uint8_t)depth;
+    }
+    return NUQ_OK;
+}
+
+uint64_t nuq_huffman_max_words(uint64_t d, uint32_t bucket)
+{
+    if (!bucket)
+        return 0;
+    return (d * 16 + 31) / 32 + nuq_num_buckets(d, bucket);
+}
+
+uint64_t nuq_encode_huffman_workspace_bytes(uint64_t d, uint32_t bucket)
+{
+    if (!bucket)
+        return 0;
+    return carve_huffman(nullptr, nuq_num_buckets(d, bucket)).bytes;
+}
+
+int nuq_encode_huffman(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint32_t sync_stride,
+                       const uint8_t *lengths, uint64_t *bit_off, uint32_t *words, uint64_t words_cap,
+                       uint32_t *sync, void *workspace, uint64_t workspace_bytes, nuq_stream_t stream)
+{
+    if (!q || !lengths || !bit_off || !words || !workspace || !valid_common(d, bucket, s) ||
+        !valid_sync(sync_stride) || (reinterpret_cast<uintptr_t>(workspace) & 15u))
+        return NUQ_EINVAL;
+    const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
+    if (nsync && !sync)
+        return NUQ_EINVAL;
+    HuffmanCode H;
+    if (!huffman_tables(lengths, s, H))
+        return NUQ_EINVAL;
+    const uint64_t nb = nuq_num_buckets(d, bucket);
+    const HuffmanWorkspace w = carve_huffman(workspace, nb);
+    if (w.bytes > workspace_bytes)
+        return NUQ_ECAPACITY;
+    uint32_t *flags = flags_ptr();
+    if (!flags)
+        return NUQ_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    EncodeParams P{};
+    EncodeBatch Wk{};
+    Wk.w[0].q_in = q;
+    Wk.w[0].bit_off = bit_off;
+    Wk.w[0].words = words;
+    Wk.w[0].words_cap = words_cap;
+    Wk.w[0].sync = sync;
+    P.d = d;
+    P.nb = nb;
+    P.nb_stride = (nb + 3) & ~3ull;
+    P.bucket = bucket;
+    P.s = s;
+    P.sync_shift = nsync ? log2u(sync_stride) : 0;
+    P.nsync = nsync;
+    P.lens = w.lens;
+    P.flags = flags;
+    const uint64_t nchunks = (nb + kChunk - 1) / kChunk;
+    return dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
+        constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
+        using G = TeamGeom<TEAM>;
+        P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
+        P.lds_words = huffman_lds_words(P.rows, TEAM, bucket, nsync);
+        const size_t lds_bytes = (size_t)P.lds_words * 4 * G::kTeamsPerWG;
+        if (lds_bytes > 160 * 1024)
+            return (int)NUQ_EINVAL;
+        auto emit = k_huffman_emit<TEAM, VPT>;
+        if (lds_bytes > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void *>(emit), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_bytes) != hipSuccess)
+            return (int)NUQ_EHIP;
+        dim3 grid;
+        if (!bucket_grid<TEAM>(nb, 1, grid))
+            return (int)NUQ_EINVAL;
+        hipLaunchKernelGGL((k_huffman_lens<TEAM, VPT>), grid, dim3(G::kWG), 0, st, P, Wk, H);
+        hipLaunchKernelGGL(k_chunk_sums, dim3((uint32_t)nchunks, 1), dim3(256), 0, st, w.lens, nb, P.nb_stride, nchunks,
+                           w.chunk_sums);
+        hipLaunchKernelGGL(k_chunk_scan, dim3(1), dim3(256), 0, st, w.chunk_sums, nchunks);
+        hipLaunchKernelGGL(k_bit_offsets, dim3((uint32_t)nchunks), dim3(256), 0, st, w.lens, nb, w.chunk_sums, bit_off);
+        ScopedTiming timing(NUQ_T_ENCODE, st);
+        hipLaunchKernelGGL(emit, grid, dim3(G::kWG), lds_bytes, st, P, Wk, H);
+        return check_launch();
+    });
+}
+
+int nuq_decode_huffman(const uint64_t *bit_off, const uint32_t *words, const uint32_t *sync, uint64_t d,
+                       uint32_t bucket, uint32_t s, uint32_t sync_stride, const uint8_t *lengths, uint8_t *q,
+                       nuq_stream_t stream)
+{
+    if (!bit_off || !words || !lengths || !q || !valid_common(d, bucket, s) || !valid_sync(sync_stride))
+        return NUQ_EINVAL;
+    const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
+    if (nsync && !sync)
+        return NUQ_EINVAL;
+    HuffmanCode H;
+    if (!huffman_tables(lengths, s, H))
+        return NUQ_EINVAL;
+    uint32_t *flags = flags_ptr();
+    if (!flags)
+        return NUQ_EHIP;
+    HuffmanDecodeParams P{};
+    P.bit_off = bit_off;
+    P.words = words;
+    P.sync = sync;
+    P.q = q;
+    P.flags = flags;
+    P.d = d;
+    P.nb = nuq_num_buckets(d, bucket);
+    P.bucket = bucket;
+    P.sync_shift = nsync ? log2u(sync_stride) : 0;
+    P.nsync = nsync;
+    P.nseg = nsync + 1;
+    const uint64_t units = P.nb * P.nseg, blocks = (units + 255) / 256;
+    if (blocks > 0x7fffffffull)
+        return NUQ_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(NUQ_T_DECODE, st);
+    hipLaunchKernelGGL(k_huffman_decode, dim3((uint32_t)blocks), dim3(256), 0, st, P, H);
+    return check_launch();
+}
+
+int nuq_average_levels(uint32_t K, const float *const *norms, const uint8_t *const *q, uint64_t d, uint32_t bucket,
+                       uint32_t s, float scale, int accumulate, float *out, nuq_stream_t stream)
+{
+    if (K < 1 || K > NUQ_MAX_WORKERS || !norms || !q || !out || !valid_common(d, bucket, s))
+        return NUQ_EINVAL;
+    AverageParams P{};
+    bool aligned = bucket % 4u == 0;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!norms[k] || !q[k])
+            return NUQ_EINVAL;
+        P.norms[k] = norms[k];
+        P.q[k] = q[k];
+        aligned = aligned && (reinterpret_cast<uintptr_t>(q[k]) & 3u) == 0;
+    }
+    P.out = out;
+    P.d = d;
+    P.K = K;
+    P.bucket = bucket;
+    P.s = s;
+    P.scale = scale;
+    P.accumulate = accumulate;
+    const uint64_t threads = aligned ? (d + 3) / 4 : d, blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffull)
+        return NUQ_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (aligned)
+        hipLaunchKernelGGL(k_average_levels<4>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
+    else
+        hipLaunchKernelGGL(k_average_levels<1>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
     return check_launch();
 }
 

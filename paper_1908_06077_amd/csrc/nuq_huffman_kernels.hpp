@@ -1,0 +1,328 @@
+// Huffman-coded levels (Sec. 5, "Efficient Encoding": a Huffman code for the level indices, built from a sample and
+// then kept).  Message of the level|sign bytes: per bucket, for every coordinate in order, the canonical codeword of
+// its level index (most significant bit first), then its sign bit when the level is not zero; bit_off, words and
+// word alignment as for the ERC strings; sync entry (b, g) = bit offset, from the bucket's start, of coordinate
+// g * stride (the bucket's bit length if the bucket ends before it).
+#pragma once
+
+#include "nuq_decode_kernels.hpp"
+#include "nuq_encode_kernels.hpp"
+
+namespace nuq {
+
+// A canonical code over the level indices 0..s+1 (at most 16 symbols, lengths 1..15).
+struct HuffmanCode {
+    uint32_t code[16];     // codeword of a symbol, right-aligned
+    uint32_t len[16];      // its length
+    uint32_t first[16];    // by length L: first codeword of that length
+    uint32_t count[16];    // number of codewords of that length
+    uint32_t offset[16];   // index into `sorted` of the first symbol of that length
+    uint32_t sorted[16];   // symbols by (length, symbol)
+    uint32_t maxlen;
+    uint32_t nsym;
+};
+
+// ---------------------------------------------------------------------------- histogram
+__global__ __launch_bounds__(256) void k_level_histogram(const uint8_t *q, uint64_t d, unsigned long long *hist)
+{
+    __shared__ uint32_t local[128];
+    if (threadIdx.x < 128u)
+        local[threadIdx.x] = 0u;
+    __syncthreads();
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < d; i += stride)
+        atomicAdd(&local[q[i] & 0x7fu], 1u);
+    __syncthreads();
+    if (threadIdx.x < 16u && local[threadIdx.x])
+        atomicAdd(&hist[threadIdx.x], (unsigned long long)local[threadIdx.x]);
+    // level indices above 15 cannot be coded; they are counted nowhere and rejected by the encoder
+}
+
+__global__ void k_zero_u64(unsigned long long *p, uint32_t n)
+{
+    if (threadIdx.x < n)
+        p[threadIdx.x] = 0ull;
+}
+
+// ------------------------------------------------------------------- bucket bit lengths
+// lens[b] = sum over the bucket of len[level] + (level != 0).  One bucket per team, bytes read as in the encoders.
+template <int TEAM, int VPT>
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_huffman_lens(EncodeParams P, EncodeBatch Wk, HuffmanCode H)
+{
+    __shared__ uint32_t scratch_all[TeamGeom<TEAM>::kTeamsPerWG][16];
+    const EncodeWorker &W = Wk.w[0];
+    const uint32_t tid = threadIdx.x % TEAM;
+    const uint32_t team = threadIdx.x / TEAM;
+    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + team;
+    const bool active = b < P.nb;
+    const uint64_t base = active ? b * P.bucket : 0;
+    const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
+    const uint8_t *qg = W.q_in + base;
+    uint32_t bits = 0;
+    bool bad = false;
+    for (uint32_t c = tid; c < nbk; c += TEAM) {
+        const uint32_t byte = qg[c], level = byte & 0x7fu;
+        bad |= level > P.s + 1u || (level == 0u && byte);
+        bits += H.len[min(level, 15u)] + (level ? 1u : 0u);
+    }
+    if (bad)
+        atomicOr(P.flags, kFlagMalformed);
+    uint32_t total;
+    team_exclusive_sum<TEAM>(bits, scratch_all[team], total);
+    if (active && tid == 0)
+        P.lens[b] = total;
+}
+
+// bit_off from lens: one workgroup per chunk of 1024 buckets, chunk_prefix[c] = words before the chunk.
+__global__ __launch_bounds__(256) void k_bit_offsets(const uint32_t *lens, uint64_t nb, const uint64_t *chunk_prefix,
+                                                     uint64_t *bit_off)
+{
+    __shared__ uint32_t wave_tot[4];
+    const uint64_t b0 = (uint64_t)blockIdx.x * kChunk + threadIdx.x * 4u;
+    uint32_t len[4], wc[4], mine = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        len[i] = b0 + i < nb ? lens[b0 + i] : 0u;
+        wc[i] = (len[i] + 31u) >> 5;
+        mine += wc[i];
+    }
+    uint32_t inc = mine;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = (uint32_t)__shfl_up((int)inc, off, 64);
+        if (lane >= off)
+            inc += t;
+    }
+    if (lane == 63)
+        wave_tot[wave] = inc;
+    __syncthreads();
+    uint64_t start = chunk_prefix[blockIdx.x] + inc - mine;
+    for (int w = 0; w < wave; ++w)
+        start += wave_tot[w];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (b0 + i < nb)
+            bit_off[b0 + i + 1] = 32ull * start + len[i];
+        start += wc[i];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        bit_off[0] = 0;
+}
+
+// --------------------------------------------------------------------------------- emit
+// LDS words per team: [qb32: rows * TEAM][field: worst case ceil(bucket * 16 / 32) + 1][sync: nsync][scratch: 64]
+__host__ __device__ inline uint32_t huffman_lds_words(uint32_t rows, uint32_t team, uint32_t bucket, uint32_t nsync)
+{
+    const uint32_t w = (rows * team + (bucket + 1u) / 2u + 1u + nsync + 1u) & ~1u;
+    return w + 64u;
+}
+
+template <int TEAM, int VPT>
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_huffman_emit(EncodeParams P, EncodeBatch Wk, HuffmanCode H)
+{
+    extern __shared__ __align__(16) uint32_t smem[];
+    const EncodeWorker &W = Wk.w[0];
+    const uint32_t tid = threadIdx.x % TEAM;
+    const uint32_t team = team_uniform_u32<TEAM>(threadIdx.x / TEAM);
+    uint32_t *lds = smem + team * P.lds_words;
+    uint32_t *qb32 = lds;
+    uint32_t *field = qb32 + P.rows * TEAM;
+    uint32_t *sync_l = field + (P.bucket + 1u) / 2u + 1u;
+    uint32_t *scratch = lds + P.lds_words - 64u;
+    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + team;
+    const bool active = b < P.nb;
+    const uint64_t base = active ? b * P.bucket : 0;
+    const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
+    front_bytes_to_lds<TEAM>(P, W, base, nbk, tid, qb32);
+    __syncthreads();
+
+    const uint8_t *qbytes = reinterpret_cast<const uint8_t *>(qb32);
+    const uint32_t per = P.rows * 4u;
+    const uint32_t c0 = min(tid * per, nbk), c1 = min(c0 + per, nbk);
+    uint32_t bits = 0;
+    for (uint32_t c = c0; c < c1; ++c) {
+        const uint32_t level = min((uint32_t)qbytes[c] & 0x7fu, 15u);
+        bits += H.len[level] + (level ? 1u : 0u);
+    }
+    uint32_t total;
+    uint32_t pos = team_exclusive_sum<TEAM>(bits, scratch, total);
+    const uint32_t nwords = (total + 31u) >> 5;
+    for (uint32_t i = tid; i < nwords; i += TEAM)
+        field[i] = 0u;
+    for (uint32_t i = tid; i < P.nsync; i += TEAM)
+        sync_l[i] = total;                          // boundaries at or beyond the bucket's end
+    team_barrier<TEAM>();
+
+    if (c0 < c1) {
+        uint32_t wi = pos >> 5, fill = pos & 31u;
+        uint64_t acc = 0;
+        const uint32_t smask = P.sync_shift ? (1u << P.sync_shift) - 1u : 0u;
+        for (uint32_t c = c0; c < c1; ++c) {
+            if (P.sync_shift && c && (c & smask) == 0u)
+                sync_l[(c >> P.sync_shift) - 1u] = pos;
+            const uint32_t byte = qbytes[c], level = min(byte & 0x7fu, 15u);
+            uint32_t n = H.len[level];
+            uint32_t v = H.code[level];
+            if (level) {
+                v = (v << 1) | (byte >> 7);
+                ++n;
+            }
+            acc = (acc << n) | v;                   // n <= 16: at most 31 + 16 bits are pending
+            fill += n;
+            pos += n;
+            if (fill >= 32u) {
+                fill -= 32u;
+                atomicOr(&field[wi++], (uint32_t)(acc >> fill));
+                acc &= (1ull << fill) - 1ull;
+            }
+        }
+        if (fill)
+            atomicOr(&field[wi], (uint32_t)(acc << (32u - fill)));
+    }
+    team_barrier<TEAM>();
+    if (active) {
+        const uint64_t start_word = (W.bit_off[b] + 31ull) >> 5;
+        const bool fits = start_word + nwords <= W.words_cap;
+        if (fits)
+            for (uint32_t i = tid; i < nwords; i += TEAM)
+                W.words[start_word + i] = field[i];
+        else if (tid == 0 && nwords)
+            atomicOr(P.flags, kFlagCapacity);
+        uint32_t *sg = W.sync + b * P.nsync;
+        for (uint32_t i = tid; i < P.nsync; i += TEAM)
+            sg[i] = sync_l[i];
+    }
+}
+
+// ------------------------------------------------------------------------------- decode
+struct HuffmanDecodeParams {
+    const uint64_t *bit_off;
+    const uint32_t *words;
+    const uint32_t *sync;
+    uint8_t *q;
+    uint32_t *flags;
+    uint64_t d;
+    uint64_t nb;
+    uint32_t bucket;
+    uint32_t sync_shift;
+    uint32_t nsync;
+    uint32_t nseg;
+};
+
+// One thread per unit = (bucket, sync segment): walks its codewords and writes level|sign bytes.
+__global__ __launch_bounds__(256) void k_huffman_decode(HuffmanDecodeParams P, HuffmanCode H)
+{
+    const uint64_t u = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (u >= P.nb * P.nseg)
+        return;
+    const uint64_t b = u / P.nseg;
+    const uint32_t g = (uint32_t)(u - b * P.nseg);
+    const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
+    const uint32_t c_lo = P.sync_shift ? g << P.sync_shift : 0u;
+    if (c_lo >= nbk)
+        return;
+    const uint32_t c_hi = P.sync_shift ? min(nbk, (g + 1u) << P.sync_shift) : nbk;
+    const uint64_t start = (P.bit_off[b] + 31ull) & ~31ull, end = P.bit_off[b + 1];
+    const uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
+    const uint32_t *sg = P.sync + b * P.nsync;
+    const uint32_t lo = g ? sg[g - 1u] : 0u;
+    const uint32_t hi = g + 1u < P.nseg ? sg[g] : len;           // where the next segment starts
+    bool bad = lo > hi || hi > len;
+    uint8_t *qb = P.q + b * P.bucket;
+    if (!bad) {
+        WalkWords gw{P.words + (start >> 5)};
+        BitReader<WalkWords> br;
+        br.init(gw, lo, (len + 31u) >> 5);
+        uint32_t pos = lo;
+        for (uint32_t c = c_lo; c < c_hi; ++c) {
+            br.refill();
+            const uint32_t w = br.peek();
+            uint32_t L = 1, sym = 0;
+            bool found = false;
+            for (; L <= H.maxlen; ++L) {
+                const uint32_t idx = (w >> (32u - L)) - H.first[L];
+                if (idx < H.count[L]) {
+                    sym = H.sorted[H.offset[L] + idx];
+                    found = true;
+                    break;
+                }
+            }
+            const uint32_t n = L + (sym ? 1u : 0u);
+            if (!found || pos + n > hi) {
+                bad = true;
+                break;
+            }
+            const uint32_t neg = sym ? (w >> (31u - L)) & 1u : 0u;
+            qb[c] = (uint8_t)(sym | (neg << 7));
+            br.skip(n);
+            pos += n;
+        }
+        bad |= pos != hi;
+    }
+    if (bad)
+        atomicOr(P.flags, kFlagMalformed);
+}
+
+// ------------------------------------------------------------------ average of level bytes
+struct AverageParams {
+    const float *norms[kMaxBatch];
+    const uint8_t *q[kMaxBatch];
+    float *out;
+    uint64_t d;
+    uint32_t K;
+    uint32_t bucket;
+    uint32_t s;
+    float scale;
+    int accumulate;
+};
+
+// out[i] = [out[i] +] scale * sum_k norms_k[bucket] * sign * 2^(level - 1 - s) from K arrays of level|sign bytes:
+// fp64 sum in worker order, rounded to fp32 (a prior is added in fp32 after that).  VEC = 4 when buckets are multiples
+// of four and everything is aligned, else 1.
+template <int VEC>
+__global__ __launch_bounds__(256) void k_average_levels(AverageParams P)
+{
+    const uint64_t i0 = ((uint64_t)blockIdx.x * 256u + threadIdx.x) * VEC;
+    if (i0 >= P.d)
+        return;
+    const uint64_t bk = i0 / P.bucket;
+    double sum[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c)
+        sum[c] = 0.0;
+    for (uint32_t k = 0; k < P.K; ++k) {
+        uint32_t bytes;
+        if constexpr (VEC == 4) {
+            if (i0 + 3u < P.d) {
+                bytes = *reinterpret_cast<const uint32_t *>(P.q[k] + i0);
+            } else {
+                bytes = 0;
+                for (uint32_t c = 0; c < 4u && i0 + c < P.d; ++c)
+                    bytes |= (uint32_t)P.q[k][i0 + c] << (8u * c);
+            }
+        } else {
+            bytes = P.q[k][i0];
+        }
+        if (!bytes)
+            continue;
+        const double nrm = (double)P.norms[k][bk];
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            const uint32_t byte = (bytes >> (8 * c)) & 0xffu, level = byte & 0x7fu;
+            if (level) {
+                const double val = ldexp(nrm, (int)level - 1 - (int)P.s);
+                sum[c] += (byte & 0x80u) ? -val : val;
+            }
+        }
+    }
+    const double sc = (double)P.scale;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+        if (i0 + c < P.d) {
+            const float r = (float)(sc * sum[c]);
+            P.out[i0 + c] = P.accumulate ? P.out[i0 + c] + r : r;
+        }
+    }
+}
+
+}  // namespace nuq

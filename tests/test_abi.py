@@ -76,3 +76,14 @@ def test_argument_errors_are_reported_on_the_host(nuq):
     lib.nuq_bucket_norms_linf.restype = ctypes.c_int
     lib.nuq_bucket_norms_linf.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p]
     assert lib.nuq_bucket_norms_linf(None, 10, 4, None, None) == EINVAL
+
+
+def test_huffman_lengths_on_the_host(nuq):
+    """nuq_huffman_lengths is host arithmetic: the hand-built examples of tests/golden/huffman_examples.txt."""
+    for line in open(os.path.join(ROOT, "tests", "golden", "huffman_examples.txt")):
+        f = [x.strip() for x in line.split("|")]
+        if f[0] != "L":
+            continue
+        s, hist, lengths = int(f[1]), [int(x) for x in f[2].split()], [int(x) for x in f[3].split()]
+        assert nuq.nuq_huffman_lengths(hist, s) == lengths
+    assert nuq.nuq_huffman_max_words(100, 10) == (100 * 16 + 31) // 32 + 10

@@ -1,0 +1,154 @@
+"""GPU parity of the Huffman-coded levels through the C ABI against the CPU oracle: histogram exact, code lengths
+equal (host arithmetic on both sides), messages (offsets, words, sync entries) bit-exact, decoded bytes equal, the
+average of decoded bytes within 1e-6."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from test_gpu_parity import make_vector
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_util
+    return gpu_util
+
+
+CASES = [
+    # (d, bucket, s, sync stride, K, kind)
+    (100_000, 8192, 3, 256, 3, "mixed"),
+    (100_003, 8192, 4, 1024, 2, "gauss"),
+    (70_001, 16384, 7, 512, 2, "mixed"),
+    (70_001, 16384, 7, 0, 1, "mixed"),
+    (40_000, 512, 3, 128, 4, "mixed"),
+    (40_000, 512, 3, 64, 2, "edges"),
+    (33_333, 1000, 2, 256, 3, "mixed"),
+    (9_999, 1001, 5, 128, 2, "mixed"),
+    (3_000, 7, 1, 0, 3, "mixed"),
+    (10_000, 2048, 14, 512, 2, "mixed"),
+    (120_000, 32768, 3, 1024, 2, "mixed"),
+    (66_000, 1536, 9, 64, 2, "edges"),         # six float4 rows per thread: sync boundaries inside a thread's chunk
+    (1, 8192, 3, 512, 1, "gauss"),
+]
+
+
+@pytest.mark.parametrize("d,n,s,S,K,kind", CASES)
+def test_histogram_code_message_decode_and_average(g, d, n, s, S, K, kind):
+    nuq = g.nuq
+    rng = np.random.default_rng(d + n + s + S)
+    B = nuq.nuq_num_buckets(d, n)
+    nsync = nuq.nuq_num_sync(n, S)
+    cap = nuq.nuq_huffman_max_words(d, n)
+    ws = torch.empty(nuq.nuq_encode_huffman_workspace_bytes(d, n), dtype=torch.uint8, device=g.DEV)
+    lengths = None
+    norms_list, q_list, q_np_list = [], [], []
+    for k in range(K):
+        v_np = make_vector(kind, d, n, rng)
+        v = torch.from_numpy(v_np).to(g.DEV)
+        norms = torch.empty(B, dtype=torch.float32, device=g.DEV)
+        nuq.nuq_bucket_norms(v, n, norms)
+        q = torch.empty(d, dtype=torch.uint8, device=g.DEV)
+        nuq.nuq_quantize(v, n, s, 31 + k, norms, q)
+        q_np = q.cpu().numpy()
+        if lengths is None:                       # the code is built once, from the first worker's levels
+            hist = torch.full((16,), -1, dtype=torch.int64, device=g.DEV)
+            nuq.nuq_level_histogram(q, hist)
+            hist_np = hist.cpu().numpy()
+            np.testing.assert_array_equal(hist_np[: s + 2], oracle.level_histogram_of(q_np, s).astype(np.int64))
+            assert not hist_np[s + 2:].any()
+            lengths = nuq.nuq_huffman_lengths([int(x) for x in hist_np[: s + 2]], s)
+            assert lengths == [int(x) for x in oracle.huffman_lengths(hist_np[: s + 2].astype(np.uint64), s)]
+        bit_off = torch.full((B + 1,), -1, dtype=torch.int64, device=g.DEV)
+        words = torch.zeros(cap, dtype=torch.int32, device=g.DEV)
+        sync = torch.full((max(1, B * nsync),), 0x55555555, dtype=torch.int32, device=g.DEV)
+        nuq.nuq_encode_huffman(q, n, s, S, lengths, bit_off, words, sync if nsync else None, ws)
+        assert nuq.nuq_last_error_flags() == 0
+        bo, w_ref, sync_ref = oracle.encode_huffman(q_np, n, s, lengths, S)
+        np.testing.assert_array_equal(g.u64(bit_off), bo)
+        np.testing.assert_array_equal(g.u32(words)[: w_ref.size], w_ref)
+        assert not g.u32(words)[w_ref.size:].any()
+        if sync_ref.size:
+            np.testing.assert_array_equal(g.u32(sync)[: sync_ref.size], sync_ref)
+        back = torch.full((d,), 0x7F, dtype=torch.uint8, device=g.DEV)
+        nuq.nuq_decode_huffman(bit_off, words, sync if nsync else None, d, n, s, S, lengths, back)
+        assert nuq.nuq_last_error_flags() == 0
+        assert torch.equal(back, q)
+        norms_list.append(norms)
+        q_list.append(back)
+        q_np_list.append(q_np)
+    out = torch.full((d,), 2.0, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_average_levels(norms_list, q_list, d, n, s, 1.0 / K, False, out)
+    scale32 = float(np.float32(1.0 / K))
+    want = np.zeros(d)
+    mag = np.zeros(d)
+    for norms, q_np in zip(norms_list, q_np_list):
+        deq = oracle.dequantize(q_np, n, s, norms.cpu().numpy())
+        want += deq
+        mag += np.abs(deq)
+    diff = np.abs(out.cpu().numpy().astype(np.float64) - want * scale32)
+    assert np.all(diff <= 1e-6 * mag * scale32 + 1e-45)
+
+
+def test_malformed_messages_raise_the_flag(g):
+    nuq = g.nuq
+    d, n, s, S = 4096, 1024, 3, 256
+    rng = np.random.default_rng(0)
+    q_np = np.where(rng.random(d) < 0.2, rng.integers(1, s + 2, d), 0).astype(np.uint8)
+    lengths = [int(x) for x in oracle.huffman_lengths(oracle.level_histogram_of(q_np, s), s)]
+    bo, words, sync = oracle.encode_huffman(q_np, n, s, lengths, S)
+    dev = lambda a, dt: torch.from_numpy(a.view(dt)).to(g.DEV)
+    q = torch.empty(d, dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_decode_huffman(dev(bo, np.int64), dev(words, np.int32), dev(sync, np.int32), d, n, s, S, lengths, q)
+    assert nuq.nuq_last_error_flags() == 0 and np.array_equal(q.cpu().numpy(), q_np)
+    bad_sync = sync.copy()
+    bad_sync[1] += 1                                  # a segment that starts one bit late
+    nuq.nuq_decode_huffman(dev(bo, np.int64), dev(words, np.int32), dev(bad_sync, np.int32), d, n, s, S, lengths, q)
+    assert nuq.nuq_last_error_flags() == nuq.FLAG_MALFORMED
+    bad_bo = bo.copy()
+    bad_bo[-1] -= 1                                   # the last bucket one bit short
+    nuq.nuq_decode_huffman(dev(bad_bo, np.int64), dev(words, np.int32), dev(sync, np.int32), d, n, s, S, lengths, q)
+    assert nuq.nuq_last_error_flags() == nuq.FLAG_MALFORMED
+    with pytest.raises(nuq.NuqError):                 # lengths that are no complete code are refused on the host
+        nuq.nuq_decode_huffman(dev(bo, np.int64), dev(words, np.int32), dev(sync, np.int32), d, n, s, S,
+                               [1, 1, 2, 3, 3], q)
+
+
+def test_config3_worker_at_full_size(g):
+    """One worker of config 3 at full size: code from its own histogram, message against the oracle on sampled
+    buckets, decode gives the bytes back."""
+    nuq = g.nuq
+    w = workloads.workload(3)
+    d, n, s, S = w.d, w.bucket, w.s, 256
+    B, nsync = nuq.nuq_num_buckets(d, n), nuq.nuq_num_sync(n, S)
+    v = workloads.generate(w, 0, g.DEV)
+    norms = torch.empty(B, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_bucket_norms(v, n, norms)
+    q = torch.empty(d, dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_quantize(v, n, s, 0, norms, q)
+    hist = torch.empty(16, dtype=torch.int64, device=g.DEV)
+    nuq.nuq_level_histogram(q, hist)
+    lengths = nuq.nuq_huffman_lengths([int(x) for x in hist.cpu().numpy()[: s + 2]], s)
+    bit_off = torch.empty(B + 1, dtype=torch.int64, device=g.DEV)
+    words = torch.zeros(nuq.nuq_huffman_max_words(d, n) // 4, dtype=torch.int32, device=g.DEV)   # ~1.1 bits/coord fit
+    sync = torch.empty(B * nsync, dtype=torch.int32, device=g.DEV)
+    ws = torch.empty(nuq.nuq_encode_huffman_workspace_bytes(d, n), dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_encode_huffman(q, n, s, S, lengths, bit_off, words, sync, ws)
+    assert nuq.nuq_last_error_flags() == 0
+    bo = g.u64(bit_off)
+    rng = np.random.default_rng(2)
+    for b in [0, B - 1] + [int(x) for x in rng.integers(0, B, size=20)]:
+        sl = slice(b * n, min(d, (b + 1) * n))
+        rbo, rw, rs = oracle.encode_huffman(q[sl].cpu().numpy(), n, s, lengths, S)
+        start = (int(bo[b]) + 31) // 32 * 32
+        assert int(bo[b + 1]) - start == int(rbo[1])
+        np.testing.assert_array_equal(g.u32(words[start // 32: start // 32 + rw.size]), rw)
+        np.testing.assert_array_equal(g.u32(sync[b * nsync:(b + 1) * nsync]), rs)
+    back = torch.empty_like(q)
+    nuq.nuq_decode_huffman(bit_off, words, sync, d, n, s, S, lengths, back)
+    assert nuq.nuq_last_error_flags() == 0
+    assert torch.equal(back, q)
+    assert 1.0 < float(bo[-1]) / d < 1.5              # one bit per zero, a few more for the 7 % that are not
