@@ -46,6 +46,10 @@ def parse_args():
     ap.add_argument("--fixed-bits", type=int, default=0,
                     help="b in 3..8: fixed-width coding (sign and level index in b bits per coordinate, the paper's "
                          "\"4-bit\"/\"8-bit\" variants) instead of the ERC bit strings; main scheme's levels only")
+    ap.add_argument("--huffman", action="store_true",
+                    help="Huffman-coded levels (the paper's \"encoded\" variant) instead of the ERC bit strings: per "
+                         "worker norms, quantizer, Huffman encode; decode to level bytes and one averaging kernel; "
+                         "the code is built once from worker 0's level histogram; main scheme's levels only")
     ap.add_argument("--norm", default="l2", choices=["l2", "linf"],
                     help="bucket norm for a level table: Euclidean, or maximum (QSGDinf with --levels uniform)")
     ap.add_argument("--reference-kernels", action="store_true",
@@ -106,7 +110,22 @@ def main():
             nuq.nuq_quantize_encode_batch(grads, n, s, seeds, S, messages, ws)
 
     fb = args.fixed_bits
-    if fb:
+    huff = args.huffman
+    if huff:
+        if lev is not None or fb:
+            print("--huffman goes with the main scheme's levels and no other coding", file=sys.stderr)
+            sys.exit(2)
+        hq = [torch.empty(d, dtype=torch.uint8, device=dev) for _ in range(K)]          # quantizer output
+        hback = [torch.empty(d, dtype=torch.uint8, device=dev) for _ in range(K)]       # decoder output
+        hnorms = [torch.empty(B, dtype=torch.float32, device=dev) for _ in range(K)]
+        hws = torch.empty(nuq.nuq_encode_huffman_workspace_bytes(d, n), dtype=torch.uint8, device=dev)
+        nuq.nuq_bucket_norms(grads[0], n, hnorms[0])
+        nuq.nuq_quantize(grads[0], n, s, seeds[0], hnorms[0], hq[0])
+        hhist = torch.empty(16, dtype=torch.int64, device=dev)
+        nuq.nuq_level_histogram(hq[0], hhist)
+        hlen = nuq.nuq_huffman_lengths([int(x) for x in hhist.cpu().numpy()[: s + 2]], s)
+        msgs = [new_msg(nuq.nuq_huffman_max_words(d, n) // 4) for _ in range(K)]       # 4 bits/coord of room
+    elif fb:
         if lev is not None:
             print("--fixed-bits goes with the main scheme's levels", file=sys.stderr)
             sys.exit(2)
@@ -123,7 +142,13 @@ def main():
     out = torch.empty(d, dtype=torch.float32, device=dev)
 
     def encode_all():
-        if fb:
+        if huff:
+            for k in range(K):
+                m = msgs[k]
+                nuq.nuq_bucket_norms(grads[k], n, hnorms[k])
+                nuq.nuq_quantize(grads[k], n, s, seeds[k], hnorms[k], hq[k])
+                nuq.nuq_encode_huffman(hq[k], n, s, S, hlen, m.bit_off, m.words, m.sync if nsync else None, hws)
+        elif fb:
             nuq.nuq_quantize_pack_fixed_batch(grads, n, s, fb, seeds, fnorms, fpacked)
         elif lev is not None:
             encode_batch(msgs)
@@ -135,7 +160,10 @@ def main():
             nuq.nuq_quantize_encode_batch(grads, n, s, seeds, S, msgs, ws)
 
     def decode_all():
-        if fb:
+        if huff:
+            nuq.nuq_decode_huffman_batch(msgs, d, n, s, S, hlen, hback)
+            nuq.nuq_average_levels(hnorms, hback, d, n, s, 1.0 / K, False, out)
+        elif fb:
             nuq.nuq_unpack_accumulate_fixed(fnorms, fpacked, d, n, s, fb, 1.0 / K, False, out)
         elif lev is not None:
             nuq.nuq_decode_accumulate_table(msgs, d, n, lev, S, 1.0 / K, False, out)
@@ -158,7 +186,7 @@ def main():
     assert nuq.nuq_last_error_flags() == 0, "device error flags raised during warmup"
 
     # the timed region: K steps, with the library's per-launch HIP-event brackets (on its launch stream) switched on
-    nuq.nuq_timing_begin(min(4096, args.steps * (K + 1)))
+    nuq.nuq_timing_begin(min(4096, args.steps * (4 * K + 2)))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -200,8 +228,15 @@ def main():
         wire_bits = float(np.mean([(32 * Wk + 32 * B + 64 * (B + 1) + 32 * B * nsync) / d for Wk in W]))
         enc_alg = [4.0 * d + 4 * B + 8 * (B + 1) + 4 * Wk + 4 * B * nsync for Wk in W]      # per worker
         dec_alg = sum(4.0 * Wk + 12 * B + 4 * B * nsync for Wk in W) + 4.0 * d               # per launch
-    enc_ms = [t for e, t in launches if e == nuq.T_QUANTIZE_ENCODE]
-    dec_ms = [t for e, t in launches if e == nuq.T_DECODE]
+    if huff:
+        # several kernels per worker: the bracketed ones (norms, quantizer, emission; decode) summed per step; the
+        # length, offset and averaging kernels are outside the brackets, so the phase figures are the honest ones
+        per_step = lambda ids: [sum(t for e, t in launches if e in ids) / args.steps]
+        enc_ms = per_step((nuq.T_NORMS, nuq.T_QUANTIZE, nuq.T_ENCODE))
+        dec_ms = per_step((nuq.T_DECODE,))
+    else:
+        enc_ms = [t for e, t in launches if e == nuq.T_QUANTIZE_ENCODE]
+        dec_ms = [t for e, t in launches if e == nuq.T_DECODE]
     enc_kernel_ms = float(np.mean(enc_ms))
     dec_kernel_ms = float(np.mean(dec_ms))
     enc_launch_bytes = float(np.mean(enc_alg)) if args.per_worker_calls else float(sum(enc_alg))
@@ -223,6 +258,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[%d] %s: d=%d fp32, bucket=%d, s=%d, K=%d workers, sync_stride=%d%s"
                                % (args.config - 1, w.name, d, n, s, K, S,
+                                  ", Huffman-coded levels, lengths %s" % hlen if huff else
                                   (", fixed-width %d bits" % fb) if fb else
                                   "" if lev is None else ", level table %s, %s norm" % (args.levels, args.norm))},
         "phases": {
@@ -232,19 +268,23 @@ def main():
                                "hbm_frac": round(dec_alg / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         },
         "bits_per_coord": {"paper": round(paper_bits, 4), "wire": round(wire_bits, 4)},
-        "roofline": {"kernel": ("k_pack_fixed (fused norms+quantize+b-bit packing), one launch per step (all K workers)"
+        "roofline": {"kernel": ("k_bucket_norms + k_quantize + k_huffman_emit of all K workers, summed per step"
+                                if huff else
+                                "k_pack_fixed (fused norms+quantize+b-bit packing), one launch per step (all K workers)"
                                 if fb else "k_encode (fused norms+quantize+ENCODE), one launch per %s"
                                 % ("worker" if args.per_worker_calls else "step (all K workers)")),
                      "bound": "hbm", "achieved": round(enc_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(enc_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None if lev is not None or fb else measured_traffic("k_encode", args.config, S),
+                     "traffic": None if lev is not None or fb or huff else measured_traffic("k_encode", args.config, S),
                      "bytes_per_launch": round(enc_launch_bytes), "launch_ms": round(enc_kernel_ms, 5),
                      "launches": len(enc_ms)},
-        "roofline_decode": {"kernel": ("k_unpack_accumulate_fixed (unpack + average of K messages)" if fb else
+        "roofline_decode": {"kernel": ("k_huffman_decode of all K workers, summed per step (k_average_levels follows)"
+                                       if huff else
+                                       "k_unpack_accumulate_fixed (unpack + average of K messages)" if fb else
                                        "k_decode_accumulate (DECODE + average of K messages)"),
                             "bound": "hbm", "achieved": round(dec_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
-                            "traffic": None if lev is not None or fb
+                            "traffic": None if lev is not None or fb or huff
                             else measured_traffic("k_decode_accumulate", args.config, S),
                             "bytes_per_launch": round(dec_alg), "launch_ms": round(dec_kernel_ms, 5),
                             "launches": len(dec_ms)},
@@ -253,7 +293,7 @@ def main():
     if args.reference_kernels:
         result["reference"] = reference_kernels(torch, d * K, dev)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, grads, S, lev, args.norm, fb)
+        result["cpu_baseline"] = cpu_baseline(w, grads, S, lev, args.norm, fb, hlen if huff else None)
     print(json.dumps(result))
 
 
@@ -296,7 +336,7 @@ def measured_traffic(kernel, config, S):
     return None if entry is None else entry.get("bytes_per_launch")
 
 
-def cpu_baseline(w, grads, S, lev=None, norm="l2", fb=0):
+def cpu_baseline(w, grads, S, lev=None, norm="l2", fb=0, hlen=None):
     """The CPU oracle as it stands, one thread, on the same workload (bounded to ~30 s of CPU work)."""
     import numpy as np
     import oracle
@@ -317,10 +357,19 @@ def cpu_baseline(w, grads, S, lev=None, norm="l2", fb=0):
         if fb:
             parts.append((norms, oracle.pack_fixed(q, n, s, fb), None))
             continue
+        if hlen is not None:
+            bo, words, _ = oracle.encode_huffman(q, n, s, hlen, S)
+            parts.append((norms, bo, words))
+            continue
         bo, words, _ = oracle.encode(q, n, s, S)
         parts.append((norms, bo, words))
     t1 = time.perf_counter()
-    if fb:
+    if hlen is not None:
+        acc = np.zeros(d_s)
+        for norms, bo, words in parts:
+            acc += oracle.dequantize(oracle.decode_huffman(bo, words, d_s, n, s, hlen), n, s, norms)
+        acc *= 1.0 / K
+    elif fb:
         oracle.unpack_average_fixed([p[0] for p in parts], [p[1] for p in parts], d_s, n, s, fb, 1.0 / K)
     elif lev is None:
         oracle.decode_average([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], d_s, n, s, 1.0 / K)

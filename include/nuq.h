@@ -257,6 +257,13 @@ int nuq_decode_huffman(const uint64_t *bit_off, const uint32_t *words, const uin
                        uint32_t bucket, uint32_t s, uint32_t sync_stride, const uint8_t *lengths,
                        uint8_t *q, nuq_stream_t stream);
 
+/* The same for K messages in one launch (bit_off, words, sync, q: HOST arrays of K device pointers;
+ * one code for all).  1 <= K <= NUQ_MAX_WORKERS. */
+int nuq_decode_huffman_batch(uint32_t K, const uint64_t *const *bit_off, const uint32_t *const *words,
+                             const uint32_t *const *sync, uint64_t d, uint32_t bucket, uint32_t s,
+                             uint32_t sync_stride, const uint8_t *lengths, uint8_t *const *q,
+                             nuq_stream_t stream);
+
 /* out[i] = (accumulate ? out[i] : 0) + scale * sum_k norms_k[b] * sign * l_j from K arrays of
  * level|sign bytes (norms, q: HOST arrays of K device pointers): the aggregate of Alg. 1 for messages
  * already decoded to bytes.  fp64 sum in worker order, rounded to fp32 once. */

@@ -49,6 +49,7 @@ _SIGNATURES = {
     "nuq_encode_huffman_workspace_bytes": (_u64, [_u64, _u32]),
     "nuq_encode_huffman": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
     "nuq_decode_huffman": (_i32, [_vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
+    "nuq_decode_huffman_batch": (_i32, [_u32, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "nuq_average_levels": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _f32, _i32, _vp, _vp]),
     "nuq_last_error_flags": (_i32, [_vp, _vp]),
     "nuq_timing_begin": (_i32, [_u32]),
@@ -329,6 +330,19 @@ def nuq_decode_huffman(bit_off: torch.Tensor, words: torch.Tensor, sync: torch.T
     _check("nuq_decode_huffman",
            _lib.nuq_decode_huffman(_ptr(bit_off, torch.int64), _ptr(words, torch.int32), _ptr(sync), d, bucket, s,
                                    sync_stride, _lengths(lengths, s), _ptr(q, torch.uint8), _stream()))
+
+
+def nuq_decode_huffman_batch(messages: list[Message], d: int, bucket: int, s: int, sync_stride: int, lengths,
+                             qs: list[torch.Tensor]) -> None:
+    K = len(messages)
+    if len(qs) != K or any(q.numel() != d for q in qs):
+        raise ValueError("K messages and K byte arrays of d entries are needed")
+    arr = lambda ts, dt=None: (ctypes.c_void_p * K)(*[_ptr(t, dt) for t in ts])
+    _check("nuq_decode_huffman_batch",
+           _lib.nuq_decode_huffman_batch(K, arr([m.bit_off for m in messages], torch.int64),
+                                         arr([m.words for m in messages], torch.int32),
+                                         arr([m.sync for m in messages]), d, bucket, s, sync_stride,
+                                         _lengths(lengths, s), arr(qs, torch.uint8), _stream()))
 
 
 def nuq_average_levels(norms: list[torch.Tensor], qs: list[torch.Tensor], d: int, bucket: int, s: int, scale: float,

@@ -895,11 +895,12 @@ int nuq_encode_huffman(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s
     });
 }
 
-int nuq_decode_huffman(const uint64_t *bit_off, const uint32_t *words, const uint32_t *sync, uint64_t d,
-                       uint32_t bucket, uint32_t s, uint32_t sync_stride, const uint8_t *lengths, uint8_t *q,
-                       nuq_stream_t stream)
+int nuq_decode_huffman_batch(uint32_t K, const uint64_t *const *bit_off, const uint32_t *const *words,
+                             const uint32_t *const *sync, uint64_t d, uint32_t bucket, uint32_t s,
+                             uint32_t sync_stride, const uint8_t *lengths, uint8_t *const *q, nuq_stream_t stream)
 {
-    if (!bit_off || !words || !lengths || !q || !valid_common(d, bucket, s) || !valid_sync(sync_stride))
+    if (K < 1 || K > kMaxBatch || !bit_off || !words || !lengths || !q || !valid_common(d, bucket, s) ||
+        !valid_sync(sync_stride))
         return NUQ_EINVAL;
     const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
     if (nsync && !sync)
@@ -911,10 +912,11 @@ int nuq_decode_huffman(const uint64_t *bit_off, const uint32_t *words, const uin
     if (!flags)
         return NUQ_EHIP;
     HuffmanDecodeParams P{};
-    P.bit_off = bit_off;
-    P.words = words;
-    P.sync = sync;
-    P.q = q;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!bit_off[k] || !words[k] || !q[k] || (nsync && !sync[k]))
+            return NUQ_EINVAL;
+        P.w[k] = HuffmanStream{bit_off[k], words[k], nsync ? sync[k] : nullptr, q[k]};
+    }
     P.flags = flags;
     P.d = d;
     P.nb = nuq_num_buckets(d, bucket);
@@ -922,13 +924,30 @@ int nuq_decode_huffman(const uint64_t *bit_off, const uint32_t *words, const uin
     P.sync_shift = nsync ? log2u(sync_stride) : 0;
     P.nsync = nsync;
     P.nseg = nsync + 1;
-    const uint64_t units = P.nb * P.nseg, blocks = (units + 255) / 256;
+    const uint64_t units = P.nb * P.nseg;
+    const uint64_t blocks = nsync ? (units + 63) / 64 : (units + 255) / 256;
     if (blocks > 0x7fffffffull)
         return NUQ_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     ScopedTiming timing(NUQ_T_DECODE, st);
-    hipLaunchKernelGGL(k_huffman_decode, dim3((uint32_t)blocks), dim3(256), 0, st, P, H);
+    if (nsync) {
+        const size_t lds_bytes = 64u * (sync_stride / 4u + 1u) * 4u;
+        if (lds_bytes > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void *>(k_huffman_decode_tile),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+            return NUQ_EHIP;
+        hipLaunchKernelGGL(k_huffman_decode_tile, dim3((uint32_t)blocks, K), dim3(64), lds_bytes, st, P, H);
+    } else {
+        hipLaunchKernelGGL(k_huffman_decode, dim3((uint32_t)blocks, K), dim3(256), 0, st, P, H);
+    }
     return check_launch();
+}
+
+int nuq_decode_huffman(const uint64_t *bit_off, const uint32_t *words, const uint32_t *sync, uint64_t d,
+                       uint32_t bucket, uint32_t s, uint32_t sync_stride, const uint8_t *lengths, uint8_t *q,
+                       nuq_stream_t stream)
+{
+    return nuq_decode_huffman_batch(1, &bit_off, &words, &sync, d, bucket, s, sync_stride, lengths, &q, stream);
 }
 
 int nuq_average_levels(uint32_t K, const float *const *norms, const uint8_t *const *q, uint64_t d, uint32_t bucket,

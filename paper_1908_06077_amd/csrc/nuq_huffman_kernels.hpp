@@ -195,11 +195,15 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_huffman_emit(EncodePara
 }
 
 // ------------------------------------------------------------------------------- decode
-struct HuffmanDecodeParams {
+struct HuffmanStream {
     const uint64_t *bit_off;
     const uint32_t *words;
     const uint32_t *sync;
     uint8_t *q;
+};
+
+struct HuffmanDecodeParams {
+    HuffmanStream w[kMaxBatch];      // one per worker: blockIdx.y
     uint32_t *flags;
     uint64_t d;
     uint64_t nb;
@@ -212,6 +216,7 @@ struct HuffmanDecodeParams {
 // One thread per unit = (bucket, sync segment): walks its codewords and writes level|sign bytes.
 __global__ __launch_bounds__(256) void k_huffman_decode(HuffmanDecodeParams P, HuffmanCode H)
 {
+    const HuffmanStream &W = P.w[blockIdx.y];
     const uint64_t u = (uint64_t)blockIdx.x * 256u + threadIdx.x;
     if (u >= P.nb * P.nseg)
         return;
@@ -222,15 +227,15 @@ __global__ __launch_bounds__(256) void k_huffman_decode(HuffmanDecodeParams P, H
     if (c_lo >= nbk)
         return;
     const uint32_t c_hi = P.sync_shift ? min(nbk, (g + 1u) << P.sync_shift) : nbk;
-    const uint64_t start = (P.bit_off[b] + 31ull) & ~31ull, end = P.bit_off[b + 1];
+    const uint64_t start = (W.bit_off[b] + 31ull) & ~31ull, end = W.bit_off[b + 1];
     const uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
-    const uint32_t *sg = P.sync + b * P.nsync;
+    const uint32_t *sg = W.sync + b * P.nsync;
     const uint32_t lo = g ? sg[g - 1u] : 0u;
     const uint32_t hi = g + 1u < P.nseg ? sg[g] : len;           // where the next segment starts
     bool bad = lo > hi || hi > len;
-    uint8_t *qb = P.q + b * P.bucket;
+    uint8_t *qb = W.q + b * P.bucket;
     if (!bad) {
-        WalkWords gw{P.words + (start >> 5)};
+        WalkWords gw{W.words + (start >> 5)};
         BitReader<WalkWords> br;
         br.init(gw, lo, (len + 31u) >> 5);
         uint32_t pos = lo;
@@ -261,6 +266,122 @@ __global__ __launch_bounds__(256) void k_huffman_decode(HuffmanDecodeParams P, H
     }
     if (bad)
         atomicOr(P.flags, kFlagMalformed);
+}
+
+// The same for messages with a sync index: a wave owns 64 consecutive units.  Code tables and a lookup table on the
+// next eight bits (symbol | length << 4; 0 for longer codewords, which take the length-by-length walk) live in LDS;
+// each lane assembles its unit's bytes four at a time into its row of an LDS tile (row stride S + 4 bytes: the lanes
+// hit different banks), and the tile goes out unit by unit with whole-wave stores.
+__global__ __launch_bounds__(64) void k_huffman_decode_tile(HuffmanDecodeParams P, HuffmanCode H)
+{
+    extern __shared__ __align__(16) uint32_t tile[];            // 64 rows of S / 4 + 1 words
+    __shared__ uint8_t lut8[256];
+    __shared__ uint32_t first[16], count[16], offset[16], sorted[16];
+    __shared__ uint32_t unit_dst_lo[64], unit_dst_hi[64], unit_len[64];
+    const uint32_t lane = threadIdx.x;
+    const uint32_t S = 1u << P.sync_shift;
+    const uint32_t row_words = S / 4u + 1u;
+    if (lane < 16u) {
+        first[lane] = H.first[lane];
+        count[lane] = H.count[lane];
+        offset[lane] = H.offset[lane];
+        sorted[lane] = H.sorted[lane];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t p = lane; p < 256u; p += 64u) {               // the codeword that starts the eight bits p, if any
+        uint32_t entry = 0;
+        for (uint32_t L = 1; L <= 8u && L <= H.maxlen; ++L) {
+            const uint32_t idx = (p >> (8u - L)) - first[L];
+            if (idx < count[L]) {
+                entry = sorted[offset[L] + idx] | (L << 4);
+                break;
+            }
+        }
+        lut8[p] = (uint8_t)entry;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+
+    const HuffmanStream &W = P.w[blockIdx.y];
+    const uint64_t u = (uint64_t)blockIdx.x * 64u + lane;
+    const bool live = u < P.nb * P.nseg;
+    const uint64_t b = live ? u / P.nseg : 0;
+    const uint32_t g = live ? (uint32_t)(u - b * P.nseg) : 0u;
+    const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
+    const uint32_t c_lo = g << P.sync_shift;
+    const uint32_t c_hi = live && c_lo < nbk ? min(nbk, c_lo + S) : c_lo;      // an empty range for idle lanes
+    uint32_t *row = tile + lane * row_words;
+    bool bad = false;
+    if (c_lo < c_hi) {
+        const uint64_t start = (W.bit_off[b] + 31ull) & ~31ull, end = W.bit_off[b + 1];
+        const uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
+        const uint32_t *sg = W.sync + b * P.nsync;
+        const uint32_t lo = g ? sg[g - 1u] : 0u;
+        const uint32_t hi = g + 1u < P.nseg ? sg[g] : len;
+        bad = lo > hi || hi > len;
+        if (!bad) {
+            WalkWords gw{W.words + (start >> 5)};
+            BitReader<WalkWords> br;
+            br.init(gw, lo, (len + 31u) >> 5);
+            uint32_t pos = lo, four = 0;
+            for (uint32_t c = c_lo; c < c_hi; ++c) {
+                br.refill();
+                const uint32_t w = br.peek();
+                uint32_t entry = lut8[w >> 24];
+                if (!entry) {                                   // a codeword of nine bits or more (rare), or none
+                    for (uint32_t L = 9; L <= H.maxlen; ++L) {
+                        const uint32_t idx = (w >> (32u - L)) - first[L];
+                        if (idx < count[L]) {
+                            entry = sorted[offset[L] + idx] | (L << 4);
+                            break;
+                        }
+                    }
+                }
+                const uint32_t sym = entry & 15u, L = entry >> 4;
+                const uint32_t n = L + (sym ? 1u : 0u);
+                if (!L || pos + n > hi) {
+                    bad = true;
+                    break;
+                }
+                const uint32_t neg = sym ? (w >> (31u - L)) & 1u : 0u;
+                four |= (sym | (neg << 7)) << (8u * (c & 3u));
+                if ((c & 3u) == 3u) {
+                    row[(c - c_lo) >> 2] = four;
+                    four = 0;
+                }
+                br.skip(n);
+                pos += n;
+            }
+            if ((c_hi - c_lo) & 3u)
+                row[(c_hi - c_lo) >> 2] = four;                 // a short last segment that is no multiple of four
+            bad |= pos != hi;
+        }
+    }
+    if (bad)
+        atomicOr(P.flags, kFlagMalformed);
+    const uint64_t dst = b * P.bucket + c_lo;
+    unit_dst_lo[lane] = (uint32_t)dst;
+    unit_dst_hi[lane] = (uint32_t)(dst >> 32);
+    unit_len[lane] = c_hi - c_lo;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t i = 0; i < 64u; ++i) {
+        const uint32_t n = unit_len[i];
+        if (!n)
+            continue;
+        uint8_t *out = W.q + (((uint64_t)unit_dst_hi[i] << 32) | unit_dst_lo[i]);
+        const uint32_t *src = tile + i * row_words;
+        if ((reinterpret_cast<uintptr_t>(out) & 3u) == 0) {
+            for (uint32_t w4 = lane; w4 < n / 4u; w4 += 64u)
+                reinterpret_cast<uint32_t *>(out)[w4] = src[w4];
+            for (uint32_t c = (n & ~3u) + lane; c < n; c += 64u)
+                out[c] = (uint8_t)(src[c >> 2] >> (8u * (c & 3u)));
+        } else {
+            for (uint32_t c = lane; c < n; c += 64u)
+                out[c] = (uint8_t)(src[c >> 2] >> (8u * (c & 3u)));
+        }
+    }
 }
 
 // ------------------------------------------------------------------ average of level bytes

@@ -45,7 +45,7 @@ def test_histogram_code_message_decode_and_average(g, d, n, s, S, K, kind):
     cap = nuq.nuq_huffman_max_words(d, n)
     ws = torch.empty(nuq.nuq_encode_huffman_workspace_bytes(d, n), dtype=torch.uint8, device=g.DEV)
     lengths = None
-    norms_list, q_list, q_np_list = [], [], []
+    norms_list, q_list, q_np_list, msg_list = [], [], [], []
     for k in range(K):
         v_np = make_vector(kind, d, n, rng)
         v = torch.from_numpy(v_np).to(g.DEV)
@@ -78,8 +78,15 @@ def test_histogram_code_message_decode_and_average(g, d, n, s, S, K, kind):
         assert nuq.nuq_last_error_flags() == 0
         assert torch.equal(back, q)
         norms_list.append(norms)
+        msg_list.append(nuq.Message(norms, bit_off, words, sync if nsync else None))
         q_list.append(back)
         q_np_list.append(q_np)
+    # all K messages decoded in one launch give the same bytes
+    again = [torch.full((d,), 0x7E, dtype=torch.uint8, device=g.DEV) for _ in range(K)]
+    nuq.nuq_decode_huffman_batch(msg_list, d, n, s, S, lengths, again)
+    assert nuq.nuq_last_error_flags() == 0
+    for a_, b_ in zip(again, q_list):
+        assert torch.equal(a_, b_)
     out = torch.full((d,), 2.0, dtype=torch.float32, device=g.DEV)
     nuq.nuq_average_levels(norms_list, q_list, d, n, s, 1.0 / K, False, out)
     scale32 = float(np.float32(1.0 / K))
