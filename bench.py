@@ -48,7 +48,7 @@ def parse_args():
                          "\"4-bit\"/\"8-bit\" variants) instead of the ERC bit strings; main scheme's levels only")
     ap.add_argument("--huffman", action="store_true",
                     help="Huffman-coded levels (the paper's \"encoded\" variant) instead of the ERC bit strings: per "
-                         "worker norms, quantizer, Huffman encode; decode to level bytes and one averaging kernel; "
+                         "fused norms + quantizer + Huffman coding; decode to level bytes and one averaging kernel; "
                          "the code is built once from worker 0's level histogram; main scheme's levels only")
     ap.add_argument("--norm", default="l2", choices=["l2", "linf"],
                     help="bucket norm for a level table: Euclidean, or maximum (QSGDinf with --levels uniform)")
@@ -118,7 +118,7 @@ def main():
         hq = [torch.empty(d, dtype=torch.uint8, device=dev) for _ in range(K)]          # quantizer output
         hback = [torch.empty(d, dtype=torch.uint8, device=dev) for _ in range(K)]       # decoder output
         hnorms = [torch.empty(B, dtype=torch.float32, device=dev) for _ in range(K)]
-        hws = torch.empty(nuq.nuq_encode_huffman_workspace_bytes(d, n), dtype=torch.uint8, device=dev)
+        hws = torch.empty(nuq.nuq_encode_huffman_batch_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=dev)
         nuq.nuq_bucket_norms(grads[0], n, hnorms[0])
         nuq.nuq_quantize(grads[0], n, s, seeds[0], hnorms[0], hq[0])
         hhist = torch.empty(16, dtype=torch.int64, device=dev)
@@ -143,11 +143,7 @@ def main():
 
     def encode_all():
         if huff:
-            for k in range(K):
-                m = msgs[k]
-                nuq.nuq_bucket_norms(grads[k], n, hnorms[k])
-                nuq.nuq_quantize(grads[k], n, s, seeds[k], hnorms[k], hq[k])
-                nuq.nuq_encode_huffman(hq[k], n, s, S, hlen, m.bit_off, m.words, m.sync if nsync else None, hws)
+            nuq.nuq_quantize_encode_huffman_batch(grads, n, s, seeds, S, hlen, msgs, hws)
         elif fb:
             nuq.nuq_quantize_pack_fixed_batch(grads, n, s, fb, seeds, fnorms, fpacked)
         elif lev is not None:
@@ -162,7 +158,7 @@ def main():
     def decode_all():
         if huff:
             nuq.nuq_decode_huffman_batch(msgs, d, n, s, S, hlen, hback)
-            nuq.nuq_average_levels(hnorms, hback, d, n, s, 1.0 / K, False, out)
+            nuq.nuq_average_levels([m.norms for m in msgs], hback, d, n, s, 1.0 / K, False, out)
         elif fb:
             nuq.nuq_unpack_accumulate_fixed(fnorms, fpacked, d, n, s, fb, 1.0 / K, False, out)
         elif lev is not None:
@@ -229,11 +225,8 @@ def main():
         enc_alg = [4.0 * d + 4 * B + 8 * (B + 1) + 4 * Wk + 4 * B * nsync for Wk in W]      # per worker
         dec_alg = sum(4.0 * Wk + 12 * B + 4 * B * nsync for Wk in W) + 4.0 * d               # per launch
     if huff:
-        # several kernels per worker: the bracketed ones (norms, quantizer, emission; decode) summed per step; the
-        # length, offset and averaging kernels are outside the brackets, so the phase figures are the honest ones
-        per_step = lambda ids: [sum(t for e, t in launches if e in ids) / args.steps]
-        enc_ms = per_step((nuq.T_NORMS, nuq.T_QUANTIZE, nuq.T_ENCODE))
-        dec_ms = per_step((nuq.T_DECODE,))
+        enc_ms = [t for e, t in launches if e == nuq.T_QUANTIZE_ENCODE]
+        dec_ms = [t for e, t in launches if e == nuq.T_DECODE]
     else:
         enc_ms = [t for e, t in launches if e == nuq.T_QUANTIZE_ENCODE]
         dec_ms = [t for e, t in launches if e == nuq.T_DECODE]
@@ -268,7 +261,7 @@ def main():
                                "hbm_frac": round(dec_alg / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         },
         "bits_per_coord": {"paper": round(paper_bits, 4), "wire": round(wire_bits, 4)},
-        "roofline": {"kernel": ("k_bucket_norms + k_quantize + k_huffman_emit of all K workers, summed per step"
+        "roofline": {"kernel": ("k_huffman_fused (norms+quantize+Huffman coding), one launch per step (all K workers)"
                                 if huff else
                                 "k_pack_fixed (fused norms+quantize+b-bit packing), one launch per step (all K workers)"
                                 if fb else "k_encode (fused norms+quantize+ENCODE), one launch per %s"
@@ -278,7 +271,7 @@ def main():
                      "traffic": None if lev is not None or fb or huff else measured_traffic("k_encode", args.config, S),
                      "bytes_per_launch": round(enc_launch_bytes), "launch_ms": round(enc_kernel_ms, 5),
                      "launches": len(enc_ms)},
-        "roofline_decode": {"kernel": ("k_huffman_decode of all K workers, summed per step (k_average_levels follows)"
+        "roofline_decode": {"kernel": ("k_huffman_decode_tile, all K messages in one launch (k_average_levels follows)"
                                        if huff else
                                        "k_unpack_accumulate_fixed (unpack + average of K messages)" if fb else
                                        "k_decode_accumulate (DECODE + average of K messages)"),

@@ -251,6 +251,18 @@ int nuq_encode_huffman(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s
                        const uint8_t *lengths, uint64_t *bit_off, uint32_t *words, uint64_t words_cap,
                        uint32_t *sync, void *workspace, uint64_t workspace_bytes, nuq_stream_t stream);
 
+/* Norms, quantizer and Huffman coding of K workers' gradients in one launch, v read once: norms[k] as
+ * nuq_bucket_norms(v[k]) and the message as nuq_encode_huffman(nuq_quantize(v[k], ..., seeds[k],
+ * norms[k])).  Array arguments as nuq_quantize_encode_batch; workspace of at least
+ * nuq_encode_huffman_batch_workspace_bytes(K, d, bucket, s) bytes, 16-byte aligned. */
+uint64_t nuq_encode_huffman_batch_workspace_bytes(uint32_t K, uint64_t d, uint32_t bucket, uint32_t s);
+int nuq_quantize_encode_huffman_batch(uint32_t K, const float *const *v, const uint64_t *seeds, uint64_t d,
+                                      uint32_t bucket, uint32_t s, uint32_t sync_stride,
+                                      const uint8_t *lengths, float *const *norms, uint64_t *const *bit_off,
+                                      uint32_t *const *words, const uint64_t *words_cap,
+                                      uint32_t *const *sync, void *workspace, uint64_t workspace_bytes,
+                                      nuq_stream_t stream);
+
 /* q[d] <- the level|sign bytes of such a message.  A segment that does not end where the next one
  * starts, a prefix that is no codeword, or a sync entry out of order raises NUQ_FLAG_MALFORMED. */
 int nuq_decode_huffman(const uint64_t *bit_off, const uint32_t *words, const uint32_t *sync, uint64_t d,

@@ -49,6 +49,9 @@ _SIGNATURES = {
     "nuq_encode_huffman_workspace_bytes": (_u64, [_u64, _u32]),
     "nuq_encode_huffman": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
     "nuq_decode_huffman": (_i32, [_vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
+    "nuq_encode_huffman_batch_workspace_bytes": (_u64, [_u32, _u64, _u32, _u32]),
+    "nuq_quantize_encode_huffman_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp,
+                                                 _vp, _u64, _vp]),
     "nuq_decode_huffman_batch": (_i32, [_u32, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "nuq_average_levels": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _f32, _i32, _vp, _vp]),
     "nuq_last_error_flags": (_i32, [_vp, _vp]),
@@ -330,6 +333,29 @@ def nuq_decode_huffman(bit_off: torch.Tensor, words: torch.Tensor, sync: torch.T
     _check("nuq_decode_huffman",
            _lib.nuq_decode_huffman(_ptr(bit_off, torch.int64), _ptr(words, torch.int32), _ptr(sync), d, bucket, s,
                                    sync_stride, _lengths(lengths, s), _ptr(q, torch.uint8), _stream()))
+
+
+def nuq_encode_huffman_batch_workspace_bytes(K: int, d: int, bucket: int, s: int) -> int:
+    return _lib.nuq_encode_huffman_batch_workspace_bytes(K, d, bucket, s)
+
+
+def nuq_quantize_encode_huffman_batch(vs: list[torch.Tensor], bucket: int, s: int, seeds: list[int], sync_stride: int,
+                                      lengths, messages: list["Message"], workspace: torch.Tensor) -> None:
+    K = len(vs)
+    d = vs[0].numel()
+    if any(v.numel() != d for v in vs) or len(seeds) != K or len(messages) != K:
+        raise ValueError("K gradients of equal length, K seeds and K messages are needed")
+    arr = lambda ts, dt=None: (ctypes.c_void_p * K)(*[_ptr(t, dt) for t in ts])
+    u64s = lambda xs: (ctypes.c_uint64 * K)(*[x & (2 ** 64 - 1) for x in xs])
+    _check("nuq_quantize_encode_huffman_batch",
+           _lib.nuq_quantize_encode_huffman_batch(K, arr(vs, torch.float32), u64s(seeds), d, bucket, s, sync_stride,
+                                                  _lengths(lengths, s),
+                                                  arr([m.norms for m in messages], torch.float32),
+                                                  arr([m.bit_off for m in messages], torch.int64),
+                                                  arr([m.words for m in messages], torch.int32),
+                                                  u64s([m.words.numel() for m in messages]),
+                                                  arr([m.sync for m in messages]), _ptr(workspace),
+                                                  workspace.numel() * workspace.element_size(), _stream()))
 
 
 def nuq_decode_huffman_batch(messages: list[Message], d: int, bucket: int, s: int, sync_stride: int, lengths,

@@ -158,6 +158,27 @@ bool bucket_grid(uint64_t nb, uint32_t K, dim3 &grid)
     return true;
 }
 
+// Offsets and gather: lens and staging slots of K workers into their bit_off and words.
+int launch_finish(const EncodeParams &P, const EncodeBatch &Wk, uint32_t K, const Workspace &w, hipStream_t st)
+{
+    const uint64_t nb = P.nb;
+    const uint64_t nchunks = (nb + kChunk - 1) / kChunk;
+    const uint64_t *prefix = nullptr;
+    if (nb > kDirectSumMax) {
+        hipLaunchKernelGGL(k_chunk_sums, dim3((uint32_t)nchunks, K), dim3(256), 0, st, w.lens, nb, P.nb_stride,
+                           nchunks, w.chunk_sums);
+        hipLaunchKernelGGL(k_chunk_scan, dim3(K), dim3(256), 0, st, w.chunk_sums, nchunks);
+        prefix = w.chunk_sums;
+    }
+    const uint32_t fb = finish_buckets(P.bucket);
+    const dim3 fgrid((uint32_t)((nb + fb - 1) / fb), K);
+    if (fb == 64u)
+        hipLaunchKernelGGL(k_finish<64>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks);
+    else
+        hipLaunchKernelGGL(k_finish<16>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks);
+    return check_launch();
+}
+
 // MODE 0: fused norms + quantize + ENCODE from v.  MODE 1: ENCODE from level/sign bytes.  MODE 2: as 0 with the
 // level table `levels` (host memory, s + 2 values) and the norm `norm_kind` selects.
 template <int MODE>
@@ -233,22 +254,7 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
     if (rc != NUQ_OK)
         return rc;
 
-    // offsets + gather
-    const uint64_t nchunks = (nb + kChunk - 1) / kChunk;
-    const uint64_t *prefix = nullptr;
-    if (nb > kDirectSumMax) {
-        hipLaunchKernelGGL(k_chunk_sums, dim3((uint32_t)nchunks, K), dim3(256), 0, st, w.lens, nb, P.nb_stride,
-                           nchunks, w.chunk_sums);
-        hipLaunchKernelGGL(k_chunk_scan, dim3(K), dim3(256), 0, st, w.chunk_sums, nchunks);
-        prefix = w.chunk_sums;
-    }
-    const uint32_t fb = finish_buckets(bucket);
-    const dim3 fgrid((uint32_t)((nb + fb - 1) / fb), K);
-    if (fb == 64u)
-        hipLaunchKernelGGL(k_finish<64>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks);
-    else
-        hipLaunchKernelGGL(k_finish<16>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks);
-    return check_launch();
+    return launch_finish(P, Wk, K, w, st);
 }
 
 bool valid_fixed(uint32_t s, uint32_t b)
@@ -895,6 +901,95 @@ int nuq_encode_huffman(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s
     });
 }
 
+// Staging words per bucket for the fused Huffman encoder: every coordinate at the longest codeword (s + 1 bits) and a
+// sign bit.
+uint32_t huffman_slot_words(uint32_t bucket, uint32_t s)
+{
+    const uint64_t bits = (uint64_t)bucket * (s + 2u);
+    return (uint32_t)(((bits + 31) / 32 + 3) & ~3ull);
+}
+
+uint64_t nuq_encode_huffman_batch_workspace_bytes(uint32_t K, uint64_t d, uint32_t bucket, uint32_t s)
+{
+    if (K < 1 || K > kMaxBatch || !valid_common(d, bucket, s))
+        return 0;
+    return carve(nullptr, K, nuq_num_buckets(d, bucket), huffman_slot_words(bucket, s)).bytes;
+}
+
+int nuq_quantize_encode_huffman_batch(uint32_t K, const float *const *v, const uint64_t *seeds, uint64_t d,
+                                      uint32_t bucket, uint32_t s, uint32_t sync_stride, const uint8_t *lengths,
+                                      float *const *norms, uint64_t *const *bit_off, uint32_t *const *words,
+                                      const uint64_t *words_cap, uint32_t *const *sync, void *workspace,
+                                      uint64_t workspace_bytes, nuq_stream_t stream)
+{
+    if (K < 1 || K > kMaxBatch || !v || !seeds || !norms || !bit_off || !words || !words_cap || !lengths ||
+        !workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || !valid_common(d, bucket, s) ||
+        !valid_sync(sync_stride))
+        return NUQ_EINVAL;
+    const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
+    HuffmanCode H;
+    if (!huffman_tables(lengths, s, H))
+        return NUQ_EINVAL;
+    EncodeBatch Wk{};
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!v[k] || !norms[k] || !bit_off[k] || !words[k] || (nsync && (!sync || !sync[k])) ||
+            (reinterpret_cast<uintptr_t>(v[k]) & 3u))
+            return NUQ_EINVAL;
+        Wk.w[k].v = v[k];
+        Wk.w[k].seed = seeds[k];
+        Wk.w[k].norms_out = norms[k];
+        Wk.w[k].bit_off = bit_off[k];
+        Wk.w[k].words = words[k];
+        Wk.w[k].words_cap = words_cap[k];
+        Wk.w[k].sync = nsync ? sync[k] : nullptr;
+    }
+    const uint64_t nb = nuq_num_buckets(d, bucket);
+    const uint32_t slot_words = huffman_slot_words(bucket, s);
+    const Workspace w = carve(workspace, K, nb, slot_words);
+    if (w.bytes > workspace_bytes)
+        return NUQ_ECAPACITY;
+    uint32_t *flags = flags_ptr();
+    if (!flags)
+        return NUQ_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    EncodeParams P{};
+    P.d = d;
+    P.nb = nb;
+    P.nb_stride = (nb + 3) & ~3ull;
+    P.bucket = bucket;
+    P.s = s;
+    P.sync_shift = nsync ? log2u(sync_stride) : 0;
+    P.nsync = nsync;
+    P.slot_words = slot_words;
+    P.out_cap = slot_words;
+    P.lens = w.lens;
+    P.staging = w.staging;
+    P.flags = flags;
+    int rc = dispatch_team(bucket, [&](auto team_c, auto vpt_c) {
+        constexpr int TEAM = decltype(team_c)::value, VPT = decltype(vpt_c)::value;
+        using G = TeamGeom<TEAM>;
+        P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
+        P.lds_words = ((P.rows * TEAM + P.out_cap + 1u + nsync + 1u) & ~1u) + 64u;
+        const size_t lds_bytes = (size_t)P.lds_words * 4 * G::kTeamsPerWG;
+        if (lds_bytes > 160 * 1024)
+            return (int)NUQ_EINVAL;
+        auto kern = k_huffman_fused<TEAM, VPT>;
+        if (lds_bytes > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_bytes) != hipSuccess)
+            return (int)NUQ_EHIP;
+        dim3 grid;
+        if (!bucket_grid<TEAM>(nb, K, grid))
+            return (int)NUQ_EINVAL;
+        ScopedTiming timing(NUQ_T_QUANTIZE_ENCODE, st);
+        hipLaunchKernelGGL(kern, grid, dim3(G::kWG), lds_bytes, st, P, Wk, H);
+        return check_launch();
+    });
+    if (rc != NUQ_OK)
+        return rc;
+    return launch_finish(P, Wk, K, w, st);
+}
+
 int nuq_decode_huffman_batch(uint32_t K, const uint64_t *const *bit_off, const uint32_t *const *words,
                              const uint32_t *const *sync, uint64_t d, uint32_t bucket, uint32_t s,
                              uint32_t sync_stride, const uint8_t *lengths, uint8_t *const *q, nuq_stream_t stream)
@@ -930,8 +1025,14 @@ int nuq_decode_huffman_batch(uint32_t K, const uint64_t *const *bit_off, const u
         return NUQ_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     ScopedTiming timing(NUQ_T_DECODE, st);
-    if (nsync) {
-        const size_t lds_bytes = 64u * (sync_stride / 4u + 1u) * 4u;
+    bool direct = nsync && bucket % 16u == 0;
+    for (uint32_t k = 0; k < K && direct; ++k)
+        direct = (reinterpret_cast<uintptr_t>(q[k]) & 15u) == 0;
+    if (direct) {
+        const size_t lds_bytes = 64u * huffman_stage_stride(sync_stride) * 4u;
+        hipLaunchKernelGGL(k_huffman_decode_direct, dim3((uint32_t)blocks, K), dim3(64), lds_bytes, st, P, H);
+    } else if (nsync) {
+        const size_t lds_bytes = 64u * (sync_stride / 4u + 1u + huffman_stage_stride(sync_stride)) * 4u;
         if (lds_bytes > 48 * 1024 &&
             hipFuncSetAttribute(reinterpret_cast<const void *>(k_huffman_decode_tile),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
@@ -971,11 +1072,16 @@ int nuq_average_levels(uint32_t K, const float *const *norms, const uint8_t *con
     P.s = s;
     P.scale = scale;
     P.accumulate = accumulate;
-    const uint64_t threads = aligned ? (d + 3) / 4 : d, blocks = (threads + 255) / 256;
+    bool wide = aligned && bucket % 16u == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0;
+    for (uint32_t k = 0; k < K && wide; ++k)
+        wide = (reinterpret_cast<uintptr_t>(q[k]) & 15u) == 0;
+    const uint64_t threads = wide ? (d + 15) / 16 : aligned ? (d + 3) / 4 : d, blocks = (threads + 255) / 256;
     if (blocks > 0x7fffffffull)
         return NUQ_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (aligned)
+    if (wide)
+        hipLaunchKernelGGL(k_average_levels16, dim3((uint32_t)blocks), dim3(256), 0, st, P);
+    else if (aligned)
         hipLaunchKernelGGL(k_average_levels<4>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
     else
         hipLaunchKernelGGL(k_average_levels<1>, dim3((uint32_t)blocks), dim3(256), 0, st, P);

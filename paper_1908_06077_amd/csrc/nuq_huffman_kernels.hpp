@@ -117,25 +117,15 @@ __host__ __device__ inline uint32_t huffman_lds_words(uint32_t rows, uint32_t te
     return w + 64u;
 }
 
-template <int TEAM, int VPT>
-__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_huffman_emit(EncodeParams P, EncodeBatch Wk, HuffmanCode H)
+// The bucket's bit string from its level|sign bytes in LDS (qb32) into the zeroed LDS words `field`, sync offsets
+// into sync_l; returns the bucket's bit length to every thread.  Each thread codes a contiguous chunk of rows * 4
+// coordinates: codewords are shifted into a 64-bit register and leave it 32 bits at a time, OR-ed into the field
+// (a chunk's first and last words are shared with its neighbours).
+template <int TEAM>
+__device__ __forceinline__ uint32_t huffman_from_lds(const EncodeParams &P, const HuffmanCode &H, const uint32_t *qb32,
+                                                     uint32_t *field, uint32_t *sync_l, uint32_t *scratch,
+                                                     uint32_t nbk, uint32_t tid)
 {
-    extern __shared__ __align__(16) uint32_t smem[];
-    const EncodeWorker &W = Wk.w[0];
-    const uint32_t tid = threadIdx.x % TEAM;
-    const uint32_t team = team_uniform_u32<TEAM>(threadIdx.x / TEAM);
-    uint32_t *lds = smem + team * P.lds_words;
-    uint32_t *qb32 = lds;
-    uint32_t *field = qb32 + P.rows * TEAM;
-    uint32_t *sync_l = field + (P.bucket + 1u) / 2u + 1u;
-    uint32_t *scratch = lds + P.lds_words - 64u;
-    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + team;
-    const bool active = b < P.nb;
-    const uint64_t base = active ? b * P.bucket : 0;
-    const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
-    front_bytes_to_lds<TEAM>(P, W, base, nbk, tid, qb32);
-    __syncthreads();
-
     const uint8_t *qbytes = reinterpret_cast<const uint8_t *>(qb32);
     const uint32_t per = P.rows * 4u;
     const uint32_t c0 = min(tid * per, nbk), c1 = min(c0 + per, nbk);
@@ -179,6 +169,66 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_huffman_emit(EncodePara
         if (fill)
             atomicOr(&field[wi], (uint32_t)(acc << (32u - fill)));
     }
+    return total;
+}
+
+// Norms + quantizer + Huffman coding of one bucket per team, v read once, all workers in one launch (blockIdx.y): the
+// bit string goes to the bucket's staging slot and its length to lens; k_finish turns those into bit_off and words as
+// for the ERC strings.
+template <int TEAM, int VPT>
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_huffman_fused(EncodeParams P, EncodeBatch Wk, HuffmanCode H)
+{
+    extern __shared__ __align__(16) uint32_t smem[];
+    const EncodeWorker &W = Wk.w[blockIdx.y];
+    const uint32_t tid = threadIdx.x % TEAM;
+    const uint32_t team = team_uniform_u32<TEAM>(threadIdx.x / TEAM);
+    uint32_t *lds = smem + team * P.lds_words;
+    uint32_t *qb32 = lds;
+    uint32_t *field = qb32 + P.rows * TEAM;
+    uint32_t *sync_l = field + P.out_cap + 1u;
+    uint32_t *scratch = lds + P.lds_words - 64u;
+    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + team;
+    const bool active = b < P.nb;
+    const uint64_t base = active ? b * P.bucket : 0;
+    const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
+    front_quantize_to_lds<TEAM, VPT>(P, W, b, active, base, nbk, tid, qb32, scratch);
+    __syncthreads();
+    const uint32_t total = huffman_from_lds<TEAM>(P, H, qb32, field, sync_l, scratch, nbk, tid);
+    const uint32_t nwords = (total + 31u) >> 5;
+    team_barrier<TEAM>();
+    if (active) {
+        uint32_t *slot = P.staging + ((uint64_t)blockIdx.y * P.nb + b) * P.slot_words;
+        for (uint32_t i = tid; i < nwords; i += TEAM)
+            slot[i] = field[i];
+        uint32_t *sg = W.sync + b * P.nsync;
+        for (uint32_t i = tid; i < P.nsync; i += TEAM)
+            sg[i] = sync_l[i];
+        if (tid == 0)
+            P.lens[(uint64_t)blockIdx.y * P.nb_stride + b] = total;
+    }
+}
+
+template <int TEAM, int VPT>
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_huffman_emit(EncodeParams P, EncodeBatch Wk, HuffmanCode H)
+{
+    extern __shared__ __align__(16) uint32_t smem[];
+    const EncodeWorker &W = Wk.w[0];
+    const uint32_t tid = threadIdx.x % TEAM;
+    const uint32_t team = team_uniform_u32<TEAM>(threadIdx.x / TEAM);
+    uint32_t *lds = smem + team * P.lds_words;
+    uint32_t *qb32 = lds;
+    uint32_t *field = qb32 + P.rows * TEAM;
+    uint32_t *sync_l = field + (P.bucket + 1u) / 2u + 1u;
+    uint32_t *scratch = lds + P.lds_words - 64u;
+    const uint64_t b = (uint64_t)blockIdx.x * TeamGeom<TEAM>::kTeamsPerWG + team;
+    const bool active = b < P.nb;
+    const uint64_t base = active ? b * P.bucket : 0;
+    const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
+    front_bytes_to_lds<TEAM>(P, W, base, nbk, tid, qb32);
+    __syncthreads();
+
+    const uint32_t total = huffman_from_lds<TEAM>(P, H, qb32, field, sync_l, scratch, nbk, tid);
+    const uint32_t nwords = (total + 31u) >> 5;
     team_barrier<TEAM>();
     if (active) {
         const uint64_t start_word = (W.bit_off[b] + 31ull) >> 5;
@@ -268,13 +318,22 @@ __global__ __launch_bounds__(256) void k_huffman_decode(HuffmanDecodeParams P, H
         atomicOr(P.flags, kFlagMalformed);
 }
 
+// Words of a unit's bit string that a lane stages in LDS (a unit of S coordinates at up to two bits per coordinate
+// and a little more; longer ones are read from global memory as they go) and the stride of a lane's staging row.
+__host__ __device__ inline uint32_t huffman_stage_cap(uint32_t S) { return S / 16u + 6u; }
+__host__ __device__ inline uint32_t huffman_stage_stride(uint32_t S) { return huffman_stage_cap(S) + 3u; }   // odd
+
 // The same for messages with a sync index: a wave owns 64 consecutive units.  Code tables and a lookup table on the
-// next eight bits (symbol | length << 4; 0 for longer codewords, which take the length-by-length walk) live in LDS;
-// each lane assembles its unit's bytes four at a time into its row of an LDS tile (row stride S + 4 bytes: the lanes
-// hit different banks), and the tile goes out unit by unit with whole-wave stores.
+// next eight bits (symbol | length << 4; 0 for longer codewords, which take the length-by-length walk) live in LDS.
+// A lane first copies its unit's words into its staging row (independent loads, all in flight together), then
+// parses them with the window of the ERC decoder: position + 31 is the loop variable, the 32-bit window comes from
+// two words through one funnel shift, and those two words and the one after them wait in registers (a codeword and
+// its sign are at most 16 bits: the pair moves on by one word at most).  Bytes are assembled four at a time into the
+// lane's row of an LDS tile (row stride S + 4 bytes: the lanes hit different banks), and the tile goes out unit by
+// unit with whole-wave stores.
 __global__ __launch_bounds__(64) void k_huffman_decode_tile(HuffmanDecodeParams P, HuffmanCode H)
 {
-    extern __shared__ __align__(16) uint32_t tile[];            // 64 rows of S / 4 + 1 words
+    extern __shared__ __align__(16) uint32_t tile[];            // 64 rows of S / 4 + 1 words, then 64 staging rows
     __shared__ uint8_t lut8[256];
     __shared__ uint32_t first[16], count[16], offset[16], sorted[16];
     __shared__ uint32_t unit_dst_lo[64], unit_dst_hi[64], unit_len[64];
@@ -312,6 +371,8 @@ __global__ __launch_bounds__(64) void k_huffman_decode_tile(HuffmanDecodeParams 
     const uint32_t c_lo = g << P.sync_shift;
     const uint32_t c_hi = live && c_lo < nbk ? min(nbk, c_lo + S) : c_lo;      // an empty range for idle lanes
     uint32_t *row = tile + lane * row_words;
+    const uint32_t cap = huffman_stage_cap(S), stride = huffman_stage_stride(S);
+    uint32_t *srow = tile + 64u * row_words + lane * stride;    // srow[1 + j] = word j of the unit's frame
     bool bad = false;
     if (c_lo < c_hi) {
         const uint64_t start = (W.bit_off[b] + 31ull) & ~31ull, end = W.bit_off[b + 1];
@@ -320,7 +381,55 @@ __global__ __launch_bounds__(64) void k_huffman_decode_tile(HuffmanDecodeParams 
         const uint32_t lo = g ? sg[g - 1u] : 0u;
         const uint32_t hi = g + 1u < P.nseg ? sg[g] : len;
         bad = lo > hi || hi > len;
-        if (!bad) {
+        const uint32_t w0 = lo >> 5, nw = bad ? 0u : ((hi + 31u) >> 5) - w0;
+        if (!bad && nw <= cap) {
+            const uint32_t *src = W.words + (start >> 5) + w0;
+            for (uint32_t j0 = 0; j0 < nw; j0 += 8u) {
+                uint32_t t[8];
+#pragma unroll
+                for (uint32_t j = 0; j < 8u; ++j)
+                    t[j] = src[min(j0 + j, nw - 1u)];
+#pragma unroll
+                for (uint32_t j = 0; j < 8u; ++j)
+                    if (j0 + j < nw)
+                        srow[1u + j0 + j] = t[j];
+            }
+            const uint32_t bit0 = lo & 31u;
+            uint32_t p31 = bit0 + 31u, q = p31 >> 5;
+            uint32_t hw = srow[q], lw = srow[q + 1u], nx = srow[q + 2u];
+            uint32_t four = 0;
+            for (uint32_t c = c_lo; c < c_hi; ++c) {
+                const uint32_t w = __builtin_amdgcn_alignbit(hw, lw, ~p31);
+                uint32_t entry = lut8[w >> 24];
+                if (!entry) {                                   // a codeword of nine bits or more (rare), or none
+                    for (uint32_t L = 9; L <= H.maxlen; ++L) {
+                        const uint32_t idx = (w >> (32u - L)) - first[L];
+                        if (idx < count[L]) {
+                            entry = sorted[offset[L] + idx] | (L << 4);
+                            break;
+                        }
+                    }
+                }
+                const uint32_t sym = entry & 15u, L = entry >> 4;
+                bad |= !L;
+                const uint32_t neg = sym ? (w >> (31u - L)) & 1u : 0u;
+                four |= (sym | (neg << 7)) << (8u * (c & 3u));
+                if ((c & 3u) == 3u) {
+                    row[(c - c_lo) >> 2] = four;
+                    four = 0;
+                }
+                p31 += L + (sym ? 1u : 0u);
+                const uint32_t qn = p31 >> 5;
+                const bool moved = qn != q;
+                hw = moved ? lw : hw;
+                lw = moved ? nx : lw;
+                q = qn;
+                nx = srow[min(qn + 2u, stride - 1u)];
+            }
+            if ((c_hi - c_lo) & 3u)
+                row[(c_hi - c_lo) >> 2] = four;
+            bad |= lo - bit0 + (p31 - 31u) != hi;
+        } else if (!bad) {
             WalkWords gw{W.words + (start >> 5)};
             BitReader<WalkWords> br;
             br.init(gw, lo, (len + 31u) >> 5);
@@ -384,6 +493,152 @@ __global__ __launch_bounds__(64) void k_huffman_decode_tile(HuffmanDecodeParams 
     }
 }
 
+// The decoder for the usual geometry (buckets and byte arrays that are multiples of 16: every unit starts on a 16-byte
+// boundary): as k_huffman_decode_tile, but a lane collects 16 bytes in registers and stores them itself.  Sixty-four
+// 16-byte stores 256 bytes apart are few enough transactions, and without the tile the wave needs 6.4 KB of LDS
+// instead of 23, so four times as many waves hide each other's latencies (the parse is one dependent chain per lane).
+__global__ __launch_bounds__(64) void k_huffman_decode_direct(HuffmanDecodeParams P, HuffmanCode H)
+{
+    extern __shared__ __align__(16) uint32_t stage_rows[];      // 64 staging rows
+    __shared__ uint8_t lut8[256];
+    __shared__ uint32_t first[16], count[16], offset[16], sorted[16];
+    const uint32_t lane = threadIdx.x;
+    const uint32_t S = 1u << P.sync_shift;
+    if (lane < 16u) {
+        first[lane] = H.first[lane];
+        count[lane] = H.count[lane];
+        offset[lane] = H.offset[lane];
+        sorted[lane] = H.sorted[lane];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t p = lane; p < 256u; p += 64u) {
+        uint32_t entry = 0;
+        for (uint32_t L = 1; L <= 8u && L <= H.maxlen; ++L) {
+            const uint32_t idx = (p >> (8u - L)) - first[L];
+            if (idx < count[L]) {
+                entry = sorted[offset[L] + idx] | (L << 4);
+                break;
+            }
+        }
+        lut8[p] = (uint8_t)entry;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+
+    const HuffmanStream &W = P.w[blockIdx.y];
+    const uint64_t u = (uint64_t)blockIdx.x * 64u + lane;
+    if (u >= P.nb * P.nseg)
+        return;
+    const uint64_t b = u / P.nseg;
+    const uint32_t g = (uint32_t)(u - b * P.nseg);
+    const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
+    const uint32_t c_lo = g << P.sync_shift;
+    if (c_lo >= nbk)
+        return;
+    const uint32_t n = min(nbk, c_lo + S) - c_lo;
+    const uint32_t cap = huffman_stage_cap(S), stride = huffman_stage_stride(S);
+    uint32_t *srow = stage_rows + lane * stride;
+    const uint64_t start = (W.bit_off[b] + 31ull) & ~31ull, end = W.bit_off[b + 1];
+    const uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
+    const uint32_t *sg = W.sync + b * P.nsync;
+    const uint32_t lo = g ? sg[g - 1u] : 0u;
+    const uint32_t hi = g + 1u < P.nseg ? sg[g] : len;
+    bool bad = lo > hi || hi > len;
+    uint8_t *out = W.q + b * P.bucket + c_lo;                   // 16-byte aligned
+    const uint32_t w0 = lo >> 5, nw = bad ? 0u : ((hi + 31u) >> 5) - w0;
+    if (!bad && nw <= cap) {
+        const uint32_t *src = W.words + (start >> 5) + w0;
+        for (uint32_t j0 = 0; j0 < nw; j0 += 8u) {
+            uint32_t t[8];
+#pragma unroll
+            for (uint32_t j = 0; j < 8u; ++j)
+                t[j] = src[min(j0 + j, nw - 1u)];
+#pragma unroll
+            for (uint32_t j = 0; j < 8u; ++j)
+                if (j0 + j < nw)
+                    srow[1u + j0 + j] = t[j];
+        }
+        const uint32_t bit0 = lo & 31u;
+        uint32_t p31 = bit0 + 31u, q = p31 >> 5;
+        uint32_t hw = srow[q], lw = srow[q + 1u], nx = srow[q + 2u];
+        uint32_t four = 0, x0 = 0, x1 = 0, x2 = 0, x3 = 0;
+        for (uint32_t i = 0; i < n; ++i) {
+            const uint32_t w = __builtin_amdgcn_alignbit(hw, lw, ~p31);
+            uint32_t entry = lut8[w >> 24];
+            if (!entry) {                                       // a codeword of nine bits or more (rare), or none
+                for (uint32_t L = 9; L <= H.maxlen; ++L) {
+                    const uint32_t idx = (w >> (32u - L)) - first[L];
+                    if (idx < count[L]) {
+                        entry = sorted[offset[L] + idx] | (L << 4);
+                        break;
+                    }
+                }
+            }
+            const uint32_t sym = entry & 15u, L = entry >> 4;
+            bad |= !L;
+            const uint32_t neg = sym ? (w >> (31u - L)) & 1u : 0u;
+            four |= (sym | (neg << 7)) << (8u * (i & 3u));
+            if ((i & 3u) == 3u) {
+                x0 = x1;
+                x1 = x2;
+                x2 = x3;
+                x3 = four;
+                four = 0;
+                if ((i & 15u) == 15u)
+                    *reinterpret_cast<uint4 *>(out + (i - 15u)) = uint4{x0, x1, x2, x3};
+            }
+            p31 += L + (sym ? 1u : 0u);
+            const uint32_t qn = p31 >> 5;
+            const bool moved = qn != q;
+            hw = moved ? lw : hw;
+            lw = moved ? nx : lw;
+            q = qn;
+            nx = srow[min(qn + 2u, stride - 1u)];
+        }
+        // what is left of a unit that is no multiple of 16 (the vector's last bucket): whole words, then bytes
+        const uint32_t done = n & ~15u, wleft = (n & 15u) >> 2;
+        const uint32_t xs[4] = {x0, x1, x2, x3};
+#pragma unroll
+        for (uint32_t j = 0; j < 3u; ++j)
+            if (j < wleft)
+                reinterpret_cast<uint32_t *>(out + done)[j] = wleft == 1u ? xs[3] : wleft == 2u ? xs[2 + j] : xs[1 + j];
+        for (uint32_t c = 0; c < (n & 3u); ++c)
+            out[done + 4u * wleft + c] = (uint8_t)(four >> (8u * c));
+        bad |= lo - bit0 + (p31 - 31u) != hi;
+    } else if (!bad) {                                          // a unit too long for its staging row
+        WalkWords gw{W.words + (start >> 5)};
+        BitReader<WalkWords> br;
+        br.init(gw, lo, (len + 31u) >> 5);
+        uint32_t pos = lo;
+        for (uint32_t i = 0; i < n; ++i) {
+            br.refill();
+            const uint32_t w = br.peek();
+            uint32_t entry = 0;
+            for (uint32_t L = 1; L <= H.maxlen; ++L) {
+                const uint32_t idx = (w >> (32u - L)) - first[L];
+                if (idx < count[L]) {
+                    entry = sorted[offset[L] + idx] | (L << 4);
+                    break;
+                }
+            }
+            const uint32_t sym = entry & 15u, L = entry >> 4;
+            const uint32_t nb = L + (sym ? 1u : 0u);
+            if (!L || pos + nb > hi) {
+                bad = true;
+                break;
+            }
+            const uint32_t neg = sym ? (w >> (31u - L)) & 1u : 0u;
+            out[i] = (uint8_t)(sym | (neg << 7));
+            br.skip(nb);
+            pos += nb;
+        }
+        bad |= pos != hi;
+    }
+    if (bad)
+        atomicOr(P.flags, kFlagMalformed);
+}
+
 // ------------------------------------------------------------------ average of level bytes
 struct AverageParams {
     const float *norms[kMaxBatch];
@@ -406,7 +661,7 @@ __global__ __launch_bounds__(256) void k_average_levels(AverageParams P)
     const uint64_t i0 = ((uint64_t)blockIdx.x * 256u + threadIdx.x) * VEC;
     if (i0 >= P.d)
         return;
-    const uint64_t bk = i0 / P.bucket;
+    const uint64_t bk = P.d <= 0xffffffffull ? (uint64_t)((uint32_t)i0 / P.bucket) : i0 / P.bucket;
     double sum[VEC];
 #pragma unroll
     for (int c = 0; c < VEC; ++c)
@@ -443,6 +698,68 @@ __global__ __launch_bounds__(256) void k_average_levels(AverageParams P)
             const float r = (float)(sc * sum[c]);
             P.out[i0 + c] = P.accumulate ? P.out[i0 + c] + r : r;
         }
+    }
+}
+
+// Buckets that are multiples of 16 coordinates, 16-byte aligned arrays: 16 coordinates per thread, one 16-byte load per
+// worker, four 16-byte stores.
+__global__ __launch_bounds__(256) void k_average_levels16(AverageParams P)
+{
+    const uint64_t i0 = ((uint64_t)blockIdx.x * 256u + threadIdx.x) * 16u;
+    if (i0 >= P.d)
+        return;
+    const uint64_t bk = P.d <= 0xffffffffull ? (uint64_t)((uint32_t)i0 / P.bucket) : i0 / P.bucket;
+    const bool whole = i0 + 15u < P.d;
+    double sum[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c)
+        sum[c] = 0.0;
+    for (uint32_t k = 0; k < P.K; ++k) {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (whole) {
+            const uint4 t = *reinterpret_cast<const uint4 *>(P.q[k] + i0);
+            w[0] = t.x;
+            w[1] = t.y;
+            w[2] = t.z;
+            w[3] = t.w;
+        } else {
+            for (uint32_t c = 0; i0 + c < P.d; ++c)
+                w[c >> 2] |= (uint32_t)P.q[k][i0 + c] << (8u * (c & 3u));
+        }
+        if (!(w[0] | w[1] | w[2] | w[3]))
+            continue;
+        const double nrm = (double)P.norms[k][bk];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const uint32_t byte = (w[c >> 2] >> (8 * (c & 3))) & 0xffu, level = byte & 0x7fu;
+            if (level) {
+                const double val = ldexp(nrm, (int)level - 1 - (int)P.s);
+                sum[c] += (byte & 0x80u) ? -val : val;
+            }
+        }
+    }
+    const double sc = (double)P.scale;
+    float r[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c)
+        r[c] = (float)(sc * sum[c]);
+    if (whole) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float4 o{r[4 * v], r[4 * v + 1], r[4 * v + 2], r[4 * v + 3]};
+            float4 *dst = reinterpret_cast<float4 *>(P.out + i0) + v;
+            if (P.accumulate) {
+                const float4 prev = *dst;
+                o.x += prev.x;
+                o.y += prev.y;
+                o.z += prev.z;
+                o.w += prev.w;
+            }
+            *dst = o;
+        }
+    } else {
+        for (uint32_t c = 0; i0 + c < P.d; ++c)
+            P.out[i0 + c] = P.accumulate ? P.out[i0 + c] + r[c] : r[c];
     }
 }
 

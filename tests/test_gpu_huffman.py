@@ -45,7 +45,7 @@ def test_histogram_code_message_decode_and_average(g, d, n, s, S, K, kind):
     cap = nuq.nuq_huffman_max_words(d, n)
     ws = torch.empty(nuq.nuq_encode_huffman_workspace_bytes(d, n), dtype=torch.uint8, device=g.DEV)
     lengths = None
-    norms_list, q_list, q_np_list, msg_list = [], [], [], []
+    norms_list, q_list, q_np_list, msg_list, v_list = [], [], [], [], []
     for k in range(K):
         v_np = make_vector(kind, d, n, rng)
         v = torch.from_numpy(v_np).to(g.DEV)
@@ -77,10 +77,26 @@ def test_histogram_code_message_decode_and_average(g, d, n, s, S, K, kind):
         nuq.nuq_decode_huffman(bit_off, words, sync if nsync else None, d, n, s, S, lengths, back)
         assert nuq.nuq_last_error_flags() == 0
         assert torch.equal(back, q)
+        v_list.append(v)
         norms_list.append(norms)
         msg_list.append(nuq.Message(norms, bit_off, words, sync if nsync else None))
         q_list.append(back)
         q_np_list.append(q_np)
+    # norms, quantizer and coding of all K workers in one launch (v read once) give the same norms and messages
+    fused = [nuq.Message(torch.full((B,), -1.0, dtype=torch.float32, device=g.DEV),
+                         torch.full((B + 1,), -1, dtype=torch.int64, device=g.DEV),
+                         torch.zeros(cap, dtype=torch.int32, device=g.DEV),
+                         torch.full((max(1, B * nsync),), 0x33333333, dtype=torch.int32, device=g.DEV)) for _ in range(K)]
+    fws = torch.empty(nuq.nuq_encode_huffman_batch_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_quantize_encode_huffman_batch(v_list, n, s, [31 + k for k in range(K)], S, lengths, fused, fws)
+    assert nuq.nuq_last_error_flags() == 0
+    for f, m in zip(fused, msg_list):
+        assert torch.equal(f.norms, m.norms)
+        assert torch.equal(f.bit_off, m.bit_off)
+        nw = (int(m.bit_off[-1].item()) + 31) // 32
+        assert torch.equal(f.words[:nw], m.words[:nw]) and not f.words[nw:].any()
+        if nsync:
+            assert torch.equal(f.sync[: B * nsync], m.sync[: B * nsync])
     # all K messages decoded in one launch give the same bytes
     again = [torch.full((d,), 0x7E, dtype=torch.uint8, device=g.DEV) for _ in range(K)]
     nuq.nuq_decode_huffman_batch(msg_list, d, n, s, S, lengths, again)
