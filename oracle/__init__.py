@@ -456,3 +456,70 @@ def decode_huffman(bit_off, words, d: int, bucket: int, s: int, lengths) -> np.n
     if rc:
         raise ValueError("malformed stream: %d" % rc)
     return q
+
+
+# ------------------------------------------------------- Alg. 1, the momentum rule, normalized variance
+# Plain numpy in fp64; the quantizer, ENCODE and DECODE steps are the C functions above.
+
+def momentum_step(w, yl_prev, g, alpha: float, mu: float, l: float):
+    """Update rule of Sec. 4.2 ("NUQSGD with Momentum"): y = w - alpha g, y^l = w - l alpha g,
+    w_next = y + mu (y^l - y^l_prev).  alpha, mu, l are taken at fp32 precision (what the caller can
+    pass through the library).  Returns (w_next, y^l) in fp64; l = 0 is heavy ball, l = 1 Nesterov."""
+    w = np.asarray(w, dtype=np.float64)
+    yl_prev = np.asarray(yl_prev, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    alpha, mu, l = (float(np.float32(x)) for x in (alpha, mu, l))
+    y = w - alpha * g
+    yl = w - (l * alpha) * g
+    return y + mu * (yl - yl_prev), yl
+
+
+def normalized_variance(samples) -> float:
+    """Mean normalized variance (App. J, "Additional Experiments"): over M draws of a gradient estimate (rows), the mean over
+    coordinates of the variance across draws divided by the mean over coordinates of the second moment
+    across draws.  Variance = mean squared deviation from the mean of the M draws."""
+    x = np.asarray(samples, dtype=np.float64)
+    mean = x.mean(axis=0)
+    var = ((x - mean) ** 2).mean(axis=0)
+    second = (x * x).mean(axis=0)
+    return float(var.mean() / second.mean())
+
+
+def step_seed(seed0: int, t: int, K: int, k: int) -> int:
+    """Seed of worker k's quantizer at step t: every (t, k) draws from its own stream."""
+    return (seed0 + t * K + k) & (2 ** 64 - 1)
+
+
+def aggregate_quantized(grads, bucket: int, s: int, sync_stride: int, seeds) -> np.ndarray:
+    """Inner loops of Alg. 1 for one step: every worker quantizes and ENCODEs its gradient, every
+    receiver DECODEs the K messages; returns (1/K) sum_k Q(g_k) in fp64."""
+    K = len(grads)
+    d = grads[0].size
+    norms_l, off_l, words_l = [], [], []
+    for k in range(K):
+        g = np.ascontiguousarray(grads[k], dtype=np.float32)
+        norms = bucket_norms(g, bucket)
+        q = quantize(g, bucket, s, seeds[k], norms)
+        bit_off, words, _ = encode(q, bucket, s, sync_stride)
+        norms_l.append(norms); off_l.append(bit_off); words_l.append(words)
+    return decode_average(norms_l, off_l, words_l, d, bucket, s, 1.0 / K)
+
+
+def data_parallel_sgd(w0, grad_fn, K: int, T: int, alpha: float, bucket: int, s: int, sync_stride: int = 0,
+                      seed0: int = 0, mu: float = 0.0, l: float = 0.0) -> np.ndarray:
+    """Alg. 1 with Omega = R^d (no projection): for t < T, worker k computes g = grad_fn(w_t, t, k)
+    (fp32, length d), the K gradients are quantized, coded, decoded and averaged, and the parameters
+    move by the plain rule w - alpha * average (mu == 0) or by the momentum rule.  Parameters and y^l are
+    held in fp32 between steps, as the library's caller holds them.  Returns w_T (fp32)."""
+    w = np.array(w0, dtype=np.float32)
+    yl = w.copy()
+    a32 = float(np.float32(alpha))
+    for t in range(T):
+        grads = [np.asarray(grad_fn(w, t, k), dtype=np.float32) for k in range(K)]
+        avg = aggregate_quantized(grads, bucket, s, sync_stride, [step_seed(seed0, t, K, k) for k in range(K)])
+        if mu == 0.0:
+            w = (w.astype(np.float64) - a32 * avg).astype(np.float32)
+        else:
+            w_next, yl_next = momentum_step(w, yl, avg.astype(np.float32), alpha, mu, l)
+            w, yl = w_next.astype(np.float32), yl_next.astype(np.float32)
+    return w
