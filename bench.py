@@ -50,6 +50,12 @@ def parse_args():
                     help="Huffman-coded levels (the paper's \"encoded\" variant) instead of the ERC bit strings: per "
                          "fused norms + quantizer + Huffman coding; decode to level bytes and one averaging kernel; "
                          "the code is built once from worker 0's level histogram; main scheme's levels only")
+    ap.add_argument("--update", default="none", choices=["none", "sgd", "momentum", "momentum-unfused"],
+                    help="what the receiver does with the average: none (write it out: the default path), sgd "
+                         "(Alg. 1's aggregate step: the decoder adds -alpha/K times the sum onto the parameters in the "
+                         "same launch), momentum (the decoder applies the momentum rule of Sec. 4.2 to the parameters and "
+                         "y^l in the same launch) or momentum-unfused (the average, then the rule in one more kernel); "
+                         "main scheme and ERC coding only")
     ap.add_argument("--norm", default="l2", choices=["l2", "linf"],
                     help="bucket norm for a level table: Euclidean, or maximum (QSGDinf with --levels uniform)")
     ap.add_argument("--reference-kernels", action="store_true",
@@ -140,6 +146,14 @@ def main():
         msgs = [new_msg((int(p.bit_off[-1].item()) + 31) // 32 + 64) for p in probes]
         del probes
     out = torch.empty(d, dtype=torch.float32, device=dev)
+    upd = args.update
+    if upd != "none":
+        if huff or fb or lev is not None:
+            print("--update goes with the main scheme and the ERC coding", file=sys.stderr)
+            sys.exit(2)
+        alpha, mu, nesterov_l = 0.1, 0.9, 1.0
+        params = torch.empty(d, dtype=torch.float32, device=dev).normal_()
+        yl = params.clone()
 
     def encode_all():
         if huff:
@@ -163,8 +177,14 @@ def main():
             nuq.nuq_unpack_accumulate_fixed(fnorms, fpacked, d, n, s, fb, 1.0 / K, False, out)
         elif lev is not None:
             nuq.nuq_decode_accumulate_table(msgs, d, n, lev, S, 1.0 / K, False, out)
+        elif upd == "sgd":
+            nuq.nuq_decode_accumulate(msgs, d, n, s, S, -alpha / K, True, params)
+        elif upd == "momentum":
+            nuq.nuq_decode_momentum_step(msgs, d, n, s, S, 1.0 / K, alpha, mu, nesterov_l, params, yl)
         else:
             nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
+            if upd == "momentum-unfused":
+                nuq.nuq_momentum_step(params, yl, out, alpha, mu, nesterov_l)
 
     def step():
         encode_all()
@@ -277,12 +297,36 @@ def main():
                                        "k_decode_accumulate (DECODE + average of K messages)"),
                             "bound": "hbm", "achieved": round(dec_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
-                            "traffic": None if lev is not None or fb or huff
+                            "traffic": None if lev is not None or fb or huff or upd in ("sgd", "momentum")
                             else measured_traffic("k_decode_accumulate", args.config, S),
                             "bytes_per_launch": round(dec_alg), "launch_ms": round(dec_kernel_ms, 5),
                             "launches": len(dec_ms)},
     }
 
+    if upd != "none":
+        result["config"]["workload"] += ", parameter update: %s" % (
+            "plain step inside the decoder" if upd == "sgd" else
+            "momentum rule, mu=%g l=%g, %s" % (mu, nesterov_l, "inside the decoder" if upd == "momentum"
+                                               else "in a kernel of its own"))
+        if upd in ("sgd", "momentum"):
+            # the decoder also reads the parameters (sgd), or reads and writes parameters and y^l instead of
+            # writing the average (momentum)
+            dec_upd = dec_alg + (4.0 if upd == "sgd" else 12.0) * d
+            result["roofline_decode"].update(bytes_per_launch=round(dec_upd),
+                                             achieved=round(dec_upd / (dec_kernel_ms * 1e-3) / 1e9, 2),
+                                             frac=round(dec_upd / (dec_kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+        else:
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(20):
+                nuq.nuq_momentum_step(params, yl, out, alpha, mu, nesterov_l)
+            b.record()
+            torch.cuda.synchronize()
+            ms_mom = a.elapsed_time(b) / 20
+            result["update"] = {"kernel": "k_momentum_step (reads w, y^l, average; writes w, y^l)", "bound": "hbm",
+                                "ms": round(ms_mom, 5), "bytes_per_launch": 20 * d,
+                                "achieved": round(20.0 * d / (ms_mom * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBS,
+                                "unit": "GB/s", "frac": round(20.0 * d / (ms_mom * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     if args.reference_kernels:
         result["reference"] = reference_kernels(torch, d * K, dev)
     if not args.no_cpu_baseline:

@@ -283,6 +283,45 @@ int nuq_average_levels(uint32_t K, const float *const *norms, const uint8_t *con
                        uint32_t bucket, uint32_t s, float scale, int accumulate, float *out,
                        nuq_stream_t stream);
 
+/* ---- parameter update and variance diagnostic (Alg. 1 aggregate; Sec. 4.2; App. J) --------------- */
+
+/* The plain aggregate step of Alg. 1 with Omega = R^d,  w <- w - (alpha/K) sum_k Q_k,  is
+ * nuq_decode_accumulate (or its table / fixed-width / byte variants) with out = w, accumulate = 1 and
+ * scale = -alpha/K: no separate pass over w.
+ *
+ * Momentum rule of Sec. 4.2 on d fp32 values in DEVICE memory, g the averaged gradient:
+ *   y = w - alpha g;  y^l = w - l alpha g;  w <- y + mu (y^l - yl);  yl <- y^l.
+ * l = 0 is heavy ball, l = 1 Nesterov's method.  The caller sets yl = w before the first step and owns
+ * all three arrays; w and yl are updated in place.  Evaluated in fp64 in this order from the fp32
+ * inputs, one rounding per stored value.  NUQ_EINVAL for a null pointer with d > 0, a non-finite
+ * alpha, mu or l, or mu outside [0, 1). */
+int nuq_momentum_step(float *w, float *yl, const float *g, uint64_t d, float alpha, float mu, float l,
+                      nuq_stream_t stream);
+
+/* nuq_decode_accumulate and nuq_momentum_step in one launch: (w, yl) <- momentum rule with
+ * g[i] = the fp32 value nuq_decode_accumulate(..., scale, accumulate = 0, ...) would store at i (scale =
+ * 1/K for Alg. 1's average).  Same bits in w and yl as the two calls give; the average itself is not
+ * stored, which saves its write and read (8 of the update's 24 bytes per coordinate).  Message
+ * arguments as nuq_decode_accumulate; alpha, mu, l, w, yl as nuq_momentum_step. */
+int nuq_decode_momentum_step(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                             const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
+                             uint32_t bucket, uint32_t s, uint32_t sync_stride, float scale, float alpha,
+                             float mu, float l, float *w, float *yl, nuq_stream_t stream);
+
+/* First and second moments of a gradient estimate across draws (App. J): sum[i] += g[i],
+ * sumsq[i] += g[i]^2 in fp64; g, sum, sumsq: DEVICE arrays of d values, sum and sumsq zeroed by the
+ * caller before the first draw. */
+int nuq_moments_accumulate(const float *g, double *sum, double *sumsq, uint64_t d, nuq_stream_t stream);
+
+/* Mean normalized variance of App. J after M >= 1 draws: out2[0] = sum_i (sumsq_i/M - (sum_i/M)^2),
+ * out2[1] = sum_i sumsq_i/M (DEVICE doubles); the diagnostic is out2[0] / out2[1] (the two means over
+ * coordinates share the factor 1/d).  Variance = mean squared deviation from the mean of the M draws.
+ * workspace: DEVICE memory of at least NUQ_VARIANCE_WORKSPACE_BYTES bytes, 8-byte aligned, overwritten.
+ * The summation order is fixed: equal inputs give equal bits. */
+#define NUQ_VARIANCE_WORKSPACE_BYTES 16384u
+int nuq_normalized_variance(const double *sum, const double *sumsq, uint64_t d, uint64_t M, void *workspace,
+                            uint64_t workspace_bytes, double *out2, nuq_stream_t stream);
+
 /* ---- errors ---------------------------------------------------------------------- */
 
 /* Waits for `stream`, copies the sticky device flags of the current device to

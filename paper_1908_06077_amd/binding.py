@@ -54,6 +54,11 @@ _SIGNATURES = {
                                                  _vp, _u64, _vp]),
     "nuq_decode_huffman_batch": (_i32, [_u32, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "nuq_average_levels": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _f32, _i32, _vp, _vp]),
+    "nuq_momentum_step": (_i32, [_vp, _vp, _vp, _u64, _f32, _f32, _f32, _vp]),
+    "nuq_decode_momentum_step": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _f32, _f32, _f32, _vp,
+                                        _vp, _vp]),
+    "nuq_moments_accumulate": (_i32, [_vp, _vp, _vp, _u64, _vp]),
+    "nuq_normalized_variance": (_i32, [_vp, _vp, _u64, _u64, _vp, _u64, _vp, _vp]),
     "nuq_last_error_flags": (_i32, [_vp, _vp]),
     "nuq_timing_begin": (_i32, [_u32]),
     "nuq_timing_collect": (_i32, [_vp, _vp, _u32, _vp]),
@@ -380,6 +385,53 @@ def nuq_average_levels(norms: list[torch.Tensor], qs: list[torch.Tensor], d: int
     _check("nuq_average_levels",
            _lib.nuq_average_levels(K, arr(norms, torch.float32), arr(qs, torch.uint8), d, bucket, s, float(scale),
                                    1 if accumulate else 0, _ptr(out, torch.float32), _stream()))
+
+
+# --------------------------------- parameter update and variance diagnostic
+
+VARIANCE_WORKSPACE_BYTES = 16384
+
+
+def nuq_momentum_step(w: torch.Tensor, yl: torch.Tensor, g: torch.Tensor, alpha: float, mu: float, l: float) -> None:
+    d = w.numel()
+    if yl.numel() != d or g.numel() != d:
+        raise ValueError("w, yl and g hold d floats each")
+    _check("nuq_momentum_step",
+           _lib.nuq_momentum_step(_ptr(w, torch.float32), _ptr(yl, torch.float32), _ptr(g, torch.float32), d,
+                                  float(alpha), float(mu), float(l), _stream()))
+
+
+def nuq_decode_momentum_step(messages: list[Message], d: int, bucket: int, s: int, sync_stride: int, scale: float,
+                             alpha: float, mu: float, l: float, w: torch.Tensor, yl: torch.Tensor) -> None:
+    K = len(messages)
+    arr = lambda ts: (ctypes.c_void_p * K)(*[_ptr(t) for t in ts])
+    if w.numel() != d or yl.numel() != d:
+        raise ValueError("w and yl hold d floats each")
+    _check("nuq_decode_momentum_step",
+           _lib.nuq_decode_momentum_step(K, arr([m.norms for m in messages]), arr([m.bit_off for m in messages]),
+                                         arr([m.words for m in messages]), arr([m.sync for m in messages]), d, bucket,
+                                         s, sync_stride, float(scale), float(alpha), float(mu), float(l),
+                                         _ptr(w, torch.float32), _ptr(yl, torch.float32), _stream()))
+
+
+def nuq_moments_accumulate(g: torch.Tensor, total: torch.Tensor, total_sq: torch.Tensor) -> None:
+    d = g.numel()
+    if total.numel() != d or total_sq.numel() != d:
+        raise ValueError("the moment sums hold d doubles each")
+    _check("nuq_moments_accumulate",
+           _lib.nuq_moments_accumulate(_ptr(g, torch.float32), _ptr(total, torch.float64),
+                                       _ptr(total_sq, torch.float64), d, _stream()))
+
+
+def nuq_normalized_variance(total: torch.Tensor, total_sq: torch.Tensor, M: int, workspace: torch.Tensor,
+                            out2: torch.Tensor) -> None:
+    d = total.numel()
+    if total_sq.numel() != d or out2.numel() != 2:
+        raise ValueError("two moment sums of d doubles and two doubles of output are needed")
+    _check("nuq_normalized_variance",
+           _lib.nuq_normalized_variance(_ptr(total, torch.float64), _ptr(total_sq, torch.float64), d, M,
+                                        _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                        _ptr(out2, torch.float64), _stream()))
 
 
 def nuq_last_error_flags() -> int:

@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <cmath>
 #include <type_traits>
 #include <vector>
 
@@ -12,6 +14,7 @@
 #include "nuq_encode_kernels.hpp"
 #include "nuq_fixed_kernels.hpp"
 #include "nuq_huffman_kernels.hpp"
+#include "nuq_sgd_kernels.hpp"
 #include "nuq_table_kernels.hpp"
 
 namespace {
@@ -362,23 +365,30 @@ HuffmanWorkspace carve_huffman(void *base, uint64_t nb)
 }
 
 // Workgroups of the persistent decode kernel that the current device holds at once (0 on error).
-uint32_t decode_resident_workgroups(bool table)
+// `variant` indexes kDecodeKernels.
+using DecodeKernel = void (*)(DecodeParams);
+constexpr DecodeKernel kDecodeKernels[] = {
+    k_decode_accumulate<false, kUpdateWrite>, k_decode_accumulate<false, kUpdateAdd>,
+    k_decode_accumulate<false, kUpdateMomentum>, k_decode_accumulate<true, kUpdateWrite>,
+    k_decode_accumulate<true, kUpdateAdd>,
+};
+
+uint32_t decode_resident_workgroups(uint32_t variant)
 {
-    static uint32_t cached[2][64] = {};
+    static uint32_t cached[5][64] = {};
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    if (variant >= 5u || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
         return 0;
-    if (!cached[table][dev]) {
+    if (!cached[variant][dev]) {
         int per_cu = 0, cus = 0;
-        const void *kern = table ? reinterpret_cast<const void *>(k_decode_accumulate<true>)
-                                 : reinterpret_cast<const void *>(k_decode_accumulate<false>);
+        const void *kern = reinterpret_cast<const void *>(kDecodeKernels[variant]);
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, (int)kDecodeWG, 0) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || per_cu < 1 ||
             cus < 1)
             return 0;
-        cached[table][dev] = (uint32_t)per_cu * (uint32_t)cus;
+        cached[variant][dev] = (uint32_t)per_cu * (uint32_t)cus;
     }
-    return cached[table][dev];
+    return cached[variant][dev];
 }
 
 }  // namespace
@@ -567,7 +577,8 @@ int nuq_quantize_encode_batch(uint32_t K, const float *const *v, const uint64_t 
 static int decode_accumulate_any(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
                                  const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
                                  uint32_t bucket, uint32_t s, uint32_t sync_stride, const float *levels, float scale,
-                                 int accumulate, float *out, nuq_stream_t stream)
+                                 int accumulate, float *out, nuq_stream_t stream,
+                                 const MomentumParams *momentum = nullptr)
 {
     if (K < 1 || K > NUQ_MAX_WORKERS || !norms || !bit_off || !words || !out || !valid_common(d, bucket, s) ||
         !valid_sync(sync_stride) || (levels && !valid_levels(levels, s)))
@@ -598,7 +609,16 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
     P.nsync = nsync;
     P.nseg = nsync + 1;
     P.scale = scale;
-    P.accumulate = accumulate;
+    if (momentum && levels)
+        return NUQ_EINVAL;
+    const uint32_t variant = (levels ? 3u : 0u) + (momentum ? (uint32_t)kUpdateMomentum
+                                                            : accumulate ? (uint32_t)kUpdateAdd : (uint32_t)kUpdateWrite);
+    if (momentum) {
+        P.yl = momentum->yl;
+        P.alpha = momentum->alpha;
+        P.la = momentum->l * momentum->alpha;
+        P.mu = momentum->mu;
+    }
     uint64_t ntiles;
     uint32_t max_streams;
     if (bucket <= kTileCoords) {
@@ -626,7 +646,7 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
     while ((2u << P.lanes_shift) * max_streams <= 64u)
         ++P.lanes_shift;
     P.stream_cap = kWordsPerLane << P.lanes_shift;
-    const uint32_t resident = decode_resident_workgroups(levels != nullptr);
+    const uint32_t resident = decode_resident_workgroups(variant);
     if (!resident)
         return NUQ_EHIP;
     // Every resident workgroup slot is used.  Workgroups walk tiles with stride `grid`, so the first
@@ -634,15 +654,10 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
     // CUs, whose parsing waves are the oldest on their SIMDs and run faster than the later ones.
     const uint32_t grid = P.ntiles < resident ? P.ntiles : resident;
     ScopedTiming timing(NUQ_T_DECODE, static_cast<hipStream_t>(stream));
-    if (levels) {
+    if (levels)
         for (uint32_t j = 0; j < s + 2u; ++j)
             P.lev[j] = levels[j];
-        hipLaunchKernelGGL(k_decode_accumulate<true>, dim3(grid), dim3(kDecodeWG), 0,
-                           static_cast<hipStream_t>(stream), P);
-    } else {
-        hipLaunchKernelGGL(k_decode_accumulate<false>, dim3(grid), dim3(kDecodeWG), 0,
-                           static_cast<hipStream_t>(stream), P);
-    }
+    hipLaunchKernelGGL(kDecodeKernels[variant], dim3(grid), dim3(kDecodeWG), 0, static_cast<hipStream_t>(stream), P);
     return check_launch();
 }
 
@@ -1085,6 +1100,75 @@ int nuq_average_levels(uint32_t K, const float *const *norms, const uint8_t *con
         hipLaunchKernelGGL(k_average_levels<4>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
     else
         hipLaunchKernelGGL(k_average_levels<1>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
+    return check_launch();
+}
+
+int nuq_momentum_step(float *w, float *yl, const float *g, uint64_t d, float alpha, float mu, float l,
+                      nuq_stream_t stream)
+{
+    if (!std::isfinite(alpha) || !std::isfinite(mu) || !std::isfinite(l) || mu < 0.0f || !(mu < 1.0f))
+        return NUQ_EINVAL;
+    if (d == 0)
+        return NUQ_OK;
+    if (!w || !yl || !g)
+        return NUQ_EINVAL;
+    const bool vec = ((reinterpret_cast<uintptr_t>(w) | reinterpret_cast<uintptr_t>(yl) |
+                       reinterpret_cast<uintptr_t>(g)) & 15u) == 0;
+    const uint64_t threads = vec ? (d + 3) / 4 : d, blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffull)
+        return NUQ_EINVAL;
+    const MomentumParams P{w, yl, g, d, (double)alpha, (double)mu, (double)l};
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (vec)
+        hipLaunchKernelGGL(k_momentum_step<true>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
+    else
+        hipLaunchKernelGGL(k_momentum_step<false>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
+    return check_launch();
+}
+
+int nuq_decode_momentum_step(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                             const uint32_t *const *words, const uint32_t *const *sync, uint64_t d, uint32_t bucket,
+                             uint32_t s, uint32_t sync_stride, float scale, float alpha, float mu, float l, float *w,
+                             float *yl, nuq_stream_t stream)
+{
+    if (!std::isfinite(alpha) || !std::isfinite(mu) || !std::isfinite(l) || mu < 0.0f || !(mu < 1.0f) || !yl)
+        return NUQ_EINVAL;
+    const MomentumParams M{w, yl, nullptr, d, (double)alpha, (double)mu, (double)l};
+    return decode_accumulate_any(K, norms, bit_off, words, sync, d, bucket, s, sync_stride, nullptr, scale, 0, w,
+                                 stream, &M);
+}
+
+int nuq_moments_accumulate(const float *g, double *sum, double *sumsq, uint64_t d, nuq_stream_t stream)
+{
+    if (d == 0)
+        return NUQ_OK;
+    if (!g || !sum || !sumsq)
+        return NUQ_EINVAL;
+    const bool vec = (reinterpret_cast<uintptr_t>(g) & 7u) == 0 &&
+                     ((reinterpret_cast<uintptr_t>(sum) | reinterpret_cast<uintptr_t>(sumsq)) & 15u) == 0;
+    const uint64_t threads = vec ? (d + 1) / 2 : d, blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffull)
+        return NUQ_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (vec)
+        hipLaunchKernelGGL(k_moments_accumulate<true>, dim3((uint32_t)blocks), dim3(256), 0, st, g, sum, sumsq, d);
+    else
+        hipLaunchKernelGGL(k_moments_accumulate<false>, dim3((uint32_t)blocks), dim3(256), 0, st, g, sum, sumsq, d);
+    return check_launch();
+}
+
+int nuq_normalized_variance(const double *sum, const double *sumsq, uint64_t d, uint64_t M, void *workspace,
+                            uint64_t workspace_bytes, double *out2, nuq_stream_t stream)
+{
+    static_assert(NUQ_VARIANCE_WORKSPACE_BYTES == kVarianceBlocks * 2u * sizeof(double), "workspace size");
+    if (M < 1 || !out2 || !workspace || workspace_bytes < NUQ_VARIANCE_WORKSPACE_BYTES ||
+        (reinterpret_cast<uintptr_t>(workspace) & 7u) != 0 || (d > 0 && (!sum || !sumsq)))
+        return NUQ_EINVAL;
+    double *partial = static_cast<double *>(workspace);
+    const uint32_t blocks = (uint32_t)std::min<uint64_t>(kVarianceBlocks, std::max<uint64_t>(1, (d + 255) / 256));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(k_variance_partials, dim3(blocks), dim3(256), 0, st, sum, sumsq, d, 1.0 / (double)M, partial);
+    hipLaunchKernelGGL(k_variance_finish, dim3(1), dim3(256), 0, st, partial, blocks, out2);
     return check_launch();
 }
 

@@ -20,6 +20,7 @@
 #pragma once
 #include "nuq_device.hpp"
 #include "nuq_encode_kernels.hpp"
+#include "nuq_sgd_kernels.hpp"
 
 namespace nuq {
 
@@ -54,9 +55,88 @@ struct DecodeParams {
     uint32_t lanes_shift;       // log2 of the lanes that copy one stream's words
     uint32_t stream_cap;        // LDS words reserved per stream = kWordsPerLane << lanes_shift
     float scale;
-    int accumulate;
+    float *yl;                  // kUpdateMomentum: y^l of the previous step, replaced by this step's
+    double alpha, la, mu;       // kUpdateMomentum: step size, l * step size, momentum parameter
     float lev[16];              // level-table variant: l_0 = 0 .. l_{s+1} = 1
 };
+
+// What the decoder (template parameter UPDATE) does with r = fp32(scale * sum over workers) of a coordinate:
+//   kUpdateWrite     out = r
+//   kUpdateAdd       out = out + r   (the aggregate step of Alg. 1 when out = w and scale = -alpha/K)
+//   kUpdateMomentum  (out, yl) <- momentum rule of Sec. 4.2 with g = r (out = w)
+constexpr int kUpdateWrite = 0, kUpdateAdd = 1, kUpdateMomentum = 2;
+
+// A full, 16-byte aligned tile: every thread handles kTileCoords/4/kDecodeWG float4 groups, two at a time, with the
+// loads of the old values issued before the LDS reads so that their latencies overlap.
+template <int UPDATE>
+__device__ __forceinline__ void apply_full_tile(const DecodeParams &P, double *tile, float *o, float *y, uint32_t tid)
+{
+    constexpr uint32_t kFull = kTileCoords / 4u / kDecodeWG;      // float4 groups per thread
+    const double sc = (double)P.scale;
+#pragma unroll
+    for (uint32_t r0 = 0; r0 < kFull; r0 += 2u) {
+        float4 w[2], yv[2];
+        double2 a[2], c[2];
+#pragma unroll
+        for (uint32_t r = 0; r < 2u; ++r) {
+            const uint32_t i = tid + (r0 + r) * kDecodeWG;
+            if constexpr (UPDATE != kUpdateWrite)
+                w[r] = reinterpret_cast<const float4 *>(o)[i];
+            if constexpr (UPDATE == kUpdateMomentum)
+                yv[r] = reinterpret_cast<const float4 *>(y)[i];
+        }
+#pragma unroll
+        for (uint32_t r = 0; r < 2u; ++r) {
+            double2 *src = reinterpret_cast<double2 *>(tile) + 2u * (tid + (r0 + r) * kDecodeWG);
+            a[r] = src[0];
+            c[r] = src[1];
+            src[0] = double2{0.0, 0.0};
+            src[1] = double2{0.0, 0.0};
+        }
+#pragma unroll
+        for (uint32_t r = 0; r < 2u; ++r) {
+            const uint32_t i = tid + (r0 + r) * kDecodeWG;
+            const float4 v{(float)(sc * a[r].x), (float)(sc * a[r].y), (float)(sc * c[r].x), (float)(sc * c[r].y)};
+            if constexpr (UPDATE == kUpdateWrite) {
+                reinterpret_cast<float4 *>(o)[i] = v;
+            } else if constexpr (UPDATE == kUpdateAdd) {
+                reinterpret_cast<float4 *>(o)[i] = float4{v.x + w[r].x, v.y + w[r].y, v.z + w[r].z, v.w + w[r].w};
+            } else {
+                momentum_one(w[r].x, yv[r].x, v.x, P.alpha, P.la, P.mu);
+                momentum_one(w[r].y, yv[r].y, v.y, P.alpha, P.la, P.mu);
+                momentum_one(w[r].z, yv[r].z, v.z, P.alpha, P.la, P.mu);
+                momentum_one(w[r].w, yv[r].w, v.w, P.alpha, P.la, P.mu);
+                reinterpret_cast<float4 *>(o)[i] = w[r];
+                reinterpret_cast<float4 *>(y)[i] = yv[r];
+            }
+        }
+    }
+}
+
+template <int UPDATE>
+__device__ __forceinline__ void apply4(const DecodeParams &P, float4 r, float4 *dst, float4 *ydst)
+{
+    if constexpr (UPDATE == kUpdateWrite) {
+        *dst = r;
+        return;
+    }
+    float4 w = *dst;
+    if constexpr (UPDATE == kUpdateAdd) {
+        w.x = r.x + w.x;
+        w.y = r.y + w.y;
+        w.z = r.z + w.z;
+        w.w = r.w + w.w;
+    } else {
+        float4 yv = *ydst;
+        momentum_one(w.x, yv.x, r.x, P.alpha, P.la, P.mu);
+        momentum_one(w.y, yv.y, r.y, P.alpha, P.la, P.mu);
+        momentum_one(w.z, yv.z, r.z, P.alpha, P.la, P.mu);
+        momentum_one(w.w, yv.w, r.w, P.alpha, P.la, P.mu);
+        *ydst = yv;
+    }
+    *dst = w;
+}
+
 
 // Branch-free decoder of Alg. 2 for values below 65536 on a 32-bit window (MSB first).
 // Code shapes: "0" -> 1;  "1x0" -> 2..3;  "1x 1y..y 0" -> 4..15 (group of x+1 bits);
@@ -392,7 +472,7 @@ __device__ __forceinline__ PackedPlan pack_plan(const UnitPlan &U)
     return Q;
 }
 
-template <bool kTable>
+template <bool kTable, int UPDATE>
 __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams P)
 {
     __shared__ __align__(16) double tile[kTileCoords];
@@ -735,62 +815,33 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             }
         }
 
-        // ---- scale, round to fp32, write; leave the tile zeroed
+        // ---- scale, round to fp32, apply to the output (write, add, or momentum rule); leave the tile zeroed
         {
             float *o = P.out + G.c_lo;
-            const double sc = (double)P.scale;
+            float *y = UPDATE == kUpdateMomentum ? P.yl + G.c_lo : o;      // (read only under kUpdateMomentum)
             const uint32_t span = G.span;
-            const bool vec = (reinterpret_cast<uintptr_t>(o) & 15u) == 0;
+            const bool vec = ((reinterpret_cast<uintptr_t>(o) | reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
             const uint32_t n4 = vec ? span >> 2 : 0u;
-            constexpr uint32_t kFull = kTileCoords / 4u / kDecodeWG;      // float4 stores per thread of a full tile
-            if (n4 == kTileCoords / 4u && !P.accumulate) {
-                // a full tile: LDS reads two at a time, so that their latencies overlap
-#pragma unroll
-                for (uint32_t r0 = 0; r0 < kFull; r0 += 2u) {
-                    double2 a[2], c[2];
-#pragma unroll
-                    for (uint32_t r = 0; r < 2u; ++r) {
-                        double2 *src = reinterpret_cast<double2 *>(tile) + 2u * (tid + (r0 + r) * kDecodeWG);
-                        a[r] = src[0];
-                        c[r] = src[1];
-                        src[0] = double2{0.0, 0.0};
-                        src[1] = double2{0.0, 0.0};
-                    }
-#pragma unroll
-                    for (uint32_t r = 0; r < 2u; ++r) {
-                        float4 v;
-                        v.x = (float)(sc * a[r].x);
-                        v.y = (float)(sc * a[r].y);
-                        v.z = (float)(sc * c[r].x);
-                        v.w = (float)(sc * c[r].y);
-                        reinterpret_cast<float4 *>(o)[tid + (r0 + r) * kDecodeWG] = v;
-                    }
+            if (n4 == kTileCoords / 4u) {
+                apply_full_tile<UPDATE>(P, tile, o, y, tid);
+            } else {
+                const double sc = (double)P.scale;
+                for (uint32_t i = tid; i < n4; i += kDecodeWG) {
+                    double2 *src = reinterpret_cast<double2 *>(tile) + 2u * i;
+                    const double2 a = src[0], c = src[1];
+                    src[0] = double2{0.0, 0.0};
+                    src[1] = double2{0.0, 0.0};
+                    const float4 r{(float)(sc * a.x), (float)(sc * a.y), (float)(sc * c.x), (float)(sc * c.y)};
+                    apply4<UPDATE>(P, r, reinterpret_cast<float4 *>(o) + i, reinterpret_cast<float4 *>(y) + i);
                 }
-            } else
-            for (uint32_t i = tid; i < n4; i += kDecodeWG) {
-                double2 *src = reinterpret_cast<double2 *>(tile) + 2u * i;
-                const double2 a = src[0], c = src[1];
-                src[0] = double2{0.0, 0.0};
-                src[1] = double2{0.0, 0.0};
-                float4 r;
-                r.x = (float)(sc * a.x);
-                r.y = (float)(sc * a.y);
-                r.z = (float)(sc * c.x);
-                r.w = (float)(sc * c.y);
-                float4 *dst = reinterpret_cast<float4 *>(o) + i;
-                if (P.accumulate) {
-                    const float4 old = *dst;
-                    r.x += old.x;
-                    r.y += old.y;
-                    r.z += old.z;
-                    r.w += old.w;
-                }
-                *dst = r;
             }
             for (uint32_t i = (n4 << 2) + tid; i < span; i += kDecodeWG) {      // (n4 = 0 without 16-byte alignment)
-                const float r = (float)(sc * tile[i]);
+                const float r = (float)((double)P.scale * tile[i]);
                 tile[i] = 0.0;
-                o[i] = P.accumulate ? o[i] + r : r;
+                if constexpr (UPDATE == kUpdateMomentum)
+                    momentum_one(o[i], y[i], r, P.alpha, P.la, P.mu);
+                else
+                    o[i] = UPDATE == kUpdateAdd ? o[i] + r : r;
             }
         }
         if (!has1)
