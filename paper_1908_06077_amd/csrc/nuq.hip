@@ -772,14 +772,31 @@ int nuq_unpack_accumulate_fixed(uint32_t K, const float *const *norms, const uin
     if (!wide) {
         hipLaunchKernelGGL(k_unpack_accumulate_fixed1, grid, dim3(256), 0, st, P);
     } else {
+        // Tables of code values in LDS when those of the buckets a workgroup (8192 coordinates) can touch fit in
+        // 16 KB beside the 33 KB output tile (three workgroups per CU at worst); else the arithmetic variant.
+        const uint64_t nb = nuq_num_buckets(d, bucket);
+        const bool tiled = 8192u % bucket == 0 || bucket % 8192u == 0;
+        const uint64_t tabs = std::min<uint64_t>(nb, tiled ? std::max(1u, 8192u / bucket) : 8192u / bucket + 2u);
+        const uint64_t lut_bytes = tabs * K * fixed_lut_entries(b) * sizeof(double);
+        const bool lut = lut_bytes <= 16384u;
+        P.lut_tabs = (uint32_t)tabs;
+        const uint32_t dyn = lut ? (uint32_t)lut_bytes : 0u;
+#define NUQ_LAUNCH_UNPACK(B)                                                                                   \
+    do {                                                                                                       \
+        if (lut)                                                                                               \
+            hipLaunchKernelGGL((k_unpack_accumulate_fixed32<B, true>), grid, dim3(256), dyn, st, P);           \
+        else                                                                                                   \
+            hipLaunchKernelGGL((k_unpack_accumulate_fixed32<B, false>), grid, dim3(256), 0, st, P);            \
+    } while (0)
         switch (b) {
-        case 3: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<3>, grid, dim3(256), 0, st, P); break;
-        case 4: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<4>, grid, dim3(256), 0, st, P); break;
-        case 5: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<5>, grid, dim3(256), 0, st, P); break;
-        case 6: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<6>, grid, dim3(256), 0, st, P); break;
-        case 7: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<7>, grid, dim3(256), 0, st, P); break;
-        default: hipLaunchKernelGGL(k_unpack_accumulate_fixed32<8>, grid, dim3(256), 0, st, P); break;
+        case 3: NUQ_LAUNCH_UNPACK(3); break;
+        case 4: NUQ_LAUNCH_UNPACK(4); break;
+        case 5: NUQ_LAUNCH_UNPACK(5); break;
+        case 6: NUQ_LAUNCH_UNPACK(6); break;
+        case 7: NUQ_LAUNCH_UNPACK(7); break;
+        default: NUQ_LAUNCH_UNPACK(8); break;
         }
+#undef NUQ_LAUNCH_UNPACK
     }
     return check_launch();
 }

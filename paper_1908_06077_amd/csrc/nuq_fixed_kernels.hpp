@@ -90,6 +90,7 @@ struct UnpackParams {
     uint32_t s;
     uint32_t b;
     uint32_t wpb;
+    uint32_t lut_tabs;          // table variant: buckets a workgroup can touch (tables per worker in LDS)
     float scale;
     int accumulate;
 };
@@ -101,12 +102,64 @@ struct UnpackParams {
 // Buckets that are multiples of 32 coordinates: a thread owns 32 consecutive coordinates, i.e. exactly B whole words
 // of every worker's field (one contiguous load per worker, coalesced over the wave), and the workgroup's 8192 results
 // go through LDS so that the stores are whole lines too.
+//
+// kLut: the value of every code, norm * sign * 2^(level - 1 - s) in fp64 (0 for level 0 and for codes that are not
+// valid), is tabulated in LDS once per (bucket the workgroup touches, worker); a code then costs a bit-field extract,
+// an LDS read and an fp64 add instead of the exponent arithmetic.  A table of 16 entries is 128 bytes = all 32 banks
+// once, so lanes that read one table never conflict whatever their codes.  Codes wider than 5 bits index 32 entries
+// by (sign, low four level bits): levels stop at 15.  `lut_tabs` tables per worker are laid out bucket-major.
+constexpr uint32_t fixed_lut_entries(uint32_t b) { return b <= 5u ? 1u << b : 32u; }
+
 template <int B>
+__device__ __forceinline__ uint32_t fixed_lut_index(uint32_t code)
+{
+    if constexpr (B <= 5)
+        return code;
+    else
+        return ((code >> (B - 1)) << 4) | (code & 15u);
+}
+
+// Whole words of codes that never straddle a word (B = 4, 8): true if some code has a level above s + 1 or is a
+// signed zero.  Per field: level + (2^(B-1) - 1) sets the top bit iff level >= 1; level + (2^(B-1) - 2 - s) sets it
+// iff level >= s + 2; neither sum leaves its field.
+template <int B>
+__device__ __forceinline__ bool fixed_word_invalid(uint32_t w, uint32_t s)
+{
+    static_assert(B == 4 || B == 8, "fields must tile the word");
+    constexpr uint32_t kOnes = B == 4 ? 0x11111111u : 0x01010101u;
+    constexpr uint32_t kTop = kOnes << (B - 1), kLevels = kTop - kOnes;
+    const uint32_t lv = w & kLevels;
+    const uint32_t nonzero = (lv + kLevels) & kTop;
+    const uint32_t above = (lv + ((1u << (B - 1)) - 2u - s) * kOnes) & kTop;
+    return (above | (w & kTop & ~nonzero)) != 0u;
+}
+
+template <int B, bool kLut>
 __global__ __launch_bounds__(256) void k_unpack_accumulate_fixed32(UnpackParams P)
 {
     __shared__ float tile[256 * 33];                          // a thread's 32 results in a row of 33: no bank conflicts
+    extern __shared__ __align__(128) double lut[];            // kLut: [lut_tabs][K][entries]
+    constexpr uint32_t kEntries = fixed_lut_entries(B);
+    constexpr uint32_t kLevelMask = (1u << (B - 1)) - 1u;
     const uint64_t chunk = (uint64_t)blockIdx.x * 256u + threadIdx.x;
     const uint64_t i0 = chunk * 32u;
+    const uint64_t wg0 = (uint64_t)blockIdx.x * 8192u;
+    const uint64_t bk_first = P.d <= 0xffffffffull ? (uint64_t)((uint32_t)wg0 / P.bucket) : wg0 / P.bucket;
+    if constexpr (kLut) {
+        const uint64_t nb = (P.d + P.bucket - 1) / P.bucket;
+        const uint32_t total = P.lut_tabs * P.K * kEntries;
+        for (uint32_t e = threadIdx.x; e < total; e += 256u) {
+            const uint32_t idx = e % kEntries, k = (e / kEntries) % P.K, tab = e / (kEntries * P.K);
+            const uint32_t level = B <= 5 ? idx & kLevelMask : idx & 15u, neg = B <= 5 ? idx >> (B - 1) : idx >> 4;
+            double val = 0.0;
+            if (bk_first + tab < nb && level >= 1u && level <= P.s + 1u) {
+                val = ldexp((double)P.norms[k][bk_first + tab], (int)level - 1 - (int)P.s);
+                val = neg ? -val : val;
+            }
+            lut[e] = val;
+        }
+        __syncthreads();
+    }
     double sum[32];
 #pragma unroll
     for (int c = 0; c < 32; ++c)
@@ -116,14 +169,21 @@ __global__ __launch_bounds__(256) void k_unpack_accumulate_fixed32(UnpackParams 
         const uint64_t bk = P.d <= 0xffffffffull ? (uint64_t)((uint32_t)i0 / P.bucket) : i0 / P.bucket;
         const uint32_t j0 = (uint32_t)(i0 - bk * P.bucket);
         const uint64_t word0 = bk * P.wpb + (uint64_t)(j0 / 32u) * B;
-        constexpr uint32_t kLevelMask = (1u << (B - 1)) - 1u;
+        const double *tab = lut + (uint32_t)(bk - bk_first) * P.K * kEntries;
         for (uint32_t k = 0; k < P.K; ++k) {
             const uint32_t *f = P.packed[k] + word0;
             uint32_t w[B];
 #pragma unroll
             for (int t = 0; t < B; ++t)
                 w[t] = f[t];
-            const double nrm = (double)P.norms[k][bk];
+            double nrm = 0.0;
+            if constexpr (!kLut)
+                nrm = (double)P.norms[k][bk];
+            if constexpr (kLut && 32 % B == 0) {
+#pragma unroll
+                for (int t = 0; t < B; ++t)
+                    bad |= fixed_word_invalid<B>(w[t], P.s);
+            }
 #pragma unroll
             for (int c = 0; c < 32; ++c) {
                 // code c occupies bits [c*B, c*B + B) of the B words, most significant bit first
@@ -133,11 +193,19 @@ __global__ __launch_bounds__(256) void k_unpack_accumulate_fixed32(UnpackParams 
                     code = (w[wi] >> (32 - off - B)) & ((1u << B) - 1u);
                 else
                     code = ((w[wi] << (off + B - 32)) | (w[wi + 1 < B ? wi + 1 : wi] >> (64 - off - B))) & ((1u << B) - 1u);
-                const uint32_t level = code & kLevelMask, neg = code >> (B - 1);
-                bad |= level > P.s + 1u || (level == 0u && neg);
-                if (level) {
-                    const double val = ldexp(nrm, (int)level - 1 - (int)P.s);
-                    sum[c] += neg ? -val : val;
+                if constexpr (kLut) {
+                    if constexpr (32 % B != 0) {
+                        const uint32_t level = code & kLevelMask;
+                        bad |= level > P.s + 1u || code == (1u << (B - 1));
+                    }
+                    sum[c] += tab[k * kEntries + fixed_lut_index<B>(code)];
+                } else {
+                    const uint32_t level = code & kLevelMask, neg = code >> (B - 1);
+                    bad |= level > P.s + 1u || (level == 0u && neg);
+                    if (level) {
+                        const double val = ldexp(nrm, (int)level - 1 - (int)P.s);
+                        sum[c] += neg ? -val : val;
+                    }
                 }
             }
         }
