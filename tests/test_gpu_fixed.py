@@ -32,6 +32,10 @@ CASES = [
     (66_000, 20000, 3, 7, 3, "edges"),
     (10_000, 2048, 14, 5, 1, "mixed"),
     (1, 8192, 3, 4, 1, "gauss"),
+    (20_000, 64, 3, 4, 8, "mixed"),          # many small buckets per workgroup: value tables too large, arithmetic route
+    (30_000, 96, 2, 3, 4, "mixed"),          # the same with buckets that do not tile a workgroup's 8192 coordinates
+    (50_000, 2016, 3, 5, 3, "mixed"),        # tables, workgroups starting inside a bucket
+    (90_000, 4096, 14, 8, 5, "mixed"),       # 32-entry tables indexed by (sign, level)
 ]
 
 
@@ -88,15 +92,29 @@ def check(norms_np, packed_np, d, n, s, b, scale, got, prior=None):
     assert np.all(diff <= 1e-6 * mag + 1e-45), float(np.max(diff / np.maximum(mag, 1e-300)))
 
 
-def test_malformed_codes_raise_the_flag(g):
+@pytest.mark.parametrize("b,s,nbuckets", [(4, 2, 1), (8, 2, 1), (8, 14, 1), (5, 2, 1), (3, 1, 1), (5, 2, 200), (4, 2, 300)])
+def test_malformed_codes_raise_the_flag(g, b, s, nbuckets):
+    # every route of the unpack kernel: value tables with the whole-word test (b = 4, 8) and the per-code test
+    # (b = 3, 5), and the arithmetic route (many buckets per workgroup); the top valid level must not raise it
     nuq = g.nuq
-    d, n, s, b = 64, 64, 2, 4
-    norms = [torch.ones(1, dtype=torch.float32, device=g.DEV)]
+    n = 64
+    d = n * nbuckets
+    wpb = n * b // 32
+    norms = [torch.ones(nbuckets, dtype=torch.float32, device=g.DEV)]
     out = torch.empty(d, dtype=torch.float32, device=g.DEV)
-    for word in (0x70000000, 0x80000000):       # level index 7 > s + 1; a signed zero
-        packed = [torch.tensor([word - (1 << 32) if word >> 31 else word] + [0] * 7, dtype=torch.int32, device=g.DEV)]
+    top = 32 - b                                  # shift of a field's first code
+    cases = [((s + 2) << top, True), (1 << 31, True), ((s + 1) << top, False), ((1 << 31) | ((s + 1) << top), False)]
+    if s + 2 >= 1 << (b - 1):
+        cases = cases[1:]                         # no level index above s + 1 fits the code
+    for word, bad in cases:
+        words = np.zeros(nbuckets * wpb, dtype=np.uint32)
+        words[(nbuckets - 1) * wpb] = word        # first code of the last bucket
+        packed = [torch.from_numpy(words.view(np.int32)).to(g.DEV)]
         nuq.nuq_unpack_accumulate_fixed(norms, packed, d, n, s, b, 1.0, False, out)
-        assert nuq.nuq_last_error_flags() == nuq.FLAG_MALFORMED
+        assert nuq.nuq_last_error_flags() == (nuq.FLAG_MALFORMED if bad else 0), (hex(word), bad)
+        if not bad:
+            want = 1.0 * (-1.0 if word >> 31 else 1.0)          # norm * sign * 2^0
+            assert out[(nbuckets - 1) * n].item() == want and out.abs().sum().item() == 1.0
 
 
 def test_four_bit_at_benchmark_size(g):
