@@ -291,7 +291,7 @@ def main():
                      "traffic": None if lev is not None or fb or huff else measured_traffic("k_encode", args.config, S),
                      "bytes_per_launch": round(enc_launch_bytes), "launch_ms": round(enc_kernel_ms, 5),
                      "launches": len(enc_ms)},
-        "roofline_decode": {"kernel": ("k_huffman_decode_tile, all K messages in one launch (k_average_levels follows)"
+        "roofline_decode": {"kernel": ("k_huffman_decode_direct, all K messages in one launch (k_average_levels follows)"
                                        if huff else
                                        "k_unpack_accumulate_fixed (unpack + average of K messages)" if fb else
                                        "k_decode_accumulate (DECODE + average of K messages)"),

@@ -1057,12 +1057,15 @@ int nuq_decode_huffman_batch(uint32_t K, const uint64_t *const *bit_off, const u
         return NUQ_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     ScopedTiming timing(NUQ_T_DECODE, st);
-    bool direct = nsync && bucket % 16u == 0;
+    // one staging row per thread: at most 1024 / 16 + 9 words
+    const size_t direct_lds = (size_t)kHuffmanDirectWG * huffman_stage_stride(sync_stride) * 4u;
+    bool direct = nsync && bucket % 16u == 0 && direct_lds <= 40u * 1024u;
     for (uint32_t k = 0; k < K && direct; ++k)
         direct = (reinterpret_cast<uintptr_t>(q[k]) & 15u) == 0;
     if (direct) {
-        const size_t lds_bytes = 64u * huffman_stage_stride(sync_stride) * 4u;
-        hipLaunchKernelGGL(k_huffman_decode_direct, dim3((uint32_t)blocks, K), dim3(64), lds_bytes, st, P, H);
+        const uint64_t wgs = (units + kHuffmanDirectWG - 1) / kHuffmanDirectWG;
+        hipLaunchKernelGGL(k_huffman_decode_direct, dim3((uint32_t)wgs, K), dim3(kHuffmanDirectWG), direct_lds, st, P,
+                           H);
     } else if (nsync) {
         const size_t lds_bytes = 64u * (sync_stride / 4u + 1u + huffman_stage_stride(sync_stride)) * 4u;
         if (lds_bytes > 48 * 1024 &&

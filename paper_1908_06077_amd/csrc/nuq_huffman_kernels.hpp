@@ -495,39 +495,139 @@ __global__ __launch_bounds__(64) void k_huffman_decode_tile(HuffmanDecodeParams 
 
 // The decoder for the usual geometry (buckets and byte arrays that are multiples of 16: every unit starts on a 16-byte
 // boundary): as k_huffman_decode_tile, but a lane collects 16 bytes in registers and stores them itself.  Sixty-four
-// 16-byte stores 256 bytes apart are few enough transactions, and without the tile the wave needs 6.4 KB of LDS
-// instead of 23, so four times as many waves hide each other's latencies (the parse is one dependent chain per lane).
-__global__ __launch_bounds__(64) void k_huffman_decode_direct(HuffmanDecodeParams P, HuffmanCode H)
+// 16-byte stores 256 bytes apart are few enough transactions, and without the tile a wave needs 6.4 KB of LDS
+// instead of 23, so several times as many waves hide each other's latencies (the parse is one dependent chain per
+// lane).
+//
+// The parse is bound by instruction issue, so it takes several symbols per step: `multi` maps the next eight bits of
+// the string to the symbols that end inside them (codeword plus sign bit; up to eight level-0 symbols), their
+// count and their total length.  An entry with no symbol (a codeword of eight bits or more, or none) falls back to
+// one symbol from the 32-bit window.  The bits after a unit's end are the next unit's (or padding that reads as
+// level-0 symbols), so the table is used only while at least eight symbols of the unit remain.
+constexpr uint32_t kHuffmanDirectWG = 256;
+
+struct MultiEntry {
+    uint32_t bytes_lo, bytes_hi;   // level|sign bytes of the symbols, first symbol in the lowest byte, rest zero
+    uint32_t count;                // symbols, 0..8
+    uint32_t bits;                 // their total length, 0..8
+};
+
+// A lane's output buffer: 16 bytes being filled (lo, hi) and up to NB - 1 full 16-byte blocks waiting (the newest
+// last), so that 16 NB consecutive bytes leave in NB back-to-back stores: a lane's blocks of one 128-byte line then
+// reach the L2 together instead of at eight different times.  All indices are compile-time: the blocks stay in
+// registers.
+template <int NB>
+struct ByteSink {
+    uint64_t lo = 0, hi = 0;
+    uint4 wait[NB - 1] = {};
+    uint32_t fill = 0, pending = 0, stored = 0;
+
+    // Appends the `count` low bytes of `nb` (its other bytes are zero).
+    __device__ __forceinline__ void append(uint64_t nb, uint32_t count, uint8_t *out)
+    {
+        const uint32_t sh = (fill & 7u) * 8u;
+        const uint64_t x = nb << sh;
+        const uint64_t y = sh ? nb >> (64u - sh) : 0ull;
+        uint64_t carry = 0;
+        if (fill < 8u) {
+            lo |= x;
+            hi |= y;
+        } else {
+            hi |= x;
+            carry = y;
+        }
+        fill += count;
+        if (fill >= 16u) {
+            const uint4 blk{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+            if (pending == NB - 1) {
+                uint4 *dst = reinterpret_cast<uint4 *>(out + stored);
+#pragma unroll
+                for (int j = 0; j < NB - 1; ++j)
+                    dst[j] = wait[j];
+                dst[NB - 1] = blk;
+                stored += 16u * NB;
+                pending = 0;
+            } else {
+#pragma unroll
+                for (int j = 0; j < NB - 2; ++j)
+                    wait[j] = wait[j + 1];
+                wait[NB - 2] = blk;
+                ++pending;
+            }
+            lo = carry;
+            hi = 0;
+            fill -= 16u;
+        }
+    }
+
+    // Writes what is left: the waiting blocks (the last `pending` entries of wait), then the bytes of the partly
+    // filled one.
+    __device__ __forceinline__ void flush(uint8_t *out)
+    {
+        uint4 *dst = reinterpret_cast<uint4 *>(out + stored);
+#pragma unroll
+        for (int j = 0; j < NB - 1; ++j) {
+            const int first = NB - 1 - (int)pending;             // wait[first..NB-2] are valid
+            if (j >= first)
+                dst[j - first] = wait[j];
+        }
+        stored += 16u * pending;
+        pending = 0;
+        for (uint32_t i = 0; i < fill; ++i)
+            out[stored + i] = (uint8_t)((i < 8u ? lo >> (8u * i) : hi >> (8u * (i - 8u))) & 0xffu);
+    }
+};
+
+__global__ __launch_bounds__(kHuffmanDirectWG) void k_huffman_decode_direct(HuffmanDecodeParams P, HuffmanCode H)
 {
-    extern __shared__ __align__(16) uint32_t stage_rows[];      // 64 staging rows
+    extern __shared__ __align__(16) uint32_t stage_rows[];      // one staging row per thread
+    __shared__ __align__(16) MultiEntry multi[256];
     __shared__ uint8_t lut8[256];
     __shared__ uint32_t first[16], count[16], offset[16], sorted[16];
-    const uint32_t lane = threadIdx.x;
+    const uint32_t tid = threadIdx.x;
     const uint32_t S = 1u << P.sync_shift;
-    if (lane < 16u) {
-        first[lane] = H.first[lane];
-        count[lane] = H.count[lane];
-        offset[lane] = H.offset[lane];
-        sorted[lane] = H.sorted[lane];
+    if (tid < 16u) {
+        first[tid] = H.first[tid];
+        count[tid] = H.count[tid];
+        offset[tid] = H.offset[tid];
+        sorted[tid] = H.sorted[tid];
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-    __builtin_amdgcn_wave_barrier();
-    for (uint32_t p = lane; p < 256u; p += 64u) {
-        uint32_t entry = 0;
-        for (uint32_t L = 1; L <= 8u && L <= H.maxlen; ++L) {
-            const uint32_t idx = (p >> (8u - L)) - first[L];
-            if (idx < count[L]) {
-                entry = sorted[offset[L] + idx] | (L << 4);
-                break;
+    __syncthreads();
+    {
+        // entry `tid` of both tables: canonical decoding of the eight bits, symbol after symbol
+        const uint32_t p = tid;
+        uint32_t used = 0, n = 0, lo = 0, hi = 0, single = 0;
+        for (;;) {
+            uint32_t entry = 0;
+            for (uint32_t L = 1; used + L <= 8u && L <= H.maxlen; ++L) {
+                const uint32_t idx = ((p >> (8u - used - L)) & ((1u << L) - 1u)) - first[L];
+                if (idx < count[L]) {
+                    entry = sorted[offset[L] + idx] | (L << 4);
+                    break;
+                }
             }
+            if (!used)
+                single = entry;                                  // the first codeword alone, sign not needed here
+            const uint32_t sym = entry & 15u, L = entry >> 4;
+            const uint32_t bits = L + (sym ? 1u : 0u);
+            if (!L || used + bits > 8u)
+                break;
+            const uint32_t neg = sym ? (p >> (8u - used - bits)) & 1u : 0u;
+            const uint32_t byte = sym | (neg << 7);
+            if (n < 4u)
+                lo |= byte << (8u * n);
+            else
+                hi |= byte << (8u * (n - 4u));
+            used += bits;
+            ++n;
         }
-        lut8[p] = (uint8_t)entry;
+        multi[p] = MultiEntry{lo, hi, n, used};
+        lut8[p] = (uint8_t)single;
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-    __builtin_amdgcn_wave_barrier();
+    __syncthreads();
 
     const HuffmanStream &W = P.w[blockIdx.y];
-    const uint64_t u = (uint64_t)blockIdx.x * 64u + lane;
+    const uint64_t u = (uint64_t)blockIdx.x * kHuffmanDirectWG + tid;
     if (u >= P.nb * P.nseg)
         return;
     const uint64_t b = u / P.nseg;
@@ -538,7 +638,7 @@ __global__ __launch_bounds__(64) void k_huffman_decode_direct(HuffmanDecodeParam
         return;
     const uint32_t n = min(nbk, c_lo + S) - c_lo;
     const uint32_t cap = huffman_stage_cap(S), stride = huffman_stage_stride(S);
-    uint32_t *srow = stage_rows + lane * stride;
+    uint32_t *srow = stage_rows + tid * stride;
     const uint64_t start = (W.bit_off[b] + 31ull) & ~31ull, end = W.bit_off[b + 1];
     const uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
     const uint32_t *sg = W.sync + b * P.nsync;
@@ -562,33 +662,38 @@ __global__ __launch_bounds__(64) void k_huffman_decode_direct(HuffmanDecodeParam
         const uint32_t bit0 = lo & 31u;
         uint32_t p31 = bit0 + 31u, q = p31 >> 5;
         uint32_t hw = srow[q], lw = srow[q + 1u], nx = srow[q + 2u];
-        uint32_t four = 0, x0 = 0, x1 = 0, x2 = 0, x3 = 0;
-        for (uint32_t i = 0; i < n; ++i) {
+        ByteSink<4> sink;
+        uint32_t i = 0;
+        while (i < n) {
             const uint32_t w = __builtin_amdgcn_alignbit(hw, lw, ~p31);
-            uint32_t entry = lut8[w >> 24];
-            if (!entry) {                                       // a codeword of nine bits or more (rare), or none
-                for (uint32_t L = 9; L <= H.maxlen; ++L) {
-                    const uint32_t idx = (w >> (32u - L)) - first[L];
-                    if (idx < count[L]) {
-                        entry = sorted[offset[L] + idx] | (L << 4);
-                        break;
+            uint64_t nb;
+            uint32_t cnt, bits;
+            const MultiEntry e = multi[w >> 24];
+            if (i + 8u <= n && e.count) {
+                nb = ((uint64_t)e.bytes_hi << 32) | e.bytes_lo;
+                cnt = e.count;
+                bits = e.bits;
+            } else {
+                uint32_t entry = lut8[w >> 24];
+                if (!entry) {                                   // a codeword of nine bits or more (rare), or none
+                    for (uint32_t L = 9; L <= H.maxlen; ++L) {
+                        const uint32_t idx = (w >> (32u - L)) - first[L];
+                        if (idx < count[L]) {
+                            entry = sorted[offset[L] + idx] | (L << 4);
+                            break;
+                        }
                     }
                 }
+                const uint32_t sym = entry & 15u, L = entry >> 4;
+                bad |= !L;
+                const uint32_t neg = sym ? (w >> (31u - L)) & 1u : 0u;
+                nb = sym | (neg << 7);
+                cnt = 1u;
+                bits = L + (sym ? 1u : 0u);
             }
-            const uint32_t sym = entry & 15u, L = entry >> 4;
-            bad |= !L;
-            const uint32_t neg = sym ? (w >> (31u - L)) & 1u : 0u;
-            four |= (sym | (neg << 7)) << (8u * (i & 3u));
-            if ((i & 3u) == 3u) {
-                x0 = x1;
-                x1 = x2;
-                x2 = x3;
-                x3 = four;
-                four = 0;
-                if ((i & 15u) == 15u)
-                    *reinterpret_cast<uint4 *>(out + (i - 15u)) = uint4{x0, x1, x2, x3};
-            }
-            p31 += L + (sym ? 1u : 0u);
+            sink.append(nb, cnt, out);
+            i += cnt;
+            p31 += bits;
             const uint32_t qn = p31 >> 5;
             const bool moved = qn != q;
             hw = moved ? lw : hw;
@@ -596,15 +701,7 @@ __global__ __launch_bounds__(64) void k_huffman_decode_direct(HuffmanDecodeParam
             q = qn;
             nx = srow[min(qn + 2u, stride - 1u)];
         }
-        // what is left of a unit that is no multiple of 16 (the vector's last bucket): whole words, then bytes
-        const uint32_t done = n & ~15u, wleft = (n & 15u) >> 2;
-        const uint32_t xs[4] = {x0, x1, x2, x3};
-#pragma unroll
-        for (uint32_t j = 0; j < 3u; ++j)
-            if (j < wleft)
-                reinterpret_cast<uint32_t *>(out + done)[j] = wleft == 1u ? xs[3] : wleft == 2u ? xs[2 + j] : xs[1 + j];
-        for (uint32_t c = 0; c < (n & 3u); ++c)
-            out[done + 4u * wleft + c] = (uint8_t)(four >> (8u * c));
+        sink.flush(out);       // (a unit that is no multiple of 64: S = 32, or the vector's last bucket)
         bad |= lo - bit0 + (p31 - 31u) != hi;
     } else if (!bad) {                                          // a unit too long for its staging row
         WalkWords gw{W.words + (start >> 5)};
