@@ -117,22 +117,54 @@ __host__ __device__ inline uint32_t huffman_lds_words(uint32_t rows, uint32_t te
     return w + 64u;
 }
 
+// What a level|sign byte sends: bits = codeword of min(byte & 0x7f, 15), then the sign bit when the level is not zero;
+// entry = length << 24 | bits.  256 entries, built once per workgroup (the codeword tables are kernel arguments: a
+// lookup by a per-lane index there is a memory access; this table is an LDS read).
+template <uint32_t WG>
+__device__ __forceinline__ void huffman_byte_table(const HuffmanCode &H, uint32_t *enc)
+{
+    for (uint32_t p = threadIdx.x; p < 256u; p += WG) {
+        const uint32_t level = min(p & 0x7fu, 15u);
+        uint32_t n = H.len[level], v = H.code[level];
+        if (level) {
+            v = (v << 1) | (p >> 7);
+            ++n;
+        }
+        enc[p] = (n << 24) | v;
+    }
+}
+
 // The bucket's bit string from its level|sign bytes in LDS (qb32) into the zeroed LDS words `field`, sync offsets
 // into sync_l; returns the bucket's bit length to every thread.  Each thread codes a contiguous chunk of rows * 4
-// coordinates: codewords are shifted into a 64-bit register and leave it 32 bits at a time, OR-ed into the field
-// (a chunk's first and last words are shared with its neighbours).
+// coordinates: codewords (looked up by byte in `enc`) are shifted into a 64-bit register and leave it 32 bits at a
+// time, OR-ed into the field (a chunk's first and last words are shared with its neighbours).
 template <int TEAM>
-__device__ __forceinline__ uint32_t huffman_from_lds(const EncodeParams &P, const HuffmanCode &H, const uint32_t *qb32,
+__device__ __forceinline__ uint32_t huffman_from_lds(const EncodeParams &P, const uint32_t *enc, const uint32_t *qb32,
                                                      uint32_t *field, uint32_t *sync_l, uint32_t *scratch,
                                                      uint32_t nbk, uint32_t tid)
 {
-    const uint8_t *qbytes = reinterpret_cast<const uint8_t *>(qb32);
     const uint32_t per = P.rows * 4u;
     const uint32_t c0 = min(tid * per, nbk), c1 = min(c0 + per, nbk);
+    const uint32_t *qw = qb32 + (c0 >> 2);              // c0 is a multiple of four, or nbk (then the chunk is empty)
+    const uint32_t nfull = (c1 - c0) >> 2, ntail = (c1 - c0) & 3u;
     uint32_t bits = 0;
-    for (uint32_t c = c0; c < c1; ++c) {
-        const uint32_t level = min((uint32_t)qbytes[c] & 0x7fu, 15u);
-        bits += H.len[level] + (level ? 1u : 0u);
+    // Four level-0 coordinates in a word (three words in four on sparse gradients) are coded in one go when their
+    // codewords fit the register's spare 16 bits.
+    const uint32_t e0 = enc[0], len0 = e0 >> 24, code0 = e0 & 0xffffffu;
+    const bool quad = len0 <= 4u;
+    const uint32_t code0x4 = quad ? ((code0 << (3u * len0)) | (code0 << (2u * len0)) | (code0 << len0) | code0) : 0u;
+    for (uint32_t i = 0; i < nfull; ++i) {
+        const uint32_t w = qw[i];
+        if (w == 0u)
+            bits += 4u * len0;
+        else
+            bits += (enc[w & 0xffu] >> 24) + (enc[(w >> 8) & 0xffu] >> 24) + (enc[(w >> 16) & 0xffu] >> 24) +
+                    (enc[w >> 24] >> 24);
+    }
+    if (ntail) {
+        const uint32_t w = qw[nfull];
+        for (uint32_t j = 0; j < ntail; ++j)
+            bits += enc[(w >> (8u * j)) & 0xffu] >> 24;
     }
     uint32_t total;
     uint32_t pos = team_exclusive_sum<TEAM>(bits, scratch, total);
@@ -147,23 +179,37 @@ __device__ __forceinline__ uint32_t huffman_from_lds(const EncodeParams &P, cons
         uint32_t wi = pos >> 5, fill = pos & 31u;
         uint64_t acc = 0;
         const uint32_t smask = P.sync_shift ? (1u << P.sync_shift) - 1u : 0u;
-        for (uint32_t c = c0; c < c1; ++c) {
-            if (P.sync_shift && c && (c & smask) == 0u)
-                sync_l[(c >> P.sync_shift) - 1u] = pos;
-            const uint32_t byte = qbytes[c], level = min(byte & 0x7fu, 15u);
-            uint32_t n = H.len[level];
-            uint32_t v = H.code[level];
-            if (level) {
-                v = (v << 1) | (byte >> 7);
-                ++n;
-            }
-            acc = (acc << n) | v;                   // n <= 16: at most 31 + 16 bits are pending
+        auto push = [&](uint32_t v, uint32_t n) {       // n <= 16: at most 31 + 16 bits are pending
+            acc = (acc << n) | v;
             fill += n;
             pos += n;
             if (fill >= 32u) {
                 fill -= 32u;
                 atomicOr(&field[wi++], (uint32_t)(acc >> fill));
                 acc &= (1ull << fill) - 1ull;
+            }
+        };
+        auto put = [&](uint32_t byte) {
+            const uint32_t e = enc[byte];
+            push(e & 0xffffffu, e >> 24);
+        };
+        for (uint32_t i = 0; i <= nfull; ++i) {
+            if (i == nfull && !ntail)
+                break;
+            // a sync boundary is a multiple of 32 coordinates, so only a word's first coordinate can be one
+            const uint32_t w = qw[i], c = c0 + 4u * i;
+            if (P.sync_shift && c && (c & smask) == 0u)
+                sync_l[(c >> P.sync_shift) - 1u] = pos;
+            if (i == nfull) {
+                for (uint32_t j = 0; j < ntail; ++j)
+                    put((w >> (8u * j)) & 0xffu);
+            } else if (w == 0u && quad) {
+                push(code0x4, 4u * len0);
+            } else {
+                put(w & 0xffu);
+                put((w >> 8) & 0xffu);
+                put((w >> 16) & 0xffu);
+                put(w >> 24);
             }
         }
         if (fill)
@@ -191,9 +237,11 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_huffman_fused(EncodePar
     const bool active = b < P.nb;
     const uint64_t base = active ? b * P.bucket : 0;
     const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
+    __shared__ uint32_t enc[256];
+    huffman_byte_table<TeamGeom<TEAM>::kWG>(H, enc);
     front_quantize_to_lds<TEAM, VPT>(P, W, b, active, base, nbk, tid, qb32, scratch);
     __syncthreads();
-    const uint32_t total = huffman_from_lds<TEAM>(P, H, qb32, field, sync_l, scratch, nbk, tid);
+    const uint32_t total = huffman_from_lds<TEAM>(P, enc, qb32, field, sync_l, scratch, nbk, tid);
     const uint32_t nwords = (total + 31u) >> 5;
     team_barrier<TEAM>();
     if (active) {
@@ -224,10 +272,12 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_huffman_emit(EncodePara
     const bool active = b < P.nb;
     const uint64_t base = active ? b * P.bucket : 0;
     const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
+    __shared__ uint32_t enc[256];
+    huffman_byte_table<TeamGeom<TEAM>::kWG>(H, enc);
     front_bytes_to_lds<TEAM>(P, W, base, nbk, tid, qb32);
     __syncthreads();
 
-    const uint32_t total = huffman_from_lds<TEAM>(P, H, qb32, field, sync_l, scratch, nbk, tid);
+    const uint32_t total = huffman_from_lds<TEAM>(P, enc, qb32, field, sync_l, scratch, nbk, tid);
     const uint32_t nwords = (total + 31u) >> 5;
     team_barrier<TEAM>();
     if (active) {
