@@ -62,6 +62,10 @@ def parse_args():
                     help="also time PyTorch's own sum, copy and fill over a tensor of the step's input size and add "
                          "them to the line as `reference` (what library streaming kernels reach on this GPU: context "
                          "for the roofline fractions, not a target)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time replays of it (the step's launches without the "
+                         "host's launch gaps); the per-kernel HIP-event brackets then come from eager steps after the "
+                         "timed region, since events cannot be read back from inside a graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-worker-calls", action="store_true",
                     help="encode with K nuq_quantize_encode calls instead of one nuq_quantize_encode_batch")
@@ -202,13 +206,33 @@ def main():
     assert nuq.nuq_last_error_flags() == 0, "device error flags raised during warmup"
 
     # the timed region: K steps, with the library's per-launch HIP-event brackets (on its launch stream) switched on
-    nuq.nuq_timing_begin(min(4096, args.steps * (4 * K + 2)))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        nuq.nuq_timing_begin(min(4096, args.steps * (4 * K + 2)))
+        for i in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+    else:
+        nuq.nuq_timing_begin(min(4096, args.steps * (4 * K + 2)))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     launches = nuq.nuq_timing_collect()
     assert nuq.nuq_last_error_flags() == 0, "device error flags raised during the timed region"
 
@@ -303,6 +327,8 @@ def main():
                             "launches": len(dec_ms)},
     }
 
+    if args.graph:
+        result["config"]["launch"] = "one HIP graph replay per step; kernel brackets from eager steps after the timed region"
     if upd != "none":
         result["config"]["workload"] += ", parameter update: %s" % (
             "plain step inside the decoder" if upd == "sgd" else

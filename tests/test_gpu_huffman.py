@@ -116,6 +116,43 @@ def test_histogram_code_message_decode_and_average(g, d, n, s, S, K, kind):
     assert np.all(diff <= 1e-6 * mag * scale32 + 1e-45)
 
 
+@pytest.mark.parametrize("s,n,S,hist", [
+    (3, 8192, 256, [1, 10, 100, 1000, 10000]),                 # level 0 has the longest codeword: no four-at-a-time
+    (3, 512, 128, [5, 4, 3, 2, 1]),                            # codeword of level 0 two bits long
+    (14, 2048, 256, [2 ** j for j in range(16)]),              # codewords up to 15 bits, frequent levels short
+    (14, 4096, 64, [2 ** (15 - j) for j in range(16)]),        # codewords up to 15 bits on levels that do occur
+    (7, 1536, 512, [1] * 9),                                   # all codewords 3 or 4 bits
+])
+def test_codes_that_do_not_fit_the_data(g, s, n, S, hist):
+    """Level bytes drawn uniformly over all levels and signs, coded with lengths built from an unrelated histogram:
+    long codewords for frequent levels, codeword plus sign beyond eight bits, no short level-0 codeword."""
+    nuq = g.nuq
+    d = 5 * n + n // 2 + 16
+    rng = np.random.default_rng(s * 1000 + n)
+    level = rng.integers(0, s + 2, size=d).astype(np.uint8)
+    level[rng.random(d) < 0.3] = 0
+    q_np = (level | ((rng.random(d) < 0.5) & (level > 0)).astype(np.uint8) << 7).astype(np.uint8)
+    lengths = nuq.nuq_huffman_lengths(hist, s)
+    assert lengths == [int(x) for x in oracle.huffman_lengths(np.array(hist, dtype=np.uint64), s)]
+    B, nsync = nuq.nuq_num_buckets(d, n), nuq.nuq_num_sync(n, S)
+    q = torch.from_numpy(q_np).to(g.DEV)
+    bit_off = torch.full((B + 1,), -1, dtype=torch.int64, device=g.DEV)
+    words = torch.zeros(nuq.nuq_huffman_max_words(d, n), dtype=torch.int32, device=g.DEV)
+    sync = torch.full((max(1, B * nsync),), 0x55555555, dtype=torch.int32, device=g.DEV)
+    ws = torch.empty(nuq.nuq_encode_huffman_workspace_bytes(d, n), dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_encode_huffman(q, n, s, S, lengths, bit_off, words, sync, ws)
+    assert nuq.nuq_last_error_flags() == 0
+    bo, w_ref, sync_ref = oracle.encode_huffman(q_np, n, s, lengths, S)
+    np.testing.assert_array_equal(g.u64(bit_off), bo)
+    np.testing.assert_array_equal(g.u32(words)[: w_ref.size], w_ref)
+    np.testing.assert_array_equal(g.u32(sync)[: sync_ref.size], sync_ref)
+    back = torch.full((d,), 0x7F, dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_decode_huffman(bit_off, words, sync, d, n, s, S, lengths, back)
+    assert nuq.nuq_last_error_flags() == 0
+    np.testing.assert_array_equal(back.cpu().numpy(), q_np)
+    np.testing.assert_array_equal(oracle.decode_huffman(bo, w_ref, d, n, s, lengths), q_np)
+
+
 def test_malformed_messages_raise_the_flag(g):
     nuq = g.nuq
     d, n, s, S = 4096, 1024, 3, 256
