@@ -109,7 +109,7 @@ def batched_encode(vs, n, s, seeds, S):
     return msgs
 
 
-def check_bucket_run(vs, msgs, out, n, s, seeds, S, scale, b_lo, b_hi):
+def check_bucket_run(vs, msgs, out, n, s, seeds, S, scale, b_lo, b_hi, prior=None):
     """Buckets [b_lo, b_hi) of a large problem: every worker's message pieces bit-exact against the oracle run
     on just those buckets (fed the GPU's norms), norms and the decoded average of the K workers to the bars."""
     d = vs[0].numel()
@@ -130,4 +130,7 @@ def check_bucket_run(vs, msgs, out, n, s, seeds, S, scale, b_lo, b_hi):
         if sync.size:
             np.testing.assert_array_equal(u32(m.sync[b_lo * nsync: b_hi * nsync]), sync)
         parts.append((norms, bo, words))
-    check_average(parts, c_hi - c_lo, n, s, scale, out[c_lo:c_hi].cpu().numpy())
+    if out is not None:
+        check_average(parts, c_hi - c_lo, n, s, scale, out[c_lo:c_hi].cpu().numpy(),
+                      prior=None if prior is None else prior[c_lo:c_hi].cpu().numpy().astype(np.float64))
+    return parts

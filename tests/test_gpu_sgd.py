@@ -196,6 +196,46 @@ def test_decode_momentum_step_equals_the_two_calls(g, d, n, S, shift):
     assert not torch.equal(w1, w0.to(g.DEV)[shift:]) or d == 0
 
 
+def test_updates_at_benchmark_size(g):
+    """Config 3 at full size, launched as bench.py --update launches it: one step of the plain rule and one of the
+    momentum rule inside the decoder, compared on sampled runs of buckets that the oracle computes one by one."""
+    import workloads
+    nuq = g.nuq
+    wl = workloads.workload(3)
+    n, s, K, d, S = wl.bucket, wl.s, wl.K, wl.d, 256
+    B = nuq.nuq_num_buckets(d, n)
+    alpha, mu, l = 0.1, 0.9, 1.0
+    vs = [workloads.generate(wl, k, g.DEV) for k in range(K)]
+    gen = torch.Generator(device=g.DEV).manual_seed(5)
+    w0 = torch.randn(d, device=g.DEV, generator=gen) * 0.05
+    rng = np.random.default_rng(33)
+    runs = sorted({0, B - 3} | {int(x) for x in rng.integers(0, B - 3, size=10)})
+    for kind in ("plain", "momentum"):
+        w = w0.clone()
+        opt = _sgd().DataParallelSGD(w, K, alpha, n, s, sync_stride=S, mu=mu if kind == "momentum" else 0.0, l=l,
+                                     seed=1234)
+        seeds = [oracle.step_seed(1234, 0, K, k) for k in range(K)]
+        opt.step(vs)
+        assert nuq.nuq_last_error_flags() == 0
+        for b_lo in runs:
+            c_lo, c_hi = b_lo * n, min(d, (b_lo + 3) * n)
+            if kind == "plain":
+                g.check_bucket_run(vs, opt.buffers.messages, w, n, s, seeds, S, -alpha / K, b_lo, b_lo + 3, prior=w0)
+                continue
+            parts = g.check_bucket_run(vs, opt.buffers.messages, None, n, s, seeds, S, 1.0 / K, b_lo, b_lo + 3)
+            avg = oracle.decode_average([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts],
+                                        c_hi - c_lo, n, s, float(np.float32(1.0 / K))).astype(np.float32)
+            ow = w0[c_lo:c_hi].cpu().numpy()
+            w64, yl64 = oracle.momentum_step(ow, ow, avg, alpha, mu, l)
+            # 2e-6: the GPU's fp32 average may sit one rounding from the oracle's
+            mag_yl = np.abs(ow) + l * alpha * np.abs(avg)
+            mag_w = np.abs(ow) + alpha * np.abs(avg) + mu * (mag_yl + np.abs(ow))
+            assert np.all(np.abs(w[c_lo:c_hi].cpu().numpy() - w64) <= 2e-6 * mag_w + 1e-45)
+            assert np.all(np.abs(opt.yl[c_lo:c_hi].cpu().numpy() - yl64) <= 2e-6 * mag_yl + 1e-45)
+        del opt, w
+    torch.cuda.empty_cache()
+
+
 def _least_squares(d, T, K, seed):
     rng = np.random.default_rng(seed)
     hdiag = rng.uniform(0.5, 2.0, d).astype(np.float32)
