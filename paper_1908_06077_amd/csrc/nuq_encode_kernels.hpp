@@ -454,22 +454,31 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
         sync_l[i] = total | kSyncEmpty;   // "no record at or after this boundary" until one is found
     team_barrier<TEAM>();
 
-    // (3) emit
+    // (3) emit.  A thread's records are consecutive in the bit string: they are shifted into a 64-bit register and
+    // leave it 32 bits at a time (a record is at most 31 bits, so at most 31 + 31 bits are pending), OR-ed into the
+    // zeroed words because a thread's first and last word are shared with its neighbours.
     {
-        uint32_t t = off0;
+        uint32_t t = off0, wi = off0 >> 5, fill = off0 & 31u;
+        uint64_t acc = 0;
         auto emit = [&](uint32_t *dst, int e, int p, uint32_t bitsrec, uint32_t len) {
-            const uint32_t wi = t >> 5, bo = t & 31u;
-            const uint64_t sh = (uint64_t)bitsrec << (64u - bo - len);
-            atomicOr(&dst[wi], (uint32_t)(sh >> 32));
-            if ((uint32_t)sh)
-                atomicOr(&dst[wi + 1u], (uint32_t)sh);
             if (P.sync_shift) {
                 // this record is the first one at or after every segment boundary in (p, e]
                 const int g_hi = e >> P.sync_shift;
                 for (int g = max((p >> P.sync_shift) + 1, 1); g <= g_hi; ++g)
                     sync_l[g - 1] = g == g_hi ? (t | ((uint32_t)(e - (g << P.sync_shift)) << 21)) : (t | kSyncEmpty);
             }
+            acc = (acc << len) | bitsrec;
+            fill += len;
             t += len;
+            if (fill >= 32u) {
+                fill -= 32u;
+                atomicOr(&dst[wi++], (uint32_t)(acc >> fill));
+                acc &= (1ull << fill) - 1ull;
+            }
+        };
+        auto flush = [&](uint32_t *dst) {
+            if (fill && t != off0)
+                atomicOr(&dst[wi], (uint32_t)(acc << (32u - fill)));
         };
         auto emit_all = [&](uint32_t *dst) {
             if (listed) {
@@ -495,10 +504,13 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
                 });
             }
         };
-        if (in_lds)
+        if (in_lds) {
             emit_all(obuf);
-        else if (active)
+            flush(obuf);
+        } else if (active) {
             emit_all(slot);
+            flush(slot);
+        }
     }
     team_barrier<TEAM>();
     if (active) {
