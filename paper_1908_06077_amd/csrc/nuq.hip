@@ -611,6 +611,20 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
     P.scale = scale;
     if (momentum && levels)
         return NUQ_EINVAL;
+    if (K == 1 && !levels && !momentum && (nsync || bucket <= 512)) {
+        // one message: a lane per (bucket, sync segment), values stored directly (k_decode_single)
+        const uint64_t wgs = (P.nb * P.nseg + kSingleWG - 1) / kSingleWG;
+        if (wgs > 0x7fffffffull)
+            return NUQ_EINVAL;
+        ScopedTiming timing(NUQ_T_DECODE, static_cast<hipStream_t>(stream));
+        if (accumulate)
+            hipLaunchKernelGGL(k_decode_single<kUpdateAdd>, dim3((uint32_t)wgs), dim3(kSingleWG), 0,
+                               static_cast<hipStream_t>(stream), P);
+        else
+            hipLaunchKernelGGL(k_decode_single<kUpdateWrite>, dim3((uint32_t)wgs), dim3(kSingleWG), 0,
+                               static_cast<hipStream_t>(stream), P);
+        return check_launch();
+    }
     const uint32_t variant = (levels ? 3u : 0u) + (momentum ? (uint32_t)kUpdateMomentum
                                                             : accumulate ? (uint32_t)kUpdateAdd : (uint32_t)kUpdateWrite);
     if (momentum) {

@@ -282,10 +282,31 @@ __device__ __forceinline__ uint32_t level_table_entry(uint32_t p, uint32_t smax)
 //
 // kTable: the value of level j is wnorm * lev[j] (an arbitrary level sequence, lev in LDS) instead of
 // wnorm * 2^j (wnorm = ||v|| * 2^(-1-s)); both are exact in fp64.
-template <bool kTable, class Words>
+// Where a decoded value goes.  TileSink: the fp64 tile in LDS that sums the workers (at0 = address of the
+// bucket's index 0).  DirectSink: a single message has nothing to sum: fp32(scale * value), the same rounding the
+// tile's output stage applies to a sum of one term, stored or added straight into the output.
+struct TileSink {
+    double *at0;
+    __device__ __forceinline__ void add(uint32_t idx, double v) const { atomicAdd(at0 + idx, v); }
+};
+template <int UPDATE>
+struct DirectSink {
+    float *at0;
+    double scale;
+    __device__ __forceinline__ void add(uint32_t idx, double v) const
+    {
+        const float r = (float)(scale * v);
+        if constexpr (UPDATE == kUpdateAdd)
+            at0[idx] = r + at0[idx];
+        else
+            at0[idx] = r;
+    }
+};
+
+template <bool kTable, class Words, class Sink>
 __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint16_t *lut, const uint8_t *lut_level,
                                                  const float *lev, uint32_t bit_lo, uint32_t bit_hi, int forced,
-                                                 uint32_t idx_hi, double wnorm, double *tile_at0, bool &bad)
+                                                 uint32_t idx_hi, double wnorm, const Sink &sink, bool &bad)
 {
     uint32_t p31 = bit_lo + 31u;
     const uint32_t end31 = bit_hi + 31u;
@@ -342,7 +363,7 @@ __device__ __forceinline__ void decode_unit_fast(const Words &words, const uint1
         const uint32_t mh = (uint32_t)((uint64_t)__double_as_longlong(mag) >> 32);
         const uint32_t vh = (mh & 0x7fffffffu) | (w2 & 0x80000000u);
         const uint64_t vb = ((uint64_t)vh << 32) | (uint32_t)__double_as_longlong(mag);
-        atomicAdd(tile_at0 + idx, __longlong_as_double((long long)vb));
+        sink.add(idx, __longlong_as_double((long long)vb));
     };
 
     chain1();
@@ -585,7 +606,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         const uint32_t nbk = G.b0 + bi == last_bucket ? last_len : P.bucket;
         const uint32_t idx_hi = P.sync_shift ? min(nbk, (g + 1u) << P.sync_shift) : nbk;
         decode_unit_fast<kTable>(StagedWords{buf + (Q.where & 0xFFFu)}, lut, lut_level, lev, Q.bits & 0xFFFFu, Q.bits >> 16,
-                         (int)(Q.where >> 16) - 1, idx_hi, (double)Q.norm * wscale, tile_origin(G, bi), bad);
+                         (int)(Q.where >> 16) - 1, idx_hi, (double)Q.norm * wscale, TileSink{tile_origin(G, bi)}, bad);
     };
     // Any unit, from scratch: units beyond the planned ones and units whose words were not staged.
     auto slow_unit = [&](const TileGeom &G, const uint32_t *buf, uint32_t k, uint32_t bi, uint32_t g, bool report,
@@ -600,7 +621,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         else if (X.kind == 2)
             decode_unit_fast<kTable>(GlobalWords{P.words[k] + X.first_word, X.nwords - 1u}, lut, lut_level, lev, X.bit_lo, X.bit_hi,
                              X.forced,
-                             X.idx_hi, (double)X.norm * wscale, tile_origin(G, bi), bad);
+                             X.idx_hi, (double)X.norm * wscale, TileSink{tile_origin(G, bi)}, bad);
     };
     // Tiles of a large bucket without a sync index: every tile parses the bucket from its first record in
     // global memory and keeps what lands inside.
@@ -849,6 +870,125 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         __syncthreads();
         t += stride;
         G = G1;
+    }
+    if (bad)
+        atomicOr(P.flags, kFlagMalformed);
+}
+
+// ---- one message (K = 1), main scheme's levels, output written or added to -------------------------------------
+// With a single worker there is nothing to sum, and a 2048-coordinate tile would hold only 2048 / stride units for
+// 64 parsing lanes.  Here every lane owns one unit (bucket, sync segment), stages its words in an LDS row of its
+// own and stores each value where it belongs; for the write mode the workgroup first clears the contiguous range of
+// coordinates its units cover (coalesced), and a coordinate belongs to exactly one unit, so nothing races.
+constexpr uint32_t kSingleWG = 128;
+constexpr uint32_t kSingleCap = 24;                     // words of a unit that are staged (longer units read global memory)
+constexpr uint32_t kSingleRow = kSingleCap + 5;         // pad word before, three after; odd: rows start in different banks
+
+template <int UPDATE>
+__global__ __launch_bounds__(kSingleWG) void k_decode_single(DecodeParams P)
+{
+    static_assert(UPDATE == kUpdateWrite || UPDATE == kUpdateAdd, "the momentum rule touches every coordinate");
+    __shared__ uint32_t rows[kSingleWG * kSingleRow];
+    __shared__ uint16_t lut[128];
+    __shared__ uint8_t lut_level[128];
+    const uint32_t tid = threadIdx.x;
+    lut[tid] = (uint16_t)gap_table_entry(tid);
+    lut_level[tid] = (uint8_t)level_table_entry(tid, P.s + 1u);
+    const uint64_t units = P.nb * P.nseg;
+    const uint64_t u0 = (uint64_t)blockIdx.x * kSingleWG;
+    const uint32_t S = P.sync_shift ? 1u << P.sync_shift : P.bucket;
+
+    // ---- this lane's unit: metadata, then its words into the lane's LDS row (before the clearing below, so that
+    // the two chains of dependent loads run under it)
+    const uint64_t u = u0 + tid;
+    const uint64_t b = min(u / P.nseg, P.nb - 1u);                  // (clamped: a lane without a unit loads and ignores)
+    const uint32_t g = (uint32_t)(u - (u / P.nseg) * P.nseg);
+    const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
+    const uint32_t idx_lo = P.sync_shift ? g << P.sync_shift : 0u;
+    const uint32_t idx_hi = P.sync_shift ? min(nbk, (g + 1u) << P.sync_shift) : nbk;
+    bool work = u < units && idx_lo < nbk;
+    const uint64_t bo0 = P.bit_off[0][b], bo1 = P.bit_off[0][b + 1];
+    const uint64_t start = (bo0 + 31ull) & ~31ull;
+    bool bad = work && bo1 > start && bo1 - start > 0x1FFFFFull;    // a bucket's bit string is below 2^21 bits
+    const uint32_t len = bo1 > start && !bad ? (uint32_t)(bo1 - start) : 0u;
+    uint32_t bit_lo = 0, bit_hi = len;
+    int forced = -1;
+    if (P.sync_shift) {
+        const uint32_t *sy = P.sync[0] + b * P.nsync;
+        if (g > 0u) {
+            const uint32_t e = sy[g - 1u];
+            work = work && (e & kSyncEmpty) == 0u;                  // no record at or after this boundary's segment
+            bit_lo = e & 0x1FFFFFu;
+            forced = (int)(idx_lo + ((e >> 21) & 0x3FFu));
+        }
+        if (g + 1u < P.nseg)
+            bit_hi = sy[g] & 0x1FFFFFu;
+        if (work && (bit_lo > bit_hi || bit_hi > len || (forced >= 0 && (uint32_t)forced >= idx_hi))) {
+            bad = true;
+            work = false;
+        }
+    }
+    work = work && bit_hi > bit_lo;
+    const uint32_t w0 = bit_lo >> 5, nw = work ? ((bit_hi + 31u) >> 5) - w0 : 0u;
+    const uint32_t *src = P.words[0] + (start >> 5) + w0;
+    uint32_t *row = rows + tid * kSingleRow;
+    const bool staged = nw <= kSingleCap;
+    if (work && staged) {
+        row[0] = 0u;
+        for (uint32_t j0 = 0; j0 < nw; j0 += 8u) {                   // loads of a group in flight together
+            uint32_t x[8];
+#pragma unroll
+            for (uint32_t j = 0; j < 8u; ++j)
+                x[j] = src[min(j0 + j, nw - 1u)];
+#pragma unroll
+            for (uint32_t j = 0; j < 8u; ++j)
+                if (j0 + j < nw)
+                    row[1u + j0 + j] = x[j];
+        }
+        row[nw + 1u] = 0u;
+        row[nw + 2u] = 0u;
+        row[nw + 3u] = 0u;
+    }
+    const float nrm = P.norms[0][b];
+
+    // ---- write mode: clear the contiguous range of coordinates that the workgroup's units cover
+    if constexpr (UPDATE == kUpdateWrite) {
+        auto first_coord = [&](uint64_t v) -> uint64_t {    // first coordinate of unit v; d for v = units
+            if (v >= units)
+                return P.d;
+            const uint64_t vb = v / P.nseg;
+            const uint64_t c = vb * P.bucket + (v - vb * P.nseg) * S;
+            return c < P.d ? c : P.d;
+        };
+        const uint64_t c0 = first_coord(u0), c1 = first_coord(u0 + kSingleWG);
+        float *o = P.out;
+        const uint64_t up = (c0 + 3u) & ~3ull, dn = c1 & ~3ull;
+        const uint64_t a0 = up < c1 ? up : c1, a1 = dn > a0 ? dn : a0;                  // whole float4 groups in [a0, a1)
+        const bool vec = (reinterpret_cast<uintptr_t>(o) & 15u) == 0;
+        if (vec) {
+            for (uint64_t c = c0 + tid; c < a0; c += kSingleWG)
+                o[c] = 0.0f;
+            for (uint64_t c = a0 + 4ull * tid; c < a1; c += 4ull * kSingleWG)
+                *reinterpret_cast<float4 *>(o + c) = float4{0.0f, 0.0f, 0.0f, 0.0f};
+            for (uint64_t c = a1 + tid; c < c1; c += kSingleWG)
+                o[c] = 0.0f;
+        } else {
+            for (uint64_t c = c0 + tid; c < c1; c += kSingleWG)
+                o[c] = 0.0f;
+        }
+    }
+    __syncthreads();          // tables in place; the cleared range is ordered before the values stored below
+
+    if (work) {
+        const uint32_t rel_lo = bit_lo & 31u, rel_hi = bit_hi - (w0 << 5);
+        const double wnorm = (double)nrm * ldexp(1.0, -1 - (int)P.s);
+        const DirectSink<UPDATE> sink{P.out + b * P.bucket, (double)P.scale};
+        if (staged)
+            decode_unit_fast<false>(StagedWords{row}, lut, lut_level, nullptr, rel_lo, rel_hi, forced, idx_hi, wnorm, sink,
+                                    bad);
+        else
+            decode_unit_fast<false>(GlobalWords{src, nw - 1u}, lut, lut_level, nullptr, rel_lo, rel_hi, forced, idx_hi,
+                                    wnorm, sink, bad);
     }
     if (bad)
         atomicOr(P.flags, kFlagMalformed);

@@ -104,6 +104,18 @@ def test_each_step_and_fused_path_match_oracle(g, d, n, s, S, kind):
     nuq.nuq_decode_accumulate([mf], d, n, s, S, 1.0, False, out)
     assert nuq.nuq_last_error_flags() == 0
     g.check_average([(norms_np, bo, words)], d, n, s, 1.0, out.cpu().numpy())
+    # ... and adds onto what is there (one message: values go straight to the output, no tile), also through a
+    # pointer off the 16-byte grid
+    prior_np = rng.standard_normal(d + 1).astype(np.float32)
+    for shift in (0, 1):
+        out2 = torch.from_numpy(prior_np).to(g.DEV)[shift:shift + d]
+        nuq.nuq_decode_accumulate([mf], d, n, s, S, -0.25, True, out2)
+        g.check_average([(norms_np, bo, words)], d, n, s, -0.25, out2.cpu().numpy(),
+                        prior=prior_np[shift:shift + d].astype(np.float64))
+        out3 = torch.full((d + 1,), 7.0, dtype=torch.float32, device=g.DEV)[shift:shift + d]
+        nuq.nuq_decode_accumulate([mf], d, n, s, S, 1.0, False, out3)
+        assert torch.equal(out3, out)
+    assert nuq.nuq_last_error_flags() == 0
 
 
 @pytest.mark.parametrize("d,n,s,S,K", [(60_000, 8192, 3, 512, 8), (30_000, 512, 3, 0, 4), (50_000, 16384, 7, 1024, 4),
