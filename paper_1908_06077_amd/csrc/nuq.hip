@@ -365,19 +365,22 @@ HuffmanWorkspace carve_huffman(void *base, uint64_t nb)
 }
 
 // Workgroups of the persistent decode kernel that the current device holds at once (0 on error).
-// `variant` indexes kDecodeKernels.
+// `variant` indexes kDecodeKernels: 2 * (3 * table + update) + big tile.
 using DecodeKernel = void (*)(DecodeParams);
 constexpr DecodeKernel kDecodeKernels[] = {
-    k_decode_accumulate<false, kUpdateWrite>, k_decode_accumulate<false, kUpdateAdd>,
-    k_decode_accumulate<false, kUpdateMomentum>, k_decode_accumulate<true, kUpdateWrite>,
-    k_decode_accumulate<true, kUpdateAdd>,
+    k_decode_accumulate<false, kUpdateWrite, kTileCoords>,    k_decode_accumulate<false, kUpdateWrite, kTileCoordsBig>,
+    k_decode_accumulate<false, kUpdateAdd, kTileCoords>,      k_decode_accumulate<false, kUpdateAdd, kTileCoordsBig>,
+    k_decode_accumulate<false, kUpdateMomentum, kTileCoords>, k_decode_accumulate<false, kUpdateMomentum, kTileCoordsBig>,
+    k_decode_accumulate<true, kUpdateWrite, kTileCoords>,     k_decode_accumulate<true, kUpdateWrite, kTileCoordsBig>,
+    k_decode_accumulate<true, kUpdateAdd, kTileCoords>,       k_decode_accumulate<true, kUpdateAdd, kTileCoordsBig>,
 };
+constexpr uint32_t kDecodeVariants = sizeof(kDecodeKernels) / sizeof(kDecodeKernels[0]);
 
 uint32_t decode_resident_workgroups(uint32_t variant)
 {
-    static uint32_t cached[5][64] = {};
+    static uint32_t cached[kDecodeVariants][64] = {};
     int dev = 0;
-    if (variant >= 5u || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    if (variant >= kDecodeVariants || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
         return 0;
     if (!cached[variant][dev]) {
         int per_cu = 0, cus = 0;
@@ -625,8 +628,14 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
                                static_cast<hipStream_t>(stream), P);
         return check_launch();
     }
-    const uint32_t variant = (levels ? 3u : 0u) + (momentum ? (uint32_t)kUpdateMomentum
-                                                            : accumulate ? (uint32_t)kUpdateAdd : (uint32_t)kUpdateWrite);
+    // Tiles of 4096 coordinates (32 KB of fp64, four workgroups per CU instead of eight) where the usual 2048 would
+    // give the 64 parsing lanes at most 32 units: parts of large buckets of few workers.  The parse is bound by
+    // instruction issue, so one full wave per SIMD gets through more records than two half-empty ones.
+    const bool big = nsync && bucket >= kTileCoordsBig && (kTileCoords / sync_stride) * K <= 32u;
+    const uint32_t tile_coords = big ? kTileCoordsBig : kTileCoords;
+    const uint32_t variant = 2u * ((levels ? 3u : 0u) + (momentum ? (uint32_t)kUpdateMomentum
+                                                                  : accumulate ? (uint32_t)kUpdateAdd
+                                                                               : (uint32_t)kUpdateWrite)) + (big ? 1u : 0u);
     if (momentum) {
         P.yl = momentum->yl;
         P.alpha = momentum->alpha;
@@ -645,9 +654,9 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
         max_streams = P.buckets_per_tile * K;
     } else {
         P.buckets_per_tile = 0;
-        P.tile_coords = kTileCoords;
-        P.tiles_per_bucket = (bucket + kTileCoords - 1) / kTileCoords;
-        P.segs_per_tile = P.sync_shift ? (kTileCoords >> P.sync_shift) : 1;
+        P.tile_coords = tile_coords;
+        P.tiles_per_bucket = (bucket + tile_coords - 1) / tile_coords;
+        P.segs_per_tile = P.sync_shift ? (tile_coords >> P.sync_shift) : 1;
         ntiles = P.nb * P.tiles_per_bucket;
         max_streams = K;
     }

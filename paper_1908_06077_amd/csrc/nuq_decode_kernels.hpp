@@ -26,7 +26,8 @@ namespace nuq {
 
 constexpr uint32_t kMaxWorkers = 32;
 constexpr uint32_t kDecodeWG = 128;        // threads per workgroup: a parsing wave and a preparing wave
-constexpr uint32_t kTileCoords = 2048;     // coordinates per tile (16 KB of fp64)
+constexpr uint32_t kTileCoords = 2048;     // coordinates per tile (16 KB of fp64) ...
+constexpr uint32_t kTileCoordsBig = 4096;  // ... or, for few workers and large buckets, twice that (see the launcher)
 constexpr uint32_t kWordsPerLane = 8;      // staged words each lane of the preparing wave carries
 constexpr uint32_t kStageWords = kWave * kWordsPerLane;   // LDS words per staging buffer
 constexpr uint32_t kMaxStreams = 64;       // (bucket, worker) bit strings per tile
@@ -66,12 +67,12 @@ struct DecodeParams {
 //   kUpdateMomentum  (out, yl) <- momentum rule of Sec. 4.2 with g = r (out = w)
 constexpr int kUpdateWrite = 0, kUpdateAdd = 1, kUpdateMomentum = 2;
 
-// A full, 16-byte aligned tile: every thread handles kTileCoords/4/kDecodeWG float4 groups, two at a time, with the
+// A full, 16-byte aligned tile of TC coordinates: every thread handles TC/4/kDecodeWG float4 groups, two at a time, with the
 // loads of the old values issued before the LDS reads so that their latencies overlap.
-template <int UPDATE>
+template <int UPDATE, uint32_t TC>
 __device__ __forceinline__ void apply_full_tile(const DecodeParams &P, double *tile, float *o, float *y, uint32_t tid)
 {
-    constexpr uint32_t kFull = kTileCoords / 4u / kDecodeWG;      // float4 groups per thread
+    constexpr uint32_t kFull = TC / 4u / kDecodeWG;               // float4 groups per thread
     const double sc = (double)P.scale;
 #pragma unroll
     for (uint32_t r0 = 0; r0 < kFull; r0 += 2u) {
@@ -493,10 +494,10 @@ __device__ __forceinline__ PackedPlan pack_plan(const UnitPlan &U)
     return Q;
 }
 
-template <bool kTable, int UPDATE>
+template <bool kTable, int UPDATE, uint32_t TC>
 __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams P)
 {
-    __shared__ __align__(16) double tile[kTileCoords];
+    __shared__ __align__(16) double tile[TC];
     // words at [1, kStageWords]; the parser may read one word before and three after a stream's region
     __shared__ uint32_t stage[kStageWords + 5];
     __shared__ PackedPlan plans[kPlanned];
@@ -744,7 +745,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     UnitRaw um{};
     uint32_t wnext[kWordsPerLane] = {};         // preparing wave: its share of the next tile's words
     if (parser) {
-        for (uint32_t i = lane; i < kTileCoords / 2u; i += kWave)
+        for (uint32_t i = lane; i < TC / 2u; i += kWave)
             reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
         lut[lane] = (uint16_t)gap_table_entry(lane);
         lut[lane + kWave] = (uint16_t)gap_table_entry(lane + kWave);
@@ -843,8 +844,8 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             const uint32_t span = G.span;
             const bool vec = ((reinterpret_cast<uintptr_t>(o) | reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
             const uint32_t n4 = vec ? span >> 2 : 0u;
-            if (n4 == kTileCoords / 4u) {
-                apply_full_tile<UPDATE>(P, tile, o, y, tid);
+            if (n4 == TC / 4u) {
+                apply_full_tile<UPDATE, TC>(P, tile, o, y, tid);
             } else {
                 const double sc = (double)P.scale;
                 for (uint32_t i = tid; i < n4; i += kDecodeWG) {
