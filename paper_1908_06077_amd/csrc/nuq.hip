@@ -663,6 +663,8 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
     if (ntiles > 0x7fffffffull)
         return NUQ_EINVAL;
     P.ntiles = (uint32_t)ntiles;
+    P.xcd_base = P.ntiles / 8u;
+    P.xcd_rem = P.ntiles % 8u;
     // lanes (of the preparing wave) per stream for the copy of its words: the largest power of two that gives
     // every stream a group
     P.lanes_shift = 0;

@@ -53,6 +53,7 @@ struct DecodeParams {
     uint32_t tiles_per_bucket;  // >= 1
     uint32_t tile_coords;       // coordinates a full tile spans
     uint32_t segs_per_tile;     // segments of one bucket inside a tile
+    uint32_t xcd_base, xcd_rem; // ntiles / 8, ntiles % 8: see xcd_tile
     uint32_t lanes_shift;       // log2 of the lanes that copy one stream's words
     uint32_t stream_cap;        // LDS words reserved per stream = kWordsPerLane << lanes_shift
     float scale;
@@ -60,6 +61,18 @@ struct DecodeParams {
     double alpha, la, mu;       // kUpdateMomentum: step size, l * step size, momentum parameter
     float lev[16];              // level-table variant: l_0 = 0 .. l_{s+1} = 1
 };
+
+// Workgroup w walks the sequence w, w + grid, w + 2 grid, ... of [0, ntiles).  Workgroups are handed to the eight
+// XCDs (each with an L2 of its own) in turn, and the grid is a multiple of eight whenever a workgroup takes more
+// than one tile, so every element v of a workgroup's sequence has v mod 8 = the workgroup's XCD.  Element v is
+// therefore mapped to tile number (v / 8) of the (v mod 8)'th of eight contiguous runs of tiles: neighbouring tiles,
+// which share the cache lines at the ends of their parts of a bit string and their bucket's offsets and sync
+// entries, are decoded under the same L2.  A bijection of [0, ntiles) whatever the placement really is.
+__device__ __forceinline__ uint32_t xcd_tile(const DecodeParams &P, uint32_t v)
+{
+    const uint32_t x = v & 7u;
+    return x * P.xcd_base + min(x, P.xcd_rem) + (v >> 3);
+}
 
 // What the decoder (template parameter UPDATE) does with r = fp32(scale * sum over workers) of a coordinate:
 //   kUpdateWrite     out = r
@@ -740,7 +753,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     bool bad = false;
     const uint32_t stride = gridDim.x;
     uint32_t t = blockIdx.x;                    // < ntiles by the launch
-    TileGeom G = tile_geom(P, t);
+    TileGeom G = tile_geom(P, xcd_tile(P, t));
     StreamRaw sr{};                             // preparing wave: metadata of the tile after the next, in flight
     UnitRaw um{};
     uint32_t wnext[kWordsPerLane] = {};         // preparing wave: its share of the next tile's words
@@ -763,7 +776,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         prepare(G, sr, um, wnext, bad);
         store_words(wnext);
         if (t + stride < P.ntiles) {
-            const TileGeom G1 = tile_geom(P, t + stride);
+            const TileGeom G1 = tile_geom(P, xcd_tile(P, t + stride));
             sr = load_stream(G1);
             um = load_unit(G1, ubi[0], G1.g0 + ugr[0], P.bit_off[uk[0]], P.norms[uk[0]], P.sync[uk[0]]);
         }
@@ -806,12 +819,12 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         } else if (has1) {
             // ---- prepare the next tile (its metadata was requested a round ago), request the metadata of the
             // one after it
-            const TileGeom GA = tile_geom(P, t + stride);
+            const TileGeom GA = tile_geom(P, xcd_tile(P, t + stride));
             prepare(GA, sr, um, wnext, bad);
             if (lane == 0)
                 next_geom = GA;
             if (has2) {
-                const TileGeom G2 = tile_geom(P, t + 2u * stride);
+                const TileGeom G2 = tile_geom(P, xcd_tile(P, t + 2u * stride));
                 sr = load_stream(G2);
                 um = load_unit(G2, ubi[0], G2.g0 + ugr[0], P.bit_off[uk[0]], P.norms[uk[0]], P.sync[uk[0]]);
             }
