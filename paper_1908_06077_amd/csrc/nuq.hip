@@ -1139,8 +1139,18 @@ int nuq_average_levels(uint32_t K, const float *const *norms, const uint8_t *con
     if (blocks > 0x7fffffffull)
         return NUQ_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (wide)
-        hipLaunchKernelGGL(k_average_levels16, dim3((uint32_t)blocks), dim3(256), 0, st, P);
+    if (wide) {
+        // value tables in LDS when those of the buckets a workgroup (4096 coordinates) can touch fit in 16 KB
+        const uint64_t nb = nuq_num_buckets(d, bucket);
+        const bool tiled = 4096u % bucket == 0 || bucket % 4096u == 0;
+        const uint64_t tabs = std::min<uint64_t>(nb, tiled ? std::max(1u, 4096u / bucket) : 4096u / bucket + 2u);
+        const uint64_t lut_bytes = tabs * K * 32u * sizeof(double);
+        P.lut_tabs = (uint32_t)tabs;
+        if (lut_bytes <= 16384u)
+            hipLaunchKernelGGL(k_average_levels16<true>, dim3((uint32_t)blocks), dim3(256), (uint32_t)lut_bytes, st, P);
+        else
+            hipLaunchKernelGGL(k_average_levels16<false>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
+    }
     else if (aligned)
         hipLaunchKernelGGL(k_average_levels<4>, dim3((uint32_t)blocks), dim3(256), 0, st, P);
     else

@@ -795,6 +795,7 @@ struct AverageParams {
     uint32_t K;
     uint32_t bucket;
     uint32_t s;
+    uint32_t lut_tabs;      // k_average_levels16<true>: buckets a workgroup can touch (value tables per worker in LDS)
     float scale;
     int accumulate;
 };
@@ -850,13 +851,36 @@ __global__ __launch_bounds__(256) void k_average_levels(AverageParams P)
 
 // Buckets that are multiples of 16 coordinates, 16-byte aligned arrays: 16 coordinates per thread, one 16-byte load per
 // worker, four 16-byte stores.
+template <bool kLut>
 __global__ __launch_bounds__(256) void k_average_levels16(AverageParams P)
 {
+    // kLut: the value of every byte, norm * sign * 2^(level - 1 - s) in fp64, tabulated once per (bucket the workgroup
+    // touches, worker): 32 entries indexed by (sign, level), level <= 15.  A byte then costs an index, an LDS read and
+    // an fp64 add instead of the exponent arithmetic.
+    extern __shared__ __align__(16) double avg_lut[];           // [lut_tabs][K][32]
+    const uint64_t wg0 = (uint64_t)blockIdx.x * 4096u;
+    const uint64_t bk_first = P.d <= 0xffffffffull ? (uint64_t)((uint32_t)wg0 / P.bucket) : wg0 / P.bucket;
+    if constexpr (kLut) {
+        const uint64_t nb = (P.d + P.bucket - 1) / P.bucket;
+        const uint32_t total = P.lut_tabs * P.K * 32u;
+        for (uint32_t e = threadIdx.x; e < total; e += 256u) {
+            const uint32_t idx = e & 31u, k = (e >> 5) % P.K, tab = (e >> 5) / P.K;
+            const uint32_t level = idx & 15u;
+            double val = 0.0;
+            if (bk_first + tab < nb && level) {
+                val = ldexp((double)P.norms[k][bk_first + tab], (int)level - 1 - (int)P.s);
+                val = (idx & 16u) ? -val : val;
+            }
+            avg_lut[e] = val;
+        }
+        __syncthreads();
+    }
     const uint64_t i0 = ((uint64_t)blockIdx.x * 256u + threadIdx.x) * 16u;
     if (i0 >= P.d)
         return;
     const uint64_t bk = P.d <= 0xffffffffull ? (uint64_t)((uint32_t)i0 / P.bucket) : i0 / P.bucket;
     const bool whole = i0 + 15u < P.d;
+    const double *tab = avg_lut + (uint32_t)(bk - bk_first) * P.K * 32u;
     double sum[16];
 #pragma unroll
     for (int c = 0; c < 16; ++c)
@@ -875,13 +899,22 @@ __global__ __launch_bounds__(256) void k_average_levels16(AverageParams P)
         }
         if (!(w[0] | w[1] | w[2] | w[3]))
             continue;
-        const double nrm = (double)P.norms[k][bk];
+        if constexpr (kLut) {
+            const double *tk = tab + k * 32u;
 #pragma unroll
-        for (int c = 0; c < 16; ++c) {
-            const uint32_t byte = (w[c >> 2] >> (8 * (c & 3))) & 0xffu, level = byte & 0x7fu;
-            if (level) {
-                const double val = ldexp(nrm, (int)level - 1 - (int)P.s);
-                sum[c] += (byte & 0x80u) ? -val : val;
+            for (int c = 0; c < 16; ++c) {
+                const uint32_t byte = (w[c >> 2] >> (8 * (c & 3))) & 0xffu;
+                sum[c] += tk[((byte >> 3) & 16u) | (byte & 15u)];
+            }
+        } else {
+            const double nrm = (double)P.norms[k][bk];
+#pragma unroll
+            for (int c = 0; c < 16; ++c) {
+                const uint32_t byte = (w[c >> 2] >> (8 * (c & 3))) & 0xffu, level = byte & 0x7fu;
+                if (level) {
+                    const double val = ldexp(nrm, (int)level - 1 - (int)P.s);
+                    sum[c] += (byte & 0x80u) ? -val : val;
+                }
             }
         }
     }

@@ -33,6 +33,8 @@ CASES = [
     (120_000, 32768, 3, 1024, 2, "mixed"),
     (66_000, 1536, 9, 64, 2, "edges"),         # six float4 rows per thread: sync boundaries inside a thread's chunk
     (1, 8192, 3, 512, 1, "gauss"),
+    (20_000, 64, 3, 0, 8, "mixed"),            # many small buckets per workgroup: the average without value tables
+    (30_000, 2000, 5, 256, 3, "mixed"),        # buckets that do not tile a workgroup's 4096 coordinates
 ]
 
 
