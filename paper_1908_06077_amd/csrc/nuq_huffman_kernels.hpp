@@ -544,10 +544,9 @@ __global__ __launch_bounds__(64) void k_huffman_decode_tile(HuffmanDecodeParams 
 }
 
 // The decoder for the usual geometry (buckets and byte arrays that are multiples of 16: every unit starts on a 16-byte
-// boundary): as k_huffman_decode_tile, but a lane collects 16 bytes in registers and stores them itself.  Sixty-four
-// 16-byte stores 256 bytes apart are few enough transactions, and without the tile a wave needs 6.4 KB of LDS
-// instead of 23, so several times as many waves hide each other's latencies (the parse is one dependent chain per
-// lane).
+// boundary): as k_huffman_decode_tile, but a lane collects its bytes in registers and stores them itself, 64
+// consecutive bytes at a time (ByteSink).  Without the tile a wave needs 6.4 KB of LDS instead of 23, so several
+// times as many waves hide each other's latencies (the parse is one dependent chain per lane).
 //
 // The parse is bound by instruction issue, so it takes several symbols per step: `multi` maps the next eight bits of
 // the string to the symbols that end inside them (codeword plus sign bit; up to eight level-0 symbols), their
