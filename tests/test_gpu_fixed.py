@@ -92,6 +92,26 @@ def check(norms_np, packed_np, d, n, s, b, scale, got, prior=None):
     assert np.all(diff <= 1e-6 * mag + 1e-45), float(np.max(diff / np.maximum(mag, 1e-300)))
 
 
+def _random_fixed_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        b = int(rng.integers(3, 9))
+        s = int(rng.integers(1, min(14, 2 ** (b - 1) - 2) + 1))
+        n = int(rng.integers(1, 400)) * 32 if rng.random() < 0.7 else int(rng.integers(1, 5000))
+        d = int(rng.integers(1, 9 * n + 2)) if rng.random() < 0.5 else int(rng.integers(1, 120_000))
+        K = int(rng.choice([1, 2, 3, 5, 8, 13]))
+        cases.append((d, n, s, b, K, str(rng.choice(["gauss", "mixed", "edges"]))))
+    return cases
+
+
+@pytest.mark.parametrize("d,n,s,b,K,kind", _random_fixed_cases(24, 77))
+def test_random_shapes(g, d, n, s, b, K, kind):
+    """Seeded draws over the parameters: code width, levels, bucket size (mostly multiples of 32: the wide unpack
+    kernel with and without value tables), vector length, workers."""
+    test_pack_fused_pack_and_unpack_average(g, d, n, s, b, K, kind)
+
+
 @pytest.mark.parametrize("b,s,nbuckets", [(4, 2, 1), (8, 2, 1), (8, 14, 1), (5, 2, 1), (3, 1, 1), (5, 2, 200), (4, 2, 300)])
 def test_malformed_codes_raise_the_flag(g, b, s, nbuckets):
     # every route of the unpack kernel: value tables with the whole-word test (b = 4, 8) and the per-code test

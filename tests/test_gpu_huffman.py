@@ -118,6 +118,26 @@ def test_histogram_code_message_decode_and_average(g, d, n, s, S, K, kind):
     assert np.all(diff <= 1e-6 * mag * scale32 + 1e-45)
 
 
+def _random_huffman_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        n = int(rng.integers(1, 300)) * 16 if rng.random() < 0.7 else int(rng.integers(1, 5000))
+        d = int(rng.integers(1, 9 * n + 2)) if rng.random() < 0.5 else int(rng.integers(1, 120_000))
+        s = int(rng.integers(1, 15))
+        S = int(rng.choice([0, 64, 128, 256, 512, 1024]))
+        K = int(rng.choice([1, 2, 3, 5, 8]))
+        cases.append((d, n, s, S, K, str(rng.choice(["gauss", "mixed", "edges"]))))
+    return cases
+
+
+@pytest.mark.parametrize("d,n,s,S,K,kind", _random_huffman_cases(24, 78))
+def test_random_shapes(g, d, n, s, S, K, kind):
+    """Seeded draws over bucket size (mostly multiples of 16: the direct decoder and the wide average), vector
+    length, levels, sync stride and workers."""
+    test_histogram_code_message_decode_and_average(g, d, n, s, S, K, kind)
+
+
 @pytest.mark.parametrize("s,n,S,hist", [
     (3, 8192, 256, [1, 10, 100, 1000, 10000]),                 # level 0 has the longest codeword: no four-at-a-time
     (3, 512, 128, [5, 4, 3, 2, 1]),                            # codeword of level 0 two bits long
