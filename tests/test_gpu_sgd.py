@@ -196,6 +196,48 @@ def test_decode_momentum_step_equals_the_two_calls(g, d, n, S, shift):
     assert not torch.equal(w1, w0.to(g.DEV)[shift:]) or d == 0
 
 
+def _random_update_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        n = int(round(2.0 ** rng.uniform(0, 15)))
+        if rng.random() < 0.4:
+            n = int(2 ** rng.integers(6, 16))
+        d = int(rng.integers(1, 12 * n + 2)) if rng.random() < 0.5 else int(rng.integers(1, 150_000))
+        S = int(rng.choice([0, 64, 128, 256, 512, 1024]))
+        K = int(rng.choice([1, 2, 3, 4, 5, 8]))
+        cases.append((d, n, S, K, int(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("d,n,S,K,shift", _random_update_cases(24, 99))
+def test_update_modes_on_random_shapes(g, d, n, S, K, shift):
+    """Every tile geometry of the decoder (small and large buckets, 2048- and 4096-coordinate tiles, one message):
+    adding onto the output equals writing the sum and adding it afterwards; the momentum rule inside the decoder
+    equals decode + momentum kernel.  Bit for bit: the same fp32 operations in the same order."""
+    nuq = g.nuq
+    s, alpha, mu, l = 3, 0.3, 0.8, 0.5
+    rng = np.random.default_rng([d, n, S, K])
+    vs = [torch.from_numpy(make_vector("mixed", d, n, rng)).to(g.DEV) for _ in range(K)]
+    buf = _sgd().MessageBuffers(K, d, n, s, S, g.DEV)
+    nuq.nuq_quantize_encode_batch(vs, n, s, list(range(K)), S, buf.messages, buf.workspace)
+    w0 = torch.from_numpy(rng.standard_normal(d + 1).astype(np.float32)).to(g.DEV)
+    y0 = torch.from_numpy(rng.standard_normal(d + 1).astype(np.float32)).to(g.DEV)
+    cut = lambda x: x.clone()[shift:shift + d]
+    total = cut(w0)
+    nuq.nuq_decode_accumulate(buf.messages, d, n, s, S, -alpha / K, False, total)          # fp32(scale * sum)
+    added = cut(w0)
+    nuq.nuq_decode_accumulate(buf.messages, d, n, s, S, -alpha / K, True, added)
+    assert torch.equal(added, total + cut(w0))
+    avg = cut(w0)
+    nuq.nuq_decode_accumulate(buf.messages, d, n, s, S, 1.0 / K, False, avg)
+    w1, y1, w2, y2 = cut(w0), cut(y0), cut(w0), cut(y0)
+    nuq.nuq_momentum_step(w1, y1, avg, alpha, mu, l)
+    nuq.nuq_decode_momentum_step(buf.messages, d, n, s, S, 1.0 / K, alpha, mu, l, w2, y2)
+    assert nuq.nuq_last_error_flags() == 0
+    assert torch.equal(w1, w2) and torch.equal(y1, y2)
+
+
 def test_updates_at_benchmark_size(g):
     """Config 3 at full size, launched as bench.py --update launches it: one step of the plain rule and one of the
     momentum rule inside the decoder, compared on sampled runs of buckets that the oracle computes one by one."""
