@@ -78,6 +78,47 @@ def test_argument_errors_are_reported_on_the_host(nuq):
     assert lib.nuq_bucket_norms_linf(None, 10, 4, None, None) == EINVAL
 
 
+def test_argument_errors_of_the_update_entry_points(nuq):
+    # rejected on the host before anything is launched
+    lib = ctypes.CDLL(nuq.library_path())
+    EINVAL, f32, vp, u64 = -1, ctypes.c_float, ctypes.c_void_p, ctypes.c_uint64
+    lib.nuq_momentum_step.restype = ctypes.c_int
+    lib.nuq_momentum_step.argtypes = [vp, vp, vp, u64, f32, f32, f32, vp]
+    assert lib.nuq_momentum_step(16, 16, 16, 8, 0.1, 1.0, 0.0, None) == EINVAL              # mu = 1
+    assert lib.nuq_momentum_step(16, 16, 16, 8, 0.1, -0.5, 0.0, None) == EINVAL             # mu < 0
+    assert lib.nuq_momentum_step(16, 16, 16, 8, float("nan"), 0.5, 0.0, None) == EINVAL
+    assert lib.nuq_momentum_step(16, 16, 16, 8, 0.1, 0.5, float("inf"), None) == EINVAL
+    assert lib.nuq_momentum_step(None, 16, 16, 8, 0.1, 0.5, 0.0, None) == EINVAL            # NULL w
+    assert lib.nuq_momentum_step(None, None, None, 0, 0.1, 0.5, 0.0, None) == 0             # d = 0: nothing to do
+    lib.nuq_moments_accumulate.restype = ctypes.c_int
+    lib.nuq_moments_accumulate.argtypes = [vp, vp, vp, u64, vp]
+    assert lib.nuq_moments_accumulate(16, None, 16, 8, None) == EINVAL
+    lib.nuq_normalized_variance.restype = ctypes.c_int
+    lib.nuq_normalized_variance.argtypes = [vp, vp, u64, u64, vp, u64, vp, vp]
+    assert lib.nuq_normalized_variance(16, 16, 8, 0, 16, 16384, 16, None) == EINVAL         # no draws
+    assert lib.nuq_normalized_variance(16, 16, 8, 3, 16, 1024, 16, None) == EINVAL          # workspace too small
+    assert lib.nuq_normalized_variance(16, 16, 8, 3, 20, 16384, 16, None) == EINVAL         # workspace misaligned
+    assert lib.nuq_normalized_variance(16, 16, 8, 3, 16, 16384, None, None) == EINVAL       # no output
+    lib.nuq_decode_momentum_step.restype = ctypes.c_int
+    lib.nuq_decode_momentum_step.argtypes = [ctypes.c_uint32, vp, vp, vp, vp, u64, ctypes.c_uint32, ctypes.c_uint32,
+                                             ctypes.c_uint32, f32, f32, f32, f32, vp, vp, vp]
+    one = (ctypes.c_void_p * 1)(16)
+    assert lib.nuq_decode_momentum_step(1, one, one, one, one, 8, 4, 3, 0, 1.0, 0.1, 0.5, 0.0, 16, None, None) == EINVAL
+    assert lib.nuq_decode_momentum_step(1, one, one, one, one, 8, 4, 3, 0, 1.0, 0.1, 1.5, 0.0, 16, 16, None) == EINVAL
+    assert lib.nuq_decode_momentum_step(0, one, one, one, one, 8, 4, 3, 0, 1.0, 0.1, 0.5, 0.0, 16, 16, None) == EINVAL
+    lib.nuq_fixed_words.restype = ctypes.c_uint64
+    lib.nuq_fixed_words.argtypes = [u64, ctypes.c_uint32, ctypes.c_uint32]
+    assert lib.nuq_fixed_words(100, 32, 4) == 4 * 4 and lib.nuq_fixed_words(100, 32, 2) == 0 and lib.nuq_fixed_words(100, 0, 4) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0 and "one GPU" in res.stderr
+
+
 def test_huffman_lengths_on_the_host(nuq):
     """nuq_huffman_lengths is host arithmetic: the hand-built examples of tests/golden/huffman_examples.txt."""
     for line in open(os.path.join(ROOT, "tests", "golden", "huffman_examples.txt")):
