@@ -57,6 +57,17 @@ struct TeamGeom {
     static constexpr int kTeamsPerWG = kWG / TEAM;
 };
 
+// A 16-byte load of data that is read once (gradients): non-temporal, so that the stream does not push the
+// staged bit strings, lengths and messages, which the next kernel reads, out of the caches.  Used by teams of a
+// wave or more (measured: 172 -> 164 us on 8192-coordinate buckets, 3 % on 16384); quarter-wave teams, whose loads
+// are 256-byte pieces, lose 5 % with it and keep plain loads.
+__device__ __forceinline__ float4 load_once4(const float4 *p)
+{
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 r = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+    return float4{r.x, r.y, r.z, r.w};
+}
+
 // Load the four coordinates of vector `vi` of a bucket of `nbk` coordinates starting at `vb`.
 __device__ __forceinline__ float4 load_vec4(const float *vb, uint32_t vi, uint32_t nbk, bool aligned)
 {
@@ -562,7 +573,8 @@ __device__ __forceinline__ void front_quantize_to_lds(const EncodeParams &P, con
     if (aligned && nbk == (uint32_t)VPT * TEAM * 4u) {   // a full bucket that fills every row: plain vector loads
 #pragma unroll
         for (int i = 0; i < VPT; ++i)
-            x[i] = reinterpret_cast<const float4 *>(vb)[(uint32_t)i * TEAM + tid];
+            x[i] = TEAM >= 64 ? load_once4(reinterpret_cast<const float4 *>(vb) + ((uint32_t)i * TEAM + tid))
+                              : reinterpret_cast<const float4 *>(vb)[(uint32_t)i * TEAM + tid];
     } else {
 #pragma unroll
         for (int i = 0; i < VPT; ++i)
