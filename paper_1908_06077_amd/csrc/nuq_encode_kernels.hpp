@@ -672,9 +672,16 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
         const float *vb = W.v + base;
         const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
         float4 x[VPT];
+        if (aligned && nbk == (uint32_t)VPT * TEAM * 4u) {   // a full bucket that fills every row (as in the main front)
 #pragma unroll
-        for (int i = 0; i < VPT; ++i)
-            x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
+            for (int i = 0; i < VPT; ++i)
+                x[i] = TEAM >= 64 ? load_once4(reinterpret_cast<const float4 *>(vb) + ((uint32_t)i * TEAM + tid))
+                                  : reinterpret_cast<const float4 *>(vb)[(uint32_t)i * TEAM + tid];
+        } else {
+#pragma unroll
+            for (int i = 0; i < VPT; ++i)
+                x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
+        }
         float nrm;
         if (P.norm_linf) {
             uint32_t m = 0;
