@@ -550,15 +550,16 @@ __global__ __launch_bounds__(64) void k_huffman_decode_tile(HuffmanDecodeParams 
 //
 // The parse is bound by instruction issue, so it takes several symbols per step: `multi` maps the next eight bits of
 // the string to the symbols that end inside them (codeword plus sign bit; up to eight level-0 symbols), their
-// count and their total length.  An entry with no symbol (a codeword of eight bits or more, or none) falls back to
-// one symbol from the 32-bit window.  The bits after a unit's end are the next unit's (or padding that reads as
-// level-0 symbols), so the table is used only while at least eight symbols of the unit remain.
+// count and the running total of their lengths.  An entry with no symbol (a codeword of eight bits or more, or none)
+// falls back to one symbol from the 32-bit window.  The bits after a unit's end are the next unit's (or padding
+// that reads as level-0 symbols): near the end only as many of an entry's symbols as the unit still has are taken,
+// with the length the running total gives, so every step of every lane goes the same way.
 constexpr uint32_t kHuffmanDirectWG = 256;
 
 struct MultiEntry {
     uint32_t bytes_lo, bytes_hi;   // level|sign bytes of the symbols, first symbol in the lowest byte, rest zero
     uint32_t count;                // symbols, 0..8
-    uint32_t bits;                 // their total length, 0..8
+    uint32_t cum;                  // nibble k: total length of the first k + 1 symbols (1..8)
 };
 
 // A lane's output buffer: 16 bytes being filled (lo, hi) and up to NB - 1 full 16-byte blocks waiting (the newest
@@ -645,7 +646,7 @@ __global__ __launch_bounds__(kHuffmanDirectWG) void k_huffman_decode_direct(Huff
     {
         // entry `tid` of both tables: canonical decoding of the eight bits, symbol after symbol
         const uint32_t p = tid;
-        uint32_t used = 0, n = 0, lo = 0, hi = 0, single = 0;
+        uint32_t used = 0, n = 0, lo = 0, hi = 0, single = 0, cum = 0;
         for (;;) {
             uint32_t entry = 0;
             for (uint32_t L = 1; used + L <= 8u && L <= H.maxlen; ++L) {
@@ -668,9 +669,10 @@ __global__ __launch_bounds__(kHuffmanDirectWG) void k_huffman_decode_direct(Huff
             else
                 hi |= byte << (8u * (n - 4u));
             used += bits;
+            cum |= used << (4u * n);
             ++n;
         }
-        multi[p] = MultiEntry{lo, hi, n, used};
+        multi[p] = MultiEntry{lo, hi, n, cum};
         lut8[p] = (uint8_t)single;
     }
     __syncthreads();
@@ -717,11 +719,12 @@ __global__ __launch_bounds__(kHuffmanDirectWG) void k_huffman_decode_direct(Huff
             const uint32_t w = __builtin_amdgcn_alignbit(hw, lw, ~p31);
             uint64_t nb;
             uint32_t cnt, bits;
-            const MultiEntry e = multi[w >> 24];
-            if (i + 8u <= n && e.count) {
-                nb = ((uint64_t)e.bytes_hi << 32) | e.bytes_lo;
-                cnt = e.count;
-                bits = e.bits;
+            const uint4 e = *reinterpret_cast<const uint4 *>(&multi[w >> 24]);      // one 16-byte LDS read
+            cnt = min(e.z, n - i);
+            if (cnt) {
+                bits = (e.w >> (4u * (cnt - 1u))) & 15u;
+                const uint64_t keep = cnt == 8u ? ~0ull : (1ull << (8u * cnt)) - 1ull;
+                nb = (((uint64_t)e.y << 32) | e.x) & keep;
             } else {
                 uint32_t entry = lut8[w >> 24];
                 if (!entry) {                                   // a codeword of nine bits or more (rare), or none
