@@ -131,6 +131,27 @@ def check_average_table(msgs_np, d, n, lev, scale, out_gpu, prior=None):
         assert np.linalg.norm(got[sl] - want[sl]) <= 1e-6 * np.linalg.norm(want[sl]) + 2.0 ** -149 * np.sqrt(n)
 
 
+@pytest.mark.parametrize("d,n,S,K", [(100_000, 8192, 256, 1), (100_000, 8192, 256, 3), (40_000, 512, 128, 1),
+                                     (70_001, 16384, 512, 4), (9_999, 1001, 0, 1), (66_000, 2048, 64, 1)])
+def test_table_of_the_main_levels_decodes_like_the_main_path(g, d, n, S, K):
+    """The level table 2^(j-1-s) through the table decoder (tile kernel, every K) against the main entry point
+    (for K = 1 the kernel that stores values directly; 4096-coordinate tiles for large buckets of few workers):
+    the same bits, written and added."""
+    nuq = g.nuq
+    s = 3
+    rng = np.random.default_rng(d + n + K)
+    vs = [torch.from_numpy(make_vector("mixed", d, n, rng)).to(g.DEV) for _ in range(K)]
+    msgs = g.batched_encode(vs, n, s, list(range(K)), S)
+    lev = [0.0] + [2.0 ** (j - 1 - s) for j in range(1, s + 2)]
+    prior = torch.from_numpy(rng.standard_normal(d).astype(np.float32)).to(g.DEV)
+    for accumulate in (False, True):
+        a, b = prior.clone(), prior.clone()
+        nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, accumulate, a)
+        nuq.nuq_decode_accumulate_table(msgs, d, n, lev, S, 1.0 / K, accumulate, b)
+        assert torch.equal(a, b)
+    assert nuq.nuq_last_error_flags() == 0
+
+
 def test_uniform_levels_at_benchmark_size(g):
     """Config 3's shape (ResNet-50-sized gradient, bucket 8192) with QSGD's uniform levels and the maximum norm
     (QSGDinf), one worker at full size: bytes bit-exact on sampled buckets, the rest by count."""
