@@ -238,6 +238,55 @@ def test_update_modes_on_random_shapes(g, d, n, S, K, shift):
     assert torch.equal(w1, w2) and torch.equal(y1, y2)
 
 
+def test_step_with_momentum_replayed_from_a_hip_graph(g):
+    """Encode of K workers, the momentum rule inside the decoder and a single-message decode captured into one HIP
+    graph; every replay (with eager work and synchronizations in between) must leave the bits the same calls leave
+    when made eagerly."""
+    nuq = g.nuq
+    d, n, s, S, K, alpha, mu, l = 150_000, 8192, 3, 256, 3, 0.2, 0.7, 1.0
+    rng = np.random.default_rng(21)
+    vs = [torch.from_numpy(make_vector("gauss", d, n, rng)).to(g.DEV) for _ in range(K)]
+    seeds = [5 + k for k in range(K)]
+    w0 = torch.from_numpy(rng.standard_normal(d).astype(np.float32)).to(g.DEV)
+
+    def make():
+        buf = _sgd().MessageBuffers(K, d, n, s, S, g.DEV)
+        return buf, w0.clone(), w0.clone(), torch.empty(d, dtype=torch.float32, device=g.DEV)
+
+    def step(buf, w, y, single):
+        nuq.nuq_quantize_encode_batch(vs, n, s, seeds, S, buf.messages, buf.workspace)
+        nuq.nuq_decode_momentum_step(buf.messages, d, n, s, S, 1.0 / K, alpha, mu, l, w, y)
+        nuq.nuq_decode_accumulate(buf.messages[:1], d, n, s, S, 1.0, False, single)
+
+    eb, ew, ey, es = make()
+    gb, gw, gy, gs = make()
+    step(eb, ew.clone(), ey.clone(), es)                     # warm-up outside the capture (first-call set-up)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(gb, gw, gy, gs)
+    torch.cuda.current_stream().wait_stream(side)
+    gw.copy_(w0)                                             # (capture does not run the kernels; start both from w0)
+    gy.copy_(w0)
+    for rep in range(3):
+        gs.fill_(7.0)
+        for m in gb.messages:
+            m.words.zero_()
+            m.bit_off.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        step(eb, ew, ey, es)
+        torch.cuda.synchronize()
+        assert torch.equal(gw, ew) and torch.equal(gy, ey) and torch.equal(gs, es), rep
+        for a, b in zip(gb.messages, eb.messages):
+            nw = (int(b.bit_off[-1].item()) + 31) // 32
+            assert torch.equal(a.bit_off, b.bit_off) and torch.equal(a.words[:nw], b.words[:nw])
+    assert nuq.nuq_last_error_flags() == 0
+    assert not torch.equal(gw, w0)
+
+
 def test_updates_at_benchmark_size(g):
     """Config 3 at full size, launched as bench.py --update launches it: one step of the plain rule and one of the
     momentum rule inside the decoder, compared on sampled runs of buckets that the oracle computes one by one."""
