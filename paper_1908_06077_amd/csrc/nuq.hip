@@ -174,11 +174,15 @@ int launch_finish(const EncodeParams &P, const EncodeBatch &Wk, uint32_t K, cons
         prefix = w.chunk_sums;
     }
     const uint32_t fb = finish_buckets(P.bucket);
-    const dim3 fgrid((uint32_t)((nb + fb - 1) / fb), K);
+    // groups of fb buckets per workgroup: one where there are few (every workgroup slot of the chip gets work), up
+    // to 8 where there are many (the sum of the lengths before a workgroup's first bucket is then paid once per 8)
+    const uint64_t ngroups = (nb + fb - 1) / fb;
+    const uint32_t per_wg = (uint32_t)std::min<uint64_t>(8, std::max<uint64_t>(1, ngroups * K / 16384));
+    const dim3 fgrid((uint32_t)((ngroups + per_wg - 1) / per_wg), K);
     if (fb == 64u)
-        hipLaunchKernelGGL(k_finish<64>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks);
+        hipLaunchKernelGGL(k_finish<64>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks, per_wg);
     else
-        hipLaunchKernelGGL(k_finish<16>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks);
+        hipLaunchKernelGGL(k_finish<16>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks, per_wg);
     return check_launch();
 }
 

@@ -805,27 +805,25 @@ __host__ __device__ inline uint32_t finish_buckets(uint32_t bucket) { return buc
 // grid (ceil(nb / FB), K), FB = 16 or 64.  chunk_prefix == nullptr: sum the lengths of all earlier buckets directly.
 template <uint32_t FB>
 __global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, const uint64_t *chunk_prefix,
-                                                uint64_t nchunks)
+                                                uint64_t nchunks, uint32_t groups)
 {
     static_assert(FB == 16 || FB == 64, "one wave scans the workgroup's word counts");
     __shared__ uint64_t scratch[4];
-    __shared__ uint32_t wstart[FB + 1];   // first word of each bucket, relative to the workgroup's first
+    __shared__ uint32_t wstart[FB + 1];   // first word of each bucket, relative to the group's first
     __shared__ uint32_t skip[FB];
     const EncodeWorker &W = Wk.w[blockIdx.y];
     const uint32_t *__restrict__ lens = P.lens + (uint64_t)blockIdx.y * P.nb_stride;
-    const uint64_t b_first = (uint64_t)blockIdx.x * FB;
     const uint32_t tid = threadIdx.x;
 
-    // words before this workgroup's first bucket
+    // A workgroup takes `groups` consecutive groups of FB buckets: the words before its first bucket are summed once
+    // (from the chunk's start), after that the running total carries over from group to group.
+    uint64_t b_first = (uint64_t)blockIdx.x * groups * FB;
     uint64_t lo = 0, base = 0;
     if (chunk_prefix) {
         const uint64_t c = b_first / kChunk;
         lo = c * kChunk;
         base = chunk_prefix[(uint64_t)blockIdx.y * (nchunks + 1) + c];
     }
-    uint32_t my_len = 0;
-    if (tid < FB && b_first + tid < P.nb)
-        my_len = lens[b_first + tid];
     uint32_t part = 0;     // < 2^32: at most 8192 lengths of < 2^21 bits each are summed here
     {
         // lo and b_first are multiples of 16, so the range splits into aligned groups of four lengths
@@ -838,44 +836,52 @@ __global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, 
         }
     }
     base += block_sum_u64(part, scratch);
-    if (tid < kWave) {                      // the first wave: inclusive scan of the word counts
-        uint32_t inc = tid < FB ? (my_len + 31u) >> 5 : 0u;
-#pragma unroll
-        for (int off = 1; off < (int)FB; off <<= 1) {
-            const uint32_t t = (uint32_t)__shfl_up((int)inc, off, kWave);
-            if ((int)tid >= off)
-                inc += t;
-        }
-        if (tid < FB)
-            wstart[tid + 1] = inc;
-        if (tid == 0)
-            wstart[0] = 0;
-    }
-    __syncthreads();
-    if (tid < FB && b_first + tid < P.nb) {
-        const uint64_t start = base + wstart[tid];
-        W.bit_off[b_first + tid + 1] = 32ull * start + my_len;
-        if (b_first + tid == 0)
-            W.bit_off[0] = 0;
-        const bool over = base + wstart[tid + 1] > W.words_cap;
-        skip[tid] = over;
-        if (over && my_len)
-            atomicOr(P.flags, kFlagCapacity);
-    }
-    __syncthreads();
 
-    // copy the staging slots: word w of the workgroup's run belongs to the bucket found by bisection
-    const uint32_t total = wstart[FB];
-    const uint32_t *__restrict__ staging = P.staging + ((uint64_t)blockIdx.y * P.nb + b_first) * P.slot_words;
-    uint32_t *__restrict__ dst = W.words + base;
-#pragma unroll 4
-    for (uint32_t w = tid; w < total; w += 256u) {
-        uint32_t j = 0;
+    for (uint32_t g = 0; g < groups && b_first < P.nb; ++g, b_first += FB) {
+        uint32_t my_len = 0;
+        if (tid < FB && b_first + tid < P.nb)
+            my_len = lens[b_first + tid];
+        if (tid < kWave) {                      // the first wave: inclusive scan of the word counts
+            uint32_t inc = tid < FB ? (my_len + 31u) >> 5 : 0u;
 #pragma unroll
-        for (uint32_t step = FB / 2; step >= 1; step >>= 1)
-            j += (wstart[j + step] <= w) ? step : 0u;
-        if (!skip[j])
-            dst[w] = staging[(uint64_t)j * P.slot_words + (w - wstart[j])];
+            for (int off = 1; off < (int)FB; off <<= 1) {
+                const uint32_t t = (uint32_t)__shfl_up((int)inc, off, kWave);
+                if ((int)tid >= off)
+                    inc += t;
+            }
+            if (tid < FB)
+                wstart[tid + 1] = inc;
+            if (tid == 0)
+                wstart[0] = 0;
+        }
+        __syncthreads();
+        if (tid < FB && b_first + tid < P.nb) {
+            const uint64_t start = base + wstart[tid];
+            W.bit_off[b_first + tid + 1] = 32ull * start + my_len;
+            if (b_first + tid == 0)
+                W.bit_off[0] = 0;
+            const bool over = base + wstart[tid + 1] > W.words_cap;
+            skip[tid] = over;
+            if (over && my_len)
+                atomicOr(P.flags, kFlagCapacity);
+        }
+        __syncthreads();
+
+        // copy the staging slots: word w of the group's run belongs to the bucket found by bisection
+        const uint32_t total = wstart[FB];
+        const uint32_t *__restrict__ staging = P.staging + ((uint64_t)blockIdx.y * P.nb + b_first) * P.slot_words;
+        uint32_t *__restrict__ dst = W.words + base;
+#pragma unroll 4
+        for (uint32_t w = tid; w < total; w += 256u) {
+            uint32_t j = 0;
+#pragma unroll
+            for (uint32_t step = FB / 2; step >= 1; step >>= 1)
+                j += (wstart[j + step] <= w) ? step : 0u;
+            if (!skip[j])
+                dst[w] = staging[(uint64_t)j * P.slot_words + (w - wstart[j])];
+        }
+        base += total;
+        __syncthreads();          // wstart and skip are read to the end before the next group overwrites them
     }
 }
 
