@@ -179,10 +179,12 @@ int launch_finish(const EncodeParams &P, const EncodeBatch &Wk, uint32_t K, cons
     const uint64_t ngroups = (nb + fb - 1) / fb;
     const uint32_t per_wg = (uint32_t)std::min<uint64_t>(8, std::max<uint64_t>(1, ngroups * K / 16384));
     const dim3 fgrid((uint32_t)((ngroups + per_wg - 1) / per_wg), K);
-    if (fb == 64u)
-        hipLaunchKernelGGL(k_finish<64>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks, per_wg);
+    if (fb == 64u && per_wg > 1u)        // many small groups: one wave per workgroup, four times the groups in flight
+        hipLaunchKernelGGL((k_finish<64, 64>), fgrid, dim3(64), 0, st, P, Wk, prefix, nchunks, per_wg);
+    else if (fb == 64u)
+        hipLaunchKernelGGL((k_finish<64, 256>), fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks, per_wg);
     else
-        hipLaunchKernelGGL(k_finish<16>, fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks, per_wg);
+        hipLaunchKernelGGL((k_finish<16, 256>), fgrid, dim3(256), 0, st, P, Wk, prefix, nchunks, per_wg);
     return check_launch();
 }
 

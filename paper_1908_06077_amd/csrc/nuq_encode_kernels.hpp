@@ -803,11 +803,12 @@ __global__ __launch_bounds__(256) void k_chunk_scan(uint64_t *chunk_sums, uint64
 __host__ __device__ inline uint32_t finish_buckets(uint32_t bucket) { return bucket <= 1024u ? 64u : 16u; }
 
 // grid (ceil(nb / FB), K), FB = 16 or 64.  chunk_prefix == nullptr: sum the lengths of all earlier buckets directly.
-template <uint32_t FB>
-__global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, const uint64_t *chunk_prefix,
+template <uint32_t FB, uint32_t WG>
+__global__ __launch_bounds__(WG) void k_finish(EncodeParams P, EncodeBatch Wk, const uint64_t *chunk_prefix,
                                                 uint64_t nchunks, uint32_t groups)
 {
     static_assert(FB == 16 || FB == 64, "one wave scans the workgroup's word counts");
+    static_assert(WG == 64 || WG == 256, "block_sum_u64 adds four waves");
     __shared__ uint64_t scratch[4];
     __shared__ uint32_t wstart[FB + 1];   // first word of each bucket, relative to the group's first
     __shared__ uint32_t skip[FB];
@@ -830,12 +831,20 @@ __global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, 
         const uint4 *__restrict__ l4 = reinterpret_cast<const uint4 *>(lens + lo);
         const uint32_t n4 = (uint32_t)((b_first - lo) >> 2);
 #pragma unroll 4
-        for (uint32_t i = tid; i < n4; i += 256u) {
+        for (uint32_t i = tid; i < n4; i += WG) {
             const uint4 v = l4[i];
             part += ((v.x + 31u) >> 5) + ((v.y + 31u) >> 5) + ((v.z + 31u) >> 5) + ((v.w + 31u) >> 5);
         }
     }
-    base += block_sum_u64(part, scratch);
+    if constexpr (WG == 64u) {            // one wave
+        uint64_t x = part;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1)
+            x += __shfl_xor((unsigned long long)x, off, kWave);
+        base += x;
+    } else {
+        base += block_sum_u64(part, scratch);
+    }
 
     for (uint32_t g = 0; g < groups && b_first < P.nb; ++g, b_first += FB) {
         uint32_t my_len = 0;
@@ -872,7 +881,7 @@ __global__ __launch_bounds__(256) void k_finish(EncodeParams P, EncodeBatch Wk, 
         const uint32_t *__restrict__ staging = P.staging + ((uint64_t)blockIdx.y * P.nb + b_first) * P.slot_words;
         uint32_t *__restrict__ dst = W.words + base;
 #pragma unroll 4
-        for (uint32_t w = tid; w < total; w += 256u) {
+        for (uint32_t w = tid; w < total; w += WG) {
             uint32_t j = 0;
 #pragma unroll
             for (uint32_t step = FB / 2; step >= 1; step >>= 1)
