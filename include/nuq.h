@@ -144,9 +144,12 @@ int nuq_quantize_encode_batch(uint32_t K, const float *const *v, const uint64_t 
  * worker, all encoded with the same d, bucket, s, sync_stride); sync may be NULL or hold
  * NULLs when sync_stride == 0.  1 <= K <= NUQ_MAX_WORKERS; average with scale = 1/K.
  * The sum over workers is taken in fp64 (in no fixed order, which cannot change it unless the
- * terms' exponents span more than 2^29), scaled in fp64 and rounded to fp32 once.  out: d floats.
- * A record that leaves its bucket's bit range or index range, or a level index outside
- * 1..s+1, raises NUQ_FLAG_MALFORMED and ends that bucket's decoding. */
+ * terms' exponents span more than 2^29), scaled in fp64 and rounded to fp32 once; with accumulate the
+ * old out[i] is then added in fp32.  out: d floats.
+ * A record that leaves its bucket's bit range or index range, a level index outside 1..s+1, or a
+ * sync entry that contradicts the bit offsets raises NUQ_FLAG_MALFORMED and ends that part's
+ * decoding.  bit_off itself is trusted to point inside words (words carries no length here): pass
+ * the encoder's arrays, or check bit_off[B] against the words received before calling. */
 int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
                           const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
                           uint32_t bucket, uint32_t s, uint32_t sync_stride, float scale,
