@@ -677,6 +677,10 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
     while ((2u << P.lanes_shift) * max_streams <= 64u)
         ++P.lanes_shift;
     P.stream_cap = kWordsPerLane << P.lanes_shift;
+    // An odd stride when a tile has many streams (small buckets): lanes of different streams stand at like offsets,
+    // and with a stride of 8 or 16 words they would read the same few banks (config 5: -5 %).  With few, long
+    // streams the word given up costs more than the conflicts (config 4: +4 %), so those keep the full stride.
+    P.stream_stride = max_streams >= 16u ? P.stream_cap - 1u : P.stream_cap;
     const uint32_t resident = decode_resident_workgroups(variant);
     if (!resident)
         return NUQ_EHIP;

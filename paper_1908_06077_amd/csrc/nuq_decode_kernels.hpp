@@ -55,7 +55,8 @@ struct DecodeParams {
     uint32_t segs_per_tile;     // segments of one bucket inside a tile
     uint32_t xcd_base, xcd_rem; // ntiles / 8, ntiles % 8: see xcd_tile
     uint32_t lanes_shift;       // log2 of the lanes that copy one stream's words
-    uint32_t stream_cap;        // LDS words reserved per stream = kWordsPerLane << lanes_shift
+    uint32_t stream_cap;        // words the lanes of a stream carry = kWordsPerLane << lanes_shift
+    uint32_t stream_stride;     // LDS words per stream: stream_cap, or stream_cap - 1 (odd) for tiles of many streams
     float scale;
     float *yl;                  // kUpdateMomentum: y^l of the previous step, replaced by this step's
     double alpha, la, mu;       // kUpdateMomentum: step size, l * step size, momentum parameter
@@ -523,6 +524,8 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         lev = lev_s;
     }
 
+    // words per stream in the staging area (big tiles have few, long streams and always use the full stride)
+    const uint32_t stream_stride = TC == kTileCoordsBig ? P.stream_cap : P.stream_stride;
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & (kWave - 1u);
     const bool parser = tid < kWave;                  // first wave parses, second wave prepares
@@ -600,9 +603,9 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         U.bit_hi = bit_hi - S.bit0;
         U.norm = m.norm;
         const uint32_t sidx = bi * P.K + k;
-        if (S.nwords <= P.stream_cap && sidx < kMaxStreams) {
+        if (S.nwords <= stream_stride && sidx < kMaxStreams) {
             U.kind = 1;
-            U.stage_off = sidx * P.stream_cap;
+            U.stage_off = sidx * stream_stride;
         } else {                                  // did not fit in LDS: read the words from global memory
             U.kind = 2;
             U.first_word = S.first_word;
@@ -723,7 +726,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         const uint32_t *src = s_words;
         if (my_stream < G.nstreams && !walk) {
             const StreamPart S = stream_part(P, G, sr.bo0, sr.bo1, sr.e0, sr.e1);
-            cnt = min(S.nwords, P.stream_cap);
+            cnt = min(S.nwords, stream_stride);
             src = s_words + S.first_word;
         }
 #pragma unroll
@@ -743,10 +746,14 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     };
     // ... and from the registers to the staging area, once the parse that read it is over
     auto store_words = [&](const uint32_t (&w)[kWordsPerLane]) {
-        const uint32_t base = 1u + my_stream * P.stream_cap + my_sub;     // <= kStageWords for every lane
+        const uint32_t base = 1u + my_stream * stream_stride + my_sub;    // + word index < kStageWords for every lane
 #pragma unroll
-        for (uint32_t i = 0; i < kWordsPerLane; ++i)
+        for (uint32_t i = 0; i + 1u < kWordsPerLane; ++i)
             stage[base + (i << P.lanes_shift)] = w[i];
+        // only the very last carried word of a stream can be the one an odd stride has no place for
+        constexpr uint32_t kLast = kWordsPerLane - 1u;
+        if (TC == kTileCoordsBig || my_sub + (kLast << P.lanes_shift) < stream_stride)
+            stage[base + (kLast << P.lanes_shift)] = w[kLast];
     };
 
     // ---- prologue
