@@ -125,6 +125,21 @@ int nuq_quantize_encode(const float *v, uint64_t d, uint32_t bucket, uint32_t s,
                         uint64_t words_cap, uint32_t *sync, void *workspace,
                         uint64_t workspace_bytes, nuq_stream_t stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): nuq_quantize_encode with the workspace in a device array that is part of
+ * the library itself, NUQ_STATIC_WORKSPACE_BYTES per GPU, held from the library's load to the end of
+ * the process.  Same arguments otherwise, same kernels, same outputs bit for bit.  The call allocates
+ * and frees nothing; its first call on a device looks the array's address up (make that call outside a
+ * capture).  Sizes with nuq_encode_workspace_bytes(1, d, bucket, s) > NUQ_STATIC_WORKSPACE_BYTES are
+ * rejected with NUQ_ECAPACITY before anything is enqueued (bucket 8192, s <= 5: up to 33.5 M
+ * coordinates).  All calls on one GPU share the one array: calls that overlap in time (different
+ * streams, or threads) race; calls on one stream do not.  Nothing in it has to be cleared between
+ * calls: every word a call reads was written by that call. */
+#define NUQ_STATIC_WORKSPACE_BYTES (32u << 20)
+int nuq_quantize_encode_static(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64_t seed,
+                               uint32_t sync_stride, float *norms, uint64_t *bit_off, uint32_t *words,
+                               uint64_t words_cap, uint32_t *sync, nuq_stream_t stream);
+
 /* The same for K workers' gradients in one launch (the K simulated workers of Alg. 1 on one
  * device).  v, norms, bit_off, words, sync: HOST arrays of K device pointers; seeds, words_cap:
  * HOST arrays of K values.  Worker k's message equals what

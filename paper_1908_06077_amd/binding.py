@@ -33,6 +33,7 @@ _SIGNATURES = {
     "nuq_quantize": (_i32, [_vp, _u64, _u32, _u32, _u64, _vp, _vp, _vp]),
     "nuq_encode": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
     "nuq_quantize_encode": (_i32, [_vp, _u64, _u32, _u32, _u64, _u32, _vp, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
+    "nuq_quantize_encode_static": (_i32, [_vp, _u64, _u32, _u32, _u64, _u32, _vp, _vp, _vp, _u64, _vp, _vp]),
     "nuq_decode_accumulate": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _i32, _vp, _vp]),
     "nuq_bucket_norms_linf": (_i32, [_vp, _u64, _u32, _vp, _vp]),
     "nuq_quantize_table": (_i32, [_vp, _u64, _u32, _u32, _vp, _u64, _vp, _vp, _vp]),
@@ -159,6 +160,18 @@ def nuq_quantize_encode(v: torch.Tensor, bucket: int, s: int, seed: int, sync_st
                                     _ptr(norms, torch.float32), _ptr(bit_off, torch.int64),
                                     _ptr(words, torch.int32), words.numel(), _ptr(sync), _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream()))
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def nuq_quantize_encode_static(v: torch.Tensor, bucket: int, s: int, seed: int, sync_stride: int, norms: torch.Tensor,
+                               bit_off: torch.Tensor, words: torch.Tensor, sync: torch.Tensor | None) -> None:
+    """nuq_quantize_encode with the library's own workspace: the call allocates nothing."""
+    _check("nuq_quantize_encode_static",
+           _lib.nuq_quantize_encode_static(_ptr(v, torch.float32), v.numel(), bucket, s, seed & (2 ** 64 - 1),
+                                           sync_stride, _ptr(norms, torch.float32), _ptr(bit_off, torch.int64),
+                                           _ptr(words, torch.int32), words.numel(), _ptr(sync), _stream()))
 
 
 def nuq_quantize_encode_batch(vs: list[torch.Tensor], bucket: int, s: int, seeds: list[int], sync_stride: int,

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <type_traits>
 #include <vector>
 
@@ -17,9 +18,32 @@
 #include "nuq_sgd_kernels.hpp"
 #include "nuq_table_kernels.hpp"
 
+// Workspace of nuq_quantize_encode_static, the entry point that allocates nothing: staging slots, bit lengths and
+// partial sums of the encoder's kernels.  Each device that loads the library holds its own copy until the process
+// ends.  In host code this name only stands for the symbol: the device address comes from hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[NUQ_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 using namespace nuq;
+
+// Address of `scratch` on the current device, looked up once per device (with that device current) and kept.
+void *static_workspace_ptr()
+{
+    static std::mutex mu;
+    static void *ptrs[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p)
+            return nullptr;
+        ptrs[dev] = p;
+    }
+    return ptrs[dev];
+}
 
 // Sticky error flags, one word per device (each device holds its own copy of the symbol).
 __device__ uint32_t g_flags;
@@ -560,6 +584,22 @@ int nuq_quantize_encode(const float *v, uint64_t d, uint32_t bucket, uint32_t s,
     Wk.w[0].words_cap = words_cap;
     Wk.w[0].sync = sync;
     return encode_batch<0>(1, Wk, d, bucket, s, sync_stride, workspace, workspace_bytes, stream);
+}
+
+int nuq_quantize_encode_static(const float *v, uint64_t d, uint32_t bucket, uint32_t s, uint64_t seed,
+                               uint32_t sync_stride, float *norms, uint64_t *bit_off, uint32_t *words,
+                               uint64_t words_cap, uint32_t *sync, nuq_stream_t stream)
+{
+    const uint64_t need = nuq_encode_workspace_bytes(1, d, bucket, s);
+    if (!need)
+        return NUQ_EINVAL;
+    if (need > NUQ_STATIC_WORKSPACE_BYTES)
+        return NUQ_ECAPACITY;
+    void *ws = static_workspace_ptr();
+    if (!ws)
+        return NUQ_EHIP;
+    return nuq_quantize_encode(v, d, bucket, s, seed, sync_stride, norms, bit_off, words, words_cap, sync, ws,
+                               NUQ_STATIC_WORKSPACE_BYTES, stream);
 }
 
 int nuq_quantize_encode_batch(uint32_t K, const float *const *v, const uint64_t *seeds, uint64_t d, uint32_t bucket,
