@@ -22,7 +22,6 @@ _SRC = os.path.join(_HERE, "nuq_oracle.c")
 _LIB = os.path.join(_HERE, "libnuq_oracle.so")
 
 OK, EINVAL, ECAPACITY, EMALFORMED = 0, -1, -2, -5
-SYNC_EMPTY = 0x80000000
 
 
 def build(force: bool = False) -> str:
@@ -71,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.nuqo_erc_decode.restype = i32
         L.nuqo_encode.argtypes = [vp, u64, u32, i32, u32, vp, vp, u64, vp]
         L.nuqo_encode.restype = i32
+        L.nuqo_num_sync.argtypes = [u32, u32]
+        L.nuqo_num_sync.restype = u64
         L.nuqo_decode_levels.argtypes = [vp, vp, u64, u32, i32, vp]
         L.nuqo_decode_levels.restype = i32
         L.nuqo_decode_average.argtypes = [u32, vp, vp, vp, u64, u32, i32, ctypes.c_double, i32, vp]
@@ -111,7 +112,25 @@ def num_buckets(d: int, bucket: int) -> int:
     return (d + bucket - 1) // bucket
 
 
+SYNC_BLOCK = 2048
+
+
+def sync_pieces(bucket: int, sync_stride: int) -> int:
+    """Pieces per block of the decoder index: the smallest power of two >= min(bucket, 2048) / sync_stride."""
+    need = (min(bucket, SYNC_BLOCK) + sync_stride - 1) // sync_stride
+    P = 1
+    while P < need:
+        P *= 2
+    return P
+
+
 def num_sync(bucket: int, sync_stride: int) -> int:
+    """Decoder index entries per bucket of an ERC message: blocks of 2048 coordinates times pieces per block."""
+    return int(lib().nuqo_num_sync(bucket, sync_stride))
+
+
+def num_sync_huffman(bucket: int, sync_stride: int) -> int:
+    """Index entries per bucket of a Huffman-coded message: one per multiple of the stride inside the bucket."""
     return 0 if sync_stride == 0 else (bucket + sync_stride - 1) // sync_stride - 1
 
 
@@ -439,7 +458,7 @@ def encode_huffman(q: np.ndarray, bucket: int, s: int, lengths, sync_stride: int
     cap = (d * 16 + 31) // 32 + nb
     bit_off = np.zeros(nb + 1, dtype=np.uint64)
     words = np.zeros(max(cap, 1), dtype=np.uint32)
-    ns = num_sync(bucket, sync_stride)
+    ns = num_sync_huffman(bucket, sync_stride)
     sync = np.zeros(max(nb * ns, 1), dtype=np.uint32)
     rc = lib().nuqo_encode_huffman(_p(q), d, bucket, s, sync_stride, _p(lengths), _p(bit_off), _p(words), cap, _p(sync))
     if rc:

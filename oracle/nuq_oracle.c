@@ -372,9 +372,35 @@ int nuqo_erc_decode(const uint32_t *words, uint64_t *pos, uint64_t end, uint64_t
 
 /* ------------------------------------------------------------------ ENCODE */
 
-#define NUQO_SYNC_EMPTY 0x80000000u
+/*
+ * Decoder index (this project's addition to the message; the bit strings do not
+ * depend on it).  A bucket is cut into blocks of NUQO_SYNC_BLOCK = 2048
+ * coordinates and the records of every block into P pieces of equal count, so
+ * that a parallel decoder can hand the pieces of a block to threads that all get
+ * the same number of records.  P = the smallest power of two that is at least
+ * min(bucket, 2048) / sync_stride: sync_stride is the mean number of coordinates
+ * per piece.  A bucket has nblk * P entries, nblk = ceil(bucket / 2048).
+ */
+#define NUQO_SYNC_BLOCK 2048u
 
-static uint64_t num_sync(uint32_t bucket, uint32_t sync_stride)
+static uint32_t sync_pieces(uint32_t bucket, uint32_t sync_stride)
+{
+    uint32_t span = bucket < NUQO_SYNC_BLOCK ? bucket : NUQO_SYNC_BLOCK;
+    uint32_t need = (span + sync_stride - 1) / sync_stride, P = 1;
+    while (P < need)
+        P *= 2;
+    return P;
+}
+
+uint64_t nuqo_num_sync(uint32_t bucket, uint32_t sync_stride)
+{
+    if (sync_stride == 0 || bucket == 0)
+        return 0;
+    return (uint64_t)((bucket + NUQO_SYNC_BLOCK - 1) / NUQO_SYNC_BLOCK) * sync_pieces(bucket, sync_stride);
+}
+
+/* Index entries per bucket of the Huffman-coded message: one per multiple of the stride inside the bucket. */
+static uint64_t num_sync_coords(uint32_t bucket, uint32_t sync_stride)
 {
     if (sync_stride == 0)
         return 0;
@@ -395,16 +421,16 @@ static uint64_t num_sync(uint32_t bucket, uint32_t sync_stride)
  * boundary at or after bit_off[b] and end (exclusive) at bit_off[b+1]; pad bits
  * are zero.  words must hold words_cap zero-initialised entries on entry.
  *
- * sync (may be NULL when sync_stride == 0): for bucket b and segment
- * g = 1 .. ceil(bucket/sync_stride)-1, entry sync[b*nsync + g-1] describes the
- * first record whose coordinate index (0-based, inside the bucket) is >= g*S:
- * bits 0..20 = bit offset of that record from the bucket's first bit (the
- * bucket's bit length if there is no such record); if that record's index is
- * inside [g*S, (g+1)*S), bits 21..30 = index - g*S and bit 31 = 0; otherwise
- * (segment g holds no nonzero) bits 21..30 = 0 and bit 31 = 1.  It lets a
- * decoder enter the bucket's bit string at a segment boundary and tells it
- * which bits belong to which run of segments; the bit string itself does not
- * depend on it.
+ * sync (may be NULL when sync_stride == 0), nsync = nuqo_num_sync entries per
+ * bucket: number the bucket's records 0 .. N-1 in index order; block t holds
+ * the n_t records whose index is in [2048 t, 2048 (t+1)), the first of them
+ * being record f_t (f_t = number of records before the block).  Entry (t, g),
+ * g = 0 .. P-1, stored at sync[b*nsync + t*P + g], describes record
+ * r = f_t + floor(g * n_t / P): bits 0..20 = bit offset of record r from the
+ * bucket's first bit (the bucket's bit length if r = N); bits 21..31 = index of
+ * record r minus 2048 t if n_t > 0, else 0.  Piece (t, g) is the records from
+ * entry (t, g)'s up to, not including, the next entry's (entry (t, g+1), or
+ * (t+1, 0), or the bucket's end): floor((g+1) n_t / P) - floor(g n_t / P) of them.
  *
  * Returns 0, or NUQO_ECAPACITY if words_cap is too small, NUQO_EINVAL on bad
  * arguments or a level index above s+1.
@@ -417,51 +443,77 @@ int nuqo_encode(const uint8_t *q, uint64_t d, uint32_t bucket, int s, uint32_t s
     if (sync_stride != 0 && (sync_stride > 1024 || (sync_stride & (sync_stride - 1))))
         return NUQO_EINVAL;
     uint64_t nb = (d + bucket - 1) / bucket;
-    uint64_t nsync = num_sync(bucket, sync_stride);
+    uint64_t nsync = nuqo_num_sync(bucket, sync_stride);
+    uint32_t P = nsync ? sync_pieces(bucket, sync_stride) : 0;
+    uint64_t *rec_idx = NULL, *rec_off = NULL; /* index and bit offset of the bucket's records, for the entries */
+    if (nsync) {
+        rec_idx = (uint64_t *)malloc(sizeof(uint64_t) * bucket);
+        rec_off = (uint64_t *)malloc(sizeof(uint64_t) * bucket);
+        if (!rec_idx || !rec_off) {
+            free(rec_idx);
+            free(rec_off);
+            return NUQO_EINVAL;
+        }
+    }
+    int rc = NUQO_OK;
     uint64_t end_prev = 0;
     bit_off[0] = 0;
     char code[96];
-    for (uint64_t b = 0; b < nb; b++) {
+    for (uint64_t b = 0; b < nb && rc == NUQO_OK; b++) {
         uint64_t lo = b * bucket, hi = lo + bucket < d ? lo + bucket : d;
         uint64_t start = (end_prev + 31) / 32 * 32;
         uint64_t t = start;
         int64_t prev = -1; /* 0-based index of the previous nonzero; t_0 = 0 in 1-based terms */
-        uint64_t next_g = 1; /* first segment whose entry is not written yet */
+        uint64_t N = 0;    /* records so far */
         for (uint64_t i = lo; i < hi; i++) {
             int j = q[i] & 0x7f;
             if (j == 0)
                 continue;
-            if (j > s + 1)
-                return NUQO_EINVAL;
-            int64_t idx = (int64_t)(i - lo);
-            /* this record is the first one at or after g*S for every pending g with g*S <= idx */
-            while (next_g <= nsync && next_g * sync_stride <= (uint64_t)idx) {
-                uint32_t e = (uint32_t)(t - start);
-                if ((uint64_t)idx < (next_g + 1) * sync_stride)
-                    e |= (uint32_t)((uint64_t)idx - next_g * sync_stride) << 21;
-                else
-                    e |= NUQO_SYNC_EMPTY;
-                sync[b * nsync + next_g - 1] = e;
-                next_g++;
+            if (j > s + 1) {
+                rc = NUQO_EINVAL;
+                break;
             }
+            int64_t idx = (int64_t)(i - lo);
             uint64_t gap = (uint64_t)(idx - prev);
             int glen = nuqo_erc_encode(gap, code);
             int jlen = nuqo_erc_encode((uint64_t)j, code + glen + 1);
             code[glen] = (q[i] & 0x80) ? '1' : '0';
             int len = glen + 1 + jlen;
-            if ((t + len + 31) / 32 > words_cap)
-                return NUQO_ECAPACITY;
+            if ((t + len + 31) / 32 > words_cap) {
+                rc = NUQO_ECAPACITY;
+                break;
+            }
+            if (nsync) {
+                rec_idx[N] = (uint64_t)idx;
+                rec_off[N] = t - start;
+            }
+            N++;
             for (int k = 0; k < len; k++)
                 put_bit(words, t + k, code[k] == '1');
             t += len;
             prev = idx;
         }
-        for (; next_g <= nsync; next_g++) /* no record at or after these boundaries */
-            sync[b * nsync + next_g - 1] = (uint32_t)(t - start) | NUQO_SYNC_EMPTY;
+        if (rc != NUQO_OK)
+            break;
+        uint64_t next = 0; /* first record not yet assigned to a block (records are in index order) */
+        for (uint64_t blk = 0; nsync && blk < nsync / P; blk++) {
+            uint64_t f = next; /* records before the block */
+            while (next < N && rec_idx[next] < (blk + 1) * NUQO_SYNC_BLOCK)
+                next++;
+            uint64_t n = next - f; /* records inside it */
+            for (uint64_t g = 0; g < P; g++) {
+                uint64_t r = f + g * n / P;
+                uint64_t off = r < N ? rec_off[r] : t - start;
+                uint64_t rel = n > 0 ? rec_idx[r] - blk * NUQO_SYNC_BLOCK : 0;
+                sync[b * nsync + blk * P + g] = (uint32_t)(off | (rel << 21));
+            }
+        }
         bit_off[b + 1] = t;
         end_prev = t;
     }
-    return NUQO_OK;
+    free(rec_idx);
+    free(rec_off);
+    return rc;
 }
 
 /* ------------------------------------------------------------------ DECODE */
@@ -701,7 +753,7 @@ int nuqo_encode_huffman(const uint8_t *q, uint64_t d, uint32_t bucket, int s, ui
     uint32_t codes[16];
     if (nuqo_huffman_codes(lengths, s, codes))
         return NUQO_EINVAL;
-    uint64_t nb = (d + bucket - 1) / bucket, nsync = num_sync(bucket, sync_stride);
+    uint64_t nb = (d + bucket - 1) / bucket, nsync = num_sync_coords(bucket, sync_stride);
     uint64_t t = 0;
     memset(words, 0, words_cap * sizeof(uint32_t));
     bit_off[0] = 0;

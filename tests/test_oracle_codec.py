@@ -130,7 +130,42 @@ def test_encode_capacity_and_bad_level():
     assert oracle.max_words(64, 64, 3) * 32 >= 64 * 8
 
 
-@pytest.mark.parametrize("bucket,s,stride", [(8192, 3, 512), (16384, 7, 1024), (512, 3, 512), (1000, 2, 256), (8192, 4, 0)])
+def erc_read(bits, pos):
+    """Alg. 2's decoder on a '0'/'1' string, written out here so that the index is checked by a reader of its own:
+    N = 1; while the next bit is 1, the next N + 1 bits are the new N; the 0 that follows ends the code."""
+    n = 1
+    while bits[pos] == "1":
+        n, pos = int(bits[pos:pos + n + 1], 2), pos + n + 1
+    return n, pos + 1
+
+
+def test_sync_entries_worked_by_hand():
+    """The decoder index of tests/golden/sync_examples.txt: offsets from Alg. 2's code lengths, pieces by hand."""
+    for row in read_rows("sync_examples.txt"):
+        bucket, s, stride, recs, bits, entries = [f.strip() for f in row.split("|")]
+        bucket, s, stride = int(bucket), int(s), int(stride)
+        q = np.zeros(bucket, np.uint8)
+        if recs != "-":
+            for r in recs.split():
+                idx, lev = r.split(":")
+                q[int(idx)] = abs(int(lev)) | (0x80 if int(lev) < 0 else 0)
+        bit_off, words, sync = oracle.encode(q, bucket, s, stride)
+        assert int(bit_off[1]) == int(bits)
+        assert sync.tolist() == [int(e) for e in entries.split()], row
+        assert oracle.num_sync(bucket, stride) == len(entries.split())
+
+
+def test_num_sync_and_pieces():
+    # blocks of 2048 coordinates, a power-of-two number of pieces of about `stride` coordinates each
+    assert oracle.num_sync(8192, 256) == 4 * 8 and oracle.num_sync(8192, 512) == 4 * 4
+    assert oracle.num_sync(16384, 256) == 8 * 8 and oracle.num_sync(32768, 64) == 16 * 32
+    assert oracle.num_sync(512, 128) == 4 and oracle.num_sync(512, 512) == 1 and oracle.num_sync(100, 512) == 1
+    assert oracle.num_sync(1000, 256) == 4 and oracle.num_sync(1300, 256) == 8      # 6 wanted -> 8
+    assert oracle.num_sync(5000, 1024) == 3 * 2 and oracle.num_sync(8192, 0) == 0
+
+
+@pytest.mark.parametrize("bucket,s,stride", [(8192, 3, 512), (8192, 3, 256), (16384, 7, 1024), (512, 3, 512),
+                                             (512, 3, 128), (1000, 2, 256), (5000, 4, 64), (8192, 4, 0)])
 def test_roundtrip_and_sync_entries(bucket, s, stride):
     rng = np.random.default_rng(bucket + s)
     d = 3 * bucket + bucket // 3
@@ -142,30 +177,40 @@ def test_roundtrip_and_sync_entries(bucket, s, stride):
     np.testing.assert_array_equal(oracle.decode_levels(bit_off, words, d, bucket, s), q)
     ns = oracle.num_sync(bucket, stride)
     assert sync.size == ns * oracle.num_buckets(d, bucket)
-    # every sync entry holds the offset of the first record at or after its boundary: decoding from
-    # there, with the first gap replaced by the recorded position, reproduces that record
+    if not ns:
+        return
+    # What the index promises a decoder, checked without the rule that places the entries: the entries of a bucket
+    # cut its bit string into pieces; decoding piece (t, g) from its entry's offset, with the first index taken from
+    # the entry instead of the first gap code, up to the next entry's offset yields records that all lie in block t;
+    # the pieces of a block together yield exactly the block's records, in order; and their record counts differ by
+    # at most one (that is what the index is for: equal work per piece).
+    P = oracle.sync_pieces(bucket, stride)
+    assert ns % P == 0 and ns // P == (bucket + 2047) // 2048
     for b in range(oracle.num_buckets(d, bucket)):
         seg = q[b * bucket:(b + 1) * bucket]
         start = (int(bit_off[b]) + 31) // 32 * 32
-        nzall = np.flatnonzero(seg & 0x7F)
-        for g in range(1, ns + 1):
-            e = int(sync[b * ns + g - 1])
-            after = nzall[nzall >= g * stride]
-            off = e & 0x1FFFFF
-            if after.size == 0:
-                assert e == (int(bit_off[b + 1]) - start) | oracle.SYNC_EMPTY
-                continue
-            first = int(after[0])
-            if first < (g + 1) * stride:
-                assert (e >> 31) == 0 and ((e >> 21) & 0x3FF) == first - g * stride
-            else:
-                assert (e >> 31) == 1 and ((e >> 21) & 0x3FF) == 0
-            bits = oracle.words_to_bits(words, start + off, int(bit_off[b + 1]))
-            gap, p = oracle.erc_decode(bits)
-            prev = nzall[nzall < first]
-            assert gap == first - (int(prev[-1]) if prev.size else -1)
-            assert bits[p] == ("1" if seg[first] & 0x80 else "0")
-            assert oracle.erc_decode(bits, p + 1)[0] == (seg[first] & 0x7F)
+        length = int(bit_off[b + 1]) - start
+        ent = [int(e) for e in sync[b * ns:(b + 1) * ns]]
+        offs = [e & 0x1FFFFF for e in ent] + [length]
+        assert offs == sorted(offs)
+        for t in range(ns // P):
+            want = [i for i in np.flatnonzero(seg & 0x7F) if 2048 * t <= i < 2048 * (t + 1)]
+            got, counts = [], []
+            for g in range(P):
+                e = t * P + g
+                bits = oracle.words_to_bits(words, start + offs[e], start + offs[e + 1])
+                pos, idx, cnt = 0, None, 0
+                while pos < len(bits):
+                    gap, pos = erc_read(bits, pos)
+                    idx = 2048 * t + (ent[e] >> 21) if idx is None else idx + gap
+                    neg = bits[pos] == "1"
+                    lev, pos = erc_read(bits, pos + 1)
+                    assert seg[idx] == (lev | (0x80 if neg else 0))
+                    got.append(idx)
+                    cnt += 1
+                counts.append(cnt)
+            assert got == want
+            assert max(counts) - min(counts) <= 1
 
 
 def test_decode_rejects_malformed_streams():

@@ -92,7 +92,7 @@ def test_round_trip_lengths_and_sync(bucket, s, S, d):
     codes = oracle.huffman_codes(lengths, s)
     bo, words, sync = oracle.encode_huffman(q, bucket, s, lengths, S)
     np.testing.assert_array_equal(oracle.decode_huffman(bo, words, d, bucket, s, lengths), q)
-    nb, ns = oracle.num_buckets(d, bucket), oracle.num_sync(bucket, S)
+    nb, ns = oracle.num_buckets(d, bucket), oracle.num_sync_huffman(bucket, S)
     lev = (q & 0x7F).astype(np.int64)
     per_coord = lengths.astype(np.int64)[lev] + (lev > 0)
     for b in range(nb):
