@@ -94,7 +94,7 @@ def main():
     if n <= S:
         S = 0
     B = nuq.nuq_num_buckets(d, n)
-    nsync = nuq.nuq_num_sync(n, S)
+    nsync = nuq.nuq_huffman_num_sync(n, S) if args.huffman else nuq.nuq_num_sync(n, S)
 
     grads = [workloads.generate(w, k, dev) for k in range(K)]
     ws = torch.empty(nuq.nuq_encode_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=dev)

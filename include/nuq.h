@@ -28,13 +28,19 @@
  *                 multiple of 32.
  *   words[W]      u32, W = ceil(bit_off[B] / 32).  Stream bit t is bit 31-(t%32) of
  *                 words[t/32].  Pad bits are zero.
- *   sync[B*nsync] u32 decoder index, nsync = nuq_num_sync(bucket, sync_stride).
- *                 Entry (b, g), g = 1..nsync, stored at sync[b*nsync + g-1], describes the
- *                 first record whose in-bucket index is >= g*S:
- *                 bits 0..20 = bit offset of that record from start_b (the bucket's bit
- *                 length if there is none); if its index is below (g+1)*S:
- *                 bits 21..30 = index - g*S, bit 31 = 0; otherwise (segment g holds no
- *                 nonzero) bits 21..30 = 0 and bit 31 (NUQ_SYNC_EMPTY) = 1.
+ *   sync[B*nsync] u32 decoder index (this library's addition to the paper's message; the bit
+ *                 strings do not depend on it), nsync = nuq_num_sync(bucket, sync_stride).  A bucket
+ *                 is cut into blocks of NUQ_SYNC_BLOCK = 2048 coordinates and the records of every
+ *                 block into P pieces of equal record count, P = the smallest power of two that is
+ *                 at least min(bucket, 2048) / sync_stride (sync_stride = mean coordinates per
+ *                 piece); nsync = ceil(bucket / 2048) * P.  With the bucket's records numbered in
+ *                 index order, block t holding n_t of them from record f_t on, entry (t, g),
+ *                 g = 0..P-1, stored at sync[b*nsync + t*P + g], describes record
+ *                 f_t + floor(g * n_t / P): bits 0..20 = its bit offset from start_b (the bucket's
+ *                 bit length if the bucket has no such record), bits 21..31 = its in-bucket index
+ *                 minus 2048 t (0 if n_t = 0).  Piece (t, g) = the records from its entry's up to
+ *                 the next entry's (or the bucket's end): a decoder parses every piece on its own,
+ *                 taking the first record's index from the entry instead of from its gap code.
  *   A record, for a nonzero at in-bucket index i whose previous nonzero is at i_prev
  *   (-1 if none): ERC(i - i_prev), one sign bit (1 = negative), ERC(j).
  */
@@ -67,15 +73,20 @@ enum {
 #define NUQ_MAX_BUCKET 32768u
 #define NUQ_MAX_S 14u
 #define NUQ_MAX_WORKERS 32u /* K per nuq_decode_accumulate call */
-#define NUQ_SYNC_EMPTY 0x80000000u
+#define NUQ_SYNC_BLOCK 2048u /* coordinates per block of the decoder index */
 
 /* ---- sizes (pure host arithmetic, no device work) -------------------------------- */
 
 /* B = ceil(d / bucket); 0 if bucket == 0. */
 uint64_t nuq_num_buckets(uint64_t d, uint32_t bucket);
 
-/* Sync entries per bucket: 0 if sync_stride == 0, else ceil(bucket / sync_stride) - 1. */
+/* Decoder index entries per bucket of an ERC message: 0 if sync_stride == 0 (or not a power of two in
+ * 64..1024), else ceil(bucket / 2048) * P with P as above. */
 uint32_t nuq_num_sync(uint32_t bucket, uint32_t sync_stride);
+
+/* The same for a Huffman-coded message (an entry per multiple of sync_stride inside the bucket):
+ * 0 if sync_stride == 0, else ceil(bucket / sync_stride) - 1. */
+uint32_t nuq_huffman_num_sync(uint32_t bucket, uint32_t sync_stride);
 
 /* Upper bound on W for any input: every coordinate nonzero at the longest level code,
  * i.e. d * (2 + |ERC(s+1)|) bits, plus one word of padding per bucket. */
@@ -262,9 +273,10 @@ uint64_t nuq_encode_huffman_workspace_bytes(uint64_t d, uint32_t bucket);
 /* Message of the bytes q[d] under the code `lengths` (HOST, s + 2 values; NUQ_EINVAL unless they give a
  * complete prefix code): per bucket, for every coordinate in order, the codeword of its level index
  * (most significant bit first), then its sign bit when the level is not zero.  bit_off[B+1], words,
- * word alignment, capacity flag and workspace alignment as for nuq_encode.  sync entry (b, g),
- * g = 1..nsync: bit offset, from the bucket's start, of coordinate g * sync_stride (the bucket's bit
- * length where the bucket ends before it). */
+ * word alignment, capacity flag and workspace alignment as for nuq_encode.  sync[B * nsync],
+ * nsync = nuq_huffman_num_sync(bucket, sync_stride): entry (b, g), g = 1..nsync, at sync[b*nsync + g-1]
+ * = bit offset, from the bucket's start, of coordinate g * sync_stride (the bucket's bit length where
+ * the bucket ends before it). */
 int nuq_encode_huffman(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s, uint32_t sync_stride,
                        const uint8_t *lengths, uint64_t *bit_off, uint32_t *words, uint64_t words_cap,
                        uint32_t *sync, void *workspace, uint64_t workspace_bytes, nuq_stream_t stream);

@@ -18,7 +18,7 @@ if not os.path.exists(_LIB_PATH):
 _lib = ctypes.CDLL(_LIB_PATH)
 
 FLAG_CAPACITY, FLAG_NONFINITE, FLAG_MALFORMED = 1, 2, 4
-SYNC_EMPTY = 0x80000000
+SYNC_BLOCK = 2048
 MAX_BUCKET, MAX_S, MAX_WORKERS = 32768, 14, 32
 
 _u64, _u32, _i32, _vp, _f32 = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p, ctypes.c_float
@@ -26,6 +26,7 @@ _u64, _u32, _i32, _vp, _f32 = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ct
 _SIGNATURES = {
     "nuq_num_buckets": (_u64, [_u64, _u32]),
     "nuq_num_sync": (_u32, [_u32, _u32]),
+    "nuq_huffman_num_sync": (_u32, [_u32, _u32]),
     "nuq_max_words": (_u64, [_u64, _u32, _u32]),
     "nuq_encode_workspace_bytes": (_u64, [_u32, _u64, _u32, _u32]),
     "nuq_quantize_encode_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]),
@@ -112,6 +113,10 @@ def nuq_num_buckets(d: int, bucket: int) -> int:
 
 def nuq_num_sync(bucket: int, sync_stride: int) -> int:
     return _lib.nuq_num_sync(bucket, sync_stride)
+
+
+def nuq_huffman_num_sync(bucket: int, sync_stride: int) -> int:
+    return _lib.nuq_huffman_num_sync(bucket, sync_stride)
 
 
 def nuq_max_words(d: int, bucket: int, s: int) -> int:

@@ -124,6 +124,19 @@ uint32_t log2u(uint32_t x)
     return l;
 }
 
+// Decoder index of an ERC message: blocks of 2048 coordinates per bucket, and log2 of the pieces per block (the
+// smallest power of two that is at least min(bucket, 2048) / sync_stride).
+uint32_t sync_blocks(uint32_t bucket)
+{
+    return (bucket + (1u << kSyncBlockShift) - 1u) >> kSyncBlockShift;
+}
+
+uint32_t sync_pieces_shift(uint32_t bucket, uint32_t sync_stride)
+{
+    const uint32_t span = std::min(bucket, 1u << kSyncBlockShift);
+    return log2u((span + sync_stride - 1u) / sync_stride);
+}
+
 uint32_t slot_words_for(uint32_t bucket, uint32_t s)
 {
     const uint64_t bits = (uint64_t)bucket * (2u + erc_len_host(s + 1));
@@ -255,8 +268,9 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
     P.nb_stride = (nb + 3) & ~3ull;
     P.bucket = bucket;
     P.s = s;
-    P.sync_shift = sync_stride ? log2u(sync_stride) : 0;
     P.nsync = nsync;
+    P.pieces_shift = nsync ? sync_pieces_shift(bucket, sync_stride) : 0;
+    P.nblk = sync_blocks(bucket);
     P.slot_words = slot_words;
     P.lens = w.lens;
     P.staging = w.staging;
@@ -268,7 +282,7 @@ int encode_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket,
         P.rows = (bucket + 4 * TEAM - 1) / (4 * TEAM);
         P.rec_cap = team_rec_cap(bucket);
         P.out_cap = team_out_cap(slot_words);
-        P.lds_words = team_lds_words(P.rows, TEAM, P.rec_cap, P.out_cap, nsync);
+        P.lds_words = team_lds_words(P.rows, TEAM, P.rec_cap, P.out_cap, nsync, P.nblk);
         const size_t lds_bytes = (size_t)P.lds_words * 4 * G::kTeamsPerWG + 2 * 256 * 4;   // + the two code tables
         if (lds_bytes > 160 * 1024)
             return (int)NUQ_EINVAL;
@@ -434,6 +448,13 @@ uint64_t nuq_num_buckets(uint64_t d, uint32_t bucket)
 }
 
 uint32_t nuq_num_sync(uint32_t bucket, uint32_t sync_stride)
+{
+    if (!bucket || !valid_sync(sync_stride) || !sync_stride)
+        return 0;
+    return sync_blocks(bucket) << sync_pieces_shift(bucket, sync_stride);
+}
+
+uint32_t nuq_huffman_num_sync(uint32_t bucket, uint32_t sync_stride)
 {
     return sync_stride ? (bucket + sync_stride - 1) / sync_stride - 1 : 0;
 }
@@ -654,9 +675,9 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
     P.K = K;
     P.bucket = bucket;
     P.s = s;
-    P.sync_shift = nsync ? log2u(sync_stride) : 0;
     P.nsync = nsync;
-    P.nseg = nsync + 1;
+    P.nseg = nsync ? nsync : 1;                 // units (pieces) per bucket and worker
+    P.pieces_shift = nsync ? sync_pieces_shift(bucket, sync_stride) : 0;
     P.scale = scale;
     if (momentum && levels)
         return NUQ_EINVAL;
@@ -677,7 +698,7 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
     // Tiles of 4096 coordinates (32 KB of fp64, four workgroups per CU instead of eight) where the usual 2048 would
     // give the 64 parsing lanes at most 32 units: parts of large buckets of few workers.  The parse is bound by
     // instruction issue, so one full wave per SIMD gets through more records than two half-empty ones.
-    const bool big = nsync && bucket >= kTileCoordsBig && (kTileCoords / sync_stride) * K <= 32u;
+    const bool big = nsync && bucket >= kTileCoordsBig && (K << P.pieces_shift) <= 32u;
     const uint32_t tile_coords = big ? kTileCoordsBig : kTileCoords;
     const uint32_t variant = 2u * ((levels ? 3u : 0u) + (momentum ? (uint32_t)kUpdateMomentum
                                                                   : accumulate ? (uint32_t)kUpdateAdd
@@ -702,7 +723,7 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
         P.buckets_per_tile = 0;
         P.tile_coords = tile_coords;
         P.tiles_per_bucket = (bucket + tile_coords - 1) / tile_coords;
-        P.segs_per_tile = P.sync_shift ? (tile_coords >> P.sync_shift) : 1;
+        P.segs_per_tile = nsync ? (tile_coords >> kSyncBlockShift) << P.pieces_shift : 1;
         ntiles = P.nb * P.tiles_per_bucket;
         max_streams = K;
     }
@@ -950,7 +971,7 @@ int nuq_encode_huffman(const uint8_t *q, uint64_t d, uint32_t bucket, uint32_t s
     if (!q || !lengths || !bit_off || !words || !workspace || !valid_common(d, bucket, s) ||
         !valid_sync(sync_stride) || (reinterpret_cast<uintptr_t>(workspace) & 15u))
         return NUQ_EINVAL;
-    const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
+    const uint32_t nsync = nuq_huffman_num_sync(bucket, sync_stride);
     if (nsync && !sync)
         return NUQ_EINVAL;
     HuffmanCode H;
@@ -1033,7 +1054,7 @@ int nuq_quantize_encode_huffman_batch(uint32_t K, const float *const *v, const u
         !workspace || (reinterpret_cast<uintptr_t>(workspace) & 15u) || !valid_common(d, bucket, s) ||
         !valid_sync(sync_stride))
         return NUQ_EINVAL;
-    const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
+    const uint32_t nsync = nuq_huffman_num_sync(bucket, sync_stride);
     HuffmanCode H;
     if (!huffman_tables(lengths, s, H))
         return NUQ_EINVAL;
@@ -1104,7 +1125,7 @@ int nuq_decode_huffman_batch(uint32_t K, const uint64_t *const *bit_off, const u
     if (K < 1 || K > kMaxBatch || !bit_off || !words || !lengths || !q || !valid_common(d, bucket, s) ||
         !valid_sync(sync_stride))
         return NUQ_EINVAL;
-    const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
+    const uint32_t nsync = nuq_huffman_num_sync(bucket, sync_stride);
     if (nsync && !sync)
         return NUQ_EINVAL;
     HuffmanCode H;

@@ -46,13 +46,13 @@ struct DecodeParams {
     uint32_t K;
     uint32_t bucket;
     uint32_t s;
-    uint32_t sync_shift;        // log2 stride, 0 = none
-    uint32_t nsync;
-    uint32_t nseg;              // segments per bucket (nsync + 1)
+    uint32_t pieces_shift;      // log2 of the index pieces per 2048-coordinate block
+    uint32_t nsync;             // index entries per bucket, 0 = no index
+    uint32_t nseg;              // units per bucket and worker: the pieces of the index (nsync), or 1 without one
     uint32_t buckets_per_tile;  // >= 1: the tile is this many whole buckets; 0: part of one bucket
     uint32_t tiles_per_bucket;  // >= 1
     uint32_t tile_coords;       // coordinates a full tile spans
-    uint32_t segs_per_tile;     // segments of one bucket inside a tile
+    uint32_t segs_per_tile;     // pieces of one bucket inside a tile
     uint32_t xcd_base, xcd_rem; // ntiles / 8, ntiles % 8: see xcd_tile
     uint32_t lanes_shift;       // log2 of the lanes that copy one stream's words
     uint32_t stream_cap;        // words the lanes of a stream carry = kWordsPerLane << lanes_shift
@@ -428,8 +428,8 @@ __device__ __forceinline__ TileGeom tile_geom(const DecodeParams &P, uint32_t t)
     if (G.span == 0u)        // a tile of the (short) last bucket that starts beyond the vector's end
         G.nbuck = 0;
     const bool partial = !P.buckets_per_tile;
-    G.g0 = P.sync_shift ? (G.in_lo >> P.sync_shift) : 0u;
-    G.g1 = partial && P.sync_shift ? min(P.nseg, G.g0 + P.segs_per_tile) : P.nseg;
+    G.g0 = P.nsync ? (G.in_lo >> kSyncBlockShift) << P.pieces_shift : 0u;
+    G.g1 = partial && P.nsync ? min(P.nseg, G.g0 + P.segs_per_tile) : P.nseg;
     G.nstreams = G.nbuck * P.K;
     G.units = G.nstreams * (G.g1 - G.g0);
     return G;
@@ -456,11 +456,10 @@ __device__ __forceinline__ StreamPart stream_part(const DecodeParams &P, const T
     const uint64_t start = (bo0 + 31ull) & ~31ull;
     S.len = bo1 > start ? (uint32_t)(bo1 - start) : 0u;
     uint32_t lo = 0, hi = S.len;
-    if (!P.buckets_per_tile && P.sync_shift) {
-        if (G.g0 > 0u)
-            lo = min(e0 & 0x1FFFFFu, S.len);
+    if (!P.buckets_per_tile && P.nsync) {
+        lo = min(e0 & kSyncOffMask, S.len);
         if (G.g1 < P.nseg)
-            hi = min(e1 & 0x1FFFFFu, S.len);
+            hi = min(e1 & kSyncOffMask, S.len);
     }
     const uint32_t w0 = lo >> 5;
     S.bit0 = w0 << 5;
@@ -530,7 +529,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     const uint32_t lane = tid & (kWave - 1u);
     const bool parser = tid < kWave;                  // first wave parses, second wave prepares
     const bool partial = !P.buckets_per_tile;        // tiles are parts of one bucket
-    const bool walk = partial && !P.sync_shift;      // no index: every tile walks its bucket from the start
+    const bool walk = partial && !P.nsync;           // no index: every tile walks its bucket from the start
     const uint64_t last_bucket = P.nb - 1u;
     const double wscale = kTable ? 1.0 : ldexp(1.0, -1 - (int)P.s);
 
@@ -551,14 +550,14 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         r.bo0 = bit_off[b];
         r.bo1 = bit_off[b + 1];
         r.norm = norms[b];
-        if (P.sync_shift) {
+        if (P.nsync) {
             const uint32_t *sy = sync + b * P.nsync;
-            const uint32_t gc = min(g, P.nsync);
-            r.e_lo = sy[max(gc, 1u) - 1u];
-            r.e_hi = sy[min(gc, P.nsync - 1u)];
+            const uint32_t last = P.nsync - 1u;
+            r.e_lo = sy[min(g, last)];
+            r.e_hi = sy[min(g + 1u, last)];       // (not looked at for the bucket's last piece)
             if (partial) {
-                r.e0 = sy[max(G.g0, 1u) - 1u];
-                r.e1 = sy[min(G.g1, P.nsync) - 1u];
+                r.e0 = sy[min(G.g0, last)];
+                r.e1 = sy[min(G.g1, last)];       // (not looked at for the bucket's last tile)
             }
         }
         return r;
@@ -573,22 +572,23 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         const uint64_t b = G.b0 + bi;
         const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
         const StreamPart S = stream_part(P, G, m.bo0, m.bo1, m.e0, m.e1);
-        uint32_t bit_lo = 0, bit_hi = S.len, idx_lo = 0;
+        uint32_t bit_lo = 0, bit_hi = S.len;
         U.idx_hi = nbk;
-        if (P.sync_shift) {
-            idx_lo = g << P.sync_shift;
-            U.idx_hi = min(nbk, (g + 1u) << P.sync_shift);
-            if (idx_lo >= nbk)
-                return U;
-            if (g > 0u) {
-                if (m.e_lo & kSyncEmpty)
-                    return U;
-                bit_lo = m.e_lo & 0x1FFFFFu;
-                U.forced = (int)(idx_lo + ((m.e_lo >> 21) & 0x3FFu));
-            }
+        if (P.nsync) {
+            // piece g of the bucket: from its entry's record (whose index the entry gives) to the next entry's
+            const uint32_t blk = g >> P.pieces_shift;
+            U.idx_hi = min(nbk, (blk + 1u) << kSyncBlockShift);
+            bit_lo = m.e_lo & kSyncOffMask;
             if (g + 1u < P.nseg)
-                bit_hi = m.e_hi & 0x1FFFFFu;
-            if (bit_lo > bit_hi || bit_hi > S.len || (U.forced >= 0 && (uint32_t)U.forced >= U.idx_hi)) {
+                bit_hi = m.e_hi & kSyncOffMask;
+            if (bit_lo > bit_hi || bit_hi > S.len) {
+                bad = true;
+                return U;
+            }
+            if (bit_hi == bit_lo)             // an empty piece (its entry's index field means nothing)
+                return U;
+            U.forced = (int)((blk << kSyncBlockShift) + (m.e_lo >> 21));
+            if ((uint32_t)U.forced >= U.idx_hi) {
                 bad = true;
                 return U;
             }
@@ -621,7 +621,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
     auto parse_planned = [&](const TileGeom &G, uint32_t bi, uint32_t g, const uint32_t *buf, const PackedPlan &Q,
                              bool &bad) {
         const uint32_t nbk = G.b0 + bi == last_bucket ? last_len : P.bucket;
-        const uint32_t idx_hi = P.sync_shift ? min(nbk, (g + 1u) << P.sync_shift) : nbk;
+        const uint32_t idx_hi = P.nsync ? min(nbk, ((g >> P.pieces_shift) + 1u) << kSyncBlockShift) : nbk;
         decode_unit_fast<kTable>(StagedWords{buf + (Q.where & 0xFFFu)}, lut, lut_level, lev, Q.bits & 0xFFFFu, Q.bits >> 16,
                          (int)(Q.where >> 16) - 1, idx_hi, (double)Q.norm * wscale, TileSink{tile_origin(G, bi)}, bad);
     };
@@ -710,10 +710,10 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         const uint64_t *s_bit_off = P.bit_off[sk];
         r.bo0 = s_bit_off[b];
         r.bo1 = s_bit_off[b + 1];
-        if (partial && P.sync_shift) {
+        if (partial && P.nsync) {
             const uint32_t *sy = P.sync[sk] + b * P.nsync;
-            r.e0 = sy[max(G.g0, 1u) - 1u];
-            r.e1 = sy[min(G.g1, P.nsync) - 1u];
+            r.e0 = sy[min(G.g0, P.nsync - 1u)];
+            r.e1 = sy[min(G.g1, P.nsync - 1u)];
         }
         return r;
     };
@@ -917,7 +917,6 @@ __global__ __launch_bounds__(kSingleWG) void k_decode_single(DecodeParams P)
     lut_level[tid] = (uint8_t)level_table_entry(tid, P.s + 1u);
     const uint64_t units = P.nb * P.nseg;
     const uint64_t u0 = (uint64_t)blockIdx.x * kSingleWG;
-    const uint32_t S = P.sync_shift ? 1u << P.sync_shift : P.bucket;
 
     // ---- this lane's unit: metadata, then its words into the lane's LDS row (before the clearing below, so that
     // the two chains of dependent loads run under it)
@@ -925,26 +924,23 @@ __global__ __launch_bounds__(kSingleWG) void k_decode_single(DecodeParams P)
     const uint64_t b = min(u / P.nseg, P.nb - 1u);                  // (clamped: a lane without a unit loads and ignores)
     const uint32_t g = (uint32_t)(u - (u / P.nseg) * P.nseg);
     const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
-    const uint32_t idx_lo = P.sync_shift ? g << P.sync_shift : 0u;
-    const uint32_t idx_hi = P.sync_shift ? min(nbk, (g + 1u) << P.sync_shift) : nbk;
-    bool work = u < units && idx_lo < nbk;
+    const uint32_t blk = g >> P.pieces_shift;                       // the piece's block of 2048 coordinates (0 without index)
+    const uint32_t idx_hi = P.nsync ? min(nbk, (blk + 1u) << kSyncBlockShift) : nbk;
+    bool work = u < units;
     const uint64_t bo0 = P.bit_off[0][b], bo1 = P.bit_off[0][b + 1];
     const uint64_t start = (bo0 + 31ull) & ~31ull;
     bool bad = work && bo1 > start && bo1 - start > 0x1FFFFFull;    // a bucket's bit string is below 2^21 bits
     const uint32_t len = bo1 > start && !bad ? (uint32_t)(bo1 - start) : 0u;
     uint32_t bit_lo = 0, bit_hi = len;
     int forced = -1;
-    if (P.sync_shift) {
+    if (P.nsync) {
         const uint32_t *sy = P.sync[0] + b * P.nsync;
-        if (g > 0u) {
-            const uint32_t e = sy[g - 1u];
-            work = work && (e & kSyncEmpty) == 0u;                  // no record at or after this boundary's segment
-            bit_lo = e & 0x1FFFFFu;
-            forced = (int)(idx_lo + ((e >> 21) & 0x3FFu));
-        }
+        const uint32_t e = sy[g];
+        bit_lo = e & kSyncOffMask;
+        forced = (int)((blk << kSyncBlockShift) + (e >> 21));
         if (g + 1u < P.nseg)
-            bit_hi = sy[g] & 0x1FFFFFu;
-        if (work && (bit_lo > bit_hi || bit_hi > len || (forced >= 0 && (uint32_t)forced >= idx_hi))) {
+            bit_hi = sy[g + 1u] & kSyncOffMask;
+        if (work && (bit_lo > bit_hi || bit_hi > len || (bit_hi > bit_lo && (uint32_t)forced >= idx_hi))) {
             bad = true;
             work = false;
         }
@@ -974,11 +970,13 @@ __global__ __launch_bounds__(kSingleWG) void k_decode_single(DecodeParams P)
 
     // ---- write mode: clear the contiguous range of coordinates that the workgroup's units cover
     if constexpr (UPDATE == kUpdateWrite) {
-        auto first_coord = [&](uint64_t v) -> uint64_t {    // first coordinate of unit v; d for v = units
+        // The workgroup's units are whole blocks (the pieces per block divide its size): the coordinates before the
+        // first block of the next workgroup are its own.
+        auto first_coord = [&](uint64_t v) -> uint64_t {    // first coordinate of the block of unit v; d for v = units
             if (v >= units)
                 return P.d;
             const uint64_t vb = v / P.nseg;
-            const uint64_t c = vb * P.bucket + (v - vb * P.nseg) * S;
+            const uint64_t c = vb * P.bucket + (((v - vb * P.nseg) >> P.pieces_shift) << kSyncBlockShift);
             return c < P.d ? c : P.d;
         };
         const uint64_t c0 = first_coord(u0), c1 = first_coord(u0 + kSingleWG);

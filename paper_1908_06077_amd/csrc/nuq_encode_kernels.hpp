@@ -10,7 +10,12 @@
 namespace nuq {
 
 constexpr uint32_t kFlagCapacity = 1u, kFlagNonfinite = 2u, kFlagMalformed = 4u;
-constexpr uint32_t kSyncEmpty = 0x80000000u;
+
+// Decoder index of an ERC message: a bucket is cut into blocks of 2^kSyncBlockShift coordinates and the records of a
+// block into 2^pieces_shift pieces of equal count.  An entry = bit offset of the piece's first record (bits 0..20) |
+// that record's index inside its block (bits 21..31).
+constexpr uint32_t kSyncBlockShift = 11;
+constexpr uint32_t kSyncOffMask = 0x1FFFFFu;
 
 constexpr uint32_t kMaxBatch = 32;   // workers per launch
 
@@ -37,8 +42,10 @@ struct EncodeParams {
     uint64_t nb;
     uint32_t bucket;
     uint32_t s;
-    uint32_t sync_shift;   // log2(sync stride), 0 = no sync
-    uint32_t nsync;
+    uint32_t sync_shift;   // Huffman-coded messages: log2(sync stride), 0 = no index
+    uint32_t nsync;        // index entries per bucket (0 = no index)
+    uint32_t pieces_shift; // ERC messages: log2(pieces per block)
+    uint32_t nblk;         // ERC messages: blocks per bucket = ceil(bucket / 2048)
     uint32_t slot_words;   // staging words per bucket
     uint32_t rows;         // ceil(bucket / (4*TEAM))
     uint32_t lds_words;    // LDS words per team
@@ -338,7 +345,7 @@ template <int TEAM, int VPT>
 __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const EncodeWorker &W, bool active, uint64_t b,
                                                 const uint32_t *qb32, uint32_t *out, uint16_t *rec,
                                                 const uint32_t *erc_lut, const uint32_t *tail_lut, uint32_t *sync_l,
-                                                uint32_t *scratch)
+                                                uint32_t *blk, uint32_t *run_off, uint32_t *scratch)
 {
     const uint32_t tid = threadIdx.x % TEAM;
     const uint32_t rows = P.rows;
@@ -364,7 +371,22 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     const uint64_t nz = ((uint64_t)nz_hi << 32) | nz_lo;
     uint32_t nnz;
     uint32_t rank = team_exclusive_sum<TEAM>((uint32_t)(__popc(nz_lo) + __popc(nz_hi)), scratch, nnz);
+    const uint32_t rank0 = rank;                   // records before this thread's chunk
     const bool listed = nnz <= P.rec_cap;          // uniform over the team
+    if (P.nsync) {
+        // blk[t] = records before block t of the decoder index: the thread whose chunk holds the block's first
+        // coordinate counts its own nonzeros below it (every block starts inside exactly one chunk)
+        constexpr uint32_t kBlock = 1u << kSyncBlockShift;
+        const uint32_t c = (base + kBlock - 1u) & ~(kBlock - 1u);
+        const uint32_t t = c >> kSyncBlockShift;
+        if (c < base + rows * 4u && t < P.nblk) {
+            const uint32_t sh = c - base;                                    // < 64
+            const uint64_t below = sh ? nz & (~0ull >> (64u - sh)) : 0ull;
+            blk[t] = rank0 + (uint32_t)__popcll((unsigned long long)below);
+        }
+        if (tid == 0)
+            blk[P.nblk] = nnz;
+    }
     int before_chunk = -1;                         // last nonzero before this thread's chunk (unlisted buckets)
     if (listed) {
         auto list = [&](uint32_t m, uint32_t at) {
@@ -469,9 +491,49 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
             slot[i] = 0u;
         __threadfence();       // the zeros are in place before any record is OR-ed over them
     }
-    for (uint32_t i = tid; i < P.nsync; i += TEAM)
-        sync_l[i] = total | kSyncEmpty;   // "no record at or after this boundary" until one is found
+    // Decoder index: entry i = (block t, piece g) describes record blk[t] + floor(g n_t / pieces) of the bucket.
+    uint32_t *const sg = W.sync + (active ? b : 0) * P.nsync;
+    const uint32_t pmask = (1u << P.pieces_shift) - 1u;
+    if (listed) {
+        run_off[tid] = off0;              // where this thread's run of records starts in the bit string
+    } else {
+        // records are not listed: their numbers go to LDS (bit 31: a block without records) and whoever emits
+        // such a record writes the entry; an entry past the last record is the bucket's length
+        for (uint32_t i = tid; i < P.nsync; i += TEAM) {
+            const uint32_t f = blk[i >> P.pieces_shift], n = blk[(i >> P.pieces_shift) + 1u] - f;
+            const uint32_t r = f + (((i & pmask) * n) >> P.pieces_shift);
+            if (r >= nnz && active)
+                sg[i] = total;
+            sync_l[i] = r | (n ? 0u : 0x80000000u);
+        }
+    }
     team_barrier<TEAM>();
+    if (listed) {
+        // the run that holds the record starts at run_off[owner]; the lengths of the records before it in that run
+        // are looked up again (a run is nnz / TEAM records)
+        for (uint32_t i = tid; i < P.nsync; i += TEAM) {
+            const uint32_t t = i >> P.pieces_shift;
+            const uint32_t f = blk[t], n = blk[t + 1u] - f;
+            const uint32_t r = f + (((i & pmask) * n) >> P.pieces_shift);
+            uint32_t entry = total;
+            if (r < nnz) {
+                const uint32_t owner = r / per;
+                uint32_t q0 = owner * per;
+                uint32_t pos = run_off[owner];
+                int p = q0 ? (int)rec[q0 - 1u] : -1;
+                for (; q0 < r; ++q0) {
+                    const int e = (int)rec[q0];
+                    uint32_t len;
+                    make_record(e, p, (uint32_t)qbytes[e], len);
+                    pos += len;
+                    p = e;
+                }
+                entry = pos | ((n ? (uint32_t)rec[r] - (t << kSyncBlockShift) : 0u) << 21);
+            }
+            if (active)
+                sg[i] = entry;
+        }
+    }
 
     // (3) emit.  A thread's records are consecutive in the bit string: they are shifted into a 64-bit register and
     // leave it 32 bits at a time (a record is at most 31 bits, so at most 31 + 31 bits are pending), OR-ed into the
@@ -479,12 +541,32 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     {
         uint32_t t = off0, wi = off0 >> 5, fill = off0 & 31u;
         uint64_t acc = 0;
+        // unlisted records: the index entries that point at this thread's records (their numbers are sorted)
+        uint32_t cur = P.nsync, rno = rank0;
+        if (!listed && P.nsync) {
+            uint32_t lo = 0, hi = P.nsync;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if ((sync_l[mid] & 0x7fffffffu) < rank0)
+                    lo = mid + 1u;
+                else
+                    hi = mid;
+            }
+            cur = lo;
+        }
         auto emit = [&](uint32_t *dst, int e, int p, uint32_t bitsrec, uint32_t len) {
-            if (P.sync_shift) {
-                // this record is the first one at or after every segment boundary in (p, e]
-                const int g_hi = e >> P.sync_shift;
-                for (int g = max((p >> P.sync_shift) + 1, 1); g <= g_hi; ++g)
-                    sync_l[g - 1] = g == g_hi ? (t | ((uint32_t)(e - (g << P.sync_shift)) << 21)) : (t | kSyncEmpty);
+            (void)p;
+            if (!listed) {
+                while (cur < P.nsync) {
+                    const uint32_t tg = sync_l[cur];
+                    if ((tg & 0x7fffffffu) != rno)
+                        break;
+                    const uint32_t rel = (tg >> 31) ? 0u : (uint32_t)e - ((cur >> P.pieces_shift) << kSyncBlockShift);
+                    if (active)
+                        sg[cur] = t | (rel << 21);
+                    ++cur;
+                }
+                ++rno;
             }
             acc = (acc << len) | bitsrec;
             fill += len;
@@ -536,9 +618,6 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
         if (in_lds)
             for (uint32_t i = tid; i < nwords; i += TEAM)
                 slot[i] = obuf[i];
-        uint32_t *sg = W.sync + b * P.nsync;
-        for (uint32_t i = tid; i < P.nsync; i += TEAM)
-            sg[i] = sync_l[i];
         if (tid == 0)
             P.lens[(uint64_t)blockIdx.y * P.nb_stride + b] = total;
     }
@@ -558,12 +637,12 @@ __host__ __device__ inline uint32_t team_out_cap(uint32_t slot_words)
 }
 
 // LDS carve-up per team (in 32-bit words): [qb32: rows*TEAM][rec: rec_cap/2 (u16 per listed nonzero)]
-// [out: out_cap + 1][sync: nsync][scratch: 64 (16 uints, 16 ints, 16 uints, 8 doubles)]; the workgroup's
-// two 256-entry code tables follow the last team.
+// [out: out_cap + 1][sync: nsync][blk: nblk + 1][run_off: TEAM][scratch: 64 (16 uints, 16 ints, 16 uints, 8 doubles)];
+// the workgroup's two 256-entry code tables follow the last team.
 __host__ __device__ inline uint32_t team_lds_words(uint32_t rows, uint32_t team, uint32_t rec_cap, uint32_t out_cap,
-                                                   uint32_t nsync)
+                                                   uint32_t nsync, uint32_t nblk)
 {
-    uint32_t w = rows * team + (rec_cap + 1u) / 2u + out_cap + 1u + nsync;
+    uint32_t w = rows * team + (rec_cap + 1u) / 2u + out_cap + 1u + nsync + nblk + 1u + team;
     w = (w + 1u) & ~1u;   // keep the scratch 8-byte aligned
     return w + 64u;
 }
@@ -653,6 +732,8 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
     uint16_t *rec = reinterpret_cast<uint16_t *>(qb32 + P.rows * TEAM);
     uint32_t *out = qb32 + P.rows * TEAM + (P.rec_cap + 1u) / 2u;
     uint32_t *sync_l = out + P.out_cap + 1u;
+    uint32_t *blk = sync_l + P.nsync;
+    uint32_t *run_off = blk + P.nblk + 1u;
     uint32_t *scratch = lds + P.lds_words - 64u;
     uint32_t *erc_lut = smem + TeamGeom<TEAM>::kTeamsPerWG * P.lds_words;
     uint32_t *tail_lut = erc_lut + 256;
@@ -721,7 +802,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
         front_bytes_to_lds<TEAM>(P, W, base, nbk, tid, qb32);
     }
     __syncthreads();
-    encode_from_lds<TEAM, VPT>(P, W, active, b, qb32, out, rec, erc_lut, tail_lut, sync_l, scratch);
+    encode_from_lds<TEAM, VPT>(P, W, active, b, qb32, out, rec, erc_lut, tail_lut, sync_l, blk, run_off, scratch);
 }
 
 // ------------------------------------------------- offsets and gather of the slots

@@ -36,8 +36,12 @@ def test_every_declared_symbol_is_exported(nuq):
 def test_size_helpers(nuq):
     assert nuq.nuq_num_buckets(25_557_032, 8192) == 3120
     assert nuq.nuq_num_buckets(8192, 8192) == 1 and nuq.nuq_num_buckets(8193, 8192) == 2
-    assert nuq.nuq_num_sync(8192, 512) == 15 and nuq.nuq_num_sync(512, 512) == 0
-    assert nuq.nuq_num_sync(1000, 256) == 3 and nuq.nuq_num_sync(8192, 0) == 0
+    # decoder index: blocks of 2048 coordinates x a power-of-two number of pieces of about sync_stride coordinates
+    assert nuq.nuq_num_sync(8192, 512) == 4 * 4 and nuq.nuq_num_sync(512, 512) == 1
+    assert nuq.nuq_num_sync(1000, 256) == 4 and nuq.nuq_num_sync(8192, 0) == 0 and nuq.nuq_num_sync(1300, 256) == 8
+    assert nuq.nuq_num_sync(16384, 256) == 8 * 8 and nuq.nuq_num_sync(32768, 64) == 16 * 32
+    assert nuq.nuq_num_sync(8192, 100) == 0                              # not a power of two in 64..1024
+    assert nuq.nuq_huffman_num_sync(8192, 512) == 15 and nuq.nuq_huffman_num_sync(1000, 256) == 3
     # worst case: every coordinate nonzero at the top level: 1 (gap) + 1 (sign) + |ERC(s+1)| bits each
     assert nuq.nuq_max_words(8192, 8192, 3) == 8192 * 8 // 32 + 1        # |ERC(4)| = 6
     assert nuq.nuq_max_words(64, 64, 7) == (64 * 9 + 31) // 32 + 1       # |ERC(8)| = 7

@@ -43,7 +43,7 @@ def test_histogram_code_message_decode_and_average(g, d, n, s, S, K, kind):
     nuq = g.nuq
     rng = np.random.default_rng(d + n + s + S)
     B = nuq.nuq_num_buckets(d, n)
-    nsync = nuq.nuq_num_sync(n, S)
+    nsync = nuq.nuq_huffman_num_sync(n, S)
     cap = nuq.nuq_huffman_max_words(d, n)
     ws = torch.empty(nuq.nuq_encode_huffman_workspace_bytes(d, n), dtype=torch.uint8, device=g.DEV)
     lengths = None
@@ -156,7 +156,7 @@ def test_codes_that_do_not_fit_the_data(g, s, n, S, hist):
     q_np = (level | ((rng.random(d) < 0.5) & (level > 0)).astype(np.uint8) << 7).astype(np.uint8)
     lengths = nuq.nuq_huffman_lengths(hist, s)
     assert lengths == [int(x) for x in oracle.huffman_lengths(np.array(hist, dtype=np.uint64), s)]
-    B, nsync = nuq.nuq_num_buckets(d, n), nuq.nuq_num_sync(n, S)
+    B, nsync = nuq.nuq_num_buckets(d, n), nuq.nuq_huffman_num_sync(n, S)
     q = torch.from_numpy(q_np).to(g.DEV)
     bit_off = torch.full((B + 1,), -1, dtype=torch.int64, device=g.DEV)
     words = torch.zeros(nuq.nuq_huffman_max_words(d, n), dtype=torch.int32, device=g.DEV)
@@ -205,7 +205,7 @@ def test_config3_worker_at_full_size(g):
     nuq = g.nuq
     w = workloads.workload(3)
     d, n, s, S = w.d, w.bucket, w.s, 256
-    B, nsync = nuq.nuq_num_buckets(d, n), nuq.nuq_num_sync(n, S)
+    B, nsync = nuq.nuq_num_buckets(d, n), nuq.nuq_huffman_num_sync(n, S)
     v = workloads.generate(w, 0, g.DEV)
     norms = torch.empty(B, dtype=torch.float32, device=g.DEV)
     nuq.nuq_bucket_norms(v, n, norms)
