@@ -419,23 +419,33 @@ constexpr DecodeKernel kDecodeKernels[] = {
     k_decode_accumulate<true, kUpdateAdd, kTileCoords>,       k_decode_accumulate<true, kUpdateAdd, kTileCoordsBig>,
 };
 constexpr uint32_t kDecodeVariants = sizeof(kDecodeKernels) / sizeof(kDecodeKernels[0]);
+// the same variants of the one-wave tile decoder
+constexpr DecodeKernel kDecodeWaveKernels[kDecodeVariants] = {
+    k_decode_wave<false, kUpdateWrite, kTileCoords>,    k_decode_wave<false, kUpdateWrite, kTileCoordsBig>,
+    k_decode_wave<false, kUpdateAdd, kTileCoords>,      k_decode_wave<false, kUpdateAdd, kTileCoordsBig>,
+    k_decode_wave<false, kUpdateMomentum, kTileCoords>, k_decode_wave<false, kUpdateMomentum, kTileCoordsBig>,
+    k_decode_wave<true, kUpdateWrite, kTileCoords>,     k_decode_wave<true, kUpdateWrite, kTileCoordsBig>,
+    k_decode_wave<true, kUpdateAdd, kTileCoords>,       k_decode_wave<true, kUpdateAdd, kTileCoordsBig>,
+};
 
-uint32_t decode_resident_workgroups(uint32_t variant)
+uint32_t decode_resident_workgroups(uint32_t variant, bool wave)
 {
-    static uint32_t cached[kDecodeVariants][64] = {};
+    static uint32_t cached[2][kDecodeVariants][64] = {};
     int dev = 0;
     if (variant >= kDecodeVariants || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
         return 0;
-    if (!cached[variant][dev]) {
+    uint32_t &slot = cached[wave ? 1 : 0][variant][dev];
+    if (!slot) {
         int per_cu = 0, cus = 0;
-        const void *kern = reinterpret_cast<const void *>(kDecodeKernels[variant]);
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, (int)kDecodeWG, 0) != hipSuccess ||
+        const void *kern = reinterpret_cast<const void *>(wave ? kDecodeWaveKernels[variant] : kDecodeKernels[variant]);
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, (int)(wave ? kWaveWG : kDecodeWG), 0) !=
+                hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || per_cu < 1 ||
             cus < 1)
             return 0;
-        cached[variant][dev] = (uint32_t)per_cu * (uint32_t)cus;
+        slot = (uint32_t)per_cu * (uint32_t)cus;
     }
-    return cached[variant][dev];
+    return slot;
 }
 
 }  // namespace
@@ -742,9 +752,15 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
     // and with a stride of 8 or 16 words they would read the same few banks (config 5: -5 %).  With few, long
     // streams the word given up costs more than the conflicts (config 4: +4 %), so those keep the full stride.
     P.stream_stride = max_streams >= 16u ? P.stream_cap - 1u : P.stream_cap;
-    const uint32_t resident = decode_resident_workgroups(variant);
+    // One wave per workgroup where a tile holds at most 64 pieces and each stream's pieces fit the lanes that copy it
+    // (every usual geometry with an index); the two-wave kernel takes the rest (no index, many workers, fine strides).
+    const bool wave = nsync && max_streams <= 64u && P.segs_per_tile <= (1u << P.lanes_shift);
+    uint32_t resident = decode_resident_workgroups(variant, wave);
     if (!resident)
         return NUQ_EHIP;
+    resident &= ~7u;                            // a multiple of the eight XCDs (see xcd_tile)
+    if (!resident)
+        resident = 8u;
     // Every resident workgroup slot is used.  Workgroups walk tiles with stride `grid`, so the first
     // ntiles mod grid of them get one tile more than the rest: those are the workgroups that arrive first on their
     // CUs, whose parsing waves are the oldest on their SIMDs and run faster than the later ones.
@@ -753,7 +769,10 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
     if (levels)
         for (uint32_t j = 0; j < s + 2u; ++j)
             P.lev[j] = levels[j];
-    hipLaunchKernelGGL(kDecodeKernels[variant], dim3(grid), dim3(kDecodeWG), 0, static_cast<hipStream_t>(stream), P);
+    if (wave)
+        hipLaunchKernelGGL(kDecodeWaveKernels[variant], dim3(grid), dim3(kWaveWG), 0, static_cast<hipStream_t>(stream), P);
+    else
+        hipLaunchKernelGGL(kDecodeKernels[variant], dim3(grid), dim3(kDecodeWG), 0, static_cast<hipStream_t>(stream), P);
     return check_launch();
 }
 

@@ -83,10 +83,10 @@ constexpr int kUpdateWrite = 0, kUpdateAdd = 1, kUpdateMomentum = 2;
 
 // A full, 16-byte aligned tile of TC coordinates: every thread handles TC/4/kDecodeWG float4 groups, two at a time, with the
 // loads of the old values issued before the LDS reads so that their latencies overlap.
-template <int UPDATE, uint32_t TC>
+template <int UPDATE, uint32_t TC, uint32_t WG = kDecodeWG>
 __device__ __forceinline__ void apply_full_tile(const DecodeParams &P, double *tile, float *o, float *y, uint32_t tid)
 {
-    constexpr uint32_t kFull = TC / 4u / kDecodeWG;               // float4 groups per thread
+    constexpr uint32_t kFull = TC / 4u / WG;                      // float4 groups per thread
     const double sc = (double)P.scale;
 #pragma unroll
     for (uint32_t r0 = 0; r0 < kFull; r0 += 2u) {
@@ -94,7 +94,7 @@ __device__ __forceinline__ void apply_full_tile(const DecodeParams &P, double *t
         double2 a[2], c[2];
 #pragma unroll
         for (uint32_t r = 0; r < 2u; ++r) {
-            const uint32_t i = tid + (r0 + r) * kDecodeWG;
+            const uint32_t i = tid + (r0 + r) * WG;
             if constexpr (UPDATE != kUpdateWrite)
                 w[r] = reinterpret_cast<const float4 *>(o)[i];
             if constexpr (UPDATE == kUpdateMomentum)
@@ -102,7 +102,7 @@ __device__ __forceinline__ void apply_full_tile(const DecodeParams &P, double *t
         }
 #pragma unroll
         for (uint32_t r = 0; r < 2u; ++r) {
-            double2 *src = reinterpret_cast<double2 *>(tile) + 2u * (tid + (r0 + r) * kDecodeWG);
+            double2 *src = reinterpret_cast<double2 *>(tile) + 2u * (tid + (r0 + r) * WG);
             a[r] = src[0];
             c[r] = src[1];
             src[0] = double2{0.0, 0.0};
@@ -110,7 +110,7 @@ __device__ __forceinline__ void apply_full_tile(const DecodeParams &P, double *t
         }
 #pragma unroll
         for (uint32_t r = 0; r < 2u; ++r) {
-            const uint32_t i = tid + (r0 + r) * kDecodeWG;
+            const uint32_t i = tid + (r0 + r) * WG;
             const float4 v{(float)(sc * a[r].x), (float)(sc * a[r].y), (float)(sc * c[r].x), (float)(sc * c[r].y)};
             if constexpr (UPDATE == kUpdateWrite) {
                 store_once4(reinterpret_cast<float4 *>(o) + i, v);     // written once, not read here again
@@ -152,6 +152,38 @@ __device__ __forceinline__ void apply4(const DecodeParams &P, float4 r, float4 *
     *dst = w;
 }
 
+
+// Output stage of a tile: scale the sums, round to fp32, apply to the output (write, add, or momentum rule), and
+// leave the tile zeroed.  Called by all WG threads of the workgroup.
+template <int UPDATE, uint32_t TC, uint32_t WG>
+__device__ __forceinline__ void tile_output(const DecodeParams &P, double *tile, uint64_t c_lo, uint32_t span, uint32_t tid)
+{
+    float *o = P.out + c_lo;
+    float *y = UPDATE == kUpdateMomentum ? P.yl + c_lo : o;      // (read only under kUpdateMomentum)
+    const bool vec = ((reinterpret_cast<uintptr_t>(o) | reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
+    const uint32_t n4 = vec ? span >> 2 : 0u;
+    if (n4 == TC / 4u) {
+        apply_full_tile<UPDATE, TC, WG>(P, tile, o, y, tid);
+    } else {
+        const double sc = (double)P.scale;
+        for (uint32_t i = tid; i < n4; i += WG) {
+            double2 *src = reinterpret_cast<double2 *>(tile) + 2u * i;
+            const double2 a = src[0], c = src[1];
+            src[0] = double2{0.0, 0.0};
+            src[1] = double2{0.0, 0.0};
+            const float4 r{(float)(sc * a.x), (float)(sc * a.y), (float)(sc * c.x), (float)(sc * c.y)};
+            apply4<UPDATE>(P, r, reinterpret_cast<float4 *>(o) + i, reinterpret_cast<float4 *>(y) + i);
+        }
+    }
+    for (uint32_t i = (n4 << 2) + tid; i < span; i += WG) {      // (n4 = 0 without 16-byte alignment)
+        const float r = (float)((double)P.scale * tile[i]);
+        tile[i] = 0.0;
+        if constexpr (UPDATE == kUpdateMomentum)
+            momentum_one(o[i], y[i], r, P.alpha, P.la, P.mu);
+        else
+            o[i] = UPDATE == kUpdateAdd ? o[i] + r : r;
+    }
+}
 
 // Branch-free decoder of Alg. 2 for values below 65536 on a 32-bit window (MSB first).
 // Code shapes: "0" -> 1;  "1x0" -> 2..3;  "1x 1y..y 0" -> 4..15 (group of x+1 bits);
@@ -858,39 +890,200 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         }
 
         // ---- scale, round to fp32, apply to the output (write, add, or momentum rule); leave the tile zeroed
-        {
-            float *o = P.out + G.c_lo;
-            float *y = UPDATE == kUpdateMomentum ? P.yl + G.c_lo : o;      // (read only under kUpdateMomentum)
-            const uint32_t span = G.span;
-            const bool vec = ((reinterpret_cast<uintptr_t>(o) | reinterpret_cast<uintptr_t>(y)) & 15u) == 0;
-            const uint32_t n4 = vec ? span >> 2 : 0u;
-            if (n4 == TC / 4u) {
-                apply_full_tile<UPDATE, TC>(P, tile, o, y, tid);
-            } else {
-                const double sc = (double)P.scale;
-                for (uint32_t i = tid; i < n4; i += kDecodeWG) {
-                    double2 *src = reinterpret_cast<double2 *>(tile) + 2u * i;
-                    const double2 a = src[0], c = src[1];
-                    src[0] = double2{0.0, 0.0};
-                    src[1] = double2{0.0, 0.0};
-                    const float4 r{(float)(sc * a.x), (float)(sc * a.y), (float)(sc * c.x), (float)(sc * c.y)};
-                    apply4<UPDATE>(P, r, reinterpret_cast<float4 *>(o) + i, reinterpret_cast<float4 *>(y) + i);
-                }
-            }
-            for (uint32_t i = (n4 << 2) + tid; i < span; i += kDecodeWG) {      // (n4 = 0 without 16-byte alignment)
-                const float r = (float)((double)P.scale * tile[i]);
-                tile[i] = 0.0;
-                if constexpr (UPDATE == kUpdateMomentum)
-                    momentum_one(o[i], y[i], r, P.alpha, P.la, P.mu);
-                else
-                    o[i] = UPDATE == kUpdateAdd ? o[i] + r : r;
-            }
-        }
+        tile_output<UPDATE, TC, kDecodeWG>(P, tile, G.c_lo, G.span, tid);
         if (!has1)
             break;
         __syncthreads();
         t += stride;
         G = G1;
+    }
+    if (bad)
+        atomicOr(P.flags, kFlagMalformed);
+}
+
+// ---- the tile decoder as one wave per workgroup --------------------------------------------------------------
+// For messages with a decoder index whose tiles hold at most 64 pieces, each stream's pieces within the lanes that copy
+// that stream (the usual geometries).  What bounds the two-wave kernel above on such tiles is neither the parse nor
+// memory but its own bookkeeping: the preparing wave works through several hundred mostly dependent instructions per
+// tile at a lone wave's pace (an instruction every nine cycles), sharing its SIMD's issue slots with the parsing waves,
+// and two barriers per tile keep the eight workgroups of a CU in step, so that all of them parse, and then all of them
+// write, at the same time.  Here one wave does everything for its tiles, in order and without barriers: the lanes
+// that copy a stream's words are the lanes that parse its pieces (so one set of offsets and index entries serves
+// both), the words of the next tile and the offsets of the tile after it are in flight in registers while this
+// tile is parsed and written (a wave per SIMD pair leaves 256 registers per lane), and the workgroups of a CU drift
+// apart, which spreads parse, LDS and store traffic over time.
+constexpr uint32_t kWaveWG = 64;
+
+struct WaveMeta {           // what a lane loads for its stream (bucket, worker) and its piece of one tile
+    uint64_t bo0, bo1;      // bit_off[b], bit_off[b + 1]
+    uint32_t e_lo, e_hi;    // index entries of the piece and of the one after it
+    float norm;
+};
+
+template <bool kTable, int UPDATE, uint32_t TC>
+__global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
+{
+    __shared__ __align__(16) double tile[TC];
+    __shared__ uint32_t stage[kStageWords + 5];       // words at [1, kStageWords]; pads as in k_decode_accumulate
+    __shared__ uint16_t lut[128];
+    __shared__ uint8_t lut_level[128];
+    float *lev = nullptr;
+    if constexpr (kTable) {
+        __shared__ float lev_s[16];
+        lev = lev_s;
+    }
+    const uint32_t lane = threadIdx.x;
+    const bool partial = !P.buckets_per_tile;         // tiles are parts of one bucket
+    const uint32_t stream_stride = TC == kTileCoordsBig ? P.stream_cap : P.stream_stride;
+    const uint64_t last_bucket = P.nb - 1u;
+    const uint32_t last_len = (uint32_t)(P.d - last_bucket * P.bucket);
+    const double wscale = kTable ? 1.0 : ldexp(1.0, -1 - (int)P.s);
+
+    // this lane's stream (bucket in tile, worker) and piece of it; its pointers into that worker's arrays
+    const uint32_t lanes = 1u << P.lanes_shift;
+    const uint32_t my_stream = lane >> P.lanes_shift, my_sub = lane & (lanes - 1u);
+    const uint32_t sk = my_stream % P.K, sbi = my_stream / P.K;
+    const uint64_t *const pb = P.bit_off[sk];
+    const float *const pn = P.norms[sk];
+    const uint32_t *const ps = P.sync[sk];
+    const uint32_t *const pw = P.words[sk];
+    const uint32_t first_lane = lane & ~(lanes - 1u);
+
+    auto load_meta = [&](const TileGeom &G) {
+        WaveMeta m;
+        const uint64_t b = min(G.b0 + sbi, last_bucket);              // (a lane without a stream loads and ignores)
+        m.bo0 = pb[b];
+        m.bo1 = pb[b + 1];
+        m.norm = pn[b];
+        const uint32_t *sy = ps + b * P.nsync;
+        const uint32_t g = min(G.g0 + my_sub, P.nsync - 1u);
+        m.e_lo = sy[g];
+        m.e_hi = sy[min(g + 1u, P.nsync - 1u)];                       // (not looked at for the bucket's last piece)
+        return m;
+    };
+    // the part of the lane's stream that the tile needs: from the entry of the tile's first piece to that of the
+    // piece after its last one (held by the stream's first and last lanes)
+    auto part_of = [&](const TileGeom &G, const WaveMeta &m) {
+        uint32_t e0 = 0, e1 = 0;
+        if (partial) {
+            const uint32_t pieces = G.g1 - G.g0;                      // >= 1 for a tile with coordinates
+            e0 = (uint32_t)__shfl((int)m.e_lo, (int)first_lane, kWave);
+            e1 = (uint32_t)__shfl((int)m.e_hi, (int)(first_lane + max(pieces, 1u) - 1u), kWave);
+        }
+        return stream_part(P, G, m.bo0, m.bo1, e0, e1);
+    };
+    auto load_words = [&](const TileGeom &G, const StreamPart &S, uint32_t (&w)[kWordsPerLane]) {
+        const uint32_t cnt = my_stream < G.nstreams ? min(S.nwords, stream_stride) : 0u;
+        const uint32_t *src = pw + S.first_word;
+#pragma unroll
+        for (uint32_t i = 0; i < kWordsPerLane; ++i) {
+            const uint32_t wi = my_sub + (i << P.lanes_shift);
+            const uint32_t *a = wi < cnt ? src + wi : P.flags;        // beyond the stream's part: any readable word
+            w[i] = *a;
+        }
+    };
+    auto store_words = [&](const uint32_t (&w)[kWordsPerLane]) {
+        const uint32_t base = 1u + my_stream * stream_stride + my_sub;
+#pragma unroll
+        for (uint32_t i = 0; i + 1u < kWordsPerLane; ++i)
+            stage[base + (i << P.lanes_shift)] = w[i];
+        constexpr uint32_t kLast = kWordsPerLane - 1u;                // an odd stride has no place for the very last word
+        if (TC == kTileCoordsBig || my_sub + (kLast << P.lanes_shift) < stream_stride)
+            stage[base + (kLast << P.lanes_shift)] = w[kLast];
+    };
+    // LDS traffic of one wave needs no hardware barrier: its operations complete in order
+    auto lds_fence = [] {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    // ---- tables, cleared tile
+    for (uint32_t i = lane; i < TC / 2u; i += kWaveWG)
+        reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
+    lut[lane] = (uint16_t)gap_table_entry(lane);
+    lut[lane + kWave] = (uint16_t)gap_table_entry(lane + kWave);
+    lut_level[lane] = (uint8_t)level_table_entry(lane, P.s + 1u);
+    lut_level[lane + kWave] = (uint8_t)level_table_entry(lane + kWave, P.s + 1u);
+    if constexpr (kTable) {
+        if (lane < 16u)
+            lev[lane] = P.lev[lane];
+    }
+    if (lane < 5u)
+        stage[lane ? kStageWords + lane : 0u] = 0u;                  // the pads
+
+    // ---- prologue: offsets of the first two tiles, words of the first
+    bool bad = false;
+    const uint32_t stride = gridDim.x;
+    uint32_t t = blockIdx.x;                                          // < ntiles by the launch
+    TileGeom G0 = tile_geom(P, xcd_tile(P, t)), G1 = G0;
+    WaveMeta M0 = load_meta(G0), M1 = M0;
+    if (t + stride < P.ntiles) {
+        G1 = tile_geom(P, xcd_tile(P, t + stride));
+        M1 = load_meta(G1);
+    }
+    StreamPart S0 = part_of(G0, M0);
+    uint32_t W0[kWordsPerLane];
+    load_words(G0, S0, W0);
+
+    for (;;) {
+        const bool has1 = t + stride < P.ntiles;                      // uniform
+        const bool has2 = has1 && t + stride < P.ntiles - stride;
+        // this tile's words to LDS; the next tile's words and the offsets of the one after it on their way
+        store_words(W0);
+        StreamPart S1 = S0;
+        TileGeom G2 = G1;
+        WaveMeta M2 = M1;
+        if (has1) {
+            S1 = part_of(G1, M1);
+            load_words(G1, S1, W0);
+        }
+        if (has2) {
+            G2 = tile_geom(P, xcd_tile(P, t + 2u * stride));
+            M2 = load_meta(G2);
+        }
+        lds_fence();
+
+        // ---- this lane's piece of tile t
+        const uint32_t pieces = G0.g1 - G0.g0;
+        if (my_stream < G0.nstreams && my_sub < pieces) {
+            const uint32_t g = G0.g0 + my_sub;
+            const uint32_t nbk = G0.b0 + sbi == last_bucket ? last_len : P.bucket;
+            const uint32_t blk = g >> P.pieces_shift;
+            const uint32_t idx_hi = min(nbk, (blk + 1u) << kSyncBlockShift);
+            const uint32_t bit_lo = M0.e_lo & kSyncOffMask;
+            const uint32_t bit_hi = g + 1u < P.nseg ? M0.e_hi & kSyncOffMask : S0.len;
+            const uint32_t forced = (blk << kSyncBlockShift) + (M0.e_lo >> 21);
+            if (bit_lo > bit_hi || bit_hi > S0.len) {
+                bad = true;
+            } else if (bit_hi > bit_lo) {
+                // (an index that is not monotone would leave the part of the stream that was copied)
+                if (forced >= idx_hi || bit_lo < S0.bit0 || bit_hi > S0.bit0 + (S0.nwords << 5)) {
+                    bad = true;
+                } else {
+                    double *origin = partial ? tile - (int)G0.in_lo : tile + sbi * P.bucket;
+                    const double wnorm = (double)M0.norm * wscale;
+                    if (S0.nwords <= stream_stride)
+                        decode_unit_fast<kTable>(StagedWords{stage + my_stream * stream_stride}, lut, lut_level, lev,
+                                                 bit_lo - S0.bit0, bit_hi - S0.bit0, (int)forced, idx_hi, wnorm,
+                                                 TileSink{origin}, bad);
+                    else                              // the part did not fit the staging area: words from global memory
+                        decode_unit_fast<kTable>(GlobalWords{pw + S0.first_word, S0.nwords - 1u}, lut, lut_level, lev,
+                                                 bit_lo - S0.bit0, bit_hi - S0.bit0, (int)forced, idx_hi, wnorm,
+                                                 TileSink{origin}, bad);
+                }
+            }
+        }
+        lds_fence();
+        tile_output<UPDATE, TC, kWaveWG>(P, tile, G0.c_lo, G0.span, lane);
+        if (!has1)
+            break;
+        lds_fence();
+        t += stride;
+        G0 = G1;
+        G1 = G2;
+        M0 = M1;
+        M1 = M2;
+        S0 = S1;
     }
     if (bad)
         atomicOr(P.flags, kFlagMalformed);
