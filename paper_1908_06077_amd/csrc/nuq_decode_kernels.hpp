@@ -973,14 +973,14 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
         return stream_part(P, G, m.bo0, m.bo1, e0, e1);
     };
     auto load_words = [&](const TileGeom &G, const StreamPart &S, uint32_t (&w)[kWordsPerLane]) {
+        // lanes beyond the part's end load its last word again (nothing reads what they store); a lane without a
+        // stream, or a part without words, loads any readable word
         const uint32_t cnt = my_stream < G.nstreams ? min(S.nwords, stream_stride) : 0u;
-        const uint32_t *src = pw + S.first_word;
+        const uint32_t *src = cnt ? pw + S.first_word : P.flags;
+        const uint32_t last = max(cnt, 1u) - 1u;
 #pragma unroll
-        for (uint32_t i = 0; i < kWordsPerLane; ++i) {
-            const uint32_t wi = my_sub + (i << P.lanes_shift);
-            const uint32_t *a = wi < cnt ? src + wi : P.flags;        // beyond the stream's part: any readable word
-            w[i] = *a;
-        }
+        for (uint32_t i = 0; i < kWordsPerLane; ++i)
+            w[i] = src[min(my_sub + (i << P.lanes_shift), last)];
     };
     auto store_words = [&](const uint32_t (&w)[kWordsPerLane]) {
         const uint32_t base = 1u + my_stream * stream_stride + my_sub;
@@ -991,10 +991,12 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
         if (TC == kTileCoordsBig || my_sub + (kLast << P.lanes_shift) < stream_stride)
             stage[base + (kLast << P.lanes_shift)] = w[kLast];
     };
-    // LDS traffic of one wave needs no hardware barrier: its operations complete in order
+    // LDS traffic of one wave needs no hardware barrier: its operations complete in order.  (No memory fence here: a
+    // fence also waits for every global load and store in flight, which is exactly what this kernel keeps in flight.)
     auto lds_fence = [] {
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        asm volatile("" ::: "memory");
         __builtin_amdgcn_wave_barrier();
+        asm volatile("" ::: "memory");
     };
 
     // ---- tables, cleared tile
@@ -1024,12 +1026,16 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
     StreamPart S0 = part_of(G0, M0);
     uint32_t W0[kWordsPerLane];
     load_words(G0, S0, W0);
+    store_words(W0);
 
+    // Order of a round, chosen for the one counter that tracks loads and stores alike and in issue order: the next
+    // tile's words and the offsets of the tile after it are requested first, this tile is parsed (which takes longer
+    // than any of those loads, or the previous tile's stores, need), then the words are moved to the staging area,
+    // which the parse no longer reads, and only then is this tile written out: no wait ever stands behind a store
+    // that has just been issued.
     for (;;) {
         const bool has1 = t + stride < P.ntiles;                      // uniform
         const bool has2 = has1 && t + stride < P.ntiles - stride;
-        // this tile's words to LDS; the next tile's words and the offsets of the one after it on their way
-        store_words(W0);
         StreamPart S1 = S0;
         TileGeom G2 = G1;
         WaveMeta M2 = M1;
@@ -1066,14 +1072,21 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
                         decode_unit_fast<kTable>(StagedWords{stage + my_stream * stream_stride}, lut, lut_level, lev,
                                                  bit_lo - S0.bit0, bit_hi - S0.bit0, (int)forced, idx_hi, wnorm,
                                                  TileSink{origin}, bad);
-                    else                              // the part did not fit the staging area: words from global memory
+                    else {                            // the part did not fit the staging area: words from global memory
                         decode_unit_fast<kTable>(GlobalWords{pw + S0.first_word, S0.nwords - 1u}, lut, lut_level, lev,
                                                  bit_lo - S0.bit0, bit_hi - S0.bit0, (int)forced, idx_hi, wnorm,
                                                  TileSink{origin}, bad);
+                        // every load of this rare path has landed before the paths join again: otherwise the compiler,
+                        // which must assume the worst of the joined paths, waits for all memory traffic wherever the
+                        // usual path later touches a register that this one loaded into
+                        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+                    }
                 }
             }
         }
         lds_fence();
+        if (has1)
+            store_words(W0);                              // (the parse of this tile is over: the staging area is free)
         tile_output<UPDATE, TC, kWaveWG>(P, tile, G0.c_lo, G0.span, lane);
         if (!has1)
             break;
