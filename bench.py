@@ -11,7 +11,9 @@ Prints one JSON line:
                encode and decode+average, inputs resident in HBM, per wall second of the step
   roofline   = the fused quantize+encode kernel (dominant by time), algorithmic bytes per launch
                over its mean launch duration from HIP events recorded on its stream
-  cpu_baseline = the CPU oracle timed on the same workload on this host (one thread)
+  cpu_baseline = the CPU oracle timed on a bounded sample of the same workload on this host: its buckets dealt out
+               to all cores (value, cores), and on one thread (one_thread)
+  per_config = the other four workloads of the benchmark spec measured in the same process (default run only)
 """
 from __future__ import annotations
 
@@ -67,6 +69,9 @@ def parse_args():
                          "host's launch gaps); the per-kernel HIP-event brackets then come from eager steps after the "
                          "timed region, since events cannot be read back from inside a graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="only the workload --config names (the default run also measures the other four workloads of "
+                         "BASELINE.json, with fewer steps, and attaches them as per_config)")
     ap.add_argument("--per-worker-calls", action="store_true",
                     help="encode with K nuq_quantize_encode calls instead of one nuq_quantize_encode_batch")
     return ap.parse_args()
@@ -77,18 +82,57 @@ def main():
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    result = measure(args, args.config, args.steps, args.warmup, None if args.no_cpu_baseline else 300_000_000)
+    plain = (args.levels == "nuq" and args.norm == "l2" and not args.fixed_bits and not args.huffman
+             and args.update == "none" and not args.graph and not args.per_worker_calls)
+    if plain and not args.no_per_config:
+        # the other four workloads of the benchmark spec in the same process (fewer steps, a smaller oracle sample), and
+        # what a launch costs at the least: the floor under the small one-worker workloads
+        result["launch_floor_ms"] = launch_floor(torch)
+        result["per_config"] = {}
+        for cfg in (1, 2, 3, 4, 5):
+            if cfg == args.config:
+                continue
+            torch.cuda.empty_cache()
+            r = measure(args, cfg, max(3, min(args.steps, 10)), min(args.warmup, 2),
+                        None if args.no_cpu_baseline else 60_000_000)
+            result["per_config"]["config%d" % cfg] = {k: r[k] for k in ("config", "value", "unit", "steps", "ms_per_step",
+                                                                        "phases", "bits_per_coord", "roofline",
+                                                                        "roofline_decode", "cpu_baseline") if k in r}
+    print(json.dumps(result))
 
+
+def launch_floor(torch):
+    """Milliseconds per launch of the library's smallest kernel (norm of one coordinate), 200 back to back."""
+    import paper_1908_06077_amd as nuq
+    dev = torch.device("cuda:0")
+    v = torch.ones(1, dtype=torch.float32, device=dev)
+    out = torch.empty(1, dtype=torch.float32, device=dev)
+    for _ in range(10):
+        nuq.nuq_bucket_norms(v, 1, out)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(200):
+        nuq.nuq_bucket_norms(v, 1, out)
+    b.record()
+    torch.cuda.synchronize()
+    return round(a.elapsed_time(b) / 200, 5)
+
+
+def measure(args, config, steps, warmup, cpu_budget):
+    """One workload: `warmup` untimed steps, `steps` timed ones, phase split, rooflines; the result as a dict."""
     import numpy as np
     import torch
 
     import paper_1908_06077_amd as nuq
     import workloads
 
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
     dev = torch.device("cuda:0")
-    w = workloads.workload(args.config)
+    w = workloads.workload(config)
     d, n, s, K = w.d, w.bucket, w.s, w.K
     S = args.sync_stride if args.sync_stride is not None else (256 if n >= 1024 else 128)
     if n <= S:
@@ -200,7 +244,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     assert nuq.nuq_last_error_flags() == 0, "device error flags raised during warmup"
@@ -217,19 +261,19 @@ def main():
         graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(args.steps):
+        for i in range(steps):
             graph.replay()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        nuq.nuq_timing_begin(min(4096, args.steps * (4 * K + 2)))
-        for i in range(args.steps):
+        nuq.nuq_timing_begin(min(4096, steps * (4 * K + 2)))
+        for i in range(steps):
             step()
         torch.cuda.synchronize()
     else:
-        nuq.nuq_timing_begin(min(4096, args.steps * (4 * K + 2)))
+        nuq.nuq_timing_begin(min(4096, steps * (4 * K + 2)))
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(args.steps):
+        for i in range(steps):
             step()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
@@ -237,7 +281,7 @@ def main():
     assert nuq.nuq_last_error_flags() == 0, "device error flags raised during the timed region"
 
     # phase split, outside the timed region: events around the two library calls of a few more steps
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(min(args.steps, 10))]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(min(steps, 10))]
     for e in ev:
         e[0].record()
         encode_all()
@@ -246,7 +290,7 @@ def main():
         e[2].record()
     torch.cuda.synchronize()
 
-    ms_step = (t1 - t0) * 1e3 / args.steps
+    ms_step = (t1 - t0) * 1e3 / steps
     ms_enc = float(np.median([e[0].elapsed_time(e[1]) for e in ev]))
     ms_dec = float(np.median([e[1].elapsed_time(e[2]) for e in ev]))
     in_bytes = 4.0 * d * K
@@ -285,8 +329,8 @@ def main():
         "value": round(value, 2),
         "unit": "GB/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(ms_step, 4),
         "higher_is_better": True,
         "scaling": "weak",
@@ -294,7 +338,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "configs[%d] %s: d=%d fp32, bucket=%d, s=%d, K=%d workers, sync_stride=%d%s"
-                               % (args.config - 1, w.name, d, n, s, K, S,
+                               % (config - 1, w.name, d, n, s, K, S,
                                   ", Huffman-coded levels, lengths %s" % hlen if huff else
                                   (", fixed-width %d bits" % fb) if fb else
                                   "" if lev is None else ", level table %s, %s norm" % (args.levels, args.norm))},
@@ -312,7 +356,7 @@ def main():
                                 % ("worker" if args.per_worker_calls else "step (all K workers)")),
                      "bound": "hbm", "achieved": round(enc_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(enc_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None if lev is not None or fb or huff else measured_traffic("k_encode", args.config, S),
+                     "traffic": None if lev is not None or fb or huff else measured_traffic("k_encode", config, S),
                      "bytes_per_launch": round(enc_launch_bytes), "launch_ms": round(enc_kernel_ms, 5),
                      "launches": len(enc_ms)},
         "roofline_decode": {"kernel": ("k_huffman_decode_direct, all K messages in one launch (k_average_levels follows)"
@@ -322,7 +366,7 @@ def main():
                             "bound": "hbm", "achieved": round(dec_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
                             "traffic": None if lev is not None or fb or huff or upd in ("sgd", "momentum")
-                            else measured_traffic("k_decode_accumulate", args.config, S),
+                            else measured_traffic("k_decode_accumulate", config, S),
                             "bytes_per_launch": round(dec_alg), "launch_ms": round(dec_kernel_ms, 5),
                             "launches": len(dec_ms)},
     }
@@ -355,9 +399,9 @@ def main():
                                 "unit": "GB/s", "frac": round(20.0 * d / (ms_mom * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     if args.reference_kernels:
         result["reference"] = reference_kernels(torch, d * K, dev)
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, grads, S, lev, args.norm, fb, hlen if huff else None)
-    print(json.dumps(result))
+    if cpu_budget:
+        result["cpu_baseline"] = cpu_baseline(w, grads, S, lev, args.norm, fb, hlen if huff else None, cpu_budget)
+    return result
 
 
 def reference_kernels(torch, numel, dev):
@@ -399,51 +443,78 @@ def measured_traffic(kernel, config, S):
     return None if entry is None else entry.get("bytes_per_launch")
 
 
-def cpu_baseline(w, grads, S, lev=None, norm="l2", fb=0, hlen=None):
-    """The CPU oracle as it stands, one thread, on the same workload (bounded to ~30 s of CPU work)."""
+def cpu_baseline(w, grads, S, lev=None, norm="l2", fb=0, hlen=None, budget_coords=300_000_000):
+    """The CPU oracle as it stands on a bounded sample of the same workload: once on one thread, once with the sample's
+    buckets dealt out to all of the host's cores (buckets are independent: every thread runs the same sequential
+    oracle calls on its own run of buckets of every worker; ctypes releases the interpreter lock during a call)."""
     import numpy as np
     import oracle
+    from concurrent.futures import ThreadPoolExecutor
 
     d, n, s, K = w.d, w.bucket, w.s, w.K
-    # bound the sample: the oracle runs ~20 M coordinates/s/worker on the encode side
-    budget_coords = 300_000_000
     d_s = d if d * K <= budget_coords else max(n, (budget_coords // K) // n * n)
     host = [g[:d_s].cpu().numpy() for g in grads]
-    t0 = time.perf_counter()
-    parts = []
-    for k in range(K):
-        norms = (oracle.bucket_norms_linf if norm == "linf" else oracle.bucket_norms)(host[k], n).astype(np.float32)
-        if lev is None:
-            q = oracle.quantize(host[k], n, s, w.quant_seed(k), norms)
-        else:
-            q = oracle.quantize_table(host[k], n, lev, w.quant_seed(k), norms)
-        if fb:
-            parts.append((norms, oracle.pack_fixed(q, n, s, fb), None))
-            continue
+    nb = (d_s + n - 1) // n
+    nproc = os.cpu_count() or 1
+    # the GPU boxes give a job 16 cores whatever the machine has
+    threads = max(1, min(nproc, int(os.environ.get("OMP_NUM_THREADS", "16")), 16))
+
+    def chunk(b_lo, b_hi):
+        """Whole step on buckets [b_lo, b_hi): encode of each worker, then decode + average of the K messages."""
+        c_lo, c_hi = b_lo * n, min(d_s, b_hi * n)
+        t0 = time.perf_counter()
+        parts = []
+        for k in range(K):
+            v = host[k][c_lo:c_hi]
+            norms = (oracle.bucket_norms_linf if norm == "linf" else oracle.bucket_norms)(v, n).astype(np.float32)
+            if lev is None:
+                q = oracle.quantize(v, n, s, w.quant_seed(k), norms, b_lo)
+            else:
+                q = oracle.quantize_table(v, n, lev, w.quant_seed(k), norms, b_lo)
+            if fb:
+                parts.append((norms, oracle.pack_fixed(q, n, s, fb), None))
+            elif hlen is not None:
+                bo, words, _ = oracle.encode_huffman(q, n, s, hlen, S)
+                parts.append((norms, bo, words))
+            else:
+                bo, words, _ = oracle.encode(q, n, s, S)
+                parts.append((norms, bo, words))
+        t1 = time.perf_counter()
+        m = c_hi - c_lo
         if hlen is not None:
-            bo, words, _ = oracle.encode_huffman(q, n, s, hlen, S)
-            parts.append((norms, bo, words))
-            continue
-        bo, words, _ = oracle.encode(q, n, s, S)
-        parts.append((norms, bo, words))
-    t1 = time.perf_counter()
-    if hlen is not None:
-        acc = np.zeros(d_s)
-        for norms, bo, words in parts:
-            acc += oracle.dequantize(oracle.decode_huffman(bo, words, d_s, n, s, hlen), n, s, norms)
-        acc *= 1.0 / K
-    elif fb:
-        oracle.unpack_average_fixed([p[0] for p in parts], [p[1] for p in parts], d_s, n, s, fb, 1.0 / K)
-    elif lev is None:
-        oracle.decode_average([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], d_s, n, s, 1.0 / K)
-    else:
-        oracle.decode_average_table([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], d_s, n, lev,
-                                    1.0 / K)
-    t2 = time.perf_counter()
+            acc = np.zeros(m)
+            for norms, bo, words in parts:
+                acc += oracle.dequantize(oracle.decode_huffman(bo, words, m, n, s, hlen), n, s, norms)
+            acc *= 1.0 / K
+        elif fb:
+            oracle.unpack_average_fixed([p[0] for p in parts], [p[1] for p in parts], m, n, s, fb, 1.0 / K)
+        elif lev is None:
+            oracle.decode_average([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], m, n, s, 1.0 / K)
+        else:
+            oracle.decode_average_table([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], m, n, lev,
+                                        1.0 / K)
+        return t1 - t0, time.perf_counter() - t1
+
+    # runs of buckets: a few per thread, so that the threads finish together
+    nchunks = max(1, min(nb, 4 * threads))
+    edges = [nb * i // nchunks for i in range(nchunks + 1)]
+    runs = [(edges[i], edges[i + 1]) for i in range(nchunks) if edges[i + 1] > edges[i]]
     in_bytes = 4.0 * d_s * K
-    return {"value": round(in_bytes / (t2 - t0) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "same workload, first %d of %d coordinates of each of the %d workers; "
-                      "encode %.2f s, decode+average %.2f s" % (d_s, d, K, t1 - t0, t2 - t1)}
+    t0 = time.perf_counter()
+    split = [chunk(lo, hi) for lo, hi in runs]
+    t_one = time.perf_counter() - t0
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        t0 = time.perf_counter()
+        list(pool.map(lambda r: chunk(*r), runs))
+        t_all = time.perf_counter() - t0
+    return {"value": round(in_bytes / t_all / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "nproc": nproc,
+            "one_thread": {"value": round(in_bytes / t_one / 1e9, 4), "unit": "GB/s", "cores": 1,
+                           "encode_s": round(sum(x[0] for x in split), 2),
+                           "decode_average_s": round(sum(x[1] for x in split), 2)},
+            "sample": "same workload, first %d of %d coordinates of each of the %d workers, whole step (encode, then "
+                      "decode + average), in %d runs of buckets: %.2f s on one thread, %.2f s on %d threads"
+                      % (d_s, d, K, len(runs), t_one, t_all, threads)}
 
 
 if __name__ == "__main__":
