@@ -352,14 +352,20 @@ def test_encode_and_decode_replayed_from_a_hip_graph(g):
     assert nuq.nuq_last_error_flags() == 0
 
 
+DIRTY = -0x5A5A5A5B           # 0xA5A5A5A5 as the int32 the word buffers are typed with
+
+
 @pytest.mark.gpu
 def test_full_size_in_the_benchmark_configuration(g):
     """BASELINE configs 3-5 at full size, launched the way bench.py launches them (all K workers in one encode
-    call, bench's sync stride, one decode call over the K messages).  Compared on sampled runs of buckets (the
-    first, the last with the short bucket, and seeded random ones), which the oracle computes one by one; global
-    structure (offsets non-decreasing, word-aligned starts accounted for, no error flags) checked everywhere."""
+    call, bench's sync stride, one decode call over the K messages), into word buffers that hold a non-zero
+    pattern before the encode.  Configs 3 and 4: every bucket of every worker's message bit-exact against the
+    oracle, every element and bucket of the average within the bar.  Config 5: every bucket of every worker's
+    message, and the average on sampled runs of buckets (the first, the last with the short bucket, seeded random
+    ones).  Offsets non-decreasing with word-aligned starts accounted for, words
+    beyond a message untouched, no error flags."""
     nuq = g.nuq
-    for cfg, nruns, run_len in ((3, 24, 4), (4, 12, 2), (5, 48, 32)):
+    for cfg in (3, 4, 5):
         w = workloads.workload(cfg)
         n, s, K, d = w.bucket, w.s, w.K, w.d
         S = 256 if n >= 1024 else 128
@@ -367,7 +373,7 @@ def test_full_size_in_the_benchmark_configuration(g):
         print("cfg %d: generating %d x %d coordinates" % (cfg, K, d), flush=True)
         vs = [workloads.generate(w, k, g.DEV) for k in range(K)]
         seeds = [w.quant_seed(k) for k in range(K)]
-        msgs = g.batched_encode(vs, n, s, seeds, S)
+        msgs = g.batched_encode(vs, n, s, seeds, S, fill=DIRTY)
         out = torch.empty(d, dtype=torch.float32, device=g.DEV)
         nuq.nuq_decode_accumulate(msgs, d, n, s, S, 1.0 / K, False, out)
         assert nuq.nuq_last_error_flags() == 0
@@ -375,10 +381,20 @@ def test_full_size_in_the_benchmark_configuration(g):
             bo = m.bit_off
             assert int(bo[0].item()) == 0
             assert bool((bo[1:] >= (bo[:-1] + 31) // 32 * 32).all())      # a bucket ends at or after its aligned start
-        rng = np.random.default_rng(cfg)
-        starts = {0, B - run_len} | {int(x) for x in rng.integers(0, B - run_len, size=nruns)}
-        for b_lo in sorted(starts):
-            g.check_bucket_run(vs, msgs, out, n, s, seeds, S, 1.0 / K, b_lo, b_lo + run_len)
-        print("cfg %d: %d runs of %d buckets bit-exact, averages within the bar" % (cfg, len(starts), run_len), flush=True)
+            W = (int(bo[-1].item()) + 31) // 32
+            assert bool((m.words[W:] == DIRTY).all())                     # nothing written past the message
+        if cfg != 5:
+            g.check_every_bucket(vs, msgs, out, n, s, seeds, S, 1.0 / K)
+            print("cfg %d: all %d buckets of %d workers bit-exact, averages within the bar" % (cfg, B, K), flush=True)
+        else:
+            g.check_every_bucket(vs, msgs, None, n, s, seeds, S, 1.0 / K)
+            print("cfg 5: all %d buckets of %d workers bit-exact" % (B, K), flush=True)
+            rng = np.random.default_rng(cfg)
+            run_len = 64
+            starts = {0, B - run_len} | {int(x) for x in rng.integers(0, B - run_len, size=96)}
+            for b_lo in sorted(starts):
+                g.check_bucket_run(vs, msgs, out, n, s, seeds, S, 1.0 / K, b_lo, b_lo + run_len)
+            print("cfg 5: %d runs of %d buckets, all workers bit-exact, averages within the bar"
+                  % (len(starts), run_len), flush=True)
         del vs, msgs, out
         torch.cuda.empty_cache()
