@@ -168,18 +168,23 @@ int nuq_quantize_encode_batch(uint32_t K, const float *const *v, const uint64_t 
  * (sign, j) of coordinate i is decoded from worker k's bit string (0 if absent).
  * norms, bit_off, words, sync: HOST arrays of K device pointers (one message per
  * worker, all encoded with the same d, bucket, s, sync_stride); sync may be NULL or hold
- * NULLs when sync_stride == 0.  1 <= K <= NUQ_MAX_WORKERS; average with scale = 1/K.
+ * NULLs when sync_stride == 0.  words_len: HOST array of K counts, the u32 words that
+ * words[k] holds (as received).  1 <= K <= NUQ_MAX_WORKERS; average with scale = 1/K.
  * The sum over workers is taken in fp64 (in no fixed order, which cannot change it unless the
  * terms' exponents span more than 2^29), scaled in fp64 and rounded to fp32 once; with accumulate the
  * old out[i] is then added in fp32.  out: d floats.
  * A record that leaves its bucket's bit range or index range, a level index outside 1..s+1, or a
  * sync entry that contradicts the bit offsets raises NUQ_FLAG_MALFORMED and ends that part's
- * decoding.  bit_off itself is trusted to point inside words (words carries no length here): pass
- * the encoder's arrays, or check bit_off[B] against the words received before calling. */
+ * decoding.  So does a bucket whose offsets run backwards (bit_off[b+1] < bit_off[b]), end beyond
+ * the words received (bit_off[b+1] > 32 * words_len[k]) or span 2^21 bits or more: such a bucket
+ * contributes nothing and no word of it is read, so a cut-off or corrupted message cannot make the
+ * kernels read outside words[k].  (norms, bit_off and sync are sized by d, bucket and sync_stride,
+ * which the caller vouches for.) */
 int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
-                          const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
-                          uint32_t bucket, uint32_t s, uint32_t sync_stride, float scale,
-                          int accumulate, float *out, nuq_stream_t stream);
+                          const uint32_t *const *words, const uint64_t *words_len,
+                          const uint32_t *const *sync, uint64_t d, uint32_t bucket, uint32_t s,
+                          uint32_t sync_stride, float scale, int accumulate, float *out,
+                          nuq_stream_t stream);
 
 /* ---- other level sequences and the maximum norm (Sec. 3.1 before the special case; Sec. 4.1,
  *      "Generally spaced levels": exponential levels (0, p^s, ..., p, 1); uniform levels = QSGD,
@@ -222,9 +227,10 @@ int nuq_quantize_encode_table_batch(uint32_t K, const float *const *v, const uin
 /* nuq_decode_accumulate with l_j = levels[j]: out[i] = (accumulate ? out[i] : 0) +
  * scale * sum_k norms_k[b] * sign * levels[j].  Everything else as nuq_decode_accumulate. */
 int nuq_decode_accumulate_table(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
-                                const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
-                                uint32_t bucket, uint32_t s, uint32_t sync_stride, const float *levels,
-                                float scale, int accumulate, float *out, nuq_stream_t stream);
+                                const uint32_t *const *words, const uint64_t *words_len,
+                                const uint32_t *const *sync, uint64_t d, uint32_t bucket, uint32_t s,
+                                uint32_t sync_stride, const float *levels, float scale, int accumulate,
+                                float *out, nuq_stream_t stream);
 
 /* ---- fixed-width coding (Sec. 5: the "4-bit" and "8-bit" variants; 3 bits in Table 1) ------------ */
 
@@ -334,9 +340,10 @@ int nuq_momentum_step(float *w, float *yl, const float *g, uint64_t d, float alp
  * stored, which saves its write and read (8 of the update's 24 bytes per coordinate).  Message
  * arguments as nuq_decode_accumulate; alpha, mu, l, w, yl as nuq_momentum_step. */
 int nuq_decode_momentum_step(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
-                             const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
-                             uint32_t bucket, uint32_t s, uint32_t sync_stride, float scale, float alpha,
-                             float mu, float l, float *w, float *yl, nuq_stream_t stream);
+                             const uint32_t *const *words, const uint64_t *words_len,
+                             const uint32_t *const *sync, uint64_t d, uint32_t bucket, uint32_t s,
+                             uint32_t sync_stride, float scale, float alpha, float mu, float l, float *w,
+                             float *yl, nuq_stream_t stream);
 
 /* First and second moments of a gradient estimate across draws (App. J): sum[i] += g[i],
  * sumsq[i] += g[i]^2 in fp64; g, sum, sumsq: DEVICE arrays of d values, sum and sumsq zeroed by the

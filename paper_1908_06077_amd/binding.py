@@ -35,12 +35,12 @@ _SIGNATURES = {
     "nuq_encode": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
     "nuq_quantize_encode": (_i32, [_vp, _u64, _u32, _u32, _u64, _u32, _vp, _vp, _vp, _u64, _vp, _vp, _u64, _vp]),
     "nuq_quantize_encode_static": (_i32, [_vp, _u64, _u32, _u32, _u64, _u32, _vp, _vp, _vp, _u64, _vp, _vp]),
-    "nuq_decode_accumulate": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _i32, _vp, _vp]),
+    "nuq_decode_accumulate": (_i32, [_u32, _vp, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _i32, _vp, _vp]),
     "nuq_bucket_norms_linf": (_i32, [_vp, _u64, _u32, _vp, _vp]),
     "nuq_quantize_table": (_i32, [_vp, _u64, _u32, _u32, _vp, _u64, _vp, _vp, _vp]),
     "nuq_quantize_encode_table_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _vp, _u32, _u32, _vp, _vp, _vp, _vp, _vp,
                                                _vp, _u64, _vp]),
-    "nuq_decode_accumulate_table": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _f32, _i32, _vp, _vp]),
+    "nuq_decode_accumulate_table": (_i32, [_u32, _vp, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _f32, _i32, _vp, _vp]),
     "nuq_fixed_words": (_u64, [_u64, _u32, _u32]),
     "nuq_pack_fixed": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp]),
     "nuq_quantize_pack_fixed_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
@@ -57,7 +57,7 @@ _SIGNATURES = {
     "nuq_decode_huffman_batch": (_i32, [_u32, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "nuq_average_levels": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _f32, _i32, _vp, _vp]),
     "nuq_momentum_step": (_i32, [_vp, _vp, _vp, _u64, _f32, _f32, _f32, _vp]),
-    "nuq_decode_momentum_step": (_i32, [_u32, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _f32, _f32, _f32, _vp,
+    "nuq_decode_momentum_step": (_i32, [_u32, _vp, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _f32, _f32, _f32, _vp,
                                         _vp, _vp]),
     "nuq_moments_accumulate": (_i32, [_vp, _vp, _vp, _u64, _vp]),
     "nuq_normalized_variance": (_i32, [_vp, _vp, _u64, _u64, _vp, _u64, _vp, _vp]),
@@ -95,14 +95,44 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def _ptr(t: torch.Tensor | None, dtype: torch.dtype | None = None) -> int:
+def _on_device(t: torch.Tensor) -> bool:
+    return t.is_cuda
+
+
+def _ptr(t: torch.Tensor | None, dtype: torch.dtype | None = None, need: int = 0, what: str = "tensor") -> int:
+    """Device address of t after checking what the kernels take on trust: placement, contiguity, element type and
+    that it holds at least `need` elements."""
     if t is None:
+        if need:
+            raise ValueError("%s is needed (%d elements)" % (what, need))
         return 0
-    if not t.is_cuda or not t.is_contiguous():
-        raise ValueError("expected a contiguous device tensor")
     if dtype is not None and t.dtype != dtype:
-        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+        raise ValueError("%s: expected dtype %s, got %s" % (what, dtype, t.dtype))
+    if t.numel() < need:
+        raise ValueError("%s holds %d elements, %d are needed" % (what, t.numel(), need))
+    if not _on_device(t) or not t.is_contiguous():
+        raise ValueError("%s: expected a contiguous device tensor" % what)
     return t.data_ptr()
+
+
+def _sizes(d: int, bucket: int, sync_stride: int, huffman: bool = False) -> tuple[int, int]:
+    """(buckets, sync entries of a whole message) for the size checks; (0, 0) for arguments the library rejects."""
+    B = _lib.nuq_num_buckets(d, bucket)
+    per = (_lib.nuq_huffman_num_sync if huffman else _lib.nuq_num_sync)(bucket, sync_stride) if bucket else 0
+    return B, B * per
+
+
+def _message_arrays(messages, d: int, bucket: int, sync_stride: int, huffman: bool = False, norms: bool = True):
+    """ctypes pointer arrays (norms, bit_off, words, words_len, sync) of K messages, every tensor checked against the
+    size that d, bucket and sync_stride imply."""
+    K = len(messages)
+    B, nsync = _sizes(d, bucket, sync_stride, huffman)
+    vp, u64 = ctypes.c_void_p * K, ctypes.c_uint64 * K
+    return (vp(*[_ptr(m.norms, torch.float32, B, "norms") for m in messages]) if norms else None,
+            vp(*[_ptr(m.bit_off, torch.int64, B + 1, "bit_off") for m in messages]),
+            vp(*[_ptr(m.words, torch.int32, 0, "words") for m in messages]),
+            u64(*[m.words.numel() for m in messages]),
+            vp(*[_ptr(m.sync, torch.int32, nsync, "sync") for m in messages]))
 
 
 # ------------------------------------------------------------------ sizes (host only)
@@ -131,13 +161,15 @@ def nuq_encode_workspace_bytes(K: int, d: int, bucket: int, s: int) -> int:
 
 def nuq_bucket_norms(v: torch.Tensor, bucket: int, norms: torch.Tensor) -> None:
     _check("nuq_bucket_norms",
-           _lib.nuq_bucket_norms(_ptr(v, torch.float32), v.numel(), bucket, _ptr(norms, torch.float32), _stream()))
+           _lib.nuq_bucket_norms(_ptr(v, torch.float32), v.numel(), bucket,
+                                 _ptr(norms, torch.float32, nuq_num_buckets(v.numel(), bucket), "norms"), _stream()))
 
 
 def nuq_quantize(v: torch.Tensor, bucket: int, s: int, seed: int, norms: torch.Tensor, q: torch.Tensor) -> None:
     _check("nuq_quantize",
            _lib.nuq_quantize(_ptr(v, torch.float32), v.numel(), bucket, s, seed & (2 ** 64 - 1),
-                             _ptr(norms, torch.float32), _ptr(q, torch.uint8), _stream()))
+                             _ptr(norms, torch.float32, nuq_num_buckets(v.numel(), bucket), "norms"),
+                             _ptr(q, torch.uint8, v.numel(), "q"), _stream()))
 
 
 @dataclass
@@ -151,20 +183,23 @@ class Message:
 
 def nuq_encode(q: torch.Tensor, bucket: int, s: int, sync_stride: int, bit_off: torch.Tensor, words: torch.Tensor,
                sync: torch.Tensor | None, workspace: torch.Tensor) -> None:
+    B, nsync = _sizes(q.numel(), bucket, sync_stride)
     _check("nuq_encode",
-           _lib.nuq_encode(_ptr(q, torch.uint8), q.numel(), bucket, s, sync_stride, _ptr(bit_off, torch.int64),
-                           _ptr(words, torch.int32), words.numel(), _ptr(sync), _ptr(workspace),
+           _lib.nuq_encode(_ptr(q, torch.uint8), q.numel(), bucket, s, sync_stride,
+                           _ptr(bit_off, torch.int64, B + 1, "bit_off"), _ptr(words, torch.int32), words.numel(),
+                           _ptr(sync, torch.int32, nsync, "sync"), _ptr(workspace),
                            workspace.numel() * workspace.element_size(), _stream()))
 
 
 def nuq_quantize_encode(v: torch.Tensor, bucket: int, s: int, seed: int, sync_stride: int, norms: torch.Tensor,
                         bit_off: torch.Tensor, words: torch.Tensor, sync: torch.Tensor | None,
                         workspace: torch.Tensor) -> None:
+    B, nsync = _sizes(v.numel(), bucket, sync_stride)
     _check("nuq_quantize_encode",
            _lib.nuq_quantize_encode(_ptr(v, torch.float32), v.numel(), bucket, s, seed & (2 ** 64 - 1), sync_stride,
-                                    _ptr(norms, torch.float32), _ptr(bit_off, torch.int64),
-                                    _ptr(words, torch.int32), words.numel(), _ptr(sync), _ptr(workspace),
-                                    workspace.numel() * workspace.element_size(), _stream()))
+                                    _ptr(norms, torch.float32, B, "norms"), _ptr(bit_off, torch.int64, B + 1, "bit_off"),
+                                    _ptr(words, torch.int32), words.numel(), _ptr(sync, torch.int32, nsync, "sync"),
+                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 STATIC_WORKSPACE_BYTES = 32 << 20
@@ -173,10 +208,12 @@ STATIC_WORKSPACE_BYTES = 32 << 20
 def nuq_quantize_encode_static(v: torch.Tensor, bucket: int, s: int, seed: int, sync_stride: int, norms: torch.Tensor,
                                bit_off: torch.Tensor, words: torch.Tensor, sync: torch.Tensor | None) -> None:
     """nuq_quantize_encode with the library's own workspace: the call allocates nothing."""
+    B, nsync = _sizes(v.numel(), bucket, sync_stride)
     _check("nuq_quantize_encode_static",
            _lib.nuq_quantize_encode_static(_ptr(v, torch.float32), v.numel(), bucket, s, seed & (2 ** 64 - 1),
-                                           sync_stride, _ptr(norms, torch.float32), _ptr(bit_off, torch.int64),
-                                           _ptr(words, torch.int32), words.numel(), _ptr(sync), _stream()))
+                                           sync_stride, _ptr(norms, torch.float32, B, "norms"),
+                                           _ptr(bit_off, torch.int64, B + 1, "bit_off"), _ptr(words, torch.int32),
+                                           words.numel(), _ptr(sync, torch.int32, nsync, "sync"), _stream()))
 
 
 def nuq_quantize_encode_batch(vs: list[torch.Tensor], bucket: int, s: int, seeds: list[int], sync_stride: int,
@@ -187,28 +224,21 @@ def nuq_quantize_encode_batch(vs: list[torch.Tensor], bucket: int, s: int, seeds
         raise ValueError("K gradients of equal length, K seeds and K messages are needed")
     arr = lambda ts, dt=None: (ctypes.c_void_p * K)(*[_ptr(t, dt) for t in ts])
     u64s = lambda xs: (ctypes.c_uint64 * K)(*[x & (2 ** 64 - 1) for x in xs])
+    norms, offs, words, caps, sync = _message_arrays(messages, d, bucket, sync_stride)
     _check("nuq_quantize_encode_batch",
            _lib.nuq_quantize_encode_batch(K, arr(vs, torch.float32), u64s(seeds), d, bucket, s, sync_stride,
-                                          arr([m.norms for m in messages], torch.float32),
-                                          arr([m.bit_off for m in messages], torch.int64),
-                                          arr([m.words for m in messages], torch.int32),
-                                          u64s([m.words.numel() for m in messages]),
-                                          arr([m.sync for m in messages]), _ptr(workspace),
+                                          norms, offs, words, caps, sync, _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream()))
 
 
 def nuq_decode_accumulate(messages: list[Message], d: int, bucket: int, s: int, sync_stride: int, scale: float,
                           accumulate: bool, out: torch.Tensor) -> None:
     K = len(messages)
-    arr = lambda ts: (ctypes.c_void_p * K)(*[_ptr(t) for t in ts])
-    norms = arr([m.norms for m in messages])
-    offs = arr([m.bit_off for m in messages])
-    words = arr([m.words for m in messages])
-    sync = arr([m.sync for m in messages])
+    norms, offs, words, lens, sync = _message_arrays(messages, d, bucket, sync_stride)
     if out.numel() != d:
         raise ValueError("out must hold d floats")
     _check("nuq_decode_accumulate",
-           _lib.nuq_decode_accumulate(K, norms, offs, words, sync, d, bucket, s, sync_stride, float(scale),
+           _lib.nuq_decode_accumulate(K, norms, offs, words, lens, sync, d, bucket, s, sync_stride, float(scale),
                                       1 if accumulate else 0, _ptr(out, torch.float32), _stream()))
 
 
@@ -222,14 +252,18 @@ def _levels(levels, s: int):
 
 def nuq_bucket_norms_linf(v: torch.Tensor, bucket: int, norms: torch.Tensor) -> None:
     _check("nuq_bucket_norms_linf",
-           _lib.nuq_bucket_norms_linf(_ptr(v, torch.float32), v.numel(), bucket, _ptr(norms, torch.float32), _stream()))
+           _lib.nuq_bucket_norms_linf(_ptr(v, torch.float32), v.numel(), bucket,
+                                      _ptr(norms, torch.float32, nuq_num_buckets(v.numel(), bucket), "norms"),
+                                      _stream()))
 
 
 def nuq_quantize_table(v: torch.Tensor, bucket: int, levels, seed: int, norms: torch.Tensor, q: torch.Tensor) -> None:
     s = len(levels) - 2
     _check("nuq_quantize_table",
            _lib.nuq_quantize_table(_ptr(v, torch.float32), v.numel(), bucket, s, _levels(levels, s),
-                                   seed & (2 ** 64 - 1), _ptr(norms, torch.float32), _ptr(q, torch.uint8), _stream()))
+                                   seed & (2 ** 64 - 1),
+                                   _ptr(norms, torch.float32, nuq_num_buckets(v.numel(), bucket), "norms"),
+                                   _ptr(q, torch.uint8, v.numel(), "q"), _stream()))
 
 
 NORM_L2, NORM_LINF = 0, 1
@@ -244,30 +278,23 @@ def nuq_quantize_encode_table_batch(vs: list[torch.Tensor], bucket: int, levels,
         raise ValueError("K gradients of equal length, K seeds and K messages are needed")
     arr = lambda ts, dt=None: (ctypes.c_void_p * K)(*[_ptr(t, dt) for t in ts])
     u64s = lambda xs: (ctypes.c_uint64 * K)(*[x & (2 ** 64 - 1) for x in xs])
+    norms, offs, words, caps, sync = _message_arrays(messages, d, bucket, sync_stride)
     _check("nuq_quantize_encode_table_batch",
            _lib.nuq_quantize_encode_table_batch(K, arr(vs, torch.float32), u64s(seeds), d, bucket, s,
-                                                _levels(levels, s), norm_kind, sync_stride,
-                                                arr([m.norms for m in messages], torch.float32),
-                                                arr([m.bit_off for m in messages], torch.int64),
-                                                arr([m.words for m in messages], torch.int32),
-                                                u64s([m.words.numel() for m in messages]),
-                                                arr([m.sync for m in messages]), _ptr(workspace),
-                                                workspace.numel() * workspace.element_size(), _stream()))
+                                                _levels(levels, s), norm_kind, sync_stride, norms, offs, words, caps,
+                                                sync, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                _stream()))
 
 
 def nuq_decode_accumulate_table(messages: list[Message], d: int, bucket: int, levels, sync_stride: int, scale: float,
                                 accumulate: bool, out: torch.Tensor) -> None:
     K = len(messages)
     s = len(levels) - 2
-    arr = lambda ts: (ctypes.c_void_p * K)(*[_ptr(t) for t in ts])
-    norms = arr([m.norms for m in messages])
-    offs = arr([m.bit_off for m in messages])
-    words = arr([m.words for m in messages])
-    sync = arr([m.sync for m in messages])
+    norms, offs, words, lens, sync = _message_arrays(messages, d, bucket, sync_stride)
     if out.numel() != d:
         raise ValueError("out must hold d floats")
     _check("nuq_decode_accumulate_table",
-           _lib.nuq_decode_accumulate_table(K, norms, offs, words, sync, d, bucket, s, sync_stride,
+           _lib.nuq_decode_accumulate_table(K, norms, offs, words, lens, sync, d, bucket, s, sync_stride,
                                             _levels(levels, s), float(scale), 1 if accumulate else 0,
                                             _ptr(out, torch.float32), _stream()))
 
@@ -422,12 +449,11 @@ def nuq_momentum_step(w: torch.Tensor, yl: torch.Tensor, g: torch.Tensor, alpha:
 def nuq_decode_momentum_step(messages: list[Message], d: int, bucket: int, s: int, sync_stride: int, scale: float,
                              alpha: float, mu: float, l: float, w: torch.Tensor, yl: torch.Tensor) -> None:
     K = len(messages)
-    arr = lambda ts: (ctypes.c_void_p * K)(*[_ptr(t) for t in ts])
+    norms, offs, words, lens, sync = _message_arrays(messages, d, bucket, sync_stride)
     if w.numel() != d or yl.numel() != d:
         raise ValueError("w and yl hold d floats each")
     _check("nuq_decode_momentum_step",
-           _lib.nuq_decode_momentum_step(K, arr([m.norms for m in messages]), arr([m.bit_off for m in messages]),
-                                         arr([m.words for m in messages]), arr([m.sync for m in messages]), d, bucket,
+           _lib.nuq_decode_momentum_step(K, norms, offs, words, lens, sync, d, bucket,
                                          s, sync_stride, float(scale), float(alpha), float(mu), float(l),
                                          _ptr(w, torch.float32), _ptr(yl, torch.float32), _stream()))
 

@@ -655,12 +655,14 @@ int nuq_quantize_encode_batch(uint32_t K, const float *const *v, const uint64_t 
 
 // levels: nullptr for the levels 2^(j-1-s), else the s + 2 values of a level table (host memory).
 static int decode_accumulate_any(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
-                                 const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
+                                 const uint32_t *const *words, const uint64_t *words_len,
+                                 const uint32_t *const *sync, uint64_t d,
                                  uint32_t bucket, uint32_t s, uint32_t sync_stride, const float *levels, float scale,
                                  int accumulate, float *out, nuq_stream_t stream,
                                  const MomentumParams *momentum = nullptr)
 {
-    if (K < 1 || K > NUQ_MAX_WORKERS || !norms || !bit_off || !words || !out || !valid_common(d, bucket, s) ||
+    if (K < 1 || K > NUQ_MAX_WORKERS || !norms || !bit_off || !words || !words_len || !out ||
+        !valid_common(d, bucket, s) ||
         !valid_sync(sync_stride) || (levels && !valid_levels(levels, s)))
         return NUQ_EINVAL;
     const uint32_t nsync = nuq_num_sync(bucket, sync_stride);
@@ -673,6 +675,7 @@ static int decode_accumulate_any(uint32_t K, const float *const *norms, const ui
         P.norms[k] = norms[k];
         P.bit_off[k] = bit_off[k];
         P.words[k] = words[k];
+        P.words_bits[k] = words_len[k] > (UINT64_MAX >> 5) ? UINT64_MAX : words_len[k] << 5;
         P.sync[k] = nsync ? sync[k] : nullptr;
     }
     uint32_t *flags = flags_ptr();
@@ -798,22 +801,23 @@ int nuq_quantize_encode_table_batch(uint32_t K, const float *const *v, const uin
 }
 
 int nuq_decode_accumulate(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
-                          const uint32_t *const *words, const uint32_t *const *sync, uint64_t d, uint32_t bucket,
-                          uint32_t s, uint32_t sync_stride, float scale, int accumulate, float *out,
-                          nuq_stream_t stream)
+                          const uint32_t *const *words, const uint64_t *words_len, const uint32_t *const *sync,
+                          uint64_t d, uint32_t bucket, uint32_t s, uint32_t sync_stride, float scale, int accumulate,
+                          float *out, nuq_stream_t stream)
 {
-    return decode_accumulate_any(K, norms, bit_off, words, sync, d, bucket, s, sync_stride, nullptr, scale,
+    return decode_accumulate_any(K, norms, bit_off, words, words_len, sync, d, bucket, s, sync_stride, nullptr, scale,
                                  accumulate, out, stream);
 }
 
 int nuq_decode_accumulate_table(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
-                                const uint32_t *const *words, const uint32_t *const *sync, uint64_t d,
-                                uint32_t bucket, uint32_t s, uint32_t sync_stride, const float *levels, float scale,
-                                int accumulate, float *out, nuq_stream_t stream)
+                                const uint32_t *const *words, const uint64_t *words_len,
+                                const uint32_t *const *sync, uint64_t d, uint32_t bucket, uint32_t s,
+                                uint32_t sync_stride, const float *levels, float scale, int accumulate, float *out,
+                                nuq_stream_t stream)
 {
     if (!levels)
         return NUQ_EINVAL;
-    return decode_accumulate_any(K, norms, bit_off, words, sync, d, bucket, s, sync_stride, levels, scale,
+    return decode_accumulate_any(K, norms, bit_off, words, words_len, sync, d, bucket, s, sync_stride, levels, scale,
                                  accumulate, out, stream);
 }
 
@@ -1272,15 +1276,16 @@ int nuq_momentum_step(float *w, float *yl, const float *g, uint64_t d, float alp
 }
 
 int nuq_decode_momentum_step(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
-                             const uint32_t *const *words, const uint32_t *const *sync, uint64_t d, uint32_t bucket,
-                             uint32_t s, uint32_t sync_stride, float scale, float alpha, float mu, float l, float *w,
-                             float *yl, nuq_stream_t stream)
+                             const uint32_t *const *words, const uint64_t *words_len,
+                             const uint32_t *const *sync, uint64_t d, uint32_t bucket, uint32_t s,
+                             uint32_t sync_stride, float scale, float alpha, float mu, float l, float *w, float *yl,
+                             nuq_stream_t stream)
 {
     if (!std::isfinite(alpha) || !std::isfinite(mu) || !std::isfinite(l) || mu < 0.0f || !(mu < 1.0f) || !yl)
         return NUQ_EINVAL;
     const MomentumParams M{w, yl, nullptr, d, (double)alpha, (double)mu, (double)l};
-    return decode_accumulate_any(K, norms, bit_off, words, sync, d, bucket, s, sync_stride, nullptr, scale, 0, w,
-                                 stream, &M);
+    return decode_accumulate_any(K, norms, bit_off, words, words_len, sync, d, bucket, s, sync_stride, nullptr, scale,
+                                 0, w, stream, &M);
 }
 
 int nuq_moments_accumulate(const float *g, double *sum, double *sumsq, uint64_t d, nuq_stream_t stream)

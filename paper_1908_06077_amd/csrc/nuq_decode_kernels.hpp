@@ -37,6 +37,7 @@ struct DecodeParams {
     const float *norms[kMaxWorkers];
     const uint64_t *bit_off[kMaxWorkers];
     const uint32_t *words[kMaxWorkers];
+    uint64_t words_bits[kMaxWorkers];   // 32 * the words each message holds: no offset may point beyond
     const uint32_t *sync[kMaxWorkers];
     float *out;
     uint32_t *flags;
@@ -481,12 +482,16 @@ struct StreamPart {
     uint32_t len;           // the bucket's bit length
 };
 
+// Offsets that run backwards, leave the worker's words (limit = 32 * their count) or span 2^21 bits or more set
+// `bad` and give an empty part: nothing is then read from words[].
 __device__ __forceinline__ StreamPart stream_part(const DecodeParams &P, const TileGeom &G, uint64_t bo0, uint64_t bo1,
-                                                  uint32_t e0, uint32_t e1)
+                                                  uint32_t e0, uint32_t e1, uint64_t limit, bool &bad)
 {
     StreamPart S;
     const uint64_t start = (bo0 + 31ull) & ~31ull;
-    S.len = bo1 > start ? (uint32_t)(bo1 - start) : 0u;
+    const bool wrong = bo1 < bo0 || bo1 > limit || (bo1 > start && bo1 - start > (uint64_t)kSyncOffMask);
+    bad |= wrong;
+    S.len = bo1 > start && !wrong ? (uint32_t)(bo1 - start) : 0u;
     uint32_t lo = 0, hi = S.len;
     if (!P.buckets_per_tile && P.nsync) {
         lo = min(e0 & kSyncOffMask, S.len);
@@ -603,7 +608,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
             return U;
         const uint64_t b = G.b0 + bi;
         const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
-        const StreamPart S = stream_part(P, G, m.bo0, m.bo1, m.e0, m.e1);
+        const StreamPart S = stream_part(P, G, m.bo0, m.bo1, m.e0, m.e1, P.words_bits[k], bad);
         uint32_t bit_lo = 0, bit_hi = S.len;
         U.idx_hi = nbk;
         if (P.nsync) {
@@ -679,8 +684,13 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         const uint32_t nbk = (uint32_t)min((uint64_t)P.bucket, P.d - b * P.bucket);
         if (G.in_lo >= nbk)
             return;
-        const uint64_t start = (P.bit_off[k][b] + 31ull) & ~31ull;
+        const uint64_t bo0 = P.bit_off[k][b];
+        const uint64_t start = (bo0 + 31ull) & ~31ull;
         const uint64_t end = P.bit_off[k][b + 1];
+        if (end < bo0 || end > P.words_bits[k] || (end > start && end - start > (uint64_t)kSyncOffMask)) {
+            bad = true;                         // offsets that run backwards, leave the words or span too much
+            return;
+        }
         const uint32_t len = end > start ? (uint32_t)(end - start) : 0u;
         const double wnorm = (double)P.norms[k][b] * wscale;
         WalkWords gw{P.words[k] + (start >> 5)};
@@ -757,7 +767,7 @@ __global__ __launch_bounds__(kDecodeWG, 4) void k_decode_accumulate(DecodeParams
         const uint32_t *const s_words = P.words[sk];
         const uint32_t *src = s_words;
         if (my_stream < G.nstreams && !walk) {
-            const StreamPart S = stream_part(P, G, sr.bo0, sr.bo1, sr.e0, sr.e1);
+            const StreamPart S = stream_part(P, G, sr.bo0, sr.bo1, sr.e0, sr.e1, P.words_bits[sk], bad);
             cnt = min(S.nwords, stream_stride);
             src = s_words + S.first_word;
         }
@@ -947,6 +957,7 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
     const float *const pn = P.norms[sk];
     const uint32_t *const ps = P.sync[sk];
     const uint32_t *const pw = P.words[sk];
+    const uint64_t words_bits = P.words_bits[sk];
     const uint32_t first_lane = lane & ~(lanes - 1u);
 
     auto load_meta = [&](const TileGeom &G) {
@@ -963,14 +974,17 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
     };
     // the part of the lane's stream that the tile needs: from the entry of the tile's first piece to that of the
     // piece after its last one (held by the stream's first and last lanes)
-    auto part_of = [&](const TileGeom &G, const WaveMeta &m) {
+    auto part_of = [&](const TileGeom &G, const WaveMeta &m, bool &bad) {
         uint32_t e0 = 0, e1 = 0;
         if (partial) {
             const uint32_t pieces = G.g1 - G.g0;                      // >= 1 for a tile with coordinates
             e0 = (uint32_t)__shfl((int)m.e_lo, (int)first_lane, kWave);
             e1 = (uint32_t)__shfl((int)m.e_hi, (int)(first_lane + max(pieces, 1u) - 1u), kWave);
         }
-        return stream_part(P, G, m.bo0, m.bo1, e0, e1);
+        bool wrong = false;
+        const StreamPart S = stream_part(P, G, m.bo0, m.bo1, e0, e1, words_bits, wrong);
+        bad |= wrong && my_stream < G.nstreams;                       // (a lane without a stream loaded any bucket's)
+        return S;
     };
     auto load_words = [&](const TileGeom &G, const StreamPart &S, uint32_t (&w)[kWordsPerLane]) {
         // lanes beyond the part's end load its last word again (nothing reads what they store); a lane without a
@@ -1023,7 +1037,7 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
         G1 = tile_geom(P, xcd_tile(P, t + stride));
         M1 = load_meta(G1);
     }
-    StreamPart S0 = part_of(G0, M0);
+    StreamPart S0 = part_of(G0, M0, bad);
     uint32_t W0[kWordsPerLane];
     load_words(G0, S0, W0);
     store_words(W0);
@@ -1040,7 +1054,7 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
         TileGeom G2 = G1;
         WaveMeta M2 = M1;
         if (has1) {
-            S1 = part_of(G1, M1);
+            S1 = part_of(G1, M1, bad);
             load_words(G1, S1, W0);
         }
         if (has2) {
@@ -1135,7 +1149,8 @@ __global__ __launch_bounds__(kSingleWG) void k_decode_single(DecodeParams P)
     bool work = u < units;
     const uint64_t bo0 = P.bit_off[0][b], bo1 = P.bit_off[0][b + 1];
     const uint64_t start = (bo0 + 31ull) & ~31ull;
-    bool bad = work && bo1 > start && bo1 - start > 0x1FFFFFull;    // a bucket's bit string is below 2^21 bits
+    // offsets run forwards, stay inside the words received, and a bucket's bit string is below 2^21 bits
+    bool bad = work && (bo1 < bo0 || bo1 > P.words_bits[0] || (bo1 > start && bo1 - start > 0x1FFFFFull));
     const uint32_t len = bo1 > start && !bad ? (uint32_t)(bo1 - start) : 0u;
     uint32_t bit_lo = 0, bit_hi = len;
     int forced = -1;

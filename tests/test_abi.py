@@ -104,15 +104,63 @@ def test_argument_errors_of_the_update_entry_points(nuq):
     assert lib.nuq_normalized_variance(16, 16, 8, 3, 20, 16384, 16, None) == EINVAL         # workspace misaligned
     assert lib.nuq_normalized_variance(16, 16, 8, 3, 16, 16384, None, None) == EINVAL       # no output
     lib.nuq_decode_momentum_step.restype = ctypes.c_int
-    lib.nuq_decode_momentum_step.argtypes = [ctypes.c_uint32, vp, vp, vp, vp, u64, ctypes.c_uint32, ctypes.c_uint32,
+    lib.nuq_decode_momentum_step.argtypes = [ctypes.c_uint32, vp, vp, vp, vp, vp, u64, ctypes.c_uint32, ctypes.c_uint32,
                                              ctypes.c_uint32, f32, f32, f32, f32, vp, vp, vp]
     one = (ctypes.c_void_p * 1)(16)
-    assert lib.nuq_decode_momentum_step(1, one, one, one, one, 8, 4, 3, 0, 1.0, 0.1, 0.5, 0.0, 16, None, None) == EINVAL
-    assert lib.nuq_decode_momentum_step(1, one, one, one, one, 8, 4, 3, 0, 1.0, 0.1, 1.5, 0.0, 16, 16, None) == EINVAL
-    assert lib.nuq_decode_momentum_step(0, one, one, one, one, 8, 4, 3, 0, 1.0, 0.1, 0.5, 0.0, 16, 16, None) == EINVAL
+    n1 = (ctypes.c_uint64 * 1)(4)
+    assert lib.nuq_decode_momentum_step(1, one, one, one, n1, one, 8, 4, 3, 0, 1.0, 0.1, 0.5, 0.0, 16, None, None) == EINVAL
+    assert lib.nuq_decode_momentum_step(1, one, one, one, n1, one, 8, 4, 3, 0, 1.0, 0.1, 1.5, 0.0, 16, 16, None) == EINVAL
+    assert lib.nuq_decode_momentum_step(0, one, one, one, n1, one, 8, 4, 3, 0, 1.0, 0.1, 0.5, 0.0, 16, 16, None) == EINVAL
+    # the decoders want the length of every message's words
+    lib.nuq_decode_accumulate.restype = ctypes.c_int
+    lib.nuq_decode_accumulate.argtypes = [ctypes.c_uint32, vp, vp, vp, vp, vp, u64, ctypes.c_uint32, ctypes.c_uint32,
+                                          ctypes.c_uint32, f32, ctypes.c_int, vp, vp]
+    assert lib.nuq_decode_accumulate(1, one, one, one, None, one, 8, 4, 3, 0, 1.0, 0, 16, None) == EINVAL
+    assert lib.nuq_decode_accumulate(1, one, one, one, n1, one, 8, 4, 3, 0, 1.0, 0, None, None) == EINVAL      # no out
     lib.nuq_fixed_words.restype = ctypes.c_uint64
     lib.nuq_fixed_words.argtypes = [u64, ctypes.c_uint32, ctypes.c_uint32]
     assert lib.nuq_fixed_words(100, 32, 4) == 4 * 4 and lib.nuq_fixed_words(100, 32, 2) == 0 and lib.nuq_fixed_words(100, 0, 4) == 0
+
+
+def test_binding_checks_buffer_sizes(nuq, monkeypatch):
+    """The wrappers refuse tensors shorter than d, bucket and sync_stride imply before anything reaches the
+    library.  Host tensors stand in for device tensors (the placement check is switched off for all but the last
+    case): every call here ends in the wrapper."""
+    import torch
+    from paper_1908_06077_amd import binding
+    monkeypatch.setattr(binding, "_on_device", lambda t: True)
+    d, n, s, S = 10_000, 1024, 3, 256
+    B, per = nuq.nuq_num_buckets(d, n), nuq.nuq_num_sync(n, S)
+    f = lambda k: torch.zeros(k, dtype=torch.float32)
+    i32 = lambda k: torch.zeros(k, dtype=torch.int32)
+    i64 = lambda k: torch.zeros(k, dtype=torch.int64)
+    good = lambda: nuq.Message(f(B), i64(B + 1), i32(64), i32(B * per))
+    ws = torch.zeros(64, dtype=torch.uint8)
+    cases = [
+        ("norms holds", lambda: nuq.nuq_bucket_norms(f(d), n, f(B - 1))),
+        ("norms holds", lambda: nuq.nuq_bucket_norms_linf(f(d), n, f(B - 1))),
+        ("norms holds", lambda: nuq.nuq_quantize(f(d), n, s, 1, f(B - 1), torch.zeros(d, dtype=torch.uint8))),
+        ("q holds", lambda: nuq.nuq_quantize(f(d), n, s, 1, f(B), torch.zeros(d - 1, dtype=torch.uint8))),
+        ("bit_off holds", lambda: nuq.nuq_encode(torch.zeros(d, dtype=torch.uint8), n, s, S, i64(B), i32(64), i32(B * per), ws)),
+        ("sync holds", lambda: nuq.nuq_encode(torch.zeros(d, dtype=torch.uint8), n, s, S, i64(B + 1), i32(64), i32(B * per - 1), ws)),
+        ("sync is needed", lambda: nuq.nuq_encode(torch.zeros(d, dtype=torch.uint8), n, s, S, i64(B + 1), i32(64), None, ws)),
+        ("norms holds", lambda: nuq.nuq_quantize_encode(f(d), n, s, 1, S, f(B - 1), i64(B + 1), i32(64), i32(B * per), ws)),
+        ("bit_off holds", lambda: nuq.nuq_quantize_encode_static(f(d), n, s, 1, S, f(B), i64(B), i32(64), i32(B * per))),
+        ("sync holds", lambda: nuq.nuq_quantize_encode_batch([f(d)], n, s, [1], S, [nuq.Message(f(B), i64(B + 1), i32(64), i32(3))], ws)),
+        ("bit_off holds", lambda: nuq.nuq_decode_accumulate([nuq.Message(f(B), i64(B), i32(64), i32(B * per))], d, n, s, S, 1.0, False, f(d))),
+        ("norms holds", lambda: nuq.nuq_decode_accumulate([good(), nuq.Message(f(1), i64(B + 1), i32(64), i32(B * per))], d, n, s, S, 1.0, False, f(d))),
+        ("out must hold", lambda: nuq.nuq_decode_accumulate([good()], d, n, s, S, 1.0, False, f(d - 1))),
+        ("expected dtype", lambda: nuq.nuq_decode_accumulate([nuq.Message(f(B), i32(B + 1), i32(64), i32(B * per))], d, n, s, S, 1.0, False, f(d))),
+        ("sync holds", lambda: nuq.nuq_decode_momentum_step([nuq.Message(f(B), i64(B + 1), i32(64), i32(1))], d, n, s, S, 1.0, 0.1, 0.5, 0.0, f(d), f(d))),
+        ("sync holds", lambda: nuq.nuq_decode_accumulate_table([nuq.Message(f(B), i64(B + 1), i32(64), i32(1))], d, n, [0, .25, .5, .75, 1], S, 1.0, False, f(d))),
+    ]
+    for want, call in cases:
+        with pytest.raises(ValueError, match=want):
+            call()
+    # tensors of the right sizes get as far as the placement check
+    monkeypatch.undo()
+    with pytest.raises(ValueError, match="device tensor"):
+        nuq.nuq_decode_accumulate([good()], d, n, s, S, 1.0, False, f(d))
 
 
 def test_bench_refuses_more_than_one_gpu():

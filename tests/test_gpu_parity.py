@@ -352,6 +352,58 @@ def test_encode_and_decode_replayed_from_a_hip_graph(g):
     assert nuq.nuq_last_error_flags() == 0
 
 
+@pytest.mark.parametrize("d,n,s,S,K", [(300_000, 8192, 3, 256, 1), (300_000, 8192, 3, 256, 4), (90_000, 512, 3, 128, 4),
+                                       (90_000, 512, 3, 0, 1), (200_000, 16384, 7, 0, 2), (400_000, 32768, 3, 1024, 2)])
+def test_offsets_beyond_the_words_received(g, d, n, s, S, K):
+    """A message cut short (fewer words than its offsets cover) and one whose offsets run backwards: the decoder
+    raises the malformed flag, reads no word of the buckets concerned (they contribute nothing) and decodes every
+    other bucket as usual.  The words tensors handed over are views of the full ones, so that even a decoder that
+    ignored the length would stay inside allocated memory."""
+    nuq = g.nuq
+    rng = np.random.default_rng(d + K)
+    vs = [torch.from_numpy((rng.standard_normal(d) * 0.01).astype(np.float32)).to(g.DEV) for _ in range(K)]
+    seeds = [5 + k for k in range(K)]
+    msgs = g.batched_encode(vs, n, s, seeds, S)
+    B = nuq.nuq_num_buckets(d, n)
+    parts = [(m.norms.cpu().numpy().copy(), g.u64(m.bit_off).copy(), g.u32(m.words).copy()) for m in msgs]
+    out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+
+    # worker 0's message loses its second half
+    bo = parts[0][1]
+    keep_words = int(bo[B // 2] + 31) // 32 + 1          # ends inside bucket B//2
+    cut = nuq.Message(msgs[0].norms, msgs[0].bit_off, msgs[0].words[:keep_words], msgs[0].sync)
+    nuq.nuq_decode_accumulate([cut] + msgs[1:], d, n, s, S, 1.0 / K, False, out)
+    assert nuq.nuq_last_error_flags() & nuq.FLAG_MALFORMED
+    norms0 = parts[0][0].copy()
+    norms0[bo[1:] > 32 * keep_words] = 0.0             # those buckets of worker 0 count for nothing
+    assert (norms0 == 0).sum() >= B - B // 2 - 1 and (norms0 != 0).sum() >= B // 2 - 1
+    g.check_average([(norms0, parts[0][1], parts[0][2])] + parts[1:], d, n, s, 1.0 / K, out.cpu().numpy())
+
+    # the last worker's offsets run backwards at one bucket: that bucket and the next count for nothing
+    b = B // 3
+    bad_bo = msgs[-1].bit_off.clone()
+    bad_bo[b + 1] = bad_bo[b] - 1 if int(bad_bo[b].item()) > 0 else bad_bo[b + 2] + 64
+    back = nuq.Message(msgs[-1].norms, bad_bo, msgs[-1].words, msgs[-1].sync)
+    nuq.nuq_decode_accumulate(msgs[:-1] + [back], d, n, s, S, 1.0 / K, False, out)
+    assert nuq.nuq_last_error_flags() & nuq.FLAG_MALFORMED
+    got = out.cpu().numpy()
+    normsL = parts[-1][0].copy()
+    normsL[b] = 0.0
+    normsL[b + 1] = 0.0
+    want_parts = parts[:-1] + [(normsL, parts[-1][1], parts[-1][2])]
+    lo, hi = b * n, min(d, (b + 2) * n)
+    ref = g.check_average([(p[0][: b], p[1][: b + 1], p[2]) for p in want_parts], lo, n, s, 1.0 / K, got[:lo]) if b else None
+    # buckets b and b+1: the other workers' terms only, if the damaged ones were dropped whole (bucket b+1 may also
+    # have been decoded from a start that is still inside the words: then its records were refused or kept)
+    others = [(p[0], p[1], p[2]) for p in want_parts[:-1]]
+    if others:
+        w_all = oracle.decode_average([p[0] for p in others], [p[1] for p in others], [p[2] for p in others],
+                                      d, n, s, float(np.float32(1.0 / K)))
+        np.testing.assert_allclose(got[lo: b * n + n], w_all[lo: b * n + n], rtol=2e-6, atol=1e-30)
+    else:
+        assert not got[lo: b * n + n].any()
+
+
 DIRTY = -0x5A5A5A5B           # 0xA5A5A5A5 as the int32 the word buffers are typed with
 
 
