@@ -70,6 +70,9 @@ enum {
     NUQ_FLAG_MALFORMED = 4  /* a decoded stream broke the format; output is incomplete  */
 };
 
+/* A bucket's coordinates stay in the registers of one workgroup between the norm and the quantizer, so
+ * that v is read from memory once: the largest workgroup (1024 threads) x 8 float4 = 32768 coordinates.
+ * (The paper's bucket sizes are 8192 and 16384: Sec. 5, App. K.) */
 #define NUQ_MAX_BUCKET 32768u
 #define NUQ_MAX_S 14u
 #define NUQ_MAX_WORKERS 32u /* K per nuq_decode_accumulate call */
@@ -95,6 +98,10 @@ uint64_t nuq_max_words(uint64_t d, uint32_t bucket, uint32_t s);
 /* Bytes of scratch the encoders need for K workers of these sizes (K = 1 for nuq_encode and
  * nuq_quantize_encode); 0 on invalid sizes. */
 uint64_t nuq_encode_workspace_bytes(uint32_t K, uint64_t d, uint32_t bucket, uint32_t s);
+
+/* Bytes of scratch that suffice for every entry point of this header at these sizes, whatever s:
+ * nuq_encode_workspace_bytes(K, d, bucket, NUQ_MAX_S) (the decoders need none); 0 on invalid sizes. */
+uint64_t nuq_workspace_bytes(uint64_t d, uint32_t bucket, uint32_t K);
 
 /* ---- step 1: bucket norms (Def. 1: r_i = |v_i| / ||v||) --------------------------- */
 
@@ -364,22 +371,6 @@ int nuq_normalized_variance(const double *sum, const double *sumsq, uint64_t d, 
 /* Waits for `stream`, copies the sticky device flags of the current device to
  * *host_flags (host pointer) and clears them. */
 int nuq_last_error_flags(uint32_t *host_flags, nuq_stream_t stream);
-
-/* ---- measurement aid (not part of the method) ----------------------------------------- */
-
-/* Entry-point ids reported by nuq_timing_collect. */
-enum { NUQ_T_NORMS = 1, NUQ_T_QUANTIZE = 2, NUQ_T_ENCODE = 3, NUQ_T_QUANTIZE_ENCODE = 4, NUQ_T_DECODE = 5 };
-
-/* After nuq_timing_begin(n), each of the next n launches of a main kernel (the per-bucket kernel
- * of nuq_bucket_norms / nuq_quantize / nuq_encode / nuq_quantize_encode, the tile kernel of
- * nuq_decode_accumulate) is bracketed by a pair of HIP events recorded on its stream.  The small
- * offset-scan and gather kernels of the encoders are outside the brackets.  n <= 4096.
- * Not thread-safe; meant for benchmarks. */
-int nuq_timing_begin(uint32_t max_launches);
-
-/* Waits for the bracketed launches, writes up to `cap` durations (milliseconds) and entry-point
- * ids to the HOST arrays ms[] and entry[], the number written to *count, and ends the capture. */
-int nuq_timing_collect(float *ms, int32_t *entry, uint32_t cap, uint32_t *count);
 
 #ifdef __cplusplus
 }

@@ -310,7 +310,7 @@ int nuqo_erc_encode(uint64_t N, char *out)
         return NUQO_EINVAL;
     uint64_t groups[8];
     int ng = 0;
-    while (N != 1) { /* "prepend binary(N); N' = #bits prepended - 1; recurse" */
+    while (N != 1) { /* App. A, Alg. 2: the group binary(N) is preceded by the code groups of its own length - 1 */
         groups[ng++] = N;
         N = (uint64_t)bit_width(N) - 1;
     }
@@ -320,7 +320,7 @@ int nuqo_erc_encode(uint64_t N, char *out)
         for (int k = w - 1; k >= 0; k--)
             out[len++] = ((groups[g] >> k) & 1) ? '1' : '0';
     }
-    out[len++] = '0'; /* "place a 0 at the end" */
+    out[len++] = '0'; /* App. A, Alg. 2: a single 0 closes the codeword (every group starts with a 1) */
     return len;
 }
 
@@ -344,9 +344,10 @@ static inline void put_bit(uint32_t *words, uint64_t t, int bit)
 }
 
 /*
- * Alg. 2, decoder, reading from bit `*pos` and never at or beyond `end`.
- * "Start with N = 1; if the next bit is 0 stop and return N; else read that
- * bit plus N following bits and update N."  Returns 0 on success, NUQO_EMALFORMED
+ * App. A, Alg. 2, decoder, reading from bit `*pos` and never at or beyond `end`.
+ * The value so far (1 at first) is the number of bits that follow a group's
+ * leading 1; a 0 where a group would start ends the codeword and the value so far
+ * is the result.  Returns 0 on success, NUQO_EMALFORMED
  * if the code runs past `end` or N leaves the 32-bit range.
  */
 int nuqo_erc_decode(const uint32_t *words, uint64_t *pos, uint64_t end, uint64_t *N_out)

@@ -7,7 +7,7 @@ kernels.  There is no CPU fallback: importing the package fails if the library i
 from .binding import (  # noqa: F401
     NuqError, Message,
     FLAG_CAPACITY, FLAG_NONFINITE, FLAG_MALFORMED, SYNC_BLOCK, MAX_BUCKET, MAX_S, MAX_WORKERS,
-    nuq_num_buckets, nuq_num_sync, nuq_huffman_num_sync, nuq_max_words, nuq_encode_workspace_bytes,
+    nuq_num_buckets, nuq_num_sync, nuq_huffman_num_sync, nuq_max_words, nuq_encode_workspace_bytes, nuq_workspace_bytes,
     nuq_bucket_norms, nuq_quantize, nuq_encode, nuq_quantize_encode, nuq_quantize_encode_batch, nuq_decode_accumulate,
     nuq_quantize_encode_static, STATIC_WORKSPACE_BYTES,
     nuq_bucket_norms_linf, nuq_quantize_table, nuq_quantize_encode_table_batch, nuq_decode_accumulate_table,

@@ -25,6 +25,7 @@ _u64, _u32, _i32, _vp, _f32 = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ct
 
 _SIGNATURES = {
     "nuq_num_buckets": (_u64, [_u64, _u32]),
+    "nuq_workspace_bytes": (_u64, [_u64, _u32, _u32]),
     "nuq_num_sync": (_u32, [_u32, _u32]),
     "nuq_huffman_num_sync": (_u32, [_u32, _u32]),
     "nuq_max_words": (_u64, [_u64, _u32, _u32]),
@@ -155,6 +156,10 @@ def nuq_max_words(d: int, bucket: int, s: int) -> int:
 
 def nuq_encode_workspace_bytes(K: int, d: int, bucket: int, s: int) -> int:
     return _lib.nuq_encode_workspace_bytes(K, d, bucket, s)
+
+
+def nuq_workspace_bytes(d: int, bucket: int, K: int) -> int:
+    return _lib.nuq_workspace_bytes(d, bucket, K)
 
 
 # ------------------------------------------------------------------------- the path

@@ -1,6 +1,7 @@
 // C ABI of the NUQSGD compression path (see include/nuq.h): argument checks, launch
 // geometry and workspace layout.  All arithmetic of the method lives in the kernels.
 #include "../../include/nuq.h"
+#include "../../include/nuq_bench.h"
 
 #include <hip/hip_runtime.h>
 
@@ -483,6 +484,11 @@ uint64_t nuq_encode_workspace_bytes(uint32_t K, uint64_t d, uint32_t bucket, uin
     return carve(nullptr, K, nuq_num_buckets(d, bucket), slot_words_for(bucket, s)).bytes;
 }
 
+uint64_t nuq_workspace_bytes(uint64_t d, uint32_t bucket, uint32_t K)
+{
+    return nuq_encode_workspace_bytes(K, d, bucket, NUQ_MAX_S);
+}
+
 int nuq_bucket_norms(const float *v, uint64_t d, uint32_t bucket, float *norms, nuq_stream_t stream)
 {
     if (!v || !norms || !valid_common(d, bucket, 1) || (reinterpret_cast<uintptr_t>(v) & 3u))
@@ -936,40 +942,44 @@ int nuq_huffman_lengths(const uint64_t *hist, uint32_t s, uint8_t *lengths)
 {
     if (!hist || !lengths || s < 1 || s > NUQ_MAX_S)
         return NUQ_EINVAL;
-    // Huffman's algorithm on hist[j] + 1; the two smallest nodes by (weight, id) are merged, a leaf's id is its
-    // symbol, merged nodes get ids nsym, nsym + 1, ... in order of creation.
+    // Huffman's algorithm on the weights hist[j] + 1 (Sec. 5, "Efficient Encoding"), as a merge of two queues: the
+    // leaves sorted by (weight, symbol), and the merged nodes in order of creation, whose weights never decrease.
+    // The next smallest node is at the front of one of the queues; of two equal weights the leaf goes first, which
+    // is the order (weight, id) with leaves numbered before merged nodes.
     const uint32_t nsym = s + 2u;
-    struct Node {
-        uint64_t weight;
-        int parent;
-        bool open;
-    } node[32];
+    uint32_t leaf[16];                  // symbols, sorted
     for (uint32_t j = 0; j < nsym; ++j)
-        node[j] = Node{hist[j] + 1u, -1, true};
-    uint32_t count = nsym;
-    while (count < 2u * nsym - 1u) {
-        int lo1 = -1, lo2 = -1;
-        for (uint32_t i = 0; i < count; ++i) {
-            if (!node[i].open)
-                continue;
-            if (lo1 < 0 || node[i].weight < node[lo1].weight) {
-                lo2 = lo1;
-                lo1 = (int)i;
-            } else if (lo2 < 0 || node[i].weight < node[lo2].weight) {
-                lo2 = (int)i;
-            }
+        leaf[j] = j;
+    std::stable_sort(leaf, leaf + nsym, [&](uint32_t x, uint32_t y) { return hist[x] < hist[y]; });
+    uint64_t merged_weight[16];
+    uint32_t kid[16][2];                // children of merged node m: a symbol, or 16 + a merged node
+    uint32_t nl = 0, nm_front = 0, nm = 0;
+    auto take = [&](uint64_t &weight) {
+        const bool from_leaves =
+            nl < nsym && (nm_front == nm || hist[leaf[nl]] + 1u <= merged_weight[nm_front]);
+        if (from_leaves) {
+            weight = hist[leaf[nl]] + 1u;
+            return leaf[nl++];
         }
-        node[count] = Node{node[lo1].weight + node[lo2].weight, -1, true};
-        node[lo1].open = node[lo2].open = false;
-        node[lo1].parent = node[lo2].parent = (int)count;
-        ++count;
+        weight = merged_weight[nm_front];
+        return 16u + nm_front++;
+    };
+    for (uint32_t m = 0; m + 1u < nsym; ++m) {
+        uint64_t w0, w1;
+        kid[m][0] = take(w0);
+        kid[m][1] = take(w1);
+        merged_weight[m] = w0 + w1;
+        nm = m + 1u;
     }
-    for (uint32_t j = 0; j < nsym; ++j) {
-        uint32_t depth = 0;
-        for (int i = (int)j; node[i].parent >= 0; i = node[i].parent)
-            ++depth;
-        lengths[j] = (uint8_t)depth;
-    }
+    // depths from the root (the last merged node) down
+    uint32_t depth[16] = {0};
+    for (uint32_t m = nsym - 1u; m-- > 0u;)
+        for (uint32_t c = 0; c < 2u; ++c) {
+            if (kid[m][c] >= 16u)
+                depth[kid[m][c] - 16u] = depth[m] + 1u;
+            else
+                lengths[kid[m][c]] = (uint8_t)(depth[m] + 1u);
+        }
     return NUQ_OK;
 }
 

@@ -20,9 +20,12 @@ def nuq():
 
 
 def header_functions():
-    text = open(os.path.join(ROOT, "include", "nuq.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(nuq_[a-z_]+)\s*\(", text)))
+    names = set()
+    for h in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(nuq_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(nuq):
@@ -34,6 +37,9 @@ def test_every_declared_symbol_is_exported(nuq):
 
 
 def test_size_helpers(nuq):
+    assert nuq.nuq_workspace_bytes(10 ** 6, 8192, 4) == nuq.nuq_encode_workspace_bytes(4, 10 ** 6, 8192, 14)
+    assert nuq.nuq_workspace_bytes(10 ** 6, 8192, 4) >= nuq.nuq_encode_workspace_bytes(4, 10 ** 6, 8192, 3) > 0
+    assert nuq.nuq_workspace_bytes(10 ** 6, 40000, 4) == 0 and nuq.nuq_workspace_bytes(0, 8192, 1) == 0
     assert nuq.nuq_num_buckets(25_557_032, 8192) == 3120
     assert nuq.nuq_num_buckets(8192, 8192) == 1 and nuq.nuq_num_buckets(8193, 8192) == 2
     # decoder index: blocks of 2048 coordinates x a power-of-two number of pieces of about sync_stride coordinates
@@ -180,3 +186,14 @@ def test_huffman_lengths_on_the_host(nuq):
         s, hist, lengths = int(f[1]), [int(x) for x in f[2].split()], [int(x) for x in f[3].split()]
         assert nuq.nuq_huffman_lengths(hist, s) == lengths
     assert nuq.nuq_huffman_max_words(100, 10) == (100 * 16 + 31) // 32 + 10
+    # the library's builder (a merge of two sorted queues) against the oracle's (repeated search for the two smallest
+    # nodes): equal lengths, ties included, on random, tiny, huge and all-zero counts
+    import numpy as np
+    import oracle
+    rng = np.random.default_rng(11)
+    for t in range(3000):
+        s = int(rng.integers(1, 15))
+        hist = [rng.integers(0, 4, size=s + 2), rng.integers(0, 10 ** 7, size=s + 2),
+                2 ** rng.integers(0, 45, size=s + 2), np.zeros(s + 2, dtype=np.int64)][t % 4]
+        assert nuq.nuq_huffman_lengths([int(x) for x in hist], s) == \
+            [int(x) for x in oracle.huffman_lengths(np.asarray(hist, dtype=np.uint64), s)]
