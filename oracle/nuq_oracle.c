@@ -226,24 +226,73 @@ void nuqo_bucket_norms_linf(const float *v, uint64_t d, uint32_t bucket, double 
 }
 
 /*
+ * Exact sign of a sum of doubles, for the decision below.  two_sum and two_prod
+ * are the classical error-free transformations (Knuth; Dekker, with fma): the
+ * pair they return adds up to the real-number sum or product exactly.  Adding a
+ * term to a list of nonoverlapping parts with a chain of two_sum keeps the list
+ * exact and nonoverlapping, smallest part first (Shewchuk's "grow expansion"),
+ * so the sign of the whole is the sign of its last nonzero part.  Valid while
+ * nothing overflows or underflows: the terms here lie between 2^-400 and 2^160.
+ */
+static void two_sum(double x, double y, double *sum, double *err)
+{
+    double t = x + y;
+    double yy = t - x;
+    *err = (x - (t - yy)) + (y - yy);
+    *sum = t;
+}
+
+static void two_prod(double x, double y, double *prod, double *err)
+{
+    *prod = x * y;
+    *err = fma(x, y, -*prod);
+}
+
+static int sign_of_sum(const double *term, int count)
+{
+    double part[16];
+    int parts = 0;
+    for (int i = 0; i < count; i++) {
+        double carry = term[i];
+        for (int k = 0; k < parts; k++)
+            two_sum(carry, part[k], &carry, &part[k]);
+        part[parts++] = carry;
+    }
+    for (int k = parts - 1; k >= 0; k--)
+        if (part[k] != 0.0)
+            return part[k] > 0.0 ? 1 : -1;
+    return 0;
+}
+
+/*
  * Level index of one coordinate for an arbitrary level sequence lev[0..s+1]
  * (fp32 values, lev[0] = 0 < lev[1] < ... < lev[s+1] = 1).  Def. 1 with the
  * two cases of Sec. 4.1: r in [l_j, l_{j+1}] goes up to l_{j+1} with probability
- * p = (r - l_j) / tau_j, tau_j = l_{j+1} - l_j.
+ * p = (r - l_j) / tau_j, tau_j = l_{j+1} - l_j, i.e. for the draw u of 24 bits
+ * iff u / 2^24 < p.
  *
- * As above everything is multiplied through by ||v||: l_j * ||v|| is a product
- * of two 24-bit significands, exact in fp64.  tau_j * ||v|| and |v_i| - l_j * ||v||
- * are each one fp64 subtraction and u * (tau_j * ||v||) one fp64 product, each
- * rounded to nearest: for levels that are not powers of two these may round, so
- * the decision is DEFINED as the outcome of exactly this sequence of IEEE fp64
- * operations (the kernels perform the same sequence).  It differs from the
- * real-number statement u / 2^24 < p(r) for at most one value of u.
+ * As above everything is multiplied through by ||v||: the test is
+ *     u * (l_{j+1} ||v|| - l_j ||v||)  <  (|v_i| - l_j ||v||) * 2^24
+ * over the real numbers.  The products l ||v|| of two 24-bit significands are
+ * exact in fp64; for levels that are not powers of two the differences and the
+ * product with u need more than 53 bits, so the two sides are not rounded but
+ * compared exactly: the sign of
+ *     |v_i| 2^24 - l_j ||v|| 2^24 - u l_{j+1} ||v|| + u l_j ||v||,
+ * each product with u split into an exact pair.
  */
 int nuqo_quantize_coord_table(float vi, float norm, int s, const float *lev, uint32_t u24)
 {
     double n = (double)norm;
     double a = fabs((double)vi);
     if (!(n > 0.0) || a == 0.0)
+        return 0;
+    /* not finite (the exact comparison below needs finite terms): a NaN coordinate has no level, an
+     * infinite one exceeds every level, and under an infinite norm every finite coordinate is at zero */
+    if (a != a)
+        return 0;
+    if (isinf(a))
+        return s + 1;
+    if (isinf(n))
         return 0;
     int j = 0; /* largest j with l_j * n <= a */
     for (int t = 1; t <= s + 1; t++)
@@ -253,11 +302,12 @@ int nuqo_quantize_coord_table(float vi, float norm, int s, const float *lev, uin
         return s + 1;
     double lo_n = (double)lev[j] * n;
     double hi_n = (double)lev[j + 1] * n;
-    double tau_n = hi_n - lo_n;
-    double x = a - lo_n;
-    double lhs = (double)u24 * tau_n;
-    double rhs = x * 16777216.0;
-    return lhs < rhs ? j + 1 : j;
+    double term[6];
+    term[0] = a * 16777216.0;
+    term[1] = -lo_n * 16777216.0;
+    two_prod(-(double)u24, hi_n, &term[2], &term[3]);
+    two_prod((double)u24, lo_n, &term[4], &term[5]);
+    return sign_of_sum(term, 6) > 0 ? j + 1 : j;
 }
 
 /* hist[j] += number of draws u in [u_begin, u_end) that give level index j. */

@@ -77,8 +77,8 @@ def test_power_of_two_table_reproduces_the_main_scheme(s):
 
 @pytest.mark.parametrize("kind,s,p", TABLES[:4])
 def test_exhaustive_draws_match_the_probability_of_the_upper_level(kind, s, p):
-    """All 2^24 draws for a few coordinates: the number that round up is ceil(p(r) 2^24) for the strict test
-    u / 2^24 < p(r), up to one draw (the table rule rounds tau ||v|| and |v_i| - l_j ||v|| once each)."""
+    """All 2^24 draws for a few coordinates: the number that round up is exactly ceil(p(r) 2^24) for the strict
+    test u / 2^24 < p(r), p(r) in rationals."""
     lev = workloads.level_table(kind, s, p if p else 0.5)
     rng = np.random.default_rng(s * 7)
     norm = np.float32(2.7182817)
@@ -91,7 +91,72 @@ def test_exhaustive_draws_match_the_probability_of_the_upper_level(kind, s, p):
         assert int(hist.sum()) == TWO24
         assert int(hist[j] + hist[j + 1]) == TWO24          # only the two neighbours of r
         want_up = math.ceil(prob * TWO24)
-        assert abs(int(hist[j + 1]) - want_up) <= 1, (r, j, prob)
+        assert int(hist[j + 1]) == want_up, (r, j, prob)
+
+
+def near_ties():
+    import os
+    rows = []
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "table_near_ties.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = [x.strip() for x in line.split("|")]
+        rows.append(([float.fromhex(x) for x in f[0].split()], float.fromhex(f[1]), float.fromhex(f[2]), int(f[3]),
+                     int(f[4])))
+    return rows
+
+
+def test_near_ties_are_decided_over_the_reals():
+    """tests/golden/table_near_ties.txt: draws at which u tau and (|v_i| - l_j ||v||) 2^24 differ by less than one
+    rounding of fp64.  The rule of Def. 1 / Sec. 4.1 in rationals says up; a chain of rounded fp64 operations would
+    say down (shown here with numpy, to keep the examples honest)."""
+    for lev, norm, a, u, up in near_ties():
+        r = F(a) / F(norm)
+        j, prob = bin_and_p(r, lev)
+        assert (F(u, TWO24) < prob) == bool(up)
+        assert oracle.quantize_coord_table(a, norm, lev, u) == j + up
+        assert oracle.quantize_coord_table(-a, norm, lev, u) == j + up
+        # the neighbours of the draw are far from the tie
+        assert oracle.quantize_coord_table(a, norm, lev, u - 1) == j + 1
+        assert oracle.quantize_coord_table(a, norm, lev, u + 1) == j
+        n = np.float64(np.float32(norm))
+        lo_n, hi_n = np.float64(np.float32(lev[j])) * n, np.float64(np.float32(lev[j + 1])) * n
+        rounded_up = np.float64(u) * (hi_n - lo_n) < (np.float64(a) - lo_n) * np.float64(TWO24)
+        assert bool(rounded_up) != bool(up)
+
+
+@pytest.mark.parametrize("kind,s,p", TABLES)
+def test_threshold_draw_of_random_coordinates(kind, s, p):
+    """For random coordinates the first draw that does not go up is exactly ceil(p(r) 2^24), p(r) in rationals;
+    also for ratios built to make p(r) 2^24 a whole number (an exact tie stays down: the test is strict)."""
+    lev = workloads.level_table(kind, s, p if p else 0.5)
+    rng = np.random.default_rng(s * 13 + 1)
+    cases = []
+    for _ in range(300):
+        norm = np.float32(10.0 ** rng.uniform(-20, 20))
+        cases.append((np.float32(rng.random() ** 3 * float(norm)), norm))
+    for _ in range(100):                                  # exact ties: norm a power of two, r = l_j + u tau / 2^24
+        j = int(rng.integers(0, s + 1))
+        u = int(rng.integers(1, TWO24))
+        norm = np.float32(2.0 ** int(rng.integers(-30, 30)))
+        r = frac(lev[j]) + F(u, TWO24) * (frac(lev[j + 1]) - frac(lev[j]))
+        a = np.float32(float(r) * float(norm))
+        cases.append((a, norm))
+    ties = 0
+    for a, norm in cases:
+        if a == 0:
+            continue
+        r = frac(a) / frac(norm)
+        j, prob = bin_and_p(r, lev)
+        if j == len(lev) - 1:
+            continue
+        first_down = math.ceil(prob * TWO24)              # smallest u with u / 2^24 >= p
+        ties += (prob * TWO24).denominator == 1
+        if first_down > 0:
+            assert oracle.quantize_coord_table(a, norm, lev, first_down - 1) == j + 1
+        if first_down < TWO24:
+            assert oracle.quantize_coord_table(a, norm, lev, first_down) == j
+    assert ties >= 5 or kind == "exp"
 
 
 @pytest.mark.parametrize("kind,s,p", TABLES)
