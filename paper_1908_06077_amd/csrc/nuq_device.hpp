@@ -352,11 +352,9 @@ __device__ __forceinline__ int team_exclusive_max(int v, int ident, int *scratch
 // --------------------------------------------------------- level tables (arbitrary level sequences)
 //
 // Def. 1 for any 0 = l_0 < l_1 < ... < l_{s+1} = 1 (Sec. 3.1 before the special case; Sec. 4.1 "Generally spaced
-// levels").  The decision is the outcome of this sequence of IEEE fp64 operations (each rounded to nearest; the
-// products of two fp32 values are exact):
-//   e_t = l_t * ||v||;  j = largest t with e_t <= |v_i| (s+1: the top level, no draw);
-//   tau = e_{j+1} - e_j;  x = |v_i| - e_j;  up iff u * tau < x * 2^24.
-// On levels that are powers of two nothing rounds and this is the rule of the main quantizer.
+// levels").  With e_t = l_t * ||v|| (a product of two fp32 values: exact in fp64) and j = the largest t with
+// e_t <= |v_i| (s+1: the top level, no draw), the coordinate goes up iff u (e_{j+1} - e_j) < (|v_i| - e_j) 2^24
+// over the real numbers (table_round_up).  On levels that are powers of two this is the rule of the main quantizer.
 
 struct LevelTable {
     float lev[16];   // lev[0] = 0 ... lev[s+1] = 1; entries above s+1 are 0
@@ -384,6 +382,60 @@ __device__ __forceinline__ uint32_t team_max_u32(uint32_t x, uint32_t *scratch)
     return x;
 }
 
+// The rounding decision of Def. 1 for a coordinate a in [lo, hi), lo = l_j ||v||, hi = l_{j+1} ||v|| (both exact
+// in fp64), and the draw u: up iff u (hi - lo) < (a - lo) 2^24 over the real numbers.  The two differences and the
+// product round once each in fp64 (relative error below 2^-52 on the left, 2^-53 on the right), so the rounded
+// comparison is the real one unless the sides agree to within 2^-49; only then (about one coordinate in 2^49) is
+// the sign of  a 2^24 - lo 2^24 - u hi + u lo  worked out exactly: each product as a pair (rounded value, fma
+// remainder), the six terms added one by one to a list of nonoverlapping doubles by error-free additions, whose
+// leading nonzero entry has the sign of the sum.
+__device__ __forceinline__ void exact_add(double x, double y, double &hi, double &lo)
+{
+    hi = x + y;
+    const double yv = hi - x;
+    lo = (x - (hi - yv)) + (y - yv);
+}
+
+__device__ inline bool table_round_up_exact(double ud, double lo, double hi, double a)
+{
+    double t[6];
+    t[0] = a * 16777216.0;
+    t[1] = -lo * 16777216.0;
+    t[2] = -ud * hi;
+    t[3] = __builtin_fma(-ud, hi, -t[2]);
+    t[4] = ud * lo;
+    t[5] = __builtin_fma(ud, lo, -t[4]);
+    // after step i the entries t[0..i] sum to the same value as before and do not overlap, smallest first
+#pragma unroll
+    for (int i = 1; i < 6; ++i) {
+        double carry = t[i];
+#pragma unroll
+        for (int k = 0; k < i; ++k)
+            exact_add(carry, t[k], carry, t[k]);
+        t[i] = carry;
+    }
+    double lead = 0.0;
+#pragma unroll
+    for (int k = 0; k < 6; ++k)
+        lead = t[k] != 0.0 ? t[k] : lead;
+    return lead > 0.0;
+}
+
+__device__ __forceinline__ bool table_round_up(uint32_t u, double lo, double hi, double a)
+{
+    const double ud = (double)u;
+    const double rhs = (a - lo) * 16777216.0;           // >= 0, and 0 or above 2^-300: a sits in [lo, hi)
+    const double diff = ud * (hi - lo) - rhs;
+    bool up = diff < 0.0;
+    // near-tie: the exponent of the difference is 49 or more below the right-hand side's, read off the high words
+    // (a gap of 49 exponents exceeds 48 << 20 whatever the mantissa bits beside them; a zero difference has high
+    // word 0; a zero right-hand side, an exact a = lo, is never flagged and stays down as it should)
+    const int hd = __double2hiint(diff) & 0x7fffffff, hr = __double2hiint(rhs);
+    if (__builtin_expect(hr - hd >= (48 << 20), 0))
+        up = table_round_up_exact(ud, lo, hi, a);
+    return up;
+}
+
 // Level|sign bytes of four coordinates whose first has in-bucket index idx0 (+ k0), for the bucket whose edges
 // e_t = l_t * ||v|| lie in LDS (e1 = edges[1]).  Called by whole waves: the first-bin route is chosen per wave.
 __device__ __forceinline__ uint32_t quantize_table_vec4(const float4 &x, uint32_t counter0, uint32_t k1,
@@ -398,7 +450,7 @@ __device__ __forceinline__ uint32_t quantize_table_vec4(const float4 &x, uint32_
             for (int c = 0; c < 4; ++c) {
                 const uint32_t u = draw24((counter0 + (uint32_t)c) * kRngC1, k1);
                 const double a = (double)fabsf(xs[c]);
-                levels |= ((double)u * e1 < a * 16777216.0 ? 1u : 0u) << (8 * c);
+                levels |= (table_round_up(u, 0.0, e1, a) ? 1u : 0u) << (8 * c);
             }
         } else {
 #pragma unroll
@@ -409,10 +461,7 @@ __device__ __forceinline__ uint32_t quantize_table_vec4(const float4 &x, uint32_
                 for (uint32_t t = 1; t <= s + 1u; ++t)
                     j += edges[t] <= a ? 1u : 0u;   // the levels increase: the count is the largest index
                 if (j <= s) {
-                    const double lo = edges[j], hi = edges[j + 1u];
-                    const double tau = hi - lo;
-                    const double over = a - lo;
-                    j += (double)u * tau < over * 16777216.0 ? 1u : 0u;
+                    j += table_round_up(u, edges[j], edges[j + 1u], a) ? 1u : 0u;
                 }
                 levels |= j << (8 * c);
             }

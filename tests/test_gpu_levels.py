@@ -1,7 +1,8 @@
 """GPU parity of the level-table variant (arbitrary level sequences, maximum norm) through the C ABI against the
 CPU oracle on the same seeded inputs.  Bars as for the main path: maximum norms exact; level|sign bytes bit-exact
-when the oracle is fed the GPU's norms (both sides take the rounding decision as the same sequence of fp64
-operations); the message of those bytes bit-exact; decoded averages within 1e-6."""
+when the oracle is fed the GPU's norms (both sides decide u / 2^24 < p(r) over the real numbers: the oracle always by
+an exact sum, the kernels by rounded fp64 operations that hand near-ties to an exact sum of their own); the message of
+those bytes bit-exact; decoded averages within 1e-6."""
 import numpy as np
 import pytest
 import torch
@@ -174,3 +175,54 @@ def test_uniform_levels_at_benchmark_size(g):
         want = oracle.quantize_table(v_np, n, lev, 5, nb, first_bucket=b)
         np.testing.assert_array_equal(q[sl].cpu().numpy(), want)
     assert nuq.nuq_last_error_flags() == 0
+
+
+def test_near_ties_of_the_rounding_decision(g):
+    """tests/golden/table_near_ties.txt: coordinates and draws at which both sides of the rounding test agree to
+    within one rounding of fp64, so that a rounded evaluation decides them wrongly.  Positions at which the counter
+    generator delivers each listed draw are looked up with the oracle's generator, the listed coordinate (with
+    either sign) is planted there under the listed norm, and the bytes of nuq_quantize_table must equal the
+    oracle's: up, as the exact rule says."""
+    from test_oracle_levels import near_ties
+    nuq = g.nuq
+    n, B = 32768, 2048
+    d = n * B
+    ties = near_ties()
+    assert len({tuple(t[0]) for t in ties}) == 1          # one level table for all listed examples
+    lev = ties[0][0]
+    s = len(lev) - 2
+    planted = 0
+    for seed in range(101, 109):
+        u = oracle.rng_fill(seed, d, n)
+        v = np.zeros(d, dtype=np.float32)
+        norms = np.ones(B, dtype=np.float32)
+        used = set()
+        want_up = []
+        for _, norm, a, draw, up in ties:
+            for i in np.flatnonzero(u == draw):
+                b = int(i) // n
+                if b in used:
+                    continue
+                used.add(b)
+                norms[b] = np.float32(norm)
+                v[i] = np.float32(a) * (1 if (i & 1) else -1)
+                want_up.append((int(i), up))
+        if not want_up:
+            continue
+        planted += len(want_up)
+        # ordinary coordinates around them
+        rng = np.random.default_rng(seed)
+        fill = rng.random(d) < 0.001
+        fill[[i for i, _ in want_up]] = False
+        v[fill] = (rng.standard_normal(int(fill.sum())) * 0.3).astype(np.float32)
+        want = oracle.quantize_table(v, n, lev, seed, norms)
+        for i, up in want_up:                              # the oracle puts them one level up from their bin
+            j = max(t for t in range(s + 1) if np.float64(np.float32(lev[t])) * np.float64(norms[i // n]) <= abs(float(v[i])))
+            assert int(want[i] & 0x7F) == j + up
+        q = torch.empty(d, dtype=torch.uint8, device=g.DEV)
+        nuq.nuq_quantize_table(torch.from_numpy(v).to(g.DEV), n, lev, seed, torch.from_numpy(norms).to(g.DEV), q)
+        got = q.cpu().numpy()
+        np.testing.assert_array_equal(got, want)
+        if planted >= 4:
+            break
+    assert planted >= 2
