@@ -52,6 +52,9 @@ def parse_args():
                     help="Huffman-coded levels (the paper's \"encoded\" variant) instead of the ERC bit strings: per "
                          "fused norms + quantizer + Huffman coding; decode to level bytes and one averaging kernel; "
                          "the code is built once from worker 0's level histogram; main scheme's levels only")
+    ap.add_argument("--huffman-two-kernels", action="store_true",
+                    help="with --huffman: decode to level bytes, then average them (two launches and K x d bytes in "
+                         "between) instead of the fused decoder")
     ap.add_argument("--update", default="none", choices=["none", "sgd", "momentum", "momentum-unfused"],
                     help="what the receiver does with the average: none (write it out: the default path), sgd "
                          "(Alg. 1's aggregate step: the decoder adds -alpha/K times the sum onto the parameters in the "
@@ -170,7 +173,8 @@ def measure(args, config, steps, warmup, cpu_budget):
             print("--huffman goes with the main scheme's levels and no other coding", file=sys.stderr)
             sys.exit(2)
         hq = [torch.empty(d, dtype=torch.uint8, device=dev) for _ in range(K)]          # quantizer output
-        hback = [torch.empty(d, dtype=torch.uint8, device=dev) for _ in range(K)]       # decoder output
+        hback = ([torch.empty(d, dtype=torch.uint8, device=dev) for _ in range(K)]      # decoder output
+                 if args.huffman_two_kernels else None)
         hnorms = [torch.empty(B, dtype=torch.float32, device=dev) for _ in range(K)]
         hws = torch.empty(nuq.nuq_encode_huffman_batch_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=dev)
         nuq.nuq_bucket_norms(grads[0], n, hnorms[0])
@@ -218,9 +222,11 @@ def measure(args, config, steps, warmup, cpu_budget):
             nuq.nuq_quantize_encode_batch(grads, n, s, seeds, S, msgs, ws)
 
     def decode_all():
-        if huff:
+        if huff and hback is not None:
             nuq.nuq_decode_huffman_batch(msgs, d, n, s, S, hlen, hback)
             nuq.nuq_average_levels([m.norms for m in msgs], hback, d, n, s, 1.0 / K, False, out)
+        elif huff:
+            nuq.nuq_decode_accumulate_huffman(msgs, d, n, s, S, hlen, 1.0 / K, False, out)
         elif fb:
             nuq.nuq_unpack_accumulate_fixed(fnorms, fpacked, d, n, s, fb, 1.0 / K, False, out)
         elif lev is not None:
@@ -360,7 +366,8 @@ def measure(args, config, steps, warmup, cpu_budget):
                      "bytes_per_launch": round(enc_launch_bytes), "launch_ms": round(enc_kernel_ms, 5),
                      "launches": len(enc_ms)},
         "roofline_decode": {"kernel": ("k_huffman_decode_direct, all K messages in one launch (k_average_levels follows)"
-                                       if huff else
+                                       if huff and args.huffman_two_kernels else
+                                       "k_decode_wave_huffman (decode + average of K Huffman-coded messages)" if huff else
                                        "k_unpack_accumulate_fixed (unpack + average of K messages)" if fb else
                                        "k_decode_accumulate (DECODE + average of K messages)"),
                             "bound": "hbm", "achieved": round(dec_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -319,6 +319,21 @@ int nuq_decode_huffman_batch(uint32_t K, const uint64_t *const *bit_off, const u
                              uint32_t sync_stride, const uint8_t *lengths, uint8_t *const *q,
                              nuq_stream_t stream);
 
+/* nuq_decode_accumulate for K Huffman-coded messages (Sec. 5, "Efficient Encoding"; App. A DECODE;
+ * Alg. 1 aggregate) in one launch: out[i] = (accumulate ? out[i] : 0) + scale * sum_k norms_k[b] *
+ * sign * 2^(j-1-s), (sign, j) decoded from worker k's string; the level|sign bytes are never written.
+ * Arguments, summation, rounding and NUQ_FLAG_MALFORMED as nuq_decode_accumulate (words_len included),
+ * lengths as nuq_encode_huffman.  Geometry: bucket > sync_stride (the messages carry an index), and
+ * the pieces of the K messages of a 2048-coordinate tile must fit the tile's 64 parsing lanes with a
+ * power-of-two group of lanes per message: for bucket > 2048, K' * 2048 / sync_stride <= 64 with K' =
+ * K rounded up to a power of two (K <= 8 at stride 256); else NUQ_EINVAL, and the caller uses
+ * nuq_decode_huffman_batch + nuq_average_levels. */
+int nuq_decode_accumulate_huffman(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                                  const uint32_t *const *words, const uint64_t *words_len,
+                                  const uint32_t *const *sync, uint64_t d, uint32_t bucket, uint32_t s,
+                                  uint32_t sync_stride, const uint8_t *lengths, float scale, int accumulate,
+                                  float *out, nuq_stream_t stream);
+
 /* out[i] = (accumulate ? out[i] : 0) + scale * sum_k norms_k[b] * sign * l_j from K arrays of
  * level|sign bytes (norms, q: HOST arrays of K device pointers): the aggregate of Alg. 1 for messages
  * already decoded to bytes.  fp64 sum in worker order, rounded to fp32 once. */

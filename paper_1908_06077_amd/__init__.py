@@ -13,7 +13,7 @@ from .binding import (  # noqa: F401
     nuq_bucket_norms_linf, nuq_quantize_table, nuq_quantize_encode_table_batch, nuq_decode_accumulate_table,
     NORM_L2, NORM_LINF,
     nuq_level_histogram, nuq_huffman_lengths, nuq_huffman_max_words, nuq_encode_huffman_workspace_bytes,
-    nuq_encode_huffman, nuq_encode_huffman_batch_workspace_bytes, nuq_quantize_encode_huffman_batch, nuq_decode_huffman, nuq_decode_huffman_batch, nuq_average_levels,
+    nuq_encode_huffman, nuq_encode_huffman_batch_workspace_bytes, nuq_quantize_encode_huffman_batch, nuq_decode_huffman, nuq_decode_huffman_batch, nuq_average_levels, nuq_decode_accumulate_huffman,
     nuq_fixed_words, nuq_pack_fixed, nuq_quantize_pack_fixed_batch, nuq_unpack_accumulate_fixed,
     nuq_momentum_step, nuq_decode_momentum_step, nuq_moments_accumulate, nuq_normalized_variance, VARIANCE_WORKSPACE_BYTES,
     nuq_last_error_flags, library_path, exported_symbols,

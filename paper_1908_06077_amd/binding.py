@@ -41,6 +41,8 @@ _SIGNATURES = {
     "nuq_quantize_table": (_i32, [_vp, _u64, _u32, _u32, _vp, _u64, _vp, _vp, _vp]),
     "nuq_quantize_encode_table_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _vp, _u32, _u32, _vp, _vp, _vp, _vp, _vp,
                                                _vp, _u64, _vp]),
+    "nuq_decode_accumulate_huffman": (_i32, [_u32, _vp, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _f32, _i32, _vp,
+                                             _vp]),
     "nuq_decode_accumulate_table": (_i32, [_u32, _vp, _vp, _vp, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _f32, _i32, _vp, _vp]),
     "nuq_fixed_words": (_u64, [_u64, _u32, _u32]),
     "nuq_pack_fixed": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp]),
@@ -424,6 +426,18 @@ def nuq_decode_huffman_batch(messages: list[Message], d: int, bucket: int, s: in
                                          arr([m.words for m in messages], torch.int32),
                                          arr([m.sync for m in messages]), d, bucket, s, sync_stride,
                                          _lengths(lengths, s), arr(qs, torch.uint8), _stream()))
+
+
+def nuq_decode_accumulate_huffman(messages: list[Message], d: int, bucket: int, s: int, sync_stride: int, lengths,
+                                  scale: float, accumulate: bool, out: torch.Tensor) -> None:
+    K = len(messages)
+    norms, offs, words, lens, sync = _message_arrays(messages, d, bucket, sync_stride, huffman=True)
+    if out.numel() != d:
+        raise ValueError("out must hold d floats")
+    _check("nuq_decode_accumulate_huffman",
+           _lib.nuq_decode_accumulate_huffman(K, norms, offs, words, lens, sync, d, bucket, s, sync_stride,
+                                              _lengths(lengths, s), float(scale), 1 if accumulate else 0,
+                                              _ptr(out, torch.float32), _stream()))
 
 
 def nuq_average_levels(norms: list[torch.Tensor], qs: list[torch.Tensor], d: int, bucket: int, s: int, scale: float,

@@ -1208,6 +1208,98 @@ int nuq_decode_huffman_batch(uint32_t K, const uint64_t *const *bit_off, const u
     return check_launch();
 }
 
+int nuq_decode_accumulate_huffman(uint32_t K, const float *const *norms, const uint64_t *const *bit_off,
+                                  const uint32_t *const *words, const uint64_t *words_len,
+                                  const uint32_t *const *sync, uint64_t d, uint32_t bucket, uint32_t s,
+                                  uint32_t sync_stride, const uint8_t *lengths, float scale, int accumulate,
+                                  float *out, nuq_stream_t stream)
+{
+    if (K < 1 || K > NUQ_MAX_WORKERS || !norms || !bit_off || !words || !words_len || !sync || !lengths || !out ||
+        !valid_common(d, bucket, s) || !valid_sync(sync_stride))
+        return NUQ_EINVAL;
+    const uint32_t nsync = nuq_huffman_num_sync(bucket, sync_stride);
+    HuffmanCode H;
+    if (!nsync || !huffman_tables(lengths, s, H))
+        return NUQ_EINVAL;
+    DecodeParams P{};
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!norms[k] || !bit_off[k] || !words[k] || !sync[k])
+            return NUQ_EINVAL;
+        P.norms[k] = norms[k];
+        P.bit_off[k] = bit_off[k];
+        P.words[k] = words[k];
+        P.words_bits[k] = words_len[k] > (UINT64_MAX >> 5) ? UINT64_MAX : words_len[k] << 5;
+        P.sync[k] = sync[k];
+    }
+    P.out = out;
+    P.d = d;
+    P.nb = nuq_num_buckets(d, bucket);
+    P.K = K;
+    P.bucket = bucket;
+    P.s = s;
+    P.scale = scale;
+    P.nsync = nsync;
+    P.nseg = nsync + 1u;                        // pieces per bucket: ceil(bucket / sync_stride)
+    P.sync_shift = log2u(sync_stride);
+    P.pieces_shift = log2u(kTileCoords / sync_stride);
+    // tiles as for the ERC strings: several whole buckets, or 2048 coordinates of one
+    uint64_t ntiles;
+    uint32_t max_streams;
+    if (bucket <= kTileCoords) {
+        const uint32_t by_size = kTileCoords / bucket, by_streams = kMaxStreams / K;
+        P.buckets_per_tile = by_size < by_streams ? by_size : by_streams;
+        P.tiles_per_bucket = 1;
+        P.tile_coords = P.buckets_per_tile * bucket;
+        P.segs_per_tile = P.nseg;
+        ntiles = (P.nb + P.buckets_per_tile - 1) / P.buckets_per_tile;
+        max_streams = P.buckets_per_tile * K;
+    } else {
+        P.buckets_per_tile = 0;
+        P.tile_coords = kTileCoords;
+        P.tiles_per_bucket = (bucket + kTileCoords - 1) / kTileCoords;
+        P.segs_per_tile = kTileCoords >> P.sync_shift;
+        ntiles = P.nb * P.tiles_per_bucket;
+        max_streams = K;
+    }
+    if (ntiles > 0x7fffffffull)
+        return NUQ_EINVAL;
+    P.ntiles = (uint32_t)ntiles;
+    P.xcd_base = P.ntiles / 8u;
+    P.xcd_rem = P.ntiles % 8u;
+    while ((2u << P.lanes_shift) * max_streams <= 64u)
+        ++P.lanes_shift;
+    // the lanes that copy a stream's words parse its pieces: a piece per lane
+    if (P.segs_per_tile > (1u << P.lanes_shift))
+        return NUQ_EINVAL;
+    P.stream_cap = HuffmanWaveCodec::kWordsPerLane << P.lanes_shift;
+    P.stream_stride = max_streams >= 16u ? P.stream_cap - 1u : P.stream_cap;
+    uint32_t *flags = flags_ptr();
+    if (!flags)
+        return NUQ_EHIP;
+    P.flags = flags;
+    auto kern = accumulate ? k_decode_wave_huffman<kUpdateAdd> : k_decode_wave_huffman<kUpdateWrite>;
+    static uint32_t cached[2][64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return NUQ_EHIP;
+    uint32_t &resident = cached[accumulate ? 1 : 0][dev];
+    if (!resident) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kern), (int)kWaveWG,
+                                                         0) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || per_cu < 1 ||
+            cus < 1)
+            return NUQ_EHIP;
+        resident = ((uint32_t)per_cu * (uint32_t)cus) & ~7u;          // a multiple of the eight XCDs (see xcd_tile)
+        if (!resident)
+            resident = 8u;
+    }
+    const uint32_t grid = P.ntiles < resident ? P.ntiles : resident;
+    ScopedTiming timing(NUQ_T_DECODE, static_cast<hipStream_t>(stream));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaveWG), 0, static_cast<hipStream_t>(stream), P, H);
+    return check_launch();
+}
+
 int nuq_decode_huffman(const uint64_t *bit_off, const uint32_t *words, const uint32_t *sync, uint64_t d,
                        uint32_t bucket, uint32_t s, uint32_t sync_stride, const uint8_t *lengths, uint8_t *q,
                        nuq_stream_t stream)

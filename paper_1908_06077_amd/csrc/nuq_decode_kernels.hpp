@@ -47,6 +47,7 @@ struct DecodeParams {
     uint32_t K;
     uint32_t bucket;
     uint32_t s;
+    uint32_t sync_shift;        // Huffman-coded messages: log2 of the coordinates per piece
     uint32_t pieces_shift;      // log2 of the index pieces per 2048-coordinate block
     uint32_t nsync;             // index entries per bucket, 0 = no index
     uint32_t nseg;              // units per bucket and worker: the pieces of the index (nsync), or 1 without one
@@ -930,24 +931,84 @@ struct WaveMeta {           // what a lane loads for its stream (bucket, worker)
     float norm;
 };
 
-template <bool kTable, int UPDATE, uint32_t TC>
-__global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
+// The paper's ENCODE (App. A): records ERC(gap) | sign | ERC(level index), pieces of equal record count.
+template <bool kTable>
+struct ErcCodec {
+    static constexpr uint32_t kWordsPerLane = nuq::kWordsPerLane;
+    uint16_t *lut;          // LDS: 128 entries (gap_table_entry)
+    uint8_t *lut_level;     // LDS: 128 entries (level_table_entry)
+    float *lev;             // LDS: 16 level values (level-table variant), else nullptr
+    struct Range {
+        uint32_t bit_lo, bit_hi;    // from the bucket's first bit
+        uint32_t forced, idx_hi;    // index of the piece's first record; records stay below idx_hi
+    };
+    __device__ __forceinline__ void init(const DecodeParams &P, uint32_t lane) const
+    {
+        lut[lane] = (uint16_t)gap_table_entry(lane);
+        lut[lane + kWave] = (uint16_t)gap_table_entry(lane + kWave);
+        lut_level[lane] = (uint8_t)level_table_entry(lane, P.s + 1u);
+        lut_level[lane + kWave] = (uint8_t)level_table_entry(lane + kWave, P.s + 1u);
+        if constexpr (kTable) {
+            if (lane < 16u)
+                lev[lane] = P.lev[lane];
+        }
+    }
+    __device__ __forceinline__ void entries(const uint32_t *sy, uint32_t g, const DecodeParams &P, uint32_t &e_lo,
+                                            uint32_t &e_hi) const
+    {
+        const uint32_t last = P.nsync - 1u;
+        e_lo = sy[min(g, last)];
+        e_hi = sy[min(g + 1u, last)];                                 // (not looked at for the bucket's last piece)
+    }
+    __device__ __forceinline__ bool range(const DecodeParams &P, uint32_t g, uint32_t nbk, uint32_t e_lo, uint32_t e_hi,
+                                          uint32_t len, Range &R, bool &bad) const
+    {
+        const uint32_t blk = g >> P.pieces_shift;
+        R.idx_hi = min(nbk, (blk + 1u) << kSyncBlockShift);
+        R.bit_lo = e_lo & kSyncOffMask;
+        R.bit_hi = g + 1u < P.nseg ? e_hi & kSyncOffMask : len;
+        R.forced = (blk << kSyncBlockShift) + (e_lo >> 21);
+        if (R.bit_lo > R.bit_hi || R.bit_hi > len) {
+            bad = true;
+            return false;
+        }
+        if (R.bit_hi == R.bit_lo)             // an empty piece (its entry's index field means nothing)
+            return false;
+        if (R.forced >= R.idx_hi) {
+            bad = true;
+            return false;
+        }
+        return true;
+    }
+    template <class Words>
+    __device__ __forceinline__ void parse(const Words &words, const Range &R, uint32_t bit0, float norm,
+                                          const TileSink &sink, bool &bad) const
+    {
+        const double wnorm = (double)norm * (kTable ? 1.0 : ldexp(1.0, -1 - (int)s));
+        decode_unit_fast<kTable>(words, lut, lut_level, lev, R.bit_lo - bit0, R.bit_hi - bit0, (int)R.forced, R.idx_hi,
+                                 wnorm, sink, bad);
+    }
+    uint32_t s;
+};
+
+// The kernel's body is written once for every code of the level indices.  A Codec supplies
+//   kWordsPerLane                    staged words each lane carries (64 x that many per tile)
+//   init(P, lane)                    its tables, into LDS that the kernel handed it
+//   entries(sy, g, P, e_lo, e_hi)    the index entries that bound piece g of a bucket (sy = the bucket's entries)
+//   range(P, g, nbk, e_lo, e_hi, len, R, bad)   piece g's bit range and what else its parse needs; false = nothing to do
+//   parse(words, R, bit0, norm, sink, bad)      the parse proper, adding values into the tile
+template <class Codec, int UPDATE, uint32_t TC>
+__device__ __forceinline__ void decode_wave(const DecodeParams &P, const Codec &codec)
 {
+    constexpr uint32_t kWordsPerLane = Codec::kWordsPerLane;
+    constexpr uint32_t kStageWords = kWave * kWordsPerLane;
     __shared__ __align__(16) double tile[TC];
     __shared__ uint32_t stage[kStageWords + 5];       // words at [1, kStageWords]; pads as in k_decode_accumulate
-    __shared__ uint16_t lut[128];
-    __shared__ uint8_t lut_level[128];
-    float *lev = nullptr;
-    if constexpr (kTable) {
-        __shared__ float lev_s[16];
-        lev = lev_s;
-    }
     const uint32_t lane = threadIdx.x;
     const bool partial = !P.buckets_per_tile;         // tiles are parts of one bucket
     const uint32_t stream_stride = TC == kTileCoordsBig ? P.stream_cap : P.stream_stride;
     const uint64_t last_bucket = P.nb - 1u;
     const uint32_t last_len = (uint32_t)(P.d - last_bucket * P.bucket);
-    const double wscale = kTable ? 1.0 : ldexp(1.0, -1 - (int)P.s);
 
     // this lane's stream (bucket in tile, worker) and piece of it; its pointers into that worker's arrays
     const uint32_t lanes = 1u << P.lanes_shift;
@@ -966,10 +1027,7 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
         m.bo0 = pb[b];
         m.bo1 = pb[b + 1];
         m.norm = pn[b];
-        const uint32_t *sy = ps + b * P.nsync;
-        const uint32_t g = min(G.g0 + my_sub, P.nsync - 1u);
-        m.e_lo = sy[g];
-        m.e_hi = sy[min(g + 1u, P.nsync - 1u)];                       // (not looked at for the bucket's last piece)
+        codec.entries(ps + b * P.nsync, G.g0 + my_sub, P, m.e_lo, m.e_hi);
         return m;
     };
     // the part of the lane's stream that the tile needs: from the entry of the tile's first piece to that of the
@@ -1016,14 +1074,7 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
     // ---- tables, cleared tile
     for (uint32_t i = lane; i < TC / 2u; i += kWaveWG)
         reinterpret_cast<double2 *>(tile)[i] = double2{0.0, 0.0};
-    lut[lane] = (uint16_t)gap_table_entry(lane);
-    lut[lane + kWave] = (uint16_t)gap_table_entry(lane + kWave);
-    lut_level[lane] = (uint8_t)level_table_entry(lane, P.s + 1u);
-    lut_level[lane + kWave] = (uint8_t)level_table_entry(lane + kWave, P.s + 1u);
-    if constexpr (kTable) {
-        if (lane < 16u)
-            lev[lane] = P.lev[lane];
-    }
+    codec.init(P, lane);
     if (lane < 5u)
         stage[lane ? kStageWords + lane : 0u] = 0u;                  // the pads
 
@@ -1066,30 +1117,18 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
         // ---- this lane's piece of tile t
         const uint32_t pieces = G0.g1 - G0.g0;
         if (my_stream < G0.nstreams && my_sub < pieces) {
-            const uint32_t g = G0.g0 + my_sub;
             const uint32_t nbk = G0.b0 + sbi == last_bucket ? last_len : P.bucket;
-            const uint32_t blk = g >> P.pieces_shift;
-            const uint32_t idx_hi = min(nbk, (blk + 1u) << kSyncBlockShift);
-            const uint32_t bit_lo = M0.e_lo & kSyncOffMask;
-            const uint32_t bit_hi = g + 1u < P.nseg ? M0.e_hi & kSyncOffMask : S0.len;
-            const uint32_t forced = (blk << kSyncBlockShift) + (M0.e_lo >> 21);
-            if (bit_lo > bit_hi || bit_hi > S0.len) {
-                bad = true;
-            } else if (bit_hi > bit_lo) {
+            typename Codec::Range R;
+            if (codec.range(P, G0.g0 + my_sub, nbk, M0.e_lo, M0.e_hi, S0.len, R, bad)) {
                 // (an index that is not monotone would leave the part of the stream that was copied)
-                if (forced >= idx_hi || bit_lo < S0.bit0 || bit_hi > S0.bit0 + (S0.nwords << 5)) {
+                if (R.bit_lo < S0.bit0 || R.bit_hi > S0.bit0 + (S0.nwords << 5)) {
                     bad = true;
                 } else {
-                    double *origin = partial ? tile - (int)G0.in_lo : tile + sbi * P.bucket;
-                    const double wnorm = (double)M0.norm * wscale;
+                    const TileSink sink{partial ? tile - (int)G0.in_lo : tile + sbi * P.bucket};
                     if (S0.nwords <= stream_stride)
-                        decode_unit_fast<kTable>(StagedWords{stage + my_stream * stream_stride}, lut, lut_level, lev,
-                                                 bit_lo - S0.bit0, bit_hi - S0.bit0, (int)forced, idx_hi, wnorm,
-                                                 TileSink{origin}, bad);
+                        codec.parse(StagedWords{stage + my_stream * stream_stride}, R, S0.bit0, M0.norm, sink, bad);
                     else {                            // the part did not fit the staging area: words from global memory
-                        decode_unit_fast<kTable>(GlobalWords{pw + S0.first_word, S0.nwords - 1u}, lut, lut_level, lev,
-                                                 bit_lo - S0.bit0, bit_hi - S0.bit0, (int)forced, idx_hi, wnorm,
-                                                 TileSink{origin}, bad);
+                        codec.parse(GlobalWords{pw + S0.first_word, S0.nwords - 1u}, R, S0.bit0, M0.norm, sink, bad);
                         // every load of this rare path has landed before the paths join again: otherwise the compiler,
                         // which must assume the worst of the joined paths, waits for all memory traffic wherever the
                         // usual path later touches a register that this one loaded into
@@ -1114,6 +1153,20 @@ __global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
     }
     if (bad)
         atomicOr(P.flags, kFlagMalformed);
+}
+
+
+template <bool kTable, int UPDATE, uint32_t TC>
+__global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
+{
+    __shared__ uint16_t lut[128];
+    __shared__ uint8_t lut_level[128];
+    float *lev = nullptr;
+    if constexpr (kTable) {
+        __shared__ float lev_s[16];
+        lev = lev_s;
+    }
+    decode_wave<ErcCodec<kTable>, UPDATE, TC>(P, ErcCodec<kTable>{lut, lut_level, lev, P.s});
 }
 
 // ---- one message (K = 1), main scheme's levels, output written or added to -------------------------------------

@@ -788,6 +788,130 @@ __global__ __launch_bounds__(kHuffmanDirectWG) void k_huffman_decode_direct(Huff
         atomicOr(P.flags, kFlagMalformed);
 }
 
+// ------------------------------------------------- decode + average of K messages in one launch
+// The tile decoder of the ERC path (decode_wave) with the parse of a Huffman-coded piece: piece g of a bucket is its
+// coordinates [g * stride, (g + 1) * stride), bounded by the index entries g - 1 (0 for the first) and g.  The
+// level|sign bytes are never written: a nonzero symbol's value goes straight into the tile's fp64 sum.
+//
+// With gradients nearly all symbols are level 0, and a canonical code gives the most frequent symbol the codeword
+// "0" once it has one bit.  Then (zero_run) a step of the parse is one run of zero symbols = the window's leading
+// zero bits, followed by one nonzero symbol when its codeword and sign still fit the 32-bit window: about as many
+// steps as the ERC parse has records.  With any other code a step is one symbol.
+struct HuffmanWaveCodec {
+    static constexpr uint32_t kWordsPerLane = 16;      // a tile's part of a string is ~75 words on gradient data
+    uint8_t *lut8;          // LDS, 256 entries: symbol | length << 4 of the codeword the eight bits start with, else 0
+    uint32_t *canon;        // LDS, 64 words: first[16], count[16], offset[16], sorted[16] of the canonical code
+    const HuffmanCode *H;
+    uint32_t s, sync_shift;
+    struct Range {
+        uint32_t bit_lo, bit_hi;    // from the bucket's first bit
+        uint32_t c_lo, n;           // first coordinate (in the bucket) and number of coordinates
+    };
+    __device__ __forceinline__ void init(const DecodeParams &, uint32_t lane) const
+    {
+        if (lane < 16u) {
+            canon[lane] = H->first[lane];
+            canon[16u + lane] = H->count[lane];
+            canon[32u + lane] = H->offset[lane];
+            canon[48u + lane] = H->sorted[lane];
+        }
+        for (uint32_t p = lane; p < 256u; p += kWave) {
+            uint32_t entry = 0;
+            for (uint32_t L = 1; L <= 8u && L <= H->maxlen; ++L) {
+                const uint32_t idx = (p >> (8u - L)) - H->first[L];
+                if (idx < H->count[L]) {
+                    entry = H->sorted[H->offset[L] + idx] | (L << 4);
+                    break;
+                }
+            }
+            lut8[p] = (uint8_t)entry;
+        }
+    }
+    __device__ __forceinline__ void entries(const uint32_t *sy, uint32_t g, const DecodeParams &P, uint32_t &e_lo,
+                                            uint32_t &e_hi) const
+    {
+        e_lo = g ? sy[min(g, P.nsync) - 1u] : 0u;
+        e_hi = sy[min(g, P.nsync - 1u)];                              // (not looked at for the bucket's last piece)
+    }
+    __device__ __forceinline__ bool range(const DecodeParams &P, uint32_t g, uint32_t nbk, uint32_t e_lo, uint32_t e_hi,
+                                          uint32_t len, Range &R, bool &bad) const
+    {
+        R.c_lo = g << sync_shift;
+        if (R.c_lo >= nbk)
+            return false;
+        R.n = min(nbk - R.c_lo, 1u << sync_shift);
+        R.bit_lo = e_lo & kSyncOffMask;
+        R.bit_hi = g + 1u < P.nseg ? e_hi & kSyncOffMask : len;
+        if (R.bit_lo > R.bit_hi || R.bit_hi > len) {
+            bad = true;
+            return false;
+        }
+        return true;
+    }
+    template <class Words>
+    __device__ __forceinline__ void parse(const Words &words, const Range &R, uint32_t bit0, float norm,
+                                          const TileSink &sink, bool &bad) const
+    {
+        const double wnorm = (double)norm * ldexp(1.0, -1 - (int)s);
+        const uint32_t maxlen = H->maxlen;
+        const bool zero_run = H->len[0] == 1u;        // symbol 0 is the codeword "0"
+        const uint32_t zcap = zero_run ? 30u - maxlen : 0u;   // zeros + codeword + sign: 31 bits of the window at most
+        uint32_t p31 = R.bit_lo - bit0 + 31u;
+        const uint32_t end31 = R.bit_hi - bit0 + 31u;
+        uint32_t q = p31 >> 5;
+        uint32_t hi = words.at(q), lo = words.at(q + 1u), nx = words.at(q + 2u);
+        uint32_t i = 0;
+        while (i < R.n && p31 < end31) {
+            const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, ~p31);
+            const uint32_t z = zero_run ? (uint32_t)__clz((int)w) : 0u;       // 32 for an all-zero window
+            const uint32_t left = R.n - i;
+            const bool symbol = z <= zcap && z < left;       // a symbol that is not part of the zero run follows
+            const uint32_t zc = min(min(z, zcap), left);
+            const uint32_t w2 = w << zc;
+            uint32_t entry = lut8[w2 >> 24];
+            if (symbol && !entry) {                            // a codeword of nine bits or more (rare), or none
+                for (uint32_t L = 9; L <= maxlen; ++L) {
+                    const uint32_t idx = (w2 >> (32u - L)) - canon[L];
+                    if (idx < canon[16u + L]) {
+                        entry = canon[48u + canon[32u + L] + idx] | (L << 4);
+                        break;
+                    }
+                }
+            }
+            const uint32_t sym = entry & 15u, L = entry >> 4;
+            uint32_t bits = zc;
+            if (symbol) {
+                bad |= !L;
+                bits += L + (sym ? 1u : 0u);
+                if (sym) {
+                    const double mag = ldexp(wnorm, (int)sym);
+                    const uint32_t neg = (w2 << L) & 0x80000000u;
+                    const uint64_t vb = (uint64_t)__double_as_longlong(mag) | ((uint64_t)neg << 32);
+                    sink.add(R.c_lo + i + zc, __longlong_as_double((long long)vb));
+                }
+                ++i;
+            }
+            i += zc;
+            p31 += max(bits, 1u);                              // (a prefix that is no codeword still moves on)
+            const uint32_t qn = p31 >> 5;
+            const bool moved = qn != q;
+            hi = moved ? lo : hi;
+            lo = moved ? nx : lo;
+            q = qn;
+            nx = words.at(qn + 2u);
+        }
+        bad |= i != R.n || p31 != end31;
+    }
+};
+
+template <int UPDATE>
+__global__ __launch_bounds__(kWaveWG, 7) void k_decode_wave_huffman(DecodeParams P, HuffmanCode H)
+{
+    __shared__ uint8_t lut8[256];
+    __shared__ uint32_t canon[64];
+    decode_wave<HuffmanWaveCodec, UPDATE, kTileCoords>(P, HuffmanWaveCodec{lut8, canon, &H, P.s, P.sync_shift});
+}
+
 // ------------------------------------------------------------------ average of level bytes
 struct AverageParams {
     const float *norms[kMaxBatch];

@@ -116,6 +116,42 @@ def test_histogram_code_message_decode_and_average(g, d, n, s, S, K, kind):
         mag += np.abs(deq)
     diff = np.abs(out.cpu().numpy().astype(np.float64) - want * scale32)
     assert np.all(diff <= 1e-6 * mag * scale32 + 1e-45)
+    # decode + average of the K messages in one launch (no bytes in between): the same average, written or added
+    if fused_decode_fits(n, S, K):
+        prior = torch.from_numpy(rng.standard_normal(d).astype(np.float32)).to(g.DEV)
+        for accumulate in (False, True):
+            out2 = prior.clone()
+            nuq.nuq_decode_accumulate_huffman(msg_list, d, n, s, S, lengths, 1.0 / K, accumulate, out2)
+            assert nuq.nuq_last_error_flags() == 0
+            ref = want * scale32
+            got = out2.cpu().numpy().astype(np.float64)
+            if accumulate:
+                # the sum is rounded to fp32 first, then added to the old value in fp32
+                ref32 = ref.astype(np.float32)
+                p64 = prior.cpu().numpy().astype(np.float64)
+                assert np.all(np.abs(got - (ref32.astype(np.float64) + p64))
+                              <= 1e-6 * mag * scale32 + 6e-8 * (np.abs(ref) + np.abs(p64)) + 1e-45)
+            else:
+                assert np.all(np.abs(got - ref) <= 1e-6 * mag * scale32 + 1e-45)
+    else:
+        with pytest.raises(nuq.NuqError):
+            nuq.nuq_decode_accumulate_huffman(msg_list, d, n, s, S, lengths, 1.0 / K, False, out)
+
+
+def fused_decode_fits(n, S, K):
+    """The geometry nuq_decode_accumulate_huffman takes (include/nuq.h): an index, and a lane per piece within the
+    power-of-two group of lanes that a message has in a tile."""
+    if S == 0 or n <= S:
+        return False
+    if n <= 2048:
+        streams = min(2048 // n, 64 // K) * K
+        pieces = -(-n // S)
+    else:
+        streams, pieces = K, 2048 // S
+    lanes = 1
+    while 2 * lanes * streams <= 64:
+        lanes *= 2
+    return pieces <= lanes
 
 
 def _random_huffman_cases(count, seed):
@@ -173,6 +209,14 @@ def test_codes_that_do_not_fit_the_data(g, s, n, S, hist):
     assert nuq.nuq_last_error_flags() == 0
     np.testing.assert_array_equal(back.cpu().numpy(), q_np)
     np.testing.assert_array_equal(oracle.decode_huffman(bo, w_ref, d, n, s, lengths), q_np)
+    # the same message through the fused decoder, with norms that differ per bucket
+    norms_np = (10.0 ** rng.uniform(-2, 2, size=B)).astype(np.float32)
+    msg = nuq.Message(torch.from_numpy(norms_np).to(g.DEV), bit_off, words, sync)
+    out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_decode_accumulate_huffman([msg], d, n, s, S, lengths, 1.0, False, out)
+    assert nuq.nuq_last_error_flags() == 0
+    want = oracle.dequantize(oracle.decode_huffman(bo, w_ref, d, n, s, lengths), n, s, norms_np)
+    np.testing.assert_allclose(out.cpu().numpy().astype(np.float64), want, rtol=1e-6, atol=1e-45)
 
 
 def test_malformed_messages_raise_the_flag(g):
@@ -193,6 +237,20 @@ def test_malformed_messages_raise_the_flag(g):
     bad_bo = bo.copy()
     bad_bo[-1] -= 1                                   # the last bucket one bit short
     nuq.nuq_decode_huffman(dev(bad_bo, np.int64), dev(words, np.int32), dev(sync, np.int32), d, n, s, S, lengths, q)
+    assert nuq.nuq_last_error_flags() == nuq.FLAG_MALFORMED
+    # the fused decoder sees the same damage
+    norms = torch.ones(d // n, dtype=torch.float32, device=g.DEV)
+    out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+    mk = lambda b_, s_: nuq.Message(norms, dev(b_, np.int64), dev(words, np.int32), dev(s_, np.int32))
+    nuq.nuq_decode_accumulate_huffman([mk(bo, sync)], d, n, s, S, lengths, 1.0, False, out)
+    assert nuq.nuq_last_error_flags() == 0
+    np.testing.assert_allclose(out.cpu().numpy(), oracle.dequantize(q_np, n, s, np.ones(d // n, np.float32)), rtol=1e-6)
+    nuq.nuq_decode_accumulate_huffman([mk(bo, bad_sync)], d, n, s, S, lengths, 1.0, False, out)
+    assert nuq.nuq_last_error_flags() == nuq.FLAG_MALFORMED
+    nuq.nuq_decode_accumulate_huffman([mk(bad_bo, sync)], d, n, s, S, lengths, 1.0, False, out)
+    assert nuq.nuq_last_error_flags() == nuq.FLAG_MALFORMED
+    short = nuq.Message(norms, dev(bo, np.int64), dev(words, np.int32)[: words.size // 2], dev(sync, np.int32))
+    nuq.nuq_decode_accumulate_huffman([short], d, n, s, S, lengths, 1.0, False, out)      # words cut off
     assert nuq.nuq_last_error_flags() == nuq.FLAG_MALFORMED
     with pytest.raises(nuq.NuqError):                 # lengths that are no complete code are refused on the host
         nuq.nuq_decode_huffman(dev(bo, np.int64), dev(words, np.int32), dev(sync, np.int32), d, n, s, S,
@@ -234,3 +292,56 @@ def test_config3_worker_at_full_size(g):
     assert nuq.nuq_last_error_flags() == 0
     assert torch.equal(back, q)
     assert 1.0 < float(bo[-1]) / d < 1.5              # one bit per zero, a few more for the 7 % that are not
+
+
+def test_config3_fused_decode_at_full_size(g):
+    """Config 3 at full size, all 8 workers coded in one launch and decoded + averaged in one launch, the way
+    bench.py --huffman runs them: on sampled runs of buckets every worker's message piece is the oracle's and the
+    average is the oracle's average of what those pieces decode to."""
+    nuq = g.nuq
+    w = workloads.workload(3)
+    d, n, s, S, K = w.d, w.bucket, w.s, 256, w.K
+    B, nsync = nuq.nuq_num_buckets(d, n), nuq.nuq_huffman_num_sync(n, S)
+    vs = [workloads.generate(w, k, g.DEV) for k in range(K)]
+    seeds = [w.quant_seed(k) for k in range(K)]
+    # the code: from worker 0's levels
+    norms0 = torch.empty(B, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_bucket_norms(vs[0], n, norms0)
+    q0 = torch.empty(d, dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_quantize(vs[0], n, s, seeds[0], norms0, q0)
+    hist = torch.empty(16, dtype=torch.int64, device=g.DEV)
+    nuq.nuq_level_histogram(q0, hist)
+    lengths = nuq.nuq_huffman_lengths([int(x) for x in hist.cpu().numpy()[: s + 2]], s)
+    del q0
+    cap = nuq.nuq_huffman_max_words(d, n) // 4
+    msgs = [nuq.Message(torch.empty(B, dtype=torch.float32, device=g.DEV),
+                        torch.empty(B + 1, dtype=torch.int64, device=g.DEV),
+                        torch.full((cap,), 0x5A5A5A5A, dtype=torch.int32, device=g.DEV),
+                        torch.empty(B * nsync, dtype=torch.int32, device=g.DEV)) for _ in range(K)]
+    ws = torch.empty(nuq.nuq_encode_huffman_batch_workspace_bytes(K, d, n, s), dtype=torch.uint8, device=g.DEV)
+    nuq.nuq_quantize_encode_huffman_batch(vs, n, s, seeds, S, lengths, msgs, ws)
+    assert nuq.nuq_last_error_flags() == 0
+    out = torch.empty(d, dtype=torch.float32, device=g.DEV)
+    nuq.nuq_decode_accumulate_huffman(msgs, d, n, s, S, lengths, 1.0 / K, False, out)
+    assert nuq.nuq_last_error_flags() == 0
+    rng = np.random.default_rng(4)
+    run = 3
+    scale32 = float(np.float32(1.0 / K))
+    for b_lo in sorted({0, B - run} | {int(x) for x in rng.integers(0, B - run, size=16)}):
+        c_lo, c_hi = b_lo * n, min(d, (b_lo + run) * n)
+        want, mag = np.zeros(c_hi - c_lo), np.zeros(c_hi - c_lo)
+        for v, m, seed in zip(vs, msgs, seeds):
+            norms = m.norms[b_lo:b_lo + run].cpu().numpy()
+            g.check_norms(v[c_lo:c_hi].cpu().numpy(), n, norms)
+            q = oracle.quantize(v[c_lo:c_hi].cpu().numpy(), n, s, seed, norms, b_lo)
+            bo, words, sync = oracle.encode_huffman(q, n, s, lengths, S)
+            got_bo = g.u64(m.bit_off[b_lo:b_lo + run + 1])
+            start = (int(got_bo[0]) + 31) // 32 * 32
+            np.testing.assert_array_equal(got_bo[1:] - np.uint64(start), bo[1:])
+            np.testing.assert_array_equal(g.u32(m.words[start // 32: start // 32 + words.size]), words)
+            np.testing.assert_array_equal(g.u32(m.sync[b_lo * nsync:(b_lo + run) * nsync]), sync)
+            deq = oracle.dequantize(oracle.decode_huffman(bo, words, c_hi - c_lo, n, s, lengths), n, s, norms)
+            want += deq
+            mag += np.abs(deq)
+        diff = np.abs(out[c_lo:c_hi].cpu().numpy().astype(np.float64) - want * scale32)
+        assert np.all(diff <= 1e-6 * mag * scale32 + 1e-45)
