@@ -369,7 +369,7 @@ def measure(args, config, steps, warmup, cpu_budget):
                                        if huff and args.huffman_two_kernels else
                                        "k_decode_wave_huffman (decode + average of K Huffman-coded messages)" if huff else
                                        "k_unpack_accumulate_fixed (unpack + average of K messages)" if fb else
-                                       "k_decode_accumulate (DECODE + average of K messages)"),
+                                       "tile decoder k_decode_wave, or k_decode_single for one message (DECODE + average of K messages)"),
                             "bound": "hbm", "achieved": round(dec_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
                             "traffic": None if lev is not None or fb or huff or upd in ("sgd", "momentum")

@@ -1157,7 +1157,7 @@ __device__ __forceinline__ void decode_wave(const DecodeParams &P, const Codec &
 
 
 template <bool kTable, int UPDATE, uint32_t TC>
-__global__ __launch_bounds__(kWaveWG, 8) void k_decode_wave(DecodeParams P)
+__global__ __launch_bounds__(kWaveWG, 2) void k_decode_wave(DecodeParams P)
 {
     __shared__ uint16_t lut[128];
     __shared__ uint8_t lut_level[128];

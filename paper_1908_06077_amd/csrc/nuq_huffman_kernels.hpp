@@ -905,7 +905,7 @@ struct HuffmanWaveCodec {
 };
 
 template <int UPDATE>
-__global__ __launch_bounds__(kWaveWG, 7) void k_decode_wave_huffman(DecodeParams P, HuffmanCode H)
+__global__ __launch_bounds__(kWaveWG, 2) void k_decode_wave_huffman(DecodeParams P, HuffmanCode H)
 {
     __shared__ uint8_t lut8[256];
     __shared__ uint32_t canon[64];
