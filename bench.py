@@ -137,7 +137,7 @@ def measure(args, config, steps, warmup, cpu_budget):
     dev = torch.device("cuda:0")
     w = workloads.workload(config)
     d, n, s, K = w.d, w.bucket, w.s, w.K
-    S = args.sync_stride if args.sync_stride is not None else (256 if n >= 1024 else 128)
+    S = args.sync_stride if args.sync_stride is not None else workloads.sync_stride(w)
     if n <= S:
         S = 0
     B = nuq.nuq_num_buckets(d, n)

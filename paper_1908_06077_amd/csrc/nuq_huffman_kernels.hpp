@@ -861,6 +861,7 @@ struct HuffmanWaveCodec {
         uint32_t q = p31 >> 5;
         uint32_t hi = words.at(q), lo = words.at(q + 1u), nx = words.at(q + 2u);
         uint32_t i = 0;
+        const bool long_codes = maxlen > 8u;                  // uniform: most codes have none
         while (i < R.n && p31 < end31) {
             const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, ~p31);
             const uint32_t z = zero_run ? (uint32_t)__clz((int)w) : 0u;       // 32 for an all-zero window
@@ -869,7 +870,7 @@ struct HuffmanWaveCodec {
             const uint32_t zc = min(min(z, zcap), left);
             const uint32_t w2 = w << zc;
             uint32_t entry = lut8[w2 >> 24];
-            if (symbol && !entry) {                            // a codeword of nine bits or more (rare), or none
+            if (long_codes && symbol && !entry) {              // a codeword of nine bits or more, or none
                 for (uint32_t L = 9; L <= maxlen; ++L) {
                     const uint32_t idx = (w2 >> (32u - L)) - canon[L];
                     if (idx < canon[16u + L]) {
@@ -878,20 +879,12 @@ struct HuffmanWaveCodec {
                     }
                 }
             }
-            const uint32_t sym = entry & 15u, L = entry >> 4;
-            uint32_t bits = zc;
-            if (symbol) {
-                bad |= !L;
-                bits += L + (sym ? 1u : 0u);
-                if (sym) {
-                    const double mag = ldexp(wnorm, (int)sym);
-                    const uint32_t neg = (w2 << L) & 0x80000000u;
-                    const uint64_t vb = (uint64_t)__double_as_longlong(mag) | ((uint64_t)neg << 32);
-                    sink.add(R.c_lo + i + zc, __longlong_as_double((long long)vb));
-                }
-                ++i;
-            }
-            i += zc;
+            // everything below is straight-line: a step without a symbol adds nothing and moves on by its zeros
+            const uint32_t sym = symbol ? entry & 15u : 0u, L = entry >> 4;
+            bad |= symbol && !L;
+            const uint32_t bits = zc + (symbol ? L + (sym ? 1u : 0u) : 0u);
+            const uint32_t at = R.c_lo + i + zc;
+            i += zc + (symbol ? 1u : 0u);
             p31 += max(bits, 1u);                              // (a prefix that is no codeword still moves on)
             const uint32_t qn = p31 >> 5;
             const bool moved = qn != q;
@@ -899,6 +892,12 @@ struct HuffmanWaveCodec {
             lo = moved ? nx : lo;
             q = qn;
             nx = words.at(qn + 2u);
+            if (sym) {
+                const double mag = ldexp(wnorm, (int)sym);
+                const uint32_t neg = (w2 << L) & 0x80000000u;
+                const uint64_t vb = (uint64_t)__double_as_longlong(mag) | ((uint64_t)neg << 32);
+                sink.add(at, __longlong_as_double((long long)vb));
+            }
         }
         bad |= i != R.n || p31 != end31;
     }

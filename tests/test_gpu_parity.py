@@ -420,7 +420,7 @@ def test_full_size_in_the_benchmark_configuration(g):
     for cfg in (3, 4, 5):
         w = workloads.workload(cfg)
         n, s, K, d = w.bucket, w.s, w.K, w.d
-        S = 256 if n >= 1024 else 128
+        S = workloads.sync_stride(w)
         B = nuq.nuq_num_buckets(d, n)
         print("cfg %d: generating %d x %d coordinates" % (cfg, K, d), flush=True)
         vs = [workloads.generate(w, k, g.DEV) for k in range(K)]

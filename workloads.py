@@ -112,6 +112,15 @@ def workload(cfg: int) -> Workload:
     raise ValueError("workloads are numbered 1..5")
 
 
+def sync_stride(w: Workload) -> int:
+    """The decoder-index stride the benchmark (and the full-size parity tests) use for a workload: the tile decoder
+    parses a 2048-coordinate tile of K messages with 64 lanes, a piece each, so K * 2048 / stride = 64, kept within
+    128..256 (a finer index costs more bytes than it saves time); one message alone decodes a lane per piece."""
+    if w.K == 1:
+        return 256
+    return max(128, min(256, 32 * w.K))
+
+
 def scaled(w: Workload, d_target: int) -> Workload:
     """Same structure at a smaller size (for CPU-sized tests): tensor sizes shrunk
     proportionally, at least one element each; flat workloads just shortened."""
