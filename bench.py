@@ -198,6 +198,7 @@ def measure(args, config, steps, warmup, cpu_budget):
         msgs = [new_msg((int(p.bit_off[-1].item()) + 31) // 32 + 64) for p in probes]
         del probes
     out = torch.empty(d, dtype=torch.float32, device=dev)
+    plain_decoder = lev is None and not fb and not huff and args.update == "none"
     upd = args.update
     if upd != "none":
         if huff or fb or lev is not None:
@@ -378,6 +379,16 @@ def measure(args, config, steps, warmup, cpu_budget):
                             "launches": len(dec_ms)},
     }
 
+    if plain_decoder:
+        # The decoder is bound by vector instruction issue, not memory: the same launch time against the chip's issue
+        # rate (1024 SIMDs, a wave instruction per 4 clocks at 2.4 GHz), with the instruction count of the counter runs.
+        insts = measured_traffic("k_decode_accumulate", config, S, "valu_insts")
+        if insts:
+            peak = 1024 * 2.4e9 / 4 / 1e9
+            rate = insts / (dec_kernel_ms * 1e-3) / 1e9
+            result["roofline_decode"]["issue"] = {"bound": "alu", "achieved": round(rate, 1), "peak": round(peak, 1),
+                                                  "unit": "G wave-instructions/s", "frac": round(rate / peak, 4),
+                                                  "instructions_per_launch": insts}
     if args.graph:
         result["config"]["launch"] = "one HIP graph replay per step; kernel brackets from eager steps after the timed region"
     if upd != "none":
@@ -436,7 +447,7 @@ def reference_kernels(torch, numel, dev):
     return out
 
 
-def measured_traffic(kernel, config, S):
+def measured_traffic(kernel, config, S, field="bytes_per_launch"):
     """HBM bytes per launch of `kernel` from the hardware-counter runs recorded in profiles/hbm_traffic.json
     (rocprofv3 FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size), or None if that file has no
     entry for this workload.  The counters cannot be read from inside this process."""
@@ -447,7 +458,7 @@ def measured_traffic(kernel, config, S):
     except (OSError, ValueError):
         return None
     entry = table.get("config%d_stride%d" % (config, S), {}).get(kernel)
-    return None if entry is None else entry.get("bytes_per_launch")
+    return None if entry is None else entry.get(field)
 
 
 def cpu_baseline(w, grads, S, lev=None, norm="l2", fb=0, hlen=None, budget_coords=300_000_000):
