@@ -47,7 +47,7 @@ def parse_args():
                          "entry points")
     ap.add_argument("--fixed-bits", type=int, default=0,
                     help="b in 3..8: fixed-width coding (sign and level index in b bits per coordinate, the paper's "
-                         "\"4-bit\"/\"8-bit\" variants) instead of the ERC bit strings; main scheme's levels only")
+                         "\"4-bit\"/\"8-bit\" variants) instead of the ERC bit strings; with --levels / --norm: QSGD and QSGDinf at fixed width")
     ap.add_argument("--huffman", action="store_true",
                     help="Huffman-coded levels (the paper's \"encoded\" variant) instead of the ERC bit strings: per "
                          "fused norms + quantizer + Huffman coding; decode to level bytes and one averaging kernel; "
@@ -184,9 +184,6 @@ def measure(args, config, steps, warmup, cpu_budget):
         hlen = nuq.nuq_huffman_lengths([int(x) for x in hhist.cpu().numpy()[: s + 2]], s)
         msgs = [new_msg(nuq.nuq_huffman_max_words(d, n) // 4) for _ in range(K)]       # 4 bits/coord of room
     elif fb:
-        if lev is not None:
-            print("--fixed-bits goes with the main scheme's levels", file=sys.stderr)
-            sys.exit(2)
         wpb = (n * fb + 31) // 32
         fnorms = [torch.empty(B, dtype=torch.float32, device=dev) for _ in range(K)]
         fpacked = [torch.empty(nuq.nuq_fixed_words(d, n, fb), dtype=torch.int32, device=dev) for _ in range(K)]
@@ -211,6 +208,8 @@ def measure(args, config, steps, warmup, cpu_budget):
     def encode_all():
         if huff:
             nuq.nuq_quantize_encode_huffman_batch(grads, n, s, seeds, S, hlen, msgs, hws)
+        elif fb and lev is not None:
+            nuq.nuq_quantize_pack_fixed_table_batch(grads, n, lev, norm_kind, fb, seeds, fnorms, fpacked)
         elif fb:
             nuq.nuq_quantize_pack_fixed_batch(grads, n, s, fb, seeds, fnorms, fpacked)
         elif lev is not None:
@@ -228,6 +227,8 @@ def measure(args, config, steps, warmup, cpu_budget):
             nuq.nuq_average_levels([m.norms for m in msgs], hback, d, n, s, 1.0 / K, False, out)
         elif huff:
             nuq.nuq_decode_accumulate_huffman(msgs, d, n, s, S, hlen, 1.0 / K, False, out)
+        elif fb and lev is not None:
+            nuq.nuq_unpack_accumulate_fixed_table(fnorms, fpacked, d, n, lev, fb, 1.0 / K, False, out)
         elif fb:
             nuq.nuq_unpack_accumulate_fixed(fnorms, fpacked, d, n, s, fb, 1.0 / K, False, out)
         elif lev is not None:
@@ -347,7 +348,8 @@ def measure(args, config, steps, warmup, cpu_budget):
         "config": {"workload": "configs[%d] %s: d=%d fp32, bucket=%d, s=%d, K=%d workers, sync_stride=%d%s"
                                % (config - 1, w.name, d, n, s, K, S,
                                   ", Huffman-coded levels, lengths %s" % hlen if huff else
-                                  (", fixed-width %d bits" % fb) if fb else
+                                  (", fixed-width %d bits" % fb + ("" if lev is None else ", level table %s, %s norm"
+                                                                    % (args.levels, args.norm))) if fb else
                                   "" if lev is None else ", level table %s, %s norm" % (args.levels, args.norm))},
         "phases": {
             "quantize_encode": {"ms": round(ms_enc, 4), "fp32_in_GBps": round(in_bytes / (ms_enc * 1e-3) / 1e9, 2),
@@ -503,6 +505,11 @@ def cpu_baseline(w, grads, S, lev=None, norm="l2", fb=0, hlen=None, budget_coord
             acc = np.zeros(m)
             for norms, bo, words in parts:
                 acc += oracle.dequantize(oracle.decode_huffman(bo, words, m, n, s, hlen), n, s, norms)
+            acc *= 1.0 / K
+        elif fb and lev is not None:
+            acc = np.zeros(m)
+            for norms, packed, _ in parts:
+                acc += oracle.dequantize_table(oracle.unpack_fixed(packed, m, n, s, fb), n, lev, norms)
             acc *= 1.0 / K
         elif fb:
             oracle.unpack_average_fixed([p[0] for p in parts], [p[1] for p in parts], m, n, s, fb, 1.0 / K)

@@ -266,6 +266,21 @@ int nuq_unpack_accumulate_fixed(uint32_t K, const float *const *norms, const uin
                                 uint64_t d, uint32_t bucket, uint32_t s, uint32_t b, float scale,
                                 int accumulate, float *out, nuq_stream_t stream);
 
+/* The two fused calls above for a level sequence `levels` (s + 2 floats in HOST memory, as for
+ * nuq_quantize_table) and the norm `norm_kind` (NUQ_NORM_L2 / NUQ_NORM_LINF): the fixed-width coding
+ * of QSGD and QSGDinf (Sec. 1, Sec. 2; Sec. 5 compares the schemes at equal bit widths).  norms[k] is
+ * what the norm entry point gives, packed[k] = nuq_pack_fixed(nuq_quantize_table(v[k], ..., levels,
+ * seeds[k], norms[k])); the receiver sums norms_k[b] * sign * levels[j].  Other arguments, rounding
+ * and flags as in the two calls above. */
+int nuq_quantize_pack_fixed_table_batch(uint32_t K, const float *const *v, const uint64_t *seeds,
+                                        uint64_t d, uint32_t bucket, uint32_t s, const float *levels,
+                                        uint32_t norm_kind, uint32_t b, float *const *norms,
+                                        uint32_t *const *packed, nuq_stream_t stream);
+int nuq_unpack_accumulate_fixed_table(uint32_t K, const float *const *norms,
+                                      const uint32_t *const *packed, uint64_t d, uint32_t bucket,
+                                      uint32_t s, const float *levels, uint32_t b, float scale,
+                                      int accumulate, float *out, nuq_stream_t stream);
+
 /* ---- Huffman-coded levels (Sec. 5, "Efficient Encoding": a Huffman code for the level indices, built
  *      from a sample and then kept) ------------------------------------------------------------------ */
 

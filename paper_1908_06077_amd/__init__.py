@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     nuq_level_histogram, nuq_huffman_lengths, nuq_huffman_max_words, nuq_encode_huffman_workspace_bytes,
     nuq_encode_huffman, nuq_encode_huffman_batch_workspace_bytes, nuq_quantize_encode_huffman_batch, nuq_decode_huffman, nuq_decode_huffman_batch, nuq_average_levels, nuq_decode_accumulate_huffman,
     nuq_fixed_words, nuq_pack_fixed, nuq_quantize_pack_fixed_batch, nuq_unpack_accumulate_fixed,
+    nuq_quantize_pack_fixed_table_batch, nuq_unpack_accumulate_fixed_table,
     nuq_momentum_step, nuq_decode_momentum_step, nuq_moments_accumulate, nuq_normalized_variance, VARIANCE_WORKSPACE_BYTES,
     nuq_last_error_flags, library_path, exported_symbols,
     nuq_timing_begin, nuq_timing_collect, T_NORMS, T_QUANTIZE, T_ENCODE, T_QUANTIZE_ENCODE, T_DECODE,

@@ -48,6 +48,8 @@ _SIGNATURES = {
     "nuq_pack_fixed": (_i32, [_vp, _u64, _u32, _u32, _u32, _vp, _vp]),
     "nuq_quantize_pack_fixed_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "nuq_unpack_accumulate_fixed": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _u32, _f32, _i32, _vp, _vp]),
+    "nuq_quantize_pack_fixed_table_batch": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _vp, _u32, _u32, _vp, _vp, _vp]),
+    "nuq_unpack_accumulate_fixed_table": (_i32, [_u32, _vp, _vp, _u64, _u32, _u32, _vp, _u32, _f32, _i32, _vp, _vp]),
     "nuq_level_histogram": (_i32, [_vp, _u64, _vp, _vp]),
     "nuq_huffman_lengths": (_i32, [_vp, _u32, _vp]),
     "nuq_huffman_max_words": (_u64, [_u64, _u32]),
@@ -339,6 +341,36 @@ def nuq_unpack_accumulate_fixed(norms: list[torch.Tensor], packed: list[torch.Te
     _check("nuq_unpack_accumulate_fixed",
            _lib.nuq_unpack_accumulate_fixed(K, arr(norms, torch.float32), arr(packed, torch.int32), d, bucket, s, b,
                                             float(scale), 1 if accumulate else 0, _ptr(out, torch.float32), _stream()))
+
+
+def nuq_quantize_pack_fixed_table_batch(vs: list[torch.Tensor], bucket: int, levels, norm_kind: int, b: int,
+                                        seeds: list[int], norms: list[torch.Tensor], packed: list[torch.Tensor]) -> None:
+    K = len(vs)
+    d = vs[0].numel()
+    s = len(levels) - 2
+    if any(v.numel() != d for v in vs) or len(seeds) != K or len(norms) != K or len(packed) != K:
+        raise ValueError("K gradients of equal length, K seeds, K norm arrays and K packed arrays are needed")
+    B, words = nuq_num_buckets(d, bucket), nuq_fixed_words(d, bucket, b)
+    _check("nuq_quantize_pack_fixed_table_batch",
+           _lib.nuq_quantize_pack_fixed_table_batch(
+               K, (ctypes.c_void_p * K)(*[_ptr(v, torch.float32) for v in vs]),
+               (ctypes.c_uint64 * K)(*[x & (2 ** 64 - 1) for x in seeds]), d, bucket, s, _levels(levels, s), norm_kind, b,
+               (ctypes.c_void_p * K)(*[_ptr(t, torch.float32, B, "norms") for t in norms]),
+               (ctypes.c_void_p * K)(*[_ptr(t, torch.int32, words, "packed") for t in packed]), _stream()))
+
+
+def nuq_unpack_accumulate_fixed_table(norms: list[torch.Tensor], packed: list[torch.Tensor], d: int, bucket: int,
+                                      levels, b: int, scale: float, accumulate: bool, out: torch.Tensor) -> None:
+    K = len(norms)
+    s = len(levels) - 2
+    if out.numel() != d or len(packed) != K:
+        raise ValueError("K norm arrays, K packed arrays and d floats of output are needed")
+    B, words = nuq_num_buckets(d, bucket), nuq_fixed_words(d, bucket, b)
+    _check("nuq_unpack_accumulate_fixed_table",
+           _lib.nuq_unpack_accumulate_fixed_table(
+               K, (ctypes.c_void_p * K)(*[_ptr(t, torch.float32, B, "norms") for t in norms]),
+               (ctypes.c_void_p * K)(*[_ptr(t, torch.int32, words, "packed") for t in packed]), d, bucket, s,
+               _levels(levels, s), b, float(scale), 1 if accumulate else 0, _ptr(out, torch.float32), _stream()))
 
 
 # -------------------------------------------------------- Huffman-coded levels

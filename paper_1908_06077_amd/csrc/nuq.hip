@@ -310,18 +310,26 @@ bool valid_fixed(uint32_t s, uint32_t b)
     return b >= 3 && b <= 8 && s + 2u <= (1u << (b - 1u));
 }
 
-// MODE 0: norms + quantizer + fixed-width packing from v.  MODE 1: packing of level|sign bytes.
+// MODE 0: norms + quantizer + fixed-width packing from v.  MODE 1: packing of level|sign bytes.  MODE 2: as 0 with
+// the level table `levels` (host memory, s + 2 values) and the norm `norm_kind` selects.
 template <int MODE>
 int pack_fixed_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t bucket, uint32_t s, uint32_t b,
-                     nuq_stream_t stream)
+                     nuq_stream_t stream, const float *levels = nullptr, uint32_t norm_kind = NUQ_NORM_L2)
 {
     if (K < 1 || K > kMaxBatch || !valid_common(d, bucket, s) || !valid_fixed(s, b))
         return NUQ_EINVAL;
+    LevelTable T{};
+    if (MODE == 2) {
+        if (!levels || !valid_levels(levels, s) || (norm_kind != NUQ_NORM_L2 && norm_kind != NUQ_NORM_LINF))
+            return NUQ_EINVAL;
+        for (uint32_t j = 0; j < s + 2u; ++j)
+            T.lev[j] = levels[j];
+    }
     for (uint32_t k = 0; k < K; ++k) {
         const EncodeWorker &w = Wk.w[k];
         if (!w.words)
             return NUQ_EINVAL;
-        if (MODE == 0 && (!w.v || !w.norms_out || (reinterpret_cast<uintptr_t>(w.v) & 3u)))
+        if (MODE != 1 && (!w.v || !w.norms_out || (reinterpret_cast<uintptr_t>(w.v) & 3u)))
             return NUQ_EINVAL;
         if (MODE == 1 && !w.q_in)
             return NUQ_EINVAL;
@@ -336,6 +344,7 @@ int pack_fixed_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t buc
     P.bucket = bucket;
     P.s = s;
     P.flags = flags;
+    P.norm_linf = norm_kind == NUQ_NORM_LINF ? 1u : 0u;
     FixedParams F{};
     F.b = b;
     F.wpb = (bucket * b + 31u) / 32u;
@@ -356,7 +365,7 @@ int pack_fixed_batch(uint32_t K, const EncodeBatch &Wk, uint64_t d, uint32_t buc
         if (!bucket_grid<TEAM>(P.nb, K, grid))
             return (int)NUQ_EINVAL;
         ScopedTiming timing(MODE == 1 ? NUQ_T_ENCODE : NUQ_T_QUANTIZE_ENCODE, st);
-        hipLaunchKernelGGL(kern, grid, dim3(G::kWG), lds_bytes, st, P, Wk, F);
+        hipLaunchKernelGGL(kern, grid, dim3(G::kWG), lds_bytes, st, P, Wk, F, T);
         return check_launch();
     });
 }
@@ -859,14 +868,35 @@ int nuq_quantize_pack_fixed_batch(uint32_t K, const float *const *v, const uint6
     return pack_fixed_batch<0>(K, Wk, d, bucket, s, b, stream);
 }
 
-int nuq_unpack_accumulate_fixed(uint32_t K, const float *const *norms, const uint32_t *const *packed, uint64_t d,
-                                uint32_t bucket, uint32_t s, uint32_t b, float scale, int accumulate, float *out,
-                                nuq_stream_t stream)
+int nuq_quantize_pack_fixed_table_batch(uint32_t K, const float *const *v, const uint64_t *seeds, uint64_t d,
+                                        uint32_t bucket, uint32_t s, const float *levels, uint32_t norm_kind, uint32_t b,
+                                        float *const *norms, uint32_t *const *packed, nuq_stream_t stream)
+{
+    if (K < 1 || K > kMaxBatch || !v || !seeds || !norms || !packed || !levels)
+        return NUQ_EINVAL;
+    EncodeBatch Wk{};
+    for (uint32_t k = 0; k < K; ++k) {
+        Wk.w[k].v = v[k];
+        Wk.w[k].seed = seeds[k];
+        Wk.w[k].norms_out = norms[k];
+        Wk.w[k].words = packed[k];
+    }
+    return pack_fixed_batch<2>(K, Wk, d, bucket, s, b, stream, levels, norm_kind);
+}
+
+static int unpack_accumulate_fixed_any(uint32_t K, const float *const *norms, const uint32_t *const *packed, uint64_t d,
+                                       uint32_t bucket, uint32_t s, const float *levels, uint32_t b, float scale,
+                                       int accumulate, float *out, nuq_stream_t stream)
 {
     if (K < 1 || K > NUQ_MAX_WORKERS || !norms || !packed || !out || !valid_common(d, bucket, s) ||
-        !valid_fixed(s, b))
+        !valid_fixed(s, b) || (levels && !valid_levels(levels, s)))
         return NUQ_EINVAL;
     UnpackParams P{};
+    if (levels) {
+        P.use_levels = 1u;
+        for (uint32_t j = 0; j < s + 2u; ++j)
+            P.lev[j] = levels[j];
+    }
     for (uint32_t k = 0; k < K; ++k) {
         if (!norms[k] || !packed[k])
             return NUQ_EINVAL;
@@ -925,6 +955,23 @@ int nuq_unpack_accumulate_fixed(uint32_t K, const float *const *norms, const uin
     }
     return check_launch();
 }
+
+int nuq_unpack_accumulate_fixed(uint32_t K, const float *const *norms, const uint32_t *const *packed, uint64_t d,
+                                uint32_t bucket, uint32_t s, uint32_t b, float scale, int accumulate, float *out,
+                                nuq_stream_t stream)
+{
+    return unpack_accumulate_fixed_any(K, norms, packed, d, bucket, s, nullptr, b, scale, accumulate, out, stream);
+}
+
+int nuq_unpack_accumulate_fixed_table(uint32_t K, const float *const *norms, const uint32_t *const *packed, uint64_t d,
+                                      uint32_t bucket, uint32_t s, const float *levels, uint32_t b, float scale,
+                                      int accumulate, float *out, nuq_stream_t stream)
+{
+    if (!levels)
+        return NUQ_EINVAL;
+    return unpack_accumulate_fixed_any(K, norms, packed, d, bucket, s, levels, b, scale, accumulate, out, stream);
+}
+
 
 int nuq_level_histogram(const uint8_t *q, uint64_t d, uint64_t *hist, nuq_stream_t stream)
 {

@@ -718,6 +718,63 @@ __device__ __forceinline__ void front_bytes_to_lds(const EncodeParams &P, const 
     }
 }
 
+// Front of the fused kernels for an arbitrary level table T and the norm P.norm_linf selects: as
+// front_quantize_to_lds, with quantize_table_vec4 on the bucket's edges l_t * ||v|| (kept in LDS).
+template <int TEAM, int VPT>
+__device__ __forceinline__ void front_quantize_table_to_lds(const EncodeParams &P, const EncodeWorker &W,
+                                                            const LevelTable &T, uint64_t b, bool active, uint64_t base,
+                                                            uint32_t nbk, uint32_t tid, uint32_t *qb32, uint32_t *scratch)
+{
+    __shared__ double edges_all[TeamGeom<TEAM>::kTeamsPerWG][16];
+    double *edges = edges_all[threadIdx.x / TEAM];
+    const float *vb = W.v + base;
+    const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
+    float4 x[VPT];
+    if (aligned && nbk == (uint32_t)VPT * TEAM * 4u) {   // a full bucket that fills every row (as in the main front)
+#pragma unroll
+        for (int i = 0; i < VPT; ++i)
+            x[i] = TEAM >= 64 ? load_once4(reinterpret_cast<const float4 *>(vb) + ((uint32_t)i * TEAM + tid))
+                              : reinterpret_cast<const float4 *>(vb)[(uint32_t)i * TEAM + tid];
+    } else {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i)
+            x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
+    }
+    float nrm;
+    if (P.norm_linf) {
+        uint32_t m = 0;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            m = max(max(m, f2u(x[i].x) & 0x7fffffffu), f2u(x[i].y) & 0x7fffffffu);
+            m = max(max(m, f2u(x[i].z) & 0x7fffffffu), f2u(x[i].w) & 0x7fffffffu);
+        }
+        nrm = u2f(team_max_u32<TEAM>(m, scratch));
+    } else {
+        auto row = [&](int i) { return x[i]; };
+        nrm = team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32));
+    }
+    nrm = team_uniform_f32<TEAM>(nrm);
+    const bool finite = nrm < __builtin_huge_valf();   // false for NaN too
+    if (active && tid == 0) {
+        W.norms_out[b] = nrm;
+        if (!finite)
+            atomicOr(P.flags, kFlagNonfinite);
+    }
+    const bool dead = !(nrm > 0.0f) || !finite;
+    if (tid < 16u)
+        edges[tid] = (double)T.lev[tid] * (double)nrm;
+    team_barrier<TEAM>();
+    const double e1 = edges[1];
+    const BucketKey key = bucket_key(W.seed, b);
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        if ((uint32_t)i < P.rows) {
+            const uint32_t vi = (uint32_t)i * TEAM + tid;
+            qb32[vi] = quantize_table_vec4(x[i], key.k0 + 4u * vi, key.k1, edges, e1, P.s, dead);
+        }
+    }
+}
+
 // MODE 0: fused norms + quantize + encode from v.  MODE 1: encode from level/sign bytes.  MODE 2: as 0 for the level
 // table T and the norm P.norm_linf selects (T is ignored in the other modes).
 template <int TEAM, int VPT, int MODE>
@@ -748,54 +805,7 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_encode(EncodeParams P, 
     const uint32_t nbk = active ? (uint32_t)min((uint64_t)P.bucket, P.d - base) : 0u;
 
     if constexpr (MODE == 2) {
-        __shared__ double edges_all[TeamGeom<TEAM>::kTeamsPerWG][16];
-        double *edges = edges_all[threadIdx.x / TEAM];
-        const float *vb = W.v + base;
-        const bool aligned = (reinterpret_cast<uintptr_t>(vb) & 15u) == 0;
-        float4 x[VPT];
-        if (aligned && nbk == (uint32_t)VPT * TEAM * 4u) {   // a full bucket that fills every row (as in the main front)
-#pragma unroll
-            for (int i = 0; i < VPT; ++i)
-                x[i] = TEAM >= 64 ? load_once4(reinterpret_cast<const float4 *>(vb) + ((uint32_t)i * TEAM + tid))
-                                  : reinterpret_cast<const float4 *>(vb)[(uint32_t)i * TEAM + tid];
-        } else {
-#pragma unroll
-            for (int i = 0; i < VPT; ++i)
-                x[i] = load_vec4(vb, (uint32_t)i * TEAM + tid, nbk, aligned);
-        }
-        float nrm;
-        if (P.norm_linf) {
-            uint32_t m = 0;
-#pragma unroll
-            for (int i = 0; i < VPT; ++i) {
-                m = max(max(m, f2u(x[i].x) & 0x7fffffffu), f2u(x[i].y) & 0x7fffffffu);
-                m = max(max(m, f2u(x[i].z) & 0x7fffffffu), f2u(x[i].w) & 0x7fffffffu);
-            }
-            nrm = u2f(team_max_u32<TEAM>(m, scratch));
-        } else {
-            auto row = [&](int i) { return x[i]; };
-            nrm = team_norm<TEAM, VPT>(row, reinterpret_cast<double *>(scratch + 32));
-        }
-        nrm = team_uniform_f32<TEAM>(nrm);
-        const bool finite = nrm < __builtin_huge_valf();   // false for NaN too
-        if (active && tid == 0) {
-            W.norms_out[b] = nrm;
-            if (!finite)
-                atomicOr(P.flags, kFlagNonfinite);
-        }
-        const bool dead = !(nrm > 0.0f) || !finite;
-        if (tid < 16u)
-            edges[tid] = (double)T.lev[tid] * (double)nrm;
-        team_barrier<TEAM>();
-        const double e1 = edges[1];
-        const BucketKey key = bucket_key(W.seed, b);
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            if ((uint32_t)i < P.rows) {
-                const uint32_t vi = (uint32_t)i * TEAM + tid;
-                qb32[vi] = quantize_table_vec4(x[i], key.k0 + 4u * vi, key.k1, edges, e1, P.s, dead);
-            }
-        }
+        front_quantize_table_to_lds<TEAM, VPT>(P, W, T, b, active, base, nbk, tid, qb32, scratch);
     } else if constexpr (MODE == 0) {
         front_quantize_to_lds<TEAM, VPT>(P, W, b, active, base, nbk, tid, qb32, scratch);
     } else {

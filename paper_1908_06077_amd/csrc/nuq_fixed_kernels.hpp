@@ -21,9 +21,11 @@ __host__ __device__ inline uint32_t fixed_lds_words(uint32_t rows, uint32_t team
     return w + 64u;
 }
 
-// MODE 0: norms + quantizer + packing from v (read once).  MODE 1: packing of level|sign bytes.  One bucket per team.
+// MODE 0: norms + quantizer + packing from v (read once).  MODE 1: packing of level|sign bytes.  MODE 2: as 0 for the
+// level table T and the norm P.norm_linf selects (T is ignored in the other modes).  One bucket per team.
 template <int TEAM, int VPT, int MODE>
-__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_pack_fixed(EncodeParams P, EncodeBatch Wk, FixedParams F)
+__global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_pack_fixed(EncodeParams P, EncodeBatch Wk, FixedParams F,
+                                                                    LevelTable T)
 {
     extern __shared__ __align__(16) uint32_t smem[];
     const EncodeWorker &W = Wk.w[blockIdx.y];
@@ -40,7 +42,9 @@ __global__ __launch_bounds__(TeamGeom<TEAM>::kWG) void k_pack_fixed(EncodeParams
 
     for (uint32_t i = tid; i < F.wpb; i += TEAM)
         field[i] = 0u;
-    if constexpr (MODE == 0)
+    if constexpr (MODE == 2)
+        front_quantize_table_to_lds<TEAM, VPT>(P, W, T, b, active, base, nbk, tid, qb32, scratch);
+    else if constexpr (MODE == 0)
         front_quantize_to_lds<TEAM, VPT>(P, W, b, active, base, nbk, tid, qb32, scratch);
     else
         front_bytes_to_lds<TEAM>(P, W, base, nbk, tid, qb32);
@@ -93,7 +97,15 @@ struct UnpackParams {
     uint32_t lut_tabs;          // table variant: buckets a workgroup can touch (tables per worker in LDS)
     float scale;
     int accumulate;
+    uint32_t use_levels;        // 1: level j has the value lev[j] (a level table), 0: 2^(j - 1 - s)
+    float lev[16];
 };
+
+// norm * l_level, exact in fp64 either way (level 1..s+1).
+__device__ __forceinline__ double fixed_level_value(const UnpackParams &P, double nrm, uint32_t level)
+{
+    return P.use_levels ? nrm * (double)P.lev[level] : ldexp(nrm, (int)level - 1 - (int)P.s);
+}
 
 // out[i] = [out[i] +] scale * sum_k norms_k[bucket] * sign * 2^(level - 1 - s): fp64 sum in worker order, rounded to
 // fp32 (the prior, when there is one, is added in fp32 after that).  A level index above s + 1, or a signed zero,
@@ -153,7 +165,7 @@ __global__ __launch_bounds__(256) void k_unpack_accumulate_fixed32(UnpackParams 
             const uint32_t level = B <= 5 ? idx & kLevelMask : idx & 15u, neg = B <= 5 ? idx >> (B - 1) : idx >> 4;
             double val = 0.0;
             if (bk_first + tab < nb && level >= 1u && level <= P.s + 1u) {
-                val = ldexp((double)P.norms[k][bk_first + tab], (int)level - 1 - (int)P.s);
+                val = fixed_level_value(P, (double)P.norms[k][bk_first + tab], level);
                 val = neg ? -val : val;
             }
             lut[e] = val;
@@ -203,7 +215,7 @@ __global__ __launch_bounds__(256) void k_unpack_accumulate_fixed32(UnpackParams 
                     const uint32_t level = code & kLevelMask, neg = code >> (B - 1);
                     bad |= level > P.s + 1u || (level == 0u && neg);
                     if (level) {
-                        const double val = ldexp(nrm, (int)level - 1 - (int)P.s);
+                        const double val = fixed_level_value(P, nrm, min(level, 15u));
                         sum[c] += neg ? -val : val;
                     }
                 }
@@ -266,7 +278,7 @@ __global__ __launch_bounds__(256) void k_unpack_accumulate_fixed1(UnpackParams P
         const uint32_t level = code & mask_level, neg = code >> (P.b - 1u);
         bad |= level > P.s + 1u || (level == 0u && neg);
         if (level) {
-            const double val = ldexp((double)P.norms[k][bk], (int)level - 1 - (int)P.s);
+            const double val = fixed_level_value(P, (double)P.norms[k][bk], min(level, 15u));
             sum += neg ? -val : val;
         }
     }

@@ -92,6 +92,67 @@ def check(norms_np, packed_np, d, n, s, b, scale, got, prior=None):
     assert np.all(diff <= 1e-6 * mag + 1e-45), float(np.max(diff / np.maximum(mag, 1e-300)))
 
 
+TABLE_CASES = [
+    # (d, bucket, table kind, s, p, norm, b, K, kind)
+    (100_000, 8192, "uniform", 3, 0.0, "linf", 4, 3, "mixed"),      # QSGDinf, 4 bits
+    (100_003, 8192, "uniform", 6, 0.0, "l2", 4, 8, "gauss"),        # QSGD, 4 bits (seven levels)
+    (70_001, 16384, "uniform", 14, 0.0, "linf", 8, 2, "mixed"),
+    (40_000, 512, "exp", 3, 0.3, "l2", 4, 4, "mixed"),
+    (33_333, 1000, "exp", 6, 0.7, "linf", 5, 3, "edges"),
+    (9_999, 1001, "uniform", 5, 0.0, "linf", 4, 2, "mixed"),        # scalar unpack
+    (20_000, 64, "uniform", 3, 0.0, "linf", 4, 8, "mixed"),         # arithmetic route of the wide unpack
+    (90_000, 4096, "exp", 14, 0.5, "l2", 8, 5, "mixed"),            # the main scheme's levels as a table
+]
+
+
+@pytest.mark.parametrize("d,n,tkind,s,p,norm,b,K,kind", TABLE_CASES)
+def test_level_tables_and_maximum_norm(g, d, n, tkind, s, p, norm, b, K, kind):
+    """The fused pack and the unpack + average for a level table and either norm (QSGD and QSGDinf at fixed width):
+    norms to the bar (maximum norms exact), packed words bit-exact against pack_fixed(quantize_table) of the oracle
+    fed the GPU's norms, averages of norm * sign * levels[j] within the bar."""
+    nuq = g.nuq
+    rng = np.random.default_rng(d + n + s + b + 1)
+    lev = workloads.level_table(tkind, s, p if p else 0.5)
+    B, W = nuq.nuq_num_buckets(d, n), nuq.nuq_fixed_words(d, n, b)
+    vs_np = [make_vector(kind, d, n, rng) for _ in range(K)]
+    vs = [torch.from_numpy(v).to(g.DEV) for v in vs_np]
+    seeds = [int(x) for x in rng.integers(0, 2 ** 63, size=K)]
+    norms = [torch.full((B,), -1.0, dtype=torch.float32, device=g.DEV) for _ in range(K)]
+    packed = [torch.full((W,), 0x55555555, dtype=torch.int32, device=g.DEV) for _ in range(K)]
+    nuq.nuq_quantize_pack_fixed_table_batch(vs, n, lev, nuq.NORM_LINF if norm == "linf" else nuq.NORM_L2, b, seeds,
+                                            norms, packed)
+    assert nuq.nuq_last_error_flags() == 0
+    norms_np, packed_np = [], []
+    for k in range(K):
+        nk = norms[k].cpu().numpy()
+        if norm == "linf":
+            np.testing.assert_array_equal(nk.astype(np.float64), oracle.bucket_norms_linf(vs_np[k], n))
+        else:
+            g.check_norms(vs_np[k], n, nk)
+        want = oracle.pack_fixed(oracle.quantize_table(vs_np[k], n, lev, seeds[k], nk), n, s, b)
+        np.testing.assert_array_equal(g.u32(packed[k]), want)
+        norms_np.append(nk)
+        packed_np.append(want)
+    for scale, prior in ((1.0 / K, None), (0.5, rng.standard_normal(d).astype(np.float32))):
+        out = torch.full((d,), 9.0, dtype=torch.float32, device=g.DEV) if prior is None else torch.from_numpy(prior).to(g.DEV)
+        nuq.nuq_unpack_accumulate_fixed_table(norms, packed, d, n, lev, b, scale, prior is not None, out)
+        assert nuq.nuq_last_error_flags() == 0
+        scale32 = float(np.float32(scale))
+        want, mag = np.zeros(d), np.zeros(d)
+        for nk, pk in zip(norms_np, packed_np):
+            deq = oracle.dequantize_table(oracle.unpack_fixed(pk, d, n, s, b), n, lev, nk)
+            want += deq
+            mag += np.abs(deq)
+        want, mag = want * scale32, mag * abs(scale32)
+        got = out.cpu().numpy().astype(np.float64)
+        if prior is not None:
+            p64 = prior.astype(np.float64)
+            assert np.all(np.abs(got - (want.astype(np.float32).astype(np.float64) + p64))
+                          <= 1e-6 * mag + 6e-8 * (np.abs(want) + np.abs(p64)) + 1e-45)
+        else:
+            assert np.all(np.abs(got - want) <= 1e-6 * mag + 1e-45)
+
+
 def _random_fixed_cases(count, seed):
     rng = np.random.default_rng(seed)
     cases = []
