@@ -798,7 +798,7 @@ __global__ __launch_bounds__(kHuffmanDirectWG) void k_huffman_decode_direct(Huff
 // zero bits, followed by one nonzero symbol when its codeword and sign still fit the 32-bit window: about as many
 // steps as the ERC parse has records.  With any other code a step is one symbol.
 struct HuffmanWaveCodec {
-    static constexpr uint32_t kWordsPerLane = 16;      // a tile's part of a string is ~75 words on gradient data
+    static constexpr uint32_t kWordsPerLane = 13;      // a tile's part of a string is ~75 words on gradient data; 13: eight workgroups per CU
     uint8_t *lut8;          // LDS, 256 entries: symbol | length << 4 of the codeword the eight bits start with, else 0
     uint32_t *canon;        // LDS, 64 words: first[16], count[16], offset[16], sorted[16] of the canonical code
     const HuffmanCode *H;
