@@ -494,11 +494,15 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
     // Decoder index: entry i = (block t, piece g) describes record blk[t] + floor(g n_t / pieces) of the bucket.
     uint32_t *const sg = W.sync + (active ? b : 0) * P.nsync;
     const uint32_t pmask = (1u << P.pieces_shift) - 1u;
-    if (listed) {
+    // Small teams (a wave or less: short runs, few entries) let the thread that owns a listed record write its entry
+    // from the lengths it holds in registers; large teams look the record up from the entry's side.
+    constexpr bool kOwnerWrites = TEAM <= (int)kWave;
+    const bool targets_to_lds = !listed || kOwnerWrites;
+    if (listed && !kOwnerWrites)
         run_off[tid] = off0;              // where this thread's run of records starts in the bit string
-    } else {
-        // records are not listed: their numbers go to LDS (bit 31: a block without records) and whoever emits
-        // such a record writes the entry; an entry past the last record is the bucket's length
+    if (targets_to_lds) {
+        // the entries' record numbers go to LDS (bit 31: a block without records); an entry past the last record is
+        // the bucket's length.  Unlisted records: whoever emits such a record writes the entry (below)
         for (uint32_t i = tid; i < P.nsync; i += TEAM) {
             const uint32_t f = blk[i >> P.pieces_shift], n = blk[(i >> P.pieces_shift) + 1u] - f;
             const uint32_t r = f + (((i & pmask) * n) >> P.pieces_shift);
@@ -508,7 +512,38 @@ __device__ __forceinline__ void encode_from_lds(const EncodeParams &P, const Enc
         }
     }
     team_barrier<TEAM>();
-    if (listed) {
+    if (listed && kOwnerWrites) {
+        // this thread's run is records [r0, r1), the first at bit off0: the entries that point into it (their record
+        // numbers are sorted) are found by bisection, a record's offset is the sum of the lengths before it in the run
+        if (r0 < r1 && P.nsync) {
+            uint32_t lo = 0, hi = P.nsync;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if ((sync_l[mid] & 0x7fffffffu) < r0)
+                    lo = mid + 1u;
+                else
+                    hi = mid;
+            }
+            for (uint32_t cur = lo; cur < P.nsync; ++cur) {
+                const uint32_t tg = sync_l[cur], r = tg & 0x7fffffffu;
+                if (r >= r1)
+                    break;
+                uint32_t pos = off0;
+#pragma unroll
+                for (uint32_t i = 0; i < kKept; ++i)
+                    pos += r0 + i < r ? kept_len[i] : 0u;
+                for (uint32_t q = r0 + kKept; q < r; ++q) {      // (a run longer than the records kept in registers)
+                    const int e = (int)rec[q];
+                    uint32_t len;
+                    make_record(e, (int)rec[q - 1u], (uint32_t)qbytes[e], len);
+                    pos += len;
+                }
+                const uint32_t rel = (tg >> 31) ? 0u : (uint32_t)rec[r] - ((cur >> P.pieces_shift) << kSyncBlockShift);
+                if (active)
+                    sg[cur] = pos | (rel << 21);
+            }
+        }
+    } else if (listed) {
         // the run that holds the record starts at run_off[owner]; the lengths of the records before it in that run
         // are looked up again (a run is nnz / TEAM records)
         for (uint32_t i = tid; i < P.nsync; i += TEAM) {
